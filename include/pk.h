@@ -1,0 +1,163 @@
+/* pk — packed multi-field embedding layer for one MI355X (gfx950).
+ *
+ * C ABI of the library.  The operations are those of the embedding layer of a
+ * wide-and-deep recommender model as the paper states them:
+ *   - Sec. II-D: Unique (drop repeated IDs), Gather (fetch embedding rows),
+ *     SegmentReduction (pool rows per sample), backward pass = mirror image;
+ *   - Sec. III-B (D-Packing / K-Packing, Fig. 7): the ID tensors of all fields
+ *     whose tables share an embedding dimension are combined into one packed
+ *     ID tensor and handled by one packed operation, and memory-bound steps
+ *     are fused with each other;
+ *   - the sparse Adagrad update is fixed by the workload configurations, not
+ *     by the paper.
+ *
+ * Conventions
+ *   - Every pointer says "host" or "device".  The library owns only the
+ *     host-side plan (plus a few KB of device metadata it uploads on the first
+ *     call that uses a plan).  Tables, accumulators, inputs, outputs and the
+ *     workspace are allocated and freed by the caller.
+ *   - pk_forward / pk_backward_update only enqueue work on the given HIP
+ *     stream and return; they never synchronise.  Data-dependent sizes (number
+ *     of distinct keys) stay in device memory.
+ *   - All functions return a pk_status (0 = success) and never throw;
+ *     pk_last_error() gives a thread-local message for the last failure.
+ *   - Limits: total rows of a pack < 2^32; dim <= 256; nnz < 2^31;
+ *     B * out_dim < 2^32.
+ */
+#ifndef PK_H
+#define PK_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    PK_OK = 0,
+    PK_EINVAL = 1,      /* null pointer, bad enum, non-positive size            */
+    PK_ESHAPE = 2,      /* B / nnz / stride inconsistent with the plan          */
+    PK_EWORKSPACE = 3,  /* workspace too small or misaligned                    */
+    PK_EOVERFLOW = 4,   /* a documented limit would be exceeded                 */
+    PK_EHIP = 5,        /* a HIP call failed                                    */
+    PK_ENOMEM = 6       /* host allocation failed                               */
+} pk_status;
+
+typedef enum { PK_F32 = 0, PK_BF16 = 1 } pk_dtype;
+typedef enum { PK_SUM = 0, PK_MEAN = 1 } pk_pool;
+
+/* One embedding table: rows x dim elements of dtype. */
+typedef struct { int64_t rows; int32_t dim; int32_t dtype; } pk_table_desc;
+/* One feature field: the table it reads (several fields may share a table)
+ * and how its bag of rows is pooled (Sec. II-D SegmentReduction; mean divides
+ * by the bag length counting repeats; an empty bag pools to zeros). */
+typedef struct { int32_t table; int32_t pool; } pk_field_desc;
+
+typedef struct {
+    int32_t max_batch;   /* largest B that will be passed (0 = no limit checked)   */
+    int64_t max_nnz;     /* largest nnz that will be passed (0 = no limit checked) */
+    int32_t max_shards;  /* Eq. 1 shard split of heavy packs; 0 or 1 = off          */
+    const double* field_volume; /* host, [n_fields] or NULL: occurrences per field
+                                   from warm-up statistics, used by the Eq. 1 split */
+} pk_plan_opts;
+
+typedef struct pk_plan pk_plan;   /* opaque, host memory, owned by the library */
+
+/* ---- plan (Sec. III-B: pack fields whose tables share the dimension) --------
+ * Packs are the distinct (dim, dtype) pairs in ascending (dim, dtype) order.
+ * Inside a pack the tables are stacked in table-index order into ONE caller
+ * buffer [total_rows, dim]; pk_plan_table_slot tells where each table starts.
+ * Fields of a pack are numbered (slots) in field-index order.  The pooled
+ * outputs of one sample are concatenated in field order: field f occupies
+ * columns [col(f), col(f)+dim) of out[B, out_dim].
+ * tables, fields, opts: host.  *out receives the plan on success. */
+pk_status pk_plan_create(const pk_table_desc* tables, int32_t n_tables,
+                         const pk_field_desc* fields, int32_t n_fields,
+                         const pk_plan_opts* opts, pk_plan** out);
+void      pk_plan_destroy(pk_plan* plan);
+int32_t   pk_plan_num_packs(const pk_plan* plan);
+/* key_bytes is always 4 in this implementation.  Any out pointer may be NULL. */
+pk_status pk_plan_pack_info(const pk_plan* plan, int32_t p, int32_t* dim, int32_t* dtype,
+                            int64_t* total_rows, int32_t* n_fields, int32_t* n_tables,
+                            int32_t* key_bytes);
+/* fields_out: host, room for the pack's n_fields entries; ascending field index. */
+pk_status pk_plan_pack_fields(const pk_plan* plan, int32_t p, int32_t* fields_out);
+pk_status pk_plan_table_slot(const pk_plan* plan, int32_t table, int32_t* pack, int64_t* base_row);
+pk_status pk_plan_field_col(const pk_plan* plan, int32_t field, int64_t* col_offset);
+int64_t   pk_plan_out_dim(const pk_plan* plan);   /* sum of dims over fields; -1 if plan is NULL */
+
+/* Upper bound of the workspace needed for a call with this B and nnz; depends
+ * on no data.  Returns 0 on error (see pk_last_error). */
+size_t    pk_workspace_bytes(const pk_plan* plan, int32_t B, int64_t nnz);
+
+/* ---- forward (Sec. II-D Unique -> Gather -> SegmentReduction, packed per
+ * Sec. III-B) ------------------------------------------------------------------
+ * W:        host array of n_packs DEVICE pointers; W[p] is pack p's stacked
+ *           table [total_rows, dim], row-major, fp32 or bf16 per the pack dtype.
+ * ids:      device, int64 [nnz]; bags are field-major: bag g = f*B + b owns
+ *           ids[offsets[g] .. offsets[g+1]).  Any 64-bit value is a valid ID:
+ *           it is read as unsigned and folded modulo the table's rows.
+ * offsets:  device, int32 [n_fields*B + 1], non-decreasing, offsets[0] = 0,
+ *           offsets[n_fields*B] = nnz.
+ * out:      device, fp32 [B, out_row_stride], out_row_stride >= out_dim;
+ *           columns [0, out_dim) of every row are overwritten.
+ * workspace: device, 256-byte aligned, >= pk_workspace_bytes(plan, B, nnz).
+ *           It carries the dedup context (keys, unique, inverse, segment lists)
+ *           from pk_forward to the pk_backward_update that follows.
+ * hip_stream: hipStream_t (NULL = default stream).
+ * Offsets that violate the contract set a device error word (pk_ctx_error);
+ * results are then undefined but all kernels still terminate. */
+pk_status pk_forward(const pk_plan* plan, void* const* W,
+                     const int64_t* ids, const int32_t* offsets, int32_t B, int64_t nnz,
+                     float* out, int64_t out_row_stride,
+                     void* workspace, size_t ws_bytes, void* hip_stream);
+
+/* ---- backward + update (Sec. II-D: mirror of the forward pass; Adagrad from
+ * the workload configurations) -------------------------------------------------
+ * For every distinct key u of the preceding pk_forward (same plan, B, nnz and
+ * workspace):
+ *   g = sum over its occurrences of grad_out[b, col(f) .. col(f)+dim) * (1/L for mean)
+ *   A[row] += g*g ;  W[row] -= lr * g / (sqrt(A[row]) + eps)
+ * Rows of keys that do not occur are neither read nor written.
+ * A:        host array of n_packs DEVICE pointers, fp32 [total_rows, dim].
+ * grad_out: device, fp32 [B, grad_row_stride]. */
+pk_status pk_backward_update(const pk_plan* plan, void* const* W, float* const* A,
+                             const float* grad_out, int64_t grad_row_stride,
+                             int32_t B, int64_t nnz,
+                             float lr, float eps,
+                             void* workspace, size_t ws_bytes, void* hip_stream);
+
+/* ---- parity access to the context saved in the workspace ---------------------
+ * SYNCHRONISES the device (copies a few bytes of the header back).  Returns
+ * device pointers into the workspace, valid until the next pk_forward:
+ *   keys            uint32 [nnz_p]      packed key per occurrence, in packed order
+ *   unique          uint32 [n_unique]   distinct keys, ascending
+ *   inverse         int32  [nnz_p]      index of each occurrence's key in unique
+ *   packed_offsets  int32  [k_p*B + 1]  bag boundaries in the packed order
+ *   seg_offsets     int32  [n_unique+1] occurrences with a smaller key, per distinct key
+ * and the host values nnz_p and n_unique.  Any out pointer may be NULL. */
+pk_status pk_ctx_pack(const pk_plan* plan, const void* workspace, int32_t B, int64_t nnz, int32_t p,
+                      const uint32_t** keys, const uint32_t** unique, const int32_t** inverse,
+                      const int32_t** packed_offsets, const int32_t** seg_offsets,
+                      int64_t* nnz_p, int64_t* n_unique);
+/* Device error word of the last pk_forward on this workspace (0 = inputs
+ * passed the checks).  SYNCHRONISES. bit 0: offsets[0] != 0 or
+ * offsets[n_fields*B] != nnz; bit 1: a scan waited too long. */
+pk_status pk_ctx_error(const pk_plan* plan, const void* workspace, int32_t* error_word);
+
+/* ---- per-kernel timing (for the benchmark's roofline figures) -----------------
+ * With profiling on, every kernel launch is bracketed by HIP events on the
+ * launch stream.  pk_profile_read synchronises, adds up the elapsed time per
+ * kernel name since the last read, and fills up to max_entries entries (names
+ * are static strings owned by the library).  Returns the number of entries. */
+pk_status pk_profile_enable(pk_plan* plan, int32_t enable);
+int32_t   pk_profile_read(pk_plan* plan, const char** names, double* total_ms, int64_t* launches,
+                          int32_t max_entries);
+
+const char* pk_last_error(void);   /* host, thread-local, never NULL */
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PK_H */

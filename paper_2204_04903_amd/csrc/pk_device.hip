@@ -1,0 +1,1057 @@
+// Device code and launch logic of the packed multi-field embedding layer for
+// gfx950 (wave64).  The path is gather / reduce / scatter and is bound by HBM
+// bandwidth, so there is no MFMA here: the work is in keeping every access
+// coalesced across the embedding dimension, in touching each distinct row once
+// (the point of Unique, Sec. II-D), and in launching once per pack instead of
+// once per field (D-Packing, Sec. III-B).
+//
+// Stages of one step (all packs of the plan share the integer stages):
+//   setup     field boundaries, per-pack occurrence counts and positions, bitmap clear
+//   keys      H1: key = base_row + (uint64)id mod rows, packed order, mark bitmap
+//   pool      H3-H5: per pack, gather rows by key, pool per bag, write concatenated
+//   tiles     H2: popcount scan of the bitmap -> rank samples, distinct keys (ascending)
+//   inverse   H2: inverse[q] = rank(key[q]); occurrence counts per distinct key
+//   segscan   H2: exclusive scan of the counts -> segment offsets; list of hot keys
+//   scatter   H2: occurrences grouped by distinct key (gradient addresses)
+//   adagrad   H6+H7: per pack, per distinct key: reduce gradients, update row in place
+#include <hip/hip_runtime.h>
+
+#include <cstdio>
+#include <map>
+#include <mutex>
+#include <string>
+#include <vector>
+
+#include "pk_internal.h"
+
+using namespace pk;
+
+// ---------------------------------------------------------------------------
+// device helpers
+// ---------------------------------------------------------------------------
+namespace {
+
+constexpr int NT = 256;   // threads per block of the streaming kernels
+
+template <int NTHREADS>
+__device__ __forceinline__ int block_excl_scan(int v, int* total)
+{
+    __shared__ int wsum[NTHREADS / 64];
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    int inc = v;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        int t = __shfl_up(inc, o, 64);
+        if (lane >= o) inc += t;
+    }
+    __syncthreads();   // readers of the previous call are done with wsum
+    if (lane == 63) wsum[w] = inc;
+    __syncthreads();
+    int base = 0, tot = 0;
+#pragma unroll
+    for (int i = 0; i < NTHREADS / 64; ++i) {
+        int s = wsum[i];
+        if (i < w) base += s;
+        tot += s;
+    }
+    *total = tot;
+    return base + inc - v;
+}
+
+__device__ __forceinline__ uint32_t fold_id(int64_t id, uint32_t rows)
+{
+    const uint64_t u = (uint64_t)id;
+    return u < rows ? (uint32_t)u : (uint32_t)(u % (uint64_t)rows);
+}
+
+// first index in [0, n) whose value exceeds x, for a non-decreasing array
+template <typename P>
+__device__ __forceinline__ int upper_bound_i32(P a, int n, int x)
+{
+    int lo = 0, hi = n;
+    while (lo < hi) {
+        int mid = (lo + hi) >> 1;
+        if (a[mid] <= x) lo = mid + 1; else hi = mid;
+    }
+    return lo;
+}
+
+// ---------------------------------------------------------------------------
+// setup: block 0 derives the per-field and per-pack positions; the other
+// blocks clear the bitmap.
+// ---------------------------------------------------------------------------
+__global__ void __launch_bounds__(1024)
+pk_setup_kernel(const int32_t* __restrict__ offsets, int B, int F, int P, int64_t nnz,
+                const PackMeta* __restrict__ pm, const int32_t* __restrict__ slot_field,
+                PackState* st, int32_t* fb, int32_t* delta, int32_t* slot_start, int32_t* packed_offsets,
+                uint4* bitmap4, int64_t n_bitmap4)
+{
+    if (blockIdx.x != 0) {
+        const uint4 z = make_uint4(0, 0, 0, 0);
+        const int64_t stride = (int64_t)(gridDim.x - 1) * blockDim.x;
+        for (int64_t i = (int64_t)(blockIdx.x - 1) * blockDim.x + threadIdx.x; i < n_bitmap4; i += stride)
+            bitmap4[i] = z;
+        return;
+    }
+    __shared__ int bad;
+    const int tid = threadIdx.x;
+    if (tid == 0) bad = 0;
+    __syncthreads();
+    for (int f = tid; f <= F; f += 1024) fb[f] = offsets[(int64_t)f * B];
+    __syncthreads();
+    for (int f = tid; f < F; f += 1024)
+        if (fb[f + 1] < fb[f]) bad = 1;
+    if (tid == 0 && (fb[0] != 0 || (int64_t)fb[F] != nnz)) bad = 1;
+    __syncthreads();
+    const int is_bad = bad;
+    int start = 0;
+    for (int p = 0; p < P; ++p) {
+        const int k = pm[p].n_fields, fs = pm[p].first_slot;
+        int carry = 0;
+        for (int base = 0; base < k; base += 1024) {
+            const int j = base + tid;
+            int len = 0, f = 0;
+            if (j < k) {
+                f = slot_field[fs + j];
+                len = is_bad ? 0 : fb[f + 1] - fb[f];
+            }
+            int tot;
+            const int ex = block_excl_scan<1024>(len, &tot);
+            if (j < k) {
+                slot_start[fs + p + j] = carry + ex;
+                delta[f] = start + carry + ex - fb[f];
+            }
+            carry += tot;
+        }
+        if (tid == 0) {
+            slot_start[fs + p + k] = carry;
+            PackState s;
+            s.nnz = carry; s.start = start; s.n_unique = 0; s.n_hot = 0; s.error = (p == 0) ? is_bad : 0;
+            s.pad[0] = s.pad[1] = s.pad[2] = 0;
+            st[p] = s;
+            packed_offsets[(int64_t)fs * B + p + (int64_t)k * B] = carry;
+        }
+        start += carry;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// H1: packed keys (Sec. III-B: one packed ID tensor per pack) and bitmap marks;
+// packed bag offsets.
+// ---------------------------------------------------------------------------
+__global__ void __launch_bounds__(NT)
+pk_keys_kernel(const int64_t* __restrict__ ids, const int32_t* __restrict__ offsets, int B, int F, int64_t nnz,
+               const FieldMeta* __restrict__ fmeta, const PackMeta* __restrict__ pm, const PackState* __restrict__ st,
+               const int32_t* __restrict__ fb, const int32_t* __restrict__ delta,
+               const int32_t* __restrict__ slot_start, uint32_t* __restrict__ keys, uint32_t* bitmap,
+               int32_t* __restrict__ packed_offsets, int use_lds)
+{
+    extern __shared__ int32_t s_fb[];
+    if (st[0].error) return;
+    if (use_lds) {
+        for (int f = threadIdx.x; f <= F; f += NT) s_fb[f] = fb[f];
+        __syncthreads();
+    }
+    const int64_t stride = (int64_t)gridDim.x * NT;
+    for (int64_t i = (int64_t)blockIdx.x * NT + threadIdx.x; i < nnz; i += stride) {
+        const int f = (use_lds ? upper_bound_i32(s_fb, F + 1, (int)i) : upper_bound_i32(fb, F + 1, (int)i)) - 1;
+        const FieldMeta m = fmeta[f];
+        const uint32_t key = m.base_row + fold_id(ids[i], m.rows);
+        const int64_t q = i + delta[f];
+        if ((uint64_t)q < (uint64_t)nnz) {
+            keys[q] = key;
+            atomicOr(&bitmap[(size_t)pm[m.pack].first_tile * kTileWords + (key >> 5)], 1u << (key & 31));
+        }
+    }
+    const int64_t n_bags = (int64_t)F * B;
+    for (int64_t g = (int64_t)blockIdx.x * NT + threadIdx.x; g < n_bags; g += stride) {
+        const int f = (int)(g / B);
+        const int b = (int)(g - (int64_t)f * B);
+        const FieldMeta m = fmeta[f];
+        const PackMeta k = pm[m.pack];
+        packed_offsets[(int64_t)k.first_slot * B + m.pack + (int64_t)m.slot * B + b] =
+            slot_start[k.first_slot + m.pack + m.slot] + offsets[g] - (use_lds ? s_fb[f] : fb[f]);
+    }
+}
+
+// ---------------------------------------------------------------------------
+// H2 (Unique, Sec. II-D) via a bitmap over the pack's rows: the ascending
+// distinct keys are the set bits in order, and the index of a key among them is
+// the number of set bits before it.
+// ---------------------------------------------------------------------------
+__global__ void __launch_bounds__(NT)
+pk_tile_count_kernel(const uint4* __restrict__ bitmap4, int32_t* __restrict__ tile_sum)
+{
+    const size_t t = (size_t)blockIdx.x * NT + threadIdx.x;
+    const uint4 a = bitmap4[2 * t], b = bitmap4[2 * t + 1];
+    int c = __popc(a.x) + __popc(a.y) + __popc(a.z) + __popc(a.w) +
+            __popc(b.x) + __popc(b.y) + __popc(b.z) + __popc(b.w);
+    int tot;
+    block_excl_scan<NT>(c, &tot);
+    if (threadIdx.x == 0) tile_sum[blockIdx.x] = tot;
+}
+
+__global__ void __launch_bounds__(1024)
+pk_tile_scan_kernel(const int32_t* __restrict__ tile_sum, int32_t* __restrict__ tile_off,
+                    const PackMeta* __restrict__ pm, PackState* st, int P)
+{
+    for (int p = 0; p < P; ++p) {
+        const int t0 = pm[p].first_tile, n = pm[p].n_tiles;
+        int carry = 0;
+        for (int base = 0; base < n; base += 1024) {
+            const int i = base + threadIdx.x;
+            const int v = i < n ? tile_sum[t0 + i] : 0;
+            int tot;
+            const int ex = block_excl_scan<1024>(v, &tot);
+            if (i < n) tile_off[t0 + i] = carry + ex;
+            carry += tot;
+        }
+        if (threadIdx.x == 0) st[p].n_unique = carry;
+    }
+}
+
+__global__ void __launch_bounds__(NT)
+pk_tile_emit_kernel(const uint4* __restrict__ bitmap4, const int32_t* __restrict__ tile_off,
+                    const PackMeta* __restrict__ pm, const PackState* __restrict__ st, int P,
+                    int32_t* __restrict__ rank, uint32_t* __restrict__ unique, int32_t* __restrict__ cnt)
+{
+    const int tile = blockIdx.x;
+    int p = 0;
+    while (p + 1 < P && tile >= pm[p + 1].first_tile) ++p;
+    const size_t t = (size_t)tile * NT + threadIdx.x;
+    const uint4 a = bitmap4[2 * t], b = bitmap4[2 * t + 1];
+    const uint32_t w[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+    int c = 0;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) c += __popc(w[i]);
+    int tot;
+    int pre = tile_off[tile] + block_excl_scan<NT>(c, &tot);
+    rank[t] = pre;
+    if (c == 0) return;
+    const int start = st[p].start;
+    uint32_t* uq = unique + start;
+    int32_t* cn = cnt + start + p;
+    const uint32_t key0 = ((uint32_t)(tile - pm[p].first_tile) * NT + threadIdx.x) * 256u;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        uint32_t x = w[i];
+        while (x) {
+            const int bit = __ffs(x) - 1;
+            x &= x - 1;
+            uq[pre] = key0 + i * 32 + bit;
+            cn[pre] = 0;
+            ++pre;
+        }
+    }
+}
+
+__global__ void __launch_bounds__(NT)
+pk_inverse_kernel(const PackMeta* __restrict__ pm, const PackState* __restrict__ st,
+                  const uint32_t* __restrict__ keys, const uint4* __restrict__ bitmap4,
+                  const int32_t* __restrict__ rank, int32_t* __restrict__ inverse,
+                  int32_t* __restrict__ occ_slot, int32_t* cnt)
+{
+    const int p = blockIdx.y;
+    const int n = st[p].nnz, start = st[p].start;
+    const size_t rb = (size_t)pm[p].first_tile * NT;          // rank blocks before this pack
+    const uint4* bm = bitmap4 + 2 * rb;
+    const int32_t* rk = rank + rb;
+    int32_t* cn = cnt + start + p;
+    const int stride = gridDim.x * NT;
+    for (int q = blockIdx.x * NT + threadIdx.x; q < n; q += stride) {
+        const uint32_t key = keys[start + q];
+        const uint32_t blk = key >> 8;
+        const int wi = (key >> 5) & 7;
+        const uint4 a = bm[2 * (size_t)blk], b = bm[2 * (size_t)blk + 1];
+        const uint32_t w[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+        int r = rk[blk];
+        uint32_t cur = 0;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            if (i < wi) r += __popc(w[i]);
+            if (i == wi) cur = w[i];
+        }
+        r += __popc(cur & ((1u << (key & 31)) - 1u));
+        inverse[start + q] = r;
+        occ_slot[start + q] = atomicAdd(&cn[r], 1);
+    }
+}
+
+// exclusive scan of the occurrence counts of a pack's distinct keys, in place
+__global__ void __launch_bounds__(NT)
+pk_seg_sum_kernel(const PackState* __restrict__ st, const int32_t* __restrict__ cnt, int32_t* __restrict__ seg_sum)
+{
+    const int p = blockIdx.y;
+    const int U = st[p].n_unique;
+    const int32_t* cn = cnt + st[p].start + p;
+    const int chunk = (U + gridDim.x - 1) / gridDim.x;
+    const int lo = blockIdx.x * chunk, hi = min(U, lo + chunk);
+    int s = 0;
+    for (int u = lo + threadIdx.x; u < hi; u += NT) s += cn[u];
+    int tot;
+    block_excl_scan<NT>(s, &tot);
+    if (threadIdx.x == 0) seg_sum[p * gridDim.x + blockIdx.x] = tot;
+}
+
+__global__ void __launch_bounds__(kSegScanBlocks)
+pk_seg_scan_sums_kernel(int32_t* seg_sum)
+{
+    const int i = blockIdx.x * kSegScanBlocks + threadIdx.x;
+    int tot;
+    seg_sum[i] = block_excl_scan<kSegScanBlocks>(seg_sum[i], &tot);
+}
+
+__global__ void __launch_bounds__(NT)
+pk_seg_offsets_kernel(PackState* st, int32_t* cnt, const int32_t* __restrict__ seg_sum, int32_t* __restrict__ hot)
+{
+    const int p = blockIdx.y;
+    const int U = st[p].n_unique, start = st[p].start;
+    int32_t* cn = cnt + start + p;
+    int32_t* hl = hot + start / kHotThreshold + p;
+    const int chunk = (U + gridDim.x - 1) / gridDim.x;
+    const int lo = blockIdx.x * chunk, hi = min(U, lo + chunk);
+    int carry = seg_sum[p * gridDim.x + blockIdx.x];
+    for (int base = lo; base < hi; base += NT) {
+        const int u = base + threadIdx.x;
+        const int v = u < hi ? cn[u] : 0;
+        int tot;
+        const int ex = block_excl_scan<NT>(v, &tot);
+        if (u < hi) {
+            cn[u] = carry + ex;
+            if (v > kHotThreshold) hl[atomicAdd(&st[p].n_hot, 1)] = u;
+        }
+        carry += tot;
+    }
+    if (blockIdx.x == 0 && threadIdx.x == 0) cn[U] = st[p].nnz;
+}
+
+// occurrences grouped by distinct key: for each, where its gradient lives
+__global__ void __launch_bounds__(NT)
+pk_scatter_kernel(const int32_t* __restrict__ offsets, int B, int64_t out_dim,
+                  const FieldMeta* __restrict__ fmeta, const PackMeta* __restrict__ pm,
+                  const PackState* __restrict__ st, const int32_t* __restrict__ slot_field,
+                  const int32_t* __restrict__ fb, const int32_t* __restrict__ slot_start,
+                  const int32_t* __restrict__ inverse, const int32_t* __restrict__ occ_slot,
+                  const int32_t* __restrict__ cnt, uint32_t* __restrict__ seg_ent, float* __restrict__ seg_scale)
+{
+    const int p = blockIdx.y;
+    const int n = st[p].nnz, start = st[p].start;
+    const PackMeta k = pm[p];
+    const int32_t* ss = slot_start + k.first_slot + p;
+    const int32_t* sf = slot_field + k.first_slot;
+    const int32_t* cn = cnt + start + p;
+    const int stride = gridDim.x * NT;
+    for (int q = blockIdx.x * NT + threadIdx.x; q < n; q += stride) {
+        const int j = upper_bound_i32(ss, k.n_fields + 1, q) - 1;
+        const int f = sf[j];
+        const FieldMeta m = fmeta[f];
+        const int i = q - ss[j] + fb[f];                       // position in the caller's ids
+        const int32_t* bo = offsets + (int64_t)f * B;
+        const int b = upper_bound_i32(bo, B + 1, i) - 1;
+        const int pos = cn[inverse[start + q]] + occ_slot[start + q];
+        if ((unsigned)pos < (unsigned)n && (unsigned)b < (unsigned)B) {
+            seg_ent[start + pos] = (uint32_t)((int64_t)b * out_dim + m.col);
+            if (k.has_mean) {
+                const int L = bo[b + 1] - bo[b];
+                seg_scale[start + pos] = (m.pool == PK_MEAN && L > 0) ? 1.0f / (float)L : 1.0f;
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// row access: VEC consecutive elements of a table row as floats
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ float bf16_to_f32(uint32_t b) { return __uint_as_float(b << 16); }
+__device__ __forceinline__ uint32_t f32_to_bf16(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    u += 0x7FFFu + ((u >> 16) & 1u);      // round to nearest, ties to even (finite inputs)
+    return u >> 16;
+}
+
+template <typename WT, int VEC> struct Row;
+
+template <> struct Row<float, 4> {
+    static __device__ __forceinline__ void load(const float* p, float* v)
+    { const float4 x = *reinterpret_cast<const float4*>(p); v[0] = x.x; v[1] = x.y; v[2] = x.z; v[3] = x.w; }
+    static __device__ __forceinline__ void store(float* p, const float* v)
+    { *reinterpret_cast<float4*>(p) = make_float4(v[0], v[1], v[2], v[3]); }
+};
+template <> struct Row<float, 1> {
+    static __device__ __forceinline__ void load(const float* p, float* v) { v[0] = *p; }
+    static __device__ __forceinline__ void store(float* p, const float* v) { *p = v[0]; }
+};
+template <> struct Row<uint16_t, 8> {
+    static __device__ __forceinline__ void load(const uint16_t* p, float* v)
+    {
+        const uint4 x = *reinterpret_cast<const uint4*>(p);
+        v[0] = bf16_to_f32(x.x & 0xFFFFu); v[1] = bf16_to_f32(x.x >> 16);
+        v[2] = bf16_to_f32(x.y & 0xFFFFu); v[3] = bf16_to_f32(x.y >> 16);
+        v[4] = bf16_to_f32(x.z & 0xFFFFu); v[5] = bf16_to_f32(x.z >> 16);
+        v[6] = bf16_to_f32(x.w & 0xFFFFu); v[7] = bf16_to_f32(x.w >> 16);
+    }
+    static __device__ __forceinline__ void store(uint16_t* p, const float* v)
+    {
+        uint4 x;
+        x.x = f32_to_bf16(v[0]) | (f32_to_bf16(v[1]) << 16);
+        x.y = f32_to_bf16(v[2]) | (f32_to_bf16(v[3]) << 16);
+        x.z = f32_to_bf16(v[4]) | (f32_to_bf16(v[5]) << 16);
+        x.w = f32_to_bf16(v[6]) | (f32_to_bf16(v[7]) << 16);
+        *reinterpret_cast<uint4*>(p) = x;
+    }
+};
+template <> struct Row<uint16_t, 1> {
+    static __device__ __forceinline__ void load(const uint16_t* p, float* v) { v[0] = bf16_to_f32(*p); }
+    static __device__ __forceinline__ void store(uint16_t* p, const float* v) { *p = (uint16_t)f32_to_bf16(v[0]); }
+};
+
+// VEC consecutive floats of out / grad_out; vector access when 16-byte aligned
+template <int VEC>
+__device__ __forceinline__ void load_f32(const float* p, float* v)
+{
+    if constexpr (VEC % 4 == 0) {
+        if ((reinterpret_cast<uintptr_t>(p) & 15) == 0) {
+#pragma unroll
+            for (int i = 0; i < VEC; i += 4) {
+                const float4 x = *reinterpret_cast<const float4*>(p + i);
+                v[i] = x.x; v[i + 1] = x.y; v[i + 2] = x.z; v[i + 3] = x.w;
+            }
+            return;
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) v[i] = p[i];
+}
+
+template <int VEC>
+__device__ __forceinline__ void store_f32(float* p, const float* v)
+{
+    if constexpr (VEC % 4 == 0) {
+        if ((reinterpret_cast<uintptr_t>(p) & 15) == 0) {
+#pragma unroll
+            for (int i = 0; i < VEC; i += 4)
+                *reinterpret_cast<float4*>(p + i) = make_float4(v[i], v[i + 1], v[i + 2], v[i + 3]);
+            return;
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) p[i] = v[i];
+}
+
+// ---------------------------------------------------------------------------
+// H3+H4+H5: Gather and SegmentReduction (Sec. II-D) fused (K-Packing, Sec.
+// III-B: both are memory-bound), one launch per pack.  A group of LPR lanes owns
+// one bag; each lane covers VEC (x NCH) columns, so a row is read with one
+// coalesced access.  The concatenation of the fields of a sample is the write
+// address.
+// ---------------------------------------------------------------------------
+template <typename WT, int VEC, int LPR, int NCH>
+__global__ void __launch_bounds__(NT)
+pk_pool_kernel(const WT* __restrict__ W, const uint32_t* __restrict__ keys_all, const int32_t* __restrict__ po,
+               const PackState* __restrict__ st, const FieldMeta* __restrict__ fmeta,
+               const int32_t* __restrict__ slot_field, int B, int D, int64_t n_bags,
+               float* __restrict__ out, int64_t out_stride)
+{
+    constexpr int GPB = NT / LPR;
+    const int li = threadIdx.x % LPR, gi = threadIdx.x / LPR;
+    const int n = st->nnz;
+    const uint32_t* keys = keys_all + st->start;
+    for (int64_t bag = (int64_t)blockIdx.x * GPB + gi; bag < n_bags; bag += (int64_t)gridDim.x * GPB) {
+        const int j = (int)(bag / B);
+        const int b = (int)(bag - (int64_t)j * B);
+        const FieldMeta m = fmeta[slot_field[j]];
+        const int q0 = min(max(po[bag], 0), n);
+        const int q1 = min(max(po[bag + 1], q0), n);
+        float acc[NCH][VEC];
+#pragma unroll
+        for (int c = 0; c < NCH; ++c)
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) acc[c][v] = 0.f;
+        int q = q0;
+        for (; q + 4 <= q1; q += 4) {
+            const size_t r0 = (size_t)keys[q] * D, r1 = (size_t)keys[q + 1] * D;
+            const size_t r2 = (size_t)keys[q + 2] * D, r3 = (size_t)keys[q + 3] * D;
+#pragma unroll
+            for (int c = 0; c < NCH; ++c) {
+                const int d0 = (c * LPR + li) * VEC;
+                if (d0 < D) {
+                    float x0[VEC], x1[VEC], x2[VEC], x3[VEC];
+                    Row<WT, VEC>::load(W + r0 + d0, x0);
+                    Row<WT, VEC>::load(W + r1 + d0, x1);
+                    Row<WT, VEC>::load(W + r2 + d0, x2);
+                    Row<WT, VEC>::load(W + r3 + d0, x3);
+#pragma unroll
+                    for (int v = 0; v < VEC; ++v) acc[c][v] += (x0[v] + x1[v]) + (x2[v] + x3[v]);
+                }
+            }
+        }
+        for (; q < q1; ++q) {
+            const size_t r0 = (size_t)keys[q] * D;
+#pragma unroll
+            for (int c = 0; c < NCH; ++c) {
+                const int d0 = (c * LPR + li) * VEC;
+                if (d0 < D) {
+                    float x0[VEC];
+                    Row<WT, VEC>::load(W + r0 + d0, x0);
+#pragma unroll
+                    for (int v = 0; v < VEC; ++v) acc[c][v] += x0[v];
+                }
+            }
+        }
+        const float scale = (m.pool == PK_MEAN && q1 > q0) ? 1.0f / (float)(q1 - q0) : 1.0f;
+        float* o = out + (size_t)b * out_stride + m.col;
+#pragma unroll
+        for (int c = 0; c < NCH; ++c) {
+            const int d0 = (c * LPR + li) * VEC;
+            if (d0 < D) {
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) acc[c][v] *= scale;
+                store_f32<VEC>(o + d0, acc[c]);
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// H6+H7: per distinct key, the gradients of its occurrences are reduced in
+// double (mirror of the forward pooling, Sec. II-D) and the row takes one
+// Adagrad step in place.  Fused so the reduced gradient never goes to memory.
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ size_t grad_addr(uint32_t ent, int64_t out_dim, int64_t gstride)
+{
+    if (gstride == out_dim) return ent;
+    const uint32_t b = ent / (uint32_t)out_dim;
+    return (size_t)b * gstride + (ent - b * (uint32_t)out_dim);
+}
+
+template <typename WT, int VEC, int LPR, int NCH>
+__device__ __forceinline__ void adagrad_row(WT* W, float* A, size_t row, int D, int li,
+                                            const double (&acc)[NCH][VEC], float lr, float eps)
+{
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) {
+        const int d0 = (c * LPR + li) * VEC;
+        if (d0 < D) {
+            float w[VEC], a[VEC];
+            Row<WT, VEC>::load(W + row * D + d0, w);
+            load_f32<VEC>(A + row * D + d0, a);
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) {
+                const float g = (float)acc[c][v];
+                a[v] = a[v] + g * g;
+                w[v] = w[v] - lr * g / (sqrtf(a[v]) + eps);
+            }
+            store_f32<VEC>(A + row * D + d0, a);
+            Row<WT, VEC>::store(W + row * D + d0, w);
+        }
+    }
+}
+
+template <typename WT, int VEC, int LPR, int NCH>
+__global__ void __launch_bounds__(NT)
+pk_adagrad_kernel(WT* W, float* A, const PackState* __restrict__ st, int p,
+                  const uint32_t* __restrict__ unique_all, const int32_t* __restrict__ cnt,
+                  const uint32_t* __restrict__ seg_ent_all, const float* __restrict__ seg_scale_all,
+                  const float* __restrict__ grad, int64_t gstride, int64_t out_dim, int D, float lr, float eps)
+{
+    constexpr int GPB = NT / LPR;
+    const int li = threadIdx.x % LPR, gi = threadIdx.x / LPR;
+    const int U = st->n_unique, start = st->start;
+    const int32_t* seg = cnt + start + p;
+    const uint32_t* ent = seg_ent_all + start;
+    const float* scl = seg_scale_all ? seg_scale_all + start : nullptr;
+    for (int u = blockIdx.x * GPB + gi; u < U; u += gridDim.x * GPB) {
+        const int s0 = seg[u], s1 = seg[u + 1];
+        if (s1 - s0 > kHotThreshold) continue;
+        double acc[NCH][VEC];
+#pragma unroll
+        for (int c = 0; c < NCH; ++c)
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) acc[c][v] = 0.0;
+        int s = s0;
+        for (; s + 2 <= s1; s += 2) {
+            const size_t a0 = grad_addr(ent[s], out_dim, gstride), a1 = grad_addr(ent[s + 1], out_dim, gstride);
+            const float c0 = scl ? scl[s] : 1.0f, c1 = scl ? scl[s + 1] : 1.0f;
+#pragma unroll
+            for (int c = 0; c < NCH; ++c) {
+                const int d0 = (c * LPR + li) * VEC;
+                if (d0 < D) {
+                    float x0[VEC], x1[VEC];
+                    load_f32<VEC>(grad + a0 + d0, x0);
+                    load_f32<VEC>(grad + a1 + d0, x1);
+#pragma unroll
+                    for (int v = 0; v < VEC; ++v) acc[c][v] += (double)(c0 * x0[v]) + (double)(c1 * x1[v]);
+                }
+            }
+        }
+        if (s < s1) {
+            const size_t a0 = grad_addr(ent[s], out_dim, gstride);
+            const float c0 = scl ? scl[s] : 1.0f;
+#pragma unroll
+            for (int c = 0; c < NCH; ++c) {
+                const int d0 = (c * LPR + li) * VEC;
+                if (d0 < D) {
+                    float x0[VEC];
+                    load_f32<VEC>(grad + a0 + d0, x0);
+#pragma unroll
+                    for (int v = 0; v < VEC; ++v) acc[c][v] += (double)(c0 * x0[v]);
+                }
+            }
+        }
+        adagrad_row<WT, VEC, LPR, NCH>(W, A, (size_t)unique_all[start + u], D, li, acc, lr, eps);
+    }
+}
+
+// keys with many occurrences (skewed IDs, Sec. II-B): one block per key
+template <typename WT, int VEC, int LPR, int NCH>
+__global__ void __launch_bounds__(NT)
+pk_adagrad_hot_kernel(WT* W, float* A, const PackState* __restrict__ st, int p,
+                      const uint32_t* __restrict__ unique_all, const int32_t* __restrict__ cnt,
+                      const int32_t* __restrict__ hot,
+                      const uint32_t* __restrict__ seg_ent_all, const float* __restrict__ seg_scale_all,
+                      const float* __restrict__ grad, int64_t gstride, int64_t out_dim, int D, float lr, float eps)
+{
+    constexpr int GPB = NT / LPR;
+    __shared__ double red[GPB][LPR][NCH][VEC];
+    const int li = threadIdx.x % LPR, gi = threadIdx.x / LPR;
+    const int start = st->start, n_hot = st->n_hot;
+    const int32_t* seg = cnt + start + p;
+    const int32_t* hl = hot + start / kHotThreshold + p;
+    const uint32_t* ent = seg_ent_all + start;
+    const float* scl = seg_scale_all ? seg_scale_all + start : nullptr;
+    for (int h = blockIdx.x; h < n_hot; h += gridDim.x) {
+        const int u = hl[h];
+        const int s0 = seg[u], s1 = seg[u + 1];
+        double acc[NCH][VEC];
+#pragma unroll
+        for (int c = 0; c < NCH; ++c)
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) acc[c][v] = 0.0;
+        for (int s = s0 + gi; s < s1; s += GPB) {
+            const size_t a0 = grad_addr(ent[s], out_dim, gstride);
+            const float c0 = scl ? scl[s] : 1.0f;
+#pragma unroll
+            for (int c = 0; c < NCH; ++c) {
+                const int d0 = (c * LPR + li) * VEC;
+                if (d0 < D) {
+                    float x0[VEC];
+                    load_f32<VEC>(grad + a0 + d0, x0);
+#pragma unroll
+                    for (int v = 0; v < VEC; ++v) acc[c][v] += (double)(c0 * x0[v]);
+                }
+            }
+        }
+        __syncthreads();   // previous key's readers are done with red
+#pragma unroll
+        for (int c = 0; c < NCH; ++c)
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) red[gi][li][c][v] = acc[c][v];
+        __syncthreads();
+        if (gi == 0) {
+#pragma unroll
+            for (int c = 0; c < NCH; ++c)
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) {
+                    double s = 0.0;
+                    for (int g = 0; g < GPB; ++g) s += red[g][li][c][v];
+                    acc[c][v] = s;
+                }
+            adagrad_row<WT, VEC, LPR, NCH>(W, A, (size_t)unique_all[start + u], D, li, acc, lr, eps);
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// host side
+// ---------------------------------------------------------------------------
+struct DeviceState {
+    int device = -1;
+    void* blob = nullptr;
+    FieldMeta* fmeta = nullptr;
+    PackMeta* pmeta = nullptr;
+    int32_t* slot_field = nullptr;
+    std::mutex mu;
+    // profiling
+    bool prof_on = false;
+    std::vector<hipEvent_t> events;
+    size_t events_used = 0;
+    struct Rec { const char* name; size_t e0; };
+    std::vector<Rec> recs;
+};
+
+std::string hip_msg(const char* what, hipError_t e)
+{
+    return std::string(what) + ": " + hipGetErrorString(e);
+}
+
+pk_status ensure_device_state(const pk_plan* cplan, DeviceState** out)
+{
+    pk_plan* plan = const_cast<pk_plan*>(cplan);
+    static std::mutex create_mu;
+    std::lock_guard<std::mutex> lock(create_mu);
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail(PK_EHIP, hip_msg("hipGetDevice", e));
+    DeviceState* ds = static_cast<DeviceState*>(plan->device_state);
+    if (ds && ds->device == dev) { *out = ds; return PK_OK; }
+    if (ds) return fail(PK_EINVAL, "a plan can be used on one device only");
+    ds = new DeviceState();
+    ds->device = dev;
+    const size_t F = plan->fields.size(), P = plan->packs.size();
+    std::vector<FieldMeta> fm(F);
+    for (size_t f = 0; f < F; ++f) {
+        const int32_t t = plan->fields[f].table;
+        fm[f].base_row = (uint32_t)plan->table_base[t];
+        fm[f].rows = (uint32_t)plan->tables[t].rows;
+        fm[f].col = (int32_t)plan->field_col[f];
+        fm[f].pack = plan->field_pack[f];
+        fm[f].slot = plan->field_slot[f];
+        fm[f].pool = plan->fields[f].pool;
+    }
+    std::vector<PackMeta> pmv(P);
+    for (size_t p = 0; p < P; ++p) {
+        const Pack& k = plan->packs[p];
+        pmv[p].dim = k.dim; pmv[p].dtype = k.dtype; pmv[p].n_fields = (int32_t)k.fields.size();
+        pmv[p].first_slot = k.first_slot; pmv[p].has_mean = k.has_mean ? 1 : 0;
+        pmv[p].first_tile = k.first_tile; pmv[p].n_tiles = k.n_tiles; pmv[p].pad = 0;
+    }
+    const size_t b_f = (F * sizeof(FieldMeta) + 255) / 256 * 256;
+    const size_t b_p = (P * sizeof(PackMeta) + 255) / 256 * 256;
+    const size_t b_s = (F * 4 + 255) / 256 * 256;
+    e = hipMalloc(&ds->blob, b_f + b_p + b_s);
+    if (e != hipSuccess) { delete ds; return fail(PK_EHIP, hip_msg("hipMalloc(plan metadata)", e)); }
+    ds->fmeta = reinterpret_cast<FieldMeta*>(ds->blob);
+    ds->pmeta = reinterpret_cast<PackMeta*>(static_cast<char*>(ds->blob) + b_f);
+    ds->slot_field = reinterpret_cast<int32_t*>(static_cast<char*>(ds->blob) + b_f + b_p);
+    e = hipMemcpy(ds->fmeta, fm.data(), F * sizeof(FieldMeta), hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = hipMemcpy(ds->pmeta, pmv.data(), P * sizeof(PackMeta), hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = hipMemcpy(ds->slot_field, plan->slot_field.data(), F * 4, hipMemcpyHostToDevice);
+    if (e != hipSuccess) { (void)hipFree(ds->blob); delete ds; return fail(PK_EHIP, hip_msg("hipMemcpy(plan metadata)", e)); }
+    plan->device_state = ds;
+    *out = ds;
+    return PK_OK;
+}
+
+void prof_begin(DeviceState* ds, const char* name, hipStream_t s)
+{
+    if (!ds->prof_on) return;
+    if (ds->events_used + 2 > ds->events.size()) {
+        const size_t old = ds->events.size();
+        ds->events.resize(old + 512);
+        for (size_t i = old; i < ds->events.size(); ++i) (void)hipEventCreate(&ds->events[i]);
+    }
+    ds->recs.push_back({name, ds->events_used});
+    (void)hipEventRecord(ds->events[ds->events_used], s);
+}
+
+void prof_end(DeviceState* ds, hipStream_t s)
+{
+    if (!ds->prof_on) return;
+    (void)hipEventRecord(ds->events[ds->events_used + 1], s);
+    ds->events_used += 2;
+}
+
+#define PK_LAUNCH(name, kernel, grid, block, shmem, ...)                                        \
+    do {                                                                                        \
+        prof_begin(ds, name, stream);                                                           \
+        kernel<<<grid, block, shmem, stream>>>(__VA_ARGS__);                                    \
+        prof_end(ds, stream);                                                                   \
+        hipError_t e_ = hipGetLastError();                                                      \
+        if (e_ != hipSuccess) return fail(PK_EHIP, hip_msg("launch of " name, e_));             \
+    } while (0)
+
+unsigned blocks_for(int64_t items, int64_t per_block, int64_t cap)
+{
+    int64_t b = (items + per_block - 1) / per_block;
+    if (b < 1) b = 1;
+    if (b > cap) b = cap;
+    return (unsigned)b;
+}
+
+int pow2_ceil(int v) { int p = 1; while (p < v) p <<= 1; return p; }
+
+// pack p's packed_offsets start (entries): the packs before it hold k*B+1 each
+int64_t po_off(const pk_plan* plan, int p, int32_t B)
+{
+    return (int64_t)plan->packs[p].first_slot * B + p;
+}
+
+struct Ws {
+    char* base;
+    Layout L;
+    template <typename T> T* at(size_t off) const { return reinterpret_cast<T*>(base + off); }
+};
+
+pk_status check_common(const pk_plan* plan, int32_t B, int64_t nnz, const void* ws, size_t ws_bytes, const char* who)
+{
+    if (!plan) return fail(PK_EINVAL, std::string(who) + ": plan is NULL");
+    if (B <= 0) return fail(PK_ESHAPE, std::string(who) + ": B must be positive");
+    if (nnz < 0) return fail(PK_ESHAPE, std::string(who) + ": nnz must be non-negative");
+    if (nnz >= ((int64_t)1 << 31)) return fail(PK_EOVERFLOW, std::string(who) + ": nnz must be below 2^31");
+    if (plan->opts.max_batch > 0 && B > plan->opts.max_batch) return fail(PK_ESHAPE, std::string(who) + ": B exceeds the plan's max_batch");
+    if (plan->opts.max_nnz > 0 && nnz > plan->opts.max_nnz) return fail(PK_ESHAPE, std::string(who) + ": nnz exceeds the plan's max_nnz");
+    if ((int64_t)B * plan->out_dim >= ((int64_t)1 << 32)) return fail(PK_EOVERFLOW, std::string(who) + ": B * out_dim must be below 2^32");
+    if ((int64_t)B * (int64_t)plan->fields.size() >= ((int64_t)1 << 31)) return fail(PK_EOVERFLOW, std::string(who) + ": n_fields * B must be below 2^31");
+    if (!ws) return fail(PK_EINVAL, std::string(who) + ": workspace is NULL");
+    if (reinterpret_cast<uintptr_t>(ws) % kAlign) return fail(PK_EWORKSPACE, std::string(who) + ": workspace must be 256-byte aligned");
+    if (ws_bytes < make_layout(plan, B, nnz).total) return fail(PK_EWORKSPACE, std::string(who) + ": workspace is smaller than pk_workspace_bytes");
+    return PK_OK;
+}
+
+// ---- per-pack template dispatch ------------------------------------------------
+struct PoolArgs {
+    const void* W; const uint32_t* keys; const int32_t* po; const PackState* st; const FieldMeta* fmeta;
+    const int32_t* slot_field; int B; int D; int64_t n_bags; float* out; int64_t out_stride; unsigned grid_cap;
+};
+struct AdaArgs {
+    void* W; float* A; const PackState* st; int p; const uint32_t* unique; const int32_t* cnt; const int32_t* hot;
+    const uint32_t* seg_ent; const float* seg_scale; const float* grad; int64_t gstride; int64_t out_dim; int D;
+    float lr; float eps; int64_t u_bound; int64_t hot_bound;
+};
+
+template <typename WT, int VEC, int LPR, int NCH>
+pk_status launch_pool(DeviceState* ds, hipStream_t stream, const PoolArgs& a)
+{
+    constexpr int GPB = NT / LPR;
+    const unsigned grid = blocks_for(a.n_bags, GPB, a.grid_cap);
+    PK_LAUNCH("pk_pool", (pk_pool_kernel<WT, VEC, LPR, NCH>), dim3(grid), dim3(NT), 0,
+              static_cast<const WT*>(a.W), a.keys, a.po, a.st, a.fmeta, a.slot_field, a.B, a.D, a.n_bags, a.out,
+              a.out_stride);
+    return PK_OK;
+}
+
+template <typename WT, int VEC, int LPR, int NCH>
+pk_status launch_adagrad(DeviceState* ds, hipStream_t stream, const AdaArgs& a)
+{
+    constexpr int GPB = NT / LPR;
+    const unsigned grid = blocks_for(a.u_bound, GPB, 256 * 32);
+    PK_LAUNCH("pk_adagrad", (pk_adagrad_kernel<WT, VEC, LPR, NCH>), dim3(grid), dim3(NT), 0,
+              static_cast<WT*>(a.W), a.A, a.st, a.p, a.unique, a.cnt, a.seg_ent, a.seg_scale, a.grad, a.gstride,
+              a.out_dim, a.D, a.lr, a.eps);
+    const unsigned hgrid = blocks_for(a.hot_bound, 1, 1024);
+    PK_LAUNCH("pk_adagrad_hot", (pk_adagrad_hot_kernel<WT, VEC, LPR, NCH>), dim3(hgrid), dim3(NT), 0,
+              static_cast<WT*>(a.W), a.A, a.st, a.p, a.unique, a.cnt, a.hot, a.seg_ent, a.seg_scale, a.grad,
+              a.gstride, a.out_dim, a.D, a.lr, a.eps);
+    return PK_OK;
+}
+
+// Picks lanes-per-row so that one row is one coalesced access: 16 bytes per
+// lane when the dimension allows it, else one element per lane.
+#define PK_DISPATCH_BODY(FN)                                                                    \
+    if (D % VECW == 0) {                                                                        \
+        switch (pow2_ceil(D / VECW)) {                                                          \
+            case 1:  return FN<WT, VECW, 1, 1>(ds, stream, a);                                  \
+            case 2:  return FN<WT, VECW, 2, 1>(ds, stream, a);                                  \
+            case 4:  return FN<WT, VECW, 4, 1>(ds, stream, a);                                  \
+            case 8:  return FN<WT, VECW, 8, 1>(ds, stream, a);                                  \
+            case 16: return FN<WT, VECW, 16, 1>(ds, stream, a);                                 \
+            case 32: return FN<WT, VECW, 32, 1>(ds, stream, a);                                 \
+            case 64: return FN<WT, VECW, 64, 1>(ds, stream, a);                                 \
+        }                                                                                       \
+    }                                                                                           \
+    if (D <= 4)   return FN<WT, 1, 4, 1>(ds, stream, a);                                        \
+    if (D <= 16)  return FN<WT, 1, 16, 1>(ds, stream, a);                                       \
+    if (D <= 64)  return FN<WT, 1, 64, 1>(ds, stream, a);                                       \
+    if (D <= 128) return FN<WT, 1, 64, 2>(ds, stream, a);                                       \
+    if (D <= 256) return FN<WT, 1, 64, 4>(ds, stream, a);                                       \
+    return fail(PK_EOVERFLOW, "dim above 256");
+
+template <typename WT, int VECW>
+pk_status dispatch_pool(DeviceState* ds, hipStream_t stream, int D, const PoolArgs& a) { PK_DISPATCH_BODY(launch_pool) }
+template <typename WT, int VECW>
+pk_status dispatch_adagrad(DeviceState* ds, hipStream_t stream, int D, const AdaArgs& a) { PK_DISPATCH_BODY(launch_adagrad) }
+
+}  // namespace
+
+namespace pk {
+void destroy_device_state(pk_plan* plan)
+{
+    DeviceState* ds = static_cast<DeviceState*>(plan->device_state);
+    if (!ds) return;
+    for (hipEvent_t ev : ds->events) (void)hipEventDestroy(ev);
+    if (ds->blob) (void)hipFree(ds->blob);
+    delete ds;
+    plan->device_state = nullptr;
+}
+}  // namespace pk
+
+extern "C" {
+
+pk_status pk_forward(const pk_plan* plan, void* const* W, const int64_t* ids, const int32_t* offsets, int32_t B,
+                     int64_t nnz, float* out, int64_t out_row_stride, void* workspace, size_t ws_bytes,
+                     void* hip_stream)
+{
+    pk_status rc = check_common(plan, B, nnz, workspace, ws_bytes, "pk_forward");
+    if (rc != PK_OK) return rc;
+    if (!W || !offsets || !out || (!ids && nnz > 0)) return fail(PK_EINVAL, "pk_forward: NULL argument");
+    const int P = (int)plan->packs.size(), F = (int)plan->fields.size();
+    for (int p = 0; p < P; ++p)
+        if (!W[p]) return fail(PK_EINVAL, "pk_forward: W[" + std::to_string(p) + "] is NULL");
+    if (out_row_stride < plan->out_dim) return fail(PK_ESHAPE, "pk_forward: out_row_stride is smaller than out_dim");
+    DeviceState* ds = nullptr;
+    rc = ensure_device_state(plan, &ds);
+    if (rc != PK_OK) return rc;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    Ws ws{static_cast<char*>(workspace), make_layout(plan, B, nnz)};
+    const Layout& L = ws.L;
+
+    PackState* st = ws.at<PackState>(L.state);
+    int32_t* fb = ws.at<int32_t>(L.fb);
+    int32_t* delta = ws.at<int32_t>(L.delta);
+    int32_t* slot_start = ws.at<int32_t>(L.slot_start);
+    int32_t* packed_offsets = ws.at<int32_t>(L.packed_offsets);
+    uint32_t* keys = ws.at<uint32_t>(L.keys);
+    int32_t* inverse = ws.at<int32_t>(L.inverse);
+    int32_t* occ_slot = ws.at<int32_t>(L.occ_slot);
+    uint32_t* seg_ent = ws.at<uint32_t>(L.seg_ent);
+    float* seg_scale = ws.at<float>(L.seg_scale);
+    uint32_t* unique = ws.at<uint32_t>(L.unique);
+    int32_t* cnt = ws.at<int32_t>(L.cnt);
+    int32_t* hot = ws.at<int32_t>(L.hot);
+    int32_t* tile_sum = ws.at<int32_t>(L.tile_sum);
+    int32_t* tile_off = ws.at<int32_t>(L.tile_off);
+    int32_t* seg_sum = ws.at<int32_t>(L.seg_sum);
+    uint32_t* bitmap = ws.at<uint32_t>(L.bitmap);
+    int32_t* rank = ws.at<int32_t>(L.rank);
+    const int64_t n_tiles = L.n_tiles_total;
+    const int64_t n_bitmap4 = n_tiles * kTileWords / 4;
+
+    const unsigned clear_blocks = blocks_for(n_bitmap4, 1024 * 4, 1024);
+    PK_LAUNCH("pk_setup", pk_setup_kernel, dim3(1 + clear_blocks), dim3(1024), 0, offsets, B, F, P, nnz, ds->pmeta,
+              ds->slot_field, st, fb, delta, slot_start, packed_offsets, reinterpret_cast<uint4*>(bitmap), n_bitmap4);
+
+    const int use_lds = (F + 1) * 4 <= 48 * 1024;
+    const int64_t key_items = std::max<int64_t>(nnz, (int64_t)F * B);
+    PK_LAUNCH("pk_keys", pk_keys_kernel, dim3(blocks_for(key_items, NT * 4, 256 * 16)), dim3(NT),
+              use_lds ? (size_t)(F + 1) * 4 : 0, ids, offsets, B, F, nnz, ds->fmeta, ds->pmeta, st, fb, delta,
+              slot_start, keys, bitmap, packed_offsets, use_lds);
+
+    for (int p = 0; p < P; ++p) {
+        const Pack& k = plan->packs[p];
+        PoolArgs a{W[p], keys, packed_offsets + po_off(plan, p, B), st + p, ds->fmeta, ds->slot_field + k.first_slot,
+                   B, k.dim, (int64_t)k.fields.size() * B, out, out_row_stride, 256 * 32};
+        rc = k.dtype == PK_F32 ? dispatch_pool<float, 4>(ds, stream, k.dim, a)
+                               : dispatch_pool<uint16_t, 8>(ds, stream, k.dim, a);
+        if (rc != PK_OK) return rc;
+    }
+
+    PK_LAUNCH("pk_tile_count", pk_tile_count_kernel, dim3((unsigned)n_tiles), dim3(NT), 0,
+              reinterpret_cast<const uint4*>(bitmap), tile_sum);
+    PK_LAUNCH("pk_tile_scan", pk_tile_scan_kernel, dim3(1), dim3(1024), 0, tile_sum, tile_off, ds->pmeta, st, P);
+    PK_LAUNCH("pk_tile_emit", pk_tile_emit_kernel, dim3((unsigned)n_tiles), dim3(NT), 0,
+              reinterpret_cast<const uint4*>(bitmap), tile_off, ds->pmeta, st, P, rank, unique, cnt);
+    const unsigned xq = blocks_for(nnz, NT * 4, 256 * 16);
+    PK_LAUNCH("pk_inverse", pk_inverse_kernel, dim3(xq, P), dim3(NT), 0, ds->pmeta, st, keys,
+              reinterpret_cast<const uint4*>(bitmap), rank, inverse, occ_slot, cnt);
+    PK_LAUNCH("pk_seg_sum", pk_seg_sum_kernel, dim3(kSegScanBlocks, P), dim3(NT), 0, st, cnt, seg_sum);
+    PK_LAUNCH("pk_seg_scan_sums", pk_seg_scan_sums_kernel, dim3(P), dim3(kSegScanBlocks), 0, seg_sum);
+    PK_LAUNCH("pk_seg_offsets", pk_seg_offsets_kernel, dim3(kSegScanBlocks, P), dim3(NT), 0, st, cnt, seg_sum, hot);
+    PK_LAUNCH("pk_scatter", pk_scatter_kernel, dim3(xq, P), dim3(NT), 0, offsets, B, plan->out_dim, ds->fmeta,
+              ds->pmeta, st, ds->slot_field, fb, slot_start, inverse, occ_slot, cnt, seg_ent, seg_scale);
+    return PK_OK;
+}
+
+pk_status pk_backward_update(const pk_plan* plan, void* const* W, float* const* A, const float* grad_out,
+                             int64_t grad_row_stride, int32_t B, int64_t nnz, float lr, float eps, void* workspace,
+                             size_t ws_bytes, void* hip_stream)
+{
+    pk_status rc = check_common(plan, B, nnz, workspace, ws_bytes, "pk_backward_update");
+    if (rc != PK_OK) return rc;
+    if (!W || !A || !grad_out) return fail(PK_EINVAL, "pk_backward_update: NULL argument");
+    const int P = (int)plan->packs.size();
+    for (int p = 0; p < P; ++p)
+        if (!W[p] || !A[p]) return fail(PK_EINVAL, "pk_backward_update: W or A of pack " + std::to_string(p) + " is NULL");
+    if (grad_row_stride < plan->out_dim) return fail(PK_ESHAPE, "pk_backward_update: grad_row_stride is smaller than out_dim");
+    DeviceState* ds = nullptr;
+    rc = ensure_device_state(plan, &ds);
+    if (rc != PK_OK) return rc;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    Ws ws{static_cast<char*>(workspace), make_layout(plan, B, nnz)};
+    const Layout& L = ws.L;
+    PackState* st = ws.at<PackState>(L.state);
+    for (int p = 0; p < P; ++p) {
+        const Pack& k = plan->packs[p];
+        const int64_t u_bound = std::max<int64_t>(1, std::min<int64_t>(nnz, k.rows));
+        AdaArgs a{W[p], A[p], st + p, p, ws.at<uint32_t>(L.unique), ws.at<int32_t>(L.cnt), ws.at<int32_t>(L.hot),
+                  ws.at<uint32_t>(L.seg_ent), k.has_mean ? ws.at<float>(L.seg_scale) : nullptr, grad_out,
+                  grad_row_stride, plan->out_dim, k.dim, lr, eps, u_bound, nnz / kHotThreshold + 1};
+        rc = k.dtype == PK_F32 ? dispatch_adagrad<float, 4>(ds, stream, k.dim, a)
+                               : dispatch_adagrad<uint16_t, 8>(ds, stream, k.dim, a);
+        if (rc != PK_OK) return rc;
+    }
+    return PK_OK;
+}
+
+pk_status pk_ctx_pack(const pk_plan* plan, const void* workspace, int32_t B, int64_t nnz, int32_t p,
+                      const uint32_t** keys, const uint32_t** unique, const int32_t** inverse,
+                      const int32_t** packed_offsets, const int32_t** seg_offsets, int64_t* nnz_p, int64_t* n_unique)
+{
+    if (!plan || !workspace) return fail(PK_EINVAL, "pk_ctx_pack: NULL argument");
+    if (p < 0 || p >= (int32_t)plan->packs.size()) return fail(PK_EINVAL, "pk_ctx_pack: pack out of range");
+    if (B <= 0 || nnz < 0) return fail(PK_ESHAPE, "pk_ctx_pack: bad B or nnz");
+    const Layout L = make_layout(plan, B, nnz);
+    const char* base = static_cast<const char*>(workspace);
+    PackState s;
+    hipError_t e = hipDeviceSynchronize();
+    if (e == hipSuccess) e = hipMemcpy(&s, base + L.state + (size_t)p * sizeof(PackState), sizeof(PackState), hipMemcpyDeviceToHost);
+    if (e != hipSuccess) return fail(PK_EHIP, hip_msg("pk_ctx_pack", e));
+    if (keys) *keys = reinterpret_cast<const uint32_t*>(base + L.keys) + s.start;
+    if (unique) *unique = reinterpret_cast<const uint32_t*>(base + L.unique) + s.start;
+    if (inverse) *inverse = reinterpret_cast<const int32_t*>(base + L.inverse) + s.start;
+    if (packed_offsets) *packed_offsets = reinterpret_cast<const int32_t*>(base + L.packed_offsets) + po_off(plan, p, B);
+    if (seg_offsets) *seg_offsets = reinterpret_cast<const int32_t*>(base + L.cnt) + s.start + p;
+    if (nnz_p) *nnz_p = s.nnz;
+    if (n_unique) *n_unique = s.n_unique;
+    return PK_OK;
+}
+
+pk_status pk_ctx_error(const pk_plan* plan, const void* workspace, int32_t* error_word)
+{
+    if (!plan || !workspace || !error_word) return fail(PK_EINVAL, "pk_ctx_error: NULL argument");
+    PackState s;
+    hipError_t e = hipDeviceSynchronize();
+    if (e == hipSuccess) e = hipMemcpy(&s, workspace, sizeof(PackState), hipMemcpyDeviceToHost);
+    if (e != hipSuccess) return fail(PK_EHIP, hip_msg("pk_ctx_error", e));
+    *error_word = s.error;
+    return PK_OK;
+}
+
+pk_status pk_profile_enable(pk_plan* plan, int32_t enable)
+{
+    if (!plan) return fail(PK_EINVAL, "pk_profile_enable: plan is NULL");
+    DeviceState* ds = nullptr;
+    pk_status rc = ensure_device_state(plan, &ds);
+    if (rc != PK_OK) return rc;
+    ds->prof_on = enable != 0;
+    if (!enable) { ds->recs.clear(); ds->events_used = 0; }
+    return PK_OK;
+}
+
+int32_t pk_profile_read(pk_plan* plan, const char** names, double* total_ms, int64_t* launches, int32_t max_entries)
+{
+    if (!plan || !plan->device_state || !names || !total_ms || !launches) return 0;
+    DeviceState* ds = static_cast<DeviceState*>(plan->device_state);
+    (void)hipDeviceSynchronize();
+    std::vector<const char*> order;
+    std::map<const char*, std::pair<double, int64_t>> acc;
+    for (const auto& r : ds->recs) {
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, ds->events[r.e0], ds->events[r.e0 + 1]) != hipSuccess) continue;
+        auto it = acc.find(r.name);
+        if (it == acc.end()) { order.push_back(r.name); it = acc.emplace(r.name, std::make_pair(0.0, (int64_t)0)).first; }
+        it->second.first += ms;
+        it->second.second += 1;
+    }
+    ds->recs.clear();
+    ds->events_used = 0;
+    int32_t n = 0;
+    for (const char* nm : order) {
+        if (n >= max_entries) break;
+        names[n] = nm; total_ms[n] = acc[nm].first; launches[n] = acc[nm].second;
+        ++n;
+    }
+    return n;
+}
+
+}  // extern "C"

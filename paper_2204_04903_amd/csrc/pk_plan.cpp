@@ -1,0 +1,215 @@
+// Host-side plan: which fields share a packed operation, and where everything
+// lives.  No HIP calls in this file, so the plan can be built and inspected on
+// a machine without a GPU.
+//
+// Packing rule (Sec. III-B, D-Packing): fields are packed together when their
+// embedding tables share the feature dimension, so the number of packed
+// operations follows the number of distinct dimensions, not of fields (Fig. 7:
+// three same-dimension tables are served by one set of packed operators).
+#include "pk_internal.h"
+
+#include <algorithm>
+#include <new>
+
+namespace pk {
+
+static thread_local std::string g_error;
+
+void set_error(const std::string& msg) { g_error = msg; }
+
+pk_status fail(pk_status s, const std::string& msg)
+{
+    g_error = msg;
+    return s;
+}
+
+static size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
+
+Layout make_layout(const pk_plan* plan, int32_t B, int64_t nnz)
+{
+    const size_t F = plan->fields.size(), P = plan->packs.size();
+    const size_t n = (size_t)std::max<int64_t>(nnz, 1);
+    Layout L{};
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
+    L.state          = take(P * sizeof(PackState));
+    L.fb             = take((F + 1) * 4);
+    L.delta          = take(F * 4);
+    L.slot_start     = take((F + P) * 4);
+    L.packed_offsets = take((F * (size_t)B + P) * 4);
+    L.keys           = take(n * 4);
+    L.inverse        = take(n * 4);
+    L.occ_slot       = take(n * 4);
+    L.seg_ent        = take(n * 4);
+    L.seg_scale      = take(plan->any_mean ? n * 4 : 4);
+    L.unique         = take(n * 4);
+    L.cnt            = take((n + P + 1) * 4);
+    L.hot            = take((n / kHotThreshold + P + 1) * 4);
+    L.n_tiles_total  = plan->n_tiles_total;
+    L.tile_sum       = take((size_t)plan->n_tiles_total * 4);
+    L.tile_off       = take((size_t)plan->n_tiles_total * 4);
+    L.seg_sum        = take(P * kSegScanBlocks * 4);
+    L.bitmap         = take((size_t)plan->n_tiles_total * kTileWords * 4);
+    L.rank           = take((size_t)plan->n_tiles_total * (kTileWords / kRankWords) * 4);
+    L.total = off;
+    return L;
+}
+
+}  // namespace pk
+
+using namespace pk;
+
+extern "C" {
+
+const char* pk_last_error(void) { return g_error.c_str(); }
+
+pk_status pk_plan_create(const pk_table_desc* tables, int32_t n_tables, const pk_field_desc* fields,
+                         int32_t n_fields, const pk_plan_opts* opts, pk_plan** out)
+{
+    if (!out) return fail(PK_EINVAL, "pk_plan_create: out is NULL");
+    *out = nullptr;
+    if (!tables || !fields) return fail(PK_EINVAL, "pk_plan_create: tables or fields is NULL");
+    if (n_tables <= 0 || n_fields <= 0) return fail(PK_EINVAL, "pk_plan_create: n_tables and n_fields must be positive");
+    for (int32_t t = 0; t < n_tables; ++t) {
+        if (tables[t].rows <= 0 || tables[t].dim <= 0)
+            return fail(PK_EINVAL, "pk_plan_create: table " + std::to_string(t) + " has non-positive rows or dim");
+        if (tables[t].dtype != PK_F32 && tables[t].dtype != PK_BF16)
+            return fail(PK_EINVAL, "pk_plan_create: table " + std::to_string(t) + " has an unknown dtype");
+        if (tables[t].dim > 256)
+            return fail(PK_EOVERFLOW, "pk_plan_create: table " + std::to_string(t) + " has dim > 256");
+    }
+    for (int32_t f = 0; f < n_fields; ++f) {
+        if (fields[f].table < 0 || fields[f].table >= n_tables)
+            return fail(PK_EINVAL, "pk_plan_create: field " + std::to_string(f) + " names a table out of range");
+        if (fields[f].pool != PK_SUM && fields[f].pool != PK_MEAN)
+            return fail(PK_EINVAL, "pk_plan_create: field " + std::to_string(f) + " has an unknown pooling mode");
+    }
+    if (opts && (opts->max_batch < 0 || opts->max_nnz < 0 || opts->max_shards < 0))
+        return fail(PK_EINVAL, "pk_plan_create: negative option");
+    if (opts && opts->max_shards > 1)
+        return fail(PK_EINVAL, "pk_plan_create: the Eq. 1 shard split is not available (max_shards must be 0 or 1)");
+
+    pk_plan* pl = new (std::nothrow) pk_plan();
+    if (!pl) return fail(PK_ENOMEM, "pk_plan_create: out of host memory");
+    pl->tables.assign(tables, tables + n_tables);
+    pl->fields.assign(fields, fields + n_fields);
+    if (opts) pl->opts = *opts;
+    pl->opts.field_volume = nullptr;   // not retained
+
+    // distinct (dim, dtype) pairs, ascending
+    std::vector<std::pair<int32_t, int32_t>> keys;
+    for (auto& t : pl->tables) keys.emplace_back(t.dim, t.dtype);
+    std::sort(keys.begin(), keys.end());
+    keys.erase(std::unique(keys.begin(), keys.end()), keys.end());
+    pl->packs.resize(keys.size());
+    for (size_t p = 0; p < keys.size(); ++p) { pl->packs[p].dim = keys[p].first; pl->packs[p].dtype = keys[p].second; }
+
+    pl->table_pack.resize(n_tables);
+    pl->table_base.resize(n_tables);
+    for (int32_t t = 0; t < n_tables; ++t) {
+        auto it = std::lower_bound(keys.begin(), keys.end(), std::make_pair(tables[t].dim, tables[t].dtype));
+        int32_t p = (int32_t)(it - keys.begin());
+        pl->table_pack[t] = p;
+        pl->table_base[t] = pl->packs[p].rows;
+        pl->packs[p].rows += tables[t].rows;
+        pl->packs[p].tables.push_back(t);
+    }
+    for (auto& pk_ : pl->packs)
+        if (pk_.rows >= ((int64_t)1 << 32)) {
+            delete pl;
+            return fail(PK_EOVERFLOW, "pk_plan_create: a pack has 2^32 or more rows");
+        }
+    pl->field_pack.resize(n_fields);
+    pl->field_slot.resize(n_fields);
+    pl->field_col.resize(n_fields);
+    int64_t col = 0;
+    for (int32_t f = 0; f < n_fields; ++f) {
+        int32_t p = pl->table_pack[fields[f].table];
+        pl->field_pack[f] = p;
+        pl->field_slot[f] = (int32_t)pl->packs[p].fields.size();
+        pl->packs[p].fields.push_back(f);
+        pl->field_col[f] = col;
+        col += tables[fields[f].table].dim;
+        if (fields[f].pool == PK_MEAN) { pl->packs[p].has_mean = true; pl->any_mean = true; }
+    }
+    pl->out_dim = col;
+    if (col >= ((int64_t)1 << 31)) {
+        delete pl;
+        return fail(PK_EOVERFLOW, "pk_plan_create: out_dim does not fit 31 bits");
+    }
+    int32_t slot0 = 0;
+    int64_t tile0 = 0;
+    for (auto& pk_ : pl->packs) {
+        pk_.first_slot = slot0;
+        slot0 += (int32_t)pk_.fields.size();
+        for (int32_t f : pk_.fields) pl->slot_field.push_back(f);
+        int64_t words = (pk_.rows + 31) / 32;
+        pk_.n_tiles = (int32_t)((words + kTileWords - 1) / kTileWords);
+        pk_.first_tile = (int32_t)tile0;
+        tile0 += pk_.n_tiles;
+    }
+    pl->n_tiles_total = (int32_t)tile0;
+    *out = pl;
+    return PK_OK;
+}
+
+void pk_plan_destroy(pk_plan* plan)
+{
+    if (!plan) return;
+    if (plan->device_state) destroy_device_state(plan);
+    delete plan;
+}
+
+int32_t pk_plan_num_packs(const pk_plan* plan) { return plan ? (int32_t)plan->packs.size() : -1; }
+
+pk_status pk_plan_pack_info(const pk_plan* plan, int32_t p, int32_t* dim, int32_t* dtype, int64_t* total_rows,
+                            int32_t* n_fields, int32_t* n_tables, int32_t* key_bytes)
+{
+    if (!plan) return fail(PK_EINVAL, "pk_plan_pack_info: plan is NULL");
+    if (p < 0 || p >= (int32_t)plan->packs.size()) return fail(PK_EINVAL, "pk_plan_pack_info: pack out of range");
+    const Pack& k = plan->packs[p];
+    if (dim) *dim = k.dim;
+    if (dtype) *dtype = k.dtype;
+    if (total_rows) *total_rows = k.rows;
+    if (n_fields) *n_fields = (int32_t)k.fields.size();
+    if (n_tables) *n_tables = (int32_t)k.tables.size();
+    if (key_bytes) *key_bytes = 4;
+    return PK_OK;
+}
+
+pk_status pk_plan_pack_fields(const pk_plan* plan, int32_t p, int32_t* fields_out)
+{
+    if (!plan || !fields_out) return fail(PK_EINVAL, "pk_plan_pack_fields: NULL argument");
+    if (p < 0 || p >= (int32_t)plan->packs.size()) return fail(PK_EINVAL, "pk_plan_pack_fields: pack out of range");
+    std::copy(plan->packs[p].fields.begin(), plan->packs[p].fields.end(), fields_out);
+    return PK_OK;
+}
+
+pk_status pk_plan_table_slot(const pk_plan* plan, int32_t table, int32_t* pack, int64_t* base_row)
+{
+    if (!plan) return fail(PK_EINVAL, "pk_plan_table_slot: plan is NULL");
+    if (table < 0 || table >= (int32_t)plan->tables.size()) return fail(PK_EINVAL, "pk_plan_table_slot: table out of range");
+    if (pack) *pack = plan->table_pack[table];
+    if (base_row) *base_row = plan->table_base[table];
+    return PK_OK;
+}
+
+pk_status pk_plan_field_col(const pk_plan* plan, int32_t field, int64_t* col_offset)
+{
+    if (!plan) return fail(PK_EINVAL, "pk_plan_field_col: plan is NULL");
+    if (field < 0 || field >= (int32_t)plan->fields.size()) return fail(PK_EINVAL, "pk_plan_field_col: field out of range");
+    if (col_offset) *col_offset = plan->field_col[field];
+    return PK_OK;
+}
+
+int64_t pk_plan_out_dim(const pk_plan* plan) { return plan ? plan->out_dim : -1; }
+
+size_t pk_workspace_bytes(const pk_plan* plan, int32_t B, int64_t nnz)
+{
+    if (!plan) { set_error("pk_workspace_bytes: plan is NULL"); return 0; }
+    if (B <= 0 || nnz < 0) { set_error("pk_workspace_bytes: B must be positive and nnz non-negative"); return 0; }
+    if (nnz >= ((int64_t)1 << 31)) { set_error("pk_workspace_bytes: nnz must be below 2^31"); return 0; }
+    return make_layout(plan, B, nnz).total;
+}
+
+}  // extern "C"

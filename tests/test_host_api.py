@@ -1,0 +1,114 @@
+"""Host-side checks that need no GPU: the library loads, exports every symbol
+the header declares, builds plans like the oracle does and rejects bad
+arguments with status codes."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import synth
+from oracle import pk_oracle as orc
+from paper_2204_04903_amd import binding as pk
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "pk.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(pk_[a-z_]+)\s*\(", header))
+    assert declared == set(pk.EXPORTS)
+    L = ctypes.CDLL(pk.LIB_PATH)
+    for name in declared:
+        assert hasattr(L, name), name
+
+
+@pytest.mark.parametrize("idx", [1, 2, 3, 4, 5])
+def test_plan_matches_oracle_plan(idx):
+    wl = synth.config(idx)
+    tables = [(t.rows, t.dim, t.dtype) for t in wl.tables]
+    fields = [(f.table, f.pool) for f in wl.fields]
+    ref = orc.plan(tables, fields)
+    plan = pk.pk_plan_create(tables, fields)
+    try:
+        assert pk.pk_plan_num_packs(plan) == ref.n_packs
+        assert pk.pk_plan_out_dim(plan) == ref.out_dim
+        for p in range(ref.n_packs):
+            info = pk.pk_plan_pack_info(plan, p)
+            assert (info["dim"], info["dtype"], info["total_rows"]) == (ref.pack_dim[p], ref.pack_dtype[p], ref.pack_rows[p])
+            assert pk.pk_plan_pack_fields(plan, p) == list(ref.pack_fields[p])
+            assert info["key_bytes"] == 4
+        for t in range(len(tables)):
+            assert pk.pk_plan_table_slot(plan, t) == (ref.table_pack[t], ref.table_base[t])
+        for f in range(len(fields)):
+            assert pk.pk_plan_field_col(plan, f) == ref.field_col[f]
+        B = wl.batch
+        nnz = int(wl.expected_nnz())
+        assert pk.pk_workspace_bytes(plan, B, nnz) > 24 * nnz
+    finally:
+        pk.pk_plan_destroy(plan)
+
+
+def test_plan_rejects_bad_arguments():
+    def status(fn):
+        with pytest.raises(pk.PkError) as e:
+            fn()
+        return e.value.status
+    assert status(lambda: pk.pk_plan_create([(0, 8, 0)], [(0, 0)])) == pk.PK_EINVAL
+    assert status(lambda: pk.pk_plan_create([(10, 0, 0)], [(0, 0)])) == pk.PK_EINVAL
+    assert status(lambda: pk.pk_plan_create([(10, 8, 7)], [(0, 0)])) == pk.PK_EINVAL
+    assert status(lambda: pk.pk_plan_create([(10, 8, 0)], [(1, 0)])) == pk.PK_EINVAL
+    assert status(lambda: pk.pk_plan_create([(10, 8, 0)], [(0, 5)])) == pk.PK_EINVAL
+    assert status(lambda: pk.pk_plan_create([(10, 8, 0)], [])) == pk.PK_EINVAL
+    assert status(lambda: pk.pk_plan_create([(10, 512, 0)], [(0, 0)])) == pk.PK_EOVERFLOW
+    assert status(lambda: pk.pk_plan_create([(2 ** 31, 8, 0), (2 ** 31, 8, 0)], [(0, 0)])) == pk.PK_EOVERFLOW
+    assert "rows" in pk.pk_last_error()
+
+
+def test_forward_rejects_bad_arguments_before_touching_the_gpu():
+    plan = pk.pk_plan_create([(100, 8, 0)], [(0, 0), (0, 1)], max_batch=64, max_nnz=1000)
+    try:
+        need = pk.pk_workspace_bytes(plan, 16, 100)
+        fake = 0x10000   # never dereferenced: every call below fails validation first
+
+        def fwd(**kw):
+            a = dict(W=[fake], ids=fake, offsets=fake, B=16, nnz=100, out=fake, stride=16, ws=fake, ws_bytes=need)
+            a.update(kw)
+            with pytest.raises(pk.PkError) as e:
+                pk.pk_forward(plan, a["W"], a["ids"], a["offsets"], a["B"], a["nnz"], a["out"], a["stride"],
+                              a["ws"], a["ws_bytes"])
+            return e.value.status
+        assert fwd(B=0) == pk.PK_ESHAPE
+        assert fwd(B=65) == pk.PK_ESHAPE
+        assert fwd(nnz=1001) == pk.PK_ESHAPE
+        assert fwd(nnz=-1) == pk.PK_ESHAPE
+        assert fwd(ws=None) == pk.PK_EINVAL
+        assert fwd(ws=fake + 4) == pk.PK_EWORKSPACE
+        assert fwd(ws_bytes=need - 1) == pk.PK_EWORKSPACE
+        assert fwd(ids=None) == pk.PK_EINVAL
+        assert fwd(W=[None]) == pk.PK_EINVAL
+        assert fwd(stride=15) == pk.PK_ESHAPE
+        with pytest.raises(pk.PkError) as e:
+            pk.pk_backward_update(plan, [fake], [fake], fake, 15, 16, 100, 0.01, 1e-8, fake, need)
+        assert e.value.status == pk.PK_ESHAPE
+        with pytest.raises(pk.PkError) as e:
+            pk.pk_backward_update(plan, [fake], [None], fake, 16, 16, 100, 0.01, 1e-8, fake, need)
+        assert e.value.status == pk.PK_EINVAL
+        with pytest.raises(pk.PkError):
+            pk.pk_workspace_bytes(plan, 16, 2 ** 31)
+    finally:
+        pk.pk_plan_destroy(plan)
+
+
+def test_generator_is_reproducible_and_shaped_like_the_configs():
+    wl = synth.config(3, batch=32, row_scale=0.001, n_fields=10)
+    a, b = synth.make_batch(wl, 2), synth.make_batches(wl, 3)[2]
+    assert np.array_equal(a.ids, b.ids) and np.array_equal(a.offsets, b.offsets) and np.array_equal(a.grad_out, b.grad_out)
+    assert a.offsets[0] == 0 and a.offsets[-1] == a.nnz and (np.diff(a.offsets) >= 1).all()
+    r1 = synth.table_rows(wl, 0, rows=[3, 1, 3])
+    r2 = synth.table_rows(wl, 0, row0=0, n=5)
+    assert np.array_equal(r1[0], r2[3]) and np.array_equal(r1[1], r2[1]) and np.array_equal(r1[0], r1[2])
+    big = synth.table_rows(synth.config(2), 0, row0=0, n=20000)
+    assert abs(float(big.std()) - 0.01) < 2e-4 and abs(float(big.mean())) < 2e-4
