@@ -1,0 +1,211 @@
+#!/usr/bin/env python3
+"""Benchmark of the packed multi-field embedding step (forward + backward +
+sparse Adagrad) on one MI355X.
+
+A "step" is one pass of the whole hot path over one batch: pk_forward followed
+by pk_backward_update.  Inputs (IDs, offsets, gradients) and tables are
+synthetic, seeded, and resident in HBM before the timed region; a ring of
+distinct batches is cycled so that no step sees the batch of the step before.
+Prints ONE JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+
+
+def algorithmic_bytes(info, mean_pack):
+    """Bytes each kernel must move for one pack with measured sizes
+    (nnz, U, k*B bags, dim D, element size sw, bitmap bytes bm).  Rows are
+    counted once per DISTINCT key: removing repeats is the method."""
+    n, U, bags, D, sw, bm = info["nnz"], info["U"], info["bags"], info["D"], info["sw"], info["bitmap_bytes"]
+    sc = 4 * n if mean_pack else 0
+    return {
+        "pk_keys": 8 * n + 4 * n + 4 * bags + 4 * bags + 4 * U,
+        "pk_pool": 4 * n + 4 * (bags + 1) + sw * D * U + 4 * D * bags,
+        "pk_tile_count": bm,
+        "pk_tile_emit": bm + bm // 8 + 8 * U,
+        "pk_inverse": 12 * n + 4 * U + min(bm + bm // 8, 36 * n),
+        "pk_seg_sum": 4 * U,
+        "pk_seg_offsets": 8 * U,
+        "pk_scatter": 12 * n + sc + 4 * U + 4 * bags,
+        "pk_adagrad": 4 * (U + 1) + 4 * U + 4 * n + sc + 4 * D * bags + (2 * sw + 8) * D * U,
+    }
+
+
+def step_model_bytes(info):
+    """Whole-step algorithmic traffic of one pack: ids, offsets, one read of each
+    distinct row, output write, gradient read, W and A read+write per distinct
+    row, inverse write+read, unique write+read."""
+    n, U, bags, D, sw = info["nnz"], info["U"], info["bags"], info["D"], info["sw"]
+    return (8 * n + 4 * (bags + 1) + sw * D * U + 4 * D * bags + 4 * D * bags + (2 * sw + 8) * D * U
+            + 8 * n + 8 * U)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
+    ap.add_argument("--ring", type=int, default=0, help="distinct batches cycled (default 16, 4 for cfg3-5)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only; run it with --gpus 1 (no collectives or sharding are "
+              "part of it)", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import synth
+    from paper_2204_04903_amd import binding as pk
+    from paper_2204_04903_amd.layer import PackedEmbedding
+
+    idx = int(args.workload[3])
+    wl = synth.config(idx)
+    ring = args.ring or (16 if idx <= 2 else 4)
+    tables = [(t.rows, t.dim, t.dtype) for t in wl.tables]
+    fields = [(f.table, f.pool) for f in wl.fields]
+    t0 = time.time()
+    batches = synth.make_batches(wl, ring)
+    gen_s = time.time() - t0
+
+    torch.cuda.set_device(0)
+    layer = PackedEmbedding(tables, fields)
+    stream = torch.cuda.current_stream().cuda_stream
+    for t, ts in enumerate(wl.tables):
+        synth.fill_device(layer.table_view(t).data_ptr(), ts.rows, ts.dim, ts.dtype, wl.seed, t, stream)
+    dev = [(torch.from_numpy(b.ids).cuda(), torch.from_numpy(b.offsets).cuda(), torch.from_numpy(b.grad_out).cuda())
+           for b in batches]
+    max_nnz = max(b.nnz for b in batches)
+    layer._ensure_ws(wl.batch, max_nnz)
+    out = torch.empty((wl.batch, layer.out_dim), dtype=torch.float32, device="cuda")
+    torch.cuda.synchronize()
+
+    def step(i):
+        ids, offsets, grad = dev[i % ring]
+        layer.forward(ids, offsets, wl.batch, out=out)
+        layer.backward_update(grad, wl.lr, wl.eps)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(args.warmup + i)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    lookups = sum(batches[(args.warmup + i) % ring].nnz for i in range(args.steps))
+    ms_per_step = elapsed * 1e3 / args.steps
+    value = lookups / elapsed
+
+    # ---- per-kernel durations (HIP events on the launch stream) and sizes --------------------
+    prof_steps = min(args.steps, 4 * ring)
+    pk.pk_profile_enable(layer.plan, True)
+    sizes = []                      # per profiled step, per pack
+    for i in range(prof_steps):
+        step(i)
+        row = []
+        for p in range(layer.n_packs):
+            d = pk.pk_ctx_pack(layer.plan, layer.ws, wl.batch, batches[i % ring].nnz, p)
+            info = layer.packs[p]
+            words = (info["total_rows"] + 31) // 32
+            tiles = (words + 2047) // 2048
+            row.append(dict(nnz=d["nnz_p"], U=d["n_unique"], bags=info["n_fields"] * wl.batch, D=info["dim"],
+                            sw=4 if info["dtype"] == 0 else 2, bitmap_bytes=tiles * 2048 * 4))
+        sizes.append(row)
+    prof = pk.pk_profile_read(layer.plan)
+    pk.pk_profile_enable(layer.plan, False)
+    mean_pack = [any(fields[f][1] == 1 for f in layer.pack_fields[p]) for p in range(layer.n_packs)]
+    kern = {}
+    for name, (ms, launches) in prof.items():
+        kern[name] = dict(ms_per_step=ms / prof_steps, launches_per_step=launches / prof_steps)
+    # fold the hot-key pass into the kernel it completes
+    if "pk_adagrad_hot" in kern:
+        kern["pk_adagrad"]["ms_per_step"] += kern.pop("pk_adagrad_hot")["ms_per_step"]
+    alg = {}
+    for row in sizes:
+        for p, info in enumerate(row):
+            for k, v in algorithmic_bytes(info, mean_pack[p]).items():
+                alg[k] = alg.get(k, 0) + v
+    model_bytes = sum(step_model_bytes(info) for row in sizes for info in row) / prof_steps
+    for k in kern:
+        if k in alg:
+            kern[k]["alg_bytes_per_step"] = alg[k] / prof_steps
+            kern[k]["GBps"] = alg[k] / prof_steps / (kern[k]["ms_per_step"] * 1e-3) / 1e9
+    dom = max(kern, key=lambda k: kern[k]["ms_per_step"])
+    dk = kern[dom]
+    launches = max(1.0, dk["launches_per_step"])
+    roofline = {
+        "kernel": dom,
+        "bound": "hbm",
+        "achieved": dk.get("GBps"),
+        "peak": HBM_PEAK_GBPS,
+        "unit": "GB/s",
+        "frac": (dk["GBps"] / HBM_PEAK_GBPS) if "GBps" in dk else None,
+        "traffic": None,
+        "alg_bytes_per_launch": dk.get("alg_bytes_per_step", 0) / launches,
+        "avg_launch_ms": dk["ms_per_step"] / launches,
+    }
+
+    # ---- the CPU oracle on the host cores, bounded sample --------------------------------------
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import pk_oracle as orc
+        from oracle.sparse_tables import SparseOracle
+        n_cpu = 3 if idx <= 2 else 1
+        so = SparseOracle(orc, synth, wl)
+        times, looks = [], 0
+        for i in range(n_cpu):
+            b = batches[i % ring]
+            pre = []
+            for p in range(so.pl.n_packs):            # materialise the rows outside the timed part
+                key, _ = orc.pack_keys(so.pl, p, wl.batch, b.ids, b.offsets)
+                uq, _ = orc.unique(key)
+                pre.append(so.current_rows(p, uq))
+            t1 = time.perf_counter()
+            so.step(b, wl.lr, wl.eps, rows=pre)
+            times.append(time.perf_counter() - t1)
+            looks += b.nnz
+        cpu = {"value": looks / sum(times), "unit": "lookups/s", "cores": 1, "kind": "oracle",
+               "sample": f"{n_cpu} batch(es) of {args.workload} ({looks} lookups), single thread; the rows of the "
+                         f"distinct keys are materialised by the input generator before the clock starts"}
+
+    result = {
+        "metric": "pooled embedding lookups/sec (fwd+bwd+update)",
+        "value": value,
+        "unit": "lookups/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32" if wl.tables[0].dtype == 0 else "bf16 tables, f32 arithmetic",
+        "data": "synthetic",
+        "config": {"workload": f"{args.workload}: {wl.description}", "batch": wl.batch, "fields": wl.n_fields,
+                   "packs": layer.n_packs, "ring_batches": ring, "lookups_per_step": lookups / args.steps,
+                   "distinct_keys_per_step": sum(i["U"] for i in sizes[0])},
+        "hbm_model": {"bytes_per_step": model_bytes, "GBps": model_bytes / (ms_per_step * 1e-3) / 1e9,
+                      "frac_of_peak": model_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS},
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+        "kernels": {k: {kk: round(vv, 6) for kk, vv in v.items()} for k, v in kern.items()},
+        "input_generation_s": round(gen_s, 2),
+    }
+    layer.close()
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

@@ -14,7 +14,8 @@ import torch
 
 import synth
 from oracle import pk_oracle as orc
-from helpers import small_problem, stack_tables, SparseOracle
+from oracle.sparse_tables import SparseOracle
+from helpers import small_problem, stack_tables
 
 pytestmark = pytest.mark.gpu
 
