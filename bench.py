@@ -30,11 +30,9 @@ def algorithmic_bytes(info, mean_pack):
     return {
         "pk_keys": 8 * n + 4 * n + 4 * bags + 4 * bags + 4 * U,
         "pk_pool": 4 * n + 4 * (bags + 1) + sw * D * U + 4 * D * bags,
-        "pk_tile_count": bm,
-        "pk_tile_emit": bm + bm // 8 + 8 * U,
+        "pk_tiles": bm + bm // 8 + 8 * U,
         "pk_inverse": 12 * n + 4 * U + min(bm + bm // 8, 36 * n),
-        "pk_seg_sum": 4 * U,
-        "pk_seg_offsets": 8 * U,
+        "pk_segs": 8 * U,
         "pk_scatter": 12 * n + sc + 4 * U + 4 * bags,
         "pk_adagrad": 4 * (U + 1) + 4 * U + 4 * n + sc + 4 * D * bags + (2 * sw + 8) * D * U,
     }

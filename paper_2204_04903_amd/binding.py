@@ -54,7 +54,7 @@ def build(force: bool = True) -> str:
         return LIB_PATH
     cmd = ["hipcc", "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
            "-I" + os.path.join(_ROOT, "include"),
-           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-munsafe-fp-atomics",
            "-o", LIB_PATH] + src
     subprocess.check_call(cmd)
     return LIB_PATH

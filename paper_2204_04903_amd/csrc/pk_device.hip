@@ -9,9 +9,9 @@
 //   setup     field boundaries, per-pack occurrence counts and positions, bitmap clear
 //   keys      H1: key = base_row + (uint64)id mod rows, packed order, mark bitmap
 //   pool      H3-H5: per pack, gather rows by key, pool per bag, write concatenated
-//   tiles     H2: popcount scan of the bitmap -> rank samples, distinct keys (ascending)
+//   tiles     H2: one-pass popcount scan of the bitmap -> rank samples, distinct keys (ascending)
 //   inverse   H2: inverse[q] = rank(key[q]); occurrence counts per distinct key
-//   segscan   H2: exclusive scan of the counts -> segment offsets; list of hot keys
+//   segs      H2: one-pass exclusive scan of the counts -> segment offsets; list of hot keys
 //   scatter   H2: occurrences grouped by distinct key (gradient addresses)
 //   adagrad   H6+H7: per pack, per distinct key: reduce gradients, update row in place
 #include <hip/hip_runtime.h>
@@ -77,20 +77,82 @@ __device__ __forceinline__ int upper_bound_i32(P a, int n, int x)
 }
 
 // ---------------------------------------------------------------------------
+// single-pass multi-block prefix sums: every tile publishes a 64-bit
+// descriptor (state | value b | value a) and sums the descriptors of the tiles
+// before it.  Tiles are handed out by an atomic ticket, so a tile only ever
+// waits for tiles that are already running: the wait always ends.  The wait is
+// bounded all the same; running out of patience sets error bit 1.
+// ---------------------------------------------------------------------------
+constexpr uint64_t kDescAgg = 1, kDescPfx = 2;
+constexpr int kSpinLimit = 1 << 22;
+
+__device__ __forceinline__ uint64_t make_desc(uint64_t state, uint32_t a, uint32_t b)
+{
+    return (state << 62) | ((uint64_t)b << 31) | (uint64_t)a;
+}
+
+__device__ __forceinline__ void publish_desc(uint64_t* d, uint64_t v)
+{
+    __hip_atomic_store(d, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Sum of (a, b) over tiles [first, me).  Called by all 64 lanes of one wave.
+__device__ __forceinline__ void lookback(uint64_t* desc, int first, int me, uint32_t* out_a, uint32_t* out_b,
+                                         int32_t* error_word)
+{
+    const int lane = threadIdx.x & 63;
+    uint32_t acc_a = 0, acc_b = 0;
+    int hi = me;
+    bool done = false;
+    while (hi > first && !done) {
+        const int idx = hi - 1 - lane;
+        const bool valid = idx >= first;
+        uint64_t d = make_desc(kDescPfx, 0, 0);
+        int spins = 0;
+        while (true) {
+            if (valid) d = __hip_atomic_load(desc + idx, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const bool ready = (d >> 62) != 0;
+            if (__ballot(ready) == ~0ull) break;
+            if (++spins > kSpinLimit) {
+                if (lane == 0) atomicOr(error_word, 2);
+                d = make_desc(kDescPfx, 0, 0);
+                break;
+            }
+            __builtin_amdgcn_s_sleep(2);
+        }
+        const uint64_t pfx_mask = __ballot((d >> 62) == kDescPfx);
+        int last = 64;                                   // lanes [0, last] contribute
+        if (pfx_mask) { last = __ffsll((unsigned long long)pfx_mask) - 1; done = true; }
+        if (lane <= last) {
+            acc_a += (uint32_t)(d & 0x7FFFFFFFull);
+            acc_b += (uint32_t)((d >> 31) & 0x7FFFFFFFull);
+        }
+        hi -= 64;
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        acc_a += __shfl_xor(acc_a, o, 64);
+        acc_b += __shfl_xor(acc_b, o, 64);
+    }
+    *out_a = acc_a;
+    *out_b = acc_b;
+}
+
+// ---------------------------------------------------------------------------
 // setup: block 0 derives the per-field and per-pack positions; the other
-// blocks clear the bitmap.
+// blocks clear the bitmap and the scan descriptors.
 // ---------------------------------------------------------------------------
 __global__ void __launch_bounds__(1024)
 pk_setup_kernel(const int32_t* __restrict__ offsets, int B, int F, int P, int64_t nnz,
                 const PackMeta* __restrict__ pm, const int32_t* __restrict__ slot_field,
                 PackState* st, int32_t* fb, int32_t* delta, int32_t* slot_start, int32_t* packed_offsets,
-                uint4* bitmap4, int64_t n_bitmap4)
+                uint4* clear4, int64_t n_clear4)
 {
     if (blockIdx.x != 0) {
         const uint4 z = make_uint4(0, 0, 0, 0);
         const int64_t stride = (int64_t)(gridDim.x - 1) * blockDim.x;
-        for (int64_t i = (int64_t)(blockIdx.x - 1) * blockDim.x + threadIdx.x; i < n_bitmap4; i += stride)
-            bitmap4[i] = z;
+        for (int64_t i = (int64_t)(blockIdx.x - 1) * blockDim.x + threadIdx.x; i < n_clear4; i += stride)
+            clear4[i] = z;
         return;
     }
     __shared__ int bad;
@@ -127,7 +189,7 @@ pk_setup_kernel(const int32_t* __restrict__ offsets, int B, int F, int P, int64_
             slot_start[fs + p + k] = carry;
             PackState s;
             s.nnz = carry; s.start = start; s.n_unique = 0; s.n_hot = 0; s.error = (p == 0) ? is_bad : 0;
-            s.pad[0] = s.pad[1] = s.pad[2] = 0;
+            s.seg_ticket = 0; s.tile_ticket = 0; s.pad = 0;
             st[p] = s;
             packed_offsets[(int64_t)fs * B + p + (int64_t)k * B] = carry;
         }
@@ -137,8 +199,19 @@ pk_setup_kernel(const int32_t* __restrict__ offsets, int B, int F, int P, int64_
 
 // ---------------------------------------------------------------------------
 // H1: packed keys (Sec. III-B: one packed ID tensor per pack) and bitmap marks;
-// packed bag offsets.
+// packed bag offsets.  Skewed IDs (Sec. II-B) would make thousands of lanes
+// hit the same bitmap word, and atomics on one address are served one at a
+// time: each block first removes repeats among its 1024 occurrences in an LDS
+// hash table, and only the first holder of a key touches the global bitmap.
 // ---------------------------------------------------------------------------
+constexpr int kKeyTile = 1024;
+constexpr int kHashSlots = 2048;
+
+__device__ __forceinline__ uint32_t hash_slot(uint64_t x)
+{
+    return (uint32_t)((x * 0x9E3779B97F4A7C15ull) >> 40) & (kHashSlots - 1);
+}
+
 __global__ void __launch_bounds__(NT)
 pk_keys_kernel(const int64_t* __restrict__ ids, const int32_t* __restrict__ offsets, int B, int F, int64_t nnz,
                const FieldMeta* __restrict__ fmeta, const PackMeta* __restrict__ pm, const PackState* __restrict__ st,
@@ -147,22 +220,40 @@ pk_keys_kernel(const int64_t* __restrict__ ids, const int32_t* __restrict__ offs
                int32_t* __restrict__ packed_offsets, int use_lds)
 {
     extern __shared__ int32_t s_fb[];
+    __shared__ unsigned long long s_tag[kHashSlots];
     if (st[0].error) return;
     if (use_lds) {
         for (int f = threadIdx.x; f <= F; f += NT) s_fb[f] = fb[f];
-        __syncthreads();
     }
-    const int64_t stride = (int64_t)gridDim.x * NT;
-    for (int64_t i = (int64_t)blockIdx.x * NT + threadIdx.x; i < nnz; i += stride) {
-        const int f = (use_lds ? upper_bound_i32(s_fb, F + 1, (int)i) : upper_bound_i32(fb, F + 1, (int)i)) - 1;
-        const FieldMeta m = fmeta[f];
-        const uint32_t key = m.base_row + fold_id(ids[i], m.rows);
-        const int64_t q = i + delta[f];
-        if ((uint64_t)q < (uint64_t)nnz) {
+    const int64_t n_tiles = (nnz + kKeyTile - 1) / kKeyTile;
+    for (int64_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+        __syncthreads();                               // table free again; s_fb loaded
+        for (int s = threadIdx.x; s < kHashSlots; s += NT) s_tag[s] = ~0ull;
+        __syncthreads();
+#pragma unroll
+        for (int k = 0; k < kKeyTile / NT; ++k) {
+            const int64_t i = tile * kKeyTile + k * NT + threadIdx.x;
+            if (i >= nnz) break;
+            const int f = (use_lds ? upper_bound_i32(s_fb, F + 1, (int)i) : upper_bound_i32(fb, F + 1, (int)i)) - 1;
+            const FieldMeta m = fmeta[f];
+            const uint32_t key = m.base_row + fold_id(ids[i], m.rows);
+            const int64_t q = i + delta[f];
+            if ((uint64_t)q >= (uint64_t)nnz) continue;
             keys[q] = key;
-            atomicOr(&bitmap[(size_t)pm[m.pack].first_tile * kTileWords + (key >> 5)], 1u << (key & 31));
+            const unsigned long long tag = ((unsigned long long)(uint32_t)m.pack << 32) | key;
+            uint32_t h = hash_slot(tag);
+            bool first = false;
+            while (true) {
+                const unsigned long long old = atomicCAS(&s_tag[h], ~0ull, tag);
+                if (old == ~0ull) { first = true; break; }
+                if (old == tag) break;
+                h = (h + 1) & (kHashSlots - 1);
+            }
+            if (first)
+                atomicOr(&bitmap[(size_t)pm[m.pack].first_tile * kTileWords + (key >> 5)], 1u << (key & 31));
         }
     }
+    const int64_t stride = (int64_t)gridDim.x * NT;
     const int64_t n_bags = (int64_t)F * B;
     for (int64_t g = (int64_t)blockIdx.x * NT + threadIdx.x; g < n_bags; g += stride) {
         const int f = (int)(g / B);
@@ -170,54 +261,29 @@ pk_keys_kernel(const int64_t* __restrict__ ids, const int32_t* __restrict__ offs
         const FieldMeta m = fmeta[f];
         const PackMeta k = pm[m.pack];
         packed_offsets[(int64_t)k.first_slot * B + m.pack + (int64_t)m.slot * B + b] =
-            slot_start[k.first_slot + m.pack + m.slot] + offsets[g] - (use_lds ? s_fb[f] : fb[f]);
+            slot_start[k.first_slot + m.pack + m.slot] + offsets[g] - fb[f];
     }
 }
 
 // ---------------------------------------------------------------------------
 // H2 (Unique, Sec. II-D) via a bitmap over the pack's rows: the ascending
 // distinct keys are the set bits in order, and the index of a key among them is
-// the number of set bits before it.
+// the number of set bits before it.  One pass: popcount per 256-bit block,
+// prefix over all blocks of the pack, rank samples, distinct keys written out.
 // ---------------------------------------------------------------------------
 __global__ void __launch_bounds__(NT)
-pk_tile_count_kernel(const uint4* __restrict__ bitmap4, int32_t* __restrict__ tile_sum)
+pk_tiles_kernel(const uint4* __restrict__ bitmap4, uint64_t* tile_desc,
+                const PackMeta* __restrict__ pm, PackState* st, int P,
+                int32_t* __restrict__ rank, uint32_t* __restrict__ unique, int32_t* __restrict__ cnt)
 {
-    const size_t t = (size_t)blockIdx.x * NT + threadIdx.x;
-    const uint4 a = bitmap4[2 * t], b = bitmap4[2 * t + 1];
-    int c = __popc(a.x) + __popc(a.y) + __popc(a.z) + __popc(a.w) +
-            __popc(b.x) + __popc(b.y) + __popc(b.z) + __popc(b.w);
-    int tot;
-    block_excl_scan<NT>(c, &tot);
-    if (threadIdx.x == 0) tile_sum[blockIdx.x] = tot;
-}
-
-__global__ void __launch_bounds__(1024)
-pk_tile_scan_kernel(const int32_t* __restrict__ tile_sum, int32_t* __restrict__ tile_off,
-                    const PackMeta* __restrict__ pm, PackState* st, int P)
-{
-    for (int p = 0; p < P; ++p) {
-        const int t0 = pm[p].first_tile, n = pm[p].n_tiles;
-        int carry = 0;
-        for (int base = 0; base < n; base += 1024) {
-            const int i = base + threadIdx.x;
-            const int v = i < n ? tile_sum[t0 + i] : 0;
-            int tot;
-            const int ex = block_excl_scan<1024>(v, &tot);
-            if (i < n) tile_off[t0 + i] = carry + ex;
-            carry += tot;
-        }
-        if (threadIdx.x == 0) st[p].n_unique = carry;
-    }
-}
-
-__global__ void __launch_bounds__(NT)
-pk_tile_emit_kernel(const uint4* __restrict__ bitmap4, const int32_t* __restrict__ tile_off,
-                    const PackMeta* __restrict__ pm, const PackState* __restrict__ st, int P,
-                    int32_t* __restrict__ rank, uint32_t* __restrict__ unique, int32_t* __restrict__ cnt)
-{
-    const int tile = blockIdx.x;
+    __shared__ int s_tile;
+    __shared__ uint32_t s_pre;
+    if (threadIdx.x == 0) s_tile = atomicAdd(&st[0].tile_ticket, 1);
+    __syncthreads();
+    const int tile = s_tile;
     int p = 0;
     while (p + 1 < P && tile >= pm[p + 1].first_tile) ++p;
+    const int first = pm[p].first_tile;
     const size_t t = (size_t)tile * NT + threadIdx.x;
     const uint4 a = bitmap4[2 * t], b = bitmap4[2 * t + 1];
     const uint32_t w[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
@@ -225,13 +291,29 @@ pk_tile_emit_kernel(const uint4* __restrict__ bitmap4, const int32_t* __restrict
 #pragma unroll
     for (int i = 0; i < 8; ++i) c += __popc(w[i]);
     int tot;
-    int pre = tile_off[tile] + block_excl_scan<NT>(c, &tot);
+    const int ex = block_excl_scan<NT>(c, &tot);
+    if (threadIdx.x < 64) {
+        if (tile == first) {
+            if (threadIdx.x == 0) { publish_desc(tile_desc + tile, make_desc(kDescPfx, (uint32_t)tot, 0)); s_pre = 0; }
+        } else {
+            if (threadIdx.x == 0) publish_desc(tile_desc + tile, make_desc(kDescAgg, (uint32_t)tot, 0));
+            uint32_t pa, pb;
+            lookback(tile_desc, first, tile, &pa, &pb, &st[0].error);
+            if (threadIdx.x == 0) {
+                publish_desc(tile_desc + tile, make_desc(kDescPfx, pa + (uint32_t)tot, 0));
+                s_pre = pa;
+            }
+        }
+    }
+    __syncthreads();
+    int pre = (int)s_pre + ex;
     rank[t] = pre;
+    if (tile == first + pm[p].n_tiles - 1 && threadIdx.x == NT - 1) st[p].n_unique = pre + c;
     if (c == 0) return;
     const int start = st[p].start;
     uint32_t* uq = unique + start;
     int32_t* cn = cnt + start + p;
-    const uint32_t key0 = ((uint32_t)(tile - pm[p].first_tile) * NT + threadIdx.x) * 256u;
+    const uint32_t key0 = ((uint32_t)(tile - first) * NT + threadIdx.x) * 256u;
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
         uint32_t x = w[i];
@@ -245,115 +327,195 @@ pk_tile_emit_kernel(const uint4* __restrict__ bitmap4, const int32_t* __restrict
     }
 }
 
+// inverse[q] = number of distinct keys below key[q]; occurrences counted per
+// distinct key.  Repeats inside a block's 1024 occurrences are merged in LDS
+// first, so a hot key costs one global atomic per block, not one per occurrence.
 __global__ void __launch_bounds__(NT)
 pk_inverse_kernel(const PackMeta* __restrict__ pm, const PackState* __restrict__ st,
                   const uint32_t* __restrict__ keys, const uint4* __restrict__ bitmap4,
                   const int32_t* __restrict__ rank, int32_t* __restrict__ inverse,
                   int32_t* __restrict__ occ_slot, int32_t* cnt)
 {
+    __shared__ uint32_t s_key[kHashSlots];
+    __shared__ int32_t s_cnt[kHashSlots];
     const int p = blockIdx.y;
     const int n = st[p].nnz, start = st[p].start;
     const size_t rb = (size_t)pm[p].first_tile * NT;          // rank blocks before this pack
     const uint4* bm = bitmap4 + 2 * rb;
     const int32_t* rk = rank + rb;
     int32_t* cn = cnt + start + p;
-    const int stride = gridDim.x * NT;
-    for (int q = blockIdx.x * NT + threadIdx.x; q < n; q += stride) {
-        const uint32_t key = keys[start + q];
-        const uint32_t blk = key >> 8;
-        const int wi = (key >> 5) & 7;
-        const uint4 a = bm[2 * (size_t)blk], b = bm[2 * (size_t)blk + 1];
-        const uint32_t w[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
-        int r = rk[blk];
-        uint32_t cur = 0;
+    const int n_tiles = (n + kKeyTile - 1) / kKeyTile;
+    for (int tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+        __syncthreads();
+        for (int s = threadIdx.x; s < kHashSlots; s += NT) { s_key[s] = 0xFFFFFFFFu; s_cnt[s] = 0; }
+        __syncthreads();
+        int r_[kKeyTile / NT], h_[kKeyTile / NT], l_[kKeyTile / NT];
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            if (i < wi) r += __popc(w[i]);
-            if (i == wi) cur = w[i];
+        for (int k = 0; k < kKeyTile / NT; ++k) {
+            const int q = tile * kKeyTile + k * NT + threadIdx.x;
+            r_[k] = -1; h_[k] = 0; l_[k] = 0;
+            if (q < n) {
+                const uint32_t key = keys[start + q];
+                const uint32_t blk = key >> 8;
+                const int wi = (key >> 5) & 7;
+                const uint4 a = bm[2 * (size_t)blk], b = bm[2 * (size_t)blk + 1];
+                const uint32_t w[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+                int r = rk[blk];
+                uint32_t cur = 0;
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    if (i < wi) r += __popc(w[i]);
+                    if (i == wi) cur = w[i];
+                }
+                r += __popc(cur & ((1u << (key & 31)) - 1u));
+                uint32_t h = hash_slot((uint64_t)(uint32_t)r);
+                while (true) {
+                    const uint32_t old = atomicCAS(&s_key[h], 0xFFFFFFFFu, (uint32_t)r);
+                    if (old == 0xFFFFFFFFu || old == (uint32_t)r) break;
+                    h = (h + 1) & (kHashSlots - 1);
+                }
+                r_[k] = r; h_[k] = (int)h; l_[k] = atomicAdd(&s_cnt[h], 1);
+            }
         }
-        r += __popc(cur & ((1u << (key & 31)) - 1u));
-        inverse[start + q] = r;
-        occ_slot[start + q] = atomicAdd(&cn[r], 1);
+        __syncthreads();
+        for (int s = threadIdx.x; s < kHashSlots; s += NT) {
+            const uint32_t r = s_key[s];
+            if (r != 0xFFFFFFFFu) s_cnt[s] = atomicAdd(&cn[r], s_cnt[s]);
+        }
+        __syncthreads();
+#pragma unroll
+        for (int k = 0; k < kKeyTile / NT; ++k) {
+            const int q = tile * kKeyTile + k * NT + threadIdx.x;
+            if (r_[k] >= 0) {
+                inverse[start + q] = r_[k];
+                occ_slot[start + q] = s_cnt[h_[k]] + l_[k];
+            }
+        }
     }
 }
 
-// exclusive scan of the occurrence counts of a pack's distinct keys, in place
+// Exclusive scan of the occurrence counts of a pack's distinct keys, in place
+// (counts -> segment offsets), in one pass.  Keys with more than kWarmMax
+// occurrences are listed (ascending) and get a zeroed row of partial sums.
 __global__ void __launch_bounds__(NT)
-pk_seg_sum_kernel(const PackState* __restrict__ st, const int32_t* __restrict__ cnt, int32_t* __restrict__ seg_sum)
+pk_segs_kernel(const PackMeta* __restrict__ pm, PackState* st, int32_t* cnt, uint64_t* seg_desc,
+               int32_t* __restrict__ hot, double* __restrict__ ghot, int dmax)
 {
+    __shared__ int s_tile;
+    __shared__ uint32_t s_pa, s_pb;
+    __shared__ unsigned long long s_w[NT / 64];
     const int p = blockIdx.y;
-    const int U = st[p].n_unique;
-    const int32_t* cn = cnt + st[p].start + p;
-    const int chunk = (U + gridDim.x - 1) / gridDim.x;
-    const int lo = blockIdx.x * chunk, hi = min(U, lo + chunk);
-    int s = 0;
-    for (int u = lo + threadIdx.x; u < hi; u += NT) s += cn[u];
-    int tot;
-    block_excl_scan<NT>(s, &tot);
-    if (threadIdx.x == 0) seg_sum[p * gridDim.x + blockIdx.x] = tot;
-}
-
-__global__ void __launch_bounds__(kSegScanBlocks)
-pk_seg_scan_sums_kernel(int32_t* seg_sum)
-{
-    const int i = blockIdx.x * kSegScanBlocks + threadIdx.x;
-    int tot;
-    seg_sum[i] = block_excl_scan<kSegScanBlocks>(seg_sum[i], &tot);
-}
-
-__global__ void __launch_bounds__(NT)
-pk_seg_offsets_kernel(PackState* st, int32_t* cnt, const int32_t* __restrict__ seg_sum, int32_t* __restrict__ hot)
-{
-    const int p = blockIdx.y;
-    const int U = st[p].n_unique, start = st[p].start;
+    const int U = st[p].n_unique, start = st[p].start, D = pm[p].dim;
     int32_t* cn = cnt + start + p;
-    int32_t* hl = hot + start / kHotThreshold + p;
-    const int chunk = (U + gridDim.x - 1) / gridDim.x;
-    const int lo = blockIdx.x * chunk, hi = min(U, lo + chunk);
-    int carry = seg_sum[p * gridDim.x + blockIdx.x];
-    for (int base = lo; base < hi; base += NT) {
-        const int u = base + threadIdx.x;
-        const int v = u < hi ? cn[u] : 0;
-        int tot;
-        const int ex = block_excl_scan<NT>(v, &tot);
-        if (u < hi) {
-            cn[u] = carry + ex;
-            if (v > kHotThreshold) hl[atomicAdd(&st[p].n_hot, 1)] = u;
-        }
-        carry += tot;
+    const size_t hbase = (size_t)(start / (kWarmMax + 1) + p);
+    int32_t* hl = hot + hbase;
+    double* gh = ghot + hbase * dmax;
+    uint64_t* desc = seg_desc + start / kSegTile + p;
+    const int n_tiles = (U + kSegTile - 1) / kSegTile;
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        cn[U] = st[p].nnz;
+        if (n_tiles == 0) st[p].n_hot = 0;
     }
-    if (blockIdx.x == 0 && threadIdx.x == 0) cn[U] = st[p].nnz;
+    while (true) {
+        __syncthreads();
+        if (threadIdx.x == 0) s_tile = atomicAdd(&st[p].seg_ticket, 1);
+        __syncthreads();
+        const int tile = s_tile;
+        if (tile >= n_tiles) break;
+        const int base = tile * kSegTile;
+        unsigned long long mine = 0;                     // low 32: occurrences, high 32: hot keys
+#pragma unroll
+        for (int k = 0; k < kSegTile / NT; ++k) {
+            const int u = base + k * NT + threadIdx.x;
+            const int v = u < U ? cn[u] : 0;
+            mine += (unsigned long long)(uint32_t)v + ((unsigned long long)(v > kWarmMax) << 32);
+        }
+        // tile totals
+        unsigned long long x = mine;
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) x += __shfl_xor(x, o, 64);
+        if (lane == 0) s_w[wv] = x;
+        __syncthreads();
+        unsigned long long tot = 0;
+#pragma unroll
+        for (int i = 0; i < NT / 64; ++i) tot += s_w[i];
+        const uint32_t tot_a = (uint32_t)tot, tot_b = (uint32_t)(tot >> 32);
+        if (threadIdx.x < 64) {
+            if (tile == 0) {
+                if (threadIdx.x == 0) { publish_desc(desc, make_desc(kDescPfx, tot_a, tot_b)); s_pa = 0; s_pb = 0; }
+            } else {
+                if (threadIdx.x == 0) publish_desc(desc + tile, make_desc(kDescAgg, tot_a, tot_b));
+                uint32_t pa, pb;
+                lookback(desc, 0, tile, &pa, &pb, &st[0].error);
+                if (threadIdx.x == 0) {
+                    publish_desc(desc + tile, make_desc(kDescPfx, pa + tot_a, pb + tot_b));
+                    s_pa = pa; s_pb = pb;
+                }
+            }
+        }
+        __syncthreads();
+        uint32_t carry_a = s_pa, carry_b = s_pb;
+        if (tile == n_tiles - 1 && threadIdx.x == 0) st[p].n_hot = (int)(carry_b + tot_b);
+        for (int k = 0; k < kSegTile / NT; ++k) {
+            const int u = base + k * NT + threadIdx.x;
+            const int v = u < U ? cn[u] : 0;
+            const int is_hot = v > kWarmMax;
+            int ta, tb;
+            const int ea = block_excl_scan<NT>(v, &ta);
+            const int eb = block_excl_scan<NT>(is_hot, &tb);
+            if (u < U) {
+                cn[u] = (int)carry_a + ea;
+                if (is_hot) {
+                    const size_t h = carry_b + eb;
+                    hl[h] = u;
+                    for (int d = 0; d < D; ++d) gh[h * D + d] = 0.0;
+                }
+            }
+            carry_a += ta;
+            carry_b += tb;
+        }
+    }
 }
 
-// occurrences grouped by distinct key: for each, where its gradient lives
+// Occurrences grouped by distinct key: for each, where its gradient lives (and
+// the 1/L of mean pooling).  A block takes 256 consecutive bags, whose
+// occurrences are contiguous, and finds each occurrence's bag in LDS.
 __global__ void __launch_bounds__(NT)
-pk_scatter_kernel(const int32_t* __restrict__ offsets, int B, int64_t out_dim,
-                  const FieldMeta* __restrict__ fmeta, const PackMeta* __restrict__ pm,
+pk_scatter_kernel(int B, int64_t out_dim, const FieldMeta* __restrict__ fmeta, const PackMeta* __restrict__ pm,
                   const PackState* __restrict__ st, const int32_t* __restrict__ slot_field,
-                  const int32_t* __restrict__ fb, const int32_t* __restrict__ slot_start,
+                  const int32_t* __restrict__ packed_offsets,
                   const int32_t* __restrict__ inverse, const int32_t* __restrict__ occ_slot,
                   const int32_t* __restrict__ cnt, uint32_t* __restrict__ seg_ent, float* __restrict__ seg_scale)
 {
+    __shared__ int32_t s_po[NT + 1];
     const int p = blockIdx.y;
     const int n = st[p].nnz, start = st[p].start;
     const PackMeta k = pm[p];
-    const int32_t* ss = slot_start + k.first_slot + p;
+    const int32_t* po = packed_offsets + (int64_t)k.first_slot * B + p;
     const int32_t* sf = slot_field + k.first_slot;
     const int32_t* cn = cnt + start + p;
-    const int stride = gridDim.x * NT;
-    for (int q = blockIdx.x * NT + threadIdx.x; q < n; q += stride) {
-        const int j = upper_bound_i32(ss, k.n_fields + 1, q) - 1;
-        const int f = sf[j];
-        const FieldMeta m = fmeta[f];
-        const int i = q - ss[j] + fb[f];                       // position in the caller's ids
-        const int32_t* bo = offsets + (int64_t)f * B;
-        const int b = upper_bound_i32(bo, B + 1, i) - 1;
-        const int pos = cn[inverse[start + q]] + occ_slot[start + q];
-        if ((unsigned)pos < (unsigned)n && (unsigned)b < (unsigned)B) {
-            seg_ent[start + pos] = (uint32_t)((int64_t)b * out_dim + m.col);
-            if (k.has_mean) {
-                const int L = bo[b + 1] - bo[b];
-                seg_scale[start + pos] = (m.pool == PK_MEAN && L > 0) ? 1.0f / (float)L : 1.0f;
+    const int64_t n_bags = (int64_t)k.n_fields * B;
+    for (int64_t bag0 = (int64_t)blockIdx.x * NT; bag0 < n_bags; bag0 += (int64_t)gridDim.x * NT) {
+        const int nb = (int)min((int64_t)NT, n_bags - bag0);
+        __syncthreads();
+        for (int t = threadIdx.x; t <= nb; t += NT) s_po[t] = min(max(po[bag0 + t], 0), n);
+        __syncthreads();
+        const int q_lo = s_po[0], q_hi = s_po[nb];
+        for (int q = q_lo + threadIdx.x; q < q_hi; q += NT) {
+            const int t = upper_bound_i32(s_po, nb + 1, q) - 1;
+            if ((unsigned)t >= (unsigned)nb) continue;
+            const int64_t g = bag0 + t;
+            const int j = (int)(g / B);
+            const int b = (int)(g - (int64_t)j * B);
+            const FieldMeta m = fmeta[sf[j]];
+            const int pos = cn[inverse[start + q]] + occ_slot[start + q];
+            if ((unsigned)pos < (unsigned)n) {
+                seg_ent[start + pos] = (uint32_t)((int64_t)b * out_dim + m.col);
+                if (k.has_mean) {
+                    const int L = s_po[t + 1] - s_po[t];
+                    seg_scale[start + pos] = (m.pool == PK_MEAN && L > 0) ? 1.0f / (float)L : 1.0f;
+                }
             }
         }
     }
@@ -517,12 +679,71 @@ pk_pool_kernel(const WT* __restrict__ W, const uint32_t* __restrict__ keys_all, 
 // H6+H7: per distinct key, the gradients of its occurrences are reduced in
 // double (mirror of the forward pooling, Sec. II-D) and the row takes one
 // Adagrad step in place.  Fused so the reduced gradient never goes to memory.
+//
+// Work is cut by OCCURRENCES, not by keys, because the ID distribution is
+// heavily skewed (Sec. II-B): a block takes kPosTile consecutive positions of
+// the key-sorted occurrence list and handles the keys that start there.
+//   up to kColdMax occurrences: one lane group per key;
+//   up to kWarmMax:             one wavefront per key, groups stride over it;
+//   more:                       every tile reduces its piece of the key and adds
+//                               it (double atomics) to the key's partial-sum row;
+//                               pk_adagrad_hot_kernel then applies the update.
 // ---------------------------------------------------------------------------
 __device__ __forceinline__ size_t grad_addr(uint32_t ent, int64_t out_dim, int64_t gstride)
 {
     if (gstride == out_dim) return ent;
     const uint32_t b = ent / (uint32_t)out_dim;
     return (size_t)b * gstride + (ent - b * (uint32_t)out_dim);
+}
+
+struct GradSrc {
+    const uint32_t* ent;    // per position: element offset of the gradient chunk in grad_out
+    const float* scl;       // per position: 1/L for mean pooling (nullptr: all ones)
+    const float* grad;
+    int64_t out_dim, gstride;
+};
+
+// acc += sum over positions s, s+step, ... < s_end of scale * grad chunk
+template <int VEC, int LPR, int NCH>
+__device__ __forceinline__ void accum_range(double (&acc)[NCH][VEC], const GradSrc& g, int D, int li,
+                                            int s, int s_end, int step)
+{
+    for (; s + 3 * step < s_end; s += 4 * step) {
+        size_t a[4];
+        float c[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            a[k] = grad_addr(g.ent[s + k * step], g.out_dim, g.gstride);
+            c[k] = g.scl ? g.scl[s + k * step] : 1.0f;
+        }
+#pragma unroll
+        for (int ch = 0; ch < NCH; ++ch) {
+            const int d0 = (ch * LPR + li) * VEC;
+            if (d0 < D) {
+                float x[4][VEC];
+#pragma unroll
+                for (int k = 0; k < 4; ++k) load_f32<VEC>(g.grad + a[k] + d0, x[k]);
+#pragma unroll
+                for (int v = 0; v < VEC; ++v)
+                    acc[ch][v] += ((double)(c[0] * x[0][v]) + (double)(c[1] * x[1][v])) +
+                                  ((double)(c[2] * x[2][v]) + (double)(c[3] * x[3][v]));
+            }
+        }
+    }
+    for (; s < s_end; s += step) {
+        const size_t a0 = grad_addr(g.ent[s], g.out_dim, g.gstride);
+        const float c0 = g.scl ? g.scl[s] : 1.0f;
+#pragma unroll
+        for (int ch = 0; ch < NCH; ++ch) {
+            const int d0 = (ch * LPR + li) * VEC;
+            if (d0 < D) {
+                float x0[VEC];
+                load_f32<VEC>(g.grad + a0 + d0, x0);
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) acc[ch][v] += (double)(c0 * x0[v]);
+            }
+        }
+    }
 }
 
 template <typename WT, int VEC, int LPR, int NCH>
@@ -548,117 +769,138 @@ __device__ __forceinline__ void adagrad_row(WT* W, float* A, size_t row, int D, 
     }
 }
 
+// sum over the lane groups of a wavefront (butterfly); every lane ends with the total
+template <int VEC, int LPR, int NCH>
+__device__ __forceinline__ void wave_group_sum(double (&acc)[NCH][VEC])
+{
+#pragma unroll
+    for (int o = LPR; o < 64; o <<= 1)
+#pragma unroll
+        for (int c = 0; c < NCH; ++c)
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) acc[c][v] += __shfl_xor(acc[c][v], o, 64);
+}
+
 template <typename WT, int VEC, int LPR, int NCH>
 __global__ void __launch_bounds__(NT)
 pk_adagrad_kernel(WT* W, float* A, const PackState* __restrict__ st, int p,
                   const uint32_t* __restrict__ unique_all, const int32_t* __restrict__ cnt,
+                  const int32_t* __restrict__ hot_all, double* ghot_all, int dmax,
                   const uint32_t* __restrict__ seg_ent_all, const float* __restrict__ seg_scale_all,
                   const float* __restrict__ grad, int64_t gstride, int64_t out_dim, int D, float lr, float eps)
 {
-    constexpr int GPB = NT / LPR;
+    constexpr int GPB = NT / LPR;          // lane groups per block
+    constexpr int GPW = 64 / LPR;          // lane groups per wavefront
+    __shared__ int s_lo, s_hi, s_nwarm, s_nhot;
+    __shared__ int s_warm[kPosTile / (kColdMax + 1) + 2];
+    __shared__ int s_hot[kPosTile / (kWarmMax + 1) + 4];
     const int li = threadIdx.x % LPR, gi = threadIdx.x / LPR;
-    const int U = st->n_unique, start = st->start;
+    const int wv = threadIdx.x >> 6, gw = (threadIdx.x & 63) / LPR;
+    const int n = st->nnz, U = st->n_unique, start = st->start, n_hot = st->n_hot;
     const int32_t* seg = cnt + start + p;
-    const uint32_t* ent = seg_ent_all + start;
-    const float* scl = seg_scale_all ? seg_scale_all + start : nullptr;
-    for (int u = blockIdx.x * GPB + gi; u < U; u += gridDim.x * GPB) {
-        const int s0 = seg[u], s1 = seg[u + 1];
-        if (s1 - s0 > kHotThreshold) continue;
-        double acc[NCH][VEC];
-#pragma unroll
-        for (int c = 0; c < NCH; ++c)
-#pragma unroll
-            for (int v = 0; v < VEC; ++v) acc[c][v] = 0.0;
-        int s = s0;
-        for (; s + 2 <= s1; s += 2) {
-            const size_t a0 = grad_addr(ent[s], out_dim, gstride), a1 = grad_addr(ent[s + 1], out_dim, gstride);
-            const float c0 = scl ? scl[s] : 1.0f, c1 = scl ? scl[s + 1] : 1.0f;
-#pragma unroll
-            for (int c = 0; c < NCH; ++c) {
-                const int d0 = (c * LPR + li) * VEC;
-                if (d0 < D) {
-                    float x0[VEC], x1[VEC];
-                    load_f32<VEC>(grad + a0 + d0, x0);
-                    load_f32<VEC>(grad + a1 + d0, x1);
-#pragma unroll
-                    for (int v = 0; v < VEC; ++v) acc[c][v] += (double)(c0 * x0[v]) + (double)(c1 * x1[v]);
-                }
-            }
-        }
-        if (s < s1) {
-            const size_t a0 = grad_addr(ent[s], out_dim, gstride);
-            const float c0 = scl ? scl[s] : 1.0f;
-#pragma unroll
-            for (int c = 0; c < NCH; ++c) {
-                const int d0 = (c * LPR + li) * VEC;
-                if (d0 < D) {
-                    float x0[VEC];
-                    load_f32<VEC>(grad + a0 + d0, x0);
-#pragma unroll
-                    for (int v = 0; v < VEC; ++v) acc[c][v] += (double)(c0 * x0[v]);
-                }
-            }
-        }
-        adagrad_row<WT, VEC, LPR, NCH>(W, A, (size_t)unique_all[start + u], D, li, acc, lr, eps);
-    }
-}
-
-// keys with many occurrences (skewed IDs, Sec. II-B): one block per key
-template <typename WT, int VEC, int LPR, int NCH>
-__global__ void __launch_bounds__(NT)
-pk_adagrad_hot_kernel(WT* W, float* A, const PackState* __restrict__ st, int p,
-                      const uint32_t* __restrict__ unique_all, const int32_t* __restrict__ cnt,
-                      const int32_t* __restrict__ hot,
-                      const uint32_t* __restrict__ seg_ent_all, const float* __restrict__ seg_scale_all,
-                      const float* __restrict__ grad, int64_t gstride, int64_t out_dim, int D, float lr, float eps)
-{
-    constexpr int GPB = NT / LPR;
-    __shared__ double red[GPB][LPR][NCH][VEC];
-    const int li = threadIdx.x % LPR, gi = threadIdx.x / LPR;
-    const int start = st->start, n_hot = st->n_hot;
-    const int32_t* seg = cnt + start + p;
-    const int32_t* hl = hot + start / kHotThreshold + p;
-    const uint32_t* ent = seg_ent_all + start;
-    const float* scl = seg_scale_all ? seg_scale_all + start : nullptr;
-    for (int h = blockIdx.x; h < n_hot; h += gridDim.x) {
-        const int u = hl[h];
-        const int s0 = seg[u], s1 = seg[u + 1];
-        double acc[NCH][VEC];
-#pragma unroll
-        for (int c = 0; c < NCH; ++c)
-#pragma unroll
-            for (int v = 0; v < VEC; ++v) acc[c][v] = 0.0;
-        for (int s = s0 + gi; s < s1; s += GPB) {
-            const size_t a0 = grad_addr(ent[s], out_dim, gstride);
-            const float c0 = scl ? scl[s] : 1.0f;
-#pragma unroll
-            for (int c = 0; c < NCH; ++c) {
-                const int d0 = (c * LPR + li) * VEC;
-                if (d0 < D) {
-                    float x0[VEC];
-                    load_f32<VEC>(grad + a0 + d0, x0);
-#pragma unroll
-                    for (int v = 0; v < VEC; ++v) acc[c][v] += (double)(c0 * x0[v]);
-                }
-            }
-        }
-        __syncthreads();   // previous key's readers are done with red
-#pragma unroll
-        for (int c = 0; c < NCH; ++c)
-#pragma unroll
-            for (int v = 0; v < VEC; ++v) red[gi][li][c][v] = acc[c][v];
+    const uint32_t* uq = unique_all + start;
+    const size_t hbase = (size_t)(start / (kWarmMax + 1) + p);
+    const int32_t* hl = hot_all + hbase;
+    double* gh = ghot_all + hbase * dmax;
+    GradSrc g{seg_ent_all + start, seg_scale_all ? seg_scale_all + start : nullptr, grad, out_dim, gstride};
+    const int n_tiles = (n + kPosTile - 1) / kPosTile;
+    for (int tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+        const int t0 = tile * kPosTile, t1 = min(t0 + kPosTile, n);
+        __syncthreads();                                   // lists of the previous tile are consumed
+        if (threadIdx.x == 0) { s_lo = upper_bound_i32(seg, U + 1, t0) - 1; s_nwarm = 0; s_nhot = 0; }
+        if (threadIdx.x == 64) s_hi = upper_bound_i32(seg, U + 1, t1 - 1) - 1;
         __syncthreads();
-        if (gi == 0) {
+        const int u_lo = s_lo, u_hi = s_hi;
+        // keys overlapping the tile: cold ones that start here are finished on the spot
+        for (int u = u_lo + gi; u <= u_hi; u += GPB) {
+            const int s0 = seg[u], s1 = seg[u + 1];
+            const int len = s1 - s0;
+            if (len <= kColdMax) {
+                if (s0 >= t0) {
+                    double acc[NCH][VEC];
+#pragma unroll
+                    for (int c = 0; c < NCH; ++c)
+#pragma unroll
+                        for (int v = 0; v < VEC; ++v) acc[c][v] = 0.0;
+                    accum_range<VEC, LPR, NCH>(acc, g, D, li, s0, s1, 1);
+                    adagrad_row<WT, VEC, LPR, NCH>(W, A, (size_t)uq[u], D, li, acc, lr, eps);
+                }
+            } else if (len <= kWarmMax) {
+                if (s0 >= t0 && li == 0) s_warm[atomicAdd(&s_nwarm, 1)] = u;
+            } else if (li == 0) {
+                s_hot[atomicAdd(&s_nhot, 1)] = u;
+            }
+        }
+        __syncthreads();
+        // warm keys that start here: one wavefront each
+        const int n_warm = s_nwarm;
+        for (int k = wv; k < n_warm; k += NT / 64) {
+            const int u = s_warm[k];
+            const int s0 = seg[u], s1 = seg[u + 1];
+            double acc[NCH][VEC];
 #pragma unroll
             for (int c = 0; c < NCH; ++c)
 #pragma unroll
-                for (int v = 0; v < VEC; ++v) {
-                    double s = 0.0;
-                    for (int g = 0; g < GPB; ++g) s += red[g][li][c][v];
-                    acc[c][v] = s;
-                }
-            adagrad_row<WT, VEC, LPR, NCH>(W, A, (size_t)unique_all[start + u], D, li, acc, lr, eps);
+                for (int v = 0; v < VEC; ++v) acc[c][v] = 0.0;
+            accum_range<VEC, LPR, NCH>(acc, g, D, li, s0 + gw, s1, GPW);
+            wave_group_sum<VEC, LPR, NCH>(acc);
+            if (gw == 0) adagrad_row<WT, VEC, LPR, NCH>(W, A, (size_t)uq[u], D, li, acc, lr, eps);
         }
+        // hot keys: this tile's piece, 256 positions per wavefront, added to the key's partial sums
+        const int n_hot_here = s_nhot;
+        for (int k = 0; k < n_hot_here; ++k) {
+            const int u = s_hot[k];
+            const int a = max(seg[u], t0), b = min(seg[u + 1], t1);
+            // row of partial sums: position of u in the ascending list of hot keys
+            int lo = 0, hi = n_hot;
+            while (lo < hi) { const int mid = (lo + hi) >> 1; if (hl[mid] < u) lo = mid + 1; else hi = mid; }
+            double* row = gh + (size_t)lo * D;
+            for (int c0 = a + wv * 256; c0 < b; c0 += (NT / 64) * 256) {
+                const int c1 = min(c0 + 256, b);
+                double acc[NCH][VEC];
+#pragma unroll
+                for (int c = 0; c < NCH; ++c)
+#pragma unroll
+                    for (int v = 0; v < VEC; ++v) acc[c][v] = 0.0;
+                accum_range<VEC, LPR, NCH>(acc, g, D, li, c0 + gw, c1, GPW);
+                wave_group_sum<VEC, LPR, NCH>(acc);
+                if (gw == 0) {
+#pragma unroll
+                    for (int c = 0; c < NCH; ++c) {
+                        const int d0 = (c * LPR + li) * VEC;
+                        if (d0 < D) {
+#pragma unroll
+                            for (int v = 0; v < VEC; ++v) atomicAdd(row + d0 + v, acc[c][v]);
+                        }
+                    }
+                }
+            }
+        }
+    }
+}
+
+// hot keys: partial sums are complete, apply the update (one lane group per key)
+template <typename WT, int VEC, int LPR, int NCH>
+__global__ void __launch_bounds__(NT)
+pk_adagrad_hot_kernel(WT* W, float* A, const PackState* __restrict__ st, int p,
+                      const uint32_t* __restrict__ unique_all, const int32_t* __restrict__ hot_all,
+                      const double* __restrict__ ghot_all, int dmax, int D, float lr, float eps)
+{
+    constexpr int GPB = NT / LPR;
+    const int li = threadIdx.x % LPR, gi = threadIdx.x / LPR;
+    const int start = st->start, n_hot = st->n_hot;
+    const size_t hbase = (size_t)(start / (kWarmMax + 1) + p);
+    const int32_t* hl = hot_all + hbase;
+    const double* gh = ghot_all + hbase * dmax;
+    for (int h = blockIdx.x * GPB + gi; h < n_hot; h += gridDim.x * GPB) {
+        double acc[NCH][VEC];
+#pragma unroll
+        for (int c = 0; c < NCH; ++c) {
+            const int d0 = (c * LPR + li) * VEC;
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) acc[c][v] = d0 < D ? gh[(size_t)h * D + d0 + v] : 0.0;
+        }
+        adagrad_row<WT, VEC, LPR, NCH>(W, A, (size_t)unique_all[start + hl[h]], D, li, acc, lr, eps);
     }
 }
 
@@ -806,8 +1048,9 @@ struct PoolArgs {
 };
 struct AdaArgs {
     void* W; float* A; const PackState* st; int p; const uint32_t* unique; const int32_t* cnt; const int32_t* hot;
+    double* ghot; int dmax;
     const uint32_t* seg_ent; const float* seg_scale; const float* grad; int64_t gstride; int64_t out_dim; int D;
-    float lr; float eps; int64_t u_bound; int64_t hot_bound;
+    float lr; float eps; int64_t nnz_bound;
 };
 
 template <typename WT, int VEC, int LPR, int NCH>
@@ -825,14 +1068,13 @@ template <typename WT, int VEC, int LPR, int NCH>
 pk_status launch_adagrad(DeviceState* ds, hipStream_t stream, const AdaArgs& a)
 {
     constexpr int GPB = NT / LPR;
-    const unsigned grid = blocks_for(a.u_bound, GPB, 256 * 32);
+    const unsigned grid = blocks_for(a.nnz_bound, kPosTile, 256 * 8);
     PK_LAUNCH("pk_adagrad", (pk_adagrad_kernel<WT, VEC, LPR, NCH>), dim3(grid), dim3(NT), 0,
-              static_cast<WT*>(a.W), a.A, a.st, a.p, a.unique, a.cnt, a.seg_ent, a.seg_scale, a.grad, a.gstride,
-              a.out_dim, a.D, a.lr, a.eps);
-    const unsigned hgrid = blocks_for(a.hot_bound, 1, 1024);
+              static_cast<WT*>(a.W), a.A, a.st, a.p, a.unique, a.cnt, a.hot, a.ghot, a.dmax, a.seg_ent, a.seg_scale,
+              a.grad, a.gstride, a.out_dim, a.D, a.lr, a.eps);
+    const unsigned hgrid = blocks_for(a.nnz_bound / (kWarmMax + 1) + 1, GPB, 1024);
     PK_LAUNCH("pk_adagrad_hot", (pk_adagrad_hot_kernel<WT, VEC, LPR, NCH>), dim3(hgrid), dim3(NT), 0,
-              static_cast<WT*>(a.W), a.A, a.st, a.p, a.unique, a.cnt, a.hot, a.seg_ent, a.seg_scale, a.grad,
-              a.gstride, a.out_dim, a.D, a.lr, a.eps);
+              static_cast<WT*>(a.W), a.A, a.st, a.p, a.unique, a.hot, a.ghot, a.dmax, a.D, a.lr, a.eps);
     return PK_OK;
 }
 
@@ -909,21 +1151,21 @@ pk_status pk_forward(const pk_plan* plan, void* const* W, const int64_t* ids, co
     uint32_t* unique = ws.at<uint32_t>(L.unique);
     int32_t* cnt = ws.at<int32_t>(L.cnt);
     int32_t* hot = ws.at<int32_t>(L.hot);
-    int32_t* tile_sum = ws.at<int32_t>(L.tile_sum);
-    int32_t* tile_off = ws.at<int32_t>(L.tile_off);
-    int32_t* seg_sum = ws.at<int32_t>(L.seg_sum);
+    double* ghot = ws.at<double>(L.ghot);
     uint32_t* bitmap = ws.at<uint32_t>(L.bitmap);
+    uint64_t* tile_desc = ws.at<uint64_t>(L.tile_desc);
+    uint64_t* seg_desc = ws.at<uint64_t>(L.seg_desc);
     int32_t* rank = ws.at<int32_t>(L.rank);
     const int64_t n_tiles = L.n_tiles_total;
-    const int64_t n_bitmap4 = n_tiles * kTileWords / 4;
+    const int64_t n_clear4 = (int64_t)(L.clear_bytes / 16);
 
-    const unsigned clear_blocks = blocks_for(n_bitmap4, 1024 * 4, 1024);
+    const unsigned clear_blocks = blocks_for(n_clear4, 1024 * 4, 1024);
     PK_LAUNCH("pk_setup", pk_setup_kernel, dim3(1 + clear_blocks), dim3(1024), 0, offsets, B, F, P, nnz, ds->pmeta,
-              ds->slot_field, st, fb, delta, slot_start, packed_offsets, reinterpret_cast<uint4*>(bitmap), n_bitmap4);
+              ds->slot_field, st, fb, delta, slot_start, packed_offsets, reinterpret_cast<uint4*>(bitmap), n_clear4);
 
-    const int use_lds = (F + 1) * 4 <= 48 * 1024;
-    const int64_t key_items = std::max<int64_t>(nnz, (int64_t)F * B);
-    PK_LAUNCH("pk_keys", pk_keys_kernel, dim3(blocks_for(key_items, NT * 4, 256 * 16)), dim3(NT),
+    const int use_lds = (F + 1) * 4 <= 32 * 1024;
+    const int64_t key_blocks = std::max<int64_t>((nnz + kKeyTile - 1) / kKeyTile, ((int64_t)F * B + NT * 4 - 1) / (NT * 4));
+    PK_LAUNCH("pk_keys", pk_keys_kernel, dim3(blocks_for(key_blocks, 1, 256 * 32)), dim3(NT),
               use_lds ? (size_t)(F + 1) * 4 : 0, ids, offsets, B, F, nnz, ds->fmeta, ds->pmeta, st, fb, delta,
               slot_start, keys, bitmap, packed_offsets, use_lds);
 
@@ -936,19 +1178,18 @@ pk_status pk_forward(const pk_plan* plan, void* const* W, const int64_t* ids, co
         if (rc != PK_OK) return rc;
     }
 
-    PK_LAUNCH("pk_tile_count", pk_tile_count_kernel, dim3((unsigned)n_tiles), dim3(NT), 0,
-              reinterpret_cast<const uint4*>(bitmap), tile_sum);
-    PK_LAUNCH("pk_tile_scan", pk_tile_scan_kernel, dim3(1), dim3(1024), 0, tile_sum, tile_off, ds->pmeta, st, P);
-    PK_LAUNCH("pk_tile_emit", pk_tile_emit_kernel, dim3((unsigned)n_tiles), dim3(NT), 0,
-              reinterpret_cast<const uint4*>(bitmap), tile_off, ds->pmeta, st, P, rank, unique, cnt);
-    const unsigned xq = blocks_for(nnz, NT * 4, 256 * 16);
+    PK_LAUNCH("pk_tiles", pk_tiles_kernel, dim3((unsigned)n_tiles), dim3(NT), 0,
+              reinterpret_cast<const uint4*>(bitmap), tile_desc, ds->pmeta, st, P, rank, unique, cnt);
+    const unsigned xq = blocks_for(nnz, kKeyTile, 256 * 16);
     PK_LAUNCH("pk_inverse", pk_inverse_kernel, dim3(xq, P), dim3(NT), 0, ds->pmeta, st, keys,
               reinterpret_cast<const uint4*>(bitmap), rank, inverse, occ_slot, cnt);
-    PK_LAUNCH("pk_seg_sum", pk_seg_sum_kernel, dim3(kSegScanBlocks, P), dim3(NT), 0, st, cnt, seg_sum);
-    PK_LAUNCH("pk_seg_scan_sums", pk_seg_scan_sums_kernel, dim3(P), dim3(kSegScanBlocks), 0, seg_sum);
-    PK_LAUNCH("pk_seg_offsets", pk_seg_offsets_kernel, dim3(kSegScanBlocks, P), dim3(NT), 0, st, cnt, seg_sum, hot);
-    PK_LAUNCH("pk_scatter", pk_scatter_kernel, dim3(xq, P), dim3(NT), 0, offsets, B, plan->out_dim, ds->fmeta,
-              ds->pmeta, st, ds->slot_field, fb, slot_start, inverse, occ_slot, cnt, seg_ent, seg_scale);
+    PK_LAUNCH("pk_segs", pk_segs_kernel, dim3(blocks_for(nnz, kSegTile, 512), P), dim3(NT), 0, ds->pmeta, st, cnt,
+              seg_desc, hot, ghot, L.dmax);
+    int64_t max_bags = 0;
+    for (int p = 0; p < P; ++p) max_bags = std::max<int64_t>(max_bags, (int64_t)plan->packs[p].fields.size() * B);
+    PK_LAUNCH("pk_scatter", pk_scatter_kernel, dim3(blocks_for(max_bags, NT, 256 * 16), P), dim3(NT), 0, B,
+              plan->out_dim, ds->fmeta, ds->pmeta, st, ds->slot_field, packed_offsets, inverse, occ_slot, cnt, seg_ent,
+              seg_scale);
     return PK_OK;
 }
 
@@ -972,10 +1213,10 @@ pk_status pk_backward_update(const pk_plan* plan, void* const* W, float* const* 
     PackState* st = ws.at<PackState>(L.state);
     for (int p = 0; p < P; ++p) {
         const Pack& k = plan->packs[p];
-        const int64_t u_bound = std::max<int64_t>(1, std::min<int64_t>(nnz, k.rows));
         AdaArgs a{W[p], A[p], st + p, p, ws.at<uint32_t>(L.unique), ws.at<int32_t>(L.cnt), ws.at<int32_t>(L.hot),
+                  ws.at<double>(L.ghot), L.dmax,
                   ws.at<uint32_t>(L.seg_ent), k.has_mean ? ws.at<float>(L.seg_scale) : nullptr, grad_out,
-                  grad_row_stride, plan->out_dim, k.dim, lr, eps, u_bound, nnz / kHotThreshold + 1};
+                  grad_row_stride, plan->out_dim, k.dim, lr, eps, nnz};
         rc = k.dtype == PK_F32 ? dispatch_adagrad<float, 4>(ds, stream, k.dim, a)
                                : dispatch_adagrad<uint16_t, 8>(ds, stream, k.dim, a);
         if (rc != PK_OK) return rc;

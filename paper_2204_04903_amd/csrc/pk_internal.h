@@ -11,10 +11,12 @@
 
 namespace pk {
 
-constexpr int kHotThreshold = 64;     // keys with more occurrences go to the block-per-key pass
-constexpr int kTileWords    = 2048;   // bitmap words scanned by one block (256 threads x 8 words)
-constexpr int kRankWords    = 8;      // one rank sample per 8 words (256 keys)
-constexpr int kSegScanBlocks = 256;   // blocks per pack in the scan over occurrence counts
+constexpr int kColdMax   = 8;      // keys with at most this many occurrences: one lane group per key
+constexpr int kWarmMax   = 256;    // up to this many: one wavefront per key; above: split, partial sums
+constexpr int kTileWords = 2048;   // bitmap words scanned by one block (256 threads x 8 words)
+constexpr int kRankWords = 8;      // one rank sample per 8 words (256 keys)
+constexpr int kSegTile   = 2048;   // occurrence counts scanned per ticket (256 threads x 8)
+constexpr int kPosTile   = 1024;   // occurrences handled per block iteration in the backward pass
 constexpr size_t kAlign = 256;
 
 // Per field, device side (indexed by field index).
@@ -46,7 +48,9 @@ struct PackState {
     int32_t n_unique;
     int32_t n_hot;
     int32_t error;      // only pack 0's word is used
-    int32_t pad[3];
+    int32_t seg_ticket; // next tile of the count scan
+    int32_t tile_ticket;// next bitmap tile (pack 0's word only)
+    int32_t pad;
 };
 
 struct Pack {
@@ -62,8 +66,10 @@ struct Pack {
 // Byte offsets of the workspace's arrays for one (plan, B, nnz).
 struct Layout {
     size_t state, fb, delta, slot_start, packed_offsets, keys, inverse, occ_slot, seg_ent, seg_scale,
-           unique, cnt, hot, tile_sum, tile_off, seg_sum, bitmap, rank, total;
+           unique, cnt, hot, ghot, bitmap, tile_desc, seg_desc, rank, total;
+    size_t clear_bytes;          // bitmap + scan descriptors, contiguous from `bitmap`
     int64_t n_tiles_total;
+    int32_t dmax;
 };
 
 }  // namespace pk
@@ -81,6 +87,7 @@ struct pk_plan {
     int64_t out_dim = 0;
     bool any_mean = false;
     int32_t n_tiles_total = 0;
+    int32_t dmax = 0;
     void* device_state = nullptr;         // owned by pk_device.hip (metadata upload, events)
 };
 

@@ -44,12 +44,15 @@ Layout make_layout(const pk_plan* plan, int32_t B, int64_t nnz)
     L.seg_scale      = take(plan->any_mean ? n * 4 : 4);
     L.unique         = take(n * 4);
     L.cnt            = take((n + P + 1) * 4);
-    L.hot            = take((n / kHotThreshold + P + 1) * 4);
+    const size_t hot_cap = n / (kWarmMax + 1) + P + 1;
+    L.hot            = take(hot_cap * 4);
+    L.dmax           = plan->dmax;
+    L.ghot           = take(hot_cap * (size_t)plan->dmax * 8);
     L.n_tiles_total  = plan->n_tiles_total;
-    L.tile_sum       = take((size_t)plan->n_tiles_total * 4);
-    L.tile_off       = take((size_t)plan->n_tiles_total * 4);
-    L.seg_sum        = take(P * kSegScanBlocks * 4);
     L.bitmap         = take((size_t)plan->n_tiles_total * kTileWords * 4);
+    L.tile_desc      = take((size_t)plan->n_tiles_total * 8);
+    L.seg_desc       = take((n / kSegTile + P + 1) * 8);
+    L.clear_bytes    = off - L.bitmap;
     L.rank           = take((size_t)plan->n_tiles_total * (kTileWords / kRankWords) * 4);
     L.total = off;
     return L;
@@ -149,6 +152,7 @@ pk_status pk_plan_create(const pk_table_desc* tables, int32_t n_tables, const pk
         tile0 += pk_.n_tiles;
     }
     pl->n_tiles_total = (int32_t)tile0;
+    for (auto& pk_ : pl->packs) pl->dmax = std::max(pl->dmax, pk_.dim);
     *out = pl;
     return PK_OK;
 }
