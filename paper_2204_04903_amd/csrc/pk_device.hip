@@ -138,6 +138,24 @@ __device__ __forceinline__ void lookback(uint64_t* desc, int first, int me, uint
     *out_b = acc_b;
 }
 
+// Workgroups are handed to the 8 XCDs round-robin and each XCD has its own L2.
+// Giving XCD x the x-th contiguous eighth of the tiles keeps the irregular
+// accesses of neighbouring tiles (same table, same gradient columns) in one L2.
+// Only locality depends on this; any placement gives the same results.
+struct XcdTiles {
+    int tile, hi, step;
+    __device__ __forceinline__ XcdTiles(int n_tiles)
+    {
+        const int x = blockIdx.x & 7, i = blockIdx.x >> 3;
+        const int chunk = (n_tiles + 7) >> 3;
+        step = (gridDim.x + 7) >> 3;
+        tile = x * chunk + i;
+        hi = min((x + 1) * chunk, n_tiles);
+    }
+    __device__ __forceinline__ bool valid() const { return tile < hi; }
+    __device__ __forceinline__ void next() { tile += step; }
+};
+
 // ---------------------------------------------------------------------------
 // setup: block 0 derives the per-field and per-pack positions; the other
 // blocks clear the bitmap and the scan descriptors.
@@ -189,7 +207,7 @@ pk_setup_kernel(const int32_t* __restrict__ offsets, int B, int F, int P, int64_
             slot_start[fs + p + k] = carry;
             PackState s;
             s.nnz = carry; s.start = start; s.n_unique = 0; s.n_hot = 0; s.error = (p == 0) ? is_bad : 0;
-            s.seg_ticket = 0; s.tile_ticket = 0; s.pad = 0;
+            s.pad[0] = s.pad[1] = s.pad[2] = 0;
             st[p] = s;
             packed_offsets[(int64_t)fs * B + p + (int64_t)k * B] = carry;
         }
@@ -225,8 +243,9 @@ pk_keys_kernel(const int64_t* __restrict__ ids, const int32_t* __restrict__ offs
     if (use_lds) {
         for (int f = threadIdx.x; f <= F; f += NT) s_fb[f] = fb[f];
     }
-    const int64_t n_tiles = (nnz + kKeyTile - 1) / kKeyTile;
-    for (int64_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+    const int n_tiles = (int)((nnz + kKeyTile - 1) / kKeyTile);
+    for (XcdTiles it(n_tiles); it.valid(); it.next()) {
+        const int64_t tile = it.tile;
         __syncthreads();                               // table free again; s_fb loaded
         for (int s = threadIdx.x; s < kHashSlots; s += NT) s_tag[s] = ~0ull;
         __syncthreads();
@@ -249,8 +268,12 @@ pk_keys_kernel(const int64_t* __restrict__ ids, const int32_t* __restrict__ offs
                 if (old == tag) break;
                 h = (h + 1) & (kHashSlots - 1);
             }
-            if (first)
-                atomicOr(&bitmap[(size_t)pm[m.pack].first_tile * kTileWords + (key >> 5)], 1u << (key & 31));
+            if (first) {
+                // atomics are the scarce resource: skip the ones whose bit is already up
+                uint32_t* word = &bitmap[(size_t)pm[m.pack].first_tile * kTileWords + (key >> 5)];
+                const uint32_t bit = 1u << (key & 31);
+                if (!(__hip_atomic_load(word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) & bit)) atomicOr(word, bit);
+            }
         }
     }
     const int64_t stride = (int64_t)gridDim.x * NT;
@@ -272,57 +295,59 @@ pk_keys_kernel(const int64_t* __restrict__ ids, const int32_t* __restrict__ offs
 // prefix over all blocks of the pack, rank samples, distinct keys written out.
 // ---------------------------------------------------------------------------
 __global__ void __launch_bounds__(NT)
-pk_tiles_kernel(const uint4* __restrict__ bitmap4, uint64_t* tile_desc,
+pk_tiles_kernel(const uint4* __restrict__ bitmap4, uint64_t* tile_desc, int n_tiles_total,
                 const PackMeta* __restrict__ pm, PackState* st, int P,
                 int32_t* __restrict__ rank, uint32_t* __restrict__ unique, int32_t* __restrict__ cnt)
 {
-    __shared__ int s_tile;
     __shared__ uint32_t s_pre;
-    if (threadIdx.x == 0) s_tile = atomicAdd(&st[0].tile_ticket, 1);
-    __syncthreads();
-    const int tile = s_tile;
+    // Block b takes tiles b, b+G, b+2G, ...: a tile only waits for lower tiles, which
+    // belong to earlier rounds or to lower blocks of this round; the launch keeps G
+    // small enough for all blocks to be resident, so the waits end.
     int p = 0;
-    while (p + 1 < P && tile >= pm[p + 1].first_tile) ++p;
-    const int first = pm[p].first_tile;
-    const size_t t = (size_t)tile * NT + threadIdx.x;
-    const uint4 a = bitmap4[2 * t], b = bitmap4[2 * t + 1];
-    const uint32_t w[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
-    int c = 0;
+    for (int tile = blockIdx.x; tile < n_tiles_total; tile += gridDim.x) {
+        while (p + 1 < P && tile >= pm[p + 1].first_tile) ++p;
+        const int first = pm[p].first_tile;
+        const size_t t = (size_t)tile * NT + threadIdx.x;
+        const uint4 a = bitmap4[2 * t], b = bitmap4[2 * t + 1];
+        const uint32_t w[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+        int c = 0;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) c += __popc(w[i]);
-    int tot;
-    const int ex = block_excl_scan<NT>(c, &tot);
-    if (threadIdx.x < 64) {
-        if (tile == first) {
-            if (threadIdx.x == 0) { publish_desc(tile_desc + tile, make_desc(kDescPfx, (uint32_t)tot, 0)); s_pre = 0; }
-        } else {
-            if (threadIdx.x == 0) publish_desc(tile_desc + tile, make_desc(kDescAgg, (uint32_t)tot, 0));
-            uint32_t pa, pb;
-            lookback(tile_desc, first, tile, &pa, &pb, &st[0].error);
-            if (threadIdx.x == 0) {
-                publish_desc(tile_desc + tile, make_desc(kDescPfx, pa + (uint32_t)tot, 0));
-                s_pre = pa;
+        for (int i = 0; i < 8; ++i) c += __popc(w[i]);
+        int tot;
+        const int ex = block_excl_scan<NT>(c, &tot);      // its barriers also fence s_pre between rounds
+        if (threadIdx.x < 64) {
+            if (tile == first) {
+                if (threadIdx.x == 0) { publish_desc(tile_desc + tile, make_desc(kDescPfx, (uint32_t)tot, 0)); s_pre = 0; }
+            } else {
+                if (threadIdx.x == 0) publish_desc(tile_desc + tile, make_desc(kDescAgg, (uint32_t)tot, 0));
+                uint32_t pa, pb;
+                lookback(tile_desc, first, tile, &pa, &pb, &st[0].error);
+                if (threadIdx.x == 0) {
+                    publish_desc(tile_desc + tile, make_desc(kDescPfx, pa + (uint32_t)tot, 0));
+                    s_pre = pa;
+                }
             }
         }
-    }
-    __syncthreads();
-    int pre = (int)s_pre + ex;
-    rank[t] = pre;
-    if (tile == first + pm[p].n_tiles - 1 && threadIdx.x == NT - 1) st[p].n_unique = pre + c;
-    if (c == 0) return;
-    const int start = st[p].start;
-    uint32_t* uq = unique + start;
-    int32_t* cn = cnt + start + p;
-    const uint32_t key0 = ((uint32_t)(tile - first) * NT + threadIdx.x) * 256u;
+        __syncthreads();
+        int pre = (int)s_pre + ex;
+        rank[t] = pre;
+        if (tile == first + pm[p].n_tiles - 1 && threadIdx.x == NT - 1) st[p].n_unique = pre + c;
+        if (c != 0) {
+            const int start = st[p].start;
+            uint32_t* uq = unique + start;
+            int32_t* cn = cnt + start + p;
+            const uint32_t key0 = ((uint32_t)(tile - first) * NT + threadIdx.x) * 256u;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        uint32_t x = w[i];
-        while (x) {
-            const int bit = __ffs(x) - 1;
-            x &= x - 1;
-            uq[pre] = key0 + i * 32 + bit;
-            cn[pre] = 0;
-            ++pre;
+            for (int i = 0; i < 8; ++i) {
+                uint32_t x = w[i];
+                while (x) {
+                    const int bit = __ffs(x) - 1;
+                    x &= x - 1;
+                    uq[pre] = key0 + i * 32 + bit;
+                    cn[pre] = 0;
+                    ++pre;
+                }
+            }
         }
     }
 }
@@ -345,7 +370,8 @@ pk_inverse_kernel(const PackMeta* __restrict__ pm, const PackState* __restrict__
     const int32_t* rk = rank + rb;
     int32_t* cn = cnt + start + p;
     const int n_tiles = (n + kKeyTile - 1) / kKeyTile;
-    for (int tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+    for (XcdTiles it(n_tiles); it.valid(); it.next()) {
+        const int tile = it.tile;
         __syncthreads();
         for (int s = threadIdx.x; s < kHashSlots; s += NT) { s_key[s] = 0xFFFFFFFFu; s_cnt[s] = 0; }
         __syncthreads();
@@ -396,12 +422,13 @@ pk_inverse_kernel(const PackMeta* __restrict__ pm, const PackState* __restrict__
 
 // Exclusive scan of the occurrence counts of a pack's distinct keys, in place
 // (counts -> segment offsets), in one pass.  Keys with more than kWarmMax
-// occurrences are listed (ascending) and get a zeroed row of partial sums.
+// occurrences are listed (ascending) and get a zeroed row of partial sums.  For
+// the backward pass, tile_first[t] = the key whose segment holds position t*tp.
 __global__ void __launch_bounds__(NT)
 pk_segs_kernel(const PackMeta* __restrict__ pm, PackState* st, int32_t* cnt, uint64_t* seg_desc,
-               int32_t* __restrict__ hot, double* __restrict__ ghot, int dmax)
+               int32_t* __restrict__ hot, double* __restrict__ ghot, int dmax,
+               int32_t* __restrict__ tile_first, int tp)
 {
-    __shared__ int s_tile;
     __shared__ uint32_t s_pa, s_pb;
     __shared__ unsigned long long s_w[NT / 64];
     const int p = blockIdx.y;
@@ -410,6 +437,7 @@ pk_segs_kernel(const PackMeta* __restrict__ pm, PackState* st, int32_t* cnt, uin
     const size_t hbase = (size_t)(start / (kWarmMax + 1) + p);
     int32_t* hl = hot + hbase;
     double* gh = ghot + hbase * dmax;
+    int32_t* tf = tile_first + start / tp + p;
     uint64_t* desc = seg_desc + start / kSegTile + p;
     const int n_tiles = (U + kSegTile - 1) / kSegTile;
     const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
@@ -417,12 +445,9 @@ pk_segs_kernel(const PackMeta* __restrict__ pm, PackState* st, int32_t* cnt, uin
         cn[U] = st[p].nnz;
         if (n_tiles == 0) st[p].n_hot = 0;
     }
-    while (true) {
-        __syncthreads();
-        if (threadIdx.x == 0) s_tile = atomicAdd(&st[p].seg_ticket, 1);
-        __syncthreads();
-        const int tile = s_tile;
-        if (tile >= n_tiles) break;
+    // Block b takes tiles b, b+G, ...; all G blocks are resident (G is small), so the
+    // wait for lower tiles ends.
+    for (int tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
         const int base = tile * kSegTile;
         unsigned long long mine = 0;                     // low 32: occurrences, high 32: hot keys
 #pragma unroll
@@ -431,10 +456,10 @@ pk_segs_kernel(const PackMeta* __restrict__ pm, PackState* st, int32_t* cnt, uin
             const int v = u < U ? cn[u] : 0;
             mine += (unsigned long long)(uint32_t)v + ((unsigned long long)(v > kWarmMax) << 32);
         }
-        // tile totals
         unsigned long long x = mine;
 #pragma unroll
         for (int o = 32; o > 0; o >>= 1) x += __shfl_xor(x, o, 64);
+        __syncthreads();                                 // s_w, s_pa, s_pb of the previous round are consumed
         if (lane == 0) s_w[wv] = x;
         __syncthreads();
         unsigned long long tot = 0;
@@ -465,7 +490,9 @@ pk_segs_kernel(const PackMeta* __restrict__ pm, PackState* st, int32_t* cnt, uin
             const int ea = block_excl_scan<NT>(v, &ta);
             const int eb = block_excl_scan<NT>(is_hot, &tb);
             if (u < U) {
-                cn[u] = (int)carry_a + ea;
+                const int s0 = (int)carry_a + ea;
+                cn[u] = s0;
+                for (int t = (s0 + tp - 1) / tp; t * tp < s0 + v; ++t) tf[t] = u;
                 if (is_hot) {
                     const size_t h = carry_b + eb;
                     hl[h] = u;
@@ -478,25 +505,26 @@ pk_segs_kernel(const PackMeta* __restrict__ pm, PackState* st, int32_t* cnt, uin
     }
 }
 
-// Occurrences grouped by distinct key: for each, where its gradient lives (and
-// the 1/L of mean pooling).  A block takes 256 consecutive bags, whose
-// occurrences are contiguous, and finds each occurrence's bag in LDS.
+// Occurrences grouped by distinct key: for each, the bag it came from (the bag
+// gives the gradient's address and the 1/L of mean pooling).  A block takes 256
+// consecutive bags, whose occurrences are contiguous, and finds each
+// occurrence's bag in LDS.
 __global__ void __launch_bounds__(NT)
-pk_scatter_kernel(int B, int64_t out_dim, const FieldMeta* __restrict__ fmeta, const PackMeta* __restrict__ pm,
-                  const PackState* __restrict__ st, const int32_t* __restrict__ slot_field,
+pk_scatter_kernel(int B, const PackMeta* __restrict__ pm, const PackState* __restrict__ st,
                   const int32_t* __restrict__ packed_offsets,
                   const int32_t* __restrict__ inverse, const int32_t* __restrict__ occ_slot,
-                  const int32_t* __restrict__ cnt, uint32_t* __restrict__ seg_ent, float* __restrict__ seg_scale)
+                  const int32_t* __restrict__ cnt, uint32_t* __restrict__ seg_bag)
 {
     __shared__ int32_t s_po[NT + 1];
     const int p = blockIdx.y;
     const int n = st[p].nnz, start = st[p].start;
     const PackMeta k = pm[p];
     const int32_t* po = packed_offsets + (int64_t)k.first_slot * B + p;
-    const int32_t* sf = slot_field + k.first_slot;
     const int32_t* cn = cnt + start + p;
     const int64_t n_bags = (int64_t)k.n_fields * B;
-    for (int64_t bag0 = (int64_t)blockIdx.x * NT; bag0 < n_bags; bag0 += (int64_t)gridDim.x * NT) {
+    const int n_tiles = (int)((n_bags + NT - 1) / NT);
+    for (XcdTiles it(n_tiles); it.valid(); it.next()) {
+        const int64_t bag0 = (int64_t)it.tile * NT;
         const int nb = (int)min((int64_t)NT, n_bags - bag0);
         __syncthreads();
         for (int t = threadIdx.x; t <= nb; t += NT) s_po[t] = min(max(po[bag0 + t], 0), n);
@@ -505,18 +533,8 @@ pk_scatter_kernel(int B, int64_t out_dim, const FieldMeta* __restrict__ fmeta, c
         for (int q = q_lo + threadIdx.x; q < q_hi; q += NT) {
             const int t = upper_bound_i32(s_po, nb + 1, q) - 1;
             if ((unsigned)t >= (unsigned)nb) continue;
-            const int64_t g = bag0 + t;
-            const int j = (int)(g / B);
-            const int b = (int)(g - (int64_t)j * B);
-            const FieldMeta m = fmeta[sf[j]];
             const int pos = cn[inverse[start + q]] + occ_slot[start + q];
-            if ((unsigned)pos < (unsigned)n) {
-                seg_ent[start + pos] = (uint32_t)((int64_t)b * out_dim + m.col);
-                if (k.has_mean) {
-                    const int L = s_po[t + 1] - s_po[t];
-                    seg_scale[start + pos] = (m.pool == PK_MEAN && L > 0) ? 1.0f / (float)L : 1.0f;
-                }
-            }
+            if ((unsigned)pos < (unsigned)n) seg_bag[start + pos] = (uint32_t)(bag0 + t);
         }
     }
 }
@@ -689,18 +707,33 @@ pk_pool_kernel(const WT* __restrict__ W, const uint32_t* __restrict__ keys_all, 
 //                               it (double atomics) to the key's partial-sum row;
 //                               pk_adagrad_hot_kernel then applies the update.
 // ---------------------------------------------------------------------------
-__device__ __forceinline__ size_t grad_addr(uint32_t ent, int64_t out_dim, int64_t gstride)
-{
-    if (gstride == out_dim) return ent;
-    const uint32_t b = ent / (uint32_t)out_dim;
-    return (size_t)b * gstride + (ent - b * (uint32_t)out_dim);
-}
-
+// Where the gradient of an occurrence lives.  The occurrence list holds the
+// bag (slot-major index inside the pack); the bag gives the sample, the
+// field's output column and, for mean pooling, the bag length.
 struct GradSrc {
-    const uint32_t* ent;    // per position: element offset of the gradient chunk in grad_out
-    const float* scl;       // per position: 1/L for mean pooling (nullptr: all ones)
+    const uint32_t* bag;         // per position of the key-sorted occurrence list
+    const int32_t* po;           // the pack's packed bag offsets
+    const int32_t* slot_field;   // the pack's fields in slot order
+    const FieldMeta* fmeta;
     const float* grad;
-    int64_t out_dim, gstride;
+    int64_t gstride;
+    uint32_t B;
+    int has_mean;
+
+    __device__ __forceinline__ void locate(int s, size_t* addr, float* scale) const
+    {
+        const uint32_t g = bag[s];
+        const uint32_t j = g / B;
+        const uint32_t b = g - j * B;
+        const FieldMeta m = fmeta[slot_field[j]];
+        *addr = (size_t)b * gstride + m.col;
+        float sc = 1.0f;
+        if (has_mean && m.pool == PK_MEAN) {
+            const int L = po[g + 1] - po[g];
+            if (L > 0) sc = 1.0f / (float)L;
+        }
+        *scale = sc;
+    }
 };
 
 // acc += sum over positions s, s+step, ... < s_end of scale * grad chunk
@@ -712,10 +745,7 @@ __device__ __forceinline__ void accum_range(double (&acc)[NCH][VEC], const GradS
         size_t a[4];
         float c[4];
 #pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            a[k] = grad_addr(g.ent[s + k * step], g.out_dim, g.gstride);
-            c[k] = g.scl ? g.scl[s + k * step] : 1.0f;
-        }
+        for (int k = 0; k < 4; ++k) g.locate(s + k * step, &a[k], &c[k]);
 #pragma unroll
         for (int ch = 0; ch < NCH; ++ch) {
             const int d0 = (ch * LPR + li) * VEC;
@@ -731,8 +761,9 @@ __device__ __forceinline__ void accum_range(double (&acc)[NCH][VEC], const GradS
         }
     }
     for (; s < s_end; s += step) {
-        const size_t a0 = grad_addr(g.ent[s], g.out_dim, g.gstride);
-        const float c0 = g.scl ? g.scl[s] : 1.0f;
+        size_t a0;
+        float c0;
+        g.locate(s, &a0, &c0);
 #pragma unroll
         for (int ch = 0; ch < NCH; ++ch) {
             const int d0 = (ch * LPR + li) * VEC;
@@ -786,14 +817,16 @@ __global__ void __launch_bounds__(NT)
 pk_adagrad_kernel(WT* W, float* A, const PackState* __restrict__ st, int p,
                   const uint32_t* __restrict__ unique_all, const int32_t* __restrict__ cnt,
                   const int32_t* __restrict__ hot_all, double* ghot_all, int dmax,
-                  const uint32_t* __restrict__ seg_ent_all, const float* __restrict__ seg_scale_all,
-                  const float* __restrict__ grad, int64_t gstride, int64_t out_dim, int D, float lr, float eps)
+                  const int32_t* __restrict__ tile_first, int tp,
+                  const uint32_t* __restrict__ seg_bag_all, const int32_t* __restrict__ po,
+                  const int32_t* __restrict__ slot_field, const FieldMeta* __restrict__ fmeta, int B, int has_mean,
+                  const float* __restrict__ grad, int64_t gstride, int D, float lr, float eps)
 {
     constexpr int GPB = NT / LPR;          // lane groups per block
     constexpr int GPW = 64 / LPR;          // lane groups per wavefront
-    __shared__ int s_lo, s_hi, s_nwarm, s_nhot;
-    __shared__ int s_warm[kPosTile / (kColdMax + 1) + 2];
-    __shared__ int s_hot[kPosTile / (kWarmMax + 1) + 4];
+    __shared__ int s_nwarm, s_nhot;
+    __shared__ int s_warm[kPosTileMax / (kColdMax + 1) + 2];
+    __shared__ int s_hot[kPosTileMax / (kWarmMax + 1) + 4];
     const int li = threadIdx.x % LPR, gi = threadIdx.x / LPR;
     const int wv = threadIdx.x >> 6, gw = (threadIdx.x & 63) / LPR;
     const int n = st->nnz, U = st->n_unique, start = st->start, n_hot = st->n_hot;
@@ -802,16 +835,23 @@ pk_adagrad_kernel(WT* W, float* A, const PackState* __restrict__ st, int p,
     const size_t hbase = (size_t)(start / (kWarmMax + 1) + p);
     const int32_t* hl = hot_all + hbase;
     double* gh = ghot_all + hbase * dmax;
-    GradSrc g{seg_ent_all + start, seg_scale_all ? seg_scale_all + start : nullptr, grad, out_dim, gstride};
-    const int n_tiles = (n + kPosTile - 1) / kPosTile;
-    for (int tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
-        const int t0 = tile * kPosTile, t1 = min(t0 + kPosTile, n);
+    const int32_t* tf = tile_first + start / tp + p;
+    const GradSrc g{seg_bag_all + start, po, slot_field, fmeta, grad, gstride, (uint32_t)B, has_mean};
+    const int n_tiles = (n + tp - 1) / tp;
+    for (XcdTiles it(n_tiles); it.valid(); it.next()) {
+        const int tile = it.tile;
+        const int t0 = tile * tp, t1 = min(t0 + tp, n);
+        // keys whose segments overlap [t0, t1)
+        const int u_lo = tf[tile];
+        int u_hi = U - 1;
+        if (tile + 1 < n_tiles) {
+            u_hi = tf[tile + 1];
+            if (seg[u_hi] >= t1) --u_hi;
+        }
         __syncthreads();                                   // lists of the previous tile are consumed
-        if (threadIdx.x == 0) { s_lo = upper_bound_i32(seg, U + 1, t0) - 1; s_nwarm = 0; s_nhot = 0; }
-        if (threadIdx.x == 64) s_hi = upper_bound_i32(seg, U + 1, t1 - 1) - 1;
+        if (threadIdx.x == 0) { s_nwarm = 0; s_nhot = 0; }
         __syncthreads();
-        const int u_lo = s_lo, u_hi = s_hi;
-        // keys overlapping the tile: cold ones that start here are finished on the spot
+        // cold keys that start here are finished on the spot
         for (int u = u_lo + gi; u <= u_hi; u += GPB) {
             const int s0 = seg[u], s1 = seg[u + 1];
             const int len = s1 - s0;
@@ -1049,7 +1089,8 @@ struct PoolArgs {
 struct AdaArgs {
     void* W; float* A; const PackState* st; int p; const uint32_t* unique; const int32_t* cnt; const int32_t* hot;
     double* ghot; int dmax;
-    const uint32_t* seg_ent; const float* seg_scale; const float* grad; int64_t gstride; int64_t out_dim; int D;
+    const int32_t* tile_first; int tp; const uint32_t* seg_bag; const int32_t* po; const int32_t* slot_field;
+    const FieldMeta* fmeta; int B; int has_mean; const float* grad; int64_t gstride; int D;
     float lr; float eps; int64_t nnz_bound;
 };
 
@@ -1068,10 +1109,10 @@ template <typename WT, int VEC, int LPR, int NCH>
 pk_status launch_adagrad(DeviceState* ds, hipStream_t stream, const AdaArgs& a)
 {
     constexpr int GPB = NT / LPR;
-    const unsigned grid = blocks_for(a.nnz_bound, kPosTile, 256 * 8);
+    const unsigned grid = (blocks_for(a.nnz_bound, a.tp, 256 * 16) + 7u) & ~7u;
     PK_LAUNCH("pk_adagrad", (pk_adagrad_kernel<WT, VEC, LPR, NCH>), dim3(grid), dim3(NT), 0,
-              static_cast<WT*>(a.W), a.A, a.st, a.p, a.unique, a.cnt, a.hot, a.ghot, a.dmax, a.seg_ent, a.seg_scale,
-              a.grad, a.gstride, a.out_dim, a.D, a.lr, a.eps);
+              static_cast<WT*>(a.W), a.A, a.st, a.p, a.unique, a.cnt, a.hot, a.ghot, a.dmax, a.tile_first, a.tp,
+              a.seg_bag, a.po, a.slot_field, a.fmeta, a.B, a.has_mean, a.grad, a.gstride, a.D, a.lr, a.eps);
     const unsigned hgrid = blocks_for(a.nnz_bound / (kWarmMax + 1) + 1, GPB, 1024);
     PK_LAUNCH("pk_adagrad_hot", (pk_adagrad_hot_kernel<WT, VEC, LPR, NCH>), dim3(hgrid), dim3(NT), 0,
               static_cast<WT*>(a.W), a.A, a.st, a.p, a.unique, a.hot, a.ghot, a.dmax, a.D, a.lr, a.eps);
@@ -1147,7 +1188,7 @@ pk_status pk_forward(const pk_plan* plan, void* const* W, const int64_t* ids, co
     int32_t* inverse = ws.at<int32_t>(L.inverse);
     int32_t* occ_slot = ws.at<int32_t>(L.occ_slot);
     uint32_t* seg_ent = ws.at<uint32_t>(L.seg_ent);
-    float* seg_scale = ws.at<float>(L.seg_scale);
+    int32_t* tile_first = ws.at<int32_t>(L.tile_first);
     uint32_t* unique = ws.at<uint32_t>(L.unique);
     int32_t* cnt = ws.at<int32_t>(L.cnt);
     int32_t* hot = ws.at<int32_t>(L.hot);
@@ -1165,7 +1206,7 @@ pk_status pk_forward(const pk_plan* plan, void* const* W, const int64_t* ids, co
 
     const int use_lds = (F + 1) * 4 <= 32 * 1024;
     const int64_t key_blocks = std::max<int64_t>((nnz + kKeyTile - 1) / kKeyTile, ((int64_t)F * B + NT * 4 - 1) / (NT * 4));
-    PK_LAUNCH("pk_keys", pk_keys_kernel, dim3(blocks_for(key_blocks, 1, 256 * 32)), dim3(NT),
+    PK_LAUNCH("pk_keys", pk_keys_kernel, dim3((blocks_for(key_blocks, 1, 256 * 32) + 7u) & ~7u), dim3(NT),
               use_lds ? (size_t)(F + 1) * 4 : 0, ids, offsets, B, F, nnz, ds->fmeta, ds->pmeta, st, fb, delta,
               slot_start, keys, bitmap, packed_offsets, use_lds);
 
@@ -1178,18 +1219,17 @@ pk_status pk_forward(const pk_plan* plan, void* const* W, const int64_t* ids, co
         if (rc != PK_OK) return rc;
     }
 
-    PK_LAUNCH("pk_tiles", pk_tiles_kernel, dim3((unsigned)n_tiles), dim3(NT), 0,
-              reinterpret_cast<const uint4*>(bitmap), tile_desc, ds->pmeta, st, P, rank, unique, cnt);
-    const unsigned xq = blocks_for(nnz, kKeyTile, 256 * 16);
+    PK_LAUNCH("pk_tiles", pk_tiles_kernel, dim3(blocks_for(n_tiles, 1, 1024)), dim3(NT), 0,
+              reinterpret_cast<const uint4*>(bitmap), tile_desc, (int)n_tiles, ds->pmeta, st, P, rank, unique, cnt);
+    const unsigned xq = (blocks_for(nnz, kKeyTile, 256 * 16) + 7u) & ~7u;
     PK_LAUNCH("pk_inverse", pk_inverse_kernel, dim3(xq, P), dim3(NT), 0, ds->pmeta, st, keys,
               reinterpret_cast<const uint4*>(bitmap), rank, inverse, occ_slot, cnt);
-    PK_LAUNCH("pk_segs", pk_segs_kernel, dim3(blocks_for(nnz, kSegTile, 512), P), dim3(NT), 0, ds->pmeta, st, cnt,
-              seg_desc, hot, ghot, L.dmax);
+    PK_LAUNCH("pk_segs", pk_segs_kernel, dim3(blocks_for(nnz, kSegTile, std::max(1, 1024 / P)), P), dim3(NT), 0,
+              ds->pmeta, st, cnt, seg_desc, hot, ghot, L.dmax, tile_first, L.pos_tile);
     int64_t max_bags = 0;
     for (int p = 0; p < P; ++p) max_bags = std::max<int64_t>(max_bags, (int64_t)plan->packs[p].fields.size() * B);
-    PK_LAUNCH("pk_scatter", pk_scatter_kernel, dim3(blocks_for(max_bags, NT, 256 * 16), P), dim3(NT), 0, B,
-              plan->out_dim, ds->fmeta, ds->pmeta, st, ds->slot_field, packed_offsets, inverse, occ_slot, cnt, seg_ent,
-              seg_scale);
+    PK_LAUNCH("pk_scatter", pk_scatter_kernel, dim3((blocks_for(max_bags, NT, 256 * 16) + 7u) & ~7u, P), dim3(NT), 0,
+              B, ds->pmeta, st, packed_offsets, inverse, occ_slot, cnt, seg_ent);
     return PK_OK;
 }
 
@@ -1214,9 +1254,10 @@ pk_status pk_backward_update(const pk_plan* plan, void* const* W, float* const* 
     for (int p = 0; p < P; ++p) {
         const Pack& k = plan->packs[p];
         AdaArgs a{W[p], A[p], st + p, p, ws.at<uint32_t>(L.unique), ws.at<int32_t>(L.cnt), ws.at<int32_t>(L.hot),
-                  ws.at<double>(L.ghot), L.dmax,
-                  ws.at<uint32_t>(L.seg_ent), k.has_mean ? ws.at<float>(L.seg_scale) : nullptr, grad_out,
-                  grad_row_stride, plan->out_dim, k.dim, lr, eps, nnz};
+                  ws.at<double>(L.ghot), L.dmax, ws.at<int32_t>(L.tile_first), L.pos_tile,
+                  ws.at<uint32_t>(L.seg_ent), ws.at<int32_t>(L.packed_offsets) + po_off(plan, p, B),
+                  ds->slot_field + k.first_slot, ds->fmeta, B, k.has_mean ? 1 : 0, grad_out, grad_row_stride, k.dim,
+                  lr, eps, nnz};
         rc = k.dtype == PK_F32 ? dispatch_adagrad<float, 4>(ds, stream, k.dim, a)
                                : dispatch_adagrad<uint16_t, 8>(ds, stream, k.dim, a);
         if (rc != PK_OK) return rc;

@@ -16,7 +16,8 @@ constexpr int kWarmMax   = 256;    // up to this many: one wavefront per key; ab
 constexpr int kTileWords = 2048;   // bitmap words scanned by one block (256 threads x 8 words)
 constexpr int kRankWords = 8;      // one rank sample per 8 words (256 keys)
 constexpr int kSegTile   = 2048;   // occurrence counts scanned per ticket (256 threads x 8)
-constexpr int kPosTile   = 1024;   // occurrences handled per block iteration in the backward pass
+constexpr int kPosTileMax = 1024;  // occurrences handled per block iteration in the backward pass (upper end)
+constexpr int kPosTileMin = 64;
 constexpr size_t kAlign = 256;
 
 // Per field, device side (indexed by field index).
@@ -48,9 +49,7 @@ struct PackState {
     int32_t n_unique;
     int32_t n_hot;
     int32_t error;      // only pack 0's word is used
-    int32_t seg_ticket; // next tile of the count scan
-    int32_t tile_ticket;// next bitmap tile (pack 0's word only)
-    int32_t pad;
+    int32_t pad[3];
 };
 
 struct Pack {
@@ -65,11 +64,12 @@ struct Pack {
 
 // Byte offsets of the workspace's arrays for one (plan, B, nnz).
 struct Layout {
-    size_t state, fb, delta, slot_start, packed_offsets, keys, inverse, occ_slot, seg_ent, seg_scale,
+    size_t state, fb, delta, slot_start, packed_offsets, keys, inverse, occ_slot, seg_ent, tile_first,
            unique, cnt, hot, ghot, bitmap, tile_desc, seg_desc, rank, total;
     size_t clear_bytes;          // bitmap + scan descriptors, contiguous from `bitmap`
     int64_t n_tiles_total;
     int32_t dmax;
+    int32_t pos_tile;            // occurrences per backward tile for this nnz
 };
 
 }  // namespace pk
@@ -95,5 +95,6 @@ namespace pk {
 void set_error(const std::string& msg);
 pk_status fail(pk_status s, const std::string& msg);
 Layout make_layout(const pk_plan* plan, int32_t B, int64_t nnz);
+int32_t pos_tile_for(int64_t nnz);
 void destroy_device_state(pk_plan* plan);   // defined in pk_device.hip
 }  // namespace pk

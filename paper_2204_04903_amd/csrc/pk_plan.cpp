@@ -25,6 +25,16 @@ pk_status fail(pk_status s, const std::string& msg)
 
 static size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
+// Occurrences per block iteration of the backward pass: small problems get small
+// tiles so that the launch still has thousands of blocks.
+int32_t pos_tile_for(int64_t nnz)
+{
+    int64_t t = (nnz / 8192 + 63) / 64 * 64;
+    if (t < kPosTileMin) t = kPosTileMin;
+    if (t > kPosTileMax) t = kPosTileMax;
+    return (int32_t)t;
+}
+
 Layout make_layout(const pk_plan* plan, int32_t B, int64_t nnz)
 {
     const size_t F = plan->fields.size(), P = plan->packs.size();
@@ -41,7 +51,8 @@ Layout make_layout(const pk_plan* plan, int32_t B, int64_t nnz)
     L.inverse        = take(n * 4);
     L.occ_slot       = take(n * 4);
     L.seg_ent        = take(n * 4);
-    L.seg_scale      = take(plan->any_mean ? n * 4 : 4);
+    L.pos_tile       = pos_tile_for(nnz);
+    L.tile_first     = take((n / L.pos_tile + P + 2) * 4);
     L.unique         = take(n * 4);
     L.cnt            = take((n + P + 1) * 4);
     const size_t hot_cap = n / (kWarmMax + 1) + P + 1;
