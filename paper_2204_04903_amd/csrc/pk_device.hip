@@ -249,30 +249,34 @@ pk_keys_kernel(const int64_t* __restrict__ ids, const int32_t* __restrict__ offs
         __syncthreads();                               // table free again; s_fb loaded
         for (int s = threadIdx.x; s < kHashSlots; s += NT) s_tag[s] = ~0ull;
         __syncthreads();
+        int64_t idv[kKeyTile / NT];
+#pragma unroll
+        for (int k = 0; k < kKeyTile / NT; ++k) {          // all loads of the tile in flight together
+            const int64_t i = tile * kKeyTile + k * NT + threadIdx.x;
+            idv[k] = i < nnz ? ids[i] : 0;
+        }
 #pragma unroll
         for (int k = 0; k < kKeyTile / NT; ++k) {
             const int64_t i = tile * kKeyTile + k * NT + threadIdx.x;
-            if (i >= nnz) break;
-            const int f = (use_lds ? upper_bound_i32(s_fb, F + 1, (int)i) : upper_bound_i32(fb, F + 1, (int)i)) - 1;
-            const FieldMeta m = fmeta[f];
-            const uint32_t key = m.base_row + fold_id(ids[i], m.rows);
-            const int64_t q = i + delta[f];
-            if ((uint64_t)q >= (uint64_t)nnz) continue;
-            keys[q] = key;
-            const unsigned long long tag = ((unsigned long long)(uint32_t)m.pack << 32) | key;
-            uint32_t h = hash_slot(tag);
-            bool first = false;
-            while (true) {
-                const unsigned long long old = atomicCAS(&s_tag[h], ~0ull, tag);
-                if (old == ~0ull) { first = true; break; }
-                if (old == tag) break;
-                h = (h + 1) & (kHashSlots - 1);
-            }
-            if (first) {
-                // atomics are the scarce resource: skip the ones whose bit is already up
-                uint32_t* word = &bitmap[(size_t)pm[m.pack].first_tile * kTileWords + (key >> 5)];
-                const uint32_t bit = 1u << (key & 31);
-                if (!(__hip_atomic_load(word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) & bit)) atomicOr(word, bit);
+            if (i < nnz) {
+                const int f = (use_lds ? upper_bound_i32(s_fb, F + 1, (int)i) : upper_bound_i32(fb, F + 1, (int)i)) - 1;
+                const FieldMeta m = fmeta[f];
+                const uint32_t key = m.base_row + fold_id(idv[k], m.rows);
+                const int64_t q = i + delta[f];
+                if ((uint64_t)q < (uint64_t)nnz) {
+                    keys[q] = key;
+                    const unsigned long long tag = ((unsigned long long)(uint32_t)m.pack << 32) | key;
+                    uint32_t h = hash_slot(tag);
+                    bool first = false;
+                    while (true) {
+                        const unsigned long long old = atomicCAS(&s_tag[h], ~0ull, tag);
+                        if (old == ~0ull) { first = true; break; }
+                        if (old == tag) break;
+                        h = (h + 1) & (kHashSlots - 1);
+                    }
+                    if (first)
+                        atomicOr(&bitmap[(size_t)pm[m.pack].first_tile * kTileWords + (key >> 5)], 1u << (key & 31));
+                }
             }
         }
     }
@@ -699,7 +703,7 @@ pk_pool_kernel(const WT* __restrict__ W, const uint32_t* __restrict__ keys_all, 
 // Adagrad step in place.  Fused so the reduced gradient never goes to memory.
 //
 // Work is cut by OCCURRENCES, not by keys, because the ID distribution is
-// heavily skewed (Sec. II-B): a block takes kPosTile consecutive positions of
+// heavily skewed (Sec. II-B): a block takes a tile of consecutive positions of
 // the key-sorted occurrence list and handles the keys that start there.
 //   up to kColdMax occurrences: one lane group per key;
 //   up to kWarmMax:             one wavefront per key, groups stride over it;
@@ -709,7 +713,9 @@ pk_pool_kernel(const WT* __restrict__ W, const uint32_t* __restrict__ keys_all, 
 // ---------------------------------------------------------------------------
 // Where the gradient of an occurrence lives.  The occurrence list holds the
 // bag (slot-major index inside the pack); the bag gives the sample, the
-// field's output column and, for mean pooling, the bag length.
+// field's output column and, for mean pooling, the bag length.  A block decodes
+// the positions of its tile once, in parallel, into LDS; positions outside the
+// tile (tails of keys that start in it) are decoded on the fly.
 struct GradSrc {
     const uint32_t* bag;         // per position of the key-sorted occurrence list
     const int32_t* po;           // the pack's packed bag offsets
@@ -719,6 +725,9 @@ struct GradSrc {
     int64_t gstride;
     uint32_t B;
     int has_mean;
+    const size_t* s_addr;        // LDS: decoded positions [t0, t1)
+    const float* s_scl;
+    int t0, t1;
 
     __device__ __forceinline__ void locate(int s, size_t* addr, float* scale) const
     {
@@ -734,6 +743,11 @@ struct GradSrc {
         }
         *scale = sc;
     }
+    __device__ __forceinline__ void fetch(int s, size_t* addr, float* scale) const
+    {
+        if (s >= t0 && s < t1) { *addr = s_addr[s - t0]; *scale = s_scl[s - t0]; }
+        else locate(s, addr, scale);
+    }
 };
 
 // acc += sum over positions s, s+step, ... < s_end of scale * grad chunk
@@ -745,7 +759,7 @@ __device__ __forceinline__ void accum_range(double (&acc)[NCH][VEC], const GradS
         size_t a[4];
         float c[4];
 #pragma unroll
-        for (int k = 0; k < 4; ++k) g.locate(s + k * step, &a[k], &c[k]);
+        for (int k = 0; k < 4; ++k) g.fetch(s + k * step, &a[k], &c[k]);
 #pragma unroll
         for (int ch = 0; ch < NCH; ++ch) {
             const int d0 = (ch * LPR + li) * VEC;
@@ -763,7 +777,7 @@ __device__ __forceinline__ void accum_range(double (&acc)[NCH][VEC], const GradS
     for (; s < s_end; s += step) {
         size_t a0;
         float c0;
-        g.locate(s, &a0, &c0);
+        g.fetch(s, &a0, &c0);
 #pragma unroll
         for (int ch = 0; ch < NCH; ++ch) {
             const int d0 = (ch * LPR + li) * VEC;
@@ -777,25 +791,40 @@ __device__ __forceinline__ void accum_range(double (&acc)[NCH][VEC], const GradS
     }
 }
 
+// the row's current weights and accumulators (issued before the gradient
+// reduction so that both sets of loads are in flight together)
 template <typename WT, int VEC, int LPR, int NCH>
-__device__ __forceinline__ void adagrad_row(WT* W, float* A, size_t row, int D, int li,
-                                            const double (&acc)[NCH][VEC], float lr, float eps)
+__device__ __forceinline__ void row_load(const WT* W, const float* A, size_t row, int D, int li,
+                                         float (&w)[NCH][VEC], float (&a)[NCH][VEC])
 {
 #pragma unroll
     for (int c = 0; c < NCH; ++c) {
         const int d0 = (c * LPR + li) * VEC;
         if (d0 < D) {
-            float w[VEC], a[VEC];
-            Row<WT, VEC>::load(W + row * D + d0, w);
-            load_f32<VEC>(A + row * D + d0, a);
+            Row<WT, VEC>::load(W + row * D + d0, w[c]);
+            load_f32<VEC>(A + row * D + d0, a[c]);
+        }
+    }
+}
+
+// one Adagrad step of the row: a += g^2 ; w -= lr * g / (sqrt(a) + eps)
+template <typename WT, int VEC, int LPR, int NCH>
+__device__ __forceinline__ void row_step(WT* W, float* A, size_t row, int D, int li,
+                                         const double (&acc)[NCH][VEC], float (&w)[NCH][VEC],
+                                         float (&a)[NCH][VEC], float lr, float eps)
+{
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) {
+        const int d0 = (c * LPR + li) * VEC;
+        if (d0 < D) {
 #pragma unroll
             for (int v = 0; v < VEC; ++v) {
                 const float g = (float)acc[c][v];
-                a[v] = a[v] + g * g;
-                w[v] = w[v] - lr * g / (sqrtf(a[v]) + eps);
+                a[c][v] = a[c][v] + g * g;
+                w[c][v] = w[c][v] - lr * g / (sqrtf(a[c][v]) + eps);
             }
-            store_f32<VEC>(A + row * D + d0, a);
-            Row<WT, VEC>::store(W + row * D + d0, w);
+            store_f32<VEC>(A + row * D + d0, a[c]);
+            Row<WT, VEC>::store(W + row * D + d0, w[c]);
         }
     }
 }
@@ -827,6 +856,10 @@ pk_adagrad_kernel(WT* W, float* A, const PackState* __restrict__ st, int p,
     __shared__ int s_nwarm, s_nhot;
     __shared__ int s_warm[kPosTileMax / (kColdMax + 1) + 2];
     __shared__ int s_hot[kPosTileMax / (kWarmMax + 1) + 4];
+    __shared__ int s_seg[kPosTileMax + 2];          // segment offsets of the tile's keys
+    __shared__ uint32_t s_row[kPosTileMax + 1];     // their table rows
+    __shared__ size_t s_addr[kPosTileMax];          // decoded positions of the tile
+    __shared__ float s_scl[kPosTileMax];
     const int li = threadIdx.x % LPR, gi = threadIdx.x / LPR;
     const int wv = threadIdx.x >> 6, gw = (threadIdx.x & 63) / LPR;
     const int n = st->nnz, U = st->n_unique, start = st->start, n_hot = st->n_hot;
@@ -836,7 +869,7 @@ pk_adagrad_kernel(WT* W, float* A, const PackState* __restrict__ st, int p,
     const int32_t* hl = hot_all + hbase;
     double* gh = ghot_all + hbase * dmax;
     const int32_t* tf = tile_first + start / tp + p;
-    const GradSrc g{seg_bag_all + start, po, slot_field, fmeta, grad, gstride, (uint32_t)B, has_mean};
+    GradSrc g{seg_bag_all + start, po, slot_field, fmeta, grad, gstride, (uint32_t)B, has_mean, s_addr, s_scl, 0, 0};
     const int n_tiles = (n + tp - 1) / tp;
     for (XcdTiles it(n_tiles); it.valid(); it.next()) {
         const int tile = it.tile;
@@ -848,35 +881,52 @@ pk_adagrad_kernel(WT* W, float* A, const PackState* __restrict__ st, int p,
             u_hi = tf[tile + 1];
             if (seg[u_hi] >= t1) --u_hi;
         }
-        __syncthreads();                                   // lists of the previous tile are consumed
+        const int nseg = u_hi - u_lo + 1;
+        __syncthreads();                                   // the previous tile's LDS is consumed
+        for (int i = threadIdx.x; i <= nseg; i += NT) s_seg[i] = seg[u_lo + i];
+        for (int i = threadIdx.x; i < nseg; i += NT) s_row[i] = uq[u_lo + i];
+        for (int i = threadIdx.x; i < t1 - t0; i += NT) {
+            size_t a;
+            float c;
+            g.locate(t0 + i, &a, &c);
+            s_addr[i] = a;
+            s_scl[i] = c;
+        }
         if (threadIdx.x == 0) { s_nwarm = 0; s_nhot = 0; }
+        g.t0 = t0; g.t1 = t1;
         __syncthreads();
         // cold keys that start here are finished on the spot
-        for (int u = u_lo + gi; u <= u_hi; u += GPB) {
-            const int s0 = seg[u], s1 = seg[u + 1];
+        for (int k = gi; k < nseg; k += GPB) {
+            const int s0 = s_seg[k], s1 = s_seg[k + 1];
             const int len = s1 - s0;
             if (len <= kColdMax) {
                 if (s0 >= t0) {
+                    const size_t row = s_row[k];
+                    float w[NCH][VEC], a[NCH][VEC];
+                    row_load<WT, VEC, LPR, NCH>(W, A, row, D, li, w, a);
                     double acc[NCH][VEC];
 #pragma unroll
                     for (int c = 0; c < NCH; ++c)
 #pragma unroll
                         for (int v = 0; v < VEC; ++v) acc[c][v] = 0.0;
                     accum_range<VEC, LPR, NCH>(acc, g, D, li, s0, s1, 1);
-                    adagrad_row<WT, VEC, LPR, NCH>(W, A, (size_t)uq[u], D, li, acc, lr, eps);
+                    row_step<WT, VEC, LPR, NCH>(W, A, row, D, li, acc, w, a, lr, eps);
                 }
             } else if (len <= kWarmMax) {
-                if (s0 >= t0 && li == 0) s_warm[atomicAdd(&s_nwarm, 1)] = u;
+                if (s0 >= t0 && li == 0) s_warm[atomicAdd(&s_nwarm, 1)] = k;
             } else if (li == 0) {
-                s_hot[atomicAdd(&s_nhot, 1)] = u;
+                s_hot[atomicAdd(&s_nhot, 1)] = k;
             }
         }
         __syncthreads();
         // warm keys that start here: one wavefront each
         const int n_warm = s_nwarm;
-        for (int k = wv; k < n_warm; k += NT / 64) {
-            const int u = s_warm[k];
-            const int s0 = seg[u], s1 = seg[u + 1];
+        for (int i = wv; i < n_warm; i += NT / 64) {
+            const int k = s_warm[i];
+            const int s0 = s_seg[k], s1 = s_seg[k + 1];
+            const size_t row = s_row[k];
+            float w[NCH][VEC], a[NCH][VEC];
+            if (gw == 0) row_load<WT, VEC, LPR, NCH>(W, A, row, D, li, w, a);
             double acc[NCH][VEC];
 #pragma unroll
             for (int c = 0; c < NCH; ++c)
@@ -884,19 +934,20 @@ pk_adagrad_kernel(WT* W, float* A, const PackState* __restrict__ st, int p,
                 for (int v = 0; v < VEC; ++v) acc[c][v] = 0.0;
             accum_range<VEC, LPR, NCH>(acc, g, D, li, s0 + gw, s1, GPW);
             wave_group_sum<VEC, LPR, NCH>(acc);
-            if (gw == 0) adagrad_row<WT, VEC, LPR, NCH>(W, A, (size_t)uq[u], D, li, acc, lr, eps);
+            if (gw == 0) row_step<WT, VEC, LPR, NCH>(W, A, row, D, li, acc, w, a, lr, eps);
         }
         // hot keys: this tile's piece, 256 positions per wavefront, added to the key's partial sums
         const int n_hot_here = s_nhot;
-        for (int k = 0; k < n_hot_here; ++k) {
-            const int u = s_hot[k];
-            const int a = max(seg[u], t0), b = min(seg[u + 1], t1);
+        for (int i = 0; i < n_hot_here; ++i) {
+            const int k = s_hot[i];
+            const int u = u_lo + k;
+            const int a0 = max(s_seg[k], t0), b0 = min(s_seg[k + 1], t1);
             // row of partial sums: position of u in the ascending list of hot keys
             int lo = 0, hi = n_hot;
             while (lo < hi) { const int mid = (lo + hi) >> 1; if (hl[mid] < u) lo = mid + 1; else hi = mid; }
-            double* row = gh + (size_t)lo * D;
-            for (int c0 = a + wv * 256; c0 < b; c0 += (NT / 64) * 256) {
-                const int c1 = min(c0 + 256, b);
+            double* prow = gh + (size_t)lo * D;
+            for (int c0 = a0 + wv * 256; c0 < b0; c0 += (NT / 64) * 256) {
+                const int c1 = min(c0 + 256, b0);
                 double acc[NCH][VEC];
 #pragma unroll
                 for (int c = 0; c < NCH; ++c)
@@ -910,7 +961,7 @@ pk_adagrad_kernel(WT* W, float* A, const PackState* __restrict__ st, int p,
                         const int d0 = (c * LPR + li) * VEC;
                         if (d0 < D) {
 #pragma unroll
-                            for (int v = 0; v < VEC; ++v) atomicAdd(row + d0 + v, acc[c][v]);
+                            for (int v = 0; v < VEC; ++v) atomicAdd(prow + d0 + v, acc[c][v]);
                         }
                     }
                 }
@@ -940,7 +991,10 @@ pk_adagrad_hot_kernel(WT* W, float* A, const PackState* __restrict__ st, int p,
 #pragma unroll
             for (int v = 0; v < VEC; ++v) acc[c][v] = d0 < D ? gh[(size_t)h * D + d0 + v] : 0.0;
         }
-        adagrad_row<WT, VEC, LPR, NCH>(W, A, (size_t)unique_all[start + hl[h]], D, li, acc, lr, eps);
+        const size_t row = unique_all[start + hl[h]];
+        float w[NCH][VEC], a[NCH][VEC];
+        row_load<WT, VEC, LPR, NCH>(W, A, row, D, li, w, a);
+        row_step<WT, VEC, LPR, NCH>(W, A, row, D, li, acc, w, a, lr, eps);
     }
 }
 

@@ -16,7 +16,7 @@ constexpr int kWarmMax   = 256;    // up to this many: one wavefront per key; ab
 constexpr int kTileWords = 2048;   // bitmap words scanned by one block (256 threads x 8 words)
 constexpr int kRankWords = 8;      // one rank sample per 8 words (256 keys)
 constexpr int kSegTile   = 2048;   // occurrence counts scanned per ticket (256 threads x 8)
-constexpr int kPosTileMax = 1024;  // occurrences handled per block iteration in the backward pass (upper end)
+constexpr int kPosTileMax = 512;   // occurrences handled per block iteration in the backward pass (upper end)
 constexpr int kPosTileMin = 64;
 constexpr size_t kAlign = 256;
 
