@@ -55,6 +55,8 @@ def main():
     ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
     ap.add_argument("--ring", type=int, default=0, help="distinct batches cycled (default 16, 4 for cfg3-5)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 1 GiB device copy (a known size for scaling rocprofv3's byte counters)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only; run it with --gpus 1 (no collectives or sharding are "
@@ -88,6 +90,14 @@ def main():
     layer._ensure_ws(wl.batch, max_nnz)
     out = torch.empty((wl.batch, layer.out_dim), dtype=torch.float32, device="cuda")
     torch.cuda.synchronize()
+
+    if args.calibrate_copy:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")      # 1 GiB read + 1 GiB written
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     def step(i):
         ids, offsets, grad = dev[i % ring]

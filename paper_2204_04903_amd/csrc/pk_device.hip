@@ -590,37 +590,36 @@ template <> struct Row<uint16_t, 1> {
     static __device__ __forceinline__ void store(uint16_t* p, const float* v) { *p = (uint16_t)f32_to_bf16(v[0]); }
 };
 
-// VEC consecutive floats of out / grad_out; vector access when 16-byte aligned
+// VEC consecutive floats of out / grad_out / the accumulators.  The vector
+// kernels (VEC a multiple of 4) are only launched when the host has checked that
+// every such address is 16-byte aligned; otherwise the one-element-per-lane
+// kernels run.
 template <int VEC>
 __device__ __forceinline__ void load_f32(const float* p, float* v)
 {
     if constexpr (VEC % 4 == 0) {
-        if ((reinterpret_cast<uintptr_t>(p) & 15) == 0) {
 #pragma unroll
-            for (int i = 0; i < VEC; i += 4) {
-                const float4 x = *reinterpret_cast<const float4*>(p + i);
-                v[i] = x.x; v[i + 1] = x.y; v[i + 2] = x.z; v[i + 3] = x.w;
-            }
-            return;
+        for (int i = 0; i < VEC; i += 4) {
+            const float4 x = *reinterpret_cast<const float4*>(p + i);
+            v[i] = x.x; v[i + 1] = x.y; v[i + 2] = x.z; v[i + 3] = x.w;
         }
-    }
+    } else {
 #pragma unroll
-    for (int i = 0; i < VEC; ++i) v[i] = p[i];
+        for (int i = 0; i < VEC; ++i) v[i] = p[i];
+    }
 }
 
 template <int VEC>
 __device__ __forceinline__ void store_f32(float* p, const float* v)
 {
     if constexpr (VEC % 4 == 0) {
-        if ((reinterpret_cast<uintptr_t>(p) & 15) == 0) {
 #pragma unroll
-            for (int i = 0; i < VEC; i += 4)
-                *reinterpret_cast<float4*>(p + i) = make_float4(v[i], v[i + 1], v[i + 2], v[i + 3]);
-            return;
-        }
+        for (int i = 0; i < VEC; i += 4)
+            *reinterpret_cast<float4*>(p + i) = make_float4(v[i], v[i + 1], v[i + 2], v[i + 3]);
+    } else {
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) p[i] = v[i];
     }
-#pragma unroll
-    for (int i = 0; i < VEC; ++i) p[i] = v[i];
 }
 
 // ---------------------------------------------------------------------------
@@ -714,8 +713,8 @@ pk_pool_kernel(const WT* __restrict__ W, const uint32_t* __restrict__ keys_all, 
 // Where the gradient of an occurrence lives.  The occurrence list holds the
 // bag (slot-major index inside the pack); the bag gives the sample, the
 // field's output column and, for mean pooling, the bag length.  A block decodes
-// the positions of its tile once, in parallel, into LDS; positions outside the
-// tile (tails of keys that start in it) are decoded on the fly.
+// the positions of its tile (plus the tail of the last key that starts in it)
+// once, in parallel, into LDS.
 struct GradSrc {
     const uint32_t* bag;         // per position of the key-sorted occurrence list
     const int32_t* po;           // the pack's packed bag offsets
@@ -725,17 +724,18 @@ struct GradSrc {
     int64_t gstride;
     uint32_t B;
     int has_mean;
-    const size_t* s_addr;        // LDS: decoded positions [t0, t1)
+    const uint32_t* s_addr;      // LDS: decoded positions [t0, t1)
     const float* s_scl;
     int t0, t1;
 
-    __device__ __forceinline__ void locate(int s, size_t* addr, float* scale) const
+    // element offset of the gradient chunk in grad_out (the host checks B * stride < 2^32)
+    __device__ __forceinline__ void locate(int s, uint32_t* addr, float* scale) const
     {
         const uint32_t g = bag[s];
         const uint32_t j = g / B;
         const uint32_t b = g - j * B;
         const FieldMeta m = fmeta[slot_field[j]];
-        *addr = (size_t)b * gstride + m.col;
+        *addr = b * (uint32_t)gstride + (uint32_t)m.col;
         float sc = 1.0f;
         if (has_mean && m.pool == PK_MEAN) {
             const int L = po[g + 1] - po[g];
@@ -743,10 +743,12 @@ struct GradSrc {
         }
         *scale = sc;
     }
-    __device__ __forceinline__ void fetch(int s, size_t* addr, float* scale) const
+    // positions [t0, t1) are decoded in LDS; the kernel makes the window cover every
+    // position its inner loops touch
+    __device__ __forceinline__ void fetch(int s, uint32_t* addr, float* scale) const
     {
-        if (s >= t0 && s < t1) { *addr = s_addr[s - t0]; *scale = s_scl[s - t0]; }
-        else locate(s, addr, scale);
+        *addr = s_addr[s - t0];
+        *scale = s_scl[s - t0];
     }
 };
 
@@ -756,7 +758,7 @@ __device__ __forceinline__ void accum_range(double (&acc)[NCH][VEC], const GradS
                                             int s, int s_end, int step)
 {
     for (; s + 3 * step < s_end; s += 4 * step) {
-        size_t a[4];
+        uint32_t a[4];
         float c[4];
 #pragma unroll
         for (int k = 0; k < 4; ++k) g.fetch(s + k * step, &a[k], &c[k]);
@@ -775,7 +777,7 @@ __device__ __forceinline__ void accum_range(double (&acc)[NCH][VEC], const GradS
         }
     }
     for (; s < s_end; s += step) {
-        size_t a0;
+        uint32_t a0;
         float c0;
         g.fetch(s, &a0, &c0);
 #pragma unroll
@@ -858,8 +860,8 @@ pk_adagrad_kernel(WT* W, float* A, const PackState* __restrict__ st, int p,
     __shared__ int s_hot[kPosTileMax / (kWarmMax + 1) + 4];
     __shared__ int s_seg[kPosTileMax + 2];          // segment offsets of the tile's keys
     __shared__ uint32_t s_row[kPosTileMax + 1];     // their table rows
-    __shared__ size_t s_addr[kPosTileMax];          // decoded positions of the tile
-    __shared__ float s_scl[kPosTileMax];
+    __shared__ uint32_t s_addr[kPosTileMax + kWarmMax];   // decoded positions of the tile and its tail
+    __shared__ float s_scl[kPosTileMax + kWarmMax];
     const int li = threadIdx.x % LPR, gi = threadIdx.x / LPR;
     const int wv = threadIdx.x >> 6, gw = (threadIdx.x & 63) / LPR;
     const int n = st->nnz, U = st->n_unique, start = st->start, n_hot = st->n_hot;
@@ -882,18 +884,25 @@ pk_adagrad_kernel(WT* W, float* A, const PackState* __restrict__ st, int p,
             if (seg[u_hi] >= t1) --u_hi;
         }
         const int nseg = u_hi - u_lo + 1;
+        // decode window: the tile, plus the tail of its last key unless that key is a hot one
+        // (hot keys are cut at the tile's end)
+        int w_end = t1;
+        {
+            const int e0 = seg[u_hi], e1 = seg[u_hi + 1];
+            if (e1 - e0 <= kWarmMax) w_end = e1;
+        }
         __syncthreads();                                   // the previous tile's LDS is consumed
         for (int i = threadIdx.x; i <= nseg; i += NT) s_seg[i] = seg[u_lo + i];
         for (int i = threadIdx.x; i < nseg; i += NT) s_row[i] = uq[u_lo + i];
-        for (int i = threadIdx.x; i < t1 - t0; i += NT) {
-            size_t a;
+        for (int i = threadIdx.x; i < w_end - t0; i += NT) {
+            uint32_t a;
             float c;
             g.locate(t0 + i, &a, &c);
             s_addr[i] = a;
             s_scl[i] = c;
         }
         if (threadIdx.x == 0) { s_nwarm = 0; s_nhot = 0; }
-        g.t0 = t0; g.t1 = t1;
+        g.t0 = t0; g.t1 = w_end;
         __syncthreads();
         // cold keys that start here are finished on the spot
         for (int k = gi; k < nseg; k += GPB) {
@@ -1136,16 +1145,27 @@ pk_status check_common(const pk_plan* plan, int32_t B, int64_t nnz, const void* 
 }
 
 // ---- per-pack template dispatch ------------------------------------------------
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
+
+// every field of the pack starts at an output column that is a multiple of 4
+bool cols_aligned(const pk_plan* plan, int p)
+{
+    for (int32_t f : plan->packs[p].fields)
+        if (plan->field_col[f] % 4) return false;
+    return true;
+}
+
 struct PoolArgs {
     const void* W; const uint32_t* keys; const int32_t* po; const PackState* st; const FieldMeta* fmeta;
     const int32_t* slot_field; int B; int D; int64_t n_bags; float* out; int64_t out_stride; unsigned grid_cap;
+    bool aligned;
 };
 struct AdaArgs {
     void* W; float* A; const PackState* st; int p; const uint32_t* unique; const int32_t* cnt; const int32_t* hot;
     double* ghot; int dmax;
     const int32_t* tile_first; int tp; const uint32_t* seg_bag; const int32_t* po; const int32_t* slot_field;
     const FieldMeta* fmeta; int B; int has_mean; const float* grad; int64_t gstride; int D;
-    float lr; float eps; int64_t nnz_bound;
+    float lr; float eps; int64_t nnz_bound; bool aligned;
 };
 
 template <typename WT, int VEC, int LPR, int NCH>
@@ -1176,7 +1196,7 @@ pk_status launch_adagrad(DeviceState* ds, hipStream_t stream, const AdaArgs& a)
 // Picks lanes-per-row so that one row is one coalesced access: 16 bytes per
 // lane when the dimension allows it, else one element per lane.
 #define PK_DISPATCH_BODY(FN)                                                                    \
-    if (D % VECW == 0) {                                                                        \
+    if (D % VECW == 0 && a.aligned) {                                                           \
         switch (pow2_ceil(D / VECW)) {                                                          \
             case 1:  return FN<WT, VECW, 1, 1>(ds, stream, a);                                  \
             case 2:  return FN<WT, VECW, 2, 1>(ds, stream, a);                                  \
@@ -1267,7 +1287,8 @@ pk_status pk_forward(const pk_plan* plan, void* const* W, const int64_t* ids, co
     for (int p = 0; p < P; ++p) {
         const Pack& k = plan->packs[p];
         PoolArgs a{W[p], keys, packed_offsets + po_off(plan, p, B), st + p, ds->fmeta, ds->slot_field + k.first_slot,
-                   B, k.dim, (int64_t)k.fields.size() * B, out, out_row_stride, 256 * 32};
+                   B, k.dim, (int64_t)k.fields.size() * B, out, out_row_stride, 256 * 32,
+                   cols_aligned(plan, p) && aligned16(out) && out_row_stride % 4 == 0 && aligned16(W[p])};
         rc = k.dtype == PK_F32 ? dispatch_pool<float, 4>(ds, stream, k.dim, a)
                                : dispatch_pool<uint16_t, 8>(ds, stream, k.dim, a);
         if (rc != PK_OK) return rc;
@@ -1298,6 +1319,7 @@ pk_status pk_backward_update(const pk_plan* plan, void* const* W, float* const* 
     for (int p = 0; p < P; ++p)
         if (!W[p] || !A[p]) return fail(PK_EINVAL, "pk_backward_update: W or A of pack " + std::to_string(p) + " is NULL");
     if (grad_row_stride < plan->out_dim) return fail(PK_ESHAPE, "pk_backward_update: grad_row_stride is smaller than out_dim");
+    if ((int64_t)B * grad_row_stride >= ((int64_t)1 << 32)) return fail(PK_EOVERFLOW, "pk_backward_update: B * grad_row_stride must be below 2^32");
     DeviceState* ds = nullptr;
     rc = ensure_device_state(plan, &ds);
     if (rc != PK_OK) return rc;
@@ -1311,7 +1333,9 @@ pk_status pk_backward_update(const pk_plan* plan, void* const* W, float* const* 
                   ws.at<double>(L.ghot), L.dmax, ws.at<int32_t>(L.tile_first), L.pos_tile,
                   ws.at<uint32_t>(L.seg_ent), ws.at<int32_t>(L.packed_offsets) + po_off(plan, p, B),
                   ds->slot_field + k.first_slot, ds->fmeta, B, k.has_mean ? 1 : 0, grad_out, grad_row_stride, k.dim,
-                  lr, eps, nnz};
+                  lr, eps, nnz,
+                  cols_aligned(plan, p) && aligned16(grad_out) && grad_row_stride % 4 == 0 && aligned16(W[p]) &&
+                      aligned16(A[p])};
         rc = k.dtype == PK_F32 ? dispatch_adagrad<float, 4>(ds, stream, k.dim, a)
                                : dispatch_adagrad<uint16_t, 8>(ds, stream, k.dim, a);
         if (rc != PK_OK) return rc;
