@@ -17,6 +17,7 @@
 #include <hip/hip_runtime.h>
 
 #include <cstdio>
+#include <cstdlib>
 #include <map>
 #include <mutex>
 #include <string>
@@ -430,7 +431,7 @@ pk_inverse_kernel(const PackMeta* __restrict__ pm, const PackState* __restrict__
 // the backward pass, tile_first[t] = the key whose segment holds position t*tp.
 __global__ void __launch_bounds__(NT)
 pk_segs_kernel(const PackMeta* __restrict__ pm, PackState* st, int32_t* cnt, uint64_t* seg_desc,
-               int32_t* __restrict__ hot, double* __restrict__ ghot, int dmax,
+               int32_t* __restrict__ hot, int32_t* __restrict__ hot_of, double* __restrict__ ghot, int dmax,
                int32_t* __restrict__ tile_first, int tp)
 {
     __shared__ uint32_t s_pa, s_pb;
@@ -500,6 +501,7 @@ pk_segs_kernel(const PackMeta* __restrict__ pm, PackState* st, int32_t* cnt, uin
                 if (is_hot) {
                     const size_t h = carry_b + eb;
                     hl[h] = u;
+                    hot_of[start + p + u] = (int)h;
                     for (int d = 0; d < D; ++d) gh[h * D + d] = 0.0;
                 }
             }
@@ -509,22 +511,28 @@ pk_segs_kernel(const PackMeta* __restrict__ pm, PackState* st, int32_t* cnt, uin
     }
 }
 
-// Occurrences grouped by distinct key: for each, the bag it came from (the bag
-// gives the gradient's address and the 1/L of mean pooling).  A block takes 256
-// consecutive bags, whose occurrences are contiguous, and finds each
+// Occurrences grouped by distinct key (counting sort): each entry says where the
+// occurrence's gradient lives in grad_out (sample * out_dim + the field's
+// column) and, in packs with mean pooling, carries the 1/L of its bag.  A block
+// takes 256 consecutive bags, whose occurrences are contiguous, and finds each
 // occurrence's bag in LDS.
 __global__ void __launch_bounds__(NT)
-pk_scatter_kernel(int B, const PackMeta* __restrict__ pm, const PackState* __restrict__ st,
+pk_scatter_kernel(int B, int64_t out_dim, const FieldMeta* __restrict__ fmeta, const PackMeta* __restrict__ pm,
+                  const PackState* __restrict__ st, const int32_t* __restrict__ slot_field,
                   const int32_t* __restrict__ packed_offsets,
                   const int32_t* __restrict__ inverse, const int32_t* __restrict__ occ_slot,
-                  const int32_t* __restrict__ cnt, uint32_t* __restrict__ seg_bag)
+                  const int32_t* __restrict__ cnt, uint32_t* __restrict__ seg_ent, int ent_mult)
 {
     __shared__ int32_t s_po[NT + 1];
+    __shared__ uint32_t s_ent[NT];
+    __shared__ float s_scl[NT];
     const int p = blockIdx.y;
     const int n = st[p].nnz, start = st[p].start;
     const PackMeta k = pm[p];
     const int32_t* po = packed_offsets + (int64_t)k.first_slot * B + p;
+    const int32_t* sf = slot_field + k.first_slot;
     const int32_t* cn = cnt + start + p;
+    uint32_t* ent = seg_ent + (size_t)start * ent_mult;
     const int64_t n_bags = (int64_t)k.n_fields * B;
     const int n_tiles = (int)((n_bags + NT - 1) / NT);
     for (XcdTiles it(n_tiles); it.valid(); it.next()) {
@@ -532,13 +540,29 @@ pk_scatter_kernel(int B, const PackMeta* __restrict__ pm, const PackState* __res
         const int nb = (int)min((int64_t)NT, n_bags - bag0);
         __syncthreads();
         for (int t = threadIdx.x; t <= nb; t += NT) s_po[t] = min(max(po[bag0 + t], 0), n);
+        if (threadIdx.x < nb) {
+            const int64_t g = bag0 + threadIdx.x;
+            const int j = (int)(g / B);
+            const int b = (int)(g - (int64_t)j * B);
+            const FieldMeta m = fmeta[sf[j]];
+            s_ent[threadIdx.x] = (uint32_t)((int64_t)b * out_dim + m.col);
+            float sc = 1.0f;
+            if (m.pool == PK_MEAN) {
+                const int L = po[g + 1] - po[g];
+                if (L > 0) sc = 1.0f / (float)L;
+            }
+            s_scl[threadIdx.x] = sc;
+        }
         __syncthreads();
         const int q_lo = s_po[0], q_hi = s_po[nb];
         for (int q = q_lo + threadIdx.x; q < q_hi; q += NT) {
             const int t = upper_bound_i32(s_po, nb + 1, q) - 1;
             if ((unsigned)t >= (unsigned)nb) continue;
             const int pos = cn[inverse[start + q]] + occ_slot[start + q];
-            if ((unsigned)pos < (unsigned)n) seg_bag[start + pos] = (uint32_t)(bag0 + t);
+            if ((unsigned)pos < (unsigned)n) {
+                if (k.has_mean) reinterpret_cast<uint2*>(ent)[pos] = make_uint2(s_ent[t], __float_as_uint(s_scl[t]));
+                else ent[pos] = s_ent[t];
+            }
         }
     }
 }
@@ -710,41 +734,13 @@ pk_pool_kernel(const WT* __restrict__ W, const uint32_t* __restrict__ keys_all, 
 //                               it (double atomics) to the key's partial-sum row;
 //                               pk_adagrad_hot_kernel then applies the update.
 // ---------------------------------------------------------------------------
-// Where the gradient of an occurrence lives.  The occurrence list holds the
-// bag (slot-major index inside the pack); the bag gives the sample, the
-// field's output column and, for mean pooling, the bag length.  A block decodes
-// the positions of its tile (plus the tail of the last key that starts in it)
-// once, in parallel, into LDS.
+// The gradient chunks of a tile's occurrences: element offsets into grad_out and
+// mean-pooling scales, decoded once per tile, in parallel, into LDS.
 struct GradSrc {
-    const uint32_t* bag;         // per position of the key-sorted occurrence list
-    const int32_t* po;           // the pack's packed bag offsets
-    const int32_t* slot_field;   // the pack's fields in slot order
-    const FieldMeta* fmeta;
     const float* grad;
-    int64_t gstride;
-    uint32_t B;
-    int has_mean;
-    const uint32_t* s_addr;      // LDS: decoded positions [t0, t1)
+    const uint32_t* s_addr;      // LDS: positions [t0, ...)
     const float* s_scl;
-    int t0, t1;
-
-    // element offset of the gradient chunk in grad_out (the host checks B * stride < 2^32)
-    __device__ __forceinline__ void locate(int s, uint32_t* addr, float* scale) const
-    {
-        const uint32_t g = bag[s];
-        const uint32_t j = g / B;
-        const uint32_t b = g - j * B;
-        const FieldMeta m = fmeta[slot_field[j]];
-        *addr = b * (uint32_t)gstride + (uint32_t)m.col;
-        float sc = 1.0f;
-        if (has_mean && m.pool == PK_MEAN) {
-            const int L = po[g + 1] - po[g];
-            if (L > 0) sc = 1.0f / (float)L;
-        }
-        *scale = sc;
-    }
-    // positions [t0, t1) are decoded in LDS; the kernel makes the window cover every
-    // position its inner loops touch
+    int t0;
     __device__ __forceinline__ void fetch(int s, uint32_t* addr, float* scale) const
     {
         *addr = s_addr[s - t0];
@@ -848,10 +844,9 @@ __global__ void __launch_bounds__(NT)
 pk_adagrad_kernel(WT* W, float* A, const PackState* __restrict__ st, int p,
                   const uint32_t* __restrict__ unique_all, const int32_t* __restrict__ cnt,
                   const int32_t* __restrict__ hot_all, double* ghot_all, int dmax,
-                  const int32_t* __restrict__ tile_first, int tp,
-                  const uint32_t* __restrict__ seg_bag_all, const int32_t* __restrict__ po,
-                  const int32_t* __restrict__ slot_field, const FieldMeta* __restrict__ fmeta, int B, int has_mean,
-                  const float* __restrict__ grad, int64_t gstride, int D, float lr, float eps)
+                  const int32_t* __restrict__ hot_of_all, const int32_t* __restrict__ tile_first, int tp, int hot_chunk,
+                  const uint32_t* __restrict__ seg_ent_all, int ent_mult, int has_mean,
+                  const float* __restrict__ grad, int64_t gstride, int64_t out_dim, int D, float lr, float eps)
 {
     constexpr int GPB = NT / LPR;          // lane groups per block
     constexpr int GPW = 64 / LPR;          // lane groups per wavefront
@@ -864,14 +859,15 @@ pk_adagrad_kernel(WT* W, float* A, const PackState* __restrict__ st, int p,
     __shared__ float s_scl[kPosTileMax + kWarmMax];
     const int li = threadIdx.x % LPR, gi = threadIdx.x / LPR;
     const int wv = threadIdx.x >> 6, gw = (threadIdx.x & 63) / LPR;
-    const int n = st->nnz, U = st->n_unique, start = st->start, n_hot = st->n_hot;
+    const int n = st->nnz, U = st->n_unique, start = st->start;
     const int32_t* seg = cnt + start + p;
     const uint32_t* uq = unique_all + start;
     const size_t hbase = (size_t)(start / (kWarmMax + 1) + p);
-    const int32_t* hl = hot_all + hbase;
     double* gh = ghot_all + hbase * dmax;
     const int32_t* tf = tile_first + start / tp + p;
-    GradSrc g{seg_bag_all + start, po, slot_field, fmeta, grad, gstride, (uint32_t)B, has_mean, s_addr, s_scl, 0, 0};
+    const int32_t* hot_of = hot_of_all + start + p;
+    const uint32_t* ent = seg_ent_all + (size_t)start * ent_mult;
+    GradSrc g{grad, s_addr, s_scl, 0};
     const int n_tiles = (n + tp - 1) / tp;
     for (XcdTiles it(n_tiles); it.valid(); it.next()) {
         const int tile = it.tile;
@@ -896,13 +892,23 @@ pk_adagrad_kernel(WT* W, float* A, const PackState* __restrict__ st, int p,
         for (int i = threadIdx.x; i < nseg; i += NT) s_row[i] = uq[u_lo + i];
         for (int i = threadIdx.x; i < w_end - t0; i += NT) {
             uint32_t a;
-            float c;
-            g.locate(t0 + i, &a, &c);
+            float c = 1.0f;
+            if (has_mean) {
+                const uint2 e = reinterpret_cast<const uint2*>(ent)[t0 + i];
+                a = e.x;
+                c = __uint_as_float(e.y);
+            } else {
+                a = ent[t0 + i];
+            }
+            if (gstride != out_dim) {                      // padded gradient rows
+                const uint32_t b = a / (uint32_t)out_dim;
+                a = b * (uint32_t)gstride + (a - b * (uint32_t)out_dim);
+            }
             s_addr[i] = a;
             s_scl[i] = c;
         }
         if (threadIdx.x == 0) { s_nwarm = 0; s_nhot = 0; }
-        g.t0 = t0; g.t1 = w_end;
+        g.t0 = t0;
         __syncthreads();
         // cold keys that start here are finished on the spot
         for (int k = gi; k < nseg; k += GPB) {
@@ -951,12 +957,9 @@ pk_adagrad_kernel(WT* W, float* A, const PackState* __restrict__ st, int p,
             const int k = s_hot[i];
             const int u = u_lo + k;
             const int a0 = max(s_seg[k], t0), b0 = min(s_seg[k + 1], t1);
-            // row of partial sums: position of u in the ascending list of hot keys
-            int lo = 0, hi = n_hot;
-            while (lo < hi) { const int mid = (lo + hi) >> 1; if (hl[mid] < u) lo = mid + 1; else hi = mid; }
-            double* prow = gh + (size_t)lo * D;
-            for (int c0 = a0 + wv * 256; c0 < b0; c0 += (NT / 64) * 256) {
-                const int c1 = min(c0 + 256, b0);
+            double* prow = gh + (size_t)hot_of[u] * D;   // the key's row of partial sums
+            for (int c0 = a0 + wv * hot_chunk; c0 < b0; c0 += (NT / 64) * hot_chunk) {
+                const int c1 = min(c0 + hot_chunk, b0);
                 double acc[NCH][VEC];
 #pragma unroll
                 for (int c = 0; c < NCH; ++c)
@@ -1017,6 +1020,14 @@ struct DeviceState {
     PackMeta* pmeta = nullptr;
     int32_t* slot_field = nullptr;
     std::mutex mu;
+    // Side streams: packs (and the pooling of a pack vs the dedup chain) are independent
+    // pieces of memory-bound work; running them side by side hides launch gaps and
+    // latency tails (the interleaving of packed operations of Sec. III-C, on one GPU).
+    static constexpr int kSide = 4;
+    hipStream_t side[kSide] = {};
+    hipEvent_t ev_fork = nullptr;
+    hipEvent_t ev_join[kSide] = {};
+    bool overlap = true;
     // profiling
     bool prof_on = false;
     std::vector<hipEvent_t> events;
@@ -1073,9 +1084,35 @@ pk_status ensure_device_state(const pk_plan* cplan, DeviceState** out)
     if (e == hipSuccess) e = hipMemcpy(ds->pmeta, pmv.data(), P * sizeof(PackMeta), hipMemcpyHostToDevice);
     if (e == hipSuccess) e = hipMemcpy(ds->slot_field, plan->slot_field.data(), F * 4, hipMemcpyHostToDevice);
     if (e != hipSuccess) { (void)hipFree(ds->blob); delete ds; return fail(PK_EHIP, hip_msg("hipMemcpy(plan metadata)", e)); }
+    for (int i = 0; i < DeviceState::kSide && e == hipSuccess; ++i) {
+        e = hipStreamCreateWithFlags(&ds->side[i], hipStreamNonBlocking);     // default priority
+        if (e == hipSuccess) e = hipEventCreateWithFlags(&ds->ev_join[i], hipEventDisableTiming);
+    }
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&ds->ev_fork, hipEventDisableTiming);
+    if (e != hipSuccess) { (void)hipFree(ds->blob); delete ds; return fail(PK_EHIP, hip_msg("side stream setup", e)); }
+    if (getenv("PK_TUNE_NO_OVERLAP")) ds->overlap = false;       // tuning aid
     plan->device_state = ds;
     *out = ds;
     return PK_OK;
+}
+
+// fork: side streams wait for what the caller's stream has enqueued so far
+pk_status fork_streams(DeviceState* ds, hipStream_t main, int n)
+{
+    hipError_t e = hipEventRecord(ds->ev_fork, main);
+    for (int i = 0; i < n && e == hipSuccess; ++i) e = hipStreamWaitEvent(ds->side[i], ds->ev_fork, 0);
+    return e == hipSuccess ? PK_OK : fail(PK_EHIP, hip_msg("stream fork", e));
+}
+
+// join: the caller's stream waits for everything enqueued on the side streams
+pk_status join_streams(DeviceState* ds, hipStream_t main, int n)
+{
+    hipError_t e = hipSuccess;
+    for (int i = 0; i < n && e == hipSuccess; ++i) {
+        e = hipEventRecord(ds->ev_join[i], ds->side[i]);
+        if (e == hipSuccess) e = hipStreamWaitEvent(main, ds->ev_join[i], 0);
+    }
+    return e == hipSuccess ? PK_OK : fail(PK_EHIP, hip_msg("stream join", e));
 }
 
 void prof_begin(DeviceState* ds, const char* name, hipStream_t s)
@@ -1163,8 +1200,8 @@ struct PoolArgs {
 struct AdaArgs {
     void* W; float* A; const PackState* st; int p; const uint32_t* unique; const int32_t* cnt; const int32_t* hot;
     double* ghot; int dmax;
-    const int32_t* tile_first; int tp; const uint32_t* seg_bag; const int32_t* po; const int32_t* slot_field;
-    const FieldMeta* fmeta; int B; int has_mean; const float* grad; int64_t gstride; int D;
+    const int32_t* hot_of; const int32_t* tile_first; int tp; int hot_chunk; const uint32_t* seg_ent; int ent_mult;
+    int has_mean; const float* grad; int64_t gstride; int64_t out_dim; int D;
     float lr; float eps; int64_t nnz_bound; bool aligned;
 };
 
@@ -1185,8 +1222,8 @@ pk_status launch_adagrad(DeviceState* ds, hipStream_t stream, const AdaArgs& a)
     constexpr int GPB = NT / LPR;
     const unsigned grid = (blocks_for(a.nnz_bound, a.tp, 256 * 16) + 7u) & ~7u;
     PK_LAUNCH("pk_adagrad", (pk_adagrad_kernel<WT, VEC, LPR, NCH>), dim3(grid), dim3(NT), 0,
-              static_cast<WT*>(a.W), a.A, a.st, a.p, a.unique, a.cnt, a.hot, a.ghot, a.dmax, a.tile_first, a.tp,
-              a.seg_bag, a.po, a.slot_field, a.fmeta, a.B, a.has_mean, a.grad, a.gstride, a.D, a.lr, a.eps);
+              static_cast<WT*>(a.W), a.A, a.st, a.p, a.unique, a.cnt, a.hot, a.ghot, a.dmax, a.hot_of, a.tile_first,
+              a.tp, a.hot_chunk, a.seg_ent, a.ent_mult, a.has_mean, a.grad, a.gstride, a.out_dim, a.D, a.lr, a.eps);
     const unsigned hgrid = blocks_for(a.nnz_bound / (kWarmMax + 1) + 1, GPB, 1024);
     PK_LAUNCH("pk_adagrad_hot", (pk_adagrad_hot_kernel<WT, VEC, LPR, NCH>), dim3(hgrid), dim3(NT), 0,
               static_cast<WT*>(a.W), a.A, a.st, a.p, a.unique, a.hot, a.ghot, a.dmax, a.D, a.lr, a.eps);
@@ -1227,6 +1264,11 @@ void destroy_device_state(pk_plan* plan)
     DeviceState* ds = static_cast<DeviceState*>(plan->device_state);
     if (!ds) return;
     for (hipEvent_t ev : ds->events) (void)hipEventDestroy(ev);
+    for (int i = 0; i < DeviceState::kSide; ++i) {
+        if (ds->side[i]) { (void)hipStreamSynchronize(ds->side[i]); (void)hipStreamDestroy(ds->side[i]); }
+        if (ds->ev_join[i]) (void)hipEventDestroy(ds->ev_join[i]);
+    }
+    if (ds->ev_fork) (void)hipEventDestroy(ds->ev_fork);
     if (ds->blob) (void)hipFree(ds->blob);
     delete ds;
     plan->device_state = nullptr;
@@ -1284,13 +1326,18 @@ pk_status pk_forward(const pk_plan* plan, void* const* W, const int64_t* ids, co
               use_lds ? (size_t)(F + 1) * 4 : 0, ids, offsets, B, F, nnz, ds->fmeta, ds->pmeta, st, fb, delta,
               slot_start, keys, bitmap, packed_offsets, use_lds);
 
+    // pooling needs the keys only: it runs beside the rest of the dedup chain
+    const bool overlap = ds->overlap && !ds->prof_on && (P > 1 || nnz >= (1 << 20));   // fork+join cost a few us
+    const int n_side = overlap ? std::min<int>(P, DeviceState::kSide) : 0;
+    if (n_side) { rc = fork_streams(ds, stream, n_side); if (rc != PK_OK) return rc; }
     for (int p = 0; p < P; ++p) {
         const Pack& k = plan->packs[p];
         PoolArgs a{W[p], keys, packed_offsets + po_off(plan, p, B), st + p, ds->fmeta, ds->slot_field + k.first_slot,
                    B, k.dim, (int64_t)k.fields.size() * B, out, out_row_stride, 256 * 32,
                    cols_aligned(plan, p) && aligned16(out) && out_row_stride % 4 == 0 && aligned16(W[p])};
-        rc = k.dtype == PK_F32 ? dispatch_pool<float, 4>(ds, stream, k.dim, a)
-                               : dispatch_pool<uint16_t, 8>(ds, stream, k.dim, a);
+        hipStream_t ps = n_side ? ds->side[p % n_side] : stream;
+        rc = k.dtype == PK_F32 ? dispatch_pool<float, 4>(ds, ps, k.dim, a)
+                               : dispatch_pool<uint16_t, 8>(ds, ps, k.dim, a);
         if (rc != PK_OK) return rc;
     }
 
@@ -1300,11 +1347,13 @@ pk_status pk_forward(const pk_plan* plan, void* const* W, const int64_t* ids, co
     PK_LAUNCH("pk_inverse", pk_inverse_kernel, dim3(xq, P), dim3(NT), 0, ds->pmeta, st, keys,
               reinterpret_cast<const uint4*>(bitmap), rank, inverse, occ_slot, cnt);
     PK_LAUNCH("pk_segs", pk_segs_kernel, dim3(blocks_for(nnz, kSegTile, std::max(1, 1024 / P)), P), dim3(NT), 0,
-              ds->pmeta, st, cnt, seg_desc, hot, ghot, L.dmax, tile_first, L.pos_tile);
+              ds->pmeta, st, cnt, seg_desc, hot, ws.at<int32_t>(L.hot_of), ghot, L.dmax, tile_first, L.pos_tile);
     int64_t max_bags = 0;
     for (int p = 0; p < P; ++p) max_bags = std::max<int64_t>(max_bags, (int64_t)plan->packs[p].fields.size() * B);
     PK_LAUNCH("pk_scatter", pk_scatter_kernel, dim3((blocks_for(max_bags, NT, 256 * 16) + 7u) & ~7u, P), dim3(NT), 0,
-              B, ds->pmeta, st, packed_offsets, inverse, occ_slot, cnt, seg_ent);
+              B, plan->out_dim, ds->fmeta, ds->pmeta, st, ds->slot_field, packed_offsets, inverse, occ_slot, cnt,
+              seg_ent, plan->any_mean ? 2 : 1);
+    if (n_side) { rc = join_streams(ds, stream, n_side); if (rc != PK_OK) return rc; }
     return PK_OK;
 }
 
@@ -1327,19 +1376,24 @@ pk_status pk_backward_update(const pk_plan* plan, void* const* W, float* const* 
     Ws ws{static_cast<char*>(workspace), make_layout(plan, B, nnz)};
     const Layout& L = ws.L;
     PackState* st = ws.at<PackState>(L.state);
+    // packs touch disjoint tables: one side stream each
+    const bool overlap = ds->overlap && !ds->prof_on && P > 1;
+    const int n_side = overlap ? std::min<int>(P, DeviceState::kSide) : 0;
+    if (n_side) { rc = fork_streams(ds, stream, n_side); if (rc != PK_OK) return rc; }
     for (int p = 0; p < P; ++p) {
         const Pack& k = plan->packs[p];
+        hipStream_t ps = n_side ? ds->side[p % n_side] : stream;
         AdaArgs a{W[p], A[p], st + p, p, ws.at<uint32_t>(L.unique), ws.at<int32_t>(L.cnt), ws.at<int32_t>(L.hot),
-                  ws.at<double>(L.ghot), L.dmax, ws.at<int32_t>(L.tile_first), L.pos_tile,
-                  ws.at<uint32_t>(L.seg_ent), ws.at<int32_t>(L.packed_offsets) + po_off(plan, p, B),
-                  ds->slot_field + k.first_slot, ds->fmeta, B, k.has_mean ? 1 : 0, grad_out, grad_row_stride, k.dim,
-                  lr, eps, nnz,
+                  ws.at<double>(L.ghot), L.dmax, ws.at<int32_t>(L.hot_of), ws.at<int32_t>(L.tile_first), L.pos_tile,
+                  nnz < (2 << 20) ? 64 : 256, ws.at<uint32_t>(L.seg_ent), plan->any_mean ? 2 : 1,
+                  k.has_mean ? 1 : 0, grad_out, grad_row_stride, plan->out_dim, k.dim, lr, eps, nnz,
                   cols_aligned(plan, p) && aligned16(grad_out) && grad_row_stride % 4 == 0 && aligned16(W[p]) &&
                       aligned16(A[p])};
-        rc = k.dtype == PK_F32 ? dispatch_adagrad<float, 4>(ds, stream, k.dim, a)
-                               : dispatch_adagrad<uint16_t, 8>(ds, stream, k.dim, a);
+        rc = k.dtype == PK_F32 ? dispatch_adagrad<float, 4>(ds, ps, k.dim, a)
+                               : dispatch_adagrad<uint16_t, 8>(ds, ps, k.dim, a);
         if (rc != PK_OK) return rc;
     }
+    if (n_side) { rc = join_streams(ds, stream, n_side); if (rc != PK_OK) return rc; }
     return PK_OK;
 }
 

@@ -64,7 +64,7 @@ struct Pack {
 
 // Byte offsets of the workspace's arrays for one (plan, B, nnz).
 struct Layout {
-    size_t state, fb, delta, slot_start, packed_offsets, keys, inverse, occ_slot, seg_ent, tile_first,
+    size_t state, fb, delta, slot_start, packed_offsets, keys, inverse, occ_slot, seg_ent, hot_of, tile_first,
            unique, cnt, hot, ghot, bitmap, tile_desc, seg_desc, rank, total;
     size_t clear_bytes;          // bitmap + scan descriptors, contiguous from `bitmap`
     int64_t n_tiles_total;

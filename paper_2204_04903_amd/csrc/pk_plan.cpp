@@ -9,6 +9,7 @@
 #include "pk_internal.h"
 
 #include <algorithm>
+#include <cstdlib>
 #include <new>
 
 namespace pk {
@@ -29,7 +30,9 @@ static size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 // tiles so that the launch still has thousands of blocks.
 int32_t pos_tile_for(int64_t nnz)
 {
-    int64_t t = (nnz / 8192 + 63) / 64 * 64;
+    static const char* env = getenv("PK_TUNE_POS_TILE");      // tuning aid
+    if (env && atoi(env) >= kPosTileMin && atoi(env) <= kPosTileMax) return atoi(env) / 64 * 64;
+    int64_t t = nnz < (2 << 20) ? 256 : 512;
     if (t < kPosTileMin) t = kPosTileMin;
     if (t > kPosTileMax) t = kPosTileMax;
     return (int32_t)t;
@@ -50,7 +53,8 @@ Layout make_layout(const pk_plan* plan, int32_t B, int64_t nnz)
     L.keys           = take(n * 4);
     L.inverse        = take(n * 4);
     L.occ_slot       = take(n * 4);
-    L.seg_ent        = take(n * 4);
+    L.seg_ent        = take(n * (plan->any_mean ? 8 : 4));
+    L.hot_of         = take((n + P + 1) * 4);
     L.pos_tile       = pos_tile_for(nnz);
     L.tile_first     = take((n / L.pos_tile + P + 2) * 4);
     L.unique         = take(n * 4);
