@@ -223,14 +223,16 @@ pk_setup_kernel(const int32_t* __restrict__ offsets, int B, int F, int P, int64_
 // time: each block first removes repeats among its 1024 occurrences in an LDS
 // hash table, and only the first holder of a key touches the global bitmap.
 // ---------------------------------------------------------------------------
-constexpr int kKeyTile = 1024;
-constexpr int kHashSlots = 2048;
 
+// KT occurrences per tile, 2*KT hash slots: small problems take small tiles to
+// keep thousands of blocks in flight, large ones take large tiles to merge more repeats.
+template <int SLOTS>
 __device__ __forceinline__ uint32_t hash_slot(uint64_t x)
 {
-    return (uint32_t)((x * 0x9E3779B97F4A7C15ull) >> 40) & (kHashSlots - 1);
+    return (uint32_t)((x * 0x9E3779B97F4A7C15ull) >> 40) & (SLOTS - 1);
 }
 
+template <int KT>
 __global__ void __launch_bounds__(NT)
 pk_keys_kernel(const int64_t* __restrict__ ids, const int32_t* __restrict__ offsets, int B, int F, int64_t nnz,
                const FieldMeta* __restrict__ fmeta, const PackMeta* __restrict__ pm, const PackState* __restrict__ st,
@@ -239,26 +241,26 @@ pk_keys_kernel(const int64_t* __restrict__ ids, const int32_t* __restrict__ offs
                int32_t* __restrict__ packed_offsets, int use_lds)
 {
     extern __shared__ int32_t s_fb[];
-    __shared__ unsigned long long s_tag[kHashSlots];
+    __shared__ unsigned long long s_tag[(2 * KT)];
     if (st[0].error) return;
     if (use_lds) {
         for (int f = threadIdx.x; f <= F; f += NT) s_fb[f] = fb[f];
     }
-    const int n_tiles = (int)((nnz + kKeyTile - 1) / kKeyTile);
+    const int n_tiles = (int)((nnz + KT - 1) / KT);
     for (XcdTiles it(n_tiles); it.valid(); it.next()) {
         const int64_t tile = it.tile;
         __syncthreads();                               // table free again; s_fb loaded
-        for (int s = threadIdx.x; s < kHashSlots; s += NT) s_tag[s] = ~0ull;
+        for (int s = threadIdx.x; s < (2 * KT); s += NT) s_tag[s] = ~0ull;
         __syncthreads();
-        int64_t idv[kKeyTile / NT];
+        int64_t idv[KT / NT];
 #pragma unroll
-        for (int k = 0; k < kKeyTile / NT; ++k) {          // all loads of the tile in flight together
-            const int64_t i = tile * kKeyTile + k * NT + threadIdx.x;
+        for (int k = 0; k < KT / NT; ++k) {          // all loads of the tile in flight together
+            const int64_t i = tile * KT + k * NT + threadIdx.x;
             idv[k] = i < nnz ? ids[i] : 0;
         }
 #pragma unroll
-        for (int k = 0; k < kKeyTile / NT; ++k) {
-            const int64_t i = tile * kKeyTile + k * NT + threadIdx.x;
+        for (int k = 0; k < KT / NT; ++k) {
+            const int64_t i = tile * KT + k * NT + threadIdx.x;
             if (i < nnz) {
                 const int f = (use_lds ? upper_bound_i32(s_fb, F + 1, (int)i) : upper_bound_i32(fb, F + 1, (int)i)) - 1;
                 const FieldMeta m = fmeta[f];
@@ -267,13 +269,13 @@ pk_keys_kernel(const int64_t* __restrict__ ids, const int32_t* __restrict__ offs
                 if ((uint64_t)q < (uint64_t)nnz) {
                     keys[q] = key;
                     const unsigned long long tag = ((unsigned long long)(uint32_t)m.pack << 32) | key;
-                    uint32_t h = hash_slot(tag);
+                    uint32_t h = hash_slot<2 * KT>(tag);
                     bool first = false;
                     while (true) {
                         const unsigned long long old = atomicCAS(&s_tag[h], ~0ull, tag);
                         if (old == ~0ull) { first = true; break; }
                         if (old == tag) break;
-                        h = (h + 1) & (kHashSlots - 1);
+                        h = (h + 1) & ((2 * KT) - 1);
                     }
                     if (first)
                         atomicOr(&bitmap[(size_t)pm[m.pack].first_tile * kTileWords + (key >> 5)], 1u << (key & 31));
@@ -360,30 +362,31 @@ pk_tiles_kernel(const uint4* __restrict__ bitmap4, uint64_t* tile_desc, int n_ti
 // inverse[q] = number of distinct keys below key[q]; occurrences counted per
 // distinct key.  Repeats inside a block's 1024 occurrences are merged in LDS
 // first, so a hot key costs one global atomic per block, not one per occurrence.
+template <int KT>
 __global__ void __launch_bounds__(NT)
 pk_inverse_kernel(const PackMeta* __restrict__ pm, const PackState* __restrict__ st,
                   const uint32_t* __restrict__ keys, const uint4* __restrict__ bitmap4,
                   const int32_t* __restrict__ rank, int32_t* __restrict__ inverse,
                   int32_t* __restrict__ occ_slot, int32_t* cnt)
 {
-    __shared__ uint32_t s_key[kHashSlots];
-    __shared__ int32_t s_cnt[kHashSlots];
+    __shared__ uint32_t s_key[(2 * KT)];
+    __shared__ int32_t s_cnt[(2 * KT)];
     const int p = blockIdx.y;
     const int n = st[p].nnz, start = st[p].start;
     const size_t rb = (size_t)pm[p].first_tile * NT;          // rank blocks before this pack
     const uint4* bm = bitmap4 + 2 * rb;
     const int32_t* rk = rank + rb;
     int32_t* cn = cnt + start + p;
-    const int n_tiles = (n + kKeyTile - 1) / kKeyTile;
+    const int n_tiles = (n + KT - 1) / KT;
     for (XcdTiles it(n_tiles); it.valid(); it.next()) {
         const int tile = it.tile;
         __syncthreads();
-        for (int s = threadIdx.x; s < kHashSlots; s += NT) { s_key[s] = 0xFFFFFFFFu; s_cnt[s] = 0; }
+        for (int s = threadIdx.x; s < (2 * KT); s += NT) { s_key[s] = 0xFFFFFFFFu; s_cnt[s] = 0; }
         __syncthreads();
-        int r_[kKeyTile / NT], h_[kKeyTile / NT], l_[kKeyTile / NT];
+        int r_[KT / NT], h_[KT / NT], l_[KT / NT];
 #pragma unroll
-        for (int k = 0; k < kKeyTile / NT; ++k) {
-            const int q = tile * kKeyTile + k * NT + threadIdx.x;
+        for (int k = 0; k < KT / NT; ++k) {
+            const int q = tile * KT + k * NT + threadIdx.x;
             r_[k] = -1; h_[k] = 0; l_[k] = 0;
             if (q < n) {
                 const uint32_t key = keys[start + q];
@@ -399,24 +402,24 @@ pk_inverse_kernel(const PackMeta* __restrict__ pm, const PackState* __restrict__
                     if (i == wi) cur = w[i];
                 }
                 r += __popc(cur & ((1u << (key & 31)) - 1u));
-                uint32_t h = hash_slot((uint64_t)(uint32_t)r);
+                uint32_t h = hash_slot<2 * KT>((uint64_t)(uint32_t)r);
                 while (true) {
                     const uint32_t old = atomicCAS(&s_key[h], 0xFFFFFFFFu, (uint32_t)r);
                     if (old == 0xFFFFFFFFu || old == (uint32_t)r) break;
-                    h = (h + 1) & (kHashSlots - 1);
+                    h = (h + 1) & ((2 * KT) - 1);
                 }
                 r_[k] = r; h_[k] = (int)h; l_[k] = atomicAdd(&s_cnt[h], 1);
             }
         }
         __syncthreads();
-        for (int s = threadIdx.x; s < kHashSlots; s += NT) {
+        for (int s = threadIdx.x; s < (2 * KT); s += NT) {
             const uint32_t r = s_key[s];
             if (r != 0xFFFFFFFFu) s_cnt[s] = atomicAdd(&cn[r], s_cnt[s]);
         }
         __syncthreads();
 #pragma unroll
-        for (int k = 0; k < kKeyTile / NT; ++k) {
-            const int q = tile * kKeyTile + k * NT + threadIdx.x;
+        for (int k = 0; k < KT / NT; ++k) {
+            const int q = tile * KT + k * NT + threadIdx.x;
             if (r_[k] >= 0) {
                 inverse[start + q] = r_[k];
                 occ_slot[start + q] = s_cnt[h_[k]] + l_[k];
@@ -514,8 +517,9 @@ pk_segs_kernel(const PackMeta* __restrict__ pm, PackState* st, int32_t* cnt, uin
 // Occurrences grouped by distinct key (counting sort): each entry says where the
 // occurrence's gradient lives in grad_out (sample * out_dim + the field's
 // column) and, in packs with mean pooling, carries the 1/L of its bag.  A block
-// takes 256 consecutive bags, whose occurrences are contiguous, and finds each
-// occurrence's bag in LDS.
+// takes BT consecutive bags (fewer when bags are long), whose occurrences are
+// contiguous, and finds each occurrence's bag in LDS.
+template <int BT>
 __global__ void __launch_bounds__(NT)
 pk_scatter_kernel(int B, int64_t out_dim, const FieldMeta* __restrict__ fmeta, const PackMeta* __restrict__ pm,
                   const PackState* __restrict__ st, const int32_t* __restrict__ slot_field,
@@ -523,9 +527,9 @@ pk_scatter_kernel(int B, int64_t out_dim, const FieldMeta* __restrict__ fmeta, c
                   const int32_t* __restrict__ inverse, const int32_t* __restrict__ occ_slot,
                   const int32_t* __restrict__ cnt, uint32_t* __restrict__ seg_ent, int ent_mult)
 {
-    __shared__ int32_t s_po[NT + 1];
-    __shared__ uint32_t s_ent[NT];
-    __shared__ float s_scl[NT];
+    __shared__ int32_t s_po[BT + 1];
+    __shared__ uint32_t s_ent[BT];
+    __shared__ float s_scl[BT];
     const int p = blockIdx.y;
     const int n = st[p].nnz, start = st[p].start;
     const PackMeta k = pm[p];
@@ -534,10 +538,10 @@ pk_scatter_kernel(int B, int64_t out_dim, const FieldMeta* __restrict__ fmeta, c
     const int32_t* cn = cnt + start + p;
     uint32_t* ent = seg_ent + (size_t)start * ent_mult;
     const int64_t n_bags = (int64_t)k.n_fields * B;
-    const int n_tiles = (int)((n_bags + NT - 1) / NT);
+    const int n_tiles = (int)((n_bags + BT - 1) / BT);
     for (XcdTiles it(n_tiles); it.valid(); it.next()) {
-        const int64_t bag0 = (int64_t)it.tile * NT;
-        const int nb = (int)min((int64_t)NT, n_bags - bag0);
+        const int64_t bag0 = (int64_t)it.tile * BT;
+        const int nb = (int)min((int64_t)BT, n_bags - bag0);
         __syncthreads();
         for (int t = threadIdx.x; t <= nb; t += NT) s_po[t] = min(max(po[bag0 + t], 0), n);
         if (threadIdx.x < nb) {
@@ -1321,10 +1325,16 @@ pk_status pk_forward(const pk_plan* plan, void* const* W, const int64_t* ids, co
               ds->slot_field, st, fb, delta, slot_start, packed_offsets, reinterpret_cast<uint4*>(bitmap), n_clear4);
 
     const int use_lds = (F + 1) * 4 <= 32 * 1024;
-    const int64_t key_blocks = std::max<int64_t>((nnz + kKeyTile - 1) / kKeyTile, ((int64_t)F * B + NT * 4 - 1) / (NT * 4));
-    PK_LAUNCH("pk_keys", pk_keys_kernel, dim3((blocks_for(key_blocks, 1, 256 * 32) + 7u) & ~7u), dim3(NT),
-              use_lds ? (size_t)(F + 1) * 4 : 0, ids, offsets, B, F, nnz, ds->fmeta, ds->pmeta, st, fb, delta,
-              slot_start, keys, bitmap, packed_offsets, use_lds);
+    const int kt = nnz < (1 << 20) ? 256 : 1024;      // occurrences per tile of the keys / inverse kernels
+    const int64_t key_blocks = std::max<int64_t>((nnz + kt - 1) / kt, ((int64_t)F * B + NT * 4 - 1) / (NT * 4));
+    const dim3 key_grid((blocks_for(key_blocks, 1, 256 * 32) + 7u) & ~7u);
+    const size_t key_lds = use_lds ? (size_t)(F + 1) * 4 : 0;
+    if (kt == 256)
+        PK_LAUNCH("pk_keys", pk_keys_kernel<256>, key_grid, dim3(NT), key_lds, ids, offsets, B, F, nnz, ds->fmeta,
+                  ds->pmeta, st, fb, delta, slot_start, keys, bitmap, packed_offsets, use_lds);
+    else
+        PK_LAUNCH("pk_keys", pk_keys_kernel<1024>, key_grid, dim3(NT), key_lds, ids, offsets, B, F, nnz, ds->fmeta,
+                  ds->pmeta, st, fb, delta, slot_start, keys, bitmap, packed_offsets, use_lds);
 
     // pooling needs the keys only: it runs beside the rest of the dedup chain
     const bool overlap = ds->overlap && !ds->prof_on && (P > 1 || nnz >= (1 << 20));   // fork+join cost a few us
@@ -1343,16 +1353,25 @@ pk_status pk_forward(const pk_plan* plan, void* const* W, const int64_t* ids, co
 
     PK_LAUNCH("pk_tiles", pk_tiles_kernel, dim3(blocks_for(n_tiles, 1, 1024)), dim3(NT), 0,
               reinterpret_cast<const uint4*>(bitmap), tile_desc, (int)n_tiles, ds->pmeta, st, P, rank, unique, cnt);
-    const unsigned xq = (blocks_for(nnz, kKeyTile, 256 * 16) + 7u) & ~7u;
-    PK_LAUNCH("pk_inverse", pk_inverse_kernel, dim3(xq, P), dim3(NT), 0, ds->pmeta, st, keys,
-              reinterpret_cast<const uint4*>(bitmap), rank, inverse, occ_slot, cnt);
+    const unsigned xq = (blocks_for(nnz, kt, 256 * 16) + 7u) & ~7u;
+    if (kt == 256)
+        PK_LAUNCH("pk_inverse", pk_inverse_kernel<256>, dim3(xq, P), dim3(NT), 0, ds->pmeta, st, keys,
+                  reinterpret_cast<const uint4*>(bitmap), rank, inverse, occ_slot, cnt);
+    else
+        PK_LAUNCH("pk_inverse", pk_inverse_kernel<1024>, dim3(xq, P), dim3(NT), 0, ds->pmeta, st, keys,
+                  reinterpret_cast<const uint4*>(bitmap), rank, inverse, occ_slot, cnt);
     PK_LAUNCH("pk_segs", pk_segs_kernel, dim3(blocks_for(nnz, kSegTile, std::max(1, 1024 / P)), P), dim3(NT), 0,
               ds->pmeta, st, cnt, seg_desc, hot, ws.at<int32_t>(L.hot_of), ghot, L.dmax, tile_first, L.pos_tile);
     int64_t max_bags = 0;
     for (int p = 0; p < P; ++p) max_bags = std::max<int64_t>(max_bags, (int64_t)plan->packs[p].fields.size() * B);
-    PK_LAUNCH("pk_scatter", pk_scatter_kernel, dim3((blocks_for(max_bags, NT, 256 * 16) + 7u) & ~7u, P), dim3(NT), 0,
-              B, plan->out_dim, ds->fmeta, ds->pmeta, st, ds->slot_field, packed_offsets, inverse, occ_slot, cnt,
-              seg_ent, plan->any_mean ? 2 : 1);
+    if (nnz / ((int64_t)F * B) >= 16)      // long bags: fewer bags per block
+        PK_LAUNCH("pk_scatter", pk_scatter_kernel<32>, dim3((blocks_for(max_bags, 32, 256 * 16) + 7u) & ~7u, P), dim3(NT),
+                  0, B, plan->out_dim, ds->fmeta, ds->pmeta, st, ds->slot_field, packed_offsets, inverse, occ_slot, cnt,
+                  seg_ent, plan->any_mean ? 2 : 1);
+    else
+        PK_LAUNCH("pk_scatter", pk_scatter_kernel<256>, dim3((blocks_for(max_bags, 256, 256 * 16) + 7u) & ~7u, P),
+                  dim3(NT), 0, B, plan->out_dim, ds->fmeta, ds->pmeta, st, ds->slot_field, packed_offsets, inverse,
+                  occ_slot, cnt, seg_ent, plan->any_mean ? 2 : 1);
     if (n_side) { rc = join_streams(ds, stream, n_side); if (rc != PK_OK) return rc; }
     return PK_OK;
 }
