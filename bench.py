@@ -137,9 +137,6 @@ def main():
     kern = {}
     for name, (ms, launches) in prof.items():
         kern[name] = dict(ms_per_step=ms / prof_steps, launches_per_step=launches / prof_steps)
-    # fold the hot-key pass into the kernel it completes
-    if "pk_adagrad_hot" in kern:
-        kern["pk_adagrad"]["ms_per_step"] += kern.pop("pk_adagrad_hot")["ms_per_step"]
     alg = {}
     for row in sizes:
         for p, info in enumerate(row):
