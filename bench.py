@@ -28,10 +28,12 @@ def algorithmic_bytes(info, mean_pack):
     n, U, bags, D, sw, bm = info["nnz"], info["U"], info["bags"], info["D"], info["sw"], info["bitmap_bytes"]
     sc = 4 * (bags + 1) if mean_pack else 0       # bag lengths for the 1/L of mean pooling
     return {
-        "pk_keys": 8 * n + 4 * n + 4 * bags + 4 * bags + 4 * U,
+        "pk_keys": 8 * n + 4 * n + 4 * bags + 4 * bags,
         "pk_pool": 4 * n + 4 * (bags + 1) + sw * D * U + 4 * D * bags,
         "pk_tiles": bm + bm // 8 + 8 * U,
-        "pk_inverse": 12 * n + 4 * U + min(bm + bm // 8, 36 * n),
+        "pk_inverse": 8 * n + min(bm + bm // 8, 36 * n),
+        "pk_mark": 4 * n + bm,
+        "pk_count": 8 * n + 4 * U,
         "pk_segs": 8 * U,
         "pk_scatter": 12 * n + 4 * U + 4 * bags,
         "pk_adagrad": 4 * (U + 1) + 4 * U + 4 * n + sc + 4 * D * bags + (2 * sw + 8) * D * U,

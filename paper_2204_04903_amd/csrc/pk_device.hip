@@ -159,7 +159,7 @@ struct XcdTiles {
 
 // ---------------------------------------------------------------------------
 // setup: block 0 derives the per-field and per-pack positions; the other
-// blocks clear the bitmap and the scan descriptors.
+// blocks clear the scan descriptors.
 // ---------------------------------------------------------------------------
 __global__ void __launch_bounds__(1024)
 pk_setup_kernel(const int32_t* __restrict__ offsets, int B, int F, int P, int64_t nnz,
@@ -217,41 +217,26 @@ pk_setup_kernel(const int32_t* __restrict__ offsets, int B, int F, int P, int64_
 }
 
 // ---------------------------------------------------------------------------
-// H1: packed keys (Sec. III-B: one packed ID tensor per pack) and bitmap marks;
-// packed bag offsets.  Skewed IDs (Sec. II-B) would make thousands of lanes
-// hit the same bitmap word, and atomics on one address are served one at a
-// time: each block first removes repeats among its 1024 occurrences in an LDS
-// hash table, and only the first holder of a key touches the global bitmap.
+// H1: packed keys (Sec. III-B: one packed ID tensor per pack) and packed bag
+// offsets.  Pure streaming: 8 bytes in, 4 bytes out per occurrence.
 // ---------------------------------------------------------------------------
-
-// KT occurrences per tile, 2*KT hash slots: small problems take small tiles to
-// keep thousands of blocks in flight, large ones take large tiles to merge more repeats.
-template <int SLOTS>
-__device__ __forceinline__ uint32_t hash_slot(uint64_t x)
-{
-    return (uint32_t)((x * 0x9E3779B97F4A7C15ull) >> 40) & (SLOTS - 1);
-}
-
 template <int KT>
 __global__ void __launch_bounds__(NT)
 pk_keys_kernel(const int64_t* __restrict__ ids, const int32_t* __restrict__ offsets, int B, int F, int64_t nnz,
                const FieldMeta* __restrict__ fmeta, const PackMeta* __restrict__ pm, const PackState* __restrict__ st,
                const int32_t* __restrict__ fb, const int32_t* __restrict__ delta,
-               const int32_t* __restrict__ slot_start, uint32_t* __restrict__ keys, uint32_t* bitmap,
+               const int32_t* __restrict__ slot_start, uint32_t* __restrict__ keys,
                int32_t* __restrict__ packed_offsets, int use_lds)
 {
     extern __shared__ int32_t s_fb[];
-    __shared__ unsigned long long s_tag[(2 * KT)];
     if (st[0].error) return;
     if (use_lds) {
         for (int f = threadIdx.x; f <= F; f += NT) s_fb[f] = fb[f];
+        __syncthreads();
     }
     const int n_tiles = (int)((nnz + KT - 1) / KT);
     for (XcdTiles it(n_tiles); it.valid(); it.next()) {
         const int64_t tile = it.tile;
-        __syncthreads();                               // table free again; s_fb loaded
-        for (int s = threadIdx.x; s < (2 * KT); s += NT) s_tag[s] = ~0ull;
-        __syncthreads();
         int64_t idv[KT / NT];
 #pragma unroll
         for (int k = 0; k < KT / NT; ++k) {          // all loads of the tile in flight together
@@ -264,22 +249,8 @@ pk_keys_kernel(const int64_t* __restrict__ ids, const int32_t* __restrict__ offs
             if (i < nnz) {
                 const int f = (use_lds ? upper_bound_i32(s_fb, F + 1, (int)i) : upper_bound_i32(fb, F + 1, (int)i)) - 1;
                 const FieldMeta m = fmeta[f];
-                const uint32_t key = m.base_row + fold_id(idv[k], m.rows);
                 const int64_t q = i + delta[f];
-                if ((uint64_t)q < (uint64_t)nnz) {
-                    keys[q] = key;
-                    const unsigned long long tag = ((unsigned long long)(uint32_t)m.pack << 32) | key;
-                    uint32_t h = hash_slot<2 * KT>(tag);
-                    bool first = false;
-                    while (true) {
-                        const unsigned long long old = atomicCAS(&s_tag[h], ~0ull, tag);
-                        if (old == ~0ull) { first = true; break; }
-                        if (old == tag) break;
-                        h = (h + 1) & ((2 * KT) - 1);
-                    }
-                    if (first)
-                        atomicOr(&bitmap[(size_t)pm[m.pack].first_tile * kTileWords + (key >> 5)], 1u << (key & 31));
-                }
+                if ((uint64_t)q < (uint64_t)nnz) keys[q] = m.base_row + fold_id(idv[k], m.rows);
             }
         }
     }
@@ -293,6 +264,60 @@ pk_keys_kernel(const int64_t* __restrict__ ids, const int32_t* __restrict__ offs
         packed_offsets[(int64_t)k.first_slot * B + m.pack + (int64_t)m.slot * B + b] =
             slot_start[k.first_slot + m.pack + m.slot] + offsets[g] - fb[f];
     }
+}
+
+// ---------------------------------------------------------------------------
+// H2, first half: which rows occur.  Global atomics run at a fixed, low rate on
+// this GPU whatever their address, so the bitmap is not built with them: a block
+// owns a slice of a pack's key space, keeps the slice's bits in LDS, scans the
+// keys of the fields whose tables overlap the slice (they are contiguous in the
+// packed order) and stores the finished words with plain coalesced writes.
+// Every bitmap word is written by exactly one block, so nothing needs clearing.
+// ---------------------------------------------------------------------------
+constexpr int kMarkThreads = 1024;
+constexpr int kMarkUnroll = 8;
+
+__global__ void __launch_bounds__(kMarkThreads)
+pk_mark_kernel(const MarkItem* __restrict__ items, const int32_t* __restrict__ item_fields,
+               const PackMeta* __restrict__ pm, const PackState* __restrict__ st,
+               const int32_t* __restrict__ fb, const int32_t* __restrict__ delta,
+               const uint32_t* __restrict__ keys, uint32_t* __restrict__ bitmap, int64_t nnz)
+{
+    __shared__ uint32_t s_bits[kMarkWords];
+    const MarkItem it = items[blockIdx.x];
+    for (int w = threadIdx.x; w < kMarkWords; w += kMarkThreads) s_bits[w] = 0;
+    __syncthreads();
+    const uint32_t span = (uint32_t)it.n_words * 32u;
+    if (!st[0].error) {
+        for (int fi = it.field_begin; fi < it.field_end; ++fi) {
+            const int f = item_fields[fi];
+            const int64_t q0 = (int64_t)fb[f] + delta[f], q1 = (int64_t)fb[f + 1] + delta[f];
+            if (q0 < 0 || q1 > nnz) continue;
+            int64_t q = q0 + threadIdx.x;
+            for (; q + (kMarkUnroll - 1) * kMarkThreads < q1; q += kMarkUnroll * kMarkThreads) {
+                uint32_t k[kMarkUnroll];
+#pragma unroll
+                for (int j = 0; j < kMarkUnroll; ++j) k[j] = keys[q + j * kMarkThreads] - it.key_lo;   // loads in flight together
+#pragma unroll
+                for (int j = 0; j < kMarkUnroll; ++j)
+                    if (k[j] < span) {
+                        const uint32_t bit = 1u << (k[j] & 31);
+                        if (!(s_bits[k[j] >> 5] & bit)) atomicOr(&s_bits[k[j] >> 5], bit);
+                    }
+            }
+            for (; q < q1; q += kMarkThreads) {
+                const uint32_t k0 = keys[q] - it.key_lo;
+                if (k0 < span) {
+                    const uint32_t bit = 1u << (k0 & 31);
+                    if (!(s_bits[k0 >> 5] & bit)) atomicOr(&s_bits[k0 >> 5], bit);
+                }
+            }
+        }
+    }
+    __syncthreads();
+    uint4* dst = reinterpret_cast<uint4*>(bitmap + (size_t)pm[it.pack].first_tile * kTileWords + it.key_lo / 32);
+    const uint4* src = reinterpret_cast<const uint4*>(s_bits);
+    for (int w = threadIdx.x; w < it.n_words / 4; w += kMarkThreads) dst[w] = src[w];
 }
 
 // ---------------------------------------------------------------------------
@@ -342,7 +367,6 @@ pk_tiles_kernel(const uint4* __restrict__ bitmap4, uint64_t* tile_desc, int n_ti
         if (c != 0) {
             const int start = st[p].start;
             uint32_t* uq = unique + start;
-            int32_t* cn = cnt + start + p;
             const uint32_t key0 = ((uint32_t)(tile - first) * NT + threadIdx.x) * 256u;
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
@@ -351,7 +375,6 @@ pk_tiles_kernel(const uint4* __restrict__ bitmap4, uint64_t* tile_desc, int n_ti
                     const int bit = __ffs(x) - 1;
                     x &= x - 1;
                     uq[pre] = key0 + i * 32 + bit;
-                    cn[pre] = 0;
                     ++pre;
                 }
             }
@@ -359,39 +382,33 @@ pk_tiles_kernel(const uint4* __restrict__ bitmap4, uint64_t* tile_desc, int n_ti
     }
 }
 
-// inverse[q] = number of distinct keys below key[q]; occurrences counted per
-// distinct key.  Repeats inside a block's 1024 occurrences are merged in LDS
-// first, so a hot key costs one global atomic per block, not one per occurrence.
+// inverse[q] = number of distinct keys below key[q]: the rank sample of the key's
+// 256-bit block plus the set bits before it inside the block.
 template <int KT>
 __global__ void __launch_bounds__(NT)
 pk_inverse_kernel(const PackMeta* __restrict__ pm, const PackState* __restrict__ st,
                   const uint32_t* __restrict__ keys, const uint4* __restrict__ bitmap4,
-                  const int32_t* __restrict__ rank, int32_t* __restrict__ inverse,
-                  int32_t* __restrict__ occ_slot, int32_t* cnt)
+                  const int32_t* __restrict__ rank, int32_t* __restrict__ inverse)
 {
-    __shared__ uint32_t s_key[(2 * KT)];
-    __shared__ int32_t s_cnt[(2 * KT)];
     const int p = blockIdx.y;
     const int n = st[p].nnz, start = st[p].start;
     const size_t rb = (size_t)pm[p].first_tile * NT;          // rank blocks before this pack
     const uint4* bm = bitmap4 + 2 * rb;
     const int32_t* rk = rank + rb;
-    int32_t* cn = cnt + start + p;
     const int n_tiles = (n + KT - 1) / KT;
     for (XcdTiles it(n_tiles); it.valid(); it.next()) {
-        const int tile = it.tile;
-        __syncthreads();
-        for (int s = threadIdx.x; s < (2 * KT); s += NT) { s_key[s] = 0xFFFFFFFFu; s_cnt[s] = 0; }
-        __syncthreads();
-        int r_[KT / NT], h_[KT / NT], l_[KT / NT];
+        uint32_t key[KT / NT];
 #pragma unroll
         for (int k = 0; k < KT / NT; ++k) {
-            const int q = tile * KT + k * NT + threadIdx.x;
-            r_[k] = -1; h_[k] = 0; l_[k] = 0;
+            const int q = it.tile * KT + k * NT + threadIdx.x;
+            key[k] = q < n ? keys[start + q] : 0;
+        }
+#pragma unroll
+        for (int k = 0; k < KT / NT; ++k) {
+            const int q = it.tile * KT + k * NT + threadIdx.x;
             if (q < n) {
-                const uint32_t key = keys[start + q];
-                const uint32_t blk = key >> 8;
-                const int wi = (key >> 5) & 7;
+                const uint32_t blk = key[k] >> 8;
+                const int wi = (key[k] >> 5) & 7;
                 const uint4 a = bm[2 * (size_t)blk], b = bm[2 * (size_t)blk + 1];
                 const uint32_t w[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
                 int r = rk[blk];
@@ -401,31 +418,85 @@ pk_inverse_kernel(const PackMeta* __restrict__ pm, const PackState* __restrict__
                     if (i < wi) r += __popc(w[i]);
                     if (i == wi) cur = w[i];
                 }
-                r += __popc(cur & ((1u << (key & 31)) - 1u));
-                uint32_t h = hash_slot<2 * KT>((uint64_t)(uint32_t)r);
-                while (true) {
-                    const uint32_t old = atomicCAS(&s_key[h], 0xFFFFFFFFu, (uint32_t)r);
-                    if (old == 0xFFFFFFFFu || old == (uint32_t)r) break;
-                    h = (h + 1) & ((2 * KT) - 1);
-                }
-                r_[k] = r; h_[k] = (int)h; l_[k] = atomicAdd(&s_cnt[h], 1);
-            }
-        }
-        __syncthreads();
-        for (int s = threadIdx.x; s < (2 * KT); s += NT) {
-            const uint32_t r = s_key[s];
-            if (r != 0xFFFFFFFFu) s_cnt[s] = atomicAdd(&cn[r], s_cnt[s]);
-        }
-        __syncthreads();
-#pragma unroll
-        for (int k = 0; k < KT / NT; ++k) {
-            const int q = tile * KT + k * NT + threadIdx.x;
-            if (r_[k] >= 0) {
-                inverse[start + q] = r_[k];
-                occ_slot[start + q] = s_cnt[h_[k]] + l_[k];
+                r += __popc(cur & ((1u << (key[k] & 31)) - 1u));
+                inverse[start + q] = r;
             }
         }
     }
+}
+
+// number of distinct keys of the pack below `key` (key may be absent, or one past the last row)
+__device__ __forceinline__ int rank_of_key(const uint4* __restrict__ bm, const int32_t* __restrict__ rk,
+                                           uint64_t key64, uint64_t key_end, int n_unique)
+{
+    if (key64 >= key_end) return n_unique;
+    const uint32_t key = (uint32_t)key64;
+    const uint32_t blk = key >> 8;
+    const int wi = (key >> 5) & 7;
+    const uint4 a = bm[2 * (size_t)blk], b = bm[2 * (size_t)blk + 1];
+    const uint32_t w[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+    int r = rk[blk];
+    uint32_t cur = 0;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        if (i < wi) r += __popc(w[i]);
+        if (i == wi) cur = w[i];
+    }
+    return r + __popc(cur & ((1u << (key & 31)) - 1u));
+}
+
+// Occurrences per distinct key, and for each occurrence its slot inside its
+// key's segment -- again without global atomics.  A table's distinct keys are a
+// contiguous range of ranks; a block takes one table and kCountCap of its ranks,
+// counts them in LDS over the occurrences of the fields that read the table, and
+// stores the counts with plain writes.  (Work items exist for every chunk the
+// table's row count allows; those beyond the batch's distinct keys exit at once.)
+__global__ void __launch_bounds__(kMarkThreads)
+pk_count_kernel(const int32_t* __restrict__ item_table, const int32_t* __restrict__ item_chunk,
+                const TableMeta* __restrict__ tmeta, const int32_t* __restrict__ table_fields,
+                const PackMeta* __restrict__ pm, const PackState* __restrict__ st,
+                const int32_t* __restrict__ fb, const int32_t* __restrict__ delta,
+                const uint4* __restrict__ bitmap4, const int32_t* __restrict__ rank,
+                const int32_t* __restrict__ inverse, int32_t* __restrict__ occ_slot, int32_t* __restrict__ cnt,
+                int64_t nnz)
+{
+    __shared__ int32_t s_cnt[kCountCap];
+    if (st[0].error) return;
+    const TableMeta tm = tmeta[item_table[blockIdx.x]];
+    const PackMeta k = pm[tm.pack];
+    const PackState ps = st[tm.pack];
+    const size_t rb = (size_t)k.first_tile * NT;
+    const uint4* bm = bitmap4 + 2 * rb;
+    const int32_t* rk = rank + rb;
+    const uint64_t key_end = (uint64_t)k.n_tiles * (uint64_t)(kTileWords * 32);    // keys the bitmap covers
+    const int r_lo = rank_of_key(bm, rk, tm.key_lo, key_end, ps.n_unique);
+    const int r_hi = rank_of_key(bm, rk, (uint64_t)tm.key_lo + tm.rows, key_end, ps.n_unique);
+    const int c0 = r_lo + item_chunk[blockIdx.x] * kCountCap;
+    if (c0 >= r_hi) return;
+    const uint32_t width = (uint32_t)min(kCountCap, r_hi - c0);
+    for (int i = threadIdx.x; i < (int)width; i += kMarkThreads) s_cnt[i] = 0;
+    __syncthreads();
+    for (int fi = tm.field_begin; fi < tm.field_end; ++fi) {
+        const int f = table_fields[fi];
+        const int64_t q0 = (int64_t)fb[f] + delta[f], q1 = (int64_t)fb[f + 1] + delta[f];
+        if (q0 < 0 || q1 > nnz) continue;
+        int64_t q = q0 + threadIdx.x;
+        for (; q + (kMarkUnroll - 1) * kMarkThreads < q1; q += kMarkUnroll * kMarkThreads) {
+            uint32_t r[kMarkUnroll];
+#pragma unroll
+            for (int j = 0; j < kMarkUnroll; ++j) r[j] = (uint32_t)(inverse[q + j * kMarkThreads] - c0);
+#pragma unroll
+            for (int j = 0; j < kMarkUnroll; ++j)
+                if (r[j] < width) occ_slot[q + j * kMarkThreads] = atomicAdd(&s_cnt[r[j]], 1);
+        }
+        for (; q < q1; q += kMarkThreads) {
+            const uint32_t r0 = (uint32_t)(inverse[q] - c0);
+            if (r0 < width) occ_slot[q] = atomicAdd(&s_cnt[r0], 1);
+        }
+    }
+    __syncthreads();
+    int32_t* cn = cnt + ps.start + tm.pack;
+    for (int i = threadIdx.x; i < (int)width; i += kMarkThreads) cn[c0 + i] = s_cnt[i];
 }
 
 // Exclusive scan of the occurrence counts of a pack's distinct keys, in place
@@ -1023,6 +1094,12 @@ struct DeviceState {
     FieldMeta* fmeta = nullptr;
     PackMeta* pmeta = nullptr;
     int32_t* slot_field = nullptr;
+    MarkItem* mark_items = nullptr;
+    int32_t* mark_fields = nullptr;
+    TableMeta* table_meta = nullptr;
+    int32_t* table_fields = nullptr;
+    int32_t* count_item_table = nullptr;
+    int32_t* count_item_chunk = nullptr;
     std::mutex mu;
     // Side streams: packs (and the pooling of a pack vs the dedup chain) are independent
     // pieces of memory-bound work; running them side by side hides launch gaps and
@@ -1079,12 +1156,34 @@ pk_status ensure_device_state(const pk_plan* cplan, DeviceState** out)
     const size_t b_f = (F * sizeof(FieldMeta) + 255) / 256 * 256;
     const size_t b_p = (P * sizeof(PackMeta) + 255) / 256 * 256;
     const size_t b_s = (F * 4 + 255) / 256 * 256;
-    e = hipMalloc(&ds->blob, b_f + b_p + b_s);
+    const size_t b_i = (plan->mark_items.size() * sizeof(MarkItem) + 255) / 256 * 256;
+    const size_t b_m = (plan->mark_fields.size() * 4 + 255) / 256 * 256;
+    const size_t b_t = (plan->table_meta.size() * sizeof(TableMeta) + 255) / 256 * 256;
+    const size_t b_tf = (plan->table_fields.size() * 4 + 255) / 256 * 256;
+    const size_t b_ci = (plan->count_item_table.size() * 4 + 255) / 256 * 256;
+    e = hipMalloc(&ds->blob, b_f + b_p + b_s + b_i + b_m + b_t + b_tf + 2 * b_ci);
     if (e != hipSuccess) { delete ds; return fail(PK_EHIP, hip_msg("hipMalloc(plan metadata)", e)); }
     ds->fmeta = reinterpret_cast<FieldMeta*>(ds->blob);
     ds->pmeta = reinterpret_cast<PackMeta*>(static_cast<char*>(ds->blob) + b_f);
     ds->slot_field = reinterpret_cast<int32_t*>(static_cast<char*>(ds->blob) + b_f + b_p);
+    ds->mark_items = reinterpret_cast<MarkItem*>(static_cast<char*>(ds->blob) + b_f + b_p + b_s);
+    ds->mark_fields = reinterpret_cast<int32_t*>(static_cast<char*>(ds->blob) + b_f + b_p + b_s + b_i);
+    {
+        char* at = static_cast<char*>(ds->blob) + b_f + b_p + b_s + b_i + b_m;
+        ds->table_meta = reinterpret_cast<TableMeta*>(at); at += b_t;
+        ds->table_fields = reinterpret_cast<int32_t*>(at); at += b_tf;
+        ds->count_item_table = reinterpret_cast<int32_t*>(at); at += b_ci;
+        ds->count_item_chunk = reinterpret_cast<int32_t*>(at);
+    }
     e = hipMemcpy(ds->fmeta, fm.data(), F * sizeof(FieldMeta), hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = hipMemcpy(ds->table_meta, plan->table_meta.data(), plan->table_meta.size() * sizeof(TableMeta), hipMemcpyHostToDevice);
+    if (e == hipSuccess && !plan->table_fields.empty()) e = hipMemcpy(ds->table_fields, plan->table_fields.data(), plan->table_fields.size() * 4, hipMemcpyHostToDevice);
+    if (e == hipSuccess && !plan->count_item_table.empty()) {
+        e = hipMemcpy(ds->count_item_table, plan->count_item_table.data(), plan->count_item_table.size() * 4, hipMemcpyHostToDevice);
+        if (e == hipSuccess) e = hipMemcpy(ds->count_item_chunk, plan->count_item_chunk.data(), plan->count_item_chunk.size() * 4, hipMemcpyHostToDevice);
+    }
+    if (e == hipSuccess) e = hipMemcpy(ds->mark_items, plan->mark_items.data(), plan->mark_items.size() * sizeof(MarkItem), hipMemcpyHostToDevice);
+    if (e == hipSuccess && !plan->mark_fields.empty()) e = hipMemcpy(ds->mark_fields, plan->mark_fields.data(), plan->mark_fields.size() * 4, hipMemcpyHostToDevice);
     if (e == hipSuccess) e = hipMemcpy(ds->pmeta, pmv.data(), P * sizeof(PackMeta), hipMemcpyHostToDevice);
     if (e == hipSuccess) e = hipMemcpy(ds->slot_field, plan->slot_field.data(), F * 4, hipMemcpyHostToDevice);
     if (e != hipSuccess) { (void)hipFree(ds->blob); delete ds; return fail(PK_EHIP, hip_msg("hipMemcpy(plan metadata)", e)); }
@@ -1322,19 +1421,19 @@ pk_status pk_forward(const pk_plan* plan, void* const* W, const int64_t* ids, co
 
     const unsigned clear_blocks = blocks_for(n_clear4, 1024 * 4, 1024);
     PK_LAUNCH("pk_setup", pk_setup_kernel, dim3(1 + clear_blocks), dim3(1024), 0, offsets, B, F, P, nnz, ds->pmeta,
-              ds->slot_field, st, fb, delta, slot_start, packed_offsets, reinterpret_cast<uint4*>(bitmap), n_clear4);
+              ds->slot_field, st, fb, delta, slot_start, packed_offsets, reinterpret_cast<uint4*>(tile_desc), n_clear4);
 
-    const int use_lds = (F + 1) * 4 <= 32 * 1024;
     const int kt = nnz < (1 << 20) ? 256 : 1024;      // occurrences per tile of the keys / inverse kernels
+    const int use_lds = (F + 1) * 4 <= 32 * 1024;
     const int64_t key_blocks = std::max<int64_t>((nnz + kt - 1) / kt, ((int64_t)F * B + NT * 4 - 1) / (NT * 4));
     const dim3 key_grid((blocks_for(key_blocks, 1, 256 * 32) + 7u) & ~7u);
     const size_t key_lds = use_lds ? (size_t)(F + 1) * 4 : 0;
     if (kt == 256)
         PK_LAUNCH("pk_keys", pk_keys_kernel<256>, key_grid, dim3(NT), key_lds, ids, offsets, B, F, nnz, ds->fmeta,
-                  ds->pmeta, st, fb, delta, slot_start, keys, bitmap, packed_offsets, use_lds);
+                  ds->pmeta, st, fb, delta, slot_start, keys, packed_offsets, use_lds);
     else
         PK_LAUNCH("pk_keys", pk_keys_kernel<1024>, key_grid, dim3(NT), key_lds, ids, offsets, B, F, nnz, ds->fmeta,
-                  ds->pmeta, st, fb, delta, slot_start, keys, bitmap, packed_offsets, use_lds);
+                  ds->pmeta, st, fb, delta, slot_start, keys, packed_offsets, use_lds);
 
     // pooling needs the keys only: it runs beside the rest of the dedup chain
     const bool overlap = ds->overlap && !ds->prof_on && (P > 1 || nnz >= (1 << 20));   // fork+join cost a few us
@@ -1351,15 +1450,21 @@ pk_status pk_forward(const pk_plan* plan, void* const* W, const int64_t* ids, co
         if (rc != PK_OK) return rc;
     }
 
+    PK_LAUNCH("pk_mark", pk_mark_kernel, dim3((unsigned)plan->mark_items.size()), dim3(kMarkThreads), 0, ds->mark_items,
+              ds->mark_fields, ds->pmeta, st, fb, delta, keys, bitmap, nnz);
     PK_LAUNCH("pk_tiles", pk_tiles_kernel, dim3(blocks_for(n_tiles, 1, 1024)), dim3(NT), 0,
               reinterpret_cast<const uint4*>(bitmap), tile_desc, (int)n_tiles, ds->pmeta, st, P, rank, unique, cnt);
     const unsigned xq = (blocks_for(nnz, kt, 256 * 16) + 7u) & ~7u;
     if (kt == 256)
         PK_LAUNCH("pk_inverse", pk_inverse_kernel<256>, dim3(xq, P), dim3(NT), 0, ds->pmeta, st, keys,
-                  reinterpret_cast<const uint4*>(bitmap), rank, inverse, occ_slot, cnt);
+                  reinterpret_cast<const uint4*>(bitmap), rank, inverse);
     else
         PK_LAUNCH("pk_inverse", pk_inverse_kernel<1024>, dim3(xq, P), dim3(NT), 0, ds->pmeta, st, keys,
-                  reinterpret_cast<const uint4*>(bitmap), rank, inverse, occ_slot, cnt);
+                  reinterpret_cast<const uint4*>(bitmap), rank, inverse);
+    if (!plan->count_item_table.empty())
+        PK_LAUNCH("pk_count", pk_count_kernel, dim3((unsigned)plan->count_item_table.size()), dim3(kMarkThreads), 0,
+                  ds->count_item_table, ds->count_item_chunk, ds->table_meta, ds->table_fields, ds->pmeta, st, fb, delta,
+                  reinterpret_cast<const uint4*>(bitmap), rank, inverse, occ_slot, cnt, nnz);
     PK_LAUNCH("pk_segs", pk_segs_kernel, dim3(blocks_for(nnz, kSegTile, std::max(1, 1024 / P)), P), dim3(NT), 0,
               ds->pmeta, st, cnt, seg_desc, hot, ws.at<int32_t>(L.hot_of), ghot, L.dmax, tile_first, L.pos_tile);
     int64_t max_bags = 0;

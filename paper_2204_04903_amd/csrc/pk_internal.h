@@ -18,6 +18,8 @@ constexpr int kRankWords = 8;      // one rank sample per 8 words (256 keys)
 constexpr int kSegTile   = 2048;   // occurrence counts scanned per ticket (256 threads x 8)
 constexpr int kPosTileMax = 512;   // occurrences handled per block iteration in the backward pass (upper end)
 constexpr int kPosTileMin = 64;
+constexpr int kMarkWords = 16384;  // bitmap words (512K keys, 64 KB of LDS) owned by one block of the mark kernel
+constexpr int kCountCap  = 16384;  // distinct keys counted in LDS by one block of the count kernel
 constexpr size_t kAlign = 256;
 
 // Per field, device side (indexed by field index).
@@ -40,6 +42,27 @@ struct PackMeta {
     int32_t first_tile;      // first bitmap tile (of kTileWords words) of the pack
     int32_t n_tiles;
     int32_t pad;
+};
+
+// A slice of a pack's key space (kMarkWords bitmap words) and the fields whose
+// tables overlap it; static, device side.
+struct MarkItem {
+    int32_t pack;
+    uint32_t key_lo;         // first key of the slice (multiple of 32)
+    int32_t n_words;         // bitmap words of the slice
+    int32_t field_begin;     // range in the item field list
+    int32_t field_end;
+    int32_t pad[3];
+};
+
+// A table and the fields that read it; static, device side.
+struct TableMeta {
+    int32_t pack;
+    uint32_t key_lo;         // first key of the table inside its pack
+    uint32_t rows;
+    int32_t field_begin;     // range in the table field list
+    int32_t field_end;
+    int32_t pad[3];
 };
 
 // Per pack, device side, rewritten by every forward call.
@@ -66,7 +89,7 @@ struct Pack {
 struct Layout {
     size_t state, fb, delta, slot_start, packed_offsets, keys, inverse, occ_slot, seg_ent, hot_of, tile_first,
            unique, cnt, hot, ghot, bitmap, tile_desc, seg_desc, rank, total;
-    size_t clear_bytes;          // bitmap + scan descriptors, contiguous from `bitmap`
+    size_t clear_bytes;          // scan descriptors, contiguous from `tile_desc`
     int64_t n_tiles_total;
     int32_t dmax;
     int32_t pos_tile;            // occurrences per backward tile for this nnz
@@ -84,6 +107,11 @@ struct pk_plan {
     std::vector<int32_t> field_pack, field_slot;
     std::vector<int64_t> field_col;
     std::vector<int32_t> slot_field;      // fields in (pack, slot) order
+    std::vector<pk::MarkItem> mark_items;
+    std::vector<int32_t> mark_fields;     // per item: the fields whose table overlaps the slice
+    std::vector<pk::TableMeta> table_meta;
+    std::vector<int32_t> table_fields;    // per table: the fields that read it
+    std::vector<int32_t> count_item_table, count_item_chunk;   // (table, chunk of kCountCap distinct keys)
     int64_t out_dim = 0;
     bool any_mean = false;
     int32_t n_tiles_total = 0;

@@ -67,7 +67,7 @@ Layout make_layout(const pk_plan* plan, int32_t B, int64_t nnz)
     L.bitmap         = take((size_t)plan->n_tiles_total * kTileWords * 4);
     L.tile_desc      = take((size_t)plan->n_tiles_total * 8);
     L.seg_desc       = take((n / kSegTile + P + 1) * 8);
-    L.clear_bytes    = off - L.bitmap;
+    L.clear_bytes    = off - L.tile_desc;     // scan descriptors only: the bitmap is fully rewritten every call
     L.rank           = take((size_t)plan->n_tiles_total * (kTileWords / kRankWords) * 4);
     L.total = off;
     return L;
@@ -167,6 +167,41 @@ pk_status pk_plan_create(const pk_table_desc* tables, int32_t n_tables, const pk
         tile0 += pk_.n_tiles;
     }
     pl->n_tiles_total = (int32_t)tile0;
+    // tables with their fields, and the (table, chunk) work list of the count kernel
+    for (int32_t t = 0; t < n_tables; ++t) {
+        TableMeta tm{};
+        tm.pack = pl->table_pack[t];
+        tm.key_lo = (uint32_t)pl->table_base[t];
+        tm.rows = (uint32_t)tables[t].rows;
+        tm.field_begin = (int32_t)pl->table_fields.size();
+        for (int32_t f = 0; f < n_fields; ++f)
+            if (fields[f].table == t) pl->table_fields.push_back(f);
+        tm.field_end = (int32_t)pl->table_fields.size();
+        pl->table_meta.push_back(tm);
+        if (tm.field_end == tm.field_begin) continue;          // nobody reads this table
+        const int64_t chunks = (tables[t].rows + kCountCap - 1) / kCountCap;
+        for (int64_t c = 0; c < chunks; ++c) { pl->count_item_table.push_back(t); pl->count_item_chunk.push_back((int32_t)c); }
+    }
+    // slices of every pack's key space for the mark kernel
+    for (size_t p = 0; p < pl->packs.size(); ++p) {
+        const Pack& k = pl->packs[p];
+        const int64_t words = (int64_t)k.n_tiles * kTileWords;
+        for (int64_t w0 = 0; w0 < words; w0 += kMarkWords) {
+            MarkItem it{};
+            it.pack = (int32_t)p;
+            it.key_lo = (uint32_t)(w0 * 32);
+            it.n_words = (int32_t)std::min<int64_t>(kMarkWords, words - w0);
+            it.field_begin = (int32_t)pl->mark_fields.size();
+            const int64_t lo = w0 * 32, hi = lo + (int64_t)it.n_words * 32;
+            for (int32_t f : k.fields) {
+                const int32_t t = fields[f].table;
+                const int64_t t_lo = pl->table_base[t], t_hi = t_lo + tables[t].rows;
+                if (t_lo < hi && t_hi > lo) pl->mark_fields.push_back(f);
+            }
+            it.field_end = (int32_t)pl->mark_fields.size();
+            pl->mark_items.push_back(it);
+        }
+    }
     for (auto& pk_ : pl->packs) pl->dmax = std::max(pl->dmax, pk_.dim);
     *out = pl;
     return PK_OK;
