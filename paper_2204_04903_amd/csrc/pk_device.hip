@@ -928,6 +928,7 @@ pk_adagrad_kernel(WT* W, float* A, const PackState* __restrict__ st, int p,
     __shared__ int s_nwarm, s_nhot;
     __shared__ int s_warm[kPosTileMax / (kColdMax + 1) + 2];
     __shared__ int s_hot[kPosTileMax / (kWarmMax + 1) + 4];
+    __shared__ double s_red[NT / 64][LPR][NCH][VEC];   // per-wavefront partial sums of a hot piece
     __shared__ int s_seg[kPosTileMax + 2];          // segment offsets of the tile's keys
     __shared__ uint32_t s_row[kPosTileMax + 1];     // their table rows
     __shared__ uint32_t s_addr[kPosTileMax + kWarmMax];   // decoded positions of the tile and its tail
@@ -1026,29 +1027,41 @@ pk_adagrad_kernel(WT* W, float* A, const PackState* __restrict__ st, int p,
             wave_group_sum<VEC, LPR, NCH>(acc);
             if (gw == 0) row_step<WT, VEC, LPR, NCH>(W, A, row, D, li, acc, w, a, lr, eps);
         }
-        // hot keys: this tile's piece, 256 positions per wavefront, added to the key's partial sums
+        // hot keys: this tile's piece is split over the block's wavefronts, reduced in LDS and
+        // added once to the key's partial sums
         const int n_hot_here = s_nhot;
         for (int i = 0; i < n_hot_here; ++i) {
             const int k = s_hot[i];
-            const int u = u_lo + k;
             const int a0 = max(s_seg[k], t0), b0 = min(s_seg[k + 1], t1);
-            double* prow = gh + (size_t)hot_of[u] * D;   // the key's row of partial sums
-            for (int c0 = a0 + wv * hot_chunk; c0 < b0; c0 += (NT / 64) * hot_chunk) {
-                const int c1 = min(c0 + hot_chunk, b0);
-                double acc[NCH][VEC];
+            const int share = (b0 - a0 + NT / 64 - 1) / (NT / 64);
+            const int c0 = a0 + wv * share, c1 = min(c0 + share, b0);
+            double acc[NCH][VEC];
+#pragma unroll
+            for (int c = 0; c < NCH; ++c)
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) acc[c][v] = 0.0;
+            accum_range<VEC, LPR, NCH>(acc, g, D, li, c0 + gw, c1, GPW);
+            wave_group_sum<VEC, LPR, NCH>(acc);
+            __syncthreads();                               // s_red of the previous piece is consumed
+            if (gw == 0) {
 #pragma unroll
                 for (int c = 0; c < NCH; ++c)
 #pragma unroll
-                    for (int v = 0; v < VEC; ++v) acc[c][v] = 0.0;
-                accum_range<VEC, LPR, NCH>(acc, g, D, li, c0 + gw, c1, GPW);
-                wave_group_sum<VEC, LPR, NCH>(acc);
-                if (gw == 0) {
+                    for (int v = 0; v < VEC; ++v) s_red[wv][li][c][v] = acc[c][v];
+            }
+            __syncthreads();
+            if (wv == 0 && gw == 0) {
+                double* prow = gh + (size_t)hot_of[u_lo + k] * D;   // the key's row of partial sums
 #pragma unroll
-                    for (int c = 0; c < NCH; ++c) {
-                        const int d0 = (c * LPR + li) * VEC;
-                        if (d0 < D) {
+                for (int c = 0; c < NCH; ++c) {
+                    const int d0 = (c * LPR + li) * VEC;
+                    if (d0 < D) {
 #pragma unroll
-                            for (int v = 0; v < VEC; ++v) atomicAdd(prow + d0 + v, acc[c][v]);
+                        for (int v = 0; v < VEC; ++v) {
+                            double t = 0.0;
+#pragma unroll
+                            for (int w2 = 0; w2 < NT / 64; ++w2) t += s_red[w2][li][c][v];
+                            atomicAdd(prow + d0 + v, t);
                         }
                     }
                 }
