@@ -26,18 +26,20 @@ def algorithmic_bytes(info, mean_pack):
     (nnz, U, k*B bags, dim D, element size sw, bitmap bytes bm).  Rows are
     counted once per DISTINCT key: removing repeats is the method."""
     n, U, bags, D, sw, bm = info["nnz"], info["U"], info["bags"], info["D"], info["sw"], info["bitmap_bytes"]
-    sc = 4 * (bags + 1) if mean_pack else 0       # bag lengths for the 1/L of mean pooling
     return {
-        "pk_keys": 8 * n + 4 * n + 4 * bags + 4 * bags,
+        "pk_keys": 8 * n + 4 * n + 4 * n + sc_occ(n, mean_pack) + 4 * bags + 4 * bags,
         "pk_pool": 4 * n + 4 * (bags + 1) + sw * D * U + 4 * D * bags,
-        "pk_tiles": bm + bm // 8 + 8 * U,
-        "pk_inverse": 8 * n + min(bm + bm // 8, 36 * n),
         "pk_mark": 4 * n + bm,
-        "pk_count": 8 * n + 4 * U,
-        "pk_segs": 8 * U,
-        "pk_scatter": 12 * n + 4 * U + 4 * bags,
-        "pk_adagrad": 4 * (U + 1) + 4 * U + 4 * n + sc + 4 * D * bags + (2 * sw + 8) * D * U,
+        "pk_tiles": bm + bm // 8 + 4 * U,
+        "pk_inverse": 8 * n + min(bm + bm // 8, 36 * n),
+        "pk_sort": 2 * (4 * n) + 4 * n + 2 * sc_occ(n, mean_pack) + 4 * n + 4 * U,
+        "pk_adagrad": 4 * (U + 1) + 4 * U + 4 * n + sc_occ(n, mean_pack) + 4 * D * bags + (2 * sw + 8) * D * U,
     }
+
+
+def sc_occ(n, mean_pack):
+    """bytes of the per-occurrence 1/L scales (only packs with mean pooling carry them)"""
+    return 4 * n if mean_pack else 0
 
 
 def step_model_bytes(info):

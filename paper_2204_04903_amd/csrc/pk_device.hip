@@ -158,111 +158,126 @@ struct XcdTiles {
 };
 
 // ---------------------------------------------------------------------------
-// setup: block 0 derives the per-field and per-pack positions; the other
-// blocks clear the scan descriptors.
+// H1: packed keys (Sec. III-B: one packed ID tensor per pack), packed bag
+// offsets, and for every occurrence the place of its bag's gradient chunk.
+// A block takes BT consecutive bags (field-major, so their IDs are contiguous),
+// keeps their offsets in LDS and finds each occurrence's bag there.
+//
+// Where a field's occurrences go in the packed order follows from the field
+// boundaries alone, so every block derives it for itself (a scan over the
+// fields in (pack, slot) order) instead of waiting for a set-up launch; block 0
+// also stores it for the later kernels.  All blocks share the clearing of the
+// scan descriptors.
 // ---------------------------------------------------------------------------
-__global__ void __launch_bounds__(1024)
-pk_setup_kernel(const int32_t* __restrict__ offsets, int B, int F, int P, int64_t nnz,
-                const PackMeta* __restrict__ pm, const int32_t* __restrict__ slot_field,
-                PackState* st, int32_t* fb, int32_t* delta, int32_t* slot_start, int32_t* packed_offsets,
-                uint4* clear4, int64_t n_clear4)
-{
-    if (blockIdx.x != 0) {
-        const uint4 z = make_uint4(0, 0, 0, 0);
-        const int64_t stride = (int64_t)(gridDim.x - 1) * blockDim.x;
-        for (int64_t i = (int64_t)(blockIdx.x - 1) * blockDim.x + threadIdx.x; i < n_clear4; i += stride)
-            clear4[i] = z;
-        return;
-    }
-    __shared__ int bad;
-    const int tid = threadIdx.x;
-    if (tid == 0) bad = 0;
-    __syncthreads();
-    for (int f = tid; f <= F; f += 1024) fb[f] = offsets[(int64_t)f * B];
-    __syncthreads();
-    for (int f = tid; f < F; f += 1024)
-        if (fb[f + 1] < fb[f]) bad = 1;
-    if (tid == 0 && (fb[0] != 0 || (int64_t)fb[F] != nnz)) bad = 1;
-    __syncthreads();
-    const int is_bad = bad;
-    int start = 0;
-    for (int p = 0; p < P; ++p) {
-        const int k = pm[p].n_fields, fs = pm[p].first_slot;
-        int carry = 0;
-        for (int base = 0; base < k; base += 1024) {
-            const int j = base + tid;
-            int len = 0, f = 0;
-            if (j < k) {
-                f = slot_field[fs + j];
-                len = is_bad ? 0 : fb[f + 1] - fb[f];
-            }
-            int tot;
-            const int ex = block_excl_scan<1024>(len, &tot);
-            if (j < k) {
-                slot_start[fs + p + j] = carry + ex;
-                delta[f] = start + carry + ex - fb[f];
-            }
-            carry += tot;
-        }
-        if (tid == 0) {
-            slot_start[fs + p + k] = carry;
-            PackState s;
-            s.nnz = carry; s.start = start; s.n_unique = 0; s.n_hot = 0; s.error = (p == 0) ? is_bad : 0;
-            s.pad[0] = s.pad[1] = s.pad[2] = 0;
-            st[p] = s;
-            packed_offsets[(int64_t)fs * B + p + (int64_t)k * B] = carry;
-        }
-        start += carry;
-    }
-}
-
-// ---------------------------------------------------------------------------
-// H1: packed keys (Sec. III-B: one packed ID tensor per pack) and packed bag
-// offsets.  Pure streaming: 8 bytes in, 4 bytes out per occurrence.
-// ---------------------------------------------------------------------------
-template <int KT>
+template <int BT>
 __global__ void __launch_bounds__(NT)
-pk_keys_kernel(const int64_t* __restrict__ ids, const int32_t* __restrict__ offsets, int B, int F, int64_t nnz,
-               const FieldMeta* __restrict__ fmeta, const PackMeta* __restrict__ pm, const PackState* __restrict__ st,
-               const int32_t* __restrict__ fb, const int32_t* __restrict__ delta,
-               const int32_t* __restrict__ slot_start, uint32_t* __restrict__ keys,
-               int32_t* __restrict__ packed_offsets, int use_lds)
+pk_keys_kernel(const int64_t* __restrict__ ids, const int32_t* __restrict__ offsets, int B, int F, int P, int64_t nnz,
+               const FieldMeta* __restrict__ fmeta, const PackMeta* __restrict__ pm,
+               const int32_t* __restrict__ slot_field, PackState* st, int32_t* fb_out, int32_t* delta_out,
+               uint32_t* __restrict__ keys, uint32_t* __restrict__ bagref, float* __restrict__ bagscl,
+               int32_t* __restrict__ packed_offsets, int64_t out_dim, uint4* clear4, int64_t n_clear4)
 {
-    extern __shared__ int32_t s_fb[];
-    if (st[0].error) return;
-    if (use_lds) {
-        for (int f = threadIdx.x; f <= F; f += NT) s_fb[f] = fb[f];
-        __syncthreads();
+    extern __shared__ int32_t s_dyn[];
+    int32_t* s_fb = s_dyn;                    // [F+1] field boundaries in ids
+    int32_t* s_delta = s_dyn + (F + 1);       // [F]   packed position minus position in ids
+    int32_t* s_slotpos = s_delta + F;         // [F+1] packed position of each (pack, slot)
+    __shared__ int s_bad;
+    __shared__ int32_t s_po[BT + 1];
+    __shared__ uint32_t s_base[BT], s_rows[BT], s_ref[BT];
+    __shared__ int32_t s_dl[BT];
+    __shared__ float s_scl[BT];
+    const int tid = threadIdx.x;
+    {
+        const uint4 z = make_uint4(0, 0, 0, 0);
+        const int64_t stride = (int64_t)gridDim.x * NT;
+        for (int64_t i = (int64_t)blockIdx.x * NT + tid; i < n_clear4; i += stride) clear4[i] = z;
     }
-    const int n_tiles = (int)((nnz + KT - 1) / KT);
-    for (XcdTiles it(n_tiles); it.valid(); it.next()) {
-        const int64_t tile = it.tile;
-        int64_t idv[KT / NT];
-#pragma unroll
-        for (int k = 0; k < KT / NT; ++k) {          // all loads of the tile in flight together
-            const int64_t i = tile * KT + k * NT + threadIdx.x;
-            idv[k] = i < nnz ? ids[i] : 0;
+    if (tid == 0) s_bad = 0;
+    for (int f = tid; f <= F; f += NT) s_fb[f] = offsets[(int64_t)f * B];
+    __syncthreads();
+    for (int f = tid; f < F; f += NT)
+        if (s_fb[f + 1] < s_fb[f]) s_bad = 1;
+    if (tid == 0 && (s_fb[0] != 0 || (int64_t)s_fb[F] != nnz)) s_bad = 1;
+    __syncthreads();
+    const int bad = s_bad;
+    int carry = 0;
+    for (int base = 0; base < F; base += NT) {
+        const int i = base + tid;
+        int len = 0, f = 0;
+        if (i < F) {
+            f = slot_field[i];
+            len = bad ? 0 : s_fb[f + 1] - s_fb[f];
         }
+        int tot;
+        const int ex = block_excl_scan<NT>(len, &tot);
+        if (i < F) {
+            s_slotpos[i] = carry + ex;
+            s_delta[f] = carry + ex - s_fb[f];
+        }
+        carry += tot;
+    }
+    if (tid == 0) s_slotpos[F] = carry;
+    __syncthreads();
+    if (blockIdx.x == 0) {
+        for (int f = tid; f <= F; f += NT) fb_out[f] = s_fb[f];
+        for (int f = tid; f < F; f += NT) delta_out[f] = s_delta[f];
+        for (int p = tid; p < P; p += NT) {
+            const PackMeta k = pm[p];
+            const int start = s_slotpos[k.first_slot];
+            PackState s;
+            s.nnz = s_slotpos[k.first_slot + k.n_fields] - start;
+            s.start = start; s.n_unique = 0; s.error = (p == 0) ? bad : 0;
+            s.pad[0] = s.pad[1] = s.pad[2] = s.pad[3] = 0;
+            st[p] = s;
+            packed_offsets[(int64_t)k.first_slot * B + p + (int64_t)k.n_fields * B] = s.nnz;
+        }
+    }
+    if (bad) return;
+    const int64_t n_bags = (int64_t)F * B;
+    const int64_t n_tiles = (n_bags + BT - 1) / BT;
+    for (int64_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+        const int64_t g0 = tile * BT;
+        const int nb = (int)min((int64_t)BT, n_bags - g0);
+        __syncthreads();                               // the previous tile's LDS is consumed
+        for (int t = tid; t <= nb; t += NT) s_po[t] = (int32_t)min((int64_t)max(offsets[g0 + t], 0), nnz);
+        __syncthreads();
+        for (int t = tid; t < nb; t += NT) {
+            const int64_t g = g0 + t;
+            const int f = (int)(g / B);
+            const int b = (int)(g - (int64_t)f * B);
+            const FieldMeta m = fmeta[f];
+            const PackMeta k = pm[m.pack];
+            s_base[t] = m.base_row;
+            s_rows[t] = m.rows;
+            s_dl[t] = s_delta[f];
+            s_ref[t] = (uint32_t)((int64_t)b * out_dim + m.col);
+            const int L = s_po[t + 1] - s_po[t];
+            s_scl[t] = (m.pool == PK_MEAN && L > 0) ? 1.0f / (float)L : 1.0f;
+            packed_offsets[(int64_t)k.first_slot * B + m.pack + (int64_t)m.slot * B + b] =
+                s_po[t] + s_delta[f] - s_slotpos[k.first_slot];
+        }
+        __syncthreads();
+        const int q_lo = s_po[0], q_hi = s_po[nb];
+        for (int i0 = q_lo + tid; i0 < q_hi; i0 += 4 * NT) {
+            int64_t idv[4];
 #pragma unroll
-        for (int k = 0; k < KT / NT; ++k) {
-            const int64_t i = tile * KT + k * NT + threadIdx.x;
-            if (i < nnz) {
-                const int f = (use_lds ? upper_bound_i32(s_fb, F + 1, (int)i) : upper_bound_i32(fb, F + 1, (int)i)) - 1;
-                const FieldMeta m = fmeta[f];
-                const int64_t q = i + delta[f];
-                if ((uint64_t)q < (uint64_t)nnz) keys[q] = m.base_row + fold_id(idv[k], m.rows);
+            for (int k = 0; k < 4; ++k) {              // the loads of four rounds in flight together
+                const int i = i0 + k * NT;
+                idv[k] = i < q_hi ? ids[i] : 0;
+            }
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const int i = i0 + k * NT;
+                if (i >= q_hi) continue;
+                const int t = upper_bound_i32(s_po, nb + 1, i) - 1;
+                if ((unsigned)t >= (unsigned)nb) continue;
+                const int64_t q = (int64_t)i + s_dl[t];
+                if ((uint64_t)q >= (uint64_t)nnz) continue;
+                keys[q] = s_base[t] + fold_id(idv[k], s_rows[t]);
+                bagref[q] = s_ref[t];
+                if (bagscl) bagscl[q] = s_scl[t];
             }
         }
-    }
-    const int64_t stride = (int64_t)gridDim.x * NT;
-    const int64_t n_bags = (int64_t)F * B;
-    for (int64_t g = (int64_t)blockIdx.x * NT + threadIdx.x; g < n_bags; g += stride) {
-        const int f = (int)(g / B);
-        const int b = (int)(g - (int64_t)f * B);
-        const FieldMeta m = fmeta[f];
-        const PackMeta k = pm[m.pack];
-        packed_offsets[(int64_t)k.first_slot * B + m.pack + (int64_t)m.slot * B + b] =
-            slot_start[k.first_slot + m.pack + m.slot] + offsets[g] - fb[f];
     }
 }
 
@@ -445,198 +460,188 @@ __device__ __forceinline__ int rank_of_key(const uint4* __restrict__ bm, const i
     return r + __popc(cur & ((1u << (key & 31)) - 1u));
 }
 
-// Occurrences per distinct key, and for each occurrence its slot inside its
-// key's segment -- again without global atomics.  A table's distinct keys are a
-// contiguous range of ranks; a block takes one table and kCountCap of its ranks,
-// counts them in LDS over the occurrences of the fields that read the table, and
-// stores the counts with plain writes.  (Work items exist for every chunk the
-// table's row count allows; those beyond the batch's distinct keys exit at once.)
-__global__ void __launch_bounds__(kMarkThreads)
-pk_count_kernel(const int32_t* __restrict__ item_table, const int32_t* __restrict__ item_chunk,
-                const TableMeta* __restrict__ tmeta, const int32_t* __restrict__ table_fields,
-                const PackMeta* __restrict__ pm, const PackState* __restrict__ st,
-                const int32_t* __restrict__ fb, const int32_t* __restrict__ delta,
-                const uint4* __restrict__ bitmap4, const int32_t* __restrict__ rank,
-                const int32_t* __restrict__ inverse, int32_t* __restrict__ occ_slot, int32_t* __restrict__ cnt,
-                int64_t nnz)
+// H2, last part: the occurrences grouped by distinct key (a counting sort by
+// rank), the segment offsets, and what the backward pass needs to cut its work
+// by occurrences -- in one kernel and without global atomics.
+//
+// A table's distinct keys are a contiguous range of ranks, and its occurrences
+// are the occurrences of the fields that read it (contiguous in the packed
+// order).  A work item is one table and up to kSortCap of its ranks; which items
+// exist depends on the batch, so every block derives the list for itself from
+// the rank samples.  An item
+//   1. counts the occurrences of each of its ranks in LDS,
+//   2. scans the counts, learns the number of occurrences before it from the
+//      items before it (descriptor look-back), and writes the segment offsets,
+//      for each backward tile the key that holds the tile's first position, and
+//      zeroed partial sums for keys that are long and cross a tile boundary,
+//   3. passes over the occurrences again and stores each one's gradient place
+//      (and mean-pooling scale) at its segment's next free position.
+// Block b takes items b, b+G, ...: an item only waits for lower items, which are
+// in earlier rounds or in lower blocks of this round; G is small enough for all
+// blocks to be resident, so the waits end.
+constexpr int kSortThreads = 1024;
+constexpr int kSortPer = kSortCap / kSortThreads;
+
+__global__ void __launch_bounds__(kSortThreads)
+pk_sort_kernel(const TableMeta* __restrict__ tmeta, const int32_t* __restrict__ table_fields, int T,
+               const PackMeta* __restrict__ pm, PackState* st, int P,
+               const int32_t* __restrict__ fb, const int32_t* __restrict__ delta,
+               const uint4* __restrict__ bitmap4, const int32_t* __restrict__ rank,
+               const int32_t* __restrict__ inverse, const uint32_t* __restrict__ bagref,
+               const float* __restrict__ bagscl, int32_t* __restrict__ seg_all, uint32_t* __restrict__ ent_all,
+               int ent_mult, int32_t* __restrict__ tile_first, int tp, uint64_t* desc, double* __restrict__ ghot, int dmax,
+               int32_t* __restrict__ arrive, int64_t nnz)
 {
-    __shared__ int32_t s_cnt[kCountCap];
+    extern __shared__ int32_t s_dyn[];
+    int32_t* s_rlo = s_dyn;                  // [T]   first rank of each table inside its pack
+    int32_t* s_u = s_dyn + T;                // [T]   distinct keys of each table
+    int32_t* s_first = s_u + T;              // [T+1] first work item of each table
+    __shared__ int32_t s_cnt[kSortCap];
+    __shared__ uint32_t s_base;
+    const int tid = threadIdx.x;
     if (st[0].error) return;
-    const TableMeta tm = tmeta[item_table[blockIdx.x]];
-    const PackMeta k = pm[tm.pack];
-    const PackState ps = st[tm.pack];
-    const size_t rb = (size_t)k.first_tile * NT;
-    const uint4* bm = bitmap4 + 2 * rb;
-    const int32_t* rk = rank + rb;
-    const uint64_t key_end = (uint64_t)k.n_tiles * (uint64_t)(kTileWords * 32);    // keys the bitmap covers
-    const int r_lo = rank_of_key(bm, rk, tm.key_lo, key_end, ps.n_unique);
-    const int r_hi = rank_of_key(bm, rk, (uint64_t)tm.key_lo + tm.rows, key_end, ps.n_unique);
-    const int c0 = r_lo + item_chunk[blockIdx.x] * kCountCap;
-    if (c0 >= r_hi) return;
-    const uint32_t width = (uint32_t)min(kCountCap, r_hi - c0);
-    for (int i = threadIdx.x; i < (int)width; i += kMarkThreads) s_cnt[i] = 0;
-    __syncthreads();
-    for (int fi = tm.field_begin; fi < tm.field_end; ++fi) {
-        const int f = table_fields[fi];
-        const int64_t q0 = (int64_t)fb[f] + delta[f], q1 = (int64_t)fb[f + 1] + delta[f];
-        if (q0 < 0 || q1 > nnz) continue;
-        int64_t q = q0 + threadIdx.x;
-        for (; q + (kMarkUnroll - 1) * kMarkThreads < q1; q += kMarkUnroll * kMarkThreads) {
-            uint32_t r[kMarkUnroll];
-#pragma unroll
-            for (int j = 0; j < kMarkUnroll; ++j) r[j] = (uint32_t)(inverse[q + j * kMarkThreads] - c0);
-#pragma unroll
-            for (int j = 0; j < kMarkUnroll; ++j)
-                if (r[j] < width) occ_slot[q + j * kMarkThreads] = atomicAdd(&s_cnt[r[j]], 1);
+    int carry = 0;
+    for (int base = 0; base < T; base += kSortThreads) {
+        const int t = base + tid;
+        int chunks = 0;
+        if (t < T) {
+            const TableMeta tm = tmeta[t];
+            const PackMeta k = pm[tm.pack];
+            const size_t rb = (size_t)k.first_tile * NT;
+            const uint64_t key_end = (uint64_t)k.n_tiles * (uint64_t)(kTileWords * 32);
+            const int nu = st[tm.pack].n_unique;
+            const int r_lo = rank_of_key(bitmap4 + 2 * rb, rank + rb, tm.key_lo, key_end, nu);
+            const int r_hi = rank_of_key(bitmap4 + 2 * rb, rank + rb, (uint64_t)tm.key_lo + tm.rows, key_end, nu);
+            s_rlo[t] = r_lo;
+            s_u[t] = r_hi - r_lo;
+            chunks = (r_hi - r_lo + kSortCap - 1) / kSortCap;
         }
-        for (; q < q1; q += kMarkThreads) {
-            const uint32_t r0 = (uint32_t)(inverse[q] - c0);
-            if (r0 < width) occ_slot[q] = atomicAdd(&s_cnt[r0], 1);
-        }
+        int tot;
+        const int ex = block_excl_scan<kSortThreads>(chunks, &tot);
+        if (t < T) s_first[t] = carry + ex;
+        carry += tot;
+    }
+    if (tid == 0) s_first[T] = carry;
+    if ((int)blockIdx.x < P && tid == 0) {       // the entry after the last segment of the pack
+        const PackState ps = st[blockIdx.x];
+        seg_all[ps.start + blockIdx.x + ps.n_unique] = ps.nnz;
     }
     __syncthreads();
-    int32_t* cn = cnt + ps.start + tm.pack;
-    for (int i = threadIdx.x; i < (int)width; i += kMarkThreads) cn[c0 + i] = s_cnt[i];
-}
-
-// Exclusive scan of the occurrence counts of a pack's distinct keys, in place
-// (counts -> segment offsets), in one pass.  Keys with more than kWarmMax
-// occurrences are listed (ascending) and get a zeroed row of partial sums.  For
-// the backward pass, tile_first[t] = the key whose segment holds position t*tp.
-__global__ void __launch_bounds__(NT)
-pk_segs_kernel(const PackMeta* __restrict__ pm, PackState* st, int32_t* cnt, uint64_t* seg_desc,
-               int32_t* __restrict__ hot, int32_t* __restrict__ hot_of, double* __restrict__ ghot, int dmax,
-               int32_t* __restrict__ tile_first, int tp)
-{
-    __shared__ uint32_t s_pa, s_pb;
-    __shared__ unsigned long long s_w[NT / 64];
-    const int p = blockIdx.y;
-    const int U = st[p].n_unique, start = st[p].start, D = pm[p].dim;
-    int32_t* cn = cnt + start + p;
-    const size_t hbase = (size_t)(start / (kWarmMax + 1) + p);
-    int32_t* hl = hot + hbase;
-    double* gh = ghot + hbase * dmax;
-    int32_t* tf = tile_first + start / tp + p;
-    uint64_t* desc = seg_desc + start / kSegTile + p;
-    const int n_tiles = (U + kSegTile - 1) / kSegTile;
-    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
-    if (blockIdx.x == 0 && threadIdx.x == 0) {
-        cn[U] = st[p].nnz;
-        if (n_tiles == 0) st[p].n_hot = 0;
-    }
-    // Block b takes tiles b, b+G, ...; all G blocks are resident (G is small), so the
-    // wait for lower tiles ends.
-    for (int tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
-        const int base = tile * kSegTile;
-        unsigned long long mine = 0;                     // low 32: occurrences, high 32: hot keys
-#pragma unroll
-        for (int k = 0; k < kSegTile / NT; ++k) {
-            const int u = base + k * NT + threadIdx.x;
-            const int v = u < U ? cn[u] : 0;
-            mine += (unsigned long long)(uint32_t)v + ((unsigned long long)(v > kWarmMax) << 32);
-        }
-        unsigned long long x = mine;
-#pragma unroll
-        for (int o = 32; o > 0; o >>= 1) x += __shfl_xor(x, o, 64);
-        __syncthreads();                                 // s_w, s_pa, s_pb of the previous round are consumed
-        if (lane == 0) s_w[wv] = x;
+    const int total = s_first[T];
+    for (int item = blockIdx.x; item < total; item += gridDim.x) {
+        const int t = upper_bound_i32(s_first, T + 1, item) - 1;
+        const TableMeta tm = tmeta[t];
+        const int p = tm.pack;
+        const PackMeta k = pm[p];
+        const int n = st[p].nnz, start = st[p].start;
+        const int c0 = s_rlo[t] + (item - s_first[t]) * kSortCap;
+        const uint32_t width = (uint32_t)min(kSortCap, s_rlo[t] + s_u[t] - c0);
+        const int first_item = s_first[k.first_stable];
+        int32_t* seg = seg_all + start + p;
+        uint32_t* ent = ent_all + (size_t)start * ent_mult;
+        const bool wide = k.has_mean != 0;             // entries of this pack carry the 1/L scale
+        const size_t tbase = (size_t)(start / tp + p);
+        int32_t* tf = tile_first + tbase;
+        int32_t* arr = arrive + tbase;
+        double* gh = ghot + tbase * dmax;
+        __syncthreads();                               // the previous item's LDS is consumed
+        for (int i = tid; i < (int)width; i += kSortThreads) s_cnt[i] = 0;
         __syncthreads();
-        unsigned long long tot = 0;
+        for (int fi = tm.field_begin; fi < tm.field_end; ++fi) {
+            const int f = table_fields[fi];
+            const int64_t q0 = (int64_t)fb[f] + delta[f], q1 = (int64_t)fb[f + 1] + delta[f];
+            if (q0 < 0 || q1 > nnz) continue;
+            int64_t q = q0 + tid;
+            for (; q + (kMarkUnroll - 1) * kSortThreads < q1; q += kMarkUnroll * kSortThreads) {
+                uint32_t r[kMarkUnroll];
 #pragma unroll
-        for (int i = 0; i < NT / 64; ++i) tot += s_w[i];
-        const uint32_t tot_a = (uint32_t)tot, tot_b = (uint32_t)(tot >> 32);
-        if (threadIdx.x < 64) {
-            if (tile == 0) {
-                if (threadIdx.x == 0) { publish_desc(desc, make_desc(kDescPfx, tot_a, tot_b)); s_pa = 0; s_pb = 0; }
+                for (int j = 0; j < kMarkUnroll; ++j) r[j] = (uint32_t)(inverse[q + j * kSortThreads] - c0);
+#pragma unroll
+                for (int j = 0; j < kMarkUnroll; ++j)
+                    if (r[j] < width) atomicAdd(&s_cnt[r[j]], 1);
+            }
+            for (; q < q1; q += kSortThreads) {
+                const uint32_t r0 = (uint32_t)(inverse[q] - c0);
+                if (r0 < width) atomicAdd(&s_cnt[r0], 1);
+            }
+        }
+        __syncthreads();
+        int v[kSortPer];
+        int mine = 0;
+#pragma unroll
+        for (int j = 0; j < kSortPer; ++j) {
+            const int i = tid * kSortPer + j;
+            v[j] = i < (int)width ? s_cnt[i] : 0;
+            mine += v[j];
+        }
+        int n_item;
+        const int ex = block_excl_scan<kSortThreads>(mine, &n_item);
+        if (tid < 64) {
+            if (item == first_item) {
+                if (tid == 0) { publish_desc(desc + item, make_desc(kDescPfx, (uint32_t)n_item, 0)); s_base = 0; }
             } else {
-                if (threadIdx.x == 0) publish_desc(desc + tile, make_desc(kDescAgg, tot_a, tot_b));
+                if (tid == 0) publish_desc(desc + item, make_desc(kDescAgg, (uint32_t)n_item, 0));
                 uint32_t pa, pb;
-                lookback(desc, 0, tile, &pa, &pb, &st[0].error);
-                if (threadIdx.x == 0) {
-                    publish_desc(desc + tile, make_desc(kDescPfx, pa + tot_a, pb + tot_b));
-                    s_pa = pa; s_pb = pb;
+                lookback(desc, first_item, item, &pa, &pb, &st[0].error);
+                if (tid == 0) {
+                    publish_desc(desc + item, make_desc(kDescPfx, pa + (uint32_t)n_item, 0));
+                    s_base = pa;
                 }
             }
         }
         __syncthreads();
-        uint32_t carry_a = s_pa, carry_b = s_pb;
-        if (tile == n_tiles - 1 && threadIdx.x == 0) st[p].n_hot = (int)(carry_b + tot_b);
-        for (int k = 0; k < kSegTile / NT; ++k) {
-            const int u = base + k * NT + threadIdx.x;
-            const int v = u < U ? cn[u] : 0;
-            const int is_hot = v > kWarmMax;
-            int ta, tb;
-            const int ea = block_excl_scan<NT>(v, &ta);
-            const int eb = block_excl_scan<NT>(is_hot, &tb);
-            if (u < U) {
-                const int s0 = (int)carry_a + ea;
-                cn[u] = s0;
-                for (int t = (s0 + tp - 1) / tp; t * tp < s0 + v; ++t) tf[t] = u;
-                if (is_hot) {
-                    const size_t h = carry_b + eb;
-                    hl[h] = u;
-                    hot_of[start + p + u] = (int)h;
-                    for (int d = 0; d < D; ++d) gh[h * D + d] = 0.0;
+        int s0 = (int)s_base + ex;
+#pragma unroll
+        for (int j = 0; j < kSortPer; ++j) {
+            const int i = tid * kSortPer + j;
+            if (i < (int)width) {
+                const int len = v[j];
+                seg[c0 + i] = s0;
+                s_cnt[i] = s0;                                 // from here on: the segment's next free position
+                const int t_in = (s0 + tp - 1) / tp;           // tiles whose first position lies in the segment
+                for (int tt = t_in; (int64_t)tt * tp < (int64_t)s0 + len; ++tt) tf[tt] = c0 + i;
+                if (len > kWarmMax && s0 / tp != (s0 + len - 1) / tp) {
+                    const int slot = s0 / tp;                  // one such key at most starts in a tile
+                    arr[slot] = 0;
+                    for (int d = 0; d < k.dim; ++d) gh[(size_t)slot * k.dim + d] = 0.0;
                 }
+                s0 += len;
             }
-            carry_a += ta;
-            carry_b += tb;
-        }
-    }
-}
-
-// Occurrences grouped by distinct key (counting sort): each entry says where the
-// occurrence's gradient lives in grad_out (sample * out_dim + the field's
-// column) and, in packs with mean pooling, carries the 1/L of its bag.  A block
-// takes BT consecutive bags (fewer when bags are long), whose occurrences are
-// contiguous, and finds each occurrence's bag in LDS.
-template <int BT>
-__global__ void __launch_bounds__(NT)
-pk_scatter_kernel(int B, int64_t out_dim, const FieldMeta* __restrict__ fmeta, const PackMeta* __restrict__ pm,
-                  const PackState* __restrict__ st, const int32_t* __restrict__ slot_field,
-                  const int32_t* __restrict__ packed_offsets,
-                  const int32_t* __restrict__ inverse, const int32_t* __restrict__ occ_slot,
-                  const int32_t* __restrict__ cnt, uint32_t* __restrict__ seg_ent, int ent_mult)
-{
-    __shared__ int32_t s_po[BT + 1];
-    __shared__ uint32_t s_ent[BT];
-    __shared__ float s_scl[BT];
-    const int p = blockIdx.y;
-    const int n = st[p].nnz, start = st[p].start;
-    const PackMeta k = pm[p];
-    const int32_t* po = packed_offsets + (int64_t)k.first_slot * B + p;
-    const int32_t* sf = slot_field + k.first_slot;
-    const int32_t* cn = cnt + start + p;
-    uint32_t* ent = seg_ent + (size_t)start * ent_mult;
-    const int64_t n_bags = (int64_t)k.n_fields * B;
-    const int n_tiles = (int)((n_bags + BT - 1) / BT);
-    for (XcdTiles it(n_tiles); it.valid(); it.next()) {
-        const int64_t bag0 = (int64_t)it.tile * BT;
-        const int nb = (int)min((int64_t)BT, n_bags - bag0);
-        __syncthreads();
-        for (int t = threadIdx.x; t <= nb; t += NT) s_po[t] = min(max(po[bag0 + t], 0), n);
-        if (threadIdx.x < nb) {
-            const int64_t g = bag0 + threadIdx.x;
-            const int j = (int)(g / B);
-            const int b = (int)(g - (int64_t)j * B);
-            const FieldMeta m = fmeta[sf[j]];
-            s_ent[threadIdx.x] = (uint32_t)((int64_t)b * out_dim + m.col);
-            float sc = 1.0f;
-            if (m.pool == PK_MEAN) {
-                const int L = po[g + 1] - po[g];
-                if (L > 0) sc = 1.0f / (float)L;
-            }
-            s_scl[threadIdx.x] = sc;
         }
         __syncthreads();
-        const int q_lo = s_po[0], q_hi = s_po[nb];
-        for (int q = q_lo + threadIdx.x; q < q_hi; q += NT) {
-            const int t = upper_bound_i32(s_po, nb + 1, q) - 1;
-            if ((unsigned)t >= (unsigned)nb) continue;
-            const int pos = cn[inverse[start + q]] + occ_slot[start + q];
-            if ((unsigned)pos < (unsigned)n) {
-                if (k.has_mean) reinterpret_cast<uint2*>(ent)[pos] = make_uint2(s_ent[t], __float_as_uint(s_scl[t]));
-                else ent[pos] = s_ent[t];
+        for (int fi = tm.field_begin; fi < tm.field_end; ++fi) {
+            const int f = table_fields[fi];
+            const int64_t q0 = (int64_t)fb[f] + delta[f], q1 = (int64_t)fb[f + 1] + delta[f];
+            if (q0 < 0 || q1 > nnz) continue;
+            int64_t q = q0 + tid;
+            for (; q + (kMarkUnroll - 1) * kSortThreads < q1; q += kMarkUnroll * kSortThreads) {
+                uint32_t r[kMarkUnroll], e[kMarkUnroll];
+                float c[kMarkUnroll];
+#pragma unroll
+                for (int j = 0; j < kMarkUnroll; ++j) {
+                    r[j] = (uint32_t)(inverse[q + j * kSortThreads] - c0);
+                    e[j] = bagref[q + j * kSortThreads];
+                    c[j] = wide ? bagscl[q + j * kSortThreads] : 1.0f;
+                }
+#pragma unroll
+                for (int j = 0; j < kMarkUnroll; ++j)
+                    if (r[j] < width) {
+                        const int pos = atomicAdd(&s_cnt[r[j]], 1);
+                        if ((unsigned)pos < (unsigned)n) {
+                            if (wide) reinterpret_cast<uint2*>(ent)[pos] = make_uint2(e[j], __float_as_uint(c[j]));
+                            else ent[pos] = e[j];
+                        }
+                    }
+            }
+            for (; q < q1; q += kSortThreads) {
+                const uint32_t r0 = (uint32_t)(inverse[q] - c0);
+                if (r0 < width) {
+                    const int pos = atomicAdd(&s_cnt[r0], 1);
+                    if ((unsigned)pos < (unsigned)n) {
+                        if (wide) reinterpret_cast<uint2*>(ent)[pos] = make_uint2(bagref[q], __float_as_uint(bagscl[q]));
+                        else ent[pos] = bagref[q];
+                    }
+                }
             }
         }
     }
@@ -805,9 +810,12 @@ pk_pool_kernel(const WT* __restrict__ W, const uint32_t* __restrict__ keys_all, 
 // the key-sorted occurrence list and handles the keys that start there.
 //   up to kColdMax occurrences: one lane group per key;
 //   up to kWarmMax:             one wavefront per key, groups stride over it;
-//   more:                       every tile reduces its piece of the key and adds
-//                               it (double atomics) to the key's partial-sum row;
-//                               pk_adagrad_hot_kernel then applies the update.
+//   more:                       the whole block reduces the tile's piece of the key.  A
+//                               key that lies inside one tile is then updated directly;
+//                               one that crosses tile boundaries has a row of partial
+//                               sums (indexed by the tile it starts in) to which every
+//                               tile adds its piece with double atomics, and the tile
+//                               that arrives last applies the update.
 // ---------------------------------------------------------------------------
 // The gradient chunks of a tile's occurrences: element offsets into grad_out and
 // mean-pooling scales, decoded once per tile, in parallel, into LDS.
@@ -917,11 +925,11 @@ __device__ __forceinline__ void wave_group_sum(double (&acc)[NCH][VEC])
 template <typename WT, int VEC, int LPR, int NCH>
 __global__ void __launch_bounds__(NT)
 pk_adagrad_kernel(WT* W, float* A, const PackState* __restrict__ st, int p,
-                  const uint32_t* __restrict__ unique_all, const int32_t* __restrict__ cnt,
-                  const int32_t* __restrict__ hot_all, double* ghot_all, int dmax,
-                  const int32_t* __restrict__ hot_of_all, const int32_t* __restrict__ tile_first, int tp, int hot_chunk,
+                  const uint32_t* __restrict__ unique_all, const int32_t* __restrict__ seg_all,
+                  double* ghot_all, int dmax, int32_t* arrive_all, const int32_t* __restrict__ tile_first, int tp,
                   const uint32_t* __restrict__ seg_ent_all, int ent_mult, int has_mean,
-                  const float* __restrict__ grad, int64_t gstride, int64_t out_dim, int D, float lr, float eps)
+                  const float* __restrict__ grad, int64_t gstride, int64_t out_dim, uint32_t addr_max, int D,
+                  float lr, float eps)
 {
     constexpr int GPB = NT / LPR;          // lane groups per block
     constexpr int GPW = 64 / LPR;          // lane groups per wavefront
@@ -936,12 +944,12 @@ pk_adagrad_kernel(WT* W, float* A, const PackState* __restrict__ st, int p,
     const int li = threadIdx.x % LPR, gi = threadIdx.x / LPR;
     const int wv = threadIdx.x >> 6, gw = (threadIdx.x & 63) / LPR;
     const int n = st->nnz, U = st->n_unique, start = st->start;
-    const int32_t* seg = cnt + start + p;
+    const int32_t* seg = seg_all + start + p;
     const uint32_t* uq = unique_all + start;
-    const size_t hbase = (size_t)(start / (kWarmMax + 1) + p);
-    double* gh = ghot_all + hbase * dmax;
-    const int32_t* tf = tile_first + start / tp + p;
-    const int32_t* hot_of = hot_of_all + start + p;
+    const size_t tbase = (size_t)(start / tp + p);
+    double* gh = ghot_all + tbase * dmax;
+    int32_t* arr = arrive_all + tbase;
+    const int32_t* tf = tile_first + tbase;
     const uint32_t* ent = seg_ent_all + (size_t)start * ent_mult;
     GradSrc g{grad, s_addr, s_scl, 0};
     const int n_tiles = (n + tp - 1) / tp;
@@ -980,6 +988,7 @@ pk_adagrad_kernel(WT* W, float* A, const PackState* __restrict__ st, int p,
                 const uint32_t b = a / (uint32_t)out_dim;
                 a = b * (uint32_t)gstride + (a - b * (uint32_t)out_dim);
             }
+            if (a > addr_max) { a = 0; c = 0.0f; }         // never leave grad_out, whatever the list holds
             s_addr[i] = a;
             s_scl[i] = c;
         }
@@ -1027,12 +1036,12 @@ pk_adagrad_kernel(WT* W, float* A, const PackState* __restrict__ st, int p,
             wave_group_sum<VEC, LPR, NCH>(acc);
             if (gw == 0) row_step<WT, VEC, LPR, NCH>(W, A, row, D, li, acc, w, a, lr, eps);
         }
-        // hot keys: this tile's piece is split over the block's wavefronts, reduced in LDS and
-        // added once to the key's partial sums
+        // long keys: the tile's piece is split over the block's wavefronts and reduced in LDS
         const int n_hot_here = s_nhot;
         for (int i = 0; i < n_hot_here; ++i) {
             const int k = s_hot[i];
-            const int a0 = max(s_seg[k], t0), b0 = min(s_seg[k + 1], t1);
+            const int s0 = s_seg[k], s1 = s_seg[k + 1];
+            const int a0 = max(s0, t0), b0 = min(s1, t1);
             const int share = (b0 - a0 + NT / 64 - 1) / (NT / 64);
             const int c0 = a0 + wv * share, c1 = min(c0 + share, b0);
             double acc[NCH][VEC];
@@ -1051,50 +1060,56 @@ pk_adagrad_kernel(WT* W, float* A, const PackState* __restrict__ st, int p,
             }
             __syncthreads();
             if (wv == 0 && gw == 0) {
-                double* prow = gh + (size_t)hot_of[u_lo + k] * D;   // the key's row of partial sums
 #pragma unroll
-                for (int c = 0; c < NCH; ++c) {
-                    const int d0 = (c * LPR + li) * VEC;
-                    if (d0 < D) {
+                for (int c = 0; c < NCH; ++c)
 #pragma unroll
-                        for (int v = 0; v < VEC; ++v) {
-                            double t = 0.0;
+                    for (int v = 0; v < VEC; ++v) {
+                        double t = 0.0;
 #pragma unroll
-                            for (int w2 = 0; w2 < NT / 64; ++w2) t += s_red[w2][li][c][v];
-                            atomicAdd(prow + d0 + v, t);
+                        for (int w2 = 0; w2 < NT / 64; ++w2) t += s_red[w2][li][c][v];
+                        acc[c][v] = t;
+                    }
+                bool apply = s0 >= t0 && s1 <= t1;             // the key lies inside this tile
+                if (!apply) {
+                    const int slot = s0 / tp;                  // the tile the key starts in
+                    double* prow = gh + (size_t)slot * D;      // the key's row of partial sums
+#pragma unroll
+                    for (int c = 0; c < NCH; ++c) {
+                        const int d0 = (c * LPR + li) * VEC;
+                        if (d0 < D) {
+#pragma unroll
+                            for (int v = 0; v < VEC; ++v) atomicAdd(prow + d0 + v, acc[c][v]);
                         }
                     }
+                    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+                    int last = 0;
+                    if (li == 0) {
+                        const int pieces = (s1 - 1) / tp - slot + 1;
+                        last = __hip_atomic_fetch_add(arr + slot, 1, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT) == pieces - 1;
+                    }
+                    last = __shfl(last, 0, 64);                // lane 0 of wavefront 0 is this group's lane 0
+                    if (last) {
+                        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+#pragma unroll
+                        for (int c = 0; c < NCH; ++c) {
+                            const int d0 = (c * LPR + li) * VEC;
+                            if (d0 < D) {
+#pragma unroll
+                                for (int v = 0; v < VEC; ++v)
+                                    acc[c][v] = __hip_atomic_load(prow + d0 + v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                            }
+                        }
+                        apply = true;
+                    }
+                }
+                if (apply) {
+                    const size_t row = s_row[k];
+                    float w[NCH][VEC], a[NCH][VEC];
+                    row_load<WT, VEC, LPR, NCH>(W, A, row, D, li, w, a);
+                    row_step<WT, VEC, LPR, NCH>(W, A, row, D, li, acc, w, a, lr, eps);
                 }
             }
         }
-    }
-}
-
-// hot keys: partial sums are complete, apply the update (one lane group per key)
-template <typename WT, int VEC, int LPR, int NCH>
-__global__ void __launch_bounds__(NT)
-pk_adagrad_hot_kernel(WT* W, float* A, const PackState* __restrict__ st, int p,
-                      const uint32_t* __restrict__ unique_all, const int32_t* __restrict__ hot_all,
-                      const double* __restrict__ ghot_all, int dmax, int D, float lr, float eps)
-{
-    constexpr int GPB = NT / LPR;
-    const int li = threadIdx.x % LPR, gi = threadIdx.x / LPR;
-    const int start = st->start, n_hot = st->n_hot;
-    const size_t hbase = (size_t)(start / (kWarmMax + 1) + p);
-    const int32_t* hl = hot_all + hbase;
-    const double* gh = ghot_all + hbase * dmax;
-    for (int h = blockIdx.x * GPB + gi; h < n_hot; h += gridDim.x * GPB) {
-        double acc[NCH][VEC];
-#pragma unroll
-        for (int c = 0; c < NCH; ++c) {
-            const int d0 = (c * LPR + li) * VEC;
-#pragma unroll
-            for (int v = 0; v < VEC; ++v) acc[c][v] = d0 < D ? gh[(size_t)h * D + d0 + v] : 0.0;
-        }
-        const size_t row = unique_all[start + hl[h]];
-        float w[NCH][VEC], a[NCH][VEC];
-        row_load<WT, VEC, LPR, NCH>(W, A, row, D, li, w, a);
-        row_step<WT, VEC, LPR, NCH>(W, A, row, D, li, acc, w, a, lr, eps);
     }
 }
 
@@ -1109,10 +1124,8 @@ struct DeviceState {
     int32_t* slot_field = nullptr;
     MarkItem* mark_items = nullptr;
     int32_t* mark_fields = nullptr;
-    TableMeta* table_meta = nullptr;
+    TableMeta* sort_tables = nullptr;
     int32_t* table_fields = nullptr;
-    int32_t* count_item_table = nullptr;
-    int32_t* count_item_chunk = nullptr;
     std::mutex mu;
     // Side streams: packs (and the pooling of a pack vs the dedup chain) are independent
     // pieces of memory-bound work; running them side by side hides launch gaps and
@@ -1164,41 +1177,34 @@ pk_status ensure_device_state(const pk_plan* cplan, DeviceState** out)
         const Pack& k = plan->packs[p];
         pmv[p].dim = k.dim; pmv[p].dtype = k.dtype; pmv[p].n_fields = (int32_t)k.fields.size();
         pmv[p].first_slot = k.first_slot; pmv[p].has_mean = k.has_mean ? 1 : 0;
-        pmv[p].first_tile = k.first_tile; pmv[p].n_tiles = k.n_tiles; pmv[p].pad = 0;
+        pmv[p].first_tile = k.first_tile; pmv[p].n_tiles = k.n_tiles; pmv[p].first_stable = k.first_stable;
     }
-    const size_t b_f = (F * sizeof(FieldMeta) + 255) / 256 * 256;
-    const size_t b_p = (P * sizeof(PackMeta) + 255) / 256 * 256;
-    const size_t b_s = (F * 4 + 255) / 256 * 256;
-    const size_t b_i = (plan->mark_items.size() * sizeof(MarkItem) + 255) / 256 * 256;
-    const size_t b_m = (plan->mark_fields.size() * 4 + 255) / 256 * 256;
-    const size_t b_t = (plan->table_meta.size() * sizeof(TableMeta) + 255) / 256 * 256;
-    const size_t b_tf = (plan->table_fields.size() * 4 + 255) / 256 * 256;
-    const size_t b_ci = (plan->count_item_table.size() * 4 + 255) / 256 * 256;
-    e = hipMalloc(&ds->blob, b_f + b_p + b_s + b_i + b_m + b_t + b_tf + 2 * b_ci);
+    auto pad = [](size_t b) { return (b + 255) / 256 * 256; };
+    const size_t b_f = pad(F * sizeof(FieldMeta)), b_p = pad(P * sizeof(PackMeta)), b_s = pad(F * 4);
+    const size_t b_i = pad(plan->mark_items.size() * sizeof(MarkItem)), b_m = pad(plan->mark_fields.size() * 4);
+    const size_t b_t = pad(plan->sort_tables.size() * sizeof(TableMeta)), b_tf = pad(plan->table_fields.size() * 4);
+    e = hipMalloc(&ds->blob, b_f + b_p + b_s + b_i + b_m + b_t + b_tf + 256);
     if (e != hipSuccess) { delete ds; return fail(PK_EHIP, hip_msg("hipMalloc(plan metadata)", e)); }
-    ds->fmeta = reinterpret_cast<FieldMeta*>(ds->blob);
-    ds->pmeta = reinterpret_cast<PackMeta*>(static_cast<char*>(ds->blob) + b_f);
-    ds->slot_field = reinterpret_cast<int32_t*>(static_cast<char*>(ds->blob) + b_f + b_p);
-    ds->mark_items = reinterpret_cast<MarkItem*>(static_cast<char*>(ds->blob) + b_f + b_p + b_s);
-    ds->mark_fields = reinterpret_cast<int32_t*>(static_cast<char*>(ds->blob) + b_f + b_p + b_s + b_i);
     {
-        char* at = static_cast<char*>(ds->blob) + b_f + b_p + b_s + b_i + b_m;
-        ds->table_meta = reinterpret_cast<TableMeta*>(at); at += b_t;
-        ds->table_fields = reinterpret_cast<int32_t*>(at); at += b_tf;
-        ds->count_item_table = reinterpret_cast<int32_t*>(at); at += b_ci;
-        ds->count_item_chunk = reinterpret_cast<int32_t*>(at);
+        char* at = static_cast<char*>(ds->blob);
+        ds->fmeta = reinterpret_cast<FieldMeta*>(at); at += b_f;
+        ds->pmeta = reinterpret_cast<PackMeta*>(at); at += b_p;
+        ds->slot_field = reinterpret_cast<int32_t*>(at); at += b_s;
+        ds->mark_items = reinterpret_cast<MarkItem*>(at); at += b_i;
+        ds->mark_fields = reinterpret_cast<int32_t*>(at); at += b_m;
+        ds->sort_tables = reinterpret_cast<TableMeta*>(at); at += b_t;
+        ds->table_fields = reinterpret_cast<int32_t*>(at);
     }
-    e = hipMemcpy(ds->fmeta, fm.data(), F * sizeof(FieldMeta), hipMemcpyHostToDevice);
-    if (e == hipSuccess) e = hipMemcpy(ds->table_meta, plan->table_meta.data(), plan->table_meta.size() * sizeof(TableMeta), hipMemcpyHostToDevice);
-    if (e == hipSuccess && !plan->table_fields.empty()) e = hipMemcpy(ds->table_fields, plan->table_fields.data(), plan->table_fields.size() * 4, hipMemcpyHostToDevice);
-    if (e == hipSuccess && !plan->count_item_table.empty()) {
-        e = hipMemcpy(ds->count_item_table, plan->count_item_table.data(), plan->count_item_table.size() * 4, hipMemcpyHostToDevice);
-        if (e == hipSuccess) e = hipMemcpy(ds->count_item_chunk, plan->count_item_chunk.data(), plan->count_item_chunk.size() * 4, hipMemcpyHostToDevice);
-    }
-    if (e == hipSuccess) e = hipMemcpy(ds->mark_items, plan->mark_items.data(), plan->mark_items.size() * sizeof(MarkItem), hipMemcpyHostToDevice);
-    if (e == hipSuccess && !plan->mark_fields.empty()) e = hipMemcpy(ds->mark_fields, plan->mark_fields.data(), plan->mark_fields.size() * 4, hipMemcpyHostToDevice);
-    if (e == hipSuccess) e = hipMemcpy(ds->pmeta, pmv.data(), P * sizeof(PackMeta), hipMemcpyHostToDevice);
-    if (e == hipSuccess) e = hipMemcpy(ds->slot_field, plan->slot_field.data(), F * 4, hipMemcpyHostToDevice);
+    auto up = [&](void* dst, const void* src, size_t bytes) {
+        if (e == hipSuccess && bytes) e = hipMemcpy(dst, src, bytes, hipMemcpyHostToDevice);
+    };
+    up(ds->fmeta, fm.data(), F * sizeof(FieldMeta));
+    up(ds->pmeta, pmv.data(), P * sizeof(PackMeta));
+    up(ds->slot_field, plan->slot_field.data(), F * 4);
+    up(ds->mark_items, plan->mark_items.data(), plan->mark_items.size() * sizeof(MarkItem));
+    up(ds->mark_fields, plan->mark_fields.data(), plan->mark_fields.size() * 4);
+    up(ds->sort_tables, plan->sort_tables.data(), plan->sort_tables.size() * sizeof(TableMeta));
+    up(ds->table_fields, plan->table_fields.data(), plan->table_fields.size() * 4);
     if (e != hipSuccess) { (void)hipFree(ds->blob); delete ds; return fail(PK_EHIP, hip_msg("hipMemcpy(plan metadata)", e)); }
     for (int i = 0; i < DeviceState::kSide && e == hipSuccess; ++i) {
         e = hipStreamCreateWithFlags(&ds->side[i], hipStreamNonBlocking);     // default priority
@@ -1314,10 +1320,9 @@ struct PoolArgs {
     bool aligned;
 };
 struct AdaArgs {
-    void* W; float* A; const PackState* st; int p; const uint32_t* unique; const int32_t* cnt; const int32_t* hot;
-    double* ghot; int dmax;
-    const int32_t* hot_of; const int32_t* tile_first; int tp; int hot_chunk; const uint32_t* seg_ent; int ent_mult;
-    int has_mean; const float* grad; int64_t gstride; int64_t out_dim; int D;
+    void* W; float* A; const PackState* st; int p; const uint32_t* unique; const int32_t* seg;
+    double* ghot; int dmax; int32_t* arrive; const int32_t* tile_first; int tp; const uint32_t* seg_ent; int ent_mult;
+    int has_mean; const float* grad; int64_t gstride; int64_t out_dim; uint32_t addr_max; int D;
     float lr; float eps; int64_t nnz_bound; bool aligned;
 };
 
@@ -1335,14 +1340,10 @@ pk_status launch_pool(DeviceState* ds, hipStream_t stream, const PoolArgs& a)
 template <typename WT, int VEC, int LPR, int NCH>
 pk_status launch_adagrad(DeviceState* ds, hipStream_t stream, const AdaArgs& a)
 {
-    constexpr int GPB = NT / LPR;
     const unsigned grid = (blocks_for(a.nnz_bound, a.tp, 256 * 16) + 7u) & ~7u;
     PK_LAUNCH("pk_adagrad", (pk_adagrad_kernel<WT, VEC, LPR, NCH>), dim3(grid), dim3(NT), 0,
-              static_cast<WT*>(a.W), a.A, a.st, a.p, a.unique, a.cnt, a.hot, a.ghot, a.dmax, a.hot_of, a.tile_first,
-              a.tp, a.hot_chunk, a.seg_ent, a.ent_mult, a.has_mean, a.grad, a.gstride, a.out_dim, a.D, a.lr, a.eps);
-    const unsigned hgrid = blocks_for(a.nnz_bound / (kWarmMax + 1) + 1, GPB, 1024);
-    PK_LAUNCH("pk_adagrad_hot", (pk_adagrad_hot_kernel<WT, VEC, LPR, NCH>), dim3(hgrid), dim3(NT), 0,
-              static_cast<WT*>(a.W), a.A, a.st, a.p, a.unique, a.hot, a.ghot, a.dmax, a.D, a.lr, a.eps);
+              static_cast<WT*>(a.W), a.A, a.st, a.p, a.unique, a.seg, a.ghot, a.dmax, a.arrive, a.tile_first,
+              a.tp, a.seg_ent, a.ent_mult, a.has_mean, a.grad, a.gstride, a.out_dim, a.addr_max, a.D, a.lr, a.eps);
     return PK_OK;
 }
 
@@ -1414,46 +1415,47 @@ pk_status pk_forward(const pk_plan* plan, void* const* W, const int64_t* ids, co
     PackState* st = ws.at<PackState>(L.state);
     int32_t* fb = ws.at<int32_t>(L.fb);
     int32_t* delta = ws.at<int32_t>(L.delta);
-    int32_t* slot_start = ws.at<int32_t>(L.slot_start);
     int32_t* packed_offsets = ws.at<int32_t>(L.packed_offsets);
     uint32_t* keys = ws.at<uint32_t>(L.keys);
     int32_t* inverse = ws.at<int32_t>(L.inverse);
-    int32_t* occ_slot = ws.at<int32_t>(L.occ_slot);
+    uint32_t* bagref = ws.at<uint32_t>(L.bagref);
+    float* bagscl = plan->any_mean ? ws.at<float>(L.bagscl) : nullptr;
     uint32_t* seg_ent = ws.at<uint32_t>(L.seg_ent);
     int32_t* tile_first = ws.at<int32_t>(L.tile_first);
     uint32_t* unique = ws.at<uint32_t>(L.unique);
-    int32_t* cnt = ws.at<int32_t>(L.cnt);
-    int32_t* hot = ws.at<int32_t>(L.hot);
+    int32_t* seg = ws.at<int32_t>(L.seg);
     double* ghot = ws.at<double>(L.ghot);
+    int32_t* arrive = ws.at<int32_t>(L.arrive);
     uint32_t* bitmap = ws.at<uint32_t>(L.bitmap);
     uint64_t* tile_desc = ws.at<uint64_t>(L.tile_desc);
-    uint64_t* seg_desc = ws.at<uint64_t>(L.seg_desc);
+    uint64_t* sort_desc = ws.at<uint64_t>(L.sort_desc);
     int32_t* rank = ws.at<int32_t>(L.rank);
     const int64_t n_tiles = L.n_tiles_total;
     const int64_t n_clear4 = (int64_t)(L.clear_bytes / 16);
+    const int T = (int)plan->sort_tables.size();
 
-    const unsigned clear_blocks = blocks_for(n_clear4, 1024 * 4, 1024);
-    PK_LAUNCH("pk_setup", pk_setup_kernel, dim3(1 + clear_blocks), dim3(1024), 0, offsets, B, F, P, nnz, ds->pmeta,
-              ds->slot_field, st, fb, delta, slot_start, packed_offsets, reinterpret_cast<uint4*>(tile_desc), n_clear4);
-
-    const int kt = nnz < (1 << 20) ? 256 : 1024;      // occurrences per tile of the keys / inverse kernels
-    const int use_lds = (F + 1) * 4 <= 32 * 1024;
-    const int64_t key_blocks = std::max<int64_t>((nnz + kt - 1) / kt, ((int64_t)F * B + NT * 4 - 1) / (NT * 4));
-    const dim3 key_grid((blocks_for(key_blocks, 1, 256 * 32) + 7u) & ~7u);
-    const size_t key_lds = use_lds ? (size_t)(F + 1) * 4 : 0;
-    if (kt == 256)
-        PK_LAUNCH("pk_keys", pk_keys_kernel<256>, key_grid, dim3(NT), key_lds, ids, offsets, B, F, nnz, ds->fmeta,
-                  ds->pmeta, st, fb, delta, slot_start, keys, packed_offsets, use_lds);
+    // keys: BT bags per block iteration; fewer when bags are long, so that blocks stay comparable
+    const int64_t n_bags = (int64_t)F * B;
+    const bool long_bags = nnz / n_bags >= 16;
+    const int bt = long_bags ? 32 : 256;
+    const dim3 key_grid(blocks_for(n_bags, bt, 256 * 8));
+    const size_t key_lds = (size_t)(3 * F + 2) * 4;
+    if (long_bags)
+        PK_LAUNCH("pk_keys", pk_keys_kernel<32>, key_grid, dim3(NT), key_lds, ids, offsets, B, F, P, nnz, ds->fmeta,
+                  ds->pmeta, ds->slot_field, st, fb, delta, keys, bagref, bagscl, packed_offsets, plan->out_dim,
+                  reinterpret_cast<uint4*>(tile_desc), n_clear4);
     else
-        PK_LAUNCH("pk_keys", pk_keys_kernel<1024>, key_grid, dim3(NT), key_lds, ids, offsets, B, F, nnz, ds->fmeta,
-                  ds->pmeta, st, fb, delta, slot_start, keys, packed_offsets, use_lds);
+        PK_LAUNCH("pk_keys", pk_keys_kernel<256>, key_grid, dim3(NT), key_lds, ids, offsets, B, F, P, nnz, ds->fmeta,
+                  ds->pmeta, ds->slot_field, st, fb, delta, keys, bagref, bagscl, packed_offsets, plan->out_dim,
+                  reinterpret_cast<uint4*>(tile_desc), n_clear4);
 
     // pooling needs the keys only: it runs beside the rest of the dedup chain
-    const bool overlap = ds->overlap && !ds->prof_on && (P > 1 || nnz >= (1 << 20));   // fork+join cost a few us
+    const bool overlap = ds->overlap && !ds->prof_on;
     const int n_side = overlap ? std::min<int>(P, DeviceState::kSide) : 0;
     if (n_side) { rc = fork_streams(ds, stream, n_side); if (rc != PK_OK) return rc; }
     for (int p = 0; p < P; ++p) {
         const Pack& k = plan->packs[p];
+        if (k.fields.empty()) continue;
         PoolArgs a{W[p], keys, packed_offsets + po_off(plan, p, B), st + p, ds->fmeta, ds->slot_field + k.first_slot,
                    B, k.dim, (int64_t)k.fields.size() * B, out, out_row_stride, 256 * 32,
                    cols_aligned(plan, p) && aligned16(out) && out_row_stride % 4 == 0 && aligned16(W[p])};
@@ -1466,7 +1468,8 @@ pk_status pk_forward(const pk_plan* plan, void* const* W, const int64_t* ids, co
     PK_LAUNCH("pk_mark", pk_mark_kernel, dim3((unsigned)plan->mark_items.size()), dim3(kMarkThreads), 0, ds->mark_items,
               ds->mark_fields, ds->pmeta, st, fb, delta, keys, bitmap, nnz);
     PK_LAUNCH("pk_tiles", pk_tiles_kernel, dim3(blocks_for(n_tiles, 1, 1024)), dim3(NT), 0,
-              reinterpret_cast<const uint4*>(bitmap), tile_desc, (int)n_tiles, ds->pmeta, st, P, rank, unique, cnt);
+              reinterpret_cast<const uint4*>(bitmap), tile_desc, (int)n_tiles, ds->pmeta, st, P, rank, unique, seg);
+    const int kt = nnz < (1 << 20) ? 256 : 1024;      // occurrences per tile of the inverse kernel
     const unsigned xq = (blocks_for(nnz, kt, 256 * 16) + 7u) & ~7u;
     if (kt == 256)
         PK_LAUNCH("pk_inverse", pk_inverse_kernel<256>, dim3(xq, P), dim3(NT), 0, ds->pmeta, st, keys,
@@ -1474,22 +1477,14 @@ pk_status pk_forward(const pk_plan* plan, void* const* W, const int64_t* ids, co
     else
         PK_LAUNCH("pk_inverse", pk_inverse_kernel<1024>, dim3(xq, P), dim3(NT), 0, ds->pmeta, st, keys,
                   reinterpret_cast<const uint4*>(bitmap), rank, inverse);
-    if (!plan->count_item_table.empty())
-        PK_LAUNCH("pk_count", pk_count_kernel, dim3((unsigned)plan->count_item_table.size()), dim3(kMarkThreads), 0,
-                  ds->count_item_table, ds->count_item_chunk, ds->table_meta, ds->table_fields, ds->pmeta, st, fb, delta,
-                  reinterpret_cast<const uint4*>(bitmap), rank, inverse, occ_slot, cnt, nnz);
-    PK_LAUNCH("pk_segs", pk_segs_kernel, dim3(blocks_for(nnz, kSegTile, std::max(1, 1024 / P)), P), dim3(NT), 0,
-              ds->pmeta, st, cnt, seg_desc, hot, ws.at<int32_t>(L.hot_of), ghot, L.dmax, tile_first, L.pos_tile);
-    int64_t max_bags = 0;
-    for (int p = 0; p < P; ++p) max_bags = std::max<int64_t>(max_bags, (int64_t)plan->packs[p].fields.size() * B);
-    if (nnz / ((int64_t)F * B) >= 16)      // long bags: fewer bags per block
-        PK_LAUNCH("pk_scatter", pk_scatter_kernel<32>, dim3((blocks_for(max_bags, 32, 256 * 16) + 7u) & ~7u, P), dim3(NT),
-                  0, B, plan->out_dim, ds->fmeta, ds->pmeta, st, ds->slot_field, packed_offsets, inverse, occ_slot, cnt,
-                  seg_ent, plan->any_mean ? 2 : 1);
-    else
-        PK_LAUNCH("pk_scatter", pk_scatter_kernel<256>, dim3((blocks_for(max_bags, 256, 256 * 16) + 7u) & ~7u, P),
-                  dim3(NT), 0, B, plan->out_dim, ds->fmeta, ds->pmeta, st, ds->slot_field, packed_offsets, inverse,
-                  occ_slot, cnt, seg_ent, plan->any_mean ? 2 : 1);
+    if (T > 0) {
+        // at most nnz / kSortCap + T work items exist; one block per CU keeps every block resident
+        const unsigned sgrid = (unsigned)std::max<int64_t>(P, std::min<int64_t>(nnz / kSortCap + T, 256));
+        PK_LAUNCH("pk_sort", pk_sort_kernel, dim3(sgrid), dim3(kSortThreads), (size_t)(3 * T + 1) * 4,
+                  ds->sort_tables, ds->table_fields, T, ds->pmeta, st, P, fb, delta,
+                  reinterpret_cast<const uint4*>(bitmap), rank, inverse, bagref, bagscl, seg, seg_ent,
+                  plan->any_mean ? 2 : 1, tile_first, L.pos_tile, sort_desc, ghot, L.dmax, arrive, nnz);
+    }
     if (n_side) { rc = join_streams(ds, stream, n_side); if (rc != PK_OK) return rc; }
     return PK_OK;
 }
@@ -1520,10 +1515,12 @@ pk_status pk_backward_update(const pk_plan* plan, void* const* W, float* const* 
     for (int p = 0; p < P; ++p) {
         const Pack& k = plan->packs[p];
         hipStream_t ps = n_side ? ds->side[p % n_side] : stream;
-        AdaArgs a{W[p], A[p], st + p, p, ws.at<uint32_t>(L.unique), ws.at<int32_t>(L.cnt), ws.at<int32_t>(L.hot),
-                  ws.at<double>(L.ghot), L.dmax, ws.at<int32_t>(L.hot_of), ws.at<int32_t>(L.tile_first), L.pos_tile,
-                  nnz < (2 << 20) ? 64 : 256, ws.at<uint32_t>(L.seg_ent), plan->any_mean ? 2 : 1,
-                  k.has_mean ? 1 : 0, grad_out, grad_row_stride, plan->out_dim, k.dim, lr, eps, nnz,
+        if (k.fields.empty()) continue;
+        AdaArgs a{W[p], A[p], st + p, p, ws.at<uint32_t>(L.unique), ws.at<int32_t>(L.seg), ws.at<double>(L.ghot),
+                  L.dmax, ws.at<int32_t>(L.arrive), ws.at<int32_t>(L.tile_first), L.pos_tile,
+                  ws.at<uint32_t>(L.seg_ent), plan->any_mean ? 2 : 1, k.has_mean ? 1 : 0, grad_out, grad_row_stride,
+                  plan->out_dim, (uint32_t)((int64_t)(B - 1) * grad_row_stride + plan->out_dim - k.dim), k.dim, lr,
+                  eps, nnz,
                   cols_aligned(plan, p) && aligned16(grad_out) && grad_row_stride % 4 == 0 && aligned16(W[p]) &&
                       aligned16(A[p])};
         rc = k.dtype == PK_F32 ? dispatch_adagrad<float, 4>(ds, ps, k.dim, a)
@@ -1551,7 +1548,7 @@ pk_status pk_ctx_pack(const pk_plan* plan, const void* workspace, int32_t B, int
     if (unique) *unique = reinterpret_cast<const uint32_t*>(base + L.unique) + s.start;
     if (inverse) *inverse = reinterpret_cast<const int32_t*>(base + L.inverse) + s.start;
     if (packed_offsets) *packed_offsets = reinterpret_cast<const int32_t*>(base + L.packed_offsets) + po_off(plan, p, B);
-    if (seg_offsets) *seg_offsets = reinterpret_cast<const int32_t*>(base + L.cnt) + s.start + p;
+    if (seg_offsets) *seg_offsets = reinterpret_cast<const int32_t*>(base + L.seg) + s.start + p;
     if (nnz_p) *nnz_p = s.nnz;
     if (n_unique) *n_unique = s.n_unique;
     return PK_OK;

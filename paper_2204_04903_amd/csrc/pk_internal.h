@@ -15,11 +15,10 @@ constexpr int kColdMax   = 8;      // keys with at most this many occurrences: o
 constexpr int kWarmMax   = 256;    // up to this many: one wavefront per key; above: split, partial sums
 constexpr int kTileWords = 2048;   // bitmap words scanned by one block (256 threads x 8 words)
 constexpr int kRankWords = 8;      // one rank sample per 8 words (256 keys)
-constexpr int kSegTile   = 2048;   // occurrence counts scanned per ticket (256 threads x 8)
 constexpr int kPosTileMax = 512;   // occurrences handled per block iteration in the backward pass (upper end)
 constexpr int kPosTileMin = 64;
 constexpr int kMarkWords = 16384;  // bitmap words (512K keys, 64 KB of LDS) owned by one block of the mark kernel
-constexpr int kCountCap  = 16384;  // distinct keys counted in LDS by one block of the count kernel
+constexpr int kSortCap   = 16384;  // distinct keys whose occurrences one block of the sort kernel groups in LDS
 constexpr size_t kAlign = 256;
 
 // Per field, device side (indexed by field index).
@@ -41,7 +40,7 @@ struct PackMeta {
     int32_t has_mean;
     int32_t first_tile;      // first bitmap tile (of kTileWords words) of the pack
     int32_t n_tiles;
-    int32_t pad;
+    int32_t first_stable;    // index of the pack's first table in the (pack, key) ordered table list
 };
 
 // A slice of a pack's key space (kMarkWords bitmap words) and the fields whose
@@ -55,7 +54,8 @@ struct MarkItem {
     int32_t pad[3];
 };
 
-// A table and the fields that read it; static, device side.
+// A table that at least one field reads, and those fields; static, device side,
+// listed in (pack, first key) order.
 struct TableMeta {
     int32_t pack;
     uint32_t key_lo;         // first key of the table inside its pack
@@ -70,9 +70,8 @@ struct PackState {
     int32_t nnz;        // occurrences in the pack
     int32_t start;      // position of the pack's first occurrence in the packed order
     int32_t n_unique;
-    int32_t n_hot;
     int32_t error;      // only pack 0's word is used
-    int32_t pad[3];
+    int32_t pad[4];
 };
 
 struct Pack {
@@ -83,12 +82,13 @@ struct Pack {
     std::vector<int32_t> fields;
     int32_t first_slot = 0;
     int32_t first_tile = 0, n_tiles = 0;
+    int32_t first_stable = 0;
 };
 
 // Byte offsets of the workspace's arrays for one (plan, B, nnz).
 struct Layout {
-    size_t state, fb, delta, slot_start, packed_offsets, keys, inverse, occ_slot, seg_ent, hot_of, tile_first,
-           unique, cnt, hot, ghot, bitmap, tile_desc, seg_desc, rank, total;
+    size_t state, fb, delta, packed_offsets, keys, inverse, bagref, bagscl, seg_ent, tile_first,
+           unique, seg, ghot, arrive, bitmap, tile_desc, sort_desc, rank, total;
     size_t clear_bytes;          // scan descriptors, contiguous from `tile_desc`
     int64_t n_tiles_total;
     int32_t dmax;
@@ -109,9 +109,8 @@ struct pk_plan {
     std::vector<int32_t> slot_field;      // fields in (pack, slot) order
     std::vector<pk::MarkItem> mark_items;
     std::vector<int32_t> mark_fields;     // per item: the fields whose table overlaps the slice
-    std::vector<pk::TableMeta> table_meta;
-    std::vector<int32_t> table_fields;    // per table: the fields that read it
-    std::vector<int32_t> count_item_table, count_item_chunk;   // (table, chunk of kCountCap distinct keys)
+    std::vector<pk::TableMeta> sort_tables;   // tables with fields, in (pack, first key) order
+    std::vector<int32_t> table_fields;        // per entry of sort_tables: the fields that read it
     int64_t out_dim = 0;
     bool any_mean = false;
     int32_t n_tiles_total = 0;

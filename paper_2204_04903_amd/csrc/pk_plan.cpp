@@ -48,25 +48,24 @@ Layout make_layout(const pk_plan* plan, int32_t B, int64_t nnz)
     L.state          = take(P * sizeof(PackState));
     L.fb             = take((F + 1) * 4);
     L.delta          = take(F * 4);
-    L.slot_start     = take((F + P) * 4);
     L.packed_offsets = take((F * (size_t)B + P) * 4);
     L.keys           = take(n * 4);
     L.inverse        = take(n * 4);
-    L.occ_slot       = take(n * 4);
+    L.bagref         = take(n * 4);
+    L.bagscl         = take(plan->any_mean ? n * 4 : 0);
     L.seg_ent        = take(n * (plan->any_mean ? 8 : 4));
-    L.hot_of         = take((n + P + 1) * 4);
     L.pos_tile       = pos_tile_for(nnz);
-    L.tile_first     = take((n / L.pos_tile + P + 2) * 4);
+    const size_t tile_cap = n / L.pos_tile + P + 2;      // backward tiles of all packs
+    L.tile_first     = take(tile_cap * 4);
     L.unique         = take(n * 4);
-    L.cnt            = take((n + P + 1) * 4);
-    const size_t hot_cap = n / (kWarmMax + 1) + P + 1;
-    L.hot            = take(hot_cap * 4);
+    L.seg            = take((n + P + 1) * 4);
     L.dmax           = plan->dmax;
-    L.ghot           = take(hot_cap * (size_t)plan->dmax * 8);
+    L.ghot           = take(tile_cap * (size_t)plan->dmax * 8);
+    L.arrive         = take(tile_cap * 4);
     L.n_tiles_total  = plan->n_tiles_total;
     L.bitmap         = take((size_t)plan->n_tiles_total * kTileWords * 4);
     L.tile_desc      = take((size_t)plan->n_tiles_total * 8);
-    L.seg_desc       = take((n / kSegTile + P + 1) * 8);
+    L.sort_desc      = take((n / kSortCap + plan->sort_tables.size() + 2) * 8);
     L.clear_bytes    = off - L.tile_desc;     // scan descriptors only: the bitmap is fully rewritten every call
     L.rank           = take((size_t)plan->n_tiles_total * (kTileWords / kRankWords) * 4);
     L.total = off;
@@ -102,6 +101,8 @@ pk_status pk_plan_create(const pk_table_desc* tables, int32_t n_tables, const pk
         if (fields[f].pool != PK_SUM && fields[f].pool != PK_MEAN)
             return fail(PK_EINVAL, "pk_plan_create: field " + std::to_string(f) + " has an unknown pooling mode");
     }
+    if (n_fields > 4096 || n_tables > 4096)
+        return fail(PK_EOVERFLOW, "pk_plan_create: at most 4096 fields and 4096 tables (their metadata is staged in LDS)");
     if (opts && (opts->max_batch < 0 || opts->max_nnz < 0 || opts->max_shards < 0))
         return fail(PK_EINVAL, "pk_plan_create: negative option");
     if (opts && opts->max_shards > 1)
@@ -167,20 +168,20 @@ pk_status pk_plan_create(const pk_table_desc* tables, int32_t n_tables, const pk
         tile0 += pk_.n_tiles;
     }
     pl->n_tiles_total = (int32_t)tile0;
-    // tables with their fields, and the (table, chunk) work list of the count kernel
-    for (int32_t t = 0; t < n_tables; ++t) {
-        TableMeta tm{};
-        tm.pack = pl->table_pack[t];
-        tm.key_lo = (uint32_t)pl->table_base[t];
-        tm.rows = (uint32_t)tables[t].rows;
-        tm.field_begin = (int32_t)pl->table_fields.size();
-        for (int32_t f = 0; f < n_fields; ++f)
-            if (fields[f].table == t) pl->table_fields.push_back(f);
-        tm.field_end = (int32_t)pl->table_fields.size();
-        pl->table_meta.push_back(tm);
-        if (tm.field_end == tm.field_begin) continue;          // nobody reads this table
-        const int64_t chunks = (tables[t].rows + kCountCap - 1) / kCountCap;
-        for (int64_t c = 0; c < chunks; ++c) { pl->count_item_table.push_back(t); pl->count_item_chunk.push_back((int32_t)c); }
+    // tables that some field reads, in (pack, first key) order, with their fields
+    for (size_t p = 0; p < pl->packs.size(); ++p) {
+        pl->packs[p].first_stable = (int32_t)pl->sort_tables.size();
+        for (int32_t t : pl->packs[p].tables) {                // ascending table index = ascending first key
+            TableMeta tm{};
+            tm.pack = (int32_t)p;
+            tm.key_lo = (uint32_t)pl->table_base[t];
+            tm.rows = (uint32_t)tables[t].rows;
+            tm.field_begin = (int32_t)pl->table_fields.size();
+            for (int32_t f = 0; f < n_fields; ++f)
+                if (fields[f].table == t) pl->table_fields.push_back(f);
+            tm.field_end = (int32_t)pl->table_fields.size();
+            if (tm.field_end > tm.field_begin) pl->sort_tables.push_back(tm);
+        }
     }
     // slices of every pack's key space for the mark kernel
     for (size_t p = 0; p < pl->packs.size(); ++p) {
