@@ -481,8 +481,9 @@ __device__ __forceinline__ int rank_of_key(const uint4* __restrict__ bm, const i
 // blocks to be resident, so the waits end.
 constexpr int kSortThreads = 1024;
 constexpr int kSortPer = kSortCap / kSortThreads;
+constexpr int kSortUnroll2 = 4;       // occurrences per thread in flight in the placing pass
 
-__global__ void __launch_bounds__(kSortThreads)
+__global__ void __launch_bounds__(kSortThreads, 8)
 pk_sort_kernel(const TableMeta* __restrict__ tmeta, const int32_t* __restrict__ table_fields, int T,
                const PackMeta* __restrict__ pm, PackState* st, int P,
                const int32_t* __restrict__ fb, const int32_t* __restrict__ delta,
@@ -490,7 +491,7 @@ pk_sort_kernel(const TableMeta* __restrict__ tmeta, const int32_t* __restrict__ 
                const int32_t* __restrict__ inverse, const uint32_t* __restrict__ bagref,
                const float* __restrict__ bagscl, int32_t* __restrict__ seg_all, uint32_t* __restrict__ ent_all,
                int ent_mult, int32_t* __restrict__ tile_first, int tp, uint64_t* desc, double* __restrict__ ghot, int dmax,
-               int32_t* __restrict__ arrive, int64_t nnz)
+               int64_t nnz)
 {
     extern __shared__ int32_t s_dyn[];
     int32_t* s_rlo = s_dyn;                  // [T]   first rank of each table inside its pack
@@ -542,7 +543,6 @@ pk_sort_kernel(const TableMeta* __restrict__ tmeta, const int32_t* __restrict__ 
         const bool wide = k.has_mean != 0;             // entries of this pack carry the 1/L scale
         const size_t tbase = (size_t)(start / tp + p);
         int32_t* tf = tile_first + tbase;
-        int32_t* arr = arrive + tbase;
         double* gh = ghot + tbase * dmax;
         __syncthreads();                               // the previous item's LDS is consumed
         for (int i = tid; i < (int)width; i += kSortThreads) s_cnt[i] = 0;
@@ -566,13 +566,11 @@ pk_sort_kernel(const TableMeta* __restrict__ tmeta, const int32_t* __restrict__ 
             }
         }
         __syncthreads();
-        int v[kSortPer];
         int mine = 0;
 #pragma unroll
         for (int j = 0; j < kSortPer; ++j) {
             const int i = tid * kSortPer + j;
-            v[j] = i < (int)width ? s_cnt[i] : 0;
-            mine += v[j];
+            mine += i < (int)width ? s_cnt[i] : 0;
         }
         int n_item;
         const int ex = block_excl_scan<kSortThreads>(mine, &n_item);
@@ -595,14 +593,13 @@ pk_sort_kernel(const TableMeta* __restrict__ tmeta, const int32_t* __restrict__ 
         for (int j = 0; j < kSortPer; ++j) {
             const int i = tid * kSortPer + j;
             if (i < (int)width) {
-                const int len = v[j];
+                const int len = s_cnt[i];
                 seg[c0 + i] = s0;
                 s_cnt[i] = s0;                                 // from here on: the segment's next free position
                 const int t_in = (s0 + tp - 1) / tp;           // tiles whose first position lies in the segment
                 for (int tt = t_in; (int64_t)tt * tp < (int64_t)s0 + len; ++tt) tf[tt] = c0 + i;
                 if (len > kWarmMax && s0 / tp != (s0 + len - 1) / tp) {
                     const int slot = s0 / tp;                  // one such key at most starts in a tile
-                    arr[slot] = 0;
                     for (int d = 0; d < k.dim; ++d) gh[(size_t)slot * k.dim + d] = 0.0;
                 }
                 s0 += len;
@@ -614,17 +611,17 @@ pk_sort_kernel(const TableMeta* __restrict__ tmeta, const int32_t* __restrict__ 
             const int64_t q0 = (int64_t)fb[f] + delta[f], q1 = (int64_t)fb[f + 1] + delta[f];
             if (q0 < 0 || q1 > nnz) continue;
             int64_t q = q0 + tid;
-            for (; q + (kMarkUnroll - 1) * kSortThreads < q1; q += kMarkUnroll * kSortThreads) {
-                uint32_t r[kMarkUnroll], e[kMarkUnroll];
-                float c[kMarkUnroll];
+            for (; q + (kSortUnroll2 - 1) * kSortThreads < q1; q += kSortUnroll2 * kSortThreads) {
+                uint32_t r[kSortUnroll2], e[kSortUnroll2];
+                float c[kSortUnroll2];
 #pragma unroll
-                for (int j = 0; j < kMarkUnroll; ++j) {
+                for (int j = 0; j < kSortUnroll2; ++j) {
                     r[j] = (uint32_t)(inverse[q + j * kSortThreads] - c0);
                     e[j] = bagref[q + j * kSortThreads];
                     c[j] = wide ? bagscl[q + j * kSortThreads] : 1.0f;
                 }
 #pragma unroll
-                for (int j = 0; j < kMarkUnroll; ++j)
+                for (int j = 0; j < kSortUnroll2; ++j)
                     if (r[j] < width) {
                         const int pos = atomicAdd(&s_cnt[r[j]], 1);
                         if ((unsigned)pos < (unsigned)n) {
@@ -809,13 +806,12 @@ pk_pool_kernel(const WT* __restrict__ W, const uint32_t* __restrict__ keys_all, 
 // heavily skewed (Sec. II-B): a block takes a tile of consecutive positions of
 // the key-sorted occurrence list and handles the keys that start there.
 //   up to kColdMax occurrences: one lane group per key;
-//   up to kWarmMax:             one wavefront per key, groups stride over it;
-//   more:                       the whole block reduces the tile's piece of the key.  A
-//                               key that lies inside one tile is then updated directly;
-//                               one that crosses tile boundaries has a row of partial
-//                               sums (indexed by the tile it starts in) to which every
-//                               tile adds its piece with double atomics, and the tile
-//                               that arrives last applies the update.
+//   up to kWarmMax, or inside
+//   one tile:                   one wavefront per key, groups stride over it;
+//   longer, across tiles:       the whole block reduces the tile's piece of the key and
+//                               adds it with double atomics to the key's row of partial
+//                               sums (indexed by the tile the key starts in);
+//                               pk_adagrad_hot_kernel then applies the update.
 // ---------------------------------------------------------------------------
 // The gradient chunks of a tile's occurrences: element offsets into grad_out and
 // mean-pooling scales, decoded once per tile, in parallel, into LDS.
@@ -926,7 +922,7 @@ template <typename WT, int VEC, int LPR, int NCH>
 __global__ void __launch_bounds__(NT)
 pk_adagrad_kernel(WT* W, float* A, const PackState* __restrict__ st, int p,
                   const uint32_t* __restrict__ unique_all, const int32_t* __restrict__ seg_all,
-                  double* ghot_all, int dmax, int32_t* arrive_all, const int32_t* __restrict__ tile_first, int tp,
+                  double* ghot_all, int dmax, const int32_t* __restrict__ tile_first, int tp,
                   const uint32_t* __restrict__ seg_ent_all, int ent_mult, int has_mean,
                   const float* __restrict__ grad, int64_t gstride, int64_t out_dim, uint32_t addr_max, int D,
                   float lr, float eps)
@@ -948,7 +944,6 @@ pk_adagrad_kernel(WT* W, float* A, const PackState* __restrict__ st, int p,
     const uint32_t* uq = unique_all + start;
     const size_t tbase = (size_t)(start / tp + p);
     double* gh = ghot_all + tbase * dmax;
-    int32_t* arr = arrive_all + tbase;
     const int32_t* tf = tile_first + tbase;
     const uint32_t* ent = seg_ent_all + (size_t)start * ent_mult;
     GradSrc g{grad, s_addr, s_scl, 0};
@@ -995,7 +990,7 @@ pk_adagrad_kernel(WT* W, float* A, const PackState* __restrict__ st, int p,
         if (threadIdx.x == 0) { s_nwarm = 0; s_nhot = 0; }
         g.t0 = t0;
         __syncthreads();
-        // cold keys that start here are finished on the spot
+        // cold keys that start here are finished on the spot; the others are listed
         for (int k = gi; k < nseg; k += GPB) {
             const int s0 = s_seg[k], s1 = s_seg[k + 1];
             const int len = s1 - s0;
@@ -1012,7 +1007,7 @@ pk_adagrad_kernel(WT* W, float* A, const PackState* __restrict__ st, int p,
                     accum_range<VEC, LPR, NCH>(acc, g, D, li, s0, s1, 1);
                     row_step<WT, VEC, LPR, NCH>(W, A, row, D, li, acc, w, a, lr, eps);
                 }
-            } else if (len <= kWarmMax) {
+            } else if (len <= kWarmMax || (s0 >= t0 && s1 <= t1)) {   // fits the decoded window
                 if (s0 >= t0 && li == 0) s_warm[atomicAdd(&s_nwarm, 1)] = k;
             } else if (li == 0) {
                 s_hot[atomicAdd(&s_nhot, 1)] = k;
@@ -1036,7 +1031,9 @@ pk_adagrad_kernel(WT* W, float* A, const PackState* __restrict__ st, int p,
             wave_group_sum<VEC, LPR, NCH>(acc);
             if (gw == 0) row_step<WT, VEC, LPR, NCH>(W, A, row, D, li, acc, w, a, lr, eps);
         }
-        // long keys: the tile's piece is split over the block's wavefronts and reduced in LDS
+        // long keys that cross tile boundaries: the tile's piece is split over the block's
+        // wavefronts, reduced in LDS and added to the key's partial sums;
+        // pk_adagrad_hot_kernel finishes those keys.
         const int n_hot_here = s_nhot;
         for (int i = 0; i < n_hot_here; ++i) {
             const int k = s_hot[i];
@@ -1069,10 +1066,8 @@ pk_adagrad_kernel(WT* W, float* A, const PackState* __restrict__ st, int p,
                         for (int w2 = 0; w2 < NT / 64; ++w2) t += s_red[w2][li][c][v];
                         acc[c][v] = t;
                     }
-                bool apply = s0 >= t0 && s1 <= t1;             // the key lies inside this tile
-                if (!apply) {
-                    const int slot = s0 / tp;                  // the tile the key starts in
-                    double* prow = gh + (size_t)slot * D;      // the key's row of partial sums
+                {
+                    double* prow = gh + (size_t)(s0 / tp) * D; // partial sums, indexed by the tile the key starts in
 #pragma unroll
                     for (int c = 0; c < NCH; ++c) {
                         const int d0 = (c * LPR + li) * VEC;
@@ -1081,33 +1076,53 @@ pk_adagrad_kernel(WT* W, float* A, const PackState* __restrict__ st, int p,
                             for (int v = 0; v < VEC; ++v) atomicAdd(prow + d0 + v, acc[c][v]);
                         }
                     }
-                    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
-                    int last = 0;
-                    if (li == 0) {
-                        const int pieces = (s1 - 1) / tp - slot + 1;
-                        last = __hip_atomic_fetch_add(arr + slot, 1, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT) == pieces - 1;
-                    }
-                    last = __shfl(last, 0, 64);                // lane 0 of wavefront 0 is this group's lane 0
-                    if (last) {
-                        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
-#pragma unroll
-                        for (int c = 0; c < NCH; ++c) {
-                            const int d0 = (c * LPR + li) * VEC;
-                            if (d0 < D) {
-#pragma unroll
-                                for (int v = 0; v < VEC; ++v)
-                                    acc[c][v] = __hip_atomic_load(prow + d0 + v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                            }
-                        }
-                        apply = true;
-                    }
                 }
-                if (apply) {
-                    const size_t row = s_row[k];
-                    float w[NCH][VEC], a[NCH][VEC];
-                    row_load<WT, VEC, LPR, NCH>(W, A, row, D, li, w, a);
-                    row_step<WT, VEC, LPR, NCH>(W, A, row, D, li, acc, w, a, lr, eps);
-                }
+            }
+        }
+    }
+}
+
+// Keys that are long and cross tile boundaries: their partial sums are complete
+// once pk_adagrad_kernel has ended; apply the update.  One wavefront per tile
+// looks at the key that runs out of the tile's end and takes it if it starts in
+// this tile (so every such key is taken exactly once).  All packs in one launch;
+// there are few such keys, so a row is handled one element per lane.
+struct HotPacks {
+    void* W[16];
+    float* A[16];
+};
+
+__global__ void __launch_bounds__(NT)
+pk_adagrad_hot_kernel(HotPacks ptrs, int p0, const PackMeta* __restrict__ pm, const PackState* __restrict__ st,
+                      const uint32_t* __restrict__ unique_all, const int32_t* __restrict__ seg_all,
+                      const double* __restrict__ ghot_all, int dmax, const int32_t* __restrict__ tile_first, int tp,
+                      float lr, float eps)
+{
+    const int p = p0 + blockIdx.y;
+    const PackMeta k = pm[p];
+    const int n = st[p].nnz, start = st[p].start, D = k.dim;
+    const int32_t* seg = seg_all + start + p;
+    const size_t tbase = (size_t)(start / tp + p);
+    const double* gh = ghot_all + tbase * dmax;
+    const int32_t* tf = tile_first + tbase;
+    const int n_tiles = (n + tp - 1) / tp;
+    const int lane = threadIdx.x & 63;
+    for (int t = blockIdx.x * (NT / 64) + (threadIdx.x >> 6); t + 1 < n_tiles; t += gridDim.x * (NT / 64)) {
+        const int u = tf[t + 1];                               // the key that holds the next tile's first position
+        const int s0 = seg[u], s1 = seg[u + 1];
+        if (s0 < t * tp || s0 >= (t + 1) * tp || s1 - s0 <= kWarmMax) continue;
+        const size_t row = unique_all[start + u];
+        float* A = ptrs.A[blockIdx.y];
+        for (int d = lane; d < D; d += 64) {
+            const float g = (float)gh[(size_t)t * D + d];
+            const float a = A[row * D + d] + g * g;
+            A[row * D + d] = a;
+            if (k.dtype == PK_F32) {
+                float* W = static_cast<float*>(ptrs.W[blockIdx.y]);
+                W[row * D + d] = W[row * D + d] - lr * g / (sqrtf(a) + eps);
+            } else {
+                uint16_t* W = static_cast<uint16_t*>(ptrs.W[blockIdx.y]);
+                W[row * D + d] = (uint16_t)f32_to_bf16(bf16_to_f32(W[row * D + d]) - lr * g / (sqrtf(a) + eps));
             }
         }
     }
@@ -1321,7 +1336,7 @@ struct PoolArgs {
 };
 struct AdaArgs {
     void* W; float* A; const PackState* st; int p; const uint32_t* unique; const int32_t* seg;
-    double* ghot; int dmax; int32_t* arrive; const int32_t* tile_first; int tp; const uint32_t* seg_ent; int ent_mult;
+    double* ghot; int dmax; const int32_t* tile_first; int tp; const uint32_t* seg_ent; int ent_mult;
     int has_mean; const float* grad; int64_t gstride; int64_t out_dim; uint32_t addr_max; int D;
     float lr; float eps; int64_t nnz_bound; bool aligned;
 };
@@ -1342,7 +1357,7 @@ pk_status launch_adagrad(DeviceState* ds, hipStream_t stream, const AdaArgs& a)
 {
     const unsigned grid = (blocks_for(a.nnz_bound, a.tp, 256 * 16) + 7u) & ~7u;
     PK_LAUNCH("pk_adagrad", (pk_adagrad_kernel<WT, VEC, LPR, NCH>), dim3(grid), dim3(NT), 0,
-              static_cast<WT*>(a.W), a.A, a.st, a.p, a.unique, a.seg, a.ghot, a.dmax, a.arrive, a.tile_first,
+              static_cast<WT*>(a.W), a.A, a.st, a.p, a.unique, a.seg, a.ghot, a.dmax, a.tile_first,
               a.tp, a.seg_ent, a.ent_mult, a.has_mean, a.grad, a.gstride, a.out_dim, a.addr_max, a.D, a.lr, a.eps);
     return PK_OK;
 }
@@ -1425,7 +1440,6 @@ pk_status pk_forward(const pk_plan* plan, void* const* W, const int64_t* ids, co
     uint32_t* unique = ws.at<uint32_t>(L.unique);
     int32_t* seg = ws.at<int32_t>(L.seg);
     double* ghot = ws.at<double>(L.ghot);
-    int32_t* arrive = ws.at<int32_t>(L.arrive);
     uint32_t* bitmap = ws.at<uint32_t>(L.bitmap);
     uint64_t* tile_desc = ws.at<uint64_t>(L.tile_desc);
     uint64_t* sort_desc = ws.at<uint64_t>(L.sort_desc);
@@ -1478,12 +1492,15 @@ pk_status pk_forward(const pk_plan* plan, void* const* W, const int64_t* ids, co
         PK_LAUNCH("pk_inverse", pk_inverse_kernel<1024>, dim3(xq, P), dim3(NT), 0, ds->pmeta, st, keys,
                   reinterpret_cast<const uint4*>(bitmap), rank, inverse);
     if (T > 0) {
-        // at most nnz / kSortCap + T work items exist; one block per CU keeps every block resident
-        const unsigned sgrid = (unsigned)std::max<int64_t>(P, std::min<int64_t>(nnz / kSortCap + T, 256));
-        PK_LAUNCH("pk_sort", pk_sort_kernel, dim3(sgrid), dim3(kSortThreads), (size_t)(3 * T + 1) * 4,
+        // at most nnz / kSortCap + T work items exist; the grid is kept small enough for every
+        // block to be resident (two per CU when their LDS fits)
+        const size_t sort_lds = (size_t)(3 * T + 1) * 4;
+        const int64_t resident = 2 * (kSortCap * 4 + 256 + sort_lds) <= 160 * 1024 ? 512 : 256;
+        const unsigned sgrid = (unsigned)std::max<int64_t>(P, std::min<int64_t>(nnz / kSortCap + T, resident));
+        PK_LAUNCH("pk_sort", pk_sort_kernel, dim3(sgrid), dim3(kSortThreads), sort_lds,
                   ds->sort_tables, ds->table_fields, T, ds->pmeta, st, P, fb, delta,
                   reinterpret_cast<const uint4*>(bitmap), rank, inverse, bagref, bagscl, seg, seg_ent,
-                  plan->any_mean ? 2 : 1, tile_first, L.pos_tile, sort_desc, ghot, L.dmax, arrive, nnz);
+                  plan->any_mean ? 2 : 1, tile_first, L.pos_tile, sort_desc, ghot, L.dmax, nnz);
     }
     if (n_side) { rc = join_streams(ds, stream, n_side); if (rc != PK_OK) return rc; }
     return PK_OK;
@@ -1517,7 +1534,7 @@ pk_status pk_backward_update(const pk_plan* plan, void* const* W, float* const* 
         hipStream_t ps = n_side ? ds->side[p % n_side] : stream;
         if (k.fields.empty()) continue;
         AdaArgs a{W[p], A[p], st + p, p, ws.at<uint32_t>(L.unique), ws.at<int32_t>(L.seg), ws.at<double>(L.ghot),
-                  L.dmax, ws.at<int32_t>(L.arrive), ws.at<int32_t>(L.tile_first), L.pos_tile,
+                  L.dmax, ws.at<int32_t>(L.tile_first), L.pos_tile,
                   ws.at<uint32_t>(L.seg_ent), plan->any_mean ? 2 : 1, k.has_mean ? 1 : 0, grad_out, grad_row_stride,
                   plan->out_dim, (uint32_t)((int64_t)(B - 1) * grad_row_stride + plan->out_dim - k.dim), k.dim, lr,
                   eps, nnz,
@@ -1528,6 +1545,16 @@ pk_status pk_backward_update(const pk_plan* plan, void* const* W, float* const* 
         if (rc != PK_OK) return rc;
     }
     if (n_side) { rc = join_streams(ds, stream, n_side); if (rc != PK_OK) return rc; }
+    // long keys that cross tile boundaries, all packs at once
+    const unsigned hgrid = blocks_for(nnz / L.pos_tile + 1, NT / 64, 1024);
+    for (int p0 = 0; p0 < P; p0 += 16) {
+        HotPacks hp{};
+        const int np = std::min(16, P - p0);
+        for (int i = 0; i < np; ++i) { hp.W[i] = W[p0 + i]; hp.A[i] = A[p0 + i]; }
+        PK_LAUNCH("pk_adagrad_hot", pk_adagrad_hot_kernel, dim3(hgrid, np), dim3(NT), 0, hp, p0, ds->pmeta, st,
+                  ws.at<uint32_t>(L.unique), ws.at<int32_t>(L.seg), ws.at<double>(L.ghot), L.dmax,
+                  ws.at<int32_t>(L.tile_first), L.pos_tile, lr, eps);
+    }
     return PK_OK;
 }
 

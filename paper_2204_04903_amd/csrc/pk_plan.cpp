@@ -61,7 +61,6 @@ Layout make_layout(const pk_plan* plan, int32_t B, int64_t nnz)
     L.seg            = take((n + P + 1) * 4);
     L.dmax           = plan->dmax;
     L.ghot           = take(tile_cap * (size_t)plan->dmax * 8);
-    L.arrive         = take(tile_cap * 4);
     L.n_tiles_total  = plan->n_tiles_total;
     L.bitmap         = take((size_t)plan->n_tiles_total * kTileWords * 4);
     L.tile_desc      = take((size_t)plan->n_tiles_total * 8);
