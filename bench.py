@@ -51,6 +51,21 @@ def step_model_bytes(info):
             + 8 * n + 8 * U)
 
 
+def measured_traffic(kernel, workload):
+    """HBM bytes per launch of `kernel` as rocprofv3's FETCH_SIZE / WRITE_SIZE counters measured them on this
+    workload (two --pmc runs of this script, scaled by what the same counters read for a plain 1 GiB copy);
+    the summary under profiles/ holds the figure and the commands.  None when no summary is there."""
+    path = os.path.join(ROOT, "profiles", f"{kernel}_{workload}_hbm_traffic.txt")
+    try:
+        with open(path) as fh:
+            for line in fh:
+                if line.startswith("traffic_bytes_per_launch"):
+                    return float(line.split("=")[1])
+    except OSError:
+        pass
+    return None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -154,6 +169,7 @@ def main():
     dom = max(kern, key=lambda k: kern[k]["ms_per_step"])
     dk = kern[dom]
     launches = max(1.0, dk["launches_per_step"])
+    traffic = measured_traffic(dom, args.workload)
     roofline = {
         "kernel": dom,
         "bound": "hbm",
@@ -161,7 +177,7 @@ def main():
         "peak": HBM_PEAK_GBPS,
         "unit": "GB/s",
         "frac": (dk["GBps"] / HBM_PEAK_GBPS) if "GBps" in dk else None,
-        "traffic": None,
+        "traffic": traffic,
         "alg_bytes_per_launch": dk.get("alg_bytes_per_step", 0) / launches,
         "avg_launch_ms": dk["ms_per_step"] / launches,
     }

@@ -22,7 +22,7 @@
  *   - All functions return a pk_status (0 = success) and never throw;
  *     pk_last_error() gives a thread-local message for the last failure.
  *   - Limits: total rows of a pack < 2^32; dim <= 256; nnz < 2^31;
- *     B * out_dim < 2^32.
+ *     B * out_dim < 2^32; at most 4096 fields and 4096 tables.
  */
 #ifndef PK_H
 #define PK_H

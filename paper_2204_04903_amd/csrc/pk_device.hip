@@ -30,9 +30,24 @@ using namespace pk;
 // ---------------------------------------------------------------------------
 // device helpers
 // ---------------------------------------------------------------------------
+#ifdef PK_PHASE_TIMING
+__device__ unsigned long long pk_dbg[32];
+#define PK_TICK(i, t0) do { if (threadIdx.x == 0) { unsigned long long t1_ = wall_clock64(); atomicAdd(&pk_dbg[i], t1_ - t0); t0 = t1_; } } while (0)
+extern "C" void pk_debug_read(unsigned long long* out) { (void)hipDeviceSynchronize(); (void)hipMemcpyFromSymbol(out, HIP_SYMBOL(pk_dbg), sizeof(pk_dbg)); unsigned long long z[32] = {}; (void)hipMemcpyToSymbol(HIP_SYMBOL(pk_dbg), z, sizeof(z)); }
+#else
+#define PK_TICK(i, t0) do { } while (0)
+#endif
+
 namespace {
 
 constexpr int NT = 256;   // threads per block of the streaming kernels
+
+#ifndef PK_ADA_WAVES
+#define PK_ADA_WAVES 1    // wavefronts per SIMD the backward kernel is compiled for (register budget)
+#endif
+#ifndef PK_ADA_UNROLL
+#define PK_ADA_UNROLL 4   // gradient chunks a lane group keeps in flight
+#endif
 
 template <int NTHREADS>
 __device__ __forceinline__ int block_excl_scan(int v, int* total)
@@ -501,6 +516,9 @@ pk_sort_kernel(const TableMeta* __restrict__ tmeta, const int32_t* __restrict__ 
     __shared__ uint32_t s_base;
     const int tid = threadIdx.x;
     if (st[0].error) return;
+#ifdef PK_PHASE_TIMING
+    unsigned long long tk = wall_clock64();
+#endif
     int carry = 0;
     for (int base = 0; base < T; base += kSortThreads) {
         const int t = base + tid;
@@ -529,6 +547,7 @@ pk_sort_kernel(const TableMeta* __restrict__ tmeta, const int32_t* __restrict__ 
     }
     __syncthreads();
     const int total = s_first[T];
+    PK_TICK(0, tk);
     for (int item = blockIdx.x; item < total; item += gridDim.x) {
         const int t = upper_bound_i32(s_first, T + 1, item) - 1;
         const TableMeta tm = tmeta[t];
@@ -566,6 +585,7 @@ pk_sort_kernel(const TableMeta* __restrict__ tmeta, const int32_t* __restrict__ 
             }
         }
         __syncthreads();
+        PK_TICK(1, tk);
         int mine = 0;
 #pragma unroll
         for (int j = 0; j < kSortPer; ++j) {
@@ -588,6 +608,7 @@ pk_sort_kernel(const TableMeta* __restrict__ tmeta, const int32_t* __restrict__ 
             }
         }
         __syncthreads();
+        PK_TICK(2, tk);
         int s0 = (int)s_base + ex;
 #pragma unroll
         for (int j = 0; j < kSortPer; ++j) {
@@ -606,6 +627,7 @@ pk_sort_kernel(const TableMeta* __restrict__ tmeta, const int32_t* __restrict__ 
             }
         }
         __syncthreads();
+        PK_TICK(3, tk);
         for (int fi = tm.field_begin; fi < tm.field_end; ++fi) {
             const int f = table_fields[fi];
             const int64_t q0 = (int64_t)fb[f] + delta[f], q1 = (int64_t)fb[f + 1] + delta[f];
@@ -624,7 +646,11 @@ pk_sort_kernel(const TableMeta* __restrict__ tmeta, const int32_t* __restrict__ 
                 for (int j = 0; j < kSortUnroll2; ++j)
                     if (r[j] < width) {
                         const int pos = atomicAdd(&s_cnt[r[j]], 1);
+#ifdef PK_EXP_NOSTORE
+                        if (pos == -12345) {
+#else
                         if ((unsigned)pos < (unsigned)n) {
+#endif
                             if (wide) reinterpret_cast<uint2*>(ent)[pos] = make_uint2(e[j], __float_as_uint(c[j]));
                             else ent[pos] = e[j];
                         }
@@ -641,6 +667,11 @@ pk_sort_kernel(const TableMeta* __restrict__ tmeta, const int32_t* __restrict__ 
                 }
             }
         }
+        __syncthreads();
+        PK_TICK(4, tk);
+#ifdef PK_PHASE_TIMING
+        if (tid == 0) atomicAdd(&pk_dbg[8], 1ull);
+#endif
     }
 }
 
@@ -832,22 +863,26 @@ template <int VEC, int LPR, int NCH>
 __device__ __forceinline__ void accum_range(double (&acc)[NCH][VEC], const GradSrc& g, int D, int li,
                                             int s, int s_end, int step)
 {
-    for (; s + 3 * step < s_end; s += 4 * step) {
-        uint32_t a[4];
-        float c[4];
+    constexpr int UN = PK_ADA_UNROLL;
+    for (; s + (UN - 1) * step < s_end; s += UN * step) {
+        uint32_t a[UN];
+        float c[UN];
 #pragma unroll
-        for (int k = 0; k < 4; ++k) g.fetch(s + k * step, &a[k], &c[k]);
+        for (int k = 0; k < UN; ++k) g.fetch(s + k * step, &a[k], &c[k]);
 #pragma unroll
         for (int ch = 0; ch < NCH; ++ch) {
             const int d0 = (ch * LPR + li) * VEC;
             if (d0 < D) {
-                float x[4][VEC];
+                float x[UN][VEC];
 #pragma unroll
-                for (int k = 0; k < 4; ++k) load_f32<VEC>(g.grad + a[k] + d0, x[k]);
+                for (int k = 0; k < UN; ++k) load_f32<VEC>(g.grad + a[k] + d0, x[k]);
 #pragma unroll
-                for (int v = 0; v < VEC; ++v)
-                    acc[ch][v] += ((double)(c[0] * x[0][v]) + (double)(c[1] * x[1][v])) +
-                                  ((double)(c[2] * x[2][v]) + (double)(c[3] * x[3][v]));
+                for (int v = 0; v < VEC; ++v) {
+                    double t = 0.0;
+#pragma unroll
+                    for (int k = 0; k < UN; ++k) t += (double)(c[k] * x[k][v]);
+                    acc[ch][v] += t;
+                }
             }
         }
     }
@@ -919,7 +954,7 @@ __device__ __forceinline__ void wave_group_sum(double (&acc)[NCH][VEC])
 }
 
 template <typename WT, int VEC, int LPR, int NCH>
-__global__ void __launch_bounds__(NT)
+__global__ void __launch_bounds__(NT, PK_ADA_WAVES)
 pk_adagrad_kernel(WT* W, float* A, const PackState* __restrict__ st, int p,
                   const uint32_t* __restrict__ unique_all, const int32_t* __restrict__ seg_all,
                   double* ghot_all, int dmax, const int32_t* __restrict__ tile_first, int tp,
@@ -948,8 +983,15 @@ pk_adagrad_kernel(WT* W, float* A, const PackState* __restrict__ st, int p,
     const uint32_t* ent = seg_ent_all + (size_t)start * ent_mult;
     GradSrc g{grad, s_addr, s_scl, 0};
     const int n_tiles = (n + tp - 1) / tp;
+#ifdef PK_PHASE_TIMING
+    unsigned long long tk = wall_clock64();
+    if (threadIdx.x == 0) atomicAdd(&pk_dbg[15], 1ull);
+#endif
     for (XcdTiles it(n_tiles); it.valid(); it.next()) {
         const int tile = it.tile;
+#ifdef PK_PHASE_TIMING
+        if (threadIdx.x == 0) atomicAdd(&pk_dbg[14], 1ull);
+#endif
         const int t0 = tile * tp, t1 = min(t0 + tp, n);
         // keys whose segments overlap [t0, t1)
         const int u_lo = tf[tile];
@@ -990,6 +1032,7 @@ pk_adagrad_kernel(WT* W, float* A, const PackState* __restrict__ st, int p,
         if (threadIdx.x == 0) { s_nwarm = 0; s_nhot = 0; }
         g.t0 = t0;
         __syncthreads();
+        PK_TICK(9, tk);
         // cold keys that start here are finished on the spot; the others are listed
         for (int k = gi; k < nseg; k += GPB) {
             const int s0 = s_seg[k], s1 = s_seg[k + 1];
@@ -1014,6 +1057,7 @@ pk_adagrad_kernel(WT* W, float* A, const PackState* __restrict__ st, int p,
             }
         }
         __syncthreads();
+        PK_TICK(10, tk);
         // warm keys that start here: one wavefront each
         const int n_warm = s_nwarm;
         for (int i = wv; i < n_warm; i += NT / 64) {
@@ -1031,6 +1075,10 @@ pk_adagrad_kernel(WT* W, float* A, const PackState* __restrict__ st, int p,
             wave_group_sum<VEC, LPR, NCH>(acc);
             if (gw == 0) row_step<WT, VEC, LPR, NCH>(W, A, row, D, li, acc, w, a, lr, eps);
         }
+#ifdef PK_PHASE_TIMING
+        __syncthreads();
+        PK_TICK(11, tk);
+#endif
         // long keys that cross tile boundaries: the tile's piece is split over the block's
         // wavefronts, reduced in LDS and added to the key's partial sums;
         // pk_adagrad_hot_kernel finishes those keys.
@@ -1079,6 +1127,10 @@ pk_adagrad_kernel(WT* W, float* A, const PackState* __restrict__ st, int p,
                 }
             }
         }
+#ifdef PK_PHASE_TIMING
+        __syncthreads();
+        PK_TICK(12, tk);
+#endif
     }
 }
 
