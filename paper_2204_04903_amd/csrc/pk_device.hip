@@ -495,7 +495,6 @@ __device__ __forceinline__ int rank_of_key(const uint4* __restrict__ bm, const i
 // in earlier rounds or in lower blocks of this round; G is small enough for all
 // blocks to be resident, so the waits end.
 constexpr int kSortThreads = 1024;
-constexpr int kSortPer = kSortCap / kSortThreads;
 constexpr int kSortUnroll2 = 4;       // occurrences per thread in flight in the placing pass
 
 __global__ void __launch_bounds__(kSortThreads, 8)
@@ -512,6 +511,7 @@ pk_sort_kernel(const TableMeta* __restrict__ tmeta, const int32_t* __restrict__ 
     int32_t* s_rlo = s_dyn;                  // [T]   first rank of each table inside its pack
     int32_t* s_u = s_dyn + T;                // [T]   distinct keys of each table
     int32_t* s_first = s_u + T;              // [T+1] first work item of each table
+    int32_t* s_occ = s_first + T + 1;        // [T]   occurrences in the tables before (all packs)
     __shared__ int32_t s_cnt[kSortCap];
     __shared__ uint32_t s_base;
     const int tid = threadIdx.x;
@@ -519,12 +519,16 @@ pk_sort_kernel(const TableMeta* __restrict__ tmeta, const int32_t* __restrict__ 
 #ifdef PK_PHASE_TIMING
     unsigned long long tk = wall_clock64();
 #endif
-    int carry = 0;
+    int carry = 0, carry_occ = 0;
     for (int base = 0; base < T; base += kSortThreads) {
         const int t = base + tid;
-        int chunks = 0;
+        int chunks = 0, occ = 0;
         if (t < T) {
             const TableMeta tm = tmeta[t];
+            for (int fi = tm.field_begin; fi < tm.field_end; ++fi) {
+                const int f = table_fields[fi];
+                occ += fb[f + 1] - fb[f];
+            }
             const PackMeta k = pm[tm.pack];
             const size_t rb = (size_t)k.first_tile * NT;
             const uint64_t key_end = (uint64_t)k.n_tiles * (uint64_t)(kTileWords * 32);
@@ -535,10 +539,12 @@ pk_sort_kernel(const TableMeta* __restrict__ tmeta, const int32_t* __restrict__ 
             s_u[t] = r_hi - r_lo;
             chunks = (r_hi - r_lo + kSortCap - 1) / kSortCap;
         }
-        int tot;
+        int tot, tot_occ;
         const int ex = block_excl_scan<kSortThreads>(chunks, &tot);
-        if (t < T) s_first[t] = carry + ex;
+        const int ex_occ = block_excl_scan<kSortThreads>(occ, &tot_occ);
+        if (t < T) { s_first[t] = carry + ex; s_occ[t] = carry_occ + ex_occ; }
         carry += tot;
+        carry_occ += tot_occ;
     }
     if (tid == 0) s_first[T] = carry;
     if ((int)blockIdx.x < P && tid == 0) {       // the entry after the last segment of the pack
@@ -555,8 +561,10 @@ pk_sort_kernel(const TableMeta* __restrict__ tmeta, const int32_t* __restrict__ 
         const PackMeta k = pm[p];
         const int n = st[p].nnz, start = st[p].start;
         const int c0 = s_rlo[t] + (item - s_first[t]) * kSortCap;
+        const uint32_t occ_before = (uint32_t)(s_occ[t] - s_occ[k.first_stable]);   // in the pack's earlier tables
         const uint32_t width = (uint32_t)min(kSortCap, s_rlo[t] + s_u[t] - c0);
-        const int first_item = s_first[k.first_stable];
+        const int chunk = item - s_first[t];
+        const int first_item = s_first[t];             // the table's first item: its start is known
         int32_t* seg = seg_all + start + p;
         uint32_t* ent = ent_all + (size_t)start * ent_mult;
         const bool wide = k.has_mean != 0;             // entries of this pack carry the 1/L scale
@@ -586,33 +594,34 @@ pk_sort_kernel(const TableMeta* __restrict__ tmeta, const int32_t* __restrict__ 
         }
         __syncthreads();
         PK_TICK(1, tk);
+        const int per = ((int)width + kSortThreads - 1) / kSortThreads;   // consecutive counters per thread
         int mine = 0;
-#pragma unroll
-        for (int j = 0; j < kSortPer; ++j) {
-            const int i = tid * kSortPer + j;
+        for (int j = 0; j < per; ++j) {
+            const int i = tid * per + j;
             mine += i < (int)width ? s_cnt[i] : 0;
         }
         int n_item;
         const int ex = block_excl_scan<kSortThreads>(mine, &n_item);
+        // occurrences before the item: those of the pack's earlier tables (known from the field
+        // boundaries) plus those of the table's earlier items (descriptor look-back inside the table)
         if (tid < 64) {
-            if (item == first_item) {
-                if (tid == 0) { publish_desc(desc + item, make_desc(kDescPfx, (uint32_t)n_item, 0)); s_base = 0; }
+            if (chunk == 0) {
+                if (tid == 0) { publish_desc(desc + item, make_desc(kDescPfx, (uint32_t)n_item, 0)); s_base = occ_before; }
             } else {
                 if (tid == 0) publish_desc(desc + item, make_desc(kDescAgg, (uint32_t)n_item, 0));
                 uint32_t pa, pb;
                 lookback(desc, first_item, item, &pa, &pb, &st[0].error);
                 if (tid == 0) {
                     publish_desc(desc + item, make_desc(kDescPfx, pa + (uint32_t)n_item, 0));
-                    s_base = pa;
+                    s_base = occ_before + pa;
                 }
             }
         }
         __syncthreads();
         PK_TICK(2, tk);
         int s0 = (int)s_base + ex;
-#pragma unroll
-        for (int j = 0; j < kSortPer; ++j) {
-            const int i = tid * kSortPer + j;
+        for (int j = 0; j < per; ++j) {
+            const int i = tid * per + j;
             if (i < (int)width) {
                 const int len = s_cnt[i];
                 seg[c0 + i] = s0;
@@ -1546,7 +1555,7 @@ pk_status pk_forward(const pk_plan* plan, void* const* W, const int64_t* ids, co
     if (T > 0) {
         // at most nnz / kSortCap + T work items exist; the grid is kept small enough for every
         // block to be resident (two per CU when their LDS fits)
-        const size_t sort_lds = (size_t)(3 * T + 1) * 4;
+        const size_t sort_lds = (size_t)(4 * T + 1) * 4;
         const int64_t resident = 2 * (kSortCap * 4 + 256 + sort_lds) <= 160 * 1024 ? 512 : 256;
         const unsigned sgrid = (unsigned)std::max<int64_t>(P, std::min<int64_t>(nnz / kSortCap + T, resident));
         PK_LAUNCH("pk_sort", pk_sort_kernel, dim3(sgrid), dim3(kSortThreads), sort_lds,
