@@ -117,6 +117,75 @@ double orc_calc_vparam(int32_t n_tables, const int32_t *table_pack, const int32_
     return v;
 }
 
+/* ---- Eq. 1 shard split (Sec. III-B) ----------------------------------------
+ * A packed operation whose volume is high is split evenly into shards.  The
+ * paper's example fixes the rule used here: with one operation for the dim-8
+ * tables and uniform data, the dim-32 tables get four shards, i.e. the number
+ * of shards of a pack is its volume relative to the lightest pack's,
+ *   shards(p) = round(V_p / min_q V_q), at least 1, at most max_shards and at
+ *   most the pack's table count;
+ * the pack's tables (in table order) are dealt to its shards in turn, so each
+ * shard holds an equal share of them.  Shards become packs of their own,
+ * ordered by (dim, dtype, shard); tables are stacked per shard in table order.
+ * Packs with zero volume do not set the minimum and are not split.
+ * In: the unsplit plan (n_base packs, base_pack per table).  Out: n_shards per
+ * unsplit pack, and the split plan's table_pack / table_base / pack_* arrays
+ * (room for n_tables packs).  Returns the number of packs after the split. */
+int32_t orc_shard_split(int32_t n_tables, const int64_t *rows, const int32_t *dim, const int32_t *dtype,
+                        int32_t n_base, const int32_t *base_pack, const double *occurrences,
+                        int32_t max_shards, int32_t *n_shards,
+                        int32_t *table_pack, int64_t *table_base,
+                        int32_t *pack_dim, int32_t *pack_dtype, int64_t *pack_rows)
+{
+    double vmin = 0.0;
+    for (int32_t p = 0; p < n_base; ++p) {
+        double v = orc_calc_vparam(n_tables, base_pack, dim, occurrences, p);
+        if (v > 0.0 && (vmin == 0.0 || v < vmin)) vmin = v;
+    }
+    int32_t n_packs = 0;
+    for (int32_t p = 0; p < n_base; ++p) {
+        double v = orc_calc_vparam(n_tables, base_pack, dim, occurrences, p);
+        int32_t n_tab = 0;
+        for (int32_t t = 0; t < n_tables; ++t) if (base_pack[t] == p) ++n_tab;
+        int32_t s = 1;
+        if (vmin > 0.0 && v > 0.0) s = (int32_t)floor(v / vmin + 0.5);
+        if (s > max_shards) s = max_shards;
+        if (s > n_tab) s = n_tab;
+        if (s < 1) s = 1;
+        n_shards[p] = s;
+        int32_t seen = 0;
+        for (int32_t t = 0; t < n_tables; ++t) {
+            if (base_pack[t] != p) continue;
+            int32_t q = n_packs + seen % s;               /* dealt in turn */
+            if (seen < s) { pack_rows[q] = 0; pack_dim[q] = dim[t]; pack_dtype[q] = dtype[t]; }
+            table_pack[t] = q;
+            table_base[t] = pack_rows[q];
+            pack_rows[q] += rows[t];
+            ++seen;
+        }
+        n_packs += s;
+    }
+    return n_packs;
+}
+
+/* Fields follow their tables: slot = rank among the pack's fields in field
+ * order; col(f) = running sum of the dims of the fields before f. */
+void orc_field_slots(int32_t n_fields, const int32_t *field_table, const int32_t *table_pack, const int32_t *dim,
+                     int32_t *field_pack, int32_t *field_slot, int64_t *field_col)
+{
+    int64_t col = 0;
+    for (int32_t f = 0; f < n_fields; ++f) {
+        int32_t p = table_pack[field_table[f]];
+        int32_t slot = 0;
+        for (int32_t g = 0; g < f; ++g)
+            if (table_pack[field_table[g]] == p) ++slot;
+        field_pack[f] = p;
+        field_slot[f] = slot;
+        field_col[f] = col;
+        col += dim[field_table[f]];
+    }
+}
+
 /* ---- H1: packed ID tensor + hash (Sec. III-B D-Packing; Fig. 2 "hashing") ----
  * Bags are field-major in the input: bag g = f*B + b owns ids[offsets[g] ..
  * offsets[g+1]).  The pack's tensor lists, slot by slot and sample by sample,

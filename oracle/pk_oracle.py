@@ -40,6 +40,8 @@ def lib():
         _lib.orc_pack_keys.restype = ctypes.c_int64
         _lib.orc_unique.restype = ctypes.c_int32
         _lib.orc_calc_vparam.restype = ctypes.c_double
+        _lib.orc_shard_split.restype = ctypes.c_int32
+        _lib.orc_field_slots.restype = None
         _lib.orc_bf16_round.restype = ctypes.c_uint16
         _lib.orc_bf16_round.argtypes = [ctypes.c_float]
         _lib.orc_bf16_widen.restype = ctypes.c_float
@@ -78,14 +80,17 @@ class Plan:
     field_slot: np.ndarray
     field_col: np.ndarray
     pack_fields: List[np.ndarray]   # per pack: field indices in slot order
+    shards: Optional[np.ndarray] = None   # Eq. 1 split: shards per unsplit pack (None = no split asked for)
 
     @property
     def out_dim(self) -> int:
         return int(self.dim[self.field_table].sum())
 
 
-def plan(tables: Sequence[Tuple[int, int, int]], fields: Sequence[Tuple[int, int]]) -> Plan:
-    """tables: (rows, dim, dtype) each; fields: (table, pool) each."""
+def plan(tables: Sequence[Tuple[int, int, int]], fields: Sequence[Tuple[int, int]],
+         max_shards: int = 0, field_volume: Optional[Sequence[float]] = None) -> Plan:
+    """tables: (rows, dim, dtype) each; fields: (table, pool) each.  max_shards > 1 applies the Eq. 1 shard
+    split; field_volume = occurrences per field from warm-up statistics (uniform when None)."""
     rows = _c([t[0] for t in tables], np.int64)
     dim = _c([t[1] for t in tables], np.int32)
     dtype = _c([t[2] for t in tables], np.int32)
@@ -98,14 +103,28 @@ def plan(tables: Sequence[Tuple[int, int, int]], fields: Sequence[Tuple[int, int
     n_packs = lib().orc_plan(i32(nt), _p(rows), _p(dim), _p(dtype), i32(nf), _p(ft),
                              _p(table_pack), _p(table_base), _p(pack_dim), _p(pack_dtype), _p(pack_rows),
                              _p(field_pack), _p(field_slot), _p(field_col))
+    shards = None
+    if max_shards > 1:
+        vol = np.ones(nf, np.float64) if field_volume is None else _c(field_volume, np.float64)
+        occ = np.zeros(nt, np.float64)
+        for f in range(nf):
+            occ[ft[f]] += vol[f]
+        base_pack = table_pack.copy()
+        shards = np.zeros(n_packs, np.int32)
+        n_packs = lib().orc_shard_split(i32(nt), _p(rows), _p(dim), _p(dtype), i32(n_packs), _p(base_pack), _p(occ),
+                                        i32(max_shards), _p(shards), _p(table_pack), _p(table_base),
+                                        _p(pack_dim), _p(pack_dtype), _p(pack_rows))
+        lib().orc_field_slots(i32(nf), _p(ft), _p(table_pack), _p(dim), _p(field_pack), _p(field_slot), _p(field_col))
     pack_fields = []
     for p in range(n_packs):
         fs = np.nonzero(field_pack == p)[0].astype(np.int32)
         assert (field_slot[fs] == np.arange(len(fs))).all()
         pack_fields.append(np.ascontiguousarray(fs))
-    return Plan(rows, dim, dtype, ft, pool, n_packs, table_pack, table_base, pack_dim[:n_packs].copy(),
-                pack_dtype[:n_packs].copy(), pack_rows[:n_packs].copy(), field_pack, field_slot, field_col,
-                pack_fields)
+    pl = Plan(rows, dim, dtype, ft, pool, n_packs, table_pack, table_base, pack_dim[:n_packs].copy(),
+              pack_dtype[:n_packs].copy(), pack_rows[:n_packs].copy(), field_pack, field_slot, field_col,
+              pack_fields)
+    pl.shards = shards
+    return pl
 
 
 def calc_vparam(pl: Plan, occurrences: Sequence[float], pack: int) -> float:

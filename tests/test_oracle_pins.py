@@ -72,6 +72,70 @@ def test_eq1_volume_ratio_of_the_worked_example():
     assert v1 / v0 == ratio
 
 
+def test_eq1_shard_split_reproduces_the_worked_example():
+    # Sec. III-B after Eq. 1: uniform data, one packed operation for the dim-8 tables ->
+    # the dim-32 tables get four shards, each holding a quarter of them.
+    (d_small, d_large, ratio), = [(int(a), int(b), float(c)) for a, b, c in _read_golden("eq1_example.txt")]
+    n = 8
+    tables = [(1000 + t, d_small, 0) for t in range(n)] + [(2000 + t, d_large, 0) for t in range(n)]
+    fields = [(t, 0) for t in range(2 * n)]
+    pl = orc.plan(tables, fields, max_shards=8)                       # uniform volumes
+    assert list(pl.shards) == [1, int(ratio)]
+    assert pl.n_packs == 1 + int(ratio)
+    assert list(pl.pack_dim) == [d_small] + [d_large] * int(ratio)
+    per_shard = [int((pl.table_pack[n:] == 1 + s).sum()) for s in range(int(ratio))]
+    assert per_shard == [n // int(ratio)] * int(ratio)                # a quarter of the tables each
+    assert list(pl.table_pack[:n]) == [0] * n
+
+
+def test_eq1_shard_split_rule_against_plain_python():
+    # the same rule written out in Python on an irregular problem: volumes from per-field
+    # statistics, rounding, both caps, tables dealt in turn, stacking per shard
+    rng = np.random.default_rng(5)
+    dims = [4, 4, 16, 16, 16, 16, 16, 8, 8, 8, 64]
+    tables = [(int(rng.integers(5, 50)), d, 0) for d in dims]
+    fields = [(t, 0) for t in range(len(tables))] + [(2, 1), (10, 0)]
+    vol = [float(v) for v in rng.integers(1, 100, size=len(fields))]
+    for max_shards in (2, 3, 16):
+        pl = orc.plan(tables, fields, max_shards=max_shards, field_volume=vol)
+        occ = [0.0] * len(tables)
+        for f, (t, _) in enumerate(fields):
+            occ[t] += vol[f]
+        base = sorted(set(dims))
+        V = {d: sum(d * occ[t] for t in range(len(tables)) if dims[t] == d) for d in base}
+        vmin = min(V.values())
+        exp_pack, exp_base, exp_rows, q0 = {}, {}, [], 0
+        exp_shards = []
+        for d in base:
+            ts = [t for t in range(len(tables)) if dims[t] == d]
+            s = max(1, min(int(np.floor(V[d] / vmin + 0.5)), max_shards, len(ts)))
+            exp_shards.append(s)
+            rows_acc = [0] * s
+            for i, t in enumerate(ts):
+                exp_pack[t] = q0 + i % s
+                exp_base[t] = rows_acc[i % s]
+                rows_acc[i % s] += tables[t][0]
+            exp_rows += rows_acc
+            q0 += s
+        assert list(pl.shards) == exp_shards
+        assert pl.n_packs == q0
+        assert [int(x) for x in pl.table_pack] == [exp_pack[t] for t in range(len(tables))]
+        assert [int(x) for x in pl.table_base] == [exp_base[t] for t in range(len(tables))]
+        assert [int(x) for x in pl.pack_rows] == exp_rows
+        # fields follow their tables; slots count the pack's fields in field order
+        for f, (t, _) in enumerate(fields):
+            assert pl.field_pack[f] == exp_pack[t]
+            assert pl.field_slot[f] == sum(1 for g in range(f) if exp_pack[fields[g][0]] == exp_pack[t])
+    # a split changes where rows live, not what the layer computes
+    pr = small_problem(31, B=5, tables=tables, fields=fields, max_len=3)
+    outs = []
+    for ms in (0, 16):
+        pl = orc.plan(tables, fields, max_shards=ms, field_volume=vol)
+        out, _ = orc.forward(pl, stack_tables(pl, pr["Wt"]), pr["B"], pr["ids"], pr["offsets"])
+        outs.append(out)
+    assert np.array_equal(outs[0], outs[1])
+
+
 # --------------------------------------------------------------------------- keys
 def test_keys_match_python_bigint_arithmetic_on_wild_ids():
     pr = small_problem(3, B=9, wild_ids=True)
