@@ -66,6 +66,14 @@ typedef struct pk_plan pk_plan;   /* opaque, host memory, owned by the library *
 
 /* ---- plan (Sec. III-B: pack fields whose tables share the dimension) --------
  * Packs are the distinct (dim, dtype) pairs in ascending (dim, dtype) order.
+ * With opts->max_shards > 1 the heavy ones are split (Sec. III-B, Eq. 1): the
+ * volume of a pack is the number of floats it gathers, sum over its tables of
+ * dim x occurrences (occurrences of a table = sum of field_volume over the
+ * fields that read it; every field counts 1 when field_volume is NULL); a pack
+ * gets round(volume / smallest non-zero volume) shards, at most max_shards and
+ * at most one per table, and its tables are dealt to the shards in turn (the
+ * paper's example: one operation for dim 8, four shards for dim 32).  Shards
+ * are packs of their own, ordered (dim, dtype, shard).
  * Inside a pack the tables are stacked in table-index order into ONE caller
  * buffer [total_rows, dim]; pk_plan_table_slot tells where each table starts.
  * Fields of a pack are numbered (slots) in field-index order.  The pooled

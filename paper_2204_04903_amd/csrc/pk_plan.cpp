@@ -9,6 +9,7 @@
 #include "pk_internal.h"
 
 #include <algorithm>
+#include <cmath>
 #include <cstdlib>
 #include <new>
 
@@ -104,8 +105,10 @@ pk_status pk_plan_create(const pk_table_desc* tables, int32_t n_tables, const pk
         return fail(PK_EOVERFLOW, "pk_plan_create: at most 4096 fields and 4096 tables (their metadata is staged in LDS)");
     if (opts && (opts->max_batch < 0 || opts->max_nnz < 0 || opts->max_shards < 0))
         return fail(PK_EINVAL, "pk_plan_create: negative option");
-    if (opts && opts->max_shards > 1)
-        return fail(PK_EINVAL, "pk_plan_create: the Eq. 1 shard split is not available (max_shards must be 0 or 1)");
+    if (opts && opts->field_volume)
+        for (int32_t f = 0; f < n_fields; ++f)
+            if (!(opts->field_volume[f] >= 0.0))
+                return fail(PK_EINVAL, "pk_plan_create: field_volume[" + std::to_string(f) + "] is negative or not a number");
 
     pk_plan* pl = new (std::nothrow) pk_plan();
     if (!pl) return fail(PK_ENOMEM, "pk_plan_create: out of host memory");
@@ -119,18 +122,45 @@ pk_status pk_plan_create(const pk_table_desc* tables, int32_t n_tables, const pk
     for (auto& t : pl->tables) keys.emplace_back(t.dim, t.dtype);
     std::sort(keys.begin(), keys.end());
     keys.erase(std::unique(keys.begin(), keys.end()), keys.end());
-    pl->packs.resize(keys.size());
-    for (size_t p = 0; p < keys.size(); ++p) { pl->packs[p].dim = keys[p].first; pl->packs[p].dtype = keys[p].second; }
-
-    pl->table_pack.resize(n_tables);
-    pl->table_base.resize(n_tables);
+    std::vector<std::vector<int32_t>> group(keys.size());            // tables per pair, ascending table index
     for (int32_t t = 0; t < n_tables; ++t) {
         auto it = std::lower_bound(keys.begin(), keys.end(), std::make_pair(tables[t].dim, tables[t].dtype));
-        int32_t p = (int32_t)(it - keys.begin());
-        pl->table_pack[t] = p;
-        pl->table_base[t] = pl->packs[p].rows;
-        pl->packs[p].rows += tables[t].rows;
-        pl->packs[p].tables.push_back(t);
+        group[it - keys.begin()].push_back(t);
+    }
+    // Eq. 1 (Sec. III-B): volume of a packed operation = floats it gathers = sum over its
+    // tables of dim x occurrences.  A pack is split into round(volume / smallest volume)
+    // shards (the paper's example: dim 8 -> one operation, dim 32 -> four), at most
+    // max_shards and at most one per table; its tables are dealt to the shards in turn.
+    std::vector<int32_t> n_shards(keys.size(), 1);
+    if (opts && opts->max_shards > 1) {
+        std::vector<double> occ(n_tables, 0.0), vol(keys.size(), 0.0);
+        for (int32_t f = 0; f < n_fields; ++f) occ[fields[f].table] += opts->field_volume ? opts->field_volume[f] : 1.0;
+        double vmin = 0.0;
+        for (size_t g = 0; g < keys.size(); ++g) {
+            for (int32_t t : group[g]) vol[g] += (double)tables[t].dim * occ[t];
+            if (vol[g] > 0.0 && (vmin == 0.0 || vol[g] < vmin)) vmin = vol[g];
+        }
+        for (size_t g = 0; g < keys.size(); ++g) {
+            int64_t s = (vmin > 0.0 && vol[g] > 0.0) ? (int64_t)std::floor(vol[g] / vmin + 0.5) : 1;
+            s = std::min<int64_t>(s, opts->max_shards);
+            s = std::min<int64_t>(s, (int64_t)group[g].size());
+            n_shards[g] = (int32_t)std::max<int64_t>(s, 1);
+        }
+    }
+    pl->table_pack.resize(n_tables);
+    pl->table_base.resize(n_tables);
+    for (size_t g = 0; g < keys.size(); ++g) {
+        const size_t p0 = pl->packs.size();
+        pl->packs.resize(p0 + n_shards[g]);
+        for (int32_t s = 0; s < n_shards[g]; ++s) { pl->packs[p0 + s].dim = keys[g].first; pl->packs[p0 + s].dtype = keys[g].second; }
+        for (size_t i = 0; i < group[g].size(); ++i) {
+            const int32_t t = group[g][i];
+            const int32_t p = (int32_t)(p0 + i % n_shards[g]);
+            pl->table_pack[t] = p;
+            pl->table_base[t] = pl->packs[p].rows;
+            pl->packs[p].rows += tables[t].rows;
+            pl->packs[p].tables.push_back(t);
+        }
     }
     for (auto& pk_ : pl->packs)
         if (pk_.rows >= ((int64_t)1 << 32)) {

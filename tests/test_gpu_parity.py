@@ -42,15 +42,16 @@ def bits_of(t: torch.Tensor):
     return t.cpu().numpy()
 
 
-def run_dense_case(name, tables, fields, steps, lr=0.05, eps=1e-8, out_pad=0, grad_pad=0):
+def run_dense_case(name, tables, fields, steps, lr=0.05, eps=1e-8, out_pad=0, grad_pad=0, **plan_opts):
     """steps: list of dicts from small_problem (ids, offsets, grad, B, Wt of the first one)."""
     from paper_2204_04903_amd.layer import PackedEmbedding
     say(f"[case] {name}: tables={len(tables)} fields={len(fields)} steps={len(steps)}")
-    pl = orc.plan(tables, fields)
+    pl = orc.plan(tables, fields, **plan_opts)
     Wt0 = steps[0]["Wt"]
     W = stack_tables(pl, [w.copy() for w in Wt0])
     A = [np.zeros(w.shape, np.float32) for w in W]
-    layer = PackedEmbedding(tables, fields)
+    layer = PackedEmbedding(tables, fields, **plan_opts)
+    assert layer.n_packs == pl.n_packs
     try:
         for t, w in enumerate(Wt0):
             layer.load_table(t, w)
@@ -100,6 +101,18 @@ def run_dense_case(name, tables, fields, steps, lr=0.05, eps=1e-8, out_pad=0, gr
 def test_small_mixed_packs_shared_tables_two_steps(seed):
     steps = [small_problem(seed * 10 + s, B=37, max_len=6) for s in range(2)]
     run_dense_case("mixed", steps[0]["tables"], steps[0]["fields"], steps)
+
+
+def test_eq1_shard_split_packs_two_steps():
+    # heavy packs split into shards (Sec. III-B, Eq. 1): 1 + 4 + 2 packs instead of 3
+    rng = np.random.default_rng(77)
+    dims = [8] * 4 + [32] * 8 + [16] * 4
+    tables = [(int(rng.integers(20, 200)), d, 0) for d in dims]
+    fields = [(t, t % 2) for t in range(len(tables))] + [(5, 0), (2, 1)]
+    steps = [small_problem(80 + s, B=33, tables=tables, fields=fields, max_len=6) for s in range(2)]
+    run_dense_case("shards", tables, fields, steps, max_shards=4)
+    vol = [float(v) for v in rng.integers(1, 30, len(fields))]
+    run_dense_case("shards+stats", tables, fields, steps, max_shards=3, field_volume=vol)
 
 
 def test_wild_64bit_ids_are_folded():

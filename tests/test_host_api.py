@@ -51,6 +51,29 @@ def test_plan_matches_oracle_plan(idx):
         pk.pk_plan_destroy(plan)
 
 
+def test_sharded_plan_matches_oracle_plan():
+    # Eq. 1 shard split: same packs, table slots and field columns as the oracle's plan
+    rng = np.random.default_rng(9)
+    dims = [8] * 8 + [32] * 8 + [16] * 3
+    tables = [(int(rng.integers(10, 99)), d, 0) for d in dims]
+    fields = [(t, t % 2) for t in range(len(tables))] + [(3, 0), (12, 1)]
+    for kw in (dict(max_shards=8), dict(max_shards=3, field_volume=[float(v) for v in rng.integers(1, 50, len(fields))])):
+        ref = orc.plan(tables, fields, **kw)
+        plan = pk.pk_plan_create(tables, fields, **kw)
+        try:
+            assert pk.pk_plan_num_packs(plan) == ref.n_packs
+            for p in range(ref.n_packs):
+                info = pk.pk_plan_pack_info(plan, p)
+                assert (info["dim"], info["dtype"], info["total_rows"]) == (ref.pack_dim[p], ref.pack_dtype[p], ref.pack_rows[p])
+                assert list(pk.pk_plan_pack_fields(plan, p)) == list(ref.pack_fields[p])
+            for t in range(len(tables)):
+                assert pk.pk_plan_table_slot(plan, t) == (ref.table_pack[t], ref.table_base[t])
+            for f in range(len(fields)):
+                assert pk.pk_plan_field_col(plan, f) == ref.field_col[f]
+        finally:
+            pk.pk_plan_destroy(plan)
+
+
 def test_plan_rejects_bad_arguments():
     def status(fn):
         with pytest.raises(pk.PkError) as e:
