@@ -43,10 +43,16 @@ namespace {
 constexpr int NT = 256;   // threads per block of the streaming kernels
 
 #ifndef PK_ADA_WAVES
-#define PK_ADA_WAVES 1    // wavefronts per SIMD the backward kernel is compiled for (register budget)
+#define PK_ADA_WAVES 6    // wavefronts per SIMD the backward kernel is compiled for (register budget)
+#endif
+#ifndef PK_ADA_WAVES_MEAN
+#define PK_ADA_WAVES_MEAN 6
 #endif
 #ifndef PK_ADA_UNROLL
 #define PK_ADA_UNROLL 4   // gradient chunks a lane group keeps in flight
+#endif
+#ifndef PK_ADA_UNROLL_MEAN
+#define PK_ADA_UNROLL_MEAN 2
 #endif
 
 template <int NTHREADS>
@@ -189,7 +195,7 @@ __global__ void __launch_bounds__(NT)
 pk_keys_kernel(const int64_t* __restrict__ ids, const int32_t* __restrict__ offsets, int B, int F, int P, int64_t nnz,
                const FieldMeta* __restrict__ fmeta, const PackMeta* __restrict__ pm,
                const int32_t* __restrict__ slot_field, PackState* st, int32_t* fb_out, int32_t* delta_out,
-               uint32_t* __restrict__ keys, uint32_t* __restrict__ bagref, float* __restrict__ bagscl,
+               uint32_t* __restrict__ keys, uint32_t* __restrict__ bagref, uint32_t* __restrict__ baglen,
                int32_t* __restrict__ packed_offsets, int64_t out_dim, uint4* clear4, int64_t n_clear4)
 {
     extern __shared__ int32_t s_dyn[];
@@ -200,7 +206,7 @@ pk_keys_kernel(const int64_t* __restrict__ ids, const int32_t* __restrict__ offs
     __shared__ int32_t s_po[BT + 1];
     __shared__ uint32_t s_base[BT], s_rows[BT], s_ref[BT];
     __shared__ int32_t s_dl[BT];
-    __shared__ float s_scl[BT];
+    __shared__ uint32_t s_len[BT];
     const int tid = threadIdx.x;
     {
         const uint4 z = make_uint4(0, 0, 0, 0);
@@ -267,7 +273,7 @@ pk_keys_kernel(const int64_t* __restrict__ ids, const int32_t* __restrict__ offs
             s_dl[t] = s_delta[f];
             s_ref[t] = (uint32_t)((int64_t)b * out_dim + m.col);
             const int L = s_po[t + 1] - s_po[t];
-            s_scl[t] = (m.pool == PK_MEAN && L > 0) ? 1.0f / (float)L : 1.0f;
+            s_len[t] = (m.pool == PK_MEAN && L > 0) ? (uint32_t)L : 1u;     // what the gradient is divided by
             packed_offsets[(int64_t)k.first_slot * B + m.pack + (int64_t)m.slot * B + b] =
                 s_po[t] + s_delta[f] - s_slotpos[k.first_slot];
         }
@@ -290,7 +296,7 @@ pk_keys_kernel(const int64_t* __restrict__ ids, const int32_t* __restrict__ offs
                 if ((uint64_t)q >= (uint64_t)nnz) continue;
                 keys[q] = s_base[t] + fold_id(idv[k], s_rows[t]);
                 bagref[q] = s_ref[t];
-                if (bagscl) bagscl[q] = s_scl[t];
+                if (baglen) baglen[q] = s_len[t];
             }
         }
     }
@@ -503,7 +509,7 @@ pk_sort_kernel(const TableMeta* __restrict__ tmeta, const int32_t* __restrict__ 
                const int32_t* __restrict__ fb, const int32_t* __restrict__ delta,
                const uint4* __restrict__ bitmap4, const int32_t* __restrict__ rank,
                const int32_t* __restrict__ inverse, const uint32_t* __restrict__ bagref,
-               const float* __restrict__ bagscl, int32_t* __restrict__ seg_all, uint32_t* __restrict__ ent_all,
+               const uint32_t* __restrict__ baglen, int32_t* __restrict__ seg_all, uint32_t* __restrict__ ent_all,
                int ent_mult, int32_t* __restrict__ tile_first, int tp, uint64_t* desc, double* __restrict__ ghot, int dmax,
                int64_t nnz)
 {
@@ -644,12 +650,12 @@ pk_sort_kernel(const TableMeta* __restrict__ tmeta, const int32_t* __restrict__ 
             int64_t q = q0 + tid;
             for (; q + (kSortUnroll2 - 1) * kSortThreads < q1; q += kSortUnroll2 * kSortThreads) {
                 uint32_t r[kSortUnroll2], e[kSortUnroll2];
-                float c[kSortUnroll2];
+                uint32_t c[kSortUnroll2];
 #pragma unroll
                 for (int j = 0; j < kSortUnroll2; ++j) {
                     r[j] = (uint32_t)(inverse[q + j * kSortThreads] - c0);
                     e[j] = bagref[q + j * kSortThreads];
-                    c[j] = wide ? bagscl[q + j * kSortThreads] : 1.0f;
+                    c[j] = wide ? baglen[q + j * kSortThreads] : 1u;
                 }
 #pragma unroll
                 for (int j = 0; j < kSortUnroll2; ++j)
@@ -660,7 +666,7 @@ pk_sort_kernel(const TableMeta* __restrict__ tmeta, const int32_t* __restrict__ 
 #else
                         if ((unsigned)pos < (unsigned)n) {
 #endif
-                            if (wide) reinterpret_cast<uint2*>(ent)[pos] = make_uint2(e[j], __float_as_uint(c[j]));
+                            if (wide) reinterpret_cast<uint2*>(ent)[pos] = make_uint2(e[j], c[j]);
                             else ent[pos] = e[j];
                         }
                     }
@@ -670,7 +676,7 @@ pk_sort_kernel(const TableMeta* __restrict__ tmeta, const int32_t* __restrict__ 
                 if (r0 < width) {
                     const int pos = atomicAdd(&s_cnt[r0], 1);
                     if ((unsigned)pos < (unsigned)n) {
-                        if (wide) reinterpret_cast<uint2*>(ent)[pos] = make_uint2(bagref[q], __float_as_uint(bagscl[q]));
+                        if (wide) reinterpret_cast<uint2*>(ent)[pos] = make_uint2(bagref[q], baglen[q]);
                         else ent[pos] = bagref[q];
                     }
                 }
@@ -855,27 +861,29 @@ pk_pool_kernel(const WT* __restrict__ W, const uint32_t* __restrict__ keys_all, 
 // ---------------------------------------------------------------------------
 // The gradient chunks of a tile's occurrences: element offsets into grad_out and
 // mean-pooling scales, decoded once per tile, in parallel, into LDS.
+template <bool MEAN>
 struct GradSrc {
     const float* grad;
     const uint32_t* s_addr;      // LDS: positions [t0, ...)
-    const float* s_scl;
+    const double* s_scl;         // LDS: 1/L per position (packs with mean pooling only)
     int t0;
-    __device__ __forceinline__ void fetch(int s, uint32_t* addr, float* scale) const
+    __device__ __forceinline__ void fetch(int s, uint32_t* addr, double* scale) const
     {
         *addr = s_addr[s - t0];
-        *scale = s_scl[s - t0];
+        *scale = MEAN ? s_scl[s - t0] : 1.0;
     }
 };
 
-// acc += sum over positions s, s+step, ... < s_end of scale * grad chunk
-template <int VEC, int LPR, int NCH>
-__device__ __forceinline__ void accum_range(double (&acc)[NCH][VEC], const GradSrc& g, int D, int li,
+// acc += sum over positions s, s+step, ... < s_end of scale * grad chunk.  Packs with
+// mean pooling carry a double per chunk in flight, so they keep fewer in flight.
+template <int VEC, int LPR, int NCH, bool MEAN>
+__device__ __forceinline__ void accum_range(double (&acc)[NCH][VEC], const GradSrc<MEAN>& g, int D, int li,
                                             int s, int s_end, int step)
 {
-    constexpr int UN = PK_ADA_UNROLL;
+    constexpr int UN = MEAN ? PK_ADA_UNROLL_MEAN : PK_ADA_UNROLL;
     for (; s + (UN - 1) * step < s_end; s += UN * step) {
         uint32_t a[UN];
-        float c[UN];
+        double c[UN];
 #pragma unroll
         for (int k = 0; k < UN; ++k) g.fetch(s + k * step, &a[k], &c[k]);
 #pragma unroll
@@ -889,7 +897,7 @@ __device__ __forceinline__ void accum_range(double (&acc)[NCH][VEC], const GradS
                 for (int v = 0; v < VEC; ++v) {
                     double t = 0.0;
 #pragma unroll
-                    for (int k = 0; k < UN; ++k) t += (double)(c[k] * x[k][v]);
+                    for (int k = 0; k < UN; ++k) t += MEAN ? c[k] * (double)x[k][v] : (double)x[k][v];
                     acc[ch][v] += t;
                 }
             }
@@ -897,7 +905,7 @@ __device__ __forceinline__ void accum_range(double (&acc)[NCH][VEC], const GradS
     }
     for (; s < s_end; s += step) {
         uint32_t a0;
-        float c0;
+        double c0;
         g.fetch(s, &a0, &c0);
 #pragma unroll
         for (int ch = 0; ch < NCH; ++ch) {
@@ -906,7 +914,7 @@ __device__ __forceinline__ void accum_range(double (&acc)[NCH][VEC], const GradS
                 float x0[VEC];
                 load_f32<VEC>(g.grad + a0 + d0, x0);
 #pragma unroll
-                for (int v = 0; v < VEC; ++v) acc[ch][v] += (double)(c0 * x0[v]);
+                for (int v = 0; v < VEC; ++v) acc[ch][v] += MEAN ? c0 * (double)x0[v] : (double)x0[v];
             }
         }
     }
@@ -962,12 +970,12 @@ __device__ __forceinline__ void wave_group_sum(double (&acc)[NCH][VEC])
             for (int v = 0; v < VEC; ++v) acc[c][v] += __shfl_xor(acc[c][v], o, 64);
 }
 
-template <typename WT, int VEC, int LPR, int NCH>
-__global__ void __launch_bounds__(NT, PK_ADA_WAVES)
+template <typename WT, int VEC, int LPR, int NCH, bool MEAN>
+__global__ void __launch_bounds__(NT, VEC > 4 ? 1 : (MEAN ? PK_ADA_WAVES_MEAN : PK_ADA_WAVES))   // 8-wide rows need their registers
 pk_adagrad_kernel(WT* W, float* A, const PackState* __restrict__ st, int p,
                   const uint32_t* __restrict__ unique_all, const int32_t* __restrict__ seg_all,
                   double* ghot_all, int dmax, const int32_t* __restrict__ tile_first, int tp,
-                  const uint32_t* __restrict__ seg_ent_all, int ent_mult, int has_mean,
+                  const uint32_t* __restrict__ seg_ent_all, int ent_mult,
                   const float* __restrict__ grad, int64_t gstride, int64_t out_dim, uint32_t addr_max, int D,
                   float lr, float eps)
 {
@@ -980,7 +988,7 @@ pk_adagrad_kernel(WT* W, float* A, const PackState* __restrict__ st, int p,
     __shared__ int s_seg[kPosTileMax + 2];          // segment offsets of the tile's keys
     __shared__ uint32_t s_row[kPosTileMax + 1];     // their table rows
     __shared__ uint32_t s_addr[kPosTileMax + kWarmMax];   // decoded positions of the tile and its tail
-    __shared__ float s_scl[kPosTileMax + kWarmMax];
+    __shared__ double s_scl[MEAN ? kPosTileMax + kWarmMax : 1];   // 1/L of mean pooling, in double: see the decode below
     const int li = threadIdx.x % LPR, gi = threadIdx.x / LPR;
     const int wv = threadIdx.x >> 6, gw = (threadIdx.x & 63) / LPR;
     const int n = st->nnz, U = st->n_unique, start = st->start;
@@ -990,7 +998,7 @@ pk_adagrad_kernel(WT* W, float* A, const PackState* __restrict__ st, int p,
     double* gh = ghot_all + tbase * dmax;
     const int32_t* tf = tile_first + tbase;
     const uint32_t* ent = seg_ent_all + (size_t)start * ent_mult;
-    GradSrc g{grad, s_addr, s_scl, 0};
+    GradSrc<MEAN> g{grad, s_addr, s_scl, 0};
     const int n_tiles = (n + tp - 1) / tp;
 #ifdef PK_PHASE_TIMING
     unsigned long long tk = wall_clock64();
@@ -1021,12 +1029,16 @@ pk_adagrad_kernel(WT* W, float* A, const PackState* __restrict__ st, int p,
         for (int i = threadIdx.x; i <= nseg; i += NT) s_seg[i] = seg[u_lo + i];
         for (int i = threadIdx.x; i < nseg; i += NT) s_row[i] = uq[u_lo + i];
         for (int i = threadIdx.x; i < w_end - t0; i += NT) {
+            // The 1/L of mean pooling is formed and applied in double.  The first Adagrad step
+            // of a row moves a weight by lr*g/(|g|+eps): where the gradients of a key cancel
+            // (|g| near eps) an error of 1e-8 in g is an error of lr in the weight, and a
+            // float 1/L alone is off by 6e-8 of every term.
             uint32_t a;
-            float c = 1.0f;
-            if (has_mean) {
+            double c = 1.0;
+            if (MEAN) {
                 const uint2 e = reinterpret_cast<const uint2*>(ent)[t0 + i];
                 a = e.x;
-                c = __uint_as_float(e.y);
+                c = 1.0 / (double)max(e.y, 1u);
             } else {
                 a = ent[t0 + i];
             }
@@ -1034,9 +1046,9 @@ pk_adagrad_kernel(WT* W, float* A, const PackState* __restrict__ st, int p,
                 const uint32_t b = a / (uint32_t)out_dim;
                 a = b * (uint32_t)gstride + (a - b * (uint32_t)out_dim);
             }
-            if (a > addr_max) { a = 0; c = 0.0f; }         // never leave grad_out, whatever the list holds
+            if (a > addr_max) { a = 0; c = 0.0; }          // never leave grad_out, whatever the list holds
             s_addr[i] = a;
-            s_scl[i] = c;
+            if (MEAN) s_scl[i] = c;
         }
         if (threadIdx.x == 0) { s_nwarm = 0; s_nhot = 0; }
         g.t0 = t0;
@@ -1056,7 +1068,7 @@ pk_adagrad_kernel(WT* W, float* A, const PackState* __restrict__ st, int p,
                     for (int c = 0; c < NCH; ++c)
 #pragma unroll
                         for (int v = 0; v < VEC; ++v) acc[c][v] = 0.0;
-                    accum_range<VEC, LPR, NCH>(acc, g, D, li, s0, s1, 1);
+                    accum_range<VEC, LPR, NCH, MEAN>(acc, g, D, li, s0, s1, 1);
                     row_step<WT, VEC, LPR, NCH>(W, A, row, D, li, acc, w, a, lr, eps);
                 }
             } else if (len <= kWarmMax || (s0 >= t0 && s1 <= t1)) {   // fits the decoded window
@@ -1080,7 +1092,7 @@ pk_adagrad_kernel(WT* W, float* A, const PackState* __restrict__ st, int p,
             for (int c = 0; c < NCH; ++c)
 #pragma unroll
                 for (int v = 0; v < VEC; ++v) acc[c][v] = 0.0;
-            accum_range<VEC, LPR, NCH>(acc, g, D, li, s0 + gw, s1, GPW);
+            accum_range<VEC, LPR, NCH, MEAN>(acc, g, D, li, s0 + gw, s1, GPW);
             wave_group_sum<VEC, LPR, NCH>(acc);
             if (gw == 0) row_step<WT, VEC, LPR, NCH>(W, A, row, D, li, acc, w, a, lr, eps);
         }
@@ -1103,7 +1115,7 @@ pk_adagrad_kernel(WT* W, float* A, const PackState* __restrict__ st, int p,
             for (int c = 0; c < NCH; ++c)
 #pragma unroll
                 for (int v = 0; v < VEC; ++v) acc[c][v] = 0.0;
-            accum_range<VEC, LPR, NCH>(acc, g, D, li, c0 + gw, c1, GPW);
+            accum_range<VEC, LPR, NCH, MEAN>(acc, g, D, li, c0 + gw, c1, GPW);
             wave_group_sum<VEC, LPR, NCH>(acc);
             __syncthreads();                               // s_red of the previous piece is consumed
             if (gw == 0) {
@@ -1417,9 +1429,14 @@ template <typename WT, int VEC, int LPR, int NCH>
 pk_status launch_adagrad(DeviceState* ds, hipStream_t stream, const AdaArgs& a)
 {
     const unsigned grid = (blocks_for(a.nnz_bound, a.tp, 256 * 16) + 7u) & ~7u;
-    PK_LAUNCH("pk_adagrad", (pk_adagrad_kernel<WT, VEC, LPR, NCH>), dim3(grid), dim3(NT), 0,
-              static_cast<WT*>(a.W), a.A, a.st, a.p, a.unique, a.seg, a.ghot, a.dmax, a.tile_first,
-              a.tp, a.seg_ent, a.ent_mult, a.has_mean, a.grad, a.gstride, a.out_dim, a.addr_max, a.D, a.lr, a.eps);
+    if (a.has_mean)
+        PK_LAUNCH("pk_adagrad", (pk_adagrad_kernel<WT, VEC, LPR, NCH, true>), dim3(grid), dim3(NT), 0,
+                  static_cast<WT*>(a.W), a.A, a.st, a.p, a.unique, a.seg, a.ghot, a.dmax, a.tile_first,
+                  a.tp, a.seg_ent, a.ent_mult, a.grad, a.gstride, a.out_dim, a.addr_max, a.D, a.lr, a.eps);
+    else
+        PK_LAUNCH("pk_adagrad", (pk_adagrad_kernel<WT, VEC, LPR, NCH, false>), dim3(grid), dim3(NT), 0,
+                  static_cast<WT*>(a.W), a.A, a.st, a.p, a.unique, a.seg, a.ghot, a.dmax, a.tile_first,
+                  a.tp, a.seg_ent, a.ent_mult, a.grad, a.gstride, a.out_dim, a.addr_max, a.D, a.lr, a.eps);
     return PK_OK;
 }
 
@@ -1495,7 +1512,7 @@ pk_status pk_forward(const pk_plan* plan, void* const* W, const int64_t* ids, co
     uint32_t* keys = ws.at<uint32_t>(L.keys);
     int32_t* inverse = ws.at<int32_t>(L.inverse);
     uint32_t* bagref = ws.at<uint32_t>(L.bagref);
-    float* bagscl = plan->any_mean ? ws.at<float>(L.bagscl) : nullptr;
+    uint32_t* baglen = plan->any_mean ? ws.at<uint32_t>(L.baglen) : nullptr;
     uint32_t* seg_ent = ws.at<uint32_t>(L.seg_ent);
     int32_t* tile_first = ws.at<int32_t>(L.tile_first);
     uint32_t* unique = ws.at<uint32_t>(L.unique);
@@ -1517,15 +1534,16 @@ pk_status pk_forward(const pk_plan* plan, void* const* W, const int64_t* ids, co
     const size_t key_lds = (size_t)(3 * F + 2) * 4;
     if (long_bags)
         PK_LAUNCH("pk_keys", pk_keys_kernel<32>, key_grid, dim3(NT), key_lds, ids, offsets, B, F, P, nnz, ds->fmeta,
-                  ds->pmeta, ds->slot_field, st, fb, delta, keys, bagref, bagscl, packed_offsets, plan->out_dim,
+                  ds->pmeta, ds->slot_field, st, fb, delta, keys, bagref, baglen, packed_offsets, plan->out_dim,
                   reinterpret_cast<uint4*>(tile_desc), n_clear4);
     else
         PK_LAUNCH("pk_keys", pk_keys_kernel<256>, key_grid, dim3(NT), key_lds, ids, offsets, B, F, P, nnz, ds->fmeta,
-                  ds->pmeta, ds->slot_field, st, fb, delta, keys, bagref, bagscl, packed_offsets, plan->out_dim,
+                  ds->pmeta, ds->slot_field, st, fb, delta, keys, bagref, baglen, packed_offsets, plan->out_dim,
                   reinterpret_cast<uint4*>(tile_desc), n_clear4);
 
     // pooling needs the keys only: it runs beside the rest of the dedup chain
-    const bool overlap = ds->overlap && !ds->prof_on;
+    // (a cross-stream dependency costs more than a small pooling kernel takes)
+    const bool overlap = ds->overlap && !ds->prof_on && (P > 1 || nnz >= (1 << 20));
     const int n_side = overlap ? std::min<int>(P, DeviceState::kSide) : 0;
     if (n_side) { rc = fork_streams(ds, stream, n_side); if (rc != PK_OK) return rc; }
     for (int p = 0; p < P; ++p) {
@@ -1560,7 +1578,7 @@ pk_status pk_forward(const pk_plan* plan, void* const* W, const int64_t* ids, co
         const unsigned sgrid = (unsigned)std::max<int64_t>(P, std::min<int64_t>(nnz / kSortCap + T, resident));
         PK_LAUNCH("pk_sort", pk_sort_kernel, dim3(sgrid), dim3(kSortThreads), sort_lds,
                   ds->sort_tables, ds->table_fields, T, ds->pmeta, st, P, fb, delta,
-                  reinterpret_cast<const uint4*>(bitmap), rank, inverse, bagref, bagscl, seg, seg_ent,
+                  reinterpret_cast<const uint4*>(bitmap), rank, inverse, bagref, baglen, seg, seg_ent,
                   plan->any_mean ? 2 : 1, tile_first, L.pos_tile, sort_desc, ghot, L.dmax, nnz);
     }
     if (n_side) { rc = join_streams(ds, stream, n_side); if (rc != PK_OK) return rc; }

@@ -53,7 +53,7 @@ Layout make_layout(const pk_plan* plan, int32_t B, int64_t nnz)
     L.keys           = take(n * 4);
     L.inverse        = take(n * 4);
     L.bagref         = take(n * 4);
-    L.bagscl         = take(plan->any_mean ? n * 4 : 0);
+    L.baglen         = take(plan->any_mean ? n * 4 : 0);
     L.seg_ent        = take(n * (plan->any_mean ? 8 : 4));
     L.pos_tile       = pos_tile_for(nnz);
     const size_t tile_cap = n / L.pos_tile + P + 2;      // backward tiles of all packs

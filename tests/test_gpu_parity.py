@@ -287,3 +287,12 @@ def test_config5_shrunk_long_sequences_bf16():
 @pytest.mark.timeout(600)
 def test_config2_full_size():
     run_config(2)
+
+
+@pytest.mark.timeout(900)
+def test_config3_full_size_one_step():
+    # 200 fields, four packs, ~21 M occurrences, ~103 GB of tables and accumulators
+    free, _ = torch.cuda.mem_get_info()
+    if free < 130 * 2**30:
+        pytest.skip("needs about 110 GB of free device memory")
+    run_config(3, steps=1)
