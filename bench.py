@@ -33,6 +33,8 @@ def algorithmic_bytes(info, mean_pack):
         "pk_tiles": bm + bm // 8 + 4 * U,
         "pk_inverse": 8 * n + min(bm + bm // 8, 36 * n),
         "pk_sort": 2 * (4 * n) + 4 * n + 2 * sc_occ(n, mean_pack) + 4 * n + 4 * U,
+        "pk_sort_pool": (2 * (4 * n) + 4 * n + 2 * sc_occ(n, mean_pack) + 4 * n + 4 * U
+                         + 4 * n + 4 * (bags + 1) + sw * D * U + 4 * D * bags),
         "pk_adagrad": 4 * (U + 1) + 4 * U + 4 * n + sc_occ(n, mean_pack) + 4 * D * bags + (2 * sw + 8) * D * U,
     }
 

@@ -503,17 +503,38 @@ __device__ __forceinline__ int rank_of_key(const uint4* __restrict__ bm, const i
 constexpr int kSortThreads = 1024;
 constexpr int kSortUnroll2 = 4;       // occurrences per thread in flight in the placing pass
 
-__global__ void __launch_bounds__(kSortThreads, 8)
-pk_sort_kernel(const TableMeta* __restrict__ tmeta, const int32_t* __restrict__ table_fields, int T,
-               const PackMeta* __restrict__ pm, PackState* st, int P,
-               const int32_t* __restrict__ fb, const int32_t* __restrict__ delta,
-               const uint4* __restrict__ bitmap4, const int32_t* __restrict__ rank,
-               const int32_t* __restrict__ inverse, const uint32_t* __restrict__ bagref,
-               const uint32_t* __restrict__ baglen, int32_t* __restrict__ seg_all, uint32_t* __restrict__ ent_all,
-               int ent_mult, int32_t* __restrict__ tile_first, int tp, uint64_t* desc, double* __restrict__ ghot, int dmax,
-               int64_t nnz)
+struct SortArgs {
+    const TableMeta* tmeta; const int32_t* table_fields; int T;
+    const PackMeta* pm; PackState* st; int P;
+    const int32_t* fb; const int32_t* delta;
+    const uint4* bitmap4; const int32_t* rank;
+    const int32_t* inverse; const uint32_t* bagref; const uint32_t* baglen;
+    int32_t* seg_all; uint32_t* ent_all; int ent_mult;
+    int32_t* tile_first; int tp; uint64_t* desc; double* ghot; int dmax;
+    int64_t nnz;
+};
+
+// `block` of `nblocks` blocks of kSortThreads threads; s_dyn: (4 T + 1) ints of LDS
+__device__ __forceinline__ void sort_body(const SortArgs& sa, int block, int nblocks, int32_t* s_dyn)
 {
-    extern __shared__ int32_t s_dyn[];
+    const TableMeta* __restrict__ tmeta = sa.tmeta;
+    const int32_t* __restrict__ table_fields = sa.table_fields;
+    const int T = sa.T, P = sa.P, ent_mult = sa.ent_mult, tp = sa.tp, dmax = sa.dmax;
+    const PackMeta* __restrict__ pm = sa.pm;
+    PackState* st = sa.st;
+    const int32_t* __restrict__ fb = sa.fb;
+    const int32_t* __restrict__ delta = sa.delta;
+    const uint4* __restrict__ bitmap4 = sa.bitmap4;
+    const int32_t* __restrict__ rank = sa.rank;
+    const int32_t* __restrict__ inverse = sa.inverse;
+    const uint32_t* __restrict__ bagref = sa.bagref;
+    const uint32_t* __restrict__ baglen = sa.baglen;
+    int32_t* __restrict__ seg_all = sa.seg_all;
+    uint32_t* __restrict__ ent_all = sa.ent_all;
+    int32_t* __restrict__ tile_first = sa.tile_first;
+    uint64_t* desc = sa.desc;
+    double* __restrict__ ghot = sa.ghot;
+    const int64_t nnz = sa.nnz;
     int32_t* s_rlo = s_dyn;                  // [T]   first rank of each table inside its pack
     int32_t* s_u = s_dyn + T;                // [T]   distinct keys of each table
     int32_t* s_first = s_u + T;              // [T+1] first work item of each table
@@ -553,14 +574,15 @@ pk_sort_kernel(const TableMeta* __restrict__ tmeta, const int32_t* __restrict__ 
         carry_occ += tot_occ;
     }
     if (tid == 0) s_first[T] = carry;
-    if ((int)blockIdx.x < P && tid == 0) {       // the entry after the last segment of the pack
-        const PackState ps = st[blockIdx.x];
-        seg_all[ps.start + blockIdx.x + ps.n_unique] = ps.nnz;
-    }
+    for (int p = block; p < P; p += nblocks)     // the entry after the last segment of each pack
+        if (tid == 0) {
+            const PackState ps = st[p];
+            seg_all[ps.start + p + ps.n_unique] = ps.nnz;
+        }
     __syncthreads();
     const int total = s_first[T];
     PK_TICK(0, tk);
-    for (int item = blockIdx.x; item < total; item += gridDim.x) {
+    for (int item = block; item < total; item += nblocks) {
         const int t = upper_bound_i32(s_first, T + 1, item) - 1;
         const TableMeta tm = tmeta[t];
         const int p = tm.pack;
@@ -690,6 +712,13 @@ pk_sort_kernel(const TableMeta* __restrict__ tmeta, const int32_t* __restrict__ 
     }
 }
 
+__global__ void __launch_bounds__(kSortThreads, 8)
+pk_sort_kernel(SortArgs sa)
+{
+    extern __shared__ int32_t s_dyn[];
+    sort_body(sa, blockIdx.x, gridDim.x, s_dyn);
+}
+
 // ---------------------------------------------------------------------------
 // row access: VEC consecutive elements of a table row as floats
 // ---------------------------------------------------------------------------
@@ -776,18 +805,19 @@ __device__ __forceinline__ void store_f32(float* p, const float* v)
 // coalesced access.  The concatenation of the fields of a sample is the write
 // address.
 // ---------------------------------------------------------------------------
+// `block` of `nblocks` blocks of `nthreads` threads
 template <typename WT, int VEC, int LPR, int NCH>
-__global__ void __launch_bounds__(NT)
-pk_pool_kernel(const WT* __restrict__ W, const uint32_t* __restrict__ keys_all, const int32_t* __restrict__ po,
-               const PackState* __restrict__ st, const FieldMeta* __restrict__ fmeta,
-               const int32_t* __restrict__ slot_field, int B, int D, int64_t n_bags,
-               float* __restrict__ out, int64_t out_stride)
+__device__ __forceinline__ void pool_body(const WT* __restrict__ W, const uint32_t* __restrict__ keys_all,
+                                          const int32_t* __restrict__ po, const PackState* __restrict__ st,
+                                          const FieldMeta* __restrict__ fmeta, const int32_t* __restrict__ slot_field,
+                                          int B, int D, int64_t n_bags, float* __restrict__ out, int64_t out_stride,
+                                          int block, int nblocks, int nthreads)
 {
-    constexpr int GPB = NT / LPR;
+    const int GPB = nthreads / LPR;
     const int li = threadIdx.x % LPR, gi = threadIdx.x / LPR;
     const int n = st->nnz;
     const uint32_t* keys = keys_all + st->start;
-    for (int64_t bag = (int64_t)blockIdx.x * GPB + gi; bag < n_bags; bag += (int64_t)gridDim.x * GPB) {
+    for (int64_t bag = (int64_t)block * GPB + gi; bag < n_bags; bag += (int64_t)nblocks * GPB) {
         const int j = (int)(bag / B);
         const int b = (int)(bag - (int64_t)j * B);
         const FieldMeta m = fmeta[slot_field[j]];
@@ -839,6 +869,76 @@ pk_pool_kernel(const WT* __restrict__ W, const uint32_t* __restrict__ keys_all, 
                 for (int v = 0; v < VEC; ++v) acc[c][v] *= scale;
                 store_f32<VEC>(o + d0, acc[c]);
             }
+        }
+    }
+}
+
+template <typename WT, int VEC, int LPR, int NCH>
+__global__ void __launch_bounds__(NT)
+pk_pool_kernel(const WT* __restrict__ W, const uint32_t* __restrict__ keys_all, const int32_t* __restrict__ po,
+               const PackState* __restrict__ st, const FieldMeta* __restrict__ fmeta,
+               const int32_t* __restrict__ slot_field, int B, int D, int64_t n_bags,
+               float* __restrict__ out, int64_t out_stride)
+{
+    pool_body<WT, VEC, LPR, NCH>(W, keys_all, po, st, fmeta, slot_field, B, D, n_bags, out, out_stride,
+                                 blockIdx.x, gridDim.x, NT);
+}
+
+// Small batches: the sort kernel has few work items (one per table) and leaves most of the
+// chip idle, and the pooling of all packs depends on the keys only, so both run in ONE
+// launch: the first `sort_blocks` blocks sort, the others pool.  (Side streams do the same
+// for large batches; for small ones a cross-stream dependency costs more than it hides.)
+constexpr int kFusedPacks = 16;
+struct PoolPack {
+    const void* W; const int32_t* po; const int32_t* slot_field;
+    int64_t n_bags; int32_t D; int32_t variant; int32_t block_begin; int32_t pad;   // pad: the pack's index
+};
+struct PoolJob {
+    PoolPack pack[kFusedPacks];
+    int32_t n_packs; int32_t B; int32_t n_blocks; int32_t pad;
+    const uint32_t* keys; const PackState* st; const FieldMeta* fmeta; float* out; int64_t out_stride;
+};
+
+// variant = 12 * dtype + shape; the shapes in the order of the host's dispatch
+#define PK_POOL_SHAPES(WT, VECW, base)                                                          \
+    case base + 0:  pool_body<WT, VECW, 1, 1>(PK_POOL_ARGS); break;                             \
+    case base + 1:  pool_body<WT, VECW, 2, 1>(PK_POOL_ARGS); break;                             \
+    case base + 2:  pool_body<WT, VECW, 4, 1>(PK_POOL_ARGS); break;                             \
+    case base + 3:  pool_body<WT, VECW, 8, 1>(PK_POOL_ARGS); break;                             \
+    case base + 4:  pool_body<WT, VECW, 16, 1>(PK_POOL_ARGS); break;                            \
+    case base + 5:  pool_body<WT, VECW, 32, 1>(PK_POOL_ARGS); break;                            \
+    case base + 6:  pool_body<WT, VECW, 64, 1>(PK_POOL_ARGS); break;                            \
+    case base + 7:  pool_body<WT, 1, 4, 1>(PK_POOL_ARGS); break;                                \
+    case base + 8:  pool_body<WT, 1, 16, 1>(PK_POOL_ARGS); break;                               \
+    case base + 9:  pool_body<WT, 1, 64, 1>(PK_POOL_ARGS); break;                               \
+    case base + 10: pool_body<WT, 1, 64, 2>(PK_POOL_ARGS); break;                               \
+    case base + 11: pool_body<WT, 1, 64, 4>(PK_POOL_ARGS); break;
+#define PK_POOL_ARGS                                                                            \
+    static_cast<const WT_*>(k.W), pj.keys, k.po, pj.st + k.pad, pj.fmeta, k.slot_field, pj.B, k.D, k.n_bags, pj.out,  \
+        pj.out_stride, local, n_local, kSortThreads
+
+__global__ void __launch_bounds__(kSortThreads, 8)
+pk_sort_pool_kernel(SortArgs sa, PoolJob pj, int sort_blocks)
+{
+    extern __shared__ int32_t s_dyn[];
+    if ((int)blockIdx.x < sort_blocks) {
+        sort_body(sa, blockIdx.x, sort_blocks, s_dyn);
+        return;
+    }
+    const int pb = (int)blockIdx.x - sort_blocks;
+    int p = 0;
+    while (p + 1 < pj.n_packs && pb >= pj.pack[p + 1].block_begin) ++p;
+    const PoolPack k = pj.pack[p];
+    const int local = pb - k.block_begin;
+    const int n_local = (p + 1 < pj.n_packs ? pj.pack[p + 1].block_begin : pj.n_blocks) - k.block_begin;
+    switch (k.variant) {
+        {
+            using WT_ = float;
+            PK_POOL_SHAPES(float, 4, 0)
+        }
+        {
+            using WT_ = uint16_t;
+            PK_POOL_SHAPES(uint16_t, 8, 12)
         }
     }
 }
@@ -1223,6 +1323,7 @@ struct DeviceState {
     hipEvent_t ev_fork = nullptr;
     hipEvent_t ev_join[kSide] = {};
     bool overlap = true;
+    bool fuse = true;
     // profiling
     bool prof_on = false;
     std::vector<hipEvent_t> events;
@@ -1300,7 +1401,8 @@ pk_status ensure_device_state(const pk_plan* cplan, DeviceState** out)
     }
     if (e == hipSuccess) e = hipEventCreateWithFlags(&ds->ev_fork, hipEventDisableTiming);
     if (e != hipSuccess) { (void)hipFree(ds->blob); delete ds; return fail(PK_EHIP, hip_msg("side stream setup", e)); }
-    if (getenv("PK_TUNE_NO_OVERLAP")) ds->overlap = false;       // tuning aid
+    if (getenv("PK_TUNE_NO_OVERLAP")) ds->overlap = false;       // tuning aids
+    if (getenv("PK_TUNE_NO_FUSE")) ds->fuse = false;
     plan->device_state = ds;
     *out = ds;
     return PK_OK;
@@ -1466,6 +1568,22 @@ pk_status dispatch_pool(DeviceState* ds, hipStream_t stream, int D, const PoolAr
 template <typename WT, int VECW>
 pk_status dispatch_adagrad(DeviceState* ds, hipStream_t stream, int D, const AdaArgs& a) { PK_DISPATCH_BODY(launch_adagrad) }
 
+// shape of the pooling code for a pack, as numbered in pk_sort_pool_kernel, and its lanes per row
+int pool_variant(int dtype, int D, bool aligned, int* lpr_out)
+{
+    static const int lanes[12] = {1, 2, 4, 8, 16, 32, 64, 4, 16, 64, 64, 64};
+    const int vecw = dtype == PK_F32 ? 4 : 8;
+    int shape;
+    if (D % vecw == 0 && aligned && pow2_ceil(D / vecw) <= 64) {
+        shape = 0;
+        while ((1 << shape) < pow2_ceil(D / vecw)) ++shape;
+    } else {
+        shape = D <= 4 ? 7 : D <= 16 ? 8 : D <= 64 ? 9 : D <= 128 ? 10 : 11;
+    }
+    *lpr_out = lanes[shape];
+    return (dtype == PK_F32 ? 0 : 12) + shape;
+}
+
 }  // namespace
 
 namespace pk {
@@ -1541,17 +1659,21 @@ pk_status pk_forward(const pk_plan* plan, void* const* W, const int64_t* ids, co
                   ds->pmeta, ds->slot_field, st, fb, delta, keys, bagref, baglen, packed_offsets, plan->out_dim,
                   reinterpret_cast<uint4*>(tile_desc), n_clear4);
 
-    // pooling needs the keys only: it runs beside the rest of the dedup chain
-    // (a cross-stream dependency costs more than a small pooling kernel takes)
-    const bool overlap = ds->overlap && !ds->prof_on && (P > 1 || nnz >= (1 << 20));
+    // Pooling needs the keys only.  Large batches: it runs on side streams beside the rest of
+    // the dedup chain.  Small ones: it shares the launch of the sort kernel (a cross-stream
+    // dependency would cost more than a small pooling kernel takes).
+    const bool overlap = ds->overlap && !ds->prof_on && (P > 1 || nnz >= (1 << 20)) && nnz >= (1 << 18);
     const int n_side = overlap ? std::min<int>(P, DeviceState::kSide) : 0;
+    const bool fuse_pool = !n_side && P <= kFusedPacks && T > 0 && nnz < (1 << 20) && ds->fuse;
+    auto pool_aligned = [&](int p) {
+        return cols_aligned(plan, p) && aligned16(out) && out_row_stride % 4 == 0 && aligned16(W[p]);
+    };
     if (n_side) { rc = fork_streams(ds, stream, n_side); if (rc != PK_OK) return rc; }
-    for (int p = 0; p < P; ++p) {
+    for (int p = 0; p < P && !fuse_pool; ++p) {
         const Pack& k = plan->packs[p];
         if (k.fields.empty()) continue;
         PoolArgs a{W[p], keys, packed_offsets + po_off(plan, p, B), st + p, ds->fmeta, ds->slot_field + k.first_slot,
-                   B, k.dim, (int64_t)k.fields.size() * B, out, out_row_stride, 256 * 32,
-                   cols_aligned(plan, p) && aligned16(out) && out_row_stride % 4 == 0 && aligned16(W[p])};
+                   B, k.dim, (int64_t)k.fields.size() * B, out, out_row_stride, 256 * 32, pool_aligned(p)};
         hipStream_t ps = n_side ? ds->side[p % n_side] : stream;
         rc = k.dtype == PK_F32 ? dispatch_pool<float, 4>(ds, ps, k.dim, a)
                                : dispatch_pool<uint16_t, 8>(ds, ps, k.dim, a);
@@ -1575,11 +1697,33 @@ pk_status pk_forward(const pk_plan* plan, void* const* W, const int64_t* ids, co
         // block to be resident (two per CU when their LDS fits)
         const size_t sort_lds = (size_t)(4 * T + 1) * 4;
         const int64_t resident = 2 * (kSortCap * 4 + 256 + sort_lds) <= 160 * 1024 ? 512 : 256;
-        const unsigned sgrid = (unsigned)std::max<int64_t>(P, std::min<int64_t>(nnz / kSortCap + T, resident));
-        PK_LAUNCH("pk_sort", pk_sort_kernel, dim3(sgrid), dim3(kSortThreads), sort_lds,
-                  ds->sort_tables, ds->table_fields, T, ds->pmeta, st, P, fb, delta,
-                  reinterpret_cast<const uint4*>(bitmap), rank, inverse, bagref, baglen, seg, seg_ent,
-                  plan->any_mean ? 2 : 1, tile_first, L.pos_tile, sort_desc, ghot, L.dmax, nnz);
+        const unsigned sgrid = (unsigned)std::max<int64_t>(1, std::min<int64_t>(nnz / kSortCap + T, resident));
+        const SortArgs sa{ds->sort_tables, ds->table_fields, T, ds->pmeta, st, P, fb, delta,
+                          reinterpret_cast<const uint4*>(bitmap), rank, inverse, bagref, baglen, seg, seg_ent,
+                          plan->any_mean ? 2 : 1, tile_first, L.pos_tile, sort_desc, ghot, L.dmax, nnz};
+        if (fuse_pool) {
+            PoolJob pj{};
+            int nb = 0, np = 0;
+            for (int p = 0; p < P; ++p) {
+                const Pack& k = plan->packs[p];
+                if (k.fields.empty()) continue;
+                int lpr = 1;
+                PoolPack& q = pj.pack[np++];
+                q.W = W[p]; q.po = packed_offsets + po_off(plan, p, B); q.slot_field = ds->slot_field + k.first_slot;
+                q.n_bags = (int64_t)k.fields.size() * B; q.D = k.dim;
+                q.variant = pool_variant(k.dtype, k.dim, pool_aligned(p), &lpr);
+                q.block_begin = nb;
+                // pj.st is indexed by pack: remember which pack this entry is
+                q.pad = p;
+                nb += (int)blocks_for(q.n_bags, kSortThreads / lpr, 2048);
+            }
+            pj.n_packs = np; pj.B = B; pj.n_blocks = nb; pj.keys = keys; pj.st = st; pj.fmeta = ds->fmeta;
+            pj.out = out; pj.out_stride = out_row_stride;
+            PK_LAUNCH("pk_sort_pool", pk_sort_pool_kernel, dim3(sgrid + (unsigned)nb), dim3(kSortThreads), sort_lds, sa,
+                      pj, (int)sgrid);
+        } else {
+            PK_LAUNCH("pk_sort", pk_sort_kernel, dim3(sgrid), dim3(kSortThreads), sort_lds, sa);
+        }
     }
     if (n_side) { rc = join_streams(ds, stream, n_side); if (rc != PK_OK) return rc; }
     return PK_OK;
