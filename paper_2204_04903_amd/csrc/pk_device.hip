@@ -510,7 +510,7 @@ struct SortArgs {
     const uint4* bitmap4; const int32_t* rank;
     const int32_t* inverse; const uint32_t* bagref; const uint32_t* baglen;
     int32_t* seg_all; uint32_t* ent_all; int ent_mult;
-    int32_t* tile_first; int tp; uint64_t* desc; double* ghot; int dmax;
+    int4* tile_hdr; int tp; uint64_t* desc; double* ghot; int dmax;
     int64_t nnz;
 };
 
@@ -531,7 +531,7 @@ __device__ __forceinline__ void sort_body(const SortArgs& sa, int block, int nbl
     const uint32_t* __restrict__ baglen = sa.baglen;
     int32_t* __restrict__ seg_all = sa.seg_all;
     uint32_t* __restrict__ ent_all = sa.ent_all;
-    int32_t* __restrict__ tile_first = sa.tile_first;
+    int4* __restrict__ tile_hdr = sa.tile_hdr;
     uint64_t* desc = sa.desc;
     double* __restrict__ ghot = sa.ghot;
     const int64_t nnz = sa.nnz;
@@ -597,7 +597,7 @@ __device__ __forceinline__ void sort_body(const SortArgs& sa, int block, int nbl
         uint32_t* ent = ent_all + (size_t)start * ent_mult;
         const bool wide = k.has_mean != 0;             // entries of this pack carry the 1/L scale
         const size_t tbase = (size_t)(start / tp + p);
-        int32_t* tf = tile_first + tbase;
+        int4* th = tile_hdr + tbase;
         double* gh = ghot + tbase * dmax;
         __syncthreads();                               // the previous item's LDS is consumed
         for (int i = tid; i < (int)width; i += kSortThreads) s_cnt[i] = 0;
@@ -654,8 +654,17 @@ __device__ __forceinline__ void sort_body(const SortArgs& sa, int block, int nbl
                 const int len = s_cnt[i];
                 seg[c0 + i] = s0;
                 s_cnt[i] = s0;                                 // from here on: the segment's next free position
-                const int t_in = (s0 + tp - 1) / tp;           // tiles whose first position lies in the segment
-                for (int tt = t_in; (int64_t)tt * tp < (int64_t)s0 + len; ++tt) tf[tt] = c0 + i;
+                // headers of the backward tiles the segment overlaps: x = the key that holds the
+                // tile's first position, y = the key that holds its last one, z = where the
+                // tile's decoded window ends (its last key is decoded to its end unless it is long)
+                for (int tt = s0 / tp; (int64_t)tt * tp < (int64_t)s0 + len; ++tt) {
+                    const int t_first = tt * tp, t_end = min(t_first + tp, n);
+                    if (t_first >= s0) th[tt].x = c0 + i;
+                    if (t_end - 1 < s0 + len) {
+                        th[tt].y = c0 + i;
+                        th[tt].z = len <= kWarmMax ? s0 + len : t_end;
+                    }
+                }
                 if (len > kWarmMax && s0 / tp != (s0 + len - 1) / tp) {
                     const int slot = s0 / tp;                  // one such key at most starts in a tile
                     for (int d = 0; d < k.dim; ++d) gh[(size_t)slot * k.dim + d] = 0.0;
@@ -1074,7 +1083,7 @@ template <typename WT, int VEC, int LPR, int NCH, bool MEAN>
 __global__ void __launch_bounds__(NT, VEC > 4 ? 1 : (MEAN ? PK_ADA_WAVES_MEAN : PK_ADA_WAVES))   // 8-wide rows need their registers
 pk_adagrad_kernel(WT* W, float* A, const PackState* __restrict__ st, int p,
                   const uint32_t* __restrict__ unique_all, const int32_t* __restrict__ seg_all,
-                  double* ghot_all, int dmax, const int32_t* __restrict__ tile_first, int tp,
+                  double* ghot_all, int dmax, const int4* __restrict__ tile_hdr, int tp, int n_host,
                   const uint32_t* __restrict__ seg_ent_all, int ent_mult,
                   const float* __restrict__ grad, int64_t gstride, int64_t out_dim, uint32_t addr_max, int D,
                   float lr, float eps)
@@ -1091,12 +1100,16 @@ pk_adagrad_kernel(WT* W, float* A, const PackState* __restrict__ st, int p,
     __shared__ double s_scl[MEAN ? kPosTileMax + kWarmMax : 1];   // 1/L of mean pooling, in double: see the decode below
     const int li = threadIdx.x % LPR, gi = threadIdx.x / LPR;
     const int wv = threadIdx.x >> 6, gw = (threadIdx.x & 63) / LPR;
-    const int n = st->nnz, U = st->n_unique, start = st->start;
+    // A plan with one pack has all occurrences in it, so the host knows the sizes and the first
+    // tile header can be requested without waiting for the pack's state; the state is still
+    // checked (it says 0 occurrences when the forward pass rejected its input).
+    const int n = n_host >= 0 ? n_host : st->nnz, start = n_host >= 0 ? 0 : st->start;
+    const bool state_ok = n_host < 0 || st->nnz == n_host;
     const int32_t* seg = seg_all + start + p;
     const uint32_t* uq = unique_all + start;
     const size_t tbase = (size_t)(start / tp + p);
     double* gh = ghot_all + tbase * dmax;
-    const int32_t* tf = tile_first + tbase;
+    const int4* th = tile_hdr + tbase;
     const uint32_t* ent = seg_ent_all + (size_t)start * ent_mult;
     GradSrc<MEAN> g{grad, s_addr, s_scl, 0};
     const int n_tiles = (n + tp - 1) / tp;
@@ -1110,21 +1123,14 @@ pk_adagrad_kernel(WT* W, float* A, const PackState* __restrict__ st, int p,
         if (threadIdx.x == 0) atomicAdd(&pk_dbg[14], 1ull);
 #endif
         const int t0 = tile * tp, t1 = min(t0 + tp, n);
-        // keys whose segments overlap [t0, t1)
-        const int u_lo = tf[tile];
-        int u_hi = U - 1;
-        if (tile + 1 < n_tiles) {
-            u_hi = tf[tile + 1];
-            if (seg[u_hi] >= t1) --u_hi;
-        }
-        const int nseg = u_hi - u_lo + 1;
-        // decode window: the tile, plus the tail of its last key unless that key is a hot one
-        // (hot keys are cut at the tile's end)
-        int w_end = t1;
-        {
-            const int e0 = seg[u_hi], e1 = seg[u_hi + 1];
-            if (e1 - e0 <= kWarmMax) w_end = e1;
-        }
+        // keys whose segments overlap [t0, t1), and the decode window: the tile, plus the tail
+        // of its last key unless that key is a long one (long keys are cut at the tile's end).
+        // The clamps keep the LDS arrays in bounds whatever the header holds.
+        const int4 hdr = th[tile];
+        if (!state_ok) return;
+        const int u_lo = hdr.x;
+        const int nseg = min(max(hdr.y - u_lo + 1, 0), tp);
+        const int w_end = min(max(hdr.z, t1), t1 + kWarmMax);
         __syncthreads();                                   // the previous tile's LDS is consumed
         for (int i = threadIdx.x; i <= nseg; i += NT) s_seg[i] = seg[u_lo + i];
         for (int i = threadIdx.x; i < nseg; i += NT) s_row[i] = uq[u_lo + i];
@@ -1268,7 +1274,7 @@ struct HotPacks {
 __global__ void __launch_bounds__(NT)
 pk_adagrad_hot_kernel(HotPacks ptrs, int p0, const PackMeta* __restrict__ pm, const PackState* __restrict__ st,
                       const uint32_t* __restrict__ unique_all, const int32_t* __restrict__ seg_all,
-                      const double* __restrict__ ghot_all, int dmax, const int32_t* __restrict__ tile_first, int tp,
+                      const double* __restrict__ ghot_all, int dmax, const int4* __restrict__ tile_hdr, int tp,
                       float lr, float eps)
 {
     const int p = p0 + blockIdx.y;
@@ -1277,11 +1283,11 @@ pk_adagrad_hot_kernel(HotPacks ptrs, int p0, const PackMeta* __restrict__ pm, co
     const int32_t* seg = seg_all + start + p;
     const size_t tbase = (size_t)(start / tp + p);
     const double* gh = ghot_all + tbase * dmax;
-    const int32_t* tf = tile_first + tbase;
+    const int4* th = tile_hdr + tbase;
     const int n_tiles = (n + tp - 1) / tp;
     const int lane = threadIdx.x & 63;
     for (int t = blockIdx.x * (NT / 64) + (threadIdx.x >> 6); t + 1 < n_tiles; t += gridDim.x * (NT / 64)) {
-        const int u = tf[t + 1];                               // the key that holds the next tile's first position
+        const int u = th[t + 1].x;                             // the key that holds the next tile's first position
         const int s0 = seg[u], s1 = seg[u + 1];
         if (s0 < t * tp || s0 >= (t + 1) * tp || s1 - s0 <= kWarmMax) continue;
         const size_t row = unique_all[start + u];
@@ -1511,7 +1517,7 @@ struct PoolArgs {
 };
 struct AdaArgs {
     void* W; float* A; const PackState* st; int p; const uint32_t* unique; const int32_t* seg;
-    double* ghot; int dmax; const int32_t* tile_first; int tp; const uint32_t* seg_ent; int ent_mult;
+    double* ghot; int dmax; const int4* tile_hdr; int tp; int n_host; const uint32_t* seg_ent; int ent_mult;
     int has_mean; const float* grad; int64_t gstride; int64_t out_dim; uint32_t addr_max; int D;
     float lr; float eps; int64_t nnz_bound; bool aligned;
 };
@@ -1533,12 +1539,12 @@ pk_status launch_adagrad(DeviceState* ds, hipStream_t stream, const AdaArgs& a)
     const unsigned grid = (blocks_for(a.nnz_bound, a.tp, 256 * 16) + 7u) & ~7u;
     if (a.has_mean)
         PK_LAUNCH("pk_adagrad", (pk_adagrad_kernel<WT, VEC, LPR, NCH, true>), dim3(grid), dim3(NT), 0,
-                  static_cast<WT*>(a.W), a.A, a.st, a.p, a.unique, a.seg, a.ghot, a.dmax, a.tile_first,
-                  a.tp, a.seg_ent, a.ent_mult, a.grad, a.gstride, a.out_dim, a.addr_max, a.D, a.lr, a.eps);
+                  static_cast<WT*>(a.W), a.A, a.st, a.p, a.unique, a.seg, a.ghot, a.dmax, a.tile_hdr,
+                  a.tp, a.n_host, a.seg_ent, a.ent_mult, a.grad, a.gstride, a.out_dim, a.addr_max, a.D, a.lr, a.eps);
     else
         PK_LAUNCH("pk_adagrad", (pk_adagrad_kernel<WT, VEC, LPR, NCH, false>), dim3(grid), dim3(NT), 0,
-                  static_cast<WT*>(a.W), a.A, a.st, a.p, a.unique, a.seg, a.ghot, a.dmax, a.tile_first,
-                  a.tp, a.seg_ent, a.ent_mult, a.grad, a.gstride, a.out_dim, a.addr_max, a.D, a.lr, a.eps);
+                  static_cast<WT*>(a.W), a.A, a.st, a.p, a.unique, a.seg, a.ghot, a.dmax, a.tile_hdr,
+                  a.tp, a.n_host, a.seg_ent, a.ent_mult, a.grad, a.gstride, a.out_dim, a.addr_max, a.D, a.lr, a.eps);
     return PK_OK;
 }
 
@@ -1632,7 +1638,7 @@ pk_status pk_forward(const pk_plan* plan, void* const* W, const int64_t* ids, co
     uint32_t* bagref = ws.at<uint32_t>(L.bagref);
     uint32_t* baglen = plan->any_mean ? ws.at<uint32_t>(L.baglen) : nullptr;
     uint32_t* seg_ent = ws.at<uint32_t>(L.seg_ent);
-    int32_t* tile_first = ws.at<int32_t>(L.tile_first);
+    int4* tile_hdr = ws.at<int4>(L.tile_hdr);
     uint32_t* unique = ws.at<uint32_t>(L.unique);
     int32_t* seg = ws.at<int32_t>(L.seg);
     double* ghot = ws.at<double>(L.ghot);
@@ -1700,7 +1706,7 @@ pk_status pk_forward(const pk_plan* plan, void* const* W, const int64_t* ids, co
         const unsigned sgrid = (unsigned)std::max<int64_t>(1, std::min<int64_t>(nnz / kSortCap + T, resident));
         const SortArgs sa{ds->sort_tables, ds->table_fields, T, ds->pmeta, st, P, fb, delta,
                           reinterpret_cast<const uint4*>(bitmap), rank, inverse, bagref, baglen, seg, seg_ent,
-                          plan->any_mean ? 2 : 1, tile_first, L.pos_tile, sort_desc, ghot, L.dmax, nnz};
+                          plan->any_mean ? 2 : 1, tile_hdr, L.pos_tile, sort_desc, ghot, L.dmax, nnz};
         if (fuse_pool) {
             PoolJob pj{};
             int nb = 0, np = 0;
@@ -1757,7 +1763,7 @@ pk_status pk_backward_update(const pk_plan* plan, void* const* W, float* const* 
         hipStream_t ps = n_side ? ds->side[p % n_side] : stream;
         if (k.fields.empty()) continue;
         AdaArgs a{W[p], A[p], st + p, p, ws.at<uint32_t>(L.unique), ws.at<int32_t>(L.seg), ws.at<double>(L.ghot),
-                  L.dmax, ws.at<int32_t>(L.tile_first), L.pos_tile,
+                  L.dmax, ws.at<int4>(L.tile_hdr), L.pos_tile, P == 1 ? (int)nnz : -1,
                   ws.at<uint32_t>(L.seg_ent), plan->any_mean ? 2 : 1, k.has_mean ? 1 : 0, grad_out, grad_row_stride,
                   plan->out_dim, (uint32_t)((int64_t)(B - 1) * grad_row_stride + plan->out_dim - k.dim), k.dim, lr,
                   eps, nnz,
@@ -1776,7 +1782,7 @@ pk_status pk_backward_update(const pk_plan* plan, void* const* W, float* const* 
         for (int i = 0; i < np; ++i) { hp.W[i] = W[p0 + i]; hp.A[i] = A[p0 + i]; }
         PK_LAUNCH("pk_adagrad_hot", pk_adagrad_hot_kernel, dim3(hgrid, np), dim3(NT), 0, hp, p0, ds->pmeta, st,
                   ws.at<uint32_t>(L.unique), ws.at<int32_t>(L.seg), ws.at<double>(L.ghot), L.dmax,
-                  ws.at<int32_t>(L.tile_first), L.pos_tile, lr, eps);
+                  ws.at<int4>(L.tile_hdr), L.pos_tile, lr, eps);
     }
     return PK_OK;
 }

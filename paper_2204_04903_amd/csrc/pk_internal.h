@@ -87,7 +87,7 @@ struct Pack {
 
 // Byte offsets of the workspace's arrays for one (plan, B, nnz).
 struct Layout {
-    size_t state, fb, delta, packed_offsets, keys, inverse, bagref, baglen, seg_ent, tile_first,
+    size_t state, fb, delta, packed_offsets, keys, inverse, bagref, baglen, seg_ent, tile_hdr,
            unique, seg, ghot, bitmap, tile_desc, sort_desc, rank, total;
     size_t clear_bytes;          // scan descriptors, contiguous from `tile_desc`
     int64_t n_tiles_total;

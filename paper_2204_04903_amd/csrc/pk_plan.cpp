@@ -57,7 +57,7 @@ Layout make_layout(const pk_plan* plan, int32_t B, int64_t nnz)
     L.seg_ent        = take(n * (plan->any_mean ? 8 : 4));
     L.pos_tile       = pos_tile_for(nnz);
     const size_t tile_cap = n / L.pos_tile + P + 2;      // backward tiles of all packs
-    L.tile_first     = take(tile_cap * 4);
+    L.tile_hdr       = take(tile_cap * 16);
     L.unique         = take(n * 4);
     L.seg            = take((n + P + 1) * 4);
     L.dmax           = plan->dmax;
