@@ -78,6 +78,8 @@ def main():
     ap.add_argument("--max-shards", type=int, default=0,
                     help="Eq. 1 shard split of heavy packs (0 = off, the configurations' own pack counts); the "
                          "per-field occurrence counts of the first batch serve as the warm-up statistics")
+    ap.add_argument("--groups", type=int, default=0,
+                    help="K-Interleaving groups of packed operations (0 = chosen by batch size, 1 = none)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (a known size for scaling rocprofv3's byte counters)")
@@ -110,6 +112,8 @@ def main():
         plan_opts = dict(max_shards=args.max_shards,
                          field_volume=[float(b0.offsets[(f + 1) * wl.batch] - b0.offsets[f * wl.batch])
                                        for f in range(wl.n_fields)])
+    if args.groups:
+        plan_opts["interleave_groups"] = args.groups
     layer = PackedEmbedding(tables, fields, **plan_opts)
     stream = torch.cuda.current_stream().cuda_stream
     for t, ts in enumerate(wl.tables):
@@ -230,7 +234,7 @@ def main():
         "dtype": "f32" if wl.tables[0].dtype == 0 else "bf16 tables, f32 arithmetic",
         "data": "synthetic",
         "config": {"workload": f"{args.workload}: {wl.description}", "batch": wl.batch, "fields": wl.n_fields,
-                   "packs": layer.n_packs, "max_shards": args.max_shards, "ring_batches": ring, "lookups_per_step": lookups / args.steps,
+                   "packs": layer.n_packs, "max_shards": args.max_shards, "interleave_groups": args.groups, "ring_batches": ring, "lookups_per_step": lookups / args.steps,
                    "distinct_keys_per_step": sum(i["U"] for i in sizes[0])},
         "hbm_model": {"bytes_per_step": model_bytes, "GBps": model_bytes / (ms_per_step * 1e-3) / 1e9,
                       "frac_of_peak": model_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS},

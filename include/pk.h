@@ -60,6 +60,13 @@ typedef struct {
     int32_t max_shards;  /* Eq. 1 shard split of heavy packs; 0 or 1 = off          */
     const double* field_volume; /* host, [n_fields] or NULL: occurrences per field
                                    from warm-up statistics, used by the Eq. 1 split */
+    int32_t interleave_groups;  /* Sec. III-C K-Interleaving: the packs are dealt to this
+                                   many groups (pack p -> group p mod G); a group's packed
+                                   operations run one after another, the groups side by
+                                   side (one internal HIP stream each, joined before the
+                                   call's work on hip_stream is complete).  0 = chosen by
+                                   batch size, 1 = none, at most 8.  Results do not depend
+                                   on it.                                               */
 } pk_plan_opts;
 
 typedef struct pk_plan pk_plan;   /* opaque, host memory, owned by the library */

@@ -1324,7 +1324,7 @@ struct DeviceState {
     // Side streams: packs (and the pooling of a pack vs the dedup chain) are independent
     // pieces of memory-bound work; running them side by side hides launch gaps and
     // latency tails (the interleaving of packed operations of Sec. III-C, on one GPU).
-    static constexpr int kSide = 4;
+    static constexpr int kSide = 8;
     hipStream_t side[kSide] = {};
     hipEvent_t ev_fork = nullptr;
     hipEvent_t ev_join[kSide] = {};
@@ -1668,8 +1668,13 @@ pk_status pk_forward(const pk_plan* plan, void* const* W, const int64_t* ids, co
     // Pooling needs the keys only.  Large batches: it runs on side streams beside the rest of
     // the dedup chain.  Small ones: it shares the launch of the sort kernel (a cross-stream
     // dependency would cost more than a small pooling kernel takes).
-    const bool overlap = ds->overlap && !ds->prof_on && (P > 1 || nnz >= (1 << 20)) && nnz >= (1 << 18);
-    const int n_side = overlap ? std::min<int>(P, DeviceState::kSide) : 0;
+    // Interleaving groups (Sec. III-C, K-Interleaving): pack p belongs to group p mod G; a
+    // group's packed operations follow one another on the group's stream, the groups run side
+    // by side.  G = 0 lets the size decide (up to 4 groups for large batches, none for small).
+    const int G = plan->opts.interleave_groups;
+    const bool overlap = ds->overlap && !ds->prof_on &&
+                         (G >= 2 || (G == 0 && (P > 1 || nnz >= (1 << 20)) && nnz >= (1 << 18)));
+    const int n_side = overlap ? std::min<int>(P, G >= 2 ? G : 4) : 0;
     const bool fuse_pool = !n_side && P <= kFusedPacks && T > 0 && nnz < (1 << 20) && ds->fuse;
     auto pool_aligned = [&](int p) {
         return cols_aligned(plan, p) && aligned16(out) && out_row_stride % 4 == 0 && aligned16(W[p]);
@@ -1755,8 +1760,9 @@ pk_status pk_backward_update(const pk_plan* plan, void* const* W, float* const* 
     const Layout& L = ws.L;
     PackState* st = ws.at<PackState>(L.state);
     // packs touch disjoint tables: one side stream each
-    const bool overlap = ds->overlap && !ds->prof_on && P > 1;
-    const int n_side = overlap ? std::min<int>(P, DeviceState::kSide) : 0;
+    const int G = plan->opts.interleave_groups;
+    const bool overlap = ds->overlap && !ds->prof_on && P > 1 && G != 1;
+    const int n_side = overlap ? std::min<int>(P, G >= 2 ? G : 4) : 0;
     if (n_side) { rc = fork_streams(ds, stream, n_side); if (rc != PK_OK) return rc; }
     for (int p = 0; p < P; ++p) {
         const Pack& k = plan->packs[p];

@@ -105,6 +105,8 @@ pk_status pk_plan_create(const pk_table_desc* tables, int32_t n_tables, const pk
         return fail(PK_EOVERFLOW, "pk_plan_create: at most 4096 fields and 4096 tables (their metadata is staged in LDS)");
     if (opts && (opts->max_batch < 0 || opts->max_nnz < 0 || opts->max_shards < 0))
         return fail(PK_EINVAL, "pk_plan_create: negative option");
+    if (opts && (opts->interleave_groups < 0 || opts->interleave_groups > 8))
+        return fail(PK_EINVAL, "pk_plan_create: interleave_groups must be 0 (automatic) to 8");
     if (opts && opts->field_volume)
         for (int32_t f = 0; f < n_fields; ++f)
             if (!(opts->field_volume[f] >= 0.0))

@@ -46,7 +46,7 @@ def run_dense_case(name, tables, fields, steps, lr=0.05, eps=1e-8, out_pad=0, gr
     """steps: list of dicts from small_problem (ids, offsets, grad, B, Wt of the first one)."""
     from paper_2204_04903_amd.layer import PackedEmbedding
     say(f"[case] {name}: tables={len(tables)} fields={len(fields)} steps={len(steps)}")
-    pl = orc.plan(tables, fields, **plan_opts)
+    pl = orc.plan(tables, fields, **{k: v for k, v in plan_opts.items() if k != "interleave_groups"})
     Wt0 = steps[0]["Wt"]
     W = stack_tables(pl, [w.copy() for w in Wt0])
     A = [np.zeros(w.shape, np.float32) for w in W]
@@ -113,6 +113,15 @@ def test_eq1_shard_split_packs_two_steps():
     run_dense_case("shards", tables, fields, steps, max_shards=4)
     vol = [float(v) for v in rng.integers(1, 30, len(fields))]
     run_dense_case("shards+stats", tables, fields, steps, max_shards=3, field_volume=vol)
+
+
+@pytest.mark.parametrize("groups", [1, 2, 3])
+def test_interleaving_groups_do_not_change_results(groups):
+    # Sec. III-C K-Interleaving: packs dealt to groups that run side by side on internal streams
+    tables = [(60, 4, 0), (80, 8, 0), (50, 16, 0), (40, 32, 0), (30, 4, 0), (70, 8, 0)]
+    fields = [(t, t % 2) for t in range(6)] + [(1, 0), (3, 1)]
+    steps = [small_problem(90 + s, B=29, tables=tables, fields=fields, max_len=7) for s in range(2)]
+    run_dense_case(f"groups={groups}", tables, fields, steps, interleave_groups=groups)
 
 
 def test_wild_64bit_ids_are_folded():

@@ -88,6 +88,8 @@ def test_plan_rejects_bad_arguments():
     assert status(lambda: pk.pk_plan_create([(10, 512, 0)], [(0, 0)])) == pk.PK_EOVERFLOW
     assert status(lambda: pk.pk_plan_create([(2 ** 31, 8, 0), (2 ** 31, 8, 0)], [(0, 0)])) == pk.PK_EOVERFLOW
     assert "rows" in pk.pk_last_error()
+    assert status(lambda: pk.pk_plan_create([(10, 8, 0)], [(0, 0)], interleave_groups=9)) == pk.PK_EINVAL
+    assert status(lambda: pk.pk_plan_create([(10, 8, 0)], [(0, 0)], field_volume=[-1.0])) == pk.PK_EINVAL
     assert status(lambda: pk.pk_plan_create([(10, 8, 0)], [(0, 0)] * 4097)) == pk.PK_EOVERFLOW
     assert status(lambda: pk.pk_plan_create([(10, 8, 0)] * 4097, [(0, 0)])) == pk.PK_EOVERFLOW
 
