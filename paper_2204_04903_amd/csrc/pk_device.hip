@@ -6,14 +6,16 @@
 // once per field (D-Packing, Sec. III-B).
 //
 // Stages of one step (all packs of the plan share the integer stages):
-//   setup     field boundaries, per-pack occurrence counts and positions, bitmap clear
-//   keys      H1: key = base_row + (uint64)id mod rows, packed order, mark bitmap
+//   keys      H1: key = base_row + (uint64)id mod rows in packed order, packed bag offsets,
+//             per occurrence the place of its bag's gradient chunk (and the bag length)
 //   pool      H3-H5: per pack, gather rows by key, pool per bag, write concatenated
+//   mark      H2: which rows occur (bitmap slices built in LDS)
 //   tiles     H2: one-pass popcount scan of the bitmap -> rank samples, distinct keys (ascending)
-//   inverse   H2: inverse[q] = rank(key[q]); occurrence counts per distinct key
-//   segs      H2: one-pass exclusive scan of the counts -> segment offsets; list of hot keys
-//   scatter   H2: occurrences grouped by distinct key (gradient addresses)
+//   inverse   H2: inverse[q] = rank(key[q])
+//   sort      H2: occurrences grouped by distinct key (LDS counting sort), segment offsets,
+//             headers of the backward tiles; small batches: pooling shares this launch
 //   adagrad   H6+H7: per pack, per distinct key: reduce gradients, update row in place
+//   hot       H7: keys whose occurrences span several backward tiles, from their partial sums
 #include <hip/hip_runtime.h>
 
 #include <cstdio>
@@ -30,14 +32,6 @@ using namespace pk;
 // ---------------------------------------------------------------------------
 // device helpers
 // ---------------------------------------------------------------------------
-#ifdef PK_PHASE_TIMING
-__device__ unsigned long long pk_dbg[32];
-#define PK_TICK(i, t0) do { if (threadIdx.x == 0) { unsigned long long t1_ = wall_clock64(); atomicAdd(&pk_dbg[i], t1_ - t0); t0 = t1_; } } while (0)
-extern "C" void pk_debug_read(unsigned long long* out) { (void)hipDeviceSynchronize(); (void)hipMemcpyFromSymbol(out, HIP_SYMBOL(pk_dbg), sizeof(pk_dbg)); unsigned long long z[32] = {}; (void)hipMemcpyToSymbol(HIP_SYMBOL(pk_dbg), z, sizeof(z)); }
-#else
-#define PK_TICK(i, t0) do { } while (0)
-#endif
-
 namespace {
 
 constexpr int NT = 256;   // threads per block of the streaming kernels
@@ -365,7 +359,7 @@ pk_mark_kernel(const MarkItem* __restrict__ items, const int32_t* __restrict__ i
 __global__ void __launch_bounds__(NT)
 pk_tiles_kernel(const uint4* __restrict__ bitmap4, uint64_t* tile_desc, int n_tiles_total,
                 const PackMeta* __restrict__ pm, PackState* st, int P,
-                int32_t* __restrict__ rank, uint32_t* __restrict__ unique, int32_t* __restrict__ cnt)
+                int32_t* __restrict__ rank, uint32_t* __restrict__ unique)
 {
     __shared__ uint32_t s_pre;
     // Block b takes tiles b, b+G, b+2G, ...: a tile only waits for lower tiles, which
@@ -543,9 +537,6 @@ __device__ __forceinline__ void sort_body(const SortArgs& sa, int block, int nbl
     __shared__ uint32_t s_base;
     const int tid = threadIdx.x;
     if (st[0].error) return;
-#ifdef PK_PHASE_TIMING
-    unsigned long long tk = wall_clock64();
-#endif
     int carry = 0, carry_occ = 0;
     for (int base = 0; base < T; base += kSortThreads) {
         const int t = base + tid;
@@ -581,7 +572,6 @@ __device__ __forceinline__ void sort_body(const SortArgs& sa, int block, int nbl
         }
     __syncthreads();
     const int total = s_first[T];
-    PK_TICK(0, tk);
     for (int item = block; item < total; item += nblocks) {
         const int t = upper_bound_i32(s_first, T + 1, item) - 1;
         const TableMeta tm = tmeta[t];
@@ -621,7 +611,6 @@ __device__ __forceinline__ void sort_body(const SortArgs& sa, int block, int nbl
             }
         }
         __syncthreads();
-        PK_TICK(1, tk);
         const int per = ((int)width + kSortThreads - 1) / kSortThreads;   // consecutive counters per thread
         int mine = 0;
         for (int j = 0; j < per; ++j) {
@@ -646,7 +635,6 @@ __device__ __forceinline__ void sort_body(const SortArgs& sa, int block, int nbl
             }
         }
         __syncthreads();
-        PK_TICK(2, tk);
         int s0 = (int)s_base + ex;
         for (int j = 0; j < per; ++j) {
             const int i = tid * per + j;
@@ -673,7 +661,6 @@ __device__ __forceinline__ void sort_body(const SortArgs& sa, int block, int nbl
             }
         }
         __syncthreads();
-        PK_TICK(3, tk);
         for (int fi = tm.field_begin; fi < tm.field_end; ++fi) {
             const int f = table_fields[fi];
             const int64_t q0 = (int64_t)fb[f] + delta[f], q1 = (int64_t)fb[f + 1] + delta[f];
@@ -714,10 +701,6 @@ __device__ __forceinline__ void sort_body(const SortArgs& sa, int block, int nbl
             }
         }
         __syncthreads();
-        PK_TICK(4, tk);
-#ifdef PK_PHASE_TIMING
-        if (tid == 0) atomicAdd(&pk_dbg[8], 1ull);
-#endif
     }
 }
 
@@ -1113,15 +1096,8 @@ pk_adagrad_kernel(WT* W, float* A, const PackState* __restrict__ st, int p,
     const uint32_t* ent = seg_ent_all + (size_t)start * ent_mult;
     GradSrc<MEAN> g{grad, s_addr, s_scl, 0};
     const int n_tiles = (n + tp - 1) / tp;
-#ifdef PK_PHASE_TIMING
-    unsigned long long tk = wall_clock64();
-    if (threadIdx.x == 0) atomicAdd(&pk_dbg[15], 1ull);
-#endif
     for (XcdTiles it(n_tiles); it.valid(); it.next()) {
         const int tile = it.tile;
-#ifdef PK_PHASE_TIMING
-        if (threadIdx.x == 0) atomicAdd(&pk_dbg[14], 1ull);
-#endif
         const int t0 = tile * tp, t1 = min(t0 + tp, n);
         // keys whose segments overlap [t0, t1), and the decode window: the tile, plus the tail
         // of its last key unless that key is a long one (long keys are cut at the tile's end).
@@ -1159,7 +1135,6 @@ pk_adagrad_kernel(WT* W, float* A, const PackState* __restrict__ st, int p,
         if (threadIdx.x == 0) { s_nwarm = 0; s_nhot = 0; }
         g.t0 = t0;
         __syncthreads();
-        PK_TICK(9, tk);
         // cold keys that start here are finished on the spot; the others are listed
         for (int k = gi; k < nseg; k += GPB) {
             const int s0 = s_seg[k], s1 = s_seg[k + 1];
@@ -1184,7 +1159,6 @@ pk_adagrad_kernel(WT* W, float* A, const PackState* __restrict__ st, int p,
             }
         }
         __syncthreads();
-        PK_TICK(10, tk);
         // warm keys that start here: one wavefront each
         const int n_warm = s_nwarm;
         for (int i = wv; i < n_warm; i += NT / 64) {
@@ -1202,10 +1176,6 @@ pk_adagrad_kernel(WT* W, float* A, const PackState* __restrict__ st, int p,
             wave_group_sum<VEC, LPR, NCH>(acc);
             if (gw == 0) row_step<WT, VEC, LPR, NCH>(W, A, row, D, li, acc, w, a, lr, eps);
         }
-#ifdef PK_PHASE_TIMING
-        __syncthreads();
-        PK_TICK(11, tk);
-#endif
         // long keys that cross tile boundaries: the tile's piece is split over the block's
         // wavefronts, reduced in LDS and added to the key's partial sums;
         // pk_adagrad_hot_kernel finishes those keys.
@@ -1254,10 +1224,6 @@ pk_adagrad_kernel(WT* W, float* A, const PackState* __restrict__ st, int p,
                 }
             }
         }
-#ifdef PK_PHASE_TIMING
-        __syncthreads();
-        PK_TICK(12, tk);
-#endif
     }
 }
 
@@ -1694,7 +1660,7 @@ pk_status pk_forward(const pk_plan* plan, void* const* W, const int64_t* ids, co
     PK_LAUNCH("pk_mark", pk_mark_kernel, dim3((unsigned)plan->mark_items.size()), dim3(kMarkThreads), 0, ds->mark_items,
               ds->mark_fields, ds->pmeta, st, fb, delta, keys, bitmap, nnz);
     PK_LAUNCH("pk_tiles", pk_tiles_kernel, dim3(blocks_for(n_tiles, 1, 1024)), dim3(NT), 0,
-              reinterpret_cast<const uint4*>(bitmap), tile_desc, (int)n_tiles, ds->pmeta, st, P, rank, unique, seg);
+              reinterpret_cast<const uint4*>(bitmap), tile_desc, (int)n_tiles, ds->pmeta, st, P, rank, unique);
     const int kt = nnz < (1 << 20) ? 256 : 1024;      // occurrences per tile of the inverse kernel
     const unsigned xq = (blocks_for(nnz, kt, 256 * 16) + 7u) & ~7u;
     if (kt == 256)

@@ -124,6 +124,16 @@ def test_interleaving_groups_do_not_change_results(groups):
     run_dense_case(f"groups={groups}", tables, fields, steps, interleave_groups=groups)
 
 
+def test_many_packs_and_a_table_nobody_reads():
+    # 20 distinct dimensions -> 20 packs (more than share one pooling launch); table 3 has no field, so
+    # its pack has rows but no occurrences, and its rows must stay untouched
+    dims = [1, 2, 3, 4, 5, 6, 7, 8, 12, 16, 20, 24, 32, 40, 48, 64, 96, 128, 200, 256]
+    tables = [(17 + 3 * i, d, 0) for i, d in enumerate(dims)]
+    fields = [(t, t % 2) for t in range(len(tables)) if t != 3] + [(0, 1), (19, 0)]
+    steps = [small_problem(120 + s, B=11, tables=tables, fields=fields, max_len=4) for s in range(2)]
+    run_dense_case("20 packs", tables, fields, steps)
+
+
 def test_wild_64bit_ids_are_folded():
     steps = [small_problem(50 + s, B=33, wild_ids=True) for s in range(2)]
     steps[0]["ids"][:4] = [-1, -2 ** 63, 2 ** 63 - 1, 0]
