@@ -508,27 +508,142 @@ struct SortArgs {
     int64_t nnz;
 };
 
+// What a work item (a table's ranks [c0, c0 + width), width counters in s_cnt) needs to know
+struct SortItem {
+    TableMeta tm;
+    int p;               // pack
+    int dim, wide;       // the pack's dimension; its entries carry the bag length (mean pooling)
+    int n, start;        // occurrences of the pack, position of its first one in the packed order
+    int c0;
+    uint32_t width;
+};
+
+// Step 1 of an item: occurrences per rank, counted in LDS.  Returns this thread's share of
+// the counters (`per` consecutive ones starting at tid * per), scanned over the block.
+__device__ __forceinline__ int sort_count(const SortArgs& sa, const SortItem& it, int32_t* s_cnt, int* per_out,
+                                          int* n_item)
+{
+    const int tid = threadIdx.x;
+    const int32_t* inverse = sa.inverse;
+    __syncthreads();                               // the previous use of s_cnt is over
+    for (int i = tid; i < (int)it.width; i += kSortThreads) s_cnt[i] = 0;
+    __syncthreads();
+    for (int fi = it.tm.field_begin; fi < it.tm.field_end; ++fi) {
+        const int f = sa.table_fields[fi];
+        const int64_t q0 = (int64_t)sa.fb[f] + sa.delta[f], q1 = (int64_t)sa.fb[f + 1] + sa.delta[f];
+        if (q0 < 0 || q1 > sa.nnz) continue;
+        int64_t q = q0 + tid;
+        for (; q + (kMarkUnroll - 1) * kSortThreads < q1; q += kMarkUnroll * kSortThreads) {
+            uint32_t r[kMarkUnroll];
+#pragma unroll
+            for (int j = 0; j < kMarkUnroll; ++j) r[j] = (uint32_t)(inverse[q + j * kSortThreads] - it.c0);
+#pragma unroll
+            for (int j = 0; j < kMarkUnroll; ++j)
+                if (r[j] < it.width) atomicAdd(&s_cnt[r[j]], 1);
+        }
+        for (; q < q1; q += kSortThreads) {
+            const uint32_t r0 = (uint32_t)(inverse[q] - it.c0);
+            if (r0 < it.width) atomicAdd(&s_cnt[r0], 1);
+        }
+    }
+    __syncthreads();
+    const int per = ((int)it.width + kSortThreads - 1) / kSortThreads;   // consecutive counters per thread
+    int mine = 0;
+    for (int j = 0; j < per; ++j) {
+        const int i = tid * per + j;
+        mine += i < (int)it.width ? s_cnt[i] : 0;
+    }
+    *per_out = per;
+    return block_excl_scan<kSortThreads>(mine, n_item);
+}
+
+// Steps 2 and 3 of an item, given the occurrences of the pack before it: segment offsets,
+// headers of the backward tiles, zeroed partial sums for long keys that cross tile
+// boundaries; then every occurrence's gradient place goes to its segment's cursor.
+__device__ __forceinline__ void sort_place(const SortArgs& sa, const SortItem& it, int32_t* s_cnt, int before,
+                                           int ex, int per)
+{
+    const int tid = threadIdx.x;
+    const int tp = sa.tp, n = it.n;
+    const int32_t* inverse = sa.inverse;
+    int32_t* seg = sa.seg_all + it.start + it.p;
+    uint32_t* ent = sa.ent_all + (size_t)it.start * sa.ent_mult;
+    const size_t tbase = (size_t)(it.start / tp + it.p);
+    int4* th = sa.tile_hdr + tbase;
+    double* gh = sa.ghot + tbase * sa.dmax;
+    const bool wide = it.wide != 0;
+    int s0 = before + ex;
+    for (int j = 0; j < per; ++j) {
+        const int i = tid * per + j;
+        if (i < (int)it.width) {
+            const int len = s_cnt[i];
+            seg[it.c0 + i] = s0;
+            s_cnt[i] = s0;                                 // from here on: the segment's next free position
+            // headers of the backward tiles the segment overlaps: x = the key that holds the
+            // tile's first position, y = the key that holds its last one, z = where the
+            // tile's decoded window ends (its last key is decoded to its end unless it is long)
+            for (int tt = s0 / tp; (int64_t)tt * tp < (int64_t)s0 + len; ++tt) {
+                const int t_first = tt * tp, t_end = min(t_first + tp, n);
+                if (t_first >= s0) th[tt].x = it.c0 + i;
+                if (t_end - 1 < s0 + len) {
+                    th[tt].y = it.c0 + i;
+                    th[tt].z = len <= kWarmMax ? s0 + len : t_end;
+                }
+            }
+            if (len > kWarmMax && s0 / tp != (s0 + len - 1) / tp) {
+                const int slot = s0 / tp;                  // one such key at most starts in a tile
+                for (int d = 0; d < it.dim; ++d) gh[(size_t)slot * it.dim + d] = 0.0;
+            }
+            s0 += len;
+        }
+    }
+    __syncthreads();
+    for (int fi = it.tm.field_begin; fi < it.tm.field_end; ++fi) {
+        const int f = sa.table_fields[fi];
+        const int64_t q0 = (int64_t)sa.fb[f] + sa.delta[f], q1 = (int64_t)sa.fb[f + 1] + sa.delta[f];
+        if (q0 < 0 || q1 > sa.nnz) continue;
+        int64_t q = q0 + tid;
+        for (; q + (kSortUnroll2 - 1) * kSortThreads < q1; q += kSortUnroll2 * kSortThreads) {
+            uint32_t r[kSortUnroll2], e[kSortUnroll2], c[kSortUnroll2];
+#pragma unroll
+            for (int j = 0; j < kSortUnroll2; ++j) {
+                r[j] = (uint32_t)(inverse[q + j * kSortThreads] - it.c0);
+                e[j] = sa.bagref[q + j * kSortThreads];
+                c[j] = wide ? sa.baglen[q + j * kSortThreads] : 1u;
+            }
+#pragma unroll
+            for (int j = 0; j < kSortUnroll2; ++j)
+                if (r[j] < it.width) {
+                    const int pos = atomicAdd(&s_cnt[r[j]], 1);
+                    if ((unsigned)pos < (unsigned)n) {
+                        if (wide) reinterpret_cast<uint2*>(ent)[pos] = make_uint2(e[j], c[j]);
+                        else ent[pos] = e[j];
+                    }
+                }
+        }
+        for (; q < q1; q += kSortThreads) {
+            const uint32_t r0 = (uint32_t)(inverse[q] - it.c0);
+            if (r0 < it.width) {
+                const int pos = atomicAdd(&s_cnt[r0], 1);
+                if ((unsigned)pos < (unsigned)n) {
+                    if (wide) reinterpret_cast<uint2*>(ent)[pos] = make_uint2(sa.bagref[q], sa.baglen[q]);
+                    else ent[pos] = sa.bagref[q];
+                }
+            }
+        }
+    }
+}
+
 // `block` of `nblocks` blocks of kSortThreads threads; s_dyn: (4 T + 1) ints of LDS
 __device__ __forceinline__ void sort_body(const SortArgs& sa, int block, int nblocks, int32_t* s_dyn)
 {
     const TableMeta* __restrict__ tmeta = sa.tmeta;
-    const int32_t* __restrict__ table_fields = sa.table_fields;
-    const int T = sa.T, P = sa.P, ent_mult = sa.ent_mult, tp = sa.tp, dmax = sa.dmax;
+    const int T = sa.T, P = sa.P;
     const PackMeta* __restrict__ pm = sa.pm;
     PackState* st = sa.st;
     const int32_t* __restrict__ fb = sa.fb;
-    const int32_t* __restrict__ delta = sa.delta;
     const uint4* __restrict__ bitmap4 = sa.bitmap4;
     const int32_t* __restrict__ rank = sa.rank;
-    const int32_t* __restrict__ inverse = sa.inverse;
-    const uint32_t* __restrict__ bagref = sa.bagref;
-    const uint32_t* __restrict__ baglen = sa.baglen;
-    int32_t* __restrict__ seg_all = sa.seg_all;
-    uint32_t* __restrict__ ent_all = sa.ent_all;
-    int4* __restrict__ tile_hdr = sa.tile_hdr;
-    uint64_t* desc = sa.desc;
-    double* __restrict__ ghot = sa.ghot;
-    const int64_t nnz = sa.nnz;
     int32_t* s_rlo = s_dyn;                  // [T]   first rank of each table inside its pack
     int32_t* s_u = s_dyn + T;                // [T]   distinct keys of each table
     int32_t* s_first = s_u + T;              // [T+1] first work item of each table
@@ -544,7 +659,7 @@ __device__ __forceinline__ void sort_body(const SortArgs& sa, int block, int nbl
         if (t < T) {
             const TableMeta tm = tmeta[t];
             for (int fi = tm.field_begin; fi < tm.field_end; ++fi) {
-                const int f = table_fields[fi];
+                const int f = sa.table_fields[fi];
                 occ += fb[f + 1] - fb[f];
             }
             const PackMeta k = pm[tm.pack];
@@ -568,139 +683,42 @@ __device__ __forceinline__ void sort_body(const SortArgs& sa, int block, int nbl
     for (int p = block; p < P; p += nblocks)     // the entry after the last segment of each pack
         if (tid == 0) {
             const PackState ps = st[p];
-            seg_all[ps.start + p + ps.n_unique] = ps.nnz;
+            sa.seg_all[ps.start + p + ps.n_unique] = ps.nnz;
         }
     __syncthreads();
     const int total = s_first[T];
     for (int item = block; item < total; item += nblocks) {
         const int t = upper_bound_i32(s_first, T + 1, item) - 1;
-        const TableMeta tm = tmeta[t];
-        const int p = tm.pack;
-        const PackMeta k = pm[p];
-        const int n = st[p].nnz, start = st[p].start;
-        const int c0 = s_rlo[t] + (item - s_first[t]) * kSortCap;
-        const uint32_t occ_before = (uint32_t)(s_occ[t] - s_occ[k.first_stable]);   // in the pack's earlier tables
-        const uint32_t width = (uint32_t)min(kSortCap, s_rlo[t] + s_u[t] - c0);
+        SortItem it;
+        it.tm = tmeta[t];
+        it.p = it.tm.pack;
+        const PackMeta k = pm[it.p];
+        it.dim = k.dim; it.wide = k.has_mean;
+        it.n = st[it.p].nnz; it.start = st[it.p].start;
         const int chunk = item - s_first[t];
+        it.c0 = s_rlo[t] + chunk * kSortCap;
+        it.width = (uint32_t)min(kSortCap, s_rlo[t] + s_u[t] - it.c0);
+        const uint32_t occ_before = (uint32_t)(s_occ[t] - s_occ[k.first_stable]);   // in the pack's earlier tables
         const int first_item = s_first[t];             // the table's first item: its start is known
-        int32_t* seg = seg_all + start + p;
-        uint32_t* ent = ent_all + (size_t)start * ent_mult;
-        const bool wide = k.has_mean != 0;             // entries of this pack carry the 1/L scale
-        const size_t tbase = (size_t)(start / tp + p);
-        int4* th = tile_hdr + tbase;
-        double* gh = ghot + tbase * dmax;
-        __syncthreads();                               // the previous item's LDS is consumed
-        for (int i = tid; i < (int)width; i += kSortThreads) s_cnt[i] = 0;
-        __syncthreads();
-        for (int fi = tm.field_begin; fi < tm.field_end; ++fi) {
-            const int f = table_fields[fi];
-            const int64_t q0 = (int64_t)fb[f] + delta[f], q1 = (int64_t)fb[f + 1] + delta[f];
-            if (q0 < 0 || q1 > nnz) continue;
-            int64_t q = q0 + tid;
-            for (; q + (kMarkUnroll - 1) * kSortThreads < q1; q += kMarkUnroll * kSortThreads) {
-                uint32_t r[kMarkUnroll];
-#pragma unroll
-                for (int j = 0; j < kMarkUnroll; ++j) r[j] = (uint32_t)(inverse[q + j * kSortThreads] - c0);
-#pragma unroll
-                for (int j = 0; j < kMarkUnroll; ++j)
-                    if (r[j] < width) atomicAdd(&s_cnt[r[j]], 1);
-            }
-            for (; q < q1; q += kSortThreads) {
-                const uint32_t r0 = (uint32_t)(inverse[q] - c0);
-                if (r0 < width) atomicAdd(&s_cnt[r0], 1);
-            }
-        }
-        __syncthreads();
-        const int per = ((int)width + kSortThreads - 1) / kSortThreads;   // consecutive counters per thread
-        int mine = 0;
-        for (int j = 0; j < per; ++j) {
-            const int i = tid * per + j;
-            mine += i < (int)width ? s_cnt[i] : 0;
-        }
-        int n_item;
-        const int ex = block_excl_scan<kSortThreads>(mine, &n_item);
+        int per, n_item;
+        const int ex = sort_count(sa, it, s_cnt, &per, &n_item);
         // occurrences before the item: those of the pack's earlier tables (known from the field
         // boundaries) plus those of the table's earlier items (descriptor look-back inside the table)
         if (tid < 64) {
             if (chunk == 0) {
-                if (tid == 0) { publish_desc(desc + item, make_desc(kDescPfx, (uint32_t)n_item, 0)); s_base = occ_before; }
+                if (tid == 0) { publish_desc(sa.desc + item, make_desc(kDescPfx, (uint32_t)n_item, 0)); s_base = occ_before; }
             } else {
-                if (tid == 0) publish_desc(desc + item, make_desc(kDescAgg, (uint32_t)n_item, 0));
+                if (tid == 0) publish_desc(sa.desc + item, make_desc(kDescAgg, (uint32_t)n_item, 0));
                 uint32_t pa, pb;
-                lookback(desc, first_item, item, &pa, &pb, &st[0].error);
+                lookback(sa.desc, first_item, item, &pa, &pb, &st[0].error);
                 if (tid == 0) {
-                    publish_desc(desc + item, make_desc(kDescPfx, pa + (uint32_t)n_item, 0));
+                    publish_desc(sa.desc + item, make_desc(kDescPfx, pa + (uint32_t)n_item, 0));
                     s_base = occ_before + pa;
                 }
             }
         }
         __syncthreads();
-        int s0 = (int)s_base + ex;
-        for (int j = 0; j < per; ++j) {
-            const int i = tid * per + j;
-            if (i < (int)width) {
-                const int len = s_cnt[i];
-                seg[c0 + i] = s0;
-                s_cnt[i] = s0;                                 // from here on: the segment's next free position
-                // headers of the backward tiles the segment overlaps: x = the key that holds the
-                // tile's first position, y = the key that holds its last one, z = where the
-                // tile's decoded window ends (its last key is decoded to its end unless it is long)
-                for (int tt = s0 / tp; (int64_t)tt * tp < (int64_t)s0 + len; ++tt) {
-                    const int t_first = tt * tp, t_end = min(t_first + tp, n);
-                    if (t_first >= s0) th[tt].x = c0 + i;
-                    if (t_end - 1 < s0 + len) {
-                        th[tt].y = c0 + i;
-                        th[tt].z = len <= kWarmMax ? s0 + len : t_end;
-                    }
-                }
-                if (len > kWarmMax && s0 / tp != (s0 + len - 1) / tp) {
-                    const int slot = s0 / tp;                  // one such key at most starts in a tile
-                    for (int d = 0; d < k.dim; ++d) gh[(size_t)slot * k.dim + d] = 0.0;
-                }
-                s0 += len;
-            }
-        }
-        __syncthreads();
-        for (int fi = tm.field_begin; fi < tm.field_end; ++fi) {
-            const int f = table_fields[fi];
-            const int64_t q0 = (int64_t)fb[f] + delta[f], q1 = (int64_t)fb[f + 1] + delta[f];
-            if (q0 < 0 || q1 > nnz) continue;
-            int64_t q = q0 + tid;
-            for (; q + (kSortUnroll2 - 1) * kSortThreads < q1; q += kSortUnroll2 * kSortThreads) {
-                uint32_t r[kSortUnroll2], e[kSortUnroll2];
-                uint32_t c[kSortUnroll2];
-#pragma unroll
-                for (int j = 0; j < kSortUnroll2; ++j) {
-                    r[j] = (uint32_t)(inverse[q + j * kSortThreads] - c0);
-                    e[j] = bagref[q + j * kSortThreads];
-                    c[j] = wide ? baglen[q + j * kSortThreads] : 1u;
-                }
-#pragma unroll
-                for (int j = 0; j < kSortUnroll2; ++j)
-                    if (r[j] < width) {
-                        const int pos = atomicAdd(&s_cnt[r[j]], 1);
-#ifdef PK_EXP_NOSTORE
-                        if (pos == -12345) {
-#else
-                        if ((unsigned)pos < (unsigned)n) {
-#endif
-                            if (wide) reinterpret_cast<uint2*>(ent)[pos] = make_uint2(e[j], c[j]);
-                            else ent[pos] = e[j];
-                        }
-                    }
-            }
-            for (; q < q1; q += kSortThreads) {
-                const uint32_t r0 = (uint32_t)(inverse[q] - c0);
-                if (r0 < width) {
-                    const int pos = atomicAdd(&s_cnt[r0], 1);
-                    if ((unsigned)pos < (unsigned)n) {
-                        if (wide) reinterpret_cast<uint2*>(ent)[pos] = make_uint2(bagref[q], baglen[q]);
-                        else ent[pos] = bagref[q];
-                    }
-                }
-            }
-        }
-        __syncthreads();
+        sort_place(sa, it, s_cnt, (int)s_base, ex, per);
     }
 }
 
