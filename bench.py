@@ -56,16 +56,18 @@ def step_model_bytes(info):
 def measured_traffic(kernel, workload):
     """HBM bytes per launch of `kernel` as rocprofv3's FETCH_SIZE / WRITE_SIZE counters measured them on this
     workload (two --pmc runs of this script, scaled by what the same counters read for a plain 1 GiB copy);
-    the summary under profiles/ holds the figure and the commands.  None when no summary is there."""
-    path = os.path.join(ROOT, "profiles", f"{kernel}_{workload}_hbm_traffic.txt")
+    the summary under profiles/ holds the per-kernel figures and the commands.  None when it is not there."""
+    path = os.path.join(ROOT, "profiles", f"all_kernels_{workload}_hbm_traffic.txt")
+    totals = []
     try:
         with open(path) as fh:
             for line in fh:
-                if line.startswith("traffic_bytes_per_launch"):
-                    return float(line.split("=")[1])
+                name = line.split(" ")[0]
+                if name == kernel + "_kernel" or name.startswith(kernel + "_kernel<"):
+                    totals.append(float(line.split("total=")[1]) * 1e6)      # MB per launch
     except OSError:
         pass
-    return None
+    return sum(totals) / len(totals) if totals else None     # one launch of each instantiation per step
 
 
 def main():
@@ -202,11 +204,10 @@ def main():
     if not args.no_cpu_baseline:
         from oracle import pk_oracle as orc
         from oracle.sparse_tables import SparseOracle
-        n_cpu = 3 if idx <= 2 else 1
         so = SparseOracle(orc, synth, wl)
-        times, looks = [], 0
-        for i in range(n_cpu):
-            b = batches[i % ring]
+        times, looks, n_cpu = [], 0, 0
+        while sum(times) < 10.0 and n_cpu < 4 * ring:      # about 10 s of oracle work, at most 4 passes of the ring
+            b = batches[n_cpu % ring]
             pre = []
             for p in range(so.pl.n_packs):            # materialise the rows outside the timed part
                 key, _ = orc.pack_keys(so.pl, p, wl.batch, b.ids, b.offsets)
@@ -216,6 +217,7 @@ def main():
             so.step(b, wl.lr, wl.eps, rows=pre)
             times.append(time.perf_counter() - t1)
             looks += b.nnz
+            n_cpu += 1
         cpu = {"value": looks / sum(times), "unit": "lookups/s", "cores": 1, "kind": "oracle",
                "sample": f"{n_cpu} batch(es) of {args.workload} ({looks} lookups), single thread; the rows of the "
                          f"distinct keys are materialised by the input generator before the clock starts"}
