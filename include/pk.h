@@ -143,6 +143,58 @@ pk_status pk_backward_update(const pk_plan* plan, void* const* W, float* const* 
                              float lr, float eps,
                              void* workspace, size_t ws_bytes, void* hip_stream);
 
+/* ---- HybridHash (Sec. III-D, Alg. 1): a Hot-storage in front of the tables -----
+ * The pack's table passed as W_cold / A_cold is the Cold-storage and holds every
+ * row; it only has to be device-ACCESSIBLE, so it may be pinned host memory
+ * (hipHostMalloc) read and written by the kernels over the bus.  The Hot-storage
+ * is a small device array holding, and taking the updates of, the rows queried
+ * most often.  FCounter counts, per row, the iterations in which the row was
+ * queried (the layer queries the distinct rows of a batch: Gather follows Unique).
+ * One iteration = pk_hh_forward, pk_hh_backward_update, pk_hh_end_iteration:
+ *   itr <  warmup_iters: every row is served by the Cold-storage, FCounter counts;
+ *   itr >= warmup_iters: a row found in the Hot-storage is read and updated there,
+ *     the others in the Cold-storage; FCounter counts; when itr is a multiple of
+ *     flush_iters the Hot-storage is written back and reloaded with the top-k
+ *     rows of FCounter (larger count first, equal counts by smaller row; rows
+ *     never queried do not enter; k = hot_rows).
+ * The Hot-storage never changes a value the layer computes.  All buffers belong
+ * to the caller; pk_hh_init must run once before the first iteration. */
+typedef struct {
+    void*     W_cold;    /* device-accessible, [total_rows, dim], the pack's dtype        */
+    float*    A_cold;    /* device-accessible, fp32 [total_rows, dim]                     */
+    void*     W_hot;     /* device, [hot_rows, dim], the pack's dtype                     */
+    float*    A_hot;     /* device, fp32 [hot_rows, dim]                                  */
+    int32_t*  slot_of;   /* device, [total_rows]: the row's slot in the Hot-storage or -1 */
+    uint32_t* hot_row;   /* device, [hot_rows]: the row each slot holds, ascending        */
+    uint32_t* fcounter;  /* device, [total_rows]                                          */
+    int64_t   hot_rows;  /* k, the capacity of the Hot-storage in rows (>= 0)             */
+} pk_hh_pack;
+
+/* Device scratch needed by pk_hh_end_iteration (256-byte aligned); 0 on error. */
+size_t    pk_hh_scratch_bytes(const pk_plan* plan);
+/* packs: host array of n_packs entries.  Empties the Hot-storage bookkeeping
+ * (slot_of = -1, FCounter = 0).  Enqueues on hip_stream. */
+pk_status pk_hh_init(pk_plan* plan, const pk_hh_pack* packs, void* hip_stream);
+/* As pk_forward / pk_backward_update, with rows read and updated where they live. */
+pk_status pk_hh_forward(const pk_plan* plan, const pk_hh_pack* packs,
+                        const int64_t* ids, const int32_t* offsets, int32_t B, int64_t nnz,
+                        float* out, int64_t out_row_stride,
+                        void* workspace, size_t ws_bytes, void* hip_stream);
+pk_status pk_hh_backward_update(const pk_plan* plan, const pk_hh_pack* packs,
+                                const float* grad_out, int64_t grad_row_stride, int32_t B, int64_t nnz,
+                                float lr, float eps, void* workspace, size_t ws_bytes, void* hip_stream);
+/* The bookkeeping of Alg. 1 for the batch of the preceding pk_hh_forward (same B,
+ * nnz, workspace): FCounter, and the reload when it is due.  queried / hits: host
+ * arrays of n_packs entries or NULL: distinct rows queried by the batch and how
+ * many of them were in the Hot-storage; *flushed (or NULL): whether a reload took
+ * place.  SYNCHRONISES hip_stream when it returns counts or reloads. */
+pk_status pk_hh_end_iteration(pk_plan* plan, const pk_hh_pack* packs, int64_t itr,
+                              int32_t warmup_iters, int32_t flush_iters, int32_t B, int64_t nnz,
+                              const void* workspace, size_t ws_bytes, void* scratch, size_t scratch_bytes,
+                              void* hip_stream, int64_t* queried, int64_t* hits, int32_t* flushed);
+/* Rows currently in pack p's Hot-storage (host-side count). */
+pk_status pk_hh_hot_count(const pk_plan* plan, int32_t p, int64_t* n_hot);
+
 /* ---- parity access to the context saved in the workspace ---------------------
  * SYNCHRONISES the device (copies a few bytes of the header back).  Returns
  * device pointers into the workspace, valid until the next pk_forward:

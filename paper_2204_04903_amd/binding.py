@@ -24,6 +24,8 @@ EXPORTS = [
     "pk_plan_create", "pk_plan_destroy", "pk_plan_num_packs", "pk_plan_pack_info", "pk_plan_pack_fields",
     "pk_plan_table_slot", "pk_plan_field_col", "pk_plan_out_dim", "pk_workspace_bytes", "pk_forward",
     "pk_backward_update", "pk_ctx_pack", "pk_ctx_error", "pk_profile_enable", "pk_profile_read", "pk_last_error",
+    "pk_hh_scratch_bytes", "pk_hh_init", "pk_hh_forward", "pk_hh_backward_update", "pk_hh_end_iteration",
+    "pk_hh_hot_count",
 ]
 
 
@@ -38,6 +40,12 @@ class pk_field_desc(ctypes.Structure):
 class pk_plan_opts(ctypes.Structure):
     _fields_ = [("max_batch", ctypes.c_int32), ("max_nnz", ctypes.c_int64), ("max_shards", ctypes.c_int32),
                 ("field_volume", ctypes.POINTER(ctypes.c_double)), ("interleave_groups", ctypes.c_int32)]
+
+
+class pk_hh_pack(ctypes.Structure):
+    _fields_ = [("W_cold", ctypes.c_void_p), ("A_cold", ctypes.c_void_p), ("W_hot", ctypes.c_void_p),
+                ("A_hot", ctypes.c_void_p), ("slot_of", ctypes.c_void_p), ("hot_row", ctypes.c_void_p),
+                ("fcounter", ctypes.c_void_p), ("hot_rows", ctypes.c_int64)]
 
 
 class PkError(RuntimeError):
@@ -105,6 +113,21 @@ def lib():
                                       ctypes.POINTER(i64), i32]
         L.pk_last_error.restype = ctypes.c_char_p
         L.pk_last_error.argtypes = []
+        hp = ctypes.POINTER(pk_hh_pack)
+        L.pk_hh_scratch_bytes.restype = ctypes.c_size_t
+        L.pk_hh_scratch_bytes.argtypes = [vp]
+        L.pk_hh_init.restype = ctypes.c_int
+        L.pk_hh_init.argtypes = [vp, hp, vp]
+        L.pk_hh_forward.restype = ctypes.c_int
+        L.pk_hh_forward.argtypes = [vp, hp, vp, vp, i32, i64, vp, i64, vp, ctypes.c_size_t, vp]
+        L.pk_hh_backward_update.restype = ctypes.c_int
+        L.pk_hh_backward_update.argtypes = [vp, hp, vp, i64, i32, i64, ctypes.c_float, ctypes.c_float, vp,
+                                            ctypes.c_size_t, vp]
+        L.pk_hh_end_iteration.restype = ctypes.c_int
+        L.pk_hh_end_iteration.argtypes = [vp, hp, i64, i32, i32, i32, i64, vp, ctypes.c_size_t, vp, ctypes.c_size_t, vp,
+                                          ctypes.POINTER(i64), ctypes.POINTER(i64), ctypes.POINTER(i32)]
+        L.pk_hh_hot_count.restype = ctypes.c_int
+        L.pk_hh_hot_count.argtypes = [vp, i32, ctypes.POINTER(i64)]
         _lib = L
     return _lib
 
@@ -204,6 +227,60 @@ def pk_backward_update(plan: int, W: Sequence, A: Sequence, grad_out, grad_row_s
                        lr: float, eps: float, workspace, ws_bytes: int, stream: int = 0) -> None:
     _check(lib().pk_backward_update(plan, _ptr_array(W), _ptr_array(A), _ptr(grad_out), grad_row_stride, B, nnz,
                                     lr, eps, _ptr(workspace), ws_bytes, stream))
+
+
+def _hh_array(packs: Sequence[dict]):
+    """packs: per pack a dict with W_cold, A_cold, W_hot, A_hot, slot_of, hot_row, fcounter (tensors or
+    addresses) and hot_rows."""
+    arr = (pk_hh_pack * max(len(packs), 1))()
+    for i, d in enumerate(packs):
+        for name in ("W_cold", "A_cold", "W_hot", "A_hot", "slot_of", "hot_row", "fcounter"):
+            setattr(arr[i], name, _ptr(d.get(name)))
+        arr[i].hot_rows = int(d["hot_rows"])
+    return arr
+
+
+def pk_hh_scratch_bytes(plan: int) -> int:
+    n = int(lib().pk_hh_scratch_bytes(plan))
+    if n == 0:
+        raise PkError(PK_EINVAL, pk_last_error())
+    return n
+
+
+def pk_hh_init(plan: int, packs: Sequence[dict], stream: int = 0) -> None:
+    _check(lib().pk_hh_init(plan, _hh_array(packs), stream))
+
+
+def pk_hh_forward(plan: int, packs: Sequence[dict], ids, offsets, B: int, nnz: int, out, out_row_stride: int,
+                  workspace, ws_bytes: int, stream: int = 0) -> None:
+    _check(lib().pk_hh_forward(plan, _hh_array(packs), _ptr(ids), _ptr(offsets), B, nnz, _ptr(out), out_row_stride,
+                               _ptr(workspace), ws_bytes, stream))
+
+
+def pk_hh_backward_update(plan: int, packs: Sequence[dict], grad_out, grad_row_stride: int, B: int, nnz: int,
+                          lr: float, eps: float, workspace, ws_bytes: int, stream: int = 0) -> None:
+    _check(lib().pk_hh_backward_update(plan, _hh_array(packs), _ptr(grad_out), grad_row_stride, B, nnz, lr, eps,
+                                       _ptr(workspace), ws_bytes, stream))
+
+
+def pk_hh_end_iteration(plan: int, packs: Sequence[dict], itr: int, warmup_iters: int, flush_iters: int, B: int,
+                        nnz: int, workspace, ws_bytes: int, scratch, scratch_bytes: int, stream: int = 0,
+                        want_counts: bool = True):
+    """Returns (queried per pack, hits per pack, flushed)."""
+    n = len(packs)
+    q = (ctypes.c_int64 * max(n, 1))()
+    h = (ctypes.c_int64 * max(n, 1))()
+    fl = ctypes.c_int32()
+    _check(lib().pk_hh_end_iteration(plan, _hh_array(packs), itr, warmup_iters, flush_iters, B, nnz, _ptr(workspace),
+                                     ws_bytes, _ptr(scratch), scratch_bytes, stream, q if want_counts else None,
+                                     h if want_counts else None, ctypes.byref(fl)))
+    return list(q)[:n], list(h)[:n], bool(fl.value)
+
+
+def pk_hh_hot_count(plan: int, p: int) -> int:
+    n = ctypes.c_int64()
+    _check(lib().pk_hh_hot_count(plan, p, ctypes.byref(n)))
+    return n.value
 
 
 def pk_ctx_pack(plan: int, workspace, B: int, nnz: int, p: int) -> dict:

@@ -809,19 +809,57 @@ __device__ __forceinline__ void store_f32(float* p, const float* v)
 }
 
 // ---------------------------------------------------------------------------
+// Where a row lives.  Plain tables: row r of the pack's table.  With HybridHash
+// (Sec. III-D) the table passed to the kernel is the Cold-storage (every row) and
+// the frequently queried rows live, and are updated, in a small Hot-storage:
+// slot_of[r] >= 0 names the row's slot there.  slot_of == nullptr: no Hot-storage.
+// ---------------------------------------------------------------------------
+struct HotView {
+    const int32_t* slot_of;
+    void* W_hot;
+    float* A_hot;
+};
+
+template <typename WT, bool HYB>
+__device__ __forceinline__ WT* row_of(WT* cold, const HotView& hv, uint32_t row, int D)
+{
+    if constexpr (HYB) {
+        const int s = hv.slot_of[row];
+        if (s >= 0) return static_cast<WT*>(hv.W_hot) + (size_t)s * D;
+    }
+    return cold + (size_t)row * D;
+}
+
+// the row's weights and its accumulator
+template <typename WT>
+__device__ __forceinline__ void rows_of(WT* W, float* A, const HotView& hv, uint32_t row, int D, WT** wrow, float** arow)
+{
+    if (hv.slot_of) {
+        const int s = hv.slot_of[row];
+        if (s >= 0) {
+            *wrow = static_cast<WT*>(hv.W_hot) + (size_t)s * D;
+            *arow = hv.A_hot + (size_t)s * D;
+            return;
+        }
+    }
+    *wrow = W + (size_t)row * D;
+    *arow = A + (size_t)row * D;
+}
+
+// ---------------------------------------------------------------------------
 // H3+H4+H5: Gather and SegmentReduction (Sec. II-D) fused (K-Packing, Sec.
 // III-B: both are memory-bound), one launch per pack.  A group of LPR lanes owns
 // one bag; each lane covers VEC (x NCH) columns, so a row is read with one
 // coalesced access.  The concatenation of the fields of a sample is the write
 // address.
 // ---------------------------------------------------------------------------
-// `block` of `nblocks` blocks of `nthreads` threads
-template <typename WT, int VEC, int LPR, int NCH>
+// `block` of `nblocks` blocks of `nthreads` threads; HYB: rows may live in a Hot-storage
+template <typename WT, int VEC, int LPR, int NCH, bool HYB>
 __device__ __forceinline__ void pool_body(const WT* __restrict__ W, const uint32_t* __restrict__ keys_all,
                                           const int32_t* __restrict__ po, const PackState* __restrict__ st,
                                           const FieldMeta* __restrict__ fmeta, const int32_t* __restrict__ slot_field,
                                           int B, int D, int64_t n_bags, float* __restrict__ out, int64_t out_stride,
-                                          int block, int nblocks, int nthreads)
+                                          int block, int nblocks, int nthreads, const HotView hv)
 {
     const int GPB = nthreads / LPR;
     const int li = threadIdx.x % LPR, gi = threadIdx.x / LPR;
@@ -840,30 +878,32 @@ __device__ __forceinline__ void pool_body(const WT* __restrict__ W, const uint32
             for (int v = 0; v < VEC; ++v) acc[c][v] = 0.f;
         int q = q0;
         for (; q + 4 <= q1; q += 4) {
-            const size_t r0 = (size_t)keys[q] * D, r1 = (size_t)keys[q + 1] * D;
-            const size_t r2 = (size_t)keys[q + 2] * D, r3 = (size_t)keys[q + 3] * D;
+            const WT* r0 = row_of<const WT, HYB>(W, hv, keys[q], D);
+            const WT* r1 = row_of<const WT, HYB>(W, hv, keys[q + 1], D);
+            const WT* r2 = row_of<const WT, HYB>(W, hv, keys[q + 2], D);
+            const WT* r3 = row_of<const WT, HYB>(W, hv, keys[q + 3], D);
 #pragma unroll
             for (int c = 0; c < NCH; ++c) {
                 const int d0 = (c * LPR + li) * VEC;
                 if (d0 < D) {
                     float x0[VEC], x1[VEC], x2[VEC], x3[VEC];
-                    Row<WT, VEC>::load(W + r0 + d0, x0);
-                    Row<WT, VEC>::load(W + r1 + d0, x1);
-                    Row<WT, VEC>::load(W + r2 + d0, x2);
-                    Row<WT, VEC>::load(W + r3 + d0, x3);
+                    Row<WT, VEC>::load(r0 + d0, x0);
+                    Row<WT, VEC>::load(r1 + d0, x1);
+                    Row<WT, VEC>::load(r2 + d0, x2);
+                    Row<WT, VEC>::load(r3 + d0, x3);
 #pragma unroll
                     for (int v = 0; v < VEC; ++v) acc[c][v] += (x0[v] + x1[v]) + (x2[v] + x3[v]);
                 }
             }
         }
         for (; q < q1; ++q) {
-            const size_t r0 = (size_t)keys[q] * D;
+            const WT* r0 = row_of<const WT, HYB>(W, hv, keys[q], D);
 #pragma unroll
             for (int c = 0; c < NCH; ++c) {
                 const int d0 = (c * LPR + li) * VEC;
                 if (d0 < D) {
                     float x0[VEC];
-                    Row<WT, VEC>::load(W + r0 + d0, x0);
+                    Row<WT, VEC>::load(r0 + d0, x0);
 #pragma unroll
                     for (int v = 0; v < VEC; ++v) acc[c][v] += x0[v];
                 }
@@ -883,15 +923,15 @@ __device__ __forceinline__ void pool_body(const WT* __restrict__ W, const uint32
     }
 }
 
-template <typename WT, int VEC, int LPR, int NCH>
+template <typename WT, int VEC, int LPR, int NCH, bool HYB>
 __global__ void __launch_bounds__(NT)
 pk_pool_kernel(const WT* __restrict__ W, const uint32_t* __restrict__ keys_all, const int32_t* __restrict__ po,
                const PackState* __restrict__ st, const FieldMeta* __restrict__ fmeta,
                const int32_t* __restrict__ slot_field, int B, int D, int64_t n_bags,
-               float* __restrict__ out, int64_t out_stride)
+               float* __restrict__ out, int64_t out_stride, const HotView hv)
 {
-    pool_body<WT, VEC, LPR, NCH>(W, keys_all, po, st, fmeta, slot_field, B, D, n_bags, out, out_stride,
-                                 blockIdx.x, gridDim.x, NT);
+    pool_body<WT, VEC, LPR, NCH, HYB>(W, keys_all, po, st, fmeta, slot_field, B, D, n_bags, out, out_stride,
+                                      blockIdx.x, gridDim.x, NT, hv);
 }
 
 // Small batches: the sort kernel has few work items (one per table) and leaves most of the
@@ -911,21 +951,21 @@ struct PoolJob {
 
 // variant = 12 * dtype + shape; the shapes in the order of the host's dispatch
 #define PK_POOL_SHAPES(WT, VECW, base)                                                          \
-    case base + 0:  pool_body<WT, VECW, 1, 1>(PK_POOL_ARGS); break;                             \
-    case base + 1:  pool_body<WT, VECW, 2, 1>(PK_POOL_ARGS); break;                             \
-    case base + 2:  pool_body<WT, VECW, 4, 1>(PK_POOL_ARGS); break;                             \
-    case base + 3:  pool_body<WT, VECW, 8, 1>(PK_POOL_ARGS); break;                             \
-    case base + 4:  pool_body<WT, VECW, 16, 1>(PK_POOL_ARGS); break;                            \
-    case base + 5:  pool_body<WT, VECW, 32, 1>(PK_POOL_ARGS); break;                            \
-    case base + 6:  pool_body<WT, VECW, 64, 1>(PK_POOL_ARGS); break;                            \
-    case base + 7:  pool_body<WT, 1, 4, 1>(PK_POOL_ARGS); break;                                \
-    case base + 8:  pool_body<WT, 1, 16, 1>(PK_POOL_ARGS); break;                               \
-    case base + 9:  pool_body<WT, 1, 64, 1>(PK_POOL_ARGS); break;                               \
-    case base + 10: pool_body<WT, 1, 64, 2>(PK_POOL_ARGS); break;                               \
-    case base + 11: pool_body<WT, 1, 64, 4>(PK_POOL_ARGS); break;
+    case base + 0:  pool_body<WT, VECW, 1, 1, false>(PK_POOL_ARGS); break;                             \
+    case base + 1:  pool_body<WT, VECW, 2, 1, false>(PK_POOL_ARGS); break;                             \
+    case base + 2:  pool_body<WT, VECW, 4, 1, false>(PK_POOL_ARGS); break;                             \
+    case base + 3:  pool_body<WT, VECW, 8, 1, false>(PK_POOL_ARGS); break;                             \
+    case base + 4:  pool_body<WT, VECW, 16, 1, false>(PK_POOL_ARGS); break;                            \
+    case base + 5:  pool_body<WT, VECW, 32, 1, false>(PK_POOL_ARGS); break;                            \
+    case base + 6:  pool_body<WT, VECW, 64, 1, false>(PK_POOL_ARGS); break;                            \
+    case base + 7:  pool_body<WT, 1, 4, 1, false>(PK_POOL_ARGS); break;                                \
+    case base + 8:  pool_body<WT, 1, 16, 1, false>(PK_POOL_ARGS); break;                               \
+    case base + 9:  pool_body<WT, 1, 64, 1, false>(PK_POOL_ARGS); break;                               \
+    case base + 10: pool_body<WT, 1, 64, 2, false>(PK_POOL_ARGS); break;                               \
+    case base + 11: pool_body<WT, 1, 64, 4, false>(PK_POOL_ARGS); break;
 #define PK_POOL_ARGS                                                                            \
     static_cast<const WT_*>(k.W), pj.keys, k.po, pj.st + k.pad, pj.fmeta, k.slot_field, pj.B, k.D, k.n_bags, pj.out,  \
-        pj.out_stride, local, n_local, kSortThreads
+        pj.out_stride, local, n_local, kSortThreads, HotView{nullptr, nullptr, nullptr}
 
 __global__ void __launch_bounds__(kSortThreads, 8)
 pk_sort_pool_kernel(SortArgs sa, PoolJob pj, int sort_blocks)
@@ -1033,22 +1073,22 @@ __device__ __forceinline__ void accum_range(double (&acc)[NCH][VEC], const GradS
 // the row's current weights and accumulators (issued before the gradient
 // reduction so that both sets of loads are in flight together)
 template <typename WT, int VEC, int LPR, int NCH>
-__device__ __forceinline__ void row_load(const WT* W, const float* A, size_t row, int D, int li,
+__device__ __forceinline__ void row_load(const WT* wrow, const float* arow, int D, int li,
                                          float (&w)[NCH][VEC], float (&a)[NCH][VEC])
 {
 #pragma unroll
     for (int c = 0; c < NCH; ++c) {
         const int d0 = (c * LPR + li) * VEC;
         if (d0 < D) {
-            Row<WT, VEC>::load(W + row * D + d0, w[c]);
-            load_f32<VEC>(A + row * D + d0, a[c]);
+            Row<WT, VEC>::load(wrow + d0, w[c]);
+            load_f32<VEC>(arow + d0, a[c]);
         }
     }
 }
 
 // one Adagrad step of the row: a += g^2 ; w -= lr * g / (sqrt(a) + eps)
 template <typename WT, int VEC, int LPR, int NCH>
-__device__ __forceinline__ void row_step(WT* W, float* A, size_t row, int D, int li,
+__device__ __forceinline__ void row_step(WT* wrow, float* arow, int D, int li,
                                          const double (&acc)[NCH][VEC], float (&w)[NCH][VEC],
                                          float (&a)[NCH][VEC], float lr, float eps)
 {
@@ -1062,8 +1102,8 @@ __device__ __forceinline__ void row_step(WT* W, float* A, size_t row, int D, int
                 a[c][v] = a[c][v] + g * g;
                 w[c][v] = w[c][v] - lr * g / (sqrtf(a[c][v]) + eps);
             }
-            store_f32<VEC>(A + row * D + d0, a[c]);
-            Row<WT, VEC>::store(W + row * D + d0, w[c]);
+            store_f32<VEC>(arow + d0, a[c]);
+            Row<WT, VEC>::store(wrow + d0, w[c]);
         }
     }
 }
@@ -1087,7 +1127,7 @@ pk_adagrad_kernel(WT* W, float* A, const PackState* __restrict__ st, int p,
                   double* ghot_all, int dmax, const int4* __restrict__ tile_hdr, int tp, int n_host,
                   const uint32_t* __restrict__ seg_ent_all, int ent_mult,
                   const float* __restrict__ grad, int64_t gstride, int64_t out_dim, uint32_t addr_max, int D,
-                  float lr, float eps)
+                  float lr, float eps, const HotView hv)
 {
     constexpr int GPB = NT / LPR;          // lane groups per block
     constexpr int GPW = 64 / LPR;          // lane groups per wavefront
@@ -1159,16 +1199,18 @@ pk_adagrad_kernel(WT* W, float* A, const PackState* __restrict__ st, int p,
             const int len = s1 - s0;
             if (len <= kColdMax) {
                 if (s0 >= t0) {
-                    const size_t row = s_row[k];
+                    WT* wrow;
+                    float* arow;
+                    rows_of<WT>(W, A, hv, s_row[k], D, &wrow, &arow);
                     float w[NCH][VEC], a[NCH][VEC];
-                    row_load<WT, VEC, LPR, NCH>(W, A, row, D, li, w, a);
+                    row_load<WT, VEC, LPR, NCH>(wrow, arow, D, li, w, a);
                     double acc[NCH][VEC];
 #pragma unroll
                     for (int c = 0; c < NCH; ++c)
 #pragma unroll
                         for (int v = 0; v < VEC; ++v) acc[c][v] = 0.0;
                     accum_range<VEC, LPR, NCH, MEAN>(acc, g, D, li, s0, s1, 1);
-                    row_step<WT, VEC, LPR, NCH>(W, A, row, D, li, acc, w, a, lr, eps);
+                    row_step<WT, VEC, LPR, NCH>(wrow, arow, D, li, acc, w, a, lr, eps);
                 }
             } else if (len <= kWarmMax || (s0 >= t0 && s1 <= t1)) {   // fits the decoded window
                 if (s0 >= t0 && li == 0) s_warm[atomicAdd(&s_nwarm, 1)] = k;
@@ -1182,9 +1224,11 @@ pk_adagrad_kernel(WT* W, float* A, const PackState* __restrict__ st, int p,
         for (int i = wv; i < n_warm; i += NT / 64) {
             const int k = s_warm[i];
             const int s0 = s_seg[k], s1 = s_seg[k + 1];
-            const size_t row = s_row[k];
+            WT* wrow;
+            float* arow;
+            rows_of<WT>(W, A, hv, s_row[k], D, &wrow, &arow);
             float w[NCH][VEC], a[NCH][VEC];
-            if (gw == 0) row_load<WT, VEC, LPR, NCH>(W, A, row, D, li, w, a);
+            if (gw == 0) row_load<WT, VEC, LPR, NCH>(wrow, arow, D, li, w, a);
             double acc[NCH][VEC];
 #pragma unroll
             for (int c = 0; c < NCH; ++c)
@@ -1192,7 +1236,7 @@ pk_adagrad_kernel(WT* W, float* A, const PackState* __restrict__ st, int p,
                 for (int v = 0; v < VEC; ++v) acc[c][v] = 0.0;
             accum_range<VEC, LPR, NCH, MEAN>(acc, g, D, li, s0 + gw, s1, GPW);
             wave_group_sum<VEC, LPR, NCH>(acc);
-            if (gw == 0) row_step<WT, VEC, LPR, NCH>(W, A, row, D, li, acc, w, a, lr, eps);
+            if (gw == 0) row_step<WT, VEC, LPR, NCH>(wrow, arow, D, li, acc, w, a, lr, eps);
         }
         // long keys that cross tile boundaries: the tile's piece is split over the block's
         // wavefronts, reduced in LDS and added to the key's partial sums;
@@ -1253,6 +1297,7 @@ pk_adagrad_kernel(WT* W, float* A, const PackState* __restrict__ st, int p,
 struct HotPacks {
     void* W[16];
     float* A[16];
+    HotView hv[16];
 };
 
 __global__ void __launch_bounds__(NT)
@@ -1274,20 +1319,162 @@ pk_adagrad_hot_kernel(HotPacks ptrs, int p0, const PackMeta* __restrict__ pm, co
         const int u = th[t + 1].x;                             // the key that holds the next tile's first position
         const int s0 = seg[u], s1 = seg[u + 1];
         if (s0 < t * tp || s0 >= (t + 1) * tp || s1 - s0 <= kWarmMax) continue;
-        const size_t row = unique_all[start + u];
-        float* A = ptrs.A[blockIdx.y];
-        for (int d = lane; d < D; d += 64) {
-            const float g = (float)gh[(size_t)t * D + d];
-            const float a = A[row * D + d] + g * g;
-            A[row * D + d] = a;
-            if (k.dtype == PK_F32) {
-                float* W = static_cast<float*>(ptrs.W[blockIdx.y]);
-                W[row * D + d] = W[row * D + d] - lr * g / (sqrtf(a) + eps);
-            } else {
-                uint16_t* W = static_cast<uint16_t*>(ptrs.W[blockIdx.y]);
-                W[row * D + d] = (uint16_t)f32_to_bf16(bf16_to_f32(W[row * D + d]) - lr * g / (sqrtf(a) + eps));
+        const uint32_t row = unique_all[start + u];
+        if (k.dtype == PK_F32) {
+            float* wrow;
+            float* arow;
+            rows_of<float>(static_cast<float*>(ptrs.W[blockIdx.y]), ptrs.A[blockIdx.y], ptrs.hv[blockIdx.y], row, D, &wrow, &arow);
+            for (int d = lane; d < D; d += 64) {
+                const float g = (float)gh[(size_t)t * D + d];
+                const float a = arow[d] + g * g;
+                arow[d] = a;
+                wrow[d] = wrow[d] - lr * g / (sqrtf(a) + eps);
+            }
+        } else {
+            uint16_t* wrow;
+            float* arow;
+            rows_of<uint16_t>(static_cast<uint16_t*>(ptrs.W[blockIdx.y]), ptrs.A[blockIdx.y], ptrs.hv[blockIdx.y], row, D, &wrow, &arow);
+            for (int d = lane; d < D; d += 64) {
+                const float g = (float)gh[(size_t)t * D + d];
+                const float a = arow[d] + g * g;
+                arow[d] = a;
+                wrow[d] = (uint16_t)f32_to_bf16(bf16_to_f32(wrow[d]) - lr * g / (sqrtf(a) + eps));
             }
         }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// HybridHash (Sec. III-D, Alg. 1): bookkeeping of the Hot-storage.
+// ---------------------------------------------------------------------------
+constexpr int kHhBins = 65536;         // histogram of FCounter values; larger counts share the last bin
+constexpr int kHhTile = 2048;          // rows per block of the selection kernels
+
+// FCounter(id) += 1 for the distinct rows the batch queried; hits = those found in the Hot-storage
+__global__ void __launch_bounds__(NT)
+pk_hh_count_kernel(const PackState* __restrict__ st, int p, const uint32_t* __restrict__ unique_all,
+                   const int32_t* __restrict__ slot_of, uint32_t* __restrict__ fcounter,
+                   unsigned long long* counters)
+{
+    __shared__ int s_hits[NT / 64];
+    const int U = st[p].n_unique;
+    const uint32_t* uq = unique_all + st[p].start;
+    int hits = 0;
+    for (int u = blockIdx.x * NT + threadIdx.x; u < U; u += gridDim.x * NT) {
+        const uint32_t row = uq[u];
+        fcounter[row] += 1;                      // the distinct rows are distinct: no two threads share one
+        hits += slot_of[row] >= 0;
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) hits += __shfl_xor(hits, o, 64);
+    if ((threadIdx.x & 63) == 0) s_hits[threadIdx.x >> 6] = hits;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int t = 0;
+        for (int i = 0; i < NT / 64; ++i) t += s_hits[i];
+        if (t) atomicAdd(&counters[2 * p + 1], (unsigned long long)t);
+        if (blockIdx.x == 0) counters[2 * p] = (unsigned long long)U;
+    }
+}
+
+// rows between the two storages: one wavefront per slot, lanes over the row's elements
+template <typename WT>
+__global__ void __launch_bounds__(NT)
+pk_hh_move_kernel(WT* W_cold, float* A_cold, WT* W_hot, float* A_hot, const uint32_t* __restrict__ hot_row,
+                  int32_t* slot_of, int64_t n_hot, int D, int to_cold)
+{
+    const int lane = threadIdx.x & 63;
+    for (int64_t s = (int64_t)blockIdx.x * (NT / 64) + (threadIdx.x >> 6); s < n_hot; s += (int64_t)gridDim.x * (NT / 64)) {
+        const size_t row = hot_row[s];
+        for (int d = lane; d < D; d += 64) {
+            if (to_cold) { W_cold[row * D + d] = W_hot[s * D + d]; A_cold[row * D + d] = A_hot[s * D + d]; }
+            else { W_hot[s * D + d] = W_cold[row * D + d]; A_hot[s * D + d] = A_cold[row * D + d]; }
+        }
+        if (lane == 0) slot_of[row] = to_cold ? -1 : (int32_t)s;
+    }
+}
+
+__global__ void __launch_bounds__(NT)
+pk_hh_hist_kernel(const uint32_t* __restrict__ fcounter, int64_t rows, uint32_t* hist)
+{
+    for (int64_t r = (int64_t)blockIdx.x * NT + threadIdx.x; r < rows; r += (int64_t)gridDim.x * NT) {
+        const uint32_t c = fcounter[r];
+        if (c) atomicAdd(&hist[min(c, (uint32_t)(kHhBins - 1))], 1u);
+    }
+}
+
+// class of a row for the selection: 2 = count above the threshold, 1 = equal to it, 0 = below
+__device__ __forceinline__ int hh_class(uint32_t c, uint32_t thr)
+{
+    const uint32_t b = min(c, (uint32_t)(kHhBins - 1));
+    return b > thr ? 2 : (b == thr ? 1 : 0);
+}
+
+// per tile of rows: how many rows above the threshold, how many equal to it
+__global__ void __launch_bounds__(NT)
+pk_hh_tilecount_kernel(const uint32_t* __restrict__ fcounter, int64_t rows, uint32_t thr,
+                       int32_t* __restrict__ tile_gt, int32_t* __restrict__ tile_eq)
+{
+    const int64_t r0 = (int64_t)blockIdx.x * kHhTile;
+    int gt = 0, eq = 0;
+    for (int i = threadIdx.x; i < kHhTile; i += NT) {
+        const int64_t r = r0 + i;
+        if (r < rows) {
+            const int cl = hh_class(fcounter[r], thr);
+            gt += cl == 2; eq += cl == 1;
+        }
+    }
+    int tg, te;
+    (void)block_excl_scan<NT>(gt, &tg);
+    (void)block_excl_scan<NT>(eq, &te);
+    if (threadIdx.x == 0) { tile_gt[blockIdx.x] = tg; tile_eq[blockIdx.x] = te; }
+}
+
+// exclusive scans of the two per-tile arrays, in place (one block)
+__global__ void __launch_bounds__(1024)
+pk_hh_scan_kernel(int32_t* tile_gt, int32_t* tile_eq, int n_tiles)
+{
+    int cg = 0, ce = 0;
+    for (int base = 0; base < n_tiles; base += 1024) {
+        const int i = base + threadIdx.x;
+        const int g = i < n_tiles ? tile_gt[i] : 0, e = i < n_tiles ? tile_eq[i] : 0;
+        int tg, te;
+        const int xg = block_excl_scan<1024>(g, &tg);
+        const int xe = block_excl_scan<1024>(e, &te);
+        if (i < n_tiles) { tile_gt[i] = cg + xg; tile_eq[i] = ce + xe; }
+        cg += tg; ce += te;
+    }
+}
+
+// the new Hot-storage: every row above the threshold and the first need_eq rows equal to it,
+// in ascending row order; slot = rank of the row among the selected ones
+__global__ void __launch_bounds__(NT)
+pk_hh_select_kernel(const uint32_t* __restrict__ fcounter, int64_t rows, uint32_t thr, int need_eq,
+                    const int32_t* __restrict__ gt_before, const int32_t* __restrict__ eq_before,
+                    uint32_t* __restrict__ hot_row, int64_t cap)
+{
+    constexpr int PER = kHhTile / NT;                 // consecutive rows per thread
+    const int64_t r0 = (int64_t)blockIdx.x * kHhTile + (int64_t)threadIdx.x * PER;
+    int cl[PER];
+    int gt = 0, eq = 0;
+#pragma unroll
+    for (int j = 0; j < PER; ++j) {
+        cl[j] = r0 + j < rows ? hh_class(fcounter[r0 + j], thr) : 0;
+        gt += cl[j] == 2; eq += cl[j] == 1;
+    }
+    int tg, te;
+    int xg = block_excl_scan<NT>(gt, &tg);
+    int xe = block_excl_scan<NT>(eq, &te);
+    const int gb = gt_before[blockIdx.x], eb = eq_before[blockIdx.x];
+#pragma unroll
+    for (int j = 0; j < PER; ++j) {
+        const int eq_rank = eb + xe;                  // equal-count rows before this one
+        const bool take = cl[j] == 2 || (cl[j] == 1 && eq_rank < need_eq);
+        if (take) {
+            const int64_t pos = (int64_t)gb + xg + min(eq_rank, need_eq);
+            if (pos < cap) hot_row[pos] = (uint32_t)(r0 + j);
+        }
+        xg += cl[j] == 2; xe += cl[j] == 1;
     }
 }
 
@@ -1314,6 +1501,7 @@ struct DeviceState {
     hipEvent_t ev_join[kSide] = {};
     bool overlap = true;
     bool fuse = true;
+    std::vector<int64_t> hh_n_hot;        // HybridHash: rows in each pack's Hot-storage
     // profiling
     bool prof_on = false;
     std::vector<hipEvent_t> events;
@@ -1497,13 +1685,13 @@ bool cols_aligned(const pk_plan* plan, int p)
 struct PoolArgs {
     const void* W; const uint32_t* keys; const int32_t* po; const PackState* st; const FieldMeta* fmeta;
     const int32_t* slot_field; int B; int D; int64_t n_bags; float* out; int64_t out_stride; unsigned grid_cap;
-    bool aligned;
+    bool aligned; HotView hv;
 };
 struct AdaArgs {
     void* W; float* A; const PackState* st; int p; const uint32_t* unique; const int32_t* seg;
     double* ghot; int dmax; const int4* tile_hdr; int tp; int n_host; const uint32_t* seg_ent; int ent_mult;
     int has_mean; const float* grad; int64_t gstride; int64_t out_dim; uint32_t addr_max; int D;
-    float lr; float eps; int64_t nnz_bound; bool aligned;
+    float lr; float eps; int64_t nnz_bound; bool aligned; HotView hv;
 };
 
 template <typename WT, int VEC, int LPR, int NCH>
@@ -1511,9 +1699,14 @@ pk_status launch_pool(DeviceState* ds, hipStream_t stream, const PoolArgs& a)
 {
     constexpr int GPB = NT / LPR;
     const unsigned grid = blocks_for(a.n_bags, GPB, a.grid_cap);
-    PK_LAUNCH("pk_pool", (pk_pool_kernel<WT, VEC, LPR, NCH>), dim3(grid), dim3(NT), 0,
-              static_cast<const WT*>(a.W), a.keys, a.po, a.st, a.fmeta, a.slot_field, a.B, a.D, a.n_bags, a.out,
-              a.out_stride);
+    if (a.hv.slot_of)
+        PK_LAUNCH("pk_pool", (pk_pool_kernel<WT, VEC, LPR, NCH, true>), dim3(grid), dim3(NT), 0,
+                  static_cast<const WT*>(a.W), a.keys, a.po, a.st, a.fmeta, a.slot_field, a.B, a.D, a.n_bags, a.out,
+                  a.out_stride, a.hv);
+    else
+        PK_LAUNCH("pk_pool", (pk_pool_kernel<WT, VEC, LPR, NCH, false>), dim3(grid), dim3(NT), 0,
+                  static_cast<const WT*>(a.W), a.keys, a.po, a.st, a.fmeta, a.slot_field, a.B, a.D, a.n_bags, a.out,
+                  a.out_stride, a.hv);
     return PK_OK;
 }
 
@@ -1524,11 +1717,11 @@ pk_status launch_adagrad(DeviceState* ds, hipStream_t stream, const AdaArgs& a)
     if (a.has_mean)
         PK_LAUNCH("pk_adagrad", (pk_adagrad_kernel<WT, VEC, LPR, NCH, true>), dim3(grid), dim3(NT), 0,
                   static_cast<WT*>(a.W), a.A, a.st, a.p, a.unique, a.seg, a.ghot, a.dmax, a.tile_hdr,
-                  a.tp, a.n_host, a.seg_ent, a.ent_mult, a.grad, a.gstride, a.out_dim, a.addr_max, a.D, a.lr, a.eps);
+                  a.tp, a.n_host, a.seg_ent, a.ent_mult, a.grad, a.gstride, a.out_dim, a.addr_max, a.D, a.lr, a.eps, a.hv);
     else
         PK_LAUNCH("pk_adagrad", (pk_adagrad_kernel<WT, VEC, LPR, NCH, false>), dim3(grid), dim3(NT), 0,
                   static_cast<WT*>(a.W), a.A, a.st, a.p, a.unique, a.seg, a.ghot, a.dmax, a.tile_hdr,
-                  a.tp, a.n_host, a.seg_ent, a.ent_mult, a.grad, a.gstride, a.out_dim, a.addr_max, a.D, a.lr, a.eps);
+                  a.tp, a.n_host, a.seg_ent, a.ent_mult, a.grad, a.gstride, a.out_dim, a.addr_max, a.D, a.lr, a.eps, a.hv);
     return PK_OK;
 }
 
@@ -1574,6 +1767,16 @@ int pool_variant(int dtype, int D, bool aligned, int* lpr_out)
     return (dtype == PK_F32 ? 0 : 12) + shape;
 }
 
+template <typename WT>
+pk_status hh_move(DeviceState* ds, hipStream_t stream, const pk_hh_pack& h, int64_t n_hot, int D, int to_cold)
+{
+    if (n_hot <= 0) return PK_OK;
+    PK_LAUNCH("pk_hh_move", pk_hh_move_kernel<WT>, dim3(blocks_for(n_hot, NT / 64, 4096)), dim3(NT), 0,
+              static_cast<WT*>(h.W_cold), h.A_cold, static_cast<WT*>(h.W_hot), h.A_hot, h.hot_row, h.slot_of, n_hot, D,
+              to_cold);
+    return PK_OK;
+}
+
 }  // namespace
 
 namespace pk {
@@ -1595,9 +1798,10 @@ void destroy_device_state(pk_plan* plan)
 
 extern "C" {
 
-pk_status pk_forward(const pk_plan* plan, void* const* W, const int64_t* ids, const int32_t* offsets, int32_t B,
-                     int64_t nnz, float* out, int64_t out_row_stride, void* workspace, size_t ws_bytes,
-                     void* hip_stream)
+// hot: per pack, where the rows of a Hot-storage live (HybridHash), or NULL
+static pk_status forward_impl(const pk_plan* plan, void* const* W, const HotView* hot, const int64_t* ids,
+                              const int32_t* offsets, int32_t B, int64_t nnz, float* out, int64_t out_row_stride,
+                              void* workspace, size_t ws_bytes, void* hip_stream)
 {
     pk_status rc = check_common(plan, B, nnz, workspace, ws_bytes, "pk_forward");
     if (rc != PK_OK) return rc;
@@ -1659,7 +1863,7 @@ pk_status pk_forward(const pk_plan* plan, void* const* W, const int64_t* ids, co
     const bool overlap = ds->overlap && !ds->prof_on &&
                          (G >= 2 || (G == 0 && (P > 1 || nnz >= (1 << 20)) && nnz >= (1 << 18)));
     const int n_side = overlap ? std::min<int>(P, G >= 2 ? G : 4) : 0;
-    const bool fuse_pool = !n_side && P <= kFusedPacks && T > 0 && nnz < (1 << 20) && ds->fuse;
+    const bool fuse_pool = !hot && !n_side && P <= kFusedPacks && T > 0 && nnz < (1 << 20) && ds->fuse;
     auto pool_aligned = [&](int p) {
         return cols_aligned(plan, p) && aligned16(out) && out_row_stride % 4 == 0 && aligned16(W[p]);
     };
@@ -1668,7 +1872,8 @@ pk_status pk_forward(const pk_plan* plan, void* const* W, const int64_t* ids, co
         const Pack& k = plan->packs[p];
         if (k.fields.empty()) continue;
         PoolArgs a{W[p], keys, packed_offsets + po_off(plan, p, B), st + p, ds->fmeta, ds->slot_field + k.first_slot,
-                   B, k.dim, (int64_t)k.fields.size() * B, out, out_row_stride, 256 * 32, pool_aligned(p)};
+                   B, k.dim, (int64_t)k.fields.size() * B, out, out_row_stride, 256 * 32, pool_aligned(p),
+                   hot ? hot[p] : HotView{nullptr, nullptr, nullptr}};
         hipStream_t ps = n_side ? ds->side[p % n_side] : stream;
         rc = k.dtype == PK_F32 ? dispatch_pool<float, 4>(ds, ps, k.dim, a)
                                : dispatch_pool<uint16_t, 8>(ds, ps, k.dim, a);
@@ -1724,9 +1929,16 @@ pk_status pk_forward(const pk_plan* plan, void* const* W, const int64_t* ids, co
     return PK_OK;
 }
 
-pk_status pk_backward_update(const pk_plan* plan, void* const* W, float* const* A, const float* grad_out,
-                             int64_t grad_row_stride, int32_t B, int64_t nnz, float lr, float eps, void* workspace,
-                             size_t ws_bytes, void* hip_stream)
+pk_status pk_forward(const pk_plan* plan, void* const* W, const int64_t* ids, const int32_t* offsets, int32_t B,
+                     int64_t nnz, float* out, int64_t out_row_stride, void* workspace, size_t ws_bytes,
+                     void* hip_stream)
+{
+    return forward_impl(plan, W, nullptr, ids, offsets, B, nnz, out, out_row_stride, workspace, ws_bytes, hip_stream);
+}
+
+static pk_status backward_impl(const pk_plan* plan, void* const* W, float* const* A, const HotView* hot,
+                               const float* grad_out, int64_t grad_row_stride, int32_t B, int64_t nnz, float lr,
+                               float eps, void* workspace, size_t ws_bytes, void* hip_stream)
 {
     pk_status rc = check_common(plan, B, nnz, workspace, ws_bytes, "pk_backward_update");
     if (rc != PK_OK) return rc;
@@ -1758,7 +1970,8 @@ pk_status pk_backward_update(const pk_plan* plan, void* const* W, float* const* 
                   plan->out_dim, (uint32_t)((int64_t)(B - 1) * grad_row_stride + plan->out_dim - k.dim), k.dim, lr,
                   eps, nnz,
                   cols_aligned(plan, p) && aligned16(grad_out) && grad_row_stride % 4 == 0 && aligned16(W[p]) &&
-                      aligned16(A[p])};
+                      aligned16(A[p]),
+                  hot ? hot[p] : HotView{nullptr, nullptr, nullptr}};
         rc = k.dtype == PK_F32 ? dispatch_adagrad<float, 4>(ds, ps, k.dim, a)
                                : dispatch_adagrad<uint16_t, 8>(ds, ps, k.dim, a);
         if (rc != PK_OK) return rc;
@@ -1769,11 +1982,201 @@ pk_status pk_backward_update(const pk_plan* plan, void* const* W, float* const* 
     for (int p0 = 0; p0 < P; p0 += 16) {
         HotPacks hp{};
         const int np = std::min(16, P - p0);
-        for (int i = 0; i < np; ++i) { hp.W[i] = W[p0 + i]; hp.A[i] = A[p0 + i]; }
+        for (int i = 0; i < np; ++i) {
+            hp.W[i] = W[p0 + i]; hp.A[i] = A[p0 + i];
+            hp.hv[i] = hot ? hot[p0 + i] : HotView{nullptr, nullptr, nullptr};
+        }
         PK_LAUNCH("pk_adagrad_hot", pk_adagrad_hot_kernel, dim3(hgrid, np), dim3(NT), 0, hp, p0, ds->pmeta, st,
                   ws.at<uint32_t>(L.unique), ws.at<int32_t>(L.seg), ws.at<double>(L.ghot), L.dmax,
                   ws.at<int4>(L.tile_hdr), L.pos_tile, lr, eps);
     }
+    return PK_OK;
+}
+
+pk_status pk_backward_update(const pk_plan* plan, void* const* W, float* const* A, const float* grad_out,
+                             int64_t grad_row_stride, int32_t B, int64_t nnz, float lr, float eps, void* workspace,
+                             size_t ws_bytes, void* hip_stream)
+{
+    return backward_impl(plan, W, A, nullptr, grad_out, grad_row_stride, B, nnz, lr, eps, workspace, ws_bytes,
+                         hip_stream);
+}
+
+// ---- HybridHash ------------------------------------------------------------------
+static pk_status hh_check(const pk_plan* plan, const pk_hh_pack* packs, const char* who)
+{
+    if (!plan || !packs) return fail(PK_EINVAL, std::string(who) + ": NULL argument");
+    for (size_t p = 0; p < plan->packs.size(); ++p) {
+        const pk_hh_pack& h = packs[p];
+        if (!h.W_cold || !h.A_cold || !h.slot_of || !h.fcounter || h.hot_rows < 0 ||
+            (h.hot_rows > 0 && (!h.W_hot || !h.A_hot || !h.hot_row)))
+            return fail(PK_EINVAL, std::string(who) + ": pack " + std::to_string(p) + " has a NULL buffer or a negative hot_rows");
+        if (h.hot_rows >= ((int64_t)1 << 31)) return fail(PK_EOVERFLOW, std::string(who) + ": hot_rows must be below 2^31");
+    }
+    return PK_OK;
+}
+
+static void hh_views(const pk_plan* plan, const pk_hh_pack* packs, std::vector<void*>* W, std::vector<float*>* A,
+                     std::vector<HotView>* hv)
+{
+    for (size_t p = 0; p < plan->packs.size(); ++p) {
+        W->push_back(packs[p].W_cold);
+        A->push_back(packs[p].A_cold);
+        hv->push_back(HotView{packs[p].slot_of, packs[p].W_hot, packs[p].A_hot});
+    }
+}
+
+static size_t hh_tiles(int64_t rows) { return (size_t)((rows + kHhTile - 1) / kHhTile); }
+
+size_t pk_hh_scratch_bytes(const pk_plan* plan)
+{
+    if (!plan) { set_error("pk_hh_scratch_bytes: plan is NULL"); return 0; }
+    size_t tiles = 0;
+    for (const Pack& k : plan->packs) tiles = std::max(tiles, hh_tiles(k.rows));
+    return (size_t)kHhBins * 4 + 256 + plan->packs.size() * 16 + 256 + 2 * (tiles * 4 + 256);
+}
+
+pk_status pk_hh_init(pk_plan* plan, const pk_hh_pack* packs, void* hip_stream)
+{
+    pk_status rc = hh_check(plan, packs, "pk_hh_init");
+    if (rc != PK_OK) return rc;
+    DeviceState* ds = nullptr;
+    rc = ensure_device_state(plan, &ds);
+    if (rc != PK_OK) return rc;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    ds->hh_n_hot.assign(plan->packs.size(), 0);
+    for (size_t p = 0; p < plan->packs.size(); ++p) {
+        const size_t rows = (size_t)plan->packs[p].rows;
+        hipError_t e = hipMemsetAsync(packs[p].slot_of, 0xFF, rows * 4, stream);
+        if (e == hipSuccess) e = hipMemsetAsync(packs[p].fcounter, 0, rows * 4, stream);
+        if (e != hipSuccess) return fail(PK_EHIP, hip_msg("pk_hh_init", e));
+    }
+    return PK_OK;
+}
+
+pk_status pk_hh_forward(const pk_plan* plan, const pk_hh_pack* packs, const int64_t* ids, const int32_t* offsets,
+                        int32_t B, int64_t nnz, float* out, int64_t out_row_stride, void* workspace,
+                        size_t ws_bytes, void* hip_stream)
+{
+    pk_status rc = hh_check(plan, packs, "pk_hh_forward");
+    if (rc != PK_OK) return rc;
+    std::vector<void*> W; std::vector<float*> A; std::vector<HotView> hv;
+    hh_views(plan, packs, &W, &A, &hv);
+    return forward_impl(plan, W.data(), hv.data(), ids, offsets, B, nnz, out, out_row_stride, workspace, ws_bytes,
+                        hip_stream);
+}
+
+pk_status pk_hh_backward_update(const pk_plan* plan, const pk_hh_pack* packs, const float* grad_out,
+                                int64_t grad_row_stride, int32_t B, int64_t nnz, float lr, float eps,
+                                void* workspace, size_t ws_bytes, void* hip_stream)
+{
+    pk_status rc = hh_check(plan, packs, "pk_hh_backward_update");
+    if (rc != PK_OK) return rc;
+    std::vector<void*> W; std::vector<float*> A; std::vector<HotView> hv;
+    hh_views(plan, packs, &W, &A, &hv);
+    return backward_impl(plan, W.data(), A.data(), hv.data(), grad_out, grad_row_stride, B, nnz, lr, eps, workspace,
+                         ws_bytes, hip_stream);
+}
+
+pk_status pk_hh_end_iteration(pk_plan* plan, const pk_hh_pack* packs, int64_t itr, int32_t warmup_iters,
+                              int32_t flush_iters, int32_t B, int64_t nnz, const void* workspace, size_t ws_bytes,
+                              void* scratch, size_t scratch_bytes, void* hip_stream, int64_t* queried, int64_t* hits,
+                              int32_t* flushed)
+{
+    pk_status rc = hh_check(plan, packs, "pk_hh_end_iteration");
+    if (rc != PK_OK) return rc;
+    rc = check_common(plan, B, nnz, workspace, ws_bytes, "pk_hh_end_iteration");
+    if (rc != PK_OK) return rc;
+    if (itr < 0 || warmup_iters < 0 || flush_iters <= 0) return fail(PK_EINVAL, "pk_hh_end_iteration: bad iteration arguments");
+    if (!scratch || reinterpret_cast<uintptr_t>(scratch) % kAlign || scratch_bytes < pk_hh_scratch_bytes(plan))
+        return fail(PK_EWORKSPACE, "pk_hh_end_iteration: scratch is NULL, misaligned or smaller than pk_hh_scratch_bytes");
+    DeviceState* ds = nullptr;
+    rc = ensure_device_state(plan, &ds);
+    if (rc != PK_OK) return rc;
+    const int P = (int)plan->packs.size();
+    if ((int)ds->hh_n_hot.size() != P) return fail(PK_EINVAL, "pk_hh_end_iteration: pk_hh_init has not run on this plan");
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    const Layout L = make_layout(plan, B, nnz);
+    const char* wsb = static_cast<const char*>(workspace);
+    const PackState* st = reinterpret_cast<const PackState*>(wsb + L.state);
+    const uint32_t* unique = reinterpret_cast<const uint32_t*>(wsb + L.unique);
+    char* sc = static_cast<char*>(scratch);
+    uint32_t* hist = reinterpret_cast<uint32_t*>(sc);
+    unsigned long long* counters = reinterpret_cast<unsigned long long*>(sc + (size_t)kHhBins * 4 + 256);
+    size_t tiles_max = 0;
+    for (const Pack& k : plan->packs) tiles_max = std::max(tiles_max, hh_tiles(k.rows));
+    int32_t* tile_gt = reinterpret_cast<int32_t*>(sc + (size_t)kHhBins * 4 + 256 + (size_t)P * 16 + 256);
+    int32_t* tile_eq = tile_gt + tiles_max + 64;
+
+    // FCounter (both branches of Alg. 1 count the queried IDs) and the hit statistics
+    hipError_t e = hipMemsetAsync(counters, 0, (size_t)P * 16, stream);
+    if (e != hipSuccess) return fail(PK_EHIP, hip_msg("pk_hh_end_iteration", e));
+    for (int p = 0; p < P; ++p) {
+        if (plan->packs[p].fields.empty()) continue;
+        PK_LAUNCH("pk_hh_count", pk_hh_count_kernel, dim3(blocks_for(nnz, NT * 4, 1024)), dim3(NT), 0, st, p, unique,
+                  packs[p].slot_of, packs[p].fcounter, counters);
+    }
+    const bool flush = itr >= warmup_iters && itr % flush_iters == 0;
+    if (flushed) *flushed = flush ? 1 : 0;
+    if (queried || hits) {
+        std::vector<unsigned long long> c((size_t)P * 2);
+        e = hipStreamSynchronize(stream);
+        if (e == hipSuccess) e = hipMemcpy(c.data(), counters, c.size() * 8, hipMemcpyDeviceToHost);
+        if (e != hipSuccess) return fail(PK_EHIP, hip_msg("pk_hh_end_iteration", e));
+        for (int p = 0; p < P; ++p) {
+            if (queried) queried[p] = (int64_t)c[2 * p];
+            if (hits) hits[p] = (int64_t)c[2 * p + 1];
+        }
+    }
+    if (!flush) return PK_OK;
+
+    // reload: write the Hot-storage back, pick the top-k rows of FCounter, load them
+    std::vector<uint32_t> h_hist(kHhBins);
+    for (int p = 0; p < P; ++p) {
+        const Pack& k = plan->packs[p];
+        const pk_hh_pack& h = packs[p];
+        if (k.fields.empty() || h.hot_rows == 0) continue;
+        rc = k.dtype == PK_F32 ? hh_move<float>(ds, stream, h, ds->hh_n_hot[p], k.dim, 1)
+                               : hh_move<uint16_t>(ds, stream, h, ds->hh_n_hot[p], k.dim, 1);
+        if (rc != PK_OK) return rc;
+        ds->hh_n_hot[p] = 0;
+        e = hipMemsetAsync(hist, 0, (size_t)kHhBins * 4, stream);
+        if (e != hipSuccess) return fail(PK_EHIP, hip_msg("pk_hh_end_iteration", e));
+        PK_LAUNCH("pk_hh_hist", pk_hh_hist_kernel, dim3(blocks_for(k.rows, NT * 8, 4096)), dim3(NT), 0, h.fcounter,
+                  k.rows, hist);
+        e = hipStreamSynchronize(stream);
+        if (e == hipSuccess) e = hipMemcpy(h_hist.data(), hist, (size_t)kHhBins * 4, hipMemcpyDeviceToHost);
+        if (e != hipSuccess) return fail(PK_EHIP, hip_msg("pk_hh_end_iteration", e));
+        // threshold: the smallest count that still enters; rows above it all enter
+        int64_t above = 0;
+        uint32_t thr = 0;
+        int64_t need_eq = 0;
+        for (int b = kHhBins - 1; b >= 1; --b) {
+            if (above + h_hist[b] >= h.hot_rows) { thr = (uint32_t)b; need_eq = h.hot_rows - above; break; }
+            above += h_hist[b];
+        }
+        if (thr == 0) { thr = 1; need_eq = h_hist[1]; above -= h_hist[1]; }     // room for every queried row
+        const int64_t n_new = above + std::min<int64_t>(need_eq, h_hist[thr]);
+        if (n_new == 0) continue;
+        const unsigned nt = (unsigned)hh_tiles(k.rows);
+        PK_LAUNCH("pk_hh_tilecount", pk_hh_tilecount_kernel, dim3(nt), dim3(NT), 0, h.fcounter, k.rows, thr, tile_gt,
+                  tile_eq);
+        PK_LAUNCH("pk_hh_scan", pk_hh_scan_kernel, dim3(1), dim3(1024), 0, tile_gt, tile_eq, (int)nt);
+        PK_LAUNCH("pk_hh_select", pk_hh_select_kernel, dim3(nt), dim3(NT), 0, h.fcounter, k.rows, thr, (int)need_eq,
+                  tile_gt, tile_eq, h.hot_row, h.hot_rows);
+        rc = k.dtype == PK_F32 ? hh_move<float>(ds, stream, h, n_new, k.dim, 0)
+                               : hh_move<uint16_t>(ds, stream, h, n_new, k.dim, 0);
+        if (rc != PK_OK) return rc;
+        ds->hh_n_hot[p] = n_new;
+    }
+    return PK_OK;
+}
+
+pk_status pk_hh_hot_count(const pk_plan* plan, int32_t p, int64_t* n_hot)
+{
+    if (!plan || !n_hot) return fail(PK_EINVAL, "pk_hh_hot_count: NULL argument");
+    if (p < 0 || p >= (int32_t)plan->packs.size()) return fail(PK_EINVAL, "pk_hh_hot_count: pack out of range");
+    const DeviceState* ds = static_cast<const DeviceState*>(plan->device_state);
+    *n_hot = (ds && (size_t)p < ds->hh_n_hot.size()) ? ds->hh_n_hot[p] : 0;
     return PK_OK;
 }
 

@@ -99,3 +99,80 @@ class PackedEmbedding:
 
     def error_word(self) -> int:
         return pk.pk_ctx_error(self.plan, self.ws)
+
+
+class HybridEmbedding(PackedEmbedding):
+    """The layer with a Hot-storage in front of its tables (HybridHash): the tables and accumulators are the
+    Cold-storage, in pinned host memory when `cold_on_host`, and the `hot_rows[p]` most queried rows of pack p
+    live in device memory.  Buffer management only."""
+
+    def __init__(self, tables, fields, hot_rows: Sequence[int], warmup_iters: int, flush_iters: int,
+                 cold_on_host: bool = True, device: str = "cuda:0", **plan_opts):
+        self.tables, self.fields = list(tables), list(fields)
+        self.device = torch.device(device)
+        self.plan = pk.pk_plan_create(self.tables, self.fields, **plan_opts)
+        self.n_packs = pk.pk_plan_num_packs(self.plan)
+        self.packs = [pk.pk_plan_pack_info(self.plan, p) for p in range(self.n_packs)]
+        self.pack_fields = [pk.pk_plan_pack_fields(self.plan, p) for p in range(self.n_packs)]
+        self.table_slot = [pk.pk_plan_table_slot(self.plan, t) for t in range(len(self.tables))]
+        self.field_col = [pk.pk_plan_field_col(self.plan, f) for f in range(len(self.fields))]
+        self.out_dim = pk.pk_plan_out_dim(self.plan)
+        self.warmup_iters, self.flush_iters, self.itr = int(warmup_iters), int(flush_iters), 0
+        self.W, self.A, self.hh = [], [], []
+        for p, info in enumerate(self.packs):
+            dt = torch.float32 if info["dtype"] == pk.PK_F32 else torch.bfloat16
+            R, D, k = info["total_rows"], info["dim"], int(hot_rows[p])
+            if cold_on_host:
+                Wc = torch.empty((R, D), dtype=dt, pin_memory=True)
+                Ac = torch.zeros((R, D), dtype=torch.float32, pin_memory=True)
+            else:
+                Wc = torch.empty((R, D), dtype=dt, device=self.device)
+                Ac = torch.zeros((R, D), dtype=torch.float32, device=self.device)
+            self.W.append(Wc)
+            self.A.append(Ac)
+            self.hh.append(dict(
+                W_cold=Wc, A_cold=Ac, hot_rows=k,
+                W_hot=torch.empty((max(k, 1), D), dtype=dt, device=self.device),
+                A_hot=torch.empty((max(k, 1), D), dtype=torch.float32, device=self.device),
+                slot_of=torch.empty(R, dtype=torch.int32, device=self.device),
+                hot_row=torch.empty(max(k, 1), dtype=torch.int32, device=self.device),
+                fcounter=torch.empty(R, dtype=torch.int32, device=self.device)))
+        self.scratch_bytes = pk.pk_hh_scratch_bytes(self.plan)
+        self.scratch = torch.empty(self.scratch_bytes + 256, dtype=torch.uint8, device=self.device)
+        self.ws, self.ws_bytes, self._shape = None, 0, None
+        pk.pk_hh_init(self.plan, self.hh, torch.cuda.current_stream(self.device).cuda_stream)
+
+    def load_table(self, t: int, values: np.ndarray) -> None:
+        values = np.ascontiguousarray(values)
+        if self.tables[t][2] == pk.PK_BF16:
+            v = torch.from_numpy(values.view(np.int16)).view(torch.bfloat16)
+        else:
+            v = torch.from_numpy(values)
+        self.table_view(t).copy_(v)
+
+    def forward(self, ids, offsets, B: int, out=None):
+        nnz = int(ids.shape[0])
+        self._ensure_ws(B, nnz)
+        if out is None:
+            out = torch.empty((B, self.out_dim), dtype=torch.float32, device=self.device)
+        stream = torch.cuda.current_stream(self.device).cuda_stream
+        pk.pk_hh_forward(self.plan, self.hh, ids, offsets, B, nnz, out, out.stride(0), self.ws, self.ws_bytes, stream)
+        return out
+
+    def backward_update(self, grad_out, lr: float, eps: float) -> None:
+        B, nnz = self._shape
+        stream = torch.cuda.current_stream(self.device).cuda_stream
+        pk.pk_hh_backward_update(self.plan, self.hh, grad_out, grad_out.stride(0), B, nnz, lr, eps, self.ws,
+                                 self.ws_bytes, stream)
+
+    def end_iteration(self, want_counts: bool = True):
+        """Alg. 1's bookkeeping for the batch just processed; returns (queried, hits, flushed)."""
+        B, nnz = self._shape
+        stream = torch.cuda.current_stream(self.device).cuda_stream
+        r = pk.pk_hh_end_iteration(self.plan, self.hh, self.itr, self.warmup_iters, self.flush_iters, B, nnz, self.ws,
+                                   self.ws_bytes, self.scratch, self.scratch_bytes, stream, want_counts)
+        self.itr += 1
+        return r
+
+    def hot_count(self, p: int) -> int:
+        return pk.pk_hh_hot_count(self.plan, p)
