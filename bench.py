@@ -82,6 +82,13 @@ def main():
                          "per-field occurrence counts of the first batch serve as the warm-up statistics")
     ap.add_argument("--groups", type=int, default=0,
                     help="K-Interleaving groups of packed operations (0 = chosen by batch size, 1 = none)")
+    ap.add_argument("--hot-fraction", type=float, default=None,
+                    help="HybridHash: keep this fraction of every pack's rows in a device Hot-storage in front of "
+                         "the tables (Cold-storage); reports the hit ratio of the batches' distinct rows")
+    ap.add_argument("--cold", default="host", choices=["host", "device"],
+                    help="HybridHash: where the Cold-storage lives (pinned host memory or device memory)")
+    ap.add_argument("--hh-warmup", type=int, default=20)
+    ap.add_argument("--hh-flush", type=int, default=10)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (a known size for scaling rocprofv3's byte counters)")
@@ -96,7 +103,7 @@ def main():
 
     import synth
     from paper_2204_04903_amd import binding as pk
-    from paper_2204_04903_amd.layer import PackedEmbedding
+    from paper_2204_04903_amd.layer import HybridEmbedding, PackedEmbedding
 
     idx = int(args.workload[3])
     wl = synth.config(idx)
@@ -116,7 +123,16 @@ def main():
                                        for f in range(wl.n_fields)])
     if args.groups:
         plan_opts["interleave_groups"] = args.groups
-    layer = PackedEmbedding(tables, fields, **plan_opts)
+    hybrid = args.hot_fraction is not None
+    if hybrid:
+        probe = pk.pk_plan_create(tables, fields, **plan_opts)
+        hot_rows = [int(pk.pk_plan_pack_info(probe, p)["total_rows"] * args.hot_fraction)
+                    for p in range(pk.pk_plan_num_packs(probe))]
+        pk.pk_plan_destroy(probe)
+        layer = HybridEmbedding(tables, fields, hot_rows, args.hh_warmup, args.hh_flush,
+                                cold_on_host=args.cold == "host", **plan_opts)
+    else:
+        layer = PackedEmbedding(tables, fields, **plan_opts)
     stream = torch.cuda.current_stream().cuda_stream
     for t, ts in enumerate(wl.tables):
         synth.fill_device(layer.table_view(t).data_ptr(), ts.rows, ts.dim, ts.dtype, wl.seed, t, stream)
@@ -139,7 +155,11 @@ def main():
         ids, offsets, grad = dev[i % ring]
         layer.forward(ids, offsets, wl.batch, out=out)
         layer.backward_update(grad, wl.lr, wl.eps)
+        if hybrid:
+            layer.end_iteration(want_counts=False)
 
+    if hybrid:                       # Alg. 1's warm-up iterations and the first reload come before the clock
+        args.warmup = max(args.warmup, args.hh_warmup + args.hh_flush + 1)
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
@@ -151,6 +171,19 @@ def main():
     lookups = sum(batches[(args.warmup + i) % ring].nnz for i in range(args.steps))
     ms_per_step = elapsed * 1e3 / args.steps
     value = lookups / elapsed
+
+    hybrid_info = None
+    if hybrid:                       # hit ratio of the distinct rows of a batch, over one pass of the ring
+        q_tot = h_tot = 0
+        for i in range(ring):
+            ids, offsets, grad = dev[i % ring]
+            layer.forward(ids, offsets, wl.batch, out=out)
+            layer.backward_update(grad, wl.lr, wl.eps)
+            q, h, _ = layer.end_iteration(want_counts=True)
+            q_tot += sum(q); h_tot += sum(h)
+        hybrid_info = {"hot_fraction": args.hot_fraction, "cold_storage": args.cold, "warmup_iters": args.hh_warmup,
+                       "flush_iters": args.hh_flush, "hit_ratio": h_tot / max(1, q_tot),
+                       "hot_rows": [layer.hot_count(p) for p in range(layer.n_packs)]}
 
     # ---- per-kernel durations (HIP events on the launch stream) and sizes --------------------
     prof_steps = min(args.steps, 4 * ring)
@@ -235,13 +268,14 @@ def main():
         "vs_baseline": None,
         "dtype": "f32" if wl.tables[0].dtype == 0 else "bf16 tables, f32 arithmetic",
         "data": "synthetic",
-        "config": {"workload": f"{args.workload}: {wl.description}", "batch": wl.batch, "fields": wl.n_fields,
+        "config": {"workload": f"{args.workload}: {wl.description}" + (" [HybridHash]" if hybrid else ""), "batch": wl.batch, "fields": wl.n_fields,
                    "packs": layer.n_packs, "max_shards": args.max_shards, "interleave_groups": args.groups, "ring_batches": ring, "lookups_per_step": lookups / args.steps,
                    "distinct_keys_per_step": sum(i["U"] for i in sizes[0])},
         "hbm_model": {"bytes_per_step": model_bytes, "GBps": model_bytes / (ms_per_step * 1e-3) / 1e9,
                       "frac_of_peak": model_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS},
         "roofline": roofline,
         "cpu_baseline": cpu,
+        "hybrid_hash": hybrid_info,
         "kernels": {k: {kk: round(vv, 6) for kk, vv in v.items()} for k, v in kern.items()},
         "input_generation_s": round(gen_s, 2),
     }

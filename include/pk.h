@@ -154,9 +154,10 @@ pk_status pk_backward_update(const pk_plan* plan, void* const* W, float* const* 
  *   itr <  warmup_iters: every row is served by the Cold-storage, FCounter counts;
  *   itr >= warmup_iters: a row found in the Hot-storage is read and updated there,
  *     the others in the Cold-storage; FCounter counts; when itr is a multiple of
- *     flush_iters the Hot-storage is written back and reloaded with the top-k
- *     rows of FCounter (larger count first, equal counts by smaller row; rows
- *     never queried do not enter; k = hot_rows).
+ *     flush_iters the Hot-storage is refreshed to hold the top-k rows of
+ *     FCounter (larger count first, equal counts by smaller row; rows never
+ *     queried do not enter; k = hot_rows): rows that leave are written back to
+ *     the Cold-storage, rows that enter are loaded, rows that stay keep their slot.
  * The Hot-storage never changes a value the layer computes.  All buffers belong
  * to the caller; pk_hh_init must run once before the first iteration. */
 typedef struct {
@@ -165,13 +166,14 @@ typedef struct {
     void*     W_hot;     /* device, [hot_rows, dim], the pack's dtype                     */
     float*    A_hot;     /* device, fp32 [hot_rows, dim]                                  */
     int32_t*  slot_of;   /* device, [total_rows]: the row's slot in the Hot-storage or -1 */
-    uint32_t* hot_row;   /* device, [hot_rows]: the row each slot holds, ascending        */
+    uint32_t* hot_row;   /* device, [hot_rows]: the row each used slot holds (any order)  */
     uint32_t* fcounter;  /* device, [total_rows]                                          */
     int64_t   hot_rows;  /* k, the capacity of the Hot-storage in rows (>= 0)             */
 } pk_hh_pack;
 
-/* Device scratch needed by pk_hh_end_iteration (256-byte aligned); 0 on error. */
-size_t    pk_hh_scratch_bytes(const pk_plan* plan);
+/* Device scratch needed by pk_hh_end_iteration (256-byte aligned) for these packs
+ * (their hot_rows matter); 0 on error.  packs: host array of n_packs entries. */
+size_t    pk_hh_scratch_bytes(const pk_plan* plan, const pk_hh_pack* packs);
 /* packs: host array of n_packs entries.  Empties the Hot-storage bookkeeping
  * (slot_of = -1, FCounter = 0).  Enqueues on hip_stream. */
 pk_status pk_hh_init(pk_plan* plan, const pk_hh_pack* packs, void* hip_stream);

@@ -115,7 +115,7 @@ def lib():
         L.pk_last_error.argtypes = []
         hp = ctypes.POINTER(pk_hh_pack)
         L.pk_hh_scratch_bytes.restype = ctypes.c_size_t
-        L.pk_hh_scratch_bytes.argtypes = [vp]
+        L.pk_hh_scratch_bytes.argtypes = [vp, hp]
         L.pk_hh_init.restype = ctypes.c_int
         L.pk_hh_init.argtypes = [vp, hp, vp]
         L.pk_hh_forward.restype = ctypes.c_int
@@ -240,8 +240,8 @@ def _hh_array(packs: Sequence[dict]):
     return arr
 
 
-def pk_hh_scratch_bytes(plan: int) -> int:
-    n = int(lib().pk_hh_scratch_bytes(plan))
+def pk_hh_scratch_bytes(plan: int, packs: Sequence[dict]) -> int:
+    n = int(lib().pk_hh_scratch_bytes(plan, _hh_array(packs)))
     if n == 0:
         raise PkError(PK_EINVAL, pk_last_error())
     return n

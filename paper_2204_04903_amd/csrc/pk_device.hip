@@ -1377,30 +1377,60 @@ pk_hh_count_kernel(const PackState* __restrict__ st, int p, const uint32_t* __re
     }
 }
 
-// rows between the two storages: one wavefront per slot, lanes over the row's elements
+// Rows leaving the Hot-storage are written back to the Cold-storage (one wavefront per row,
+// lanes over its elements) ...
 template <typename WT>
 __global__ void __launch_bounds__(NT)
-pk_hh_move_kernel(WT* W_cold, float* A_cold, WT* W_hot, float* A_hot, const uint32_t* __restrict__ hot_row,
-                  int32_t* slot_of, int64_t n_hot, int D, int to_cold)
+pk_hh_evict_kernel(WT* W_cold, float* A_cold, const WT* __restrict__ W_hot, const float* __restrict__ A_hot,
+                   const uint32_t* __restrict__ hot_row, int32_t* slot_of, const int32_t* __restrict__ evict_slot,
+                   const uint32_t* __restrict__ counts, int D)
 {
-    const int lane = threadIdx.x & 63;
-    for (int64_t s = (int64_t)blockIdx.x * (NT / 64) + (threadIdx.x >> 6); s < n_hot; s += (int64_t)gridDim.x * (NT / 64)) {
-        const size_t row = hot_row[s];
-        for (int d = lane; d < D; d += 64) {
-            if (to_cold) { W_cold[row * D + d] = W_hot[s * D + d]; A_cold[row * D + d] = A_hot[s * D + d]; }
-            else { W_hot[s * D + d] = W_cold[row * D + d]; A_hot[s * D + d] = A_cold[row * D + d]; }
-        }
-        if (lane == 0) slot_of[row] = to_cold ? -1 : (int32_t)s;
+    const int n = (int)counts[0], lane = threadIdx.x & 63;
+    for (int i = blockIdx.x * (NT / 64) + (threadIdx.x >> 6); i < n; i += gridDim.x * (NT / 64)) {
+        const size_t s = (size_t)evict_slot[i], row = hot_row[s];
+        for (int d = lane; d < D; d += 64) { W_cold[row * D + d] = W_hot[s * D + d]; A_cold[row * D + d] = A_hot[s * D + d]; }
+        if (lane == 0) slot_of[row] = -1;
     }
 }
+
+// ... and the rows entering it take the freed slots first, then unused ones.
+template <typename WT>
+__global__ void __launch_bounds__(NT)
+pk_hh_insert_kernel(const WT* __restrict__ W_cold, const float* __restrict__ A_cold, WT* W_hot, float* A_hot,
+                    uint32_t* hot_row, int32_t* slot_of, const int32_t* __restrict__ evict_slot,
+                    const uint32_t* __restrict__ ins_row, const uint32_t* __restrict__ counts, int64_t n_hot_old,
+                    int64_t cap, int D)
+{
+    const int n_evict = (int)counts[0], n_ins = (int)counts[1], lane = threadIdx.x & 63;
+    for (int i = blockIdx.x * (NT / 64) + (threadIdx.x >> 6); i < n_ins; i += gridDim.x * (NT / 64)) {
+        const size_t row = ins_row[i];
+        const int64_t s = i < n_evict ? (int64_t)evict_slot[i] : n_hot_old + (i - n_evict);
+        if (s >= cap) continue;
+        for (int d = lane; d < D; d += 64) { W_hot[s * D + d] = W_cold[row * D + d]; A_hot[s * D + d] = A_cold[row * D + d]; }
+        if (lane == 0) { slot_of[row] = (int32_t)s; hot_row[s] = (uint32_t)row; }
+    }
+}
+
+// Histogram of the FCounter values of the rows that were ever queried.  Most of them share a
+// few small counts, and contended global atomics are served one at a time, so small counts
+// are tallied in LDS first.
+constexpr int kHhLdsBins = 2048;
 
 __global__ void __launch_bounds__(NT)
 pk_hh_hist_kernel(const uint32_t* __restrict__ fcounter, int64_t rows, uint32_t* hist)
 {
+    __shared__ uint32_t s_hist[kHhLdsBins];
+    for (int i = threadIdx.x; i < kHhLdsBins; i += NT) s_hist[i] = 0;
+    __syncthreads();
     for (int64_t r = (int64_t)blockIdx.x * NT + threadIdx.x; r < rows; r += (int64_t)gridDim.x * NT) {
         const uint32_t c = fcounter[r];
-        if (c) atomicAdd(&hist[min(c, (uint32_t)(kHhBins - 1))], 1u);
+        if (c == 0) continue;
+        if (c < (uint32_t)kHhLdsBins) atomicAdd(&s_hist[c], 1u);
+        else atomicAdd(&hist[min(c, (uint32_t)(kHhBins - 1))], 1u);
     }
+    __syncthreads();
+    for (int i = threadIdx.x; i < kHhLdsBins; i += NT)
+        if (s_hist[i]) atomicAdd(&hist[i], s_hist[i]);
 }
 
 // class of a row for the selection: 2 = count above the threshold, 1 = equal to it, 0 = below
@@ -1446,35 +1476,51 @@ pk_hh_scan_kernel(int32_t* tile_gt, int32_t* tile_eq, int n_tiles)
     }
 }
 
-// the new Hot-storage: every row above the threshold and the first need_eq rows equal to it,
-// in ascending row order; slot = rank of the row among the selected ones
+// The new content of the Hot-storage: every row above the threshold and the first need_eq
+// rows equal to it (ascending row order decides among those).  Compared with where the rows
+// live now this gives the slots to free and the rows to bring in; rows that stay are not moved.
 __global__ void __launch_bounds__(NT)
-pk_hh_select_kernel(const uint32_t* __restrict__ fcounter, int64_t rows, uint32_t thr, int need_eq,
-                    const int32_t* __restrict__ gt_before, const int32_t* __restrict__ eq_before,
-                    uint32_t* __restrict__ hot_row, int64_t cap)
+pk_hh_diff_kernel(const uint32_t* __restrict__ fcounter, int64_t rows, uint32_t thr, int need_eq,
+                  const int32_t* __restrict__ eq_before, const int32_t* __restrict__ slot_of,
+                  int32_t* __restrict__ evict_slot, uint32_t* __restrict__ ins_row, uint32_t* counts, int64_t cap)
 {
     constexpr int PER = kHhTile / NT;                 // consecutive rows per thread
     const int64_t r0 = (int64_t)blockIdx.x * kHhTile + (int64_t)threadIdx.x * PER;
     int cl[PER];
-    int gt = 0, eq = 0;
+    int eq = 0;
 #pragma unroll
     for (int j = 0; j < PER; ++j) {
         cl[j] = r0 + j < rows ? hh_class(fcounter[r0 + j], thr) : 0;
-        gt += cl[j] == 2; eq += cl[j] == 1;
+        eq += cl[j] == 1;
     }
-    int tg, te;
-    int xg = block_excl_scan<NT>(gt, &tg);
+    int te;
     int xe = block_excl_scan<NT>(eq, &te);
-    const int gb = gt_before[blockIdx.x], eb = eq_before[blockIdx.x];
+    const int eb = eq_before[blockIdx.x];
 #pragma unroll
     for (int j = 0; j < PER; ++j) {
-        const int eq_rank = eb + xe;                  // equal-count rows before this one
-        const bool take = cl[j] == 2 || (cl[j] == 1 && eq_rank < need_eq);
-        if (take) {
-            const int64_t pos = (int64_t)gb + xg + min(eq_rank, need_eq);
-            if (pos < cap) hot_row[pos] = (uint32_t)(r0 + j);
+        const bool take = cl[j] == 2 || (cl[j] == 1 && eb + xe < need_eq);
+        xe += cl[j] == 1;
+        const bool live = r0 + j < rows;
+        const int s = live ? slot_of[r0 + j] : -1;
+        // one atomic per wavefront and list: contended atomics are served one at a time
+        const bool ev = live && s >= 0 && !take, in = live && s < 0 && take;
+        const unsigned long long m_ev = __ballot(ev), m_in = __ballot(in);
+        const int lane = threadIdx.x & 63;
+        const unsigned long long below = (1ull << lane) - 1ull;
+        if (m_ev) {
+            uint32_t base = 0;
+            if (lane == __ffsll((unsigned long long)m_ev) - 1) base = atomicAdd(&counts[0], (uint32_t)__popcll(m_ev));
+            base = __shfl(base, __ffsll((unsigned long long)m_ev) - 1, 64);
+            const uint32_t i = base + (uint32_t)__popcll(m_ev & below);
+            if (ev && (int64_t)i < cap) evict_slot[i] = s;
         }
-        xg += cl[j] == 2; xe += cl[j] == 1;
+        if (m_in) {
+            uint32_t base = 0;
+            if (lane == __ffsll((unsigned long long)m_in) - 1) base = atomicAdd(&counts[1], (uint32_t)__popcll(m_in));
+            base = __shfl(base, __ffsll((unsigned long long)m_in) - 1, 64);
+            const uint32_t i = base + (uint32_t)__popcll(m_in & below);
+            if (in && (int64_t)i < cap) ins_row[i] = (uint32_t)(r0 + j);
+        }
     }
 }
 
@@ -1768,12 +1814,16 @@ int pool_variant(int dtype, int D, bool aligned, int* lpr_out)
 }
 
 template <typename WT>
-pk_status hh_move(DeviceState* ds, hipStream_t stream, const pk_hh_pack& h, int64_t n_hot, int D, int to_cold)
+pk_status hh_swap(DeviceState* ds, hipStream_t stream, const pk_hh_pack& h, int64_t n_hot_old, int64_t n_new, int D,
+                  const int32_t* evict_slot, const uint32_t* ins_row, const uint32_t* counts)
 {
-    if (n_hot <= 0) return PK_OK;
-    PK_LAUNCH("pk_hh_move", pk_hh_move_kernel<WT>, dim3(blocks_for(n_hot, NT / 64, 4096)), dim3(NT), 0,
-              static_cast<WT*>(h.W_cold), h.A_cold, static_cast<WT*>(h.W_hot), h.A_hot, h.hot_row, h.slot_of, n_hot, D,
-              to_cold);
+    // how many rows move is only known on the device; the grids cover the most that can
+    const unsigned grid = blocks_for(std::max<int64_t>(n_new, n_hot_old), NT / 64, 4096);
+    PK_LAUNCH("pk_hh_evict", pk_hh_evict_kernel<WT>, dim3(grid), dim3(NT), 0, static_cast<WT*>(h.W_cold), h.A_cold,
+              static_cast<const WT*>(h.W_hot), h.A_hot, h.hot_row, h.slot_of, evict_slot, counts, D);
+    PK_LAUNCH("pk_hh_insert", pk_hh_insert_kernel<WT>, dim3(grid), dim3(NT), 0, static_cast<const WT*>(h.W_cold),
+              h.A_cold, static_cast<WT*>(h.W_hot), h.A_hot, h.hot_row, h.slot_of, evict_slot, ins_row, counts, n_hot_old,
+              h.hot_rows, D);
     return PK_OK;
 }
 
@@ -2025,14 +2075,39 @@ static void hh_views(const pk_plan* plan, const pk_hh_pack* packs, std::vector<v
     }
 }
 
+
 static size_t hh_tiles(int64_t rows) { return (size_t)((rows + kHhTile - 1) / kHhTile); }
 
-size_t pk_hh_scratch_bytes(const pk_plan* plan)
+// scratch: histogram | per-pack counters | move counters | per-tile counts (2 arrays) | slots to free | rows to load
+struct HhScratch {
+    size_t hist, counters, moves, tile_gt, tile_eq, evict, ins, total;
+};
+
+static HhScratch hh_scratch_layout(const pk_plan* plan, const pk_hh_pack* packs)
 {
-    if (!plan) { set_error("pk_hh_scratch_bytes: plan is NULL"); return 0; }
-    size_t tiles = 0;
-    for (const Pack& k : plan->packs) tiles = std::max(tiles, hh_tiles(k.rows));
-    return (size_t)kHhBins * 4 + 256 + plan->packs.size() * 16 + 256 + 2 * (tiles * 4 + 256);
+    size_t tiles = 0, hot = 0;
+    for (size_t p = 0; p < plan->packs.size(); ++p) {
+        tiles = std::max(tiles, hh_tiles(plan->packs[p].rows));
+        hot = std::max(hot, (size_t)std::max<int64_t>(packs[p].hot_rows, 0));
+    }
+    auto up = [](size_t b) { return (b + 255) / 256 * 256; };
+    HhScratch L{};
+    size_t off = 0;
+    L.hist = off;     off += up((size_t)kHhBins * 4);
+    L.counters = off; off += up(plan->packs.size() * 16);
+    L.moves = off;    off += 256;
+    L.tile_gt = off;  off += up(tiles * 4);
+    L.tile_eq = off;  off += up(tiles * 4);
+    L.evict = off;    off += up(hot * 4);
+    L.ins = off;      off += up(hot * 4);
+    L.total = off;
+    return L;
+}
+
+size_t pk_hh_scratch_bytes(const pk_plan* plan, const pk_hh_pack* packs)
+{
+    if (!plan || !packs) { set_error("pk_hh_scratch_bytes: NULL argument"); return 0; }
+    return hh_scratch_layout(plan, packs).total;
 }
 
 pk_status pk_hh_init(pk_plan* plan, const pk_hh_pack* packs, void* hip_stream)
@@ -2087,7 +2162,7 @@ pk_status pk_hh_end_iteration(pk_plan* plan, const pk_hh_pack* packs, int64_t it
     rc = check_common(plan, B, nnz, workspace, ws_bytes, "pk_hh_end_iteration");
     if (rc != PK_OK) return rc;
     if (itr < 0 || warmup_iters < 0 || flush_iters <= 0) return fail(PK_EINVAL, "pk_hh_end_iteration: bad iteration arguments");
-    if (!scratch || reinterpret_cast<uintptr_t>(scratch) % kAlign || scratch_bytes < pk_hh_scratch_bytes(plan))
+    if (!scratch || reinterpret_cast<uintptr_t>(scratch) % kAlign || scratch_bytes < pk_hh_scratch_bytes(plan, packs))
         return fail(PK_EWORKSPACE, "pk_hh_end_iteration: scratch is NULL, misaligned or smaller than pk_hh_scratch_bytes");
     DeviceState* ds = nullptr;
     rc = ensure_device_state(plan, &ds);
@@ -2100,12 +2175,14 @@ pk_status pk_hh_end_iteration(pk_plan* plan, const pk_hh_pack* packs, int64_t it
     const PackState* st = reinterpret_cast<const PackState*>(wsb + L.state);
     const uint32_t* unique = reinterpret_cast<const uint32_t*>(wsb + L.unique);
     char* sc = static_cast<char*>(scratch);
-    uint32_t* hist = reinterpret_cast<uint32_t*>(sc);
-    unsigned long long* counters = reinterpret_cast<unsigned long long*>(sc + (size_t)kHhBins * 4 + 256);
-    size_t tiles_max = 0;
-    for (const Pack& k : plan->packs) tiles_max = std::max(tiles_max, hh_tiles(k.rows));
-    int32_t* tile_gt = reinterpret_cast<int32_t*>(sc + (size_t)kHhBins * 4 + 256 + (size_t)P * 16 + 256);
-    int32_t* tile_eq = tile_gt + tiles_max + 64;
+    const HhScratch S = hh_scratch_layout(plan, packs);
+    uint32_t* hist = reinterpret_cast<uint32_t*>(sc + S.hist);
+    unsigned long long* counters = reinterpret_cast<unsigned long long*>(sc + S.counters);
+    uint32_t* moves = reinterpret_cast<uint32_t*>(sc + S.moves);
+    int32_t* tile_gt = reinterpret_cast<int32_t*>(sc + S.tile_gt);
+    int32_t* tile_eq = reinterpret_cast<int32_t*>(sc + S.tile_eq);
+    int32_t* evict_slot = reinterpret_cast<int32_t*>(sc + S.evict);
+    uint32_t* ins_row = reinterpret_cast<uint32_t*>(sc + S.ins);
 
     // FCounter (both branches of Alg. 1 count the queried IDs) and the hit statistics
     hipError_t e = hipMemsetAsync(counters, 0, (size_t)P * 16, stream);
@@ -2129,19 +2206,17 @@ pk_status pk_hh_end_iteration(pk_plan* plan, const pk_hh_pack* packs, int64_t it
     }
     if (!flush) return PK_OK;
 
-    // reload: write the Hot-storage back, pick the top-k rows of FCounter, load them
+    // reload: pick the top-k rows of FCounter; rows that leave are written back, rows that enter
+    // are loaded, rows that stay are not touched
     std::vector<uint32_t> h_hist(kHhBins);
     for (int p = 0; p < P; ++p) {
         const Pack& k = plan->packs[p];
         const pk_hh_pack& h = packs[p];
         if (k.fields.empty() || h.hot_rows == 0) continue;
-        rc = k.dtype == PK_F32 ? hh_move<float>(ds, stream, h, ds->hh_n_hot[p], k.dim, 1)
-                               : hh_move<uint16_t>(ds, stream, h, ds->hh_n_hot[p], k.dim, 1);
-        if (rc != PK_OK) return rc;
-        ds->hh_n_hot[p] = 0;
         e = hipMemsetAsync(hist, 0, (size_t)kHhBins * 4, stream);
+        if (e == hipSuccess) e = hipMemsetAsync(moves, 0, 8, stream);
         if (e != hipSuccess) return fail(PK_EHIP, hip_msg("pk_hh_end_iteration", e));
-        PK_LAUNCH("pk_hh_hist", pk_hh_hist_kernel, dim3(blocks_for(k.rows, NT * 8, 4096)), dim3(NT), 0, h.fcounter,
+        PK_LAUNCH("pk_hh_hist", pk_hh_hist_kernel, dim3(blocks_for(k.rows, NT * 64, 1024)), dim3(NT), 0, h.fcounter,
                   k.rows, hist);
         e = hipStreamSynchronize(stream);
         if (e == hipSuccess) e = hipMemcpy(h_hist.data(), hist, (size_t)kHhBins * 4, hipMemcpyDeviceToHost);
@@ -2161,10 +2236,10 @@ pk_status pk_hh_end_iteration(pk_plan* plan, const pk_hh_pack* packs, int64_t it
         PK_LAUNCH("pk_hh_tilecount", pk_hh_tilecount_kernel, dim3(nt), dim3(NT), 0, h.fcounter, k.rows, thr, tile_gt,
                   tile_eq);
         PK_LAUNCH("pk_hh_scan", pk_hh_scan_kernel, dim3(1), dim3(1024), 0, tile_gt, tile_eq, (int)nt);
-        PK_LAUNCH("pk_hh_select", pk_hh_select_kernel, dim3(nt), dim3(NT), 0, h.fcounter, k.rows, thr, (int)need_eq,
-                  tile_gt, tile_eq, h.hot_row, h.hot_rows);
-        rc = k.dtype == PK_F32 ? hh_move<float>(ds, stream, h, n_new, k.dim, 0)
-                               : hh_move<uint16_t>(ds, stream, h, n_new, k.dim, 0);
+        PK_LAUNCH("pk_hh_diff", pk_hh_diff_kernel, dim3(nt), dim3(NT), 0, h.fcounter, k.rows, thr, (int)need_eq, tile_eq,
+                  h.slot_of, evict_slot, ins_row, moves, h.hot_rows);
+        rc = k.dtype == PK_F32 ? hh_swap<float>(ds, stream, h, ds->hh_n_hot[p], n_new, k.dim, evict_slot, ins_row, moves)
+                               : hh_swap<uint16_t>(ds, stream, h, ds->hh_n_hot[p], n_new, k.dim, evict_slot, ins_row, moves);
         if (rc != PK_OK) return rc;
         ds->hh_n_hot[p] = n_new;
     }

@@ -137,7 +137,7 @@ class HybridEmbedding(PackedEmbedding):
                 slot_of=torch.empty(R, dtype=torch.int32, device=self.device),
                 hot_row=torch.empty(max(k, 1), dtype=torch.int32, device=self.device),
                 fcounter=torch.empty(R, dtype=torch.int32, device=self.device)))
-        self.scratch_bytes = pk.pk_hh_scratch_bytes(self.plan)
+        self.scratch_bytes = pk.pk_hh_scratch_bytes(self.plan, self.hh)
         self.scratch = torch.empty(self.scratch_bytes + 256, dtype=torch.uint8, device=self.device)
         self.ws, self.ws_bytes, self._shape = None, 0, None
         pk.pk_hh_init(self.plan, self.hh, torch.cuda.current_stream(self.device).cuda_stream)

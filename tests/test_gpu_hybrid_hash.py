@@ -72,8 +72,8 @@ def test_hybrid_hash_follows_alg1_and_is_transparent(cold_on_host, dtype):
                 assert queried[p] == len(ctx[p].unique) and hits[p] == int(hit.sum()), f"iteration {itr} pack {p}: hits"
                 assert flushed == fl
                 n_hot = layer.hot_count(p)
-                got_hot = layer.hh[p]["hot_row"].cpu().numpy()[:n_hot].astype(np.int64)
-                assert np.array_equal(got_hot, oracles[p].hot), f"iteration {itr} pack {p}: Hot-storage content"
+                got_hot = layer.hh[p]["hot_row"].cpu().numpy()[:n_hot].astype(np.int64)     # slots in any order
+                assert np.array_equal(np.sort(got_hot), oracles[p].hot), f"iteration {itr} pack {p}: Hot-storage content"
                 assert np.array_equal(layer.hh[p]["fcounter"].cpu().numpy().astype(np.int64), oracles[p].fcounter)
                 Wl, Al, slot = logical_rows(layer, p)
                 assert int((slot >= 0).sum()) == n_hot and np.array_equal(slot[got_hot], np.arange(n_hot))
