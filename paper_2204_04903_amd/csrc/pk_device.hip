@@ -1440,39 +1440,33 @@ __device__ __forceinline__ int hh_class(uint32_t c, uint32_t thr)
     return b > thr ? 2 : (b == thr ? 1 : 0);
 }
 
-// per tile of rows: how many rows above the threshold, how many equal to it
+// per tile of rows: how many rows have a count equal to the threshold
 __global__ void __launch_bounds__(NT)
-pk_hh_tilecount_kernel(const uint32_t* __restrict__ fcounter, int64_t rows, uint32_t thr,
-                       int32_t* __restrict__ tile_gt, int32_t* __restrict__ tile_eq)
+pk_hh_tilecount_kernel(const uint32_t* __restrict__ fcounter, int64_t rows, uint32_t thr, int32_t* __restrict__ tile_eq)
 {
     const int64_t r0 = (int64_t)blockIdx.x * kHhTile;
-    int gt = 0, eq = 0;
+    int eq = 0;
     for (int i = threadIdx.x; i < kHhTile; i += NT) {
         const int64_t r = r0 + i;
-        if (r < rows) {
-            const int cl = hh_class(fcounter[r], thr);
-            gt += cl == 2; eq += cl == 1;
-        }
+        if (r < rows) eq += hh_class(fcounter[r], thr) == 1;
     }
-    int tg, te;
-    (void)block_excl_scan<NT>(gt, &tg);
+    int te;
     (void)block_excl_scan<NT>(eq, &te);
-    if (threadIdx.x == 0) { tile_gt[blockIdx.x] = tg; tile_eq[blockIdx.x] = te; }
+    if (threadIdx.x == 0) tile_eq[blockIdx.x] = te;
 }
 
-// exclusive scans of the two per-tile arrays, in place (one block)
+// exclusive scan of the per-tile array, in place (one block)
 __global__ void __launch_bounds__(1024)
-pk_hh_scan_kernel(int32_t* tile_gt, int32_t* tile_eq, int n_tiles)
+pk_hh_scan_kernel(int32_t* tile_eq, int n_tiles)
 {
-    int cg = 0, ce = 0;
+    int ce = 0;
     for (int base = 0; base < n_tiles; base += 1024) {
         const int i = base + threadIdx.x;
-        const int g = i < n_tiles ? tile_gt[i] : 0, e = i < n_tiles ? tile_eq[i] : 0;
-        int tg, te;
-        const int xg = block_excl_scan<1024>(g, &tg);
+        const int e = i < n_tiles ? tile_eq[i] : 0;
+        int te;
         const int xe = block_excl_scan<1024>(e, &te);
-        if (i < n_tiles) { tile_gt[i] = cg + xg; tile_eq[i] = ce + xe; }
-        cg += tg; ce += te;
+        if (i < n_tiles) tile_eq[i] = ce + xe;
+        ce += te;
     }
 }
 
@@ -2078,9 +2072,9 @@ static void hh_views(const pk_plan* plan, const pk_hh_pack* packs, std::vector<v
 
 static size_t hh_tiles(int64_t rows) { return (size_t)((rows + kHhTile - 1) / kHhTile); }
 
-// scratch: histogram | per-pack counters | move counters | per-tile counts (2 arrays) | slots to free | rows to load
+// scratch: histogram | per-pack counters | move counters | per-tile counts | slots to free | rows to load
 struct HhScratch {
-    size_t hist, counters, moves, tile_gt, tile_eq, evict, ins, total;
+    size_t hist, counters, moves, tile_eq, evict, ins, total;
 };
 
 static HhScratch hh_scratch_layout(const pk_plan* plan, const pk_hh_pack* packs)
@@ -2096,7 +2090,6 @@ static HhScratch hh_scratch_layout(const pk_plan* plan, const pk_hh_pack* packs)
     L.hist = off;     off += up((size_t)kHhBins * 4);
     L.counters = off; off += up(plan->packs.size() * 16);
     L.moves = off;    off += 256;
-    L.tile_gt = off;  off += up(tiles * 4);
     L.tile_eq = off;  off += up(tiles * 4);
     L.evict = off;    off += up(hot * 4);
     L.ins = off;      off += up(hot * 4);
@@ -2179,7 +2172,6 @@ pk_status pk_hh_end_iteration(pk_plan* plan, const pk_hh_pack* packs, int64_t it
     uint32_t* hist = reinterpret_cast<uint32_t*>(sc + S.hist);
     unsigned long long* counters = reinterpret_cast<unsigned long long*>(sc + S.counters);
     uint32_t* moves = reinterpret_cast<uint32_t*>(sc + S.moves);
-    int32_t* tile_gt = reinterpret_cast<int32_t*>(sc + S.tile_gt);
     int32_t* tile_eq = reinterpret_cast<int32_t*>(sc + S.tile_eq);
     int32_t* evict_slot = reinterpret_cast<int32_t*>(sc + S.evict);
     uint32_t* ins_row = reinterpret_cast<uint32_t*>(sc + S.ins);
@@ -2233,9 +2225,8 @@ pk_status pk_hh_end_iteration(pk_plan* plan, const pk_hh_pack* packs, int64_t it
         const int64_t n_new = above + std::min<int64_t>(need_eq, h_hist[thr]);
         if (n_new == 0) continue;
         const unsigned nt = (unsigned)hh_tiles(k.rows);
-        PK_LAUNCH("pk_hh_tilecount", pk_hh_tilecount_kernel, dim3(nt), dim3(NT), 0, h.fcounter, k.rows, thr, tile_gt,
-                  tile_eq);
-        PK_LAUNCH("pk_hh_scan", pk_hh_scan_kernel, dim3(1), dim3(1024), 0, tile_gt, tile_eq, (int)nt);
+        PK_LAUNCH("pk_hh_tilecount", pk_hh_tilecount_kernel, dim3(nt), dim3(NT), 0, h.fcounter, k.rows, thr, tile_eq);
+        PK_LAUNCH("pk_hh_scan", pk_hh_scan_kernel, dim3(1), dim3(1024), 0, tile_eq, (int)nt);
         PK_LAUNCH("pk_hh_diff", pk_hh_diff_kernel, dim3(nt), dim3(NT), 0, h.fcounter, k.rows, thr, (int)need_eq, tile_eq,
                   h.slot_of, evict_slot, ins_row, moves, h.hot_rows);
         rc = k.dtype == PK_F32 ? hh_swap<float>(ds, stream, h, ds->hh_n_hot[p], n_new, k.dim, evict_slot, ins_row, moves)

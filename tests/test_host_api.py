@@ -139,3 +139,27 @@ def test_generator_is_reproducible_and_shaped_like_the_configs():
     assert np.array_equal(r1[0], r2[3]) and np.array_equal(r1[1], r2[1]) and np.array_equal(r1[0], r1[2])
     big = synth.table_rows(synth.config(2), 0, row0=0, n=20000)
     assert abs(float(big.std()) - 0.01) < 2e-4 and abs(float(big.mean())) < 2e-4
+
+
+def test_hybrid_hash_calls_reject_bad_arguments_before_touching_the_gpu():
+    plan = pk.pk_plan_create([(100, 8, 0)], [(0, 0)])
+    try:
+        fake = 0x10000   # never dereferenced: every call below fails validation first
+        good = dict(W_cold=fake, A_cold=fake, W_hot=fake, A_hot=fake, slot_of=fake, hot_row=fake, fcounter=fake, hot_rows=10)
+        assert pk.pk_hh_scratch_bytes(plan, [good]) > 0
+        assert pk.pk_hh_scratch_bytes(plan, [dict(good, hot_rows=1000)]) > pk.pk_hh_scratch_bytes(plan, [good])
+
+        def status(fn):
+            with pytest.raises(pk.PkError) as e:
+                fn()
+            return e.value.status
+        for missing in ("W_cold", "A_cold", "slot_of", "fcounter", "W_hot"):
+            bad = dict(good, **{missing: None})
+            assert status(lambda: pk.pk_hh_forward(plan, [bad], fake, fake, 4, 4, fake, 8, fake, 1 << 20)) == pk.PK_EINVAL
+        assert status(lambda: pk.pk_hh_forward(plan, [dict(good, hot_rows=-1)], fake, fake, 4, 4, fake, 8, fake, 1 << 20)) == pk.PK_EINVAL
+        need = pk.pk_workspace_bytes(plan, 4, 4)
+        assert status(lambda: pk.pk_hh_end_iteration(plan, [good], 0, 1, 0, 4, 4, fake, need, fake, 1 << 30)) == pk.PK_EINVAL
+        assert status(lambda: pk.pk_hh_end_iteration(plan, [good], 0, 1, 1, 4, 4, fake, need, fake, 16)) == pk.PK_EWORKSPACE
+        assert pk.pk_hh_hot_count(plan, 0) == 0
+    finally:
+        pk.pk_plan_destroy(plan)
