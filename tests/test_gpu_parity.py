@@ -309,9 +309,27 @@ def test_config2_full_size():
 
 
 @pytest.mark.timeout(900)
-def test_config3_full_size_one_step():
+def test_config3_full_size():
     # 200 fields, four packs, ~21 M occurrences, ~103 GB of tables and accumulators
     free, _ = torch.cuda.mem_get_info()
     if free < 130 * 2**30:
         pytest.skip("needs about 110 GB of free device memory")
-    run_config(3, steps=1)
+    run_config(3)
+
+
+@pytest.mark.timeout(900)
+def test_config4_full_size():
+    # 1000 fields, two packs, ~11 M occurrences of raw 64-bit IDs, ~21 GB of tables and accumulators
+    free, _ = torch.cuda.mem_get_info()
+    if free < 40 * 2**30:
+        pytest.skip("needs about 25 GB of free device memory")
+    run_config(4)
+
+
+@pytest.mark.timeout(900)
+def test_config5_full_size():
+    # 60 fields of bf16 tables, sequences of 100-1000 IDs, ~5.7 M occurrences, ~46 GB of tables and accumulators
+    free, _ = torch.cuda.mem_get_info()
+    if free < 70 * 2**30:
+        pytest.skip("needs about 50 GB of free device memory")
+    run_config(5)
