@@ -89,6 +89,12 @@ def main():
                     help="HybridHash: where the Cold-storage lives (pinned host memory or device memory)")
     ap.add_argument("--hh-warmup", type=int, default=20)
     ap.add_argument("--hh-flush", type=int, default=10)
+    ap.add_argument("--micro-batches", type=int, default=0,
+                    help="D-Interleaving: cut every batch into this many micro-batches and pass them through the "
+                         "layer one after the other, the next one's dedup on a second stream (1 = whole batches, "
+                         "pipelined the same way; 0 = off: one pk_forward and one pk_backward_update per batch)")
+    ap.add_argument("--micro-serial", action="store_true",
+                    help="with --micro-batches: no second stream, every micro-batch starts when the one before is done")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (a known size for scaling rocprofv3's byte counters)")
@@ -103,7 +109,7 @@ def main():
 
     import synth
     from paper_2204_04903_amd import binding as pk
-    from paper_2204_04903_amd.layer import HybridEmbedding, PackedEmbedding
+    from paper_2204_04903_amd.layer import HybridEmbedding, MicroBatchPipeline, PackedEmbedding
 
     idx = int(args.workload[3])
     wl = synth.config(idx)
@@ -158,14 +164,55 @@ def main():
         if hybrid:
             layer.end_iteration(want_counts=False)
 
+    micro_info = None
+    if args.micro_batches > 0 and not hybrid:
+        # the ring's batches cut into micro-batches, resident like the whole batches
+        M = args.micro_batches
+        mdev = []
+        for b in batches:
+            row = []
+            for mb in synth.split_batch(b, wl.n_fields, wl.batch, M):
+                row.append((torch.from_numpy(mb.ids).cuda(), torch.from_numpy(mb.offsets).cuda(),
+                            torch.from_numpy(mb.grad_out).cuda(), mb.grad_out.shape[0]))
+            mdev.append(row)
+        b_max = max(m[3] for row in mdev for m in row)
+        n_max = max(int(m[0].shape[0]) for row in mdev for m in row)
+        pipe = MicroBatchPipeline(layer, b_max, n_max)
+        bounds = [(wl.batch * m) // M for m in range(M + 1)]
+
+        def run_steps(first, count):
+            seq = [((first + i) % ring, m) for i in range(count) for m in range(M)]
+            if args.micro_serial:
+                for r, m in seq:
+                    ids, offsets, grad, bm = mdev[r][m]
+                    t = pipe.submit(ids, offsets, bm)
+                    pipe.pool(t, out[bounds[m]:bounds[m + 1]])
+                    pipe.backward_update(t, grad, wl.lr, wl.eps)
+                return
+            t = pipe.submit(*mdev[seq[0][0]][seq[0][1]][:2], mdev[seq[0][0]][seq[0][1]][3])
+            for j, (r, m) in enumerate(seq):
+                nxt = None
+                if j + 1 < len(seq):
+                    ids, offsets, _, bm = mdev[seq[j + 1][0]][seq[j + 1][1]]
+                    nxt = pipe.submit(ids, offsets, bm)
+                pipe.pool(t, out[bounds[m]:bounds[m + 1]])
+                pipe.backward_update(t, mdev[r][m][2], wl.lr, wl.eps)
+                t = nxt
+
+        micro_info = {"micro_batches": M, "micro_batch_size": b_max, "interleaved": not args.micro_serial,
+                      "workspace_bytes": 2 * pipe.ws_bytes,
+                      "whole_batch_workspace_bytes": pk.pk_workspace_bytes(layer.plan, wl.batch, max_nnz)}
+    else:
+        def run_steps(first, count):
+            for i in range(count):
+                step(first + i)
+
     if hybrid:                       # Alg. 1's warm-up iterations and the first reload come before the clock
         args.warmup = max(args.warmup, args.hh_warmup + args.hh_flush + 1)
-    for i in range(args.warmup):
-        step(i)
+    run_steps(0, args.warmup)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for i in range(args.steps):
-        step(args.warmup + i)
+    run_steps(args.warmup, args.steps)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     lookups = sum(batches[(args.warmup + i) % ring].nnz for i in range(args.steps))
@@ -268,7 +315,7 @@ def main():
         "vs_baseline": None,
         "dtype": "f32" if wl.tables[0].dtype == 0 else "bf16 tables, f32 arithmetic",
         "data": "synthetic",
-        "config": {"workload": f"{args.workload}: {wl.description}" + (" [HybridHash]" if hybrid else ""), "batch": wl.batch, "fields": wl.n_fields,
+        "config": {"workload": f"{args.workload}: {wl.description}" + (" [HybridHash]" if hybrid else "") + (f" [{args.micro_batches} micro-batch(es) per batch]" if micro_info else ""), "batch": wl.batch, "fields": wl.n_fields,
                    "packs": layer.n_packs, "max_shards": args.max_shards, "interleave_groups": args.groups, "ring_batches": ring, "lookups_per_step": lookups / args.steps,
                    "distinct_keys_per_step": sum(i["U"] for i in sizes[0])},
         "hbm_model": {"bytes_per_step": model_bytes, "GBps": model_bytes / (ms_per_step * 1e-3) / 1e9,
@@ -276,6 +323,7 @@ def main():
         "roofline": roofline,
         "cpu_baseline": cpu,
         "hybrid_hash": hybrid_info,
+        "d_interleaving": micro_info,
         "kernels": {k: {kk: round(vv, 6) for kk, vv in v.items()} for k, v in kern.items()},
         "input_generation_s": round(gen_s, 2),
     }

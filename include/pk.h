@@ -143,6 +143,41 @@ pk_status pk_backward_update(const pk_plan* plan, void* const* W, float* const* 
                              float lr, float eps,
                              void* workspace, size_t ws_bytes, void* hip_stream);
 
+/* ---- D-Interleaving (Sec. III-C, Eq. 2): the layer on micro-batches -------------
+ * A batch is cut into micro-batches that pass through the layer one after the
+ * other, each with a workspace of its own size, so that the memory that grows
+ * with the batch is bounded; stages of different micro-batches that use
+ * different resources run side by side.  The forward pass is offered in its two
+ * stages for that: the dedup of a micro-batch (H1 + H2: integer work that reads
+ * no table) may run on another stream while the previous micro-batch is pooled
+ * and updated.
+ *
+ * pk_forward_dedup + pk_forward_pool on the same workspace, B and nnz, in this order, compute
+ * exactly what pk_forward computes (pk_forward may share launches between the
+ * two stages).  Arguments as for pk_forward.  The caller orders the streams:
+ * pk_forward_pool after the pk_forward_dedup of its workspace, pk_backward_update after the
+ * pool stage, and a pool stage that must see an update after that update. */
+pk_status pk_forward_dedup(const pk_plan* plan, const int64_t* ids, const int32_t* offsets, int32_t B, int64_t nnz,
+                   void* workspace, size_t ws_bytes, void* hip_stream);
+pk_status pk_forward_pool(const pk_plan* plan, void* const* W, int32_t B, int64_t nnz,
+                  float* out, int64_t out_row_stride,
+                  void* workspace, size_t ws_bytes, void* hip_stream);
+
+/* Eq. 2: BS_micro = min over the layer's operators of RBound_op / RInstance_op,
+ * for the two resources of this layer that grow with the batch:
+ *   - the workspace: RInstance from pk_workspace_bytes at the observed
+ *     occurrences per sample (nnz / B of a warm-up batch; the part of the
+ *     workspace that does not depend on the batch is taken off the bound first),
+ *     RBound = ws_bound_bytes;
+ *   - the activations: 8 * out_dim bytes per sample (pooled output and its
+ *     gradient, fp32), RBound = act_bound_bytes.
+ * A bound of 0 means "no bound".  The result is evened out as the paper does
+ * (micro-batches of equal size): with M = ceil(B / BS_micro) micro-batches it is
+ * ceil(B / M).  Returns 0 if not even one sample fits, -1 on bad arguments.
+ * Host only. */
+int32_t pk_micro_batch_size(const pk_plan* plan, int32_t B, int64_t nnz,
+                            size_t ws_bound_bytes, size_t act_bound_bytes);
+
 /* ---- HybridHash (Sec. III-D, Alg. 1): a Hot-storage in front of the tables -----
  * The pack's table passed as W_cold / A_cold is the Cold-storage and holds every
  * row; it only has to be device-ACCESSIBLE, so it may be pinned host memory

@@ -168,6 +168,27 @@ int32_t orc_shard_split(int32_t n_tables, const int64_t *rows, const int32_t *di
     return n_packs;
 }
 
+/* Sec. III-C, Eq. 2 (D-Interleaving): the micro-batch size is the smallest, over
+ * the layer's operators, of the bound of the operator's dominant resource
+ * divided by what one data instance costs of it,
+ *   BS_micro = min_op RBound_op / RInstance_op ,
+ * taken as whole samples and never more than the batch; the batch is then cut
+ * into micro-batches of equal size (the paper's default), so with
+ * M = ceil(B / BS_micro) micro-batches the size is ceil(B / M).  0 if not even
+ * one sample fits. */
+int32_t orc_micro_batch_size(int32_t B, int32_t n_ops, const double *rbound, const double *rinstance)
+{
+    double bs = (double)B;
+    for (int32_t o = 0; o < n_ops; ++o) {
+        double r = floor(rbound[o] / rinstance[o]);
+        if (r < bs) bs = r;
+    }
+    if (bs < 1.0) return 0;
+    int32_t b = (int32_t)bs;
+    int32_t M = (B + b - 1) / b;
+    return (B + M - 1) / M;
+}
+
 /* Fields follow their tables: slot = rank among the pack's fields in field
  * order; col(f) = running sum of the dims of the fields before f. */
 void orc_field_slots(int32_t n_fields, const int32_t *field_table, const int32_t *table_pack, const int32_t *dim,

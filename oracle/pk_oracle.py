@@ -41,6 +41,7 @@ def lib():
         _lib.orc_unique.restype = ctypes.c_int32
         _lib.orc_calc_vparam.restype = ctypes.c_double
         _lib.orc_shard_split.restype = ctypes.c_int32
+        _lib.orc_micro_batch_size.restype = ctypes.c_int32
         _lib.orc_field_slots.restype = None
         _lib.orc_bf16_round.restype = ctypes.c_uint16
         _lib.orc_bf16_round.argtypes = [ctypes.c_float]
@@ -130,6 +131,12 @@ def plan(tables: Sequence[Tuple[int, int, int]], fields: Sequence[Tuple[int, int
 def calc_vparam(pl: Plan, occurrences: Sequence[float], pack: int) -> float:
     occ = _c(occurrences, np.float64)
     return float(lib().orc_calc_vparam(i32(len(pl.rows)), _p(pl.table_pack), _p(pl.dim), _p(occ), i32(pack)))
+
+
+def micro_batch_size(B: int, rbound: Sequence[float], rinstance: Sequence[float]) -> int:
+    """Sec. III-C, Eq. 2, then the even cut into micro-batches."""
+    rb, ri = _c(rbound, np.float64), _c(rinstance, np.float64)
+    return int(lib().orc_micro_batch_size(ctypes.c_int32(B), ctypes.c_int32(len(rb)), _p(rb), _p(ri)))
 
 
 def pack_keys(pl: Plan, p: int, B: int, ids: np.ndarray, offsets: np.ndarray):

@@ -62,12 +62,14 @@ class SparseOracle:
         W[i_new], A[i_new] = Wnew, Anew
         self.keys_seen[p], self.W_seen[p], self.A_seen[p] = allk, W, A
 
-    def step(self, batch, lr, eps, rows=None):
+    def step(self, batch, lr, eps, rows=None, B=None):
         """One forward + backward + update.  Returns (out, per-pack dict with the
         integer context and the updated rows).  `rows[p]`, when given, is the
         (W, A) pair current_rows would return for pack p (lets a caller keep the
-        input generator out of a timed region)."""
-        orc, pl, B = self.orc, self.pl, self.wl.batch
+        input generator out of a timed region).  `B`: samples in `batch` when it
+        is not a whole batch of the workload (a micro-batch)."""
+        orc, pl = self.orc, self.pl
+        B = self.wl.batch if B is None else B
         out = np.zeros((B, pl.out_dim), np.float32)
         res = []
         for p in range(pl.n_packs):

@@ -25,7 +25,7 @@ EXPORTS = [
     "pk_plan_table_slot", "pk_plan_field_col", "pk_plan_out_dim", "pk_workspace_bytes", "pk_forward",
     "pk_backward_update", "pk_ctx_pack", "pk_ctx_error", "pk_profile_enable", "pk_profile_read", "pk_last_error",
     "pk_hh_scratch_bytes", "pk_hh_init", "pk_hh_forward", "pk_hh_backward_update", "pk_hh_end_iteration",
-    "pk_hh_hot_count",
+    "pk_hh_hot_count", "pk_forward_dedup", "pk_forward_pool", "pk_micro_batch_size",
 ]
 
 
@@ -99,6 +99,12 @@ def lib():
         L.pk_workspace_bytes.argtypes = [vp, i32, i64]
         L.pk_forward.restype = ctypes.c_int
         L.pk_forward.argtypes = [vp, ctypes.POINTER(vp), vp, vp, i32, i64, vp, i64, vp, ctypes.c_size_t, vp]
+        L.pk_forward_dedup.restype = ctypes.c_int
+        L.pk_forward_dedup.argtypes = [vp, vp, vp, i32, i64, vp, ctypes.c_size_t, vp]
+        L.pk_forward_pool.restype = ctypes.c_int
+        L.pk_forward_pool.argtypes = [vp, ctypes.POINTER(vp), i32, i64, vp, i64, vp, ctypes.c_size_t, vp]
+        L.pk_micro_batch_size.restype = ctypes.c_int32
+        L.pk_micro_batch_size.argtypes = [vp, i32, i64, ctypes.c_size_t, ctypes.c_size_t]
         L.pk_backward_update.restype = ctypes.c_int
         L.pk_backward_update.argtypes = [vp, ctypes.POINTER(vp), ctypes.POINTER(vp), vp, i64, i32, i64,
                                          ctypes.c_float, ctypes.c_float, vp, ctypes.c_size_t, vp]
@@ -221,6 +227,22 @@ def pk_forward(plan: int, W: Sequence, ids, offsets, B: int, nnz: int, out, out_
                workspace, ws_bytes: int, stream: int = 0) -> None:
     _check(lib().pk_forward(plan, _ptr_array(W), _ptr(ids), _ptr(offsets), B, nnz, _ptr(out), out_row_stride,
                             _ptr(workspace), ws_bytes, stream))
+
+
+def pk_forward_dedup(plan: int, ids, offsets, B: int, nnz: int, workspace, ws_bytes: int, stream: int = 0) -> None:
+    _check(lib().pk_forward_dedup(plan, _ptr(ids), _ptr(offsets), B, nnz, _ptr(workspace), ws_bytes, stream))
+
+
+def pk_forward_pool(plan: int, W: Sequence, B: int, nnz: int, out, out_row_stride: int, workspace, ws_bytes: int,
+            stream: int = 0) -> None:
+    _check(lib().pk_forward_pool(plan, _ptr_array(W), B, nnz, _ptr(out), out_row_stride, _ptr(workspace), ws_bytes, stream))
+
+
+def pk_micro_batch_size(plan: int, B: int, nnz: int, ws_bound_bytes: int = 0, act_bound_bytes: int = 0) -> int:
+    n = int(lib().pk_micro_batch_size(plan, B, nnz, ws_bound_bytes, act_bound_bytes))
+    if n < 0:
+        raise PkError(PK_EINVAL, pk_last_error())
+    return n
 
 
 def pk_backward_update(plan: int, W: Sequence, A: Sequence, grad_out, grad_row_stride: int, B: int, nnz: int,

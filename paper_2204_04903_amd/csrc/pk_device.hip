@@ -1842,18 +1842,25 @@ void destroy_device_state(pk_plan* plan)
 
 extern "C" {
 
-// hot: per pack, where the rows of a Hot-storage live (HybridHash), or NULL
-static pk_status forward_impl(const pk_plan* plan, void* const* W, const HotView* hot, const int64_t* ids,
-                              const int32_t* offsets, int32_t B, int64_t nnz, float* out, int64_t out_row_stride,
-                              void* workspace, size_t ws_bytes, void* hip_stream)
+// The forward pass, or one of its two stages (Sec. III-C, D-Interleaving runs them on different
+// streams for different micro-batches): kDedup = H1 + H2, kPool = H3-H5 from a workspace that a
+// dedup stage filled.  hot: per pack, where the rows of a Hot-storage live (HybridHash), or NULL.
+enum { kDedup = 1, kPool = 2 };
+
+static pk_status forward_impl(const pk_plan* plan, int stages, const char* who, void* const* W, const HotView* hot,
+                              const int64_t* ids, const int32_t* offsets, int32_t B, int64_t nnz, float* out,
+                              int64_t out_row_stride, void* workspace, size_t ws_bytes, void* hip_stream)
 {
-    pk_status rc = check_common(plan, B, nnz, workspace, ws_bytes, "pk_forward");
+    const bool do_dedup = stages & kDedup, do_pool = stages & kPool;
+    pk_status rc = check_common(plan, B, nnz, workspace, ws_bytes, who);
     if (rc != PK_OK) return rc;
-    if (!W || !offsets || !out || (!ids && nnz > 0)) return fail(PK_EINVAL, "pk_forward: NULL argument");
+    if (do_dedup && (!offsets || (!ids && nnz > 0))) return fail(PK_EINVAL, std::string(who) + ": NULL argument");
+    if (do_pool && (!W || !out)) return fail(PK_EINVAL, std::string(who) + ": NULL argument");
     const int P = (int)plan->packs.size(), F = (int)plan->fields.size();
-    for (int p = 0; p < P; ++p)
-        if (!W[p]) return fail(PK_EINVAL, "pk_forward: W[" + std::to_string(p) + "] is NULL");
-    if (out_row_stride < plan->out_dim) return fail(PK_ESHAPE, "pk_forward: out_row_stride is smaller than out_dim");
+    for (int p = 0; p < P && do_pool; ++p)
+        if (!W[p]) return fail(PK_EINVAL, std::string(who) + ": W[" + std::to_string(p) + "] is NULL");
+    if (do_pool && out_row_stride < plan->out_dim)
+        return fail(PK_ESHAPE, std::string(who) + ": out_row_stride is smaller than out_dim");
     DeviceState* ds = nullptr;
     rc = ensure_device_state(plan, &ds);
     if (rc != PK_OK) return rc;
@@ -1888,7 +1895,8 @@ static pk_status forward_impl(const pk_plan* plan, void* const* W, const HotView
     const int bt = long_bags ? 32 : 256;
     const dim3 key_grid(blocks_for(n_bags, bt, 256 * 8));
     const size_t key_lds = (size_t)(3 * F + 2) * 4;
-    if (long_bags)
+    if (!do_dedup) {
+    } else if (long_bags)
         PK_LAUNCH("pk_keys", pk_keys_kernel<32>, key_grid, dim3(NT), key_lds, ids, offsets, B, F, P, nnz, ds->fmeta,
                   ds->pmeta, ds->slot_field, st, fb, delta, keys, bagref, baglen, packed_offsets, plan->out_dim,
                   reinterpret_cast<uint4*>(tile_desc), n_clear4);
@@ -1906,13 +1914,14 @@ static pk_status forward_impl(const pk_plan* plan, void* const* W, const HotView
     const int G = plan->opts.interleave_groups;
     const bool overlap = ds->overlap && !ds->prof_on &&
                          (G >= 2 || (G == 0 && (P > 1 || nnz >= (1 << 20)) && nnz >= (1 << 18)));
-    const int n_side = overlap ? std::min<int>(P, G >= 2 ? G : 4) : 0;
-    const bool fuse_pool = !hot && !n_side && P <= kFusedPacks && T > 0 && nnz < (1 << 20) && ds->fuse;
+    const int n_side = overlap && do_pool ? std::min<int>(P, G >= 2 ? G : 4) : 0;
+    const bool fuse_pool = do_dedup && do_pool && !hot && !n_side && P <= kFusedPacks && T > 0 && nnz < (1 << 20) &&
+                           ds->fuse;
     auto pool_aligned = [&](int p) {
         return cols_aligned(plan, p) && aligned16(out) && out_row_stride % 4 == 0 && aligned16(W[p]);
     };
     if (n_side) { rc = fork_streams(ds, stream, n_side); if (rc != PK_OK) return rc; }
-    for (int p = 0; p < P && !fuse_pool; ++p) {
+    for (int p = 0; p < P && do_pool && !fuse_pool; ++p) {
         const Pack& k = plan->packs[p];
         if (k.fields.empty()) continue;
         PoolArgs a{W[p], keys, packed_offsets + po_off(plan, p, B), st + p, ds->fmeta, ds->slot_field + k.first_slot,
@@ -1924,6 +1933,10 @@ static pk_status forward_impl(const pk_plan* plan, void* const* W, const HotView
         if (rc != PK_OK) return rc;
     }
 
+    if (!do_dedup) {
+        if (n_side) { rc = join_streams(ds, stream, n_side); if (rc != PK_OK) return rc; }
+        return PK_OK;
+    }
     PK_LAUNCH("pk_mark", pk_mark_kernel, dim3((unsigned)plan->mark_items.size()), dim3(kMarkThreads), 0, ds->mark_items,
               ds->mark_fields, ds->pmeta, st, fb, delta, keys, bitmap, nnz);
     PK_LAUNCH("pk_tiles", pk_tiles_kernel, dim3(blocks_for(n_tiles, 1, 1024)), dim3(NT), 0,
@@ -1977,7 +1990,22 @@ pk_status pk_forward(const pk_plan* plan, void* const* W, const int64_t* ids, co
                      int64_t nnz, float* out, int64_t out_row_stride, void* workspace, size_t ws_bytes,
                      void* hip_stream)
 {
-    return forward_impl(plan, W, nullptr, ids, offsets, B, nnz, out, out_row_stride, workspace, ws_bytes, hip_stream);
+    return forward_impl(plan, kDedup | kPool, "pk_forward", W, nullptr, ids, offsets, B, nnz, out, out_row_stride,
+                        workspace, ws_bytes, hip_stream);
+}
+
+pk_status pk_forward_dedup(const pk_plan* plan, const int64_t* ids, const int32_t* offsets, int32_t B, int64_t nnz,
+                   void* workspace, size_t ws_bytes, void* hip_stream)
+{
+    return forward_impl(plan, kDedup, "pk_forward_dedup", nullptr, nullptr, ids, offsets, B, nnz, nullptr, 0, workspace,
+                        ws_bytes, hip_stream);
+}
+
+pk_status pk_forward_pool(const pk_plan* plan, void* const* W, int32_t B, int64_t nnz, float* out, int64_t out_row_stride,
+                  void* workspace, size_t ws_bytes, void* hip_stream)
+{
+    return forward_impl(plan, kPool, "pk_forward_pool", W, nullptr, nullptr, nullptr, B, nnz, out, out_row_stride, workspace,
+                        ws_bytes, hip_stream);
 }
 
 static pk_status backward_impl(const pk_plan* plan, void* const* W, float* const* A, const HotView* hot,
@@ -2129,7 +2157,8 @@ pk_status pk_hh_forward(const pk_plan* plan, const pk_hh_pack* packs, const int6
     if (rc != PK_OK) return rc;
     std::vector<void*> W; std::vector<float*> A; std::vector<HotView> hv;
     hh_views(plan, packs, &W, &A, &hv);
-    return forward_impl(plan, W.data(), hv.data(), ids, offsets, B, nnz, out, out_row_stride, workspace, ws_bytes,
+    return forward_impl(plan, kDedup | kPool, "pk_hh_forward", W.data(), hv.data(), ids, offsets, B, nnz, out,
+                        out_row_stride, workspace, ws_bytes,
                         hip_stream);
 }
 

@@ -298,4 +298,33 @@ size_t pk_workspace_bytes(const pk_plan* plan, int32_t B, int64_t nnz)
     return make_layout(plan, B, nnz).total;
 }
 
+// Sec. III-C, Eq. 2: BS_micro = min over operators of RBound / RInstance, for the workspace
+// (RInstance from the layout at the observed occurrences per sample) and the activations.
+int32_t pk_micro_batch_size(const pk_plan* plan, int32_t B, int64_t nnz, size_t ws_bound_bytes, size_t act_bound_bytes)
+{
+    if (!plan) { set_error("pk_micro_batch_size: plan is NULL"); return -1; }
+    if (B <= 0 || nnz < 0 || nnz >= ((int64_t)1 << 31)) {
+        set_error("pk_micro_batch_size: B must be positive and nnz in [0, 2^31)");
+        return -1;
+    }
+    auto nnz_of = [&](int64_t b) { return (nnz * b + B - 1) / B; };
+    auto ws_of = [&](int64_t b) { return make_layout(plan, (int32_t)b, nnz_of(b)).total; };
+    int64_t bs = B;
+    if (ws_bound_bytes) {
+        const size_t fixed = make_layout(plan, 1, 0).total;          // bitmap, rank samples, descriptors of an empty batch
+        if (ws_bound_bytes <= fixed) return 0;
+        const double r_instance = std::max(1.0, ((double)ws_of(B) - (double)fixed) / (double)B);
+        int64_t b = (int64_t)std::min<double>((double)B, (double)(ws_bound_bytes - fixed) / r_instance);
+        // the layout rounds its arrays up, so the ratio can be off by a few samples: settle on
+        // the largest size whose workspace really fits
+        while (b < B && ws_of(b + 1) <= ws_bound_bytes) ++b;
+        while (b > 0 && ws_of(b) > ws_bound_bytes) --b;
+        bs = std::min(bs, b);
+    }
+    if (act_bound_bytes) bs = std::min<int64_t>(bs, (int64_t)(act_bound_bytes / (size_t)(8 * std::max<int64_t>(plan->out_dim, 1))));
+    if (bs <= 0) return 0;
+    const int64_t M = (B + bs - 1) / bs;
+    return (int32_t)((B + M - 1) / M);
+}
+
 }  // extern "C"

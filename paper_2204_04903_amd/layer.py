@@ -101,6 +101,62 @@ class PackedEmbedding:
         return pk.pk_ctx_error(self.plan, self.ws)
 
 
+class MicroBatchPipeline:
+    """D-Interleaving of the layer (Sec. III-C): micro-batches pass through it one after the other, and the
+    dedup of the next one (integer work that reads no table) is enqueued on a second stream while the current
+    one is pooled and updated on the caller's stream.  Two workspaces, sized for a micro-batch, alternate.
+    Scheduling only: every step runs in the library's kernels.
+
+        t = pipe.submit(ids0, offsets0, B0)
+        for m in range(M):
+            nxt = pipe.submit(ids[m + 1], offsets[m + 1], B[m + 1]) if m + 1 < M else None
+            pipe.pool(t, out[m]); ...; pipe.backward_update(t, grad[m], lr, eps)
+            t = nxt
+
+    The tensors handed to `submit` must stay alive until the micro-batch has been updated."""
+
+    def __init__(self, layer: PackedEmbedding, max_B: int, max_nnz: int):
+        self.layer = layer
+        self.ws_bytes = pk.pk_workspace_bytes(layer.plan, max_B, max_nnz)
+        self.ws = [torch.empty(self.ws_bytes + 256, dtype=torch.uint8, device=layer.device) for _ in range(2)]
+        self.side = torch.cuda.Stream(device=layer.device)
+        self.ev_inputs = [torch.cuda.Event() for _ in range(2)]
+        self.ev_dedup = [torch.cuda.Event() for _ in range(2)]
+        self.count = 0
+
+    def submit(self, ids: torch.Tensor, offsets: torch.Tensor, B: int) -> dict:
+        """Enqueue the dedup of a micro-batch.  It starts once everything enqueued so far on the caller's
+        stream has run: the inputs are there, and the workspace's previous micro-batch has been updated."""
+        layer, slot = self.layer, self.count % 2
+        self.count += 1
+        nnz = int(ids.shape[0])
+        if pk.pk_workspace_bytes(layer.plan, B, nnz) > self.ws_bytes:
+            raise ValueError("micro-batch larger than the pipeline was sized for")
+        main = torch.cuda.current_stream(layer.device)
+        self.ev_inputs[slot].record(main)
+        self.side.wait_event(self.ev_inputs[slot])
+        pk.pk_forward_dedup(layer.plan, ids, offsets, B, nnz, self.ws[slot], self.ws_bytes, self.side.cuda_stream)
+        self.ev_dedup[slot].record(self.side)
+        return dict(slot=slot, B=B, nnz=nnz)
+
+    def pool(self, t: dict, out: torch.Tensor) -> torch.Tensor:
+        layer = self.layer
+        main = torch.cuda.current_stream(layer.device)
+        main.wait_event(self.ev_dedup[t["slot"]])
+        pk.pk_forward_pool(layer.plan, layer.W, t["B"], t["nnz"], out, out.stride(0), self.ws[t["slot"]],
+                           self.ws_bytes, main.cuda_stream)
+        return out
+
+    def backward_update(self, t: dict, grad_out: torch.Tensor, lr: float, eps: float) -> None:
+        layer = self.layer
+        main = torch.cuda.current_stream(layer.device)
+        pk.pk_backward_update(layer.plan, layer.W, layer.A, grad_out, grad_out.stride(0), t["B"], t["nnz"], lr, eps,
+                              self.ws[t["slot"]], self.ws_bytes, main.cuda_stream)
+
+    def ctx_error(self, t: dict) -> int:
+        return pk.pk_ctx_error(self.layer.plan, self.ws[t["slot"]])
+
+
 class HybridEmbedding(PackedEmbedding):
     """The layer with a Hot-storage in front of its tables (HybridHash): the tables and accumulators are the
     Cold-storage, in pinned host memory when `cold_on_host`, and the `hot_rows[p]` most queried rows of pack p

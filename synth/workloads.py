@@ -228,6 +228,27 @@ def make_batch(wl: Workload, index: int = 0) -> Batch:
     return make_batches(wl, 1, first=index)[0]
 
 
+def split_batch(batch: Batch, n_fields: int, B: int, n_micro: int) -> List[Batch]:
+    """The batch cut into `n_micro` micro-batches of consecutive samples, as even as they come
+    (sizes differ by one at most), each in the layer's field-major layout.  Data movement only."""
+    M = max(1, min(int(n_micro), B))
+    bounds = [(B * m) // M for m in range(M + 1)]
+    off = batch.offsets.astype(np.int64)
+    out = []
+    for m in range(M):
+        b0, b1 = bounds[m], bounds[m + 1]
+        parts, lens = [], []
+        for f in range(n_fields):
+            o = off[f * B + b0:f * B + b1 + 1]
+            parts.append(batch.ids[o[0]:o[-1]])
+            lens.append(np.diff(o))
+        offsets = np.zeros(n_fields * (b1 - b0) + 1, dtype=np.int64)
+        np.cumsum(np.concatenate(lens), out=offsets[1:])
+        out.append(Batch(np.ascontiguousarray(np.concatenate(parts)), offsets.astype(np.int32),
+                         np.ascontiguousarray(batch.grad_out[b0:b1])))
+    return out
+
+
 # ---------------------------------------------------------------------------
 # table values (host side; the device twin is in fill.hip)
 # ---------------------------------------------------------------------------

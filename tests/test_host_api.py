@@ -163,3 +163,63 @@ def test_hybrid_hash_calls_reject_bad_arguments_before_touching_the_gpu():
         assert pk.pk_hh_hot_count(plan, 0) == 0
     finally:
         pk.pk_plan_destroy(plan)
+
+
+def test_micro_batch_size_follows_eq2():
+    # Sec. III-C, Eq. 2 with the two resources the layer has: the activations (8 * out_dim bytes per sample,
+    # an exact ratio, compared with the oracle's Eq. 2) and the workspace (whose cost per sample comes from
+    # the layout: checked through what it must guarantee).
+    wl = synth.config(2)
+    plan = pk.pk_plan_create([(t.rows, t.dim, t.dtype) for t in wl.tables], [(f.table, f.pool) for f in wl.fields])
+    try:
+        B, nnz = wl.batch, wl.batch * wl.n_fields
+        out_dim = pk.pk_plan_out_dim(plan)
+        assert pk.pk_micro_batch_size(plan, B, nnz, 0, 0) == B
+        for bound in (8 * out_dim * 1000, 8 * out_dim * 1000 + 17, 8 * out_dim - 1, 10 ** 12):
+            assert pk.pk_micro_batch_size(plan, B, nnz, 0, bound) == orc.micro_batch_size(B, [bound], [8 * out_dim])
+        full = pk.pk_workspace_bytes(plan, B, nnz)
+        fixed = pk.pk_workspace_bytes(plan, 1, 0)
+        assert pk.pk_micro_batch_size(plan, B, nnz, full, 0) == B
+        assert pk.pk_micro_batch_size(plan, B, nnz, fixed, 0) == 0
+        for frac in (0.9, 0.6, 0.45, 0.38):
+            bound = int(full * frac)
+            bs = pk.pk_micro_batch_size(plan, B, nnz, bound, 0)
+            assert 0 < bs < B
+            assert pk.pk_workspace_bytes(plan, bs, -(-nnz * bs // B)) <= bound          # it fits
+            M = -(-B // bs)
+            assert bs == -(-B // M)                                                     # an even cut
+            if M > 1:                                                                   # and fewer micro-batches would not fit
+                bigger = -(-B // (M - 1))
+                assert pk.pk_workspace_bytes(plan, bigger, -(-nnz * bigger // B)) > bound
+            # both bounds: the smaller of the two sizes decides
+            both = pk.pk_micro_batch_size(plan, B, nnz, bound, 8 * out_dim * 100)
+            assert both == min(bs, orc.micro_batch_size(B, [8 * out_dim * 100], [8 * out_dim]))
+        with pytest.raises(pk.PkError):
+            pk.pk_micro_batch_size(plan, 0, nnz, 0, 0)
+        with pytest.raises(pk.PkError):
+            pk.pk_micro_batch_size(0, B, nnz, 0, 0)
+    finally:
+        pk.pk_plan_destroy(plan)
+
+
+def test_forward_stages_reject_bad_arguments_before_touching_the_gpu():
+    plan = pk.pk_plan_create([(100, 8, 0)], [(0, 0)])
+    try:
+        need = pk.pk_workspace_bytes(plan, 4, 4)
+        with pytest.raises(pk.PkError) as e:
+            pk.pk_forward_dedup(plan, 0x1000, 0, 4, 4, 0x1000, need, 0)          # offsets NULL
+        assert e.value.status == pk.PK_EINVAL
+        with pytest.raises(pk.PkError) as e:
+            pk.pk_forward_dedup(plan, 0x1000, 0x1000, 4, 4, 0x1000, need - 1, 0)   # workspace too small
+        assert e.value.status == pk.PK_EWORKSPACE
+        with pytest.raises(pk.PkError) as e:
+            pk.pk_forward_pool(plan, [0x1000], 4, 4, 0, 8, 0x1000, need, 0)      # out NULL
+        assert e.value.status == pk.PK_EINVAL
+        with pytest.raises(pk.PkError) as e:
+            pk.pk_forward_pool(plan, [0x1000], 4, 4, 0x1000, 7, 0x1000, need, 0) # row stride below out_dim
+        assert e.value.status == pk.PK_ESHAPE
+        with pytest.raises(pk.PkError) as e:
+            pk.pk_forward_pool(plan, [0], 4, 4, 0x1000, 8, 0x1000, need, 0)      # W[0] NULL
+        assert e.value.status == pk.PK_EINVAL
+    finally:
+        pk.pk_plan_destroy(plan)

@@ -137,6 +137,30 @@ def test_eq1_shard_split_rule_against_plain_python():
 
 
 # --------------------------------------------------------------------------- keys
+def test_eq2_micro_batch_size_hand_worked_and_brute_force():
+    # Sec. III-C, Eq. 2.  By hand: 1000 samples; one operator may use 10000 units at 30 per sample (333
+    # samples), another 8000 at 20 (400): the first one binds, 333 samples need 4 micro-batches, and an even
+    # cut makes them 250 each.
+    assert orc.micro_batch_size(1000, [10000, 8000], [30, 20]) == 250
+    assert orc.micro_batch_size(1000, [8000, 10000], [20, 30]) == 250          # the order of operators is irrelevant
+    assert orc.micro_batch_size(1000, [1e12], [1.0]) == 1000                   # nothing binds: the whole batch
+    assert orc.micro_batch_size(10, [5.0], [7.0]) == 0                         # not even one sample fits
+    assert orc.micro_batch_size(10, [7.0], [7.0]) == 1
+    # brute force: the largest size within every bound, then the fewest equal micro-batches of at most that size
+    rng = np.random.default_rng(5)
+    for _ in range(200):
+        B = int(rng.integers(1, 5000))
+        n = int(rng.integers(1, 4))
+        ri = rng.integers(1, 1000, size=n).astype(np.float64)
+        rb = rng.integers(1, 2_000_000, size=n).astype(np.float64)
+        fit = [b for b in range(1, B + 1) if all(b * ri[o] <= rb[o] for o in range(n))]
+        want = 0
+        if fit:
+            M = min(m for m in range(1, B + 1) if -(-B // m) <= fit[-1])
+            want = -(-B // M)
+        assert orc.micro_batch_size(B, rb, ri) == want
+
+
 def test_keys_match_python_bigint_arithmetic_on_wild_ids():
     pr = small_problem(3, B=9, wild_ids=True)
     pr["ids"][:4] = [-1, -2**63, 2**63 - 1, 0]
