@@ -853,8 +853,10 @@ __device__ __forceinline__ void rows_of(WT* W, float* A, const HotView& hv, uint
 // coalesced access.  The concatenation of the fields of a sample is the write
 // address.
 // ---------------------------------------------------------------------------
-// `block` of `nblocks` blocks of `nthreads` threads; HYB: rows may live in a Hot-storage
-template <typename WT, int VEC, int LPR, int NCH, bool HYB>
+// `block` of `nblocks` blocks of `nthreads` threads; HYB: rows may live in a Hot-storage;
+// DEEP: eight rows of a bag in flight instead of four (the kernel that shares the sort's
+// launch has no registers for that)
+template <typename WT, int VEC, int LPR, int NCH, bool HYB, bool DEEP>
 __device__ __forceinline__ void pool_body(const WT* __restrict__ W, const uint32_t* __restrict__ keys_all,
                                           const int32_t* __restrict__ po, const PackState* __restrict__ st,
                                           const FieldMeta* __restrict__ fmeta, const int32_t* __restrict__ slot_field,
@@ -877,6 +879,27 @@ __device__ __forceinline__ void pool_body(const WT* __restrict__ W, const uint32
 #pragma unroll
             for (int v = 0; v < VEC; ++v) acc[c][v] = 0.f;
         int q = q0;
+        if (DEEP) {                                        // eight rows in flight where the registers allow it
+            for (; q + 8 <= q1; q += 8) {
+                const WT* r[8];
+#pragma unroll
+                for (int k = 0; k < 8; ++k) r[k] = row_of<const WT, HYB>(W, hv, keys[q + k], D);
+#pragma unroll
+                for (int c = 0; c < NCH; ++c) {
+                    const int d0 = (c * LPR + li) * VEC;
+                    if (d0 < D) {
+                        float x[8][VEC];
+#pragma unroll
+                        for (int k = 0; k < 8; ++k) Row<WT, VEC>::load(r[k] + d0, x[k]);
+#pragma unroll
+                        for (int v = 0; v < VEC; ++v) {        // the order of additions of two rounds of four
+                            acc[c][v] += (x[0][v] + x[1][v]) + (x[2][v] + x[3][v]);
+                            acc[c][v] += (x[4][v] + x[5][v]) + (x[6][v] + x[7][v]);
+                        }
+                    }
+                }
+            }
+        }
         for (; q + 4 <= q1; q += 4) {
             const WT* r0 = row_of<const WT, HYB>(W, hv, keys[q], D);
             const WT* r1 = row_of<const WT, HYB>(W, hv, keys[q + 1], D);
@@ -930,7 +953,7 @@ pk_pool_kernel(const WT* __restrict__ W, const uint32_t* __restrict__ keys_all, 
                const int32_t* __restrict__ slot_field, int B, int D, int64_t n_bags,
                float* __restrict__ out, int64_t out_stride, const HotView hv)
 {
-    pool_body<WT, VEC, LPR, NCH, HYB>(W, keys_all, po, st, fmeta, slot_field, B, D, n_bags, out, out_stride,
+    pool_body<WT, VEC, LPR, NCH, HYB, true>(W, keys_all, po, st, fmeta, slot_field, B, D, n_bags, out, out_stride,
                                       blockIdx.x, gridDim.x, NT, hv);
 }
 
@@ -951,18 +974,18 @@ struct PoolJob {
 
 // variant = 12 * dtype + shape; the shapes in the order of the host's dispatch
 #define PK_POOL_SHAPES(WT, VECW, base)                                                          \
-    case base + 0:  pool_body<WT, VECW, 1, 1, false>(PK_POOL_ARGS); break;                             \
-    case base + 1:  pool_body<WT, VECW, 2, 1, false>(PK_POOL_ARGS); break;                             \
-    case base + 2:  pool_body<WT, VECW, 4, 1, false>(PK_POOL_ARGS); break;                             \
-    case base + 3:  pool_body<WT, VECW, 8, 1, false>(PK_POOL_ARGS); break;                             \
-    case base + 4:  pool_body<WT, VECW, 16, 1, false>(PK_POOL_ARGS); break;                            \
-    case base + 5:  pool_body<WT, VECW, 32, 1, false>(PK_POOL_ARGS); break;                            \
-    case base + 6:  pool_body<WT, VECW, 64, 1, false>(PK_POOL_ARGS); break;                            \
-    case base + 7:  pool_body<WT, 1, 4, 1, false>(PK_POOL_ARGS); break;                                \
-    case base + 8:  pool_body<WT, 1, 16, 1, false>(PK_POOL_ARGS); break;                               \
-    case base + 9:  pool_body<WT, 1, 64, 1, false>(PK_POOL_ARGS); break;                               \
-    case base + 10: pool_body<WT, 1, 64, 2, false>(PK_POOL_ARGS); break;                               \
-    case base + 11: pool_body<WT, 1, 64, 4, false>(PK_POOL_ARGS); break;
+    case base + 0:  pool_body<WT, VECW, 1, 1, false, false>(PK_POOL_ARGS); break;                       \
+    case base + 1:  pool_body<WT, VECW, 2, 1, false, false>(PK_POOL_ARGS); break;                       \
+    case base + 2:  pool_body<WT, VECW, 4, 1, false, false>(PK_POOL_ARGS); break;                       \
+    case base + 3:  pool_body<WT, VECW, 8, 1, false, false>(PK_POOL_ARGS); break;                       \
+    case base + 4:  pool_body<WT, VECW, 16, 1, false, false>(PK_POOL_ARGS); break;                      \
+    case base + 5:  pool_body<WT, VECW, 32, 1, false, false>(PK_POOL_ARGS); break;                      \
+    case base + 6:  pool_body<WT, VECW, 64, 1, false, false>(PK_POOL_ARGS); break;                      \
+    case base + 7:  pool_body<WT, 1, 4, 1, false, false>(PK_POOL_ARGS); break;                          \
+    case base + 8:  pool_body<WT, 1, 16, 1, false, false>(PK_POOL_ARGS); break;                         \
+    case base + 9:  pool_body<WT, 1, 64, 1, false, false>(PK_POOL_ARGS); break;                         \
+    case base + 10: pool_body<WT, 1, 64, 2, false, false>(PK_POOL_ARGS); break;                         \
+    case base + 11: pool_body<WT, 1, 64, 4, false, false>(PK_POOL_ARGS); break;
 #define PK_POOL_ARGS                                                                            \
     static_cast<const WT_*>(k.W), pj.keys, k.po, pj.st + k.pad, pj.fmeta, k.slot_field, pj.B, k.D, k.n_bags, pj.out,  \
         pj.out_stride, local, n_local, kSortThreads, HotView{nullptr, nullptr, nullptr}
