@@ -122,7 +122,11 @@ size_t    pk_workspace_bytes(const pk_plan* plan, int32_t B, int64_t nnz);
  *           from pk_forward to the pk_backward_update that follows.
  * hip_stream: hipStream_t (NULL = default stream).
  * Offsets that violate the contract set a device error word (pk_ctx_error);
- * results are then undefined but all kernels still terminate. */
+ * results are then undefined but all kernels still terminate.
+ * Calls on one device are meant to follow one another (one stream, or streams
+ * ordered by events as for the two stages below): the dedup kernels of two
+ * calls running side by side can wait for each other's places on the chip
+ * until their bounded waits give up, which raises the error word. */
 pk_status pk_forward(const pk_plan* plan, void* const* W,
                      const int64_t* ids, const int32_t* offsets, int32_t B, int64_t nnz,
                      float* out, int64_t out_row_stride,
@@ -134,7 +138,9 @@ pk_status pk_forward(const pk_plan* plan, void* const* W,
  * workspace):
  *   g = sum over its occurrences of grad_out[b, col(f) .. col(f)+dim) * (1/L for mean)
  *   A[row] += g*g ;  W[row] -= lr * g / (sqrt(A[row]) + eps)
- * Rows of keys that do not occur are neither read nor written.
+ * Rows of keys that do not occur are neither read nor written.  If that
+ * pk_forward raised the device error word (pk_ctx_error), nothing is read or
+ * written: W and A stay as they are.
  * A:        host array of n_packs DEVICE pointers, fp32 [total_rows, dim].
  * grad_out: device, fp32 [B, grad_row_stride]. */
 pk_status pk_backward_update(const pk_plan* plan, void* const* W, float* const* A,

@@ -95,9 +95,14 @@ __device__ __forceinline__ int upper_bound_i32(P a, int n, int x)
 // ---------------------------------------------------------------------------
 // single-pass multi-block prefix sums: every tile publishes a 64-bit
 // descriptor (state | value b | value a) and sums the descriptors of the tiles
-// before it.  Tiles are handed out by an atomic ticket, so a tile only ever
-// waits for tiles that are already running: the wait always ends.  The wait is
-// bounded all the same; running out of patience sets error bit 1.
+// before it.  A block takes tiles b, b + G, ...; a tile of a later round waits
+// for tiles of the round before, of every block, so the wait ends when all G
+// blocks are resident together: the launches keep G below what the chip holds
+// of that kernel alone.  (Two such kernels side by side on one GPU can hold
+// each other's places; calls of this library on one device are meant to follow
+// one another.)  The wait is bounded all the same: running out of patience sets
+// bit 1 of the error word, the kernels after it skip their work and the tables
+// stay as they are.
 // ---------------------------------------------------------------------------
 constexpr uint64_t kDescAgg = 1, kDescPfx = 2;
 constexpr int kSpinLimit = 1 << 22;
@@ -1166,9 +1171,10 @@ pk_adagrad_kernel(WT* W, float* A, const PackState* __restrict__ st, int p,
     const int wv = threadIdx.x >> 6, gw = (threadIdx.x & 63) / LPR;
     // A plan with one pack has all occurrences in it, so the host knows the sizes and the first
     // tile header can be requested without waiting for the pack's state; the state is still
-    // checked (it says 0 occurrences when the forward pass rejected its input).
+    // checked.  A forward pass that raised the error word (input rejected, or a scan that ran
+    // out of patience) left no lists worth reading: the tables are then left alone.
     const int n = n_host >= 0 ? n_host : st->nnz, start = n_host >= 0 ? 0 : st->start;
-    const bool state_ok = n_host < 0 || st->nnz == n_host;
+    const bool state_ok = (n_host < 0 || st->nnz == n_host) && (st - p)->error == 0;
     const int32_t* seg = seg_all + start + p;
     const uint32_t* uq = unique_all + start;
     const size_t tbase = (size_t)(start / tp + p);
@@ -1331,6 +1337,7 @@ pk_adagrad_hot_kernel(HotPacks ptrs, int p0, const PackMeta* __restrict__ pm, co
 {
     const int p = p0 + blockIdx.y;
     const PackMeta k = pm[p];
+    if (st[0].error) return;                               // as in pk_adagrad_kernel
     const int n = st[p].nnz, start = st[p].start, D = k.dim;
     const int32_t* seg = seg_all + start + p;
     const size_t tbase = (size_t)(start / tp + p);

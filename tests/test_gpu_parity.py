@@ -216,6 +216,12 @@ def test_bad_offsets_raise_the_error_word_and_terminate():
         torch.cuda.synchronize()
         assert layer.error_word() & 1
         assert (out.cpu().numpy() == 0).all()
+        # a backward pass after a rejected forward pass leaves the table and the accumulator alone
+        say("[bad offsets] backward after the rejected forward")
+        layer.backward_update(torch.from_numpy(pr["grad"]).cuda(), 0.05, 1e-8)
+        torch.cuda.synchronize()
+        assert np.array_equal(bits_of(layer.W[0]), stack_tables(orc.plan(tables, fields), [pr["Wt"][0]])[0])
+        assert (layer.A[0] == 0).all()
         # and the same workspace works again afterwards
         out = layer.forward(torch.from_numpy(pr["ids"]).cuda(), torch.from_numpy(pr["offsets"]).cuda(), 8)
         torch.cuda.synchronize()
