@@ -361,56 +361,75 @@ pk_mark_kernel(const MarkItem* __restrict__ items, const int32_t* __restrict__ i
 // the number of set bits before it.  One pass: popcount per 256-bit block,
 // prefix over all blocks of the pack, rank samples, distinct keys written out.
 // ---------------------------------------------------------------------------
-__global__ void __launch_bounds__(NT)
-pk_tiles_kernel(const uint4* __restrict__ bitmap4, uint64_t* tile_desc, int n_tiles_total,
+// A block iteration scans a run of K tiles of one pack (K * kTileWords bitmap words, every
+// thread K consecutive 256-bit blocks): with several thousand tiles, fewer and larger steps
+// keep the chain of prefixes short.
+template <int K>
+__global__ void __launch_bounds__(NT, 4)   // four blocks per CU must fit: 1024 blocks resident at once
+pk_tiles_kernel(const uint4* __restrict__ bitmap4, uint64_t* tile_desc, int n_runs_total,
                 const PackMeta* __restrict__ pm, PackState* st, int P,
                 int32_t* __restrict__ rank, uint32_t* __restrict__ unique)
 {
     __shared__ uint32_t s_pre;
-    // Block b takes tiles b, b+G, b+2G, ...: a tile only waits for lower tiles, which
-    // belong to earlier rounds or to lower blocks of this round; the launch keeps G
-    // small enough for all blocks to be resident, so the waits end.
-    int p = 0;
-    for (int tile = blockIdx.x; tile < n_tiles_total; tile += gridDim.x) {
-        while (p + 1 < P && tile >= pm[p + 1].first_tile) ++p;
-        const int first = pm[p].first_tile;
-        const size_t t = (size_t)tile * NT + threadIdx.x;
-        const uint4 a = bitmap4[2 * t], b = bitmap4[2 * t + 1];
-        const uint32_t w[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
-        int c = 0;
+    // Block b takes runs b, b+G, b+2G, ...: a run waits for the runs before it, those of
+    // other blocks' earlier rounds included; the launch keeps G small enough for all blocks
+    // to be resident, so the waits end.
+    int p = 0, first = 0;                                  // the pack of the run, the pack's first run
+    for (int run = blockIdx.x; run < n_runs_total; run += gridDim.x) {
+        while (p + 1 < P && run >= first + (pm[p].n_tiles + K - 1) / K) {
+            first += (pm[p].n_tiles + K - 1) / K;
+            ++p;
+        }
+        const int n_blocks = pm[p].n_tiles * NT;           // 256-bit blocks of the pack
+        const int b0 = ((run - first) * NT + (int)threadIdx.x) * K;   // this thread's first one
+        const size_t t0 = (size_t)pm[p].first_tile * NT + b0;
+        uint32_t w[K][8];
+        int c[K], mine = 0;
 #pragma unroll
-        for (int i = 0; i < 8; ++i) c += __popc(w[i]);
+        for (int k = 0; k < K; ++k) {
+            uint4 a = make_uint4(0, 0, 0, 0), b = a;
+            if (b0 + k < n_blocks) { a = bitmap4[2 * (t0 + k)]; b = bitmap4[2 * (t0 + k) + 1]; }
+            w[k][0] = a.x; w[k][1] = a.y; w[k][2] = a.z; w[k][3] = a.w;
+            w[k][4] = b.x; w[k][5] = b.y; w[k][6] = b.z; w[k][7] = b.w;
+            c[k] = 0;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) c[k] += __popc(w[k][i]);
+            mine += c[k];
+        }
         int tot;
-        const int ex = block_excl_scan<NT>(c, &tot);      // its barriers also fence s_pre between rounds
+        const int ex = block_excl_scan<NT>(mine, &tot);    // its barriers also fence s_pre between rounds
         if (threadIdx.x < 64) {
-            if (tile == first) {
-                if (threadIdx.x == 0) { publish_desc(tile_desc + tile, make_desc(kDescPfx, (uint32_t)tot, 0)); s_pre = 0; }
+            if (run == first) {
+                if (threadIdx.x == 0) { publish_desc(tile_desc + run, make_desc(kDescPfx, (uint32_t)tot, 0)); s_pre = 0; }
             } else {
-                if (threadIdx.x == 0) publish_desc(tile_desc + tile, make_desc(kDescAgg, (uint32_t)tot, 0));
+                if (threadIdx.x == 0) publish_desc(tile_desc + run, make_desc(kDescAgg, (uint32_t)tot, 0));
                 uint32_t pa, pb;
-                lookback(tile_desc, first, tile, &pa, &pb, &st[0].error);
+                lookback(tile_desc, first, run, &pa, &pb, &st[0].error);
                 if (threadIdx.x == 0) {
-                    publish_desc(tile_desc + tile, make_desc(kDescPfx, pa + (uint32_t)tot, 0));
+                    publish_desc(tile_desc + run, make_desc(kDescPfx, pa + (uint32_t)tot, 0));
                     s_pre = pa;
                 }
             }
         }
         __syncthreads();
         int pre = (int)s_pre + ex;
-        rank[t] = pre;
-        if (tile == first + pm[p].n_tiles - 1 && threadIdx.x == NT - 1) st[p].n_unique = pre + c;
-        if (c != 0) {
-            const int start = st[p].start;
-            uint32_t* uq = unique + start;
-            const uint32_t key0 = ((uint32_t)(tile - first) * NT + threadIdx.x) * 256u;
+        if (run == first + (pm[p].n_tiles + K - 1) / K - 1 && threadIdx.x == 0) st[p].n_unique = (int)s_pre + tot;
+        uint32_t* uq = unique + st[p].start;
 #pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                uint32_t x = w[i];
-                while (x) {
-                    const int bit = __ffs(x) - 1;
-                    x &= x - 1;
-                    uq[pre] = key0 + i * 32 + bit;
-                    ++pre;
+        for (int k = 0; k < K; ++k) {
+            if (b0 + k >= n_blocks) break;
+            rank[t0 + k] = pre;
+            if (c[k] != 0) {
+                const uint32_t key0 = (uint32_t)(b0 + k) * 256u;
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    uint32_t x = w[k][i];
+                    while (x) {
+                        const int bit = __ffs(x) - 1;
+                        x &= x - 1;
+                        uq[pre] = key0 + i * 32 + bit;
+                        ++pre;
+                    }
                 }
             }
         }
@@ -1969,8 +1988,18 @@ static pk_status forward_impl(const pk_plan* plan, int stages, const char* who, 
     }
     PK_LAUNCH("pk_mark", pk_mark_kernel, dim3((unsigned)plan->mark_items.size()), dim3(kMarkThreads), 0, ds->mark_items,
               ds->mark_fields, ds->pmeta, st, fb, delta, keys, bitmap, nnz);
-    PK_LAUNCH("pk_tiles", pk_tiles_kernel, dim3(blocks_for(n_tiles, 1, 1024)), dim3(NT), 0,
-              reinterpret_cast<const uint4*>(bitmap), tile_desc, (int)n_tiles, ds->pmeta, st, P, rank, unique);
+    // a grid that the chip holds at once (the scan's waits need that); with more tiles than that,
+    // runs of four tiles per block iteration
+    constexpr int kTilesGrid = 1024, kTileRun = 4;
+    if (n_tiles <= kTilesGrid) {
+        PK_LAUNCH("pk_tiles", pk_tiles_kernel<1>, dim3(blocks_for(n_tiles, 1, kTilesGrid)), dim3(NT), 0,
+                  reinterpret_cast<const uint4*>(bitmap), tile_desc, (int)n_tiles, ds->pmeta, st, P, rank, unique);
+    } else {
+        int64_t n_runs = 0;
+        for (const Pack& k : plan->packs) n_runs += (k.n_tiles + kTileRun - 1) / kTileRun;
+        PK_LAUNCH("pk_tiles", pk_tiles_kernel<kTileRun>, dim3(blocks_for(n_runs, 1, kTilesGrid)), dim3(NT), 0,
+                  reinterpret_cast<const uint4*>(bitmap), tile_desc, (int)n_runs, ds->pmeta, st, P, rank, unique);
+    }
     const int kt = nnz < (1 << 20) ? 256 : 1024;      // occurrences per tile of the inverse kernel
     const unsigned xq = (blocks_for(nnz, kt, 256 * 16) + 7u) & ~7u;
     if (kt == 256)
