@@ -320,7 +320,7 @@ pk_mark_kernel(const MarkItem* __restrict__ items, const int32_t* __restrict__ i
 {
     __shared__ uint32_t s_bits[kMarkWords];
     const MarkItem it = items[blockIdx.x];
-    for (int w = threadIdx.x; w < kMarkWords; w += kMarkThreads) s_bits[w] = 0;
+    for (int w = threadIdx.x; w < it.n_words; w += kMarkThreads) s_bits[w] = 0;
     __syncthreads();
     const uint32_t span = (uint32_t)it.n_words * 32u;
     if (!st[0].error) {

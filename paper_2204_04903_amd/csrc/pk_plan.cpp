@@ -214,17 +214,29 @@ pk_status pk_plan_create(const pk_table_desc* tables, int32_t n_tables, const pk
             if (tm.field_end > tm.field_begin) pl->sort_tables.push_back(tm);
         }
     }
-    // slices of every pack's key space for the mark kernel
+    // Slices of every pack's key space for the mark kernel.  A block scans all keys of the
+    // fields whose tables overlap its slice, so a slice ends where a table ends (at the
+    // 128-key boundary below it: slices are copied out in 16-byte pieces): a slice then overlaps
+    // one table and at most a sliver of the one before, and blocks have comparable work
+    // however small the tables are.  Large tables are cut every kMarkWords words.
     for (size_t p = 0; p < pl->packs.size(); ++p) {
         const Pack& k = pl->packs[p];
         const int64_t words = (int64_t)k.n_tiles * kTileWords;
-        for (int64_t w0 = 0; w0 < words; w0 += kMarkWords) {
+        size_t next_table = 0;                                 // first table of the pack that ends above `lo`
+        for (int64_t w0 = 0; w0 < words;) {
+            const int64_t lo = w0 * 32;
+            int64_t hi = std::min<int64_t>(lo + (int64_t)kMarkWords * 32, words * 32);
+            for (; next_table < k.tables.size(); ++next_table) {
+                const int32_t t = k.tables[next_table];
+                const int64_t cut = (pl->table_base[t] + tables[t].rows) / 128 * 128;
+                if (cut > lo) { hi = std::min(hi, cut); break; }
+            }
             MarkItem it{};
             it.pack = (int32_t)p;
-            it.key_lo = (uint32_t)(w0 * 32);
-            it.n_words = (int32_t)std::min<int64_t>(kMarkWords, words - w0);
+            it.key_lo = (uint32_t)lo;
+            it.n_words = (int32_t)((hi - lo) / 32);
+            w0 += it.n_words;
             it.field_begin = (int32_t)pl->mark_fields.size();
-            const int64_t lo = w0 * 32, hi = lo + (int64_t)it.n_words * 32;
             for (int32_t f : k.fields) {
                 const int32_t t = fields[f].table;
                 const int64_t t_lo = pl->table_base[t], t_hi = t_lo + tables[t].rows;
