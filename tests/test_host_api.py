@@ -223,3 +223,25 @@ def test_forward_stages_reject_bad_arguments_before_touching_the_gpu():
         assert e.value.status == pk.PK_EINVAL
     finally:
         pk.pk_plan_destroy(plan)
+
+
+def test_split_batch_keeps_every_bag_and_gradient_row():
+    # the micro-batches of D-Interleaving are a re-layout of the batch: every bag of every field, and every
+    # sample's gradient row, turns up once, in sample order
+    wl = synth.config(3, batch=37, row_scale=0.01, n_fields=5)
+    b = synth.make_batch(wl, 0)
+    for n_micro in (1, 4, 37, 100):
+        parts = synth.split_batch(b, wl.n_fields, wl.batch, n_micro)
+        sizes = [p.grad_out.shape[0] for p in parts]
+        assert sum(sizes) == wl.batch and max(sizes) - min(sizes) <= 1 and min(sizes) >= 1
+        assert sum(p.nnz for p in parts) == b.nnz
+        assert np.array_equal(np.concatenate([p.grad_out for p in parts]), b.grad_out)
+        first = 0
+        for p in parts:
+            Bm = p.grad_out.shape[0]
+            assert p.offsets[0] == 0 and p.offsets[-1] == p.nnz and len(p.offsets) == wl.n_fields * Bm + 1
+            for f in range(wl.n_fields):
+                for s in range(Bm):
+                    g, G = f * Bm + s, f * wl.batch + first + s
+                    assert np.array_equal(p.ids[p.offsets[g]:p.offsets[g + 1]], b.ids[b.offsets[G]:b.offsets[G + 1]])
+            first += Bm
