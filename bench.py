@@ -30,6 +30,7 @@ def algorithmic_bytes(info, mean_pack):
         "pk_keys": 8 * n + 4 * n + 4 * n + sc_occ(n, mean_pack) + 4 * bags + 4 * bags,
         "pk_pool": 4 * n + 4 * (bags + 1) + sw * D * U + 4 * D * bags,
         "pk_mark": 4 * n + bm,
+        "pk_keys_mark": 8 * n + 4 * n + 4 * n + sc_occ(n, mean_pack) + 4 * bags + 4 * bags + 8 * n + bm,
         "pk_tiles": bm + bm // 8 + 4 * U,
         "pk_inverse": 8 * n + min(bm + bm // 8, 36 * n),
         "pk_sort": 2 * (4 * n) + 4 * n + 2 * sc_occ(n, mean_pack) + 4 * n + 4 * U,

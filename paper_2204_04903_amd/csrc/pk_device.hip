@@ -189,39 +189,60 @@ struct XcdTiles {
 // also stores it for the later kernels.  All blocks share the clearing of the
 // scan descriptors.
 // ---------------------------------------------------------------------------
+struct KeysArgs {
+    const int64_t* ids; const int32_t* offsets; int B, F, P; int64_t nnz;
+    const FieldMeta* fmeta; const PackMeta* pm; const int32_t* slot_field; PackState* st;
+    int32_t* fb_out; int32_t* delta_out;
+    uint32_t* keys; uint32_t* bagref; uint32_t* baglen; int32_t* packed_offsets;
+    int64_t out_dim; uint4* clear4; int64_t n_clear4;
+};
+
+// LDS words of keys_body: per bag (a flag, the offsets of BT bags and five values per bag) and
+// per field (the scan of the field boundaries)
 template <int BT>
-__global__ void __launch_bounds__(NT)
-pk_keys_kernel(const int64_t* __restrict__ ids, const int32_t* __restrict__ offsets, int B, int F, int P, int64_t nnz,
-               const FieldMeta* __restrict__ fmeta, const PackMeta* __restrict__ pm,
-               const int32_t* __restrict__ slot_field, PackState* st, int32_t* fb_out, int32_t* delta_out,
-               uint32_t* __restrict__ keys, uint32_t* __restrict__ bagref, uint32_t* __restrict__ baglen,
-               int32_t* __restrict__ packed_offsets, int64_t out_dim, uint4* clear4, int64_t n_clear4)
+constexpr int keys_bag_words() { return 1 + (BT + 1) + 5 * BT; }
+constexpr size_t keys_field_words(int F) { return (size_t)(3 * F + 2); }
+
+// `block` of `nblocks` blocks of NTH threads.  (The arrays come as restrict-qualified parameters
+// of their own: the compiler orders the loads and stores of the inner loop far better when it
+// knows that they do not overlap.)
+template <int BT, int NTH>
+__device__ __forceinline__ void keys_core(const int64_t* __restrict__ ids, const int32_t* __restrict__ offsets,
+                                          const FieldMeta* __restrict__ fmeta, const PackMeta* __restrict__ pm,
+                                          const int32_t* __restrict__ slot_field, uint32_t* __restrict__ keys,
+                                          uint32_t* __restrict__ bagref, uint32_t* __restrict__ baglen,
+                                          int32_t* __restrict__ packed_offsets, const KeysArgs& a, int block,
+                                          int nblocks, int32_t* lds_bag, int32_t* lds_field)
 {
-    extern __shared__ int32_t s_dyn[];
-    int32_t* s_fb = s_dyn;                    // [F+1] field boundaries in ids
-    int32_t* s_delta = s_dyn + (F + 1);       // [F]   packed position minus position in ids
+    const int B = a.B, F = a.F, P = a.P;
+    const int64_t nnz = a.nnz;
+    const int64_t out_dim = a.out_dim;
+    int32_t* s_po = lds_bag;                  // [BT+1] offsets of the tile's bags
+    uint32_t* s_base = reinterpret_cast<uint32_t*>(s_po + (BT + 1));   // [BT] each
+    uint32_t* s_rows = s_base + BT;
+    uint32_t* s_ref = s_rows + BT;
+    int32_t* s_dl = reinterpret_cast<int32_t*>(s_ref + BT);
+    uint32_t* s_len = reinterpret_cast<uint32_t*>(s_dl + BT);
+    int32_t* s_badp = reinterpret_cast<int32_t*>(s_len + BT);
+    int32_t* s_fb = lds_field;                // [F+1] field boundaries in ids
+    int32_t* s_delta = s_fb + (F + 1);        // [F]   packed position minus position in ids
     int32_t* s_slotpos = s_delta + F;         // [F+1] packed position of each (pack, slot)
-    __shared__ int s_bad;
-    __shared__ int32_t s_po[BT + 1];
-    __shared__ uint32_t s_base[BT], s_rows[BT], s_ref[BT];
-    __shared__ int32_t s_dl[BT];
-    __shared__ uint32_t s_len[BT];
     const int tid = threadIdx.x;
     {
         const uint4 z = make_uint4(0, 0, 0, 0);
-        const int64_t stride = (int64_t)gridDim.x * NT;
-        for (int64_t i = (int64_t)blockIdx.x * NT + tid; i < n_clear4; i += stride) clear4[i] = z;
+        const int64_t stride = (int64_t)nblocks * NTH;
+        for (int64_t i = (int64_t)block * NTH + tid; i < a.n_clear4; i += stride) a.clear4[i] = z;
     }
-    if (tid == 0) s_bad = 0;
-    for (int f = tid; f <= F; f += NT) s_fb[f] = offsets[(int64_t)f * B];
+    if (tid == 0) *s_badp = 0;
+    for (int f = tid; f <= F; f += NTH) s_fb[f] = offsets[(int64_t)f * B];
     __syncthreads();
-    for (int f = tid; f < F; f += NT)
-        if (s_fb[f + 1] < s_fb[f]) s_bad = 1;
-    if (tid == 0 && (s_fb[0] != 0 || (int64_t)s_fb[F] != nnz)) s_bad = 1;
+    for (int f = tid; f < F; f += NTH)
+        if (s_fb[f + 1] < s_fb[f]) *s_badp = 1;
+    if (tid == 0 && (s_fb[0] != 0 || (int64_t)s_fb[F] != nnz)) *s_badp = 1;
     __syncthreads();
-    const int bad = s_bad;
+    const int bad = *s_badp;
     int carry = 0;
-    for (int base = 0; base < F; base += NT) {
+    for (int base = 0; base < F; base += NTH) {
         const int i = base + tid;
         int len = 0, f = 0;
         if (i < F) {
@@ -229,7 +250,7 @@ pk_keys_kernel(const int64_t* __restrict__ ids, const int32_t* __restrict__ offs
             len = bad ? 0 : s_fb[f + 1] - s_fb[f];
         }
         int tot;
-        const int ex = block_excl_scan<NT>(len, &tot);
+        const int ex = block_excl_scan<NTH>(len, &tot);
         if (i < F) {
             s_slotpos[i] = carry + ex;
             s_delta[f] = carry + ex - s_fb[f];
@@ -238,30 +259,30 @@ pk_keys_kernel(const int64_t* __restrict__ ids, const int32_t* __restrict__ offs
     }
     if (tid == 0) s_slotpos[F] = carry;
     __syncthreads();
-    if (blockIdx.x == 0) {
-        for (int f = tid; f <= F; f += NT) fb_out[f] = s_fb[f];
-        for (int f = tid; f < F; f += NT) delta_out[f] = s_delta[f];
-        for (int p = tid; p < P; p += NT) {
+    if (block == 0) {
+        for (int f = tid; f <= F; f += NTH) a.fb_out[f] = s_fb[f];
+        for (int f = tid; f < F; f += NTH) a.delta_out[f] = s_delta[f];
+        for (int p = tid; p < P; p += NTH) {
             const PackMeta k = pm[p];
             const int start = s_slotpos[k.first_slot];
             PackState s;
             s.nnz = s_slotpos[k.first_slot + k.n_fields] - start;
             s.start = start; s.n_unique = 0; s.error = (p == 0) ? bad : 0;
             s.pad[0] = s.pad[1] = s.pad[2] = s.pad[3] = 0;
-            st[p] = s;
+            a.st[p] = s;
             packed_offsets[(int64_t)k.first_slot * B + p + (int64_t)k.n_fields * B] = s.nnz;
         }
     }
     if (bad) return;
     const int64_t n_bags = (int64_t)F * B;
     const int64_t n_tiles = (n_bags + BT - 1) / BT;
-    for (int64_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+    for (int64_t tile = block; tile < n_tiles; tile += nblocks) {
         const int64_t g0 = tile * BT;
         const int nb = (int)min((int64_t)BT, n_bags - g0);
         __syncthreads();                               // the previous tile's LDS is consumed
-        for (int t = tid; t <= nb; t += NT) s_po[t] = (int32_t)min((int64_t)max(offsets[g0 + t], 0), nnz);
+        for (int t = tid; t <= nb; t += NTH) s_po[t] = (int32_t)min((int64_t)max(offsets[g0 + t], 0), nnz);
         __syncthreads();
-        for (int t = tid; t < nb; t += NT) {
+        for (int t = tid; t < nb; t += NTH) {
             const int64_t g = g0 + t;
             const int f = (int)(g / B);
             const int b = (int)(g - (int64_t)f * B);
@@ -278,16 +299,16 @@ pk_keys_kernel(const int64_t* __restrict__ ids, const int32_t* __restrict__ offs
         }
         __syncthreads();
         const int q_lo = s_po[0], q_hi = s_po[nb];
-        for (int i0 = q_lo + tid; i0 < q_hi; i0 += 4 * NT) {
+        for (int i0 = q_lo + tid; i0 < q_hi; i0 += 4 * NTH) {
             int64_t idv[4];
 #pragma unroll
             for (int k = 0; k < 4; ++k) {              // the loads of four rounds in flight together
-                const int i = i0 + k * NT;
+                const int i = i0 + k * NTH;
                 idv[k] = i < q_hi ? ids[i] : 0;
             }
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
-                const int i = i0 + k * NT;
+                const int i = i0 + k * NTH;
                 if (i >= q_hi) continue;
                 const int t = upper_bound_i32(s_po, nb + 1, i) - 1;
                 if ((unsigned)t >= (unsigned)nb) continue;
@@ -301,6 +322,22 @@ pk_keys_kernel(const int64_t* __restrict__ ids, const int32_t* __restrict__ offs
     }
 }
 
+template <int BT>
+__global__ void __launch_bounds__(NT)
+pk_keys_kernel(const int64_t* __restrict__ ids, const int32_t* __restrict__ offsets, int B, int F, int P, int64_t nnz,
+               const FieldMeta* __restrict__ fmeta, const PackMeta* __restrict__ pm,
+               const int32_t* __restrict__ slot_field, PackState* st, int32_t* fb_out, int32_t* delta_out,
+               uint32_t* __restrict__ keys, uint32_t* __restrict__ bagref, uint32_t* __restrict__ baglen,
+               int32_t* __restrict__ packed_offsets, int64_t out_dim, uint4* clear4, int64_t n_clear4)
+{
+    extern __shared__ int32_t s_dyn[];                     // keys_field_words(F)
+    __shared__ int32_t s_bag[keys_bag_words<BT>()];
+    const KeysArgs a{ids, offsets, B, F, P, nnz, fmeta, pm, slot_field, st, fb_out, delta_out, keys, bagref, baglen,
+                     packed_offsets, out_dim, clear4, n_clear4};
+    keys_core<BT, NT>(ids, offsets, fmeta, pm, slot_field, keys, bagref, baglen, packed_offsets, a, blockIdx.x,
+                      gridDim.x, s_bag, s_dyn);
+}
+
 // ---------------------------------------------------------------------------
 // H2, first half: which rows occur.  Global atomics run at a fixed, low rate on
 // this GPU whatever their address, so the bitmap is not built with them: a block
@@ -312,47 +349,109 @@ pk_keys_kernel(const int64_t* __restrict__ ids, const int32_t* __restrict__ offs
 constexpr int kMarkThreads = 1024;
 constexpr int kMarkUnroll = 8;
 
-__global__ void __launch_bounds__(kMarkThreads)
-pk_mark_kernel(const MarkItem* __restrict__ items, const int32_t* __restrict__ item_fields,
-               const PackMeta* __restrict__ pm, const PackState* __restrict__ st,
-               const int32_t* __restrict__ fb, const int32_t* __restrict__ delta,
-               const uint32_t* __restrict__ keys, uint32_t* __restrict__ bitmap, int64_t nnz)
+struct MarkArgs {
+    const MarkItem* items; const int32_t* item_fields; const PackMeta* pm; const PackState* st;
+    const int32_t* fb; const int32_t* delta; const uint32_t* keys; uint32_t* bitmap; int64_t nnz;
+};
+
+// set bit k of the slice if it is inside (one LDS read where the bit is already there)
+__device__ __forceinline__ void mark_bit(uint32_t* s_bits, uint32_t k, uint32_t span)
 {
-    __shared__ uint32_t s_bits[kMarkWords];
-    const MarkItem it = items[blockIdx.x];
+    if (k < span) {
+        const uint32_t bit = 1u << (k & 31);
+        if (!(s_bits[k >> 5] & bit)) atomicOr(&s_bits[k >> 5], bit);
+    }
+}
+
+// One slice.  FROM_IDS: the keys are formed here from the IDs of the fields (the same hash
+// as in keys_body), so that this does not have to wait for the keys kernel and can share
+// its launch; `ka` is then that kernel's argument block.
+template <bool FROM_IDS>
+__device__ __forceinline__ void mark_body(const MarkArgs& ma, const KeysArgs& ka, int item, uint32_t* s_bits)
+{
+    int mine = 0;
+    if (FROM_IDS) {                                        // the checks of keys_body, which runs beside this
+        for (int f = threadIdx.x; f < ka.F; f += kMarkThreads)
+            mine |= ka.offsets[(int64_t)(f + 1) * ka.B] < ka.offsets[(int64_t)f * ka.B];
+        if (threadIdx.x == 0) mine |= ka.offsets[0] != 0 || (int64_t)ka.offsets[(int64_t)ka.F * ka.B] != ka.nnz;
+    }
+    const MarkItem it = ma.items[item];
     for (int w = threadIdx.x; w < it.n_words; w += kMarkThreads) s_bits[w] = 0;
-    __syncthreads();
     const uint32_t span = (uint32_t)it.n_words * 32u;
-    if (!st[0].error) {
+    int bad;
+    if (FROM_IDS) {
+        bad = __syncthreads_or(mine);
+    } else {
+        __syncthreads();
+        bad = ma.st[0].error;
+    }
+    if (!bad) {
         for (int fi = it.field_begin; fi < it.field_end; ++fi) {
-            const int f = item_fields[fi];
-            const int64_t q0 = (int64_t)fb[f] + delta[f], q1 = (int64_t)fb[f + 1] + delta[f];
-            if (q0 < 0 || q1 > nnz) continue;
-            int64_t q = q0 + threadIdx.x;
-            for (; q + (kMarkUnroll - 1) * kMarkThreads < q1; q += kMarkUnroll * kMarkThreads) {
-                uint32_t k[kMarkUnroll];
+            const int f = ma.item_fields[fi];
+            if (FROM_IDS) {
+                const FieldMeta m = ka.fmeta[f];
+                const int64_t q0 = ka.offsets[(int64_t)f * ka.B], q1 = ka.offsets[(int64_t)(f + 1) * ka.B];
+                const uint32_t base = m.base_row - it.key_lo;      // modulo 2^32, like the subtraction below
+                int64_t q = q0 + threadIdx.x;
+                for (; q + (kMarkUnroll - 1) * kMarkThreads < q1; q += kMarkUnroll * kMarkThreads) {
+                    int64_t id[kMarkUnroll];
 #pragma unroll
-                for (int j = 0; j < kMarkUnroll; ++j) k[j] = keys[q + j * kMarkThreads] - it.key_lo;   // loads in flight together
+                    for (int j = 0; j < kMarkUnroll; ++j) id[j] = ka.ids[q + j * kMarkThreads];
 #pragma unroll
-                for (int j = 0; j < kMarkUnroll; ++j)
-                    if (k[j] < span) {
-                        const uint32_t bit = 1u << (k[j] & 31);
-                        if (!(s_bits[k[j] >> 5] & bit)) atomicOr(&s_bits[k[j] >> 5], bit);
-                    }
-            }
-            for (; q < q1; q += kMarkThreads) {
-                const uint32_t k0 = keys[q] - it.key_lo;
-                if (k0 < span) {
-                    const uint32_t bit = 1u << (k0 & 31);
-                    if (!(s_bits[k0 >> 5] & bit)) atomicOr(&s_bits[k0 >> 5], bit);
+                    for (int j = 0; j < kMarkUnroll; ++j) mark_bit(s_bits, base + fold_id(id[j], m.rows), span);
                 }
+                for (; q < q1; q += kMarkThreads) mark_bit(s_bits, base + fold_id(ka.ids[q], m.rows), span);
+            } else {
+                const int64_t q0 = (int64_t)ma.fb[f] + ma.delta[f], q1 = (int64_t)ma.fb[f + 1] + ma.delta[f];
+                if (q0 < 0 || q1 > ma.nnz) continue;
+                int64_t q = q0 + threadIdx.x;
+                for (; q + (kMarkUnroll - 1) * kMarkThreads < q1; q += kMarkUnroll * kMarkThreads) {
+                    uint32_t k[kMarkUnroll];
+#pragma unroll
+                    for (int j = 0; j < kMarkUnroll; ++j) k[j] = ma.keys[q + j * kMarkThreads] - it.key_lo;   // loads in flight together
+#pragma unroll
+                    for (int j = 0; j < kMarkUnroll; ++j) mark_bit(s_bits, k[j], span);
+                }
+                for (; q < q1; q += kMarkThreads) mark_bit(s_bits, ma.keys[q] - it.key_lo, span);
             }
         }
     }
     __syncthreads();
-    uint4* dst = reinterpret_cast<uint4*>(bitmap + (size_t)pm[it.pack].first_tile * kTileWords + it.key_lo / 32);
+    uint4* dst = reinterpret_cast<uint4*>(ma.bitmap + (size_t)ma.pm[it.pack].first_tile * kTileWords + it.key_lo / 32);
     const uint4* src = reinterpret_cast<const uint4*>(s_bits);
     for (int w = threadIdx.x; w < it.n_words / 4; w += kMarkThreads) dst[w] = src[w];
+}
+
+__global__ void __launch_bounds__(kMarkThreads)
+pk_mark_kernel(MarkArgs ma)
+{
+    __shared__ uint32_t s_bits[kMarkWords];
+    mark_body<false>(ma, KeysArgs{}, blockIdx.x, s_bits);
+}
+
+// Small batches: the keys and the bitmap in one launch.  Blocks [0, mark_blocks) take the
+// slices and form the keys they need themselves; the others are the keys kernel.  (With few
+// occurrences every launch is mostly latency, and the second one would wait for the first.)
+constexpr int kFusedKeysBags = 1024;       // bags per block iteration of the keys part
+template <int BT>
+__global__ void __launch_bounds__(kMarkThreads)
+pk_keys_mark_kernel(const int64_t* __restrict__ ids, const int32_t* __restrict__ offsets, int B, int F, int P,
+                    int64_t nnz, const FieldMeta* __restrict__ fmeta, const PackMeta* __restrict__ pm,
+                    const int32_t* __restrict__ slot_field, PackState* st, int32_t* fb_out, int32_t* delta_out,
+                    uint32_t* __restrict__ keys, uint32_t* __restrict__ bagref, uint32_t* __restrict__ baglen,
+                    int32_t* __restrict__ packed_offsets, int64_t out_dim, uint4* clear4, int64_t n_clear4,
+                    MarkArgs ma, int mark_blocks)
+{
+    __shared__ uint32_t s_raw[kMarkWords];                 // either role's LDS
+    const KeysArgs ka{ids, offsets, B, F, P, nnz, fmeta, pm, slot_field, st, fb_out, delta_out, keys, bagref, baglen,
+                      packed_offsets, out_dim, clear4, n_clear4};
+    if ((int)blockIdx.x < mark_blocks)
+        mark_body<true>(ma, ka, blockIdx.x, s_raw);
+    else
+        keys_core<BT, kMarkThreads>(ids, offsets, fmeta, pm, slot_field, keys, bagref, baglen, packed_offsets, ka,
+                                    (int)blockIdx.x - mark_blocks, (int)gridDim.x - mark_blocks,
+                                    reinterpret_cast<int32_t*>(s_raw),
+                                    reinterpret_cast<int32_t*>(s_raw) + keys_bag_words<BT>());
 }
 
 // ---------------------------------------------------------------------------
@@ -1943,16 +2042,32 @@ static pk_status forward_impl(const pk_plan* plan, int stages, const char* who, 
     const bool long_bags = nnz / n_bags >= 16;
     const int bt = long_bags ? 32 : 256;
     const dim3 key_grid(blocks_for(n_bags, bt, 256 * 8));
-    const size_t key_lds = (size_t)(3 * F + 2) * 4;
+    const MarkArgs ma{ds->mark_items, ds->mark_fields, ds->pmeta, st, fb, delta, keys, bitmap, nnz};
+    const int n_mark = (int)plan->mark_items.size();
+    // small batches: the keys and the bitmap in one launch (its LDS holds either role's arrays)
+    const bool fuse_keys_mark = do_dedup && ds->fuse && nnz < (1 << 20) &&
+                                keys_bag_words<kFusedKeysBags>() + keys_field_words(F) <= (size_t)kMarkWords;
     if (!do_dedup) {
-    } else if (long_bags)
-        PK_LAUNCH("pk_keys", pk_keys_kernel<32>, key_grid, dim3(NT), key_lds, ids, offsets, B, F, P, nnz, ds->fmeta,
-                  ds->pmeta, ds->slot_field, st, fb, delta, keys, bagref, baglen, packed_offsets, plan->out_dim,
-                  reinterpret_cast<uint4*>(tile_desc), n_clear4);
-    else
-        PK_LAUNCH("pk_keys", pk_keys_kernel<256>, key_grid, dim3(NT), key_lds, ids, offsets, B, F, P, nnz, ds->fmeta,
-                  ds->pmeta, ds->slot_field, st, fb, delta, keys, bagref, baglen, packed_offsets, plan->out_dim,
-                  reinterpret_cast<uint4*>(tile_desc), n_clear4);
+    } else if (fuse_keys_mark) {
+        if (long_bags)
+            PK_LAUNCH("pk_keys_mark", pk_keys_mark_kernel<kFusedKeysBags / 8>,
+                      dim3((unsigned)n_mark + blocks_for(n_bags, kFusedKeysBags / 8, 512)), dim3(kMarkThreads), 0, ids,
+                      offsets, B, F, P, nnz, ds->fmeta, ds->pmeta, ds->slot_field, st, fb, delta, keys, bagref, baglen,
+                      packed_offsets, plan->out_dim, reinterpret_cast<uint4*>(tile_desc), n_clear4, ma, n_mark);
+        else
+            PK_LAUNCH("pk_keys_mark", pk_keys_mark_kernel<kFusedKeysBags>,
+                      dim3((unsigned)n_mark + blocks_for(n_bags, kFusedKeysBags, 512)), dim3(kMarkThreads), 0, ids,
+                      offsets, B, F, P, nnz, ds->fmeta, ds->pmeta, ds->slot_field, st, fb, delta, keys, bagref, baglen,
+                      packed_offsets, plan->out_dim, reinterpret_cast<uint4*>(tile_desc), n_clear4, ma, n_mark);
+    } else if (long_bags) {
+        PK_LAUNCH("pk_keys", pk_keys_kernel<32>, key_grid, dim3(NT), keys_field_words(F) * 4, ids, offsets, B, F, P, nnz,
+                  ds->fmeta, ds->pmeta, ds->slot_field, st, fb, delta, keys, bagref, baglen, packed_offsets,
+                  plan->out_dim, reinterpret_cast<uint4*>(tile_desc), n_clear4);
+    } else {
+        PK_LAUNCH("pk_keys", pk_keys_kernel<256>, key_grid, dim3(NT), keys_field_words(F) * 4, ids, offsets, B, F, P, nnz,
+                  ds->fmeta, ds->pmeta, ds->slot_field, st, fb, delta, keys, bagref, baglen, packed_offsets,
+                  plan->out_dim, reinterpret_cast<uint4*>(tile_desc), n_clear4);
+    }
 
     // Pooling needs the keys only.  Large batches: it runs on side streams beside the rest of
     // the dedup chain.  Small ones: it shares the launch of the sort kernel (a cross-stream
@@ -1986,8 +2101,7 @@ static pk_status forward_impl(const pk_plan* plan, int stages, const char* who, 
         if (n_side) { rc = join_streams(ds, stream, n_side); if (rc != PK_OK) return rc; }
         return PK_OK;
     }
-    PK_LAUNCH("pk_mark", pk_mark_kernel, dim3((unsigned)plan->mark_items.size()), dim3(kMarkThreads), 0, ds->mark_items,
-              ds->mark_fields, ds->pmeta, st, fb, delta, keys, bitmap, nnz);
+    if (!fuse_keys_mark) PK_LAUNCH("pk_mark", pk_mark_kernel, dim3((unsigned)n_mark), dim3(kMarkThreads), 0, ma);
     // a grid that the chip holds at once (the scan's waits need that); with more tiles than that,
     // runs of four tiles per block iteration
     constexpr int kTilesGrid = 1024, kTileRun = 4;
