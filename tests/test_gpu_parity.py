@@ -202,14 +202,17 @@ def test_hot_key_with_integer_gradients_is_exact():
         layer.close()
 
 
-def test_bad_offsets_raise_the_error_word_and_terminate():
+@pytest.mark.parametrize("tables,fields", [
+    ([(11, 8, 0)], [(0, 0), (0, 0)]),                      # one pack
+    ([(11, 8, 0), (7, 16, 0)], [(0, 0), (1, 1)]),          # two packs: the error word lives in the first one's state
+])
+def test_bad_offsets_raise_the_error_word_and_terminate(tables, fields):
     from paper_2204_04903_amd.layer import PackedEmbedding
-    tables = [(11, 8, 0)]
-    fields = [(0, 0), (0, 0)]
     pr = small_problem(95, B=8, tables=tables, fields=fields, max_len=3, allow_empty=False)
     layer = PackedEmbedding(tables, fields)
     try:
-        layer.load_table(0, pr["Wt"][0])
+        for t in range(len(tables)):
+            layer.load_table(t, pr["Wt"][t])
         bad = pr["offsets"].copy()
         bad[8] = bad[16] + 3          # the boundary between the two fields runs past the end
         out = layer.forward(torch.from_numpy(pr["ids"]).cuda(), torch.from_numpy(bad).cuda(), 8)
@@ -220,14 +223,16 @@ def test_bad_offsets_raise_the_error_word_and_terminate():
         say("[bad offsets] backward after the rejected forward")
         layer.backward_update(torch.from_numpy(pr["grad"]).cuda(), 0.05, 1e-8)
         torch.cuda.synchronize()
-        assert np.array_equal(bits_of(layer.W[0]), stack_tables(orc.plan(tables, fields), [pr["Wt"][0]])[0])
-        assert (layer.A[0] == 0).all()
+        W0 = stack_tables(orc.plan(tables, fields), [w.copy() for w in pr["Wt"]])
+        for p in range(layer.n_packs):
+            assert np.array_equal(bits_of(layer.W[p]), W0[p])
+            assert (layer.A[p] == 0).all()
         # and the same workspace works again afterwards
         out = layer.forward(torch.from_numpy(pr["ids"]).cuda(), torch.from_numpy(pr["offsets"]).cuda(), 8)
         torch.cuda.synchronize()
         assert layer.error_word() == 0
         pl = orc.plan(tables, fields)
-        ref, _ = orc.forward(pl, [pr["Wt"][0]], 8, pr["ids"], pr["offsets"])
+        ref, _ = orc.forward(pl, stack_tables(pl, [w.copy() for w in pr["Wt"]]), 8, pr["ids"], pr["offsets"])
         assert close(out.cpu().numpy(), ref)[0]
     finally:
         layer.close()
