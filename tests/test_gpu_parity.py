@@ -134,6 +134,35 @@ def test_many_packs_and_a_table_nobody_reads():
     run_dense_case("20 packs", tables, fields, steps)
 
 
+@pytest.mark.parametrize("seed", list(range(300, 312)))
+def test_random_small_layers(seed):
+    # seeded random layers: table sizes from one row up, dimensions of every lane shape, both dtypes,
+    # fields sharing tables, both poolings, empty bags, now and then raw 64-bit IDs
+    rng = np.random.default_rng(seed)
+    dims_pool = [1, 2, 3, 4, 5, 8, 12, 16, 17, 32, 48, 64, 100, 128, 256]
+    n_tables = int(rng.integers(1, 7))
+    dims = rng.choice(dims_pool, size=int(rng.integers(1, 4)), replace=False)
+    tables = [(int(rng.choice([1, 2, 3, 17, 64, 200, 1000])), int(rng.choice(dims)), int(rng.integers(0, 2)))
+              for _ in range(n_tables)]
+    fields = [(int(rng.integers(0, n_tables)), int(rng.integers(0, 2))) for _ in range(int(rng.integers(1, 9)))]
+    B = int(rng.choice([1, 2, 7, 31, 64, 129]))
+    steps = [small_problem(seed * 7 + s, B=B, tables=tables, fields=fields, max_len=int(rng.integers(1, 9)),
+                           wild_ids=bool(rng.integers(0, 4) == 0)) for s in range(2)]
+    run_dense_case(f"random {seed}", tables, fields, steps, lr=0.01)
+
+
+@pytest.mark.parametrize("seed,B", [(400, 1500), (401, 4096), (402, 2500), (403, 3333)])
+def test_random_medium_layers_hot_keys_and_many_distinct_keys(seed, B):
+    # tiny tables make keys with thousands of occurrences (long keys across several backward tiles),
+    # large ones make more than 16384 distinct keys in a table (several work items in the sort, chained
+    # by look-back); bags of 0..12 IDs
+    rng = np.random.default_rng(seed)
+    tables = [(5, 8, 0), (300, 64, 0), (40000, 8, 0), (3, 64, int(rng.integers(0, 2))), (50000, 32, 0), (40, 32, 0)]
+    fields = [(0, 0), (1, 1), (2, 0), (3, 1), (4, 0), (5, 1), (2, 1), (4, 1), (0, 1)]
+    steps = [small_problem(seed * 11 + s, B=B, tables=tables, fields=fields, max_len=12) for s in range(2)]
+    run_dense_case(f"medium {seed}", tables, fields, steps, lr=0.01)
+
+
 def test_wild_64bit_ids_are_folded():
     steps = [small_problem(50 + s, B=33, wild_ids=True) for s in range(2)]
     steps[0]["ids"][:4] = [-1, -2 ** 63, 2 ** 63 - 1, 0]
