@@ -57,7 +57,8 @@ class PkError(RuntimeError):
 def build(force: bool = True) -> str:
     """Compile the library for gfx950 (hipcc cross-compiles without a GPU)."""
     src = [os.path.join(_HERE, "csrc", "pk_plan.cpp"), os.path.join(_HERE, "csrc", "pk_device.hip")]
-    deps = src + [os.path.join(_HERE, "csrc", "pk_internal.h"), os.path.join(_ROOT, "include", "pk.h")]
+    deps = src + [os.path.join(_HERE, "csrc", f) for f in sorted(os.listdir(os.path.join(_HERE, "csrc")))
+                  if f.endswith(".h")] + [os.path.join(_ROOT, "include", "pk.h")]
     if not force and os.path.exists(LIB_PATH) and all(os.path.getmtime(LIB_PATH) >= os.path.getmtime(d) for d in deps):
         return LIB_PATH
     cmd = ["hipcc", "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

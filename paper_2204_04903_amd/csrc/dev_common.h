@@ -1,0 +1,146 @@
+// Device helpers shared by the kernels: block scans, the folding hash, single-pass multi-block prefix
+// sums (descriptors and look-back), the XCD-aware tile order.
+// Part of pk_device.hip: included there, in this order, inside its anonymous namespace.
+
+constexpr int NT = 256;   // threads per block of the streaming kernels
+
+#ifndef PK_ADA_WAVES
+#define PK_ADA_WAVES 6    // wavefronts per SIMD the backward kernel is compiled for (register budget)
+#endif
+#ifndef PK_ADA_WAVES_MEAN
+#define PK_ADA_WAVES_MEAN 6
+#endif
+#ifndef PK_ADA_UNROLL
+#define PK_ADA_UNROLL 4   // gradient chunks a lane group keeps in flight
+#endif
+#ifndef PK_ADA_UNROLL_MEAN
+#define PK_ADA_UNROLL_MEAN 2
+#endif
+
+template <int NTHREADS>
+__device__ __forceinline__ int block_excl_scan(int v, int* total)
+{
+    __shared__ int wsum[NTHREADS / 64];
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    int inc = v;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        int t = __shfl_up(inc, o, 64);
+        if (lane >= o) inc += t;
+    }
+    __syncthreads();   // readers of the previous call are done with wsum
+    if (lane == 63) wsum[w] = inc;
+    __syncthreads();
+    int base = 0, tot = 0;
+#pragma unroll
+    for (int i = 0; i < NTHREADS / 64; ++i) {
+        int s = wsum[i];
+        if (i < w) base += s;
+        tot += s;
+    }
+    *total = tot;
+    return base + inc - v;
+}
+
+__device__ __forceinline__ uint32_t fold_id(int64_t id, uint32_t rows)
+{
+    const uint64_t u = (uint64_t)id;
+    return u < rows ? (uint32_t)u : (uint32_t)(u % (uint64_t)rows);
+}
+
+// first index in [0, n) whose value exceeds x, for a non-decreasing array
+template <typename P>
+__device__ __forceinline__ int upper_bound_i32(P a, int n, int x)
+{
+    int lo = 0, hi = n;
+    while (lo < hi) {
+        int mid = (lo + hi) >> 1;
+        if (a[mid] <= x) lo = mid + 1; else hi = mid;
+    }
+    return lo;
+}
+
+// ---------------------------------------------------------------------------
+// single-pass multi-block prefix sums: every tile publishes a 64-bit
+// descriptor (state | value b | value a) and sums the descriptors of the tiles
+// before it.  A block takes tiles b, b + G, ...; a tile of a later round waits
+// for tiles of the round before, of every block, so the wait ends when all G
+// blocks are resident together: the launches keep G below what the chip holds
+// of that kernel alone.  (Two such kernels side by side on one GPU can hold
+// each other's places; calls of this library on one device are meant to follow
+// one another.)  The wait is bounded all the same: running out of patience sets
+// bit 1 of the error word, the kernels after it skip their work and the tables
+// stay as they are.
+// ---------------------------------------------------------------------------
+constexpr uint64_t kDescAgg = 1, kDescPfx = 2;
+constexpr int kSpinLimit = 1 << 22;
+
+__device__ __forceinline__ uint64_t make_desc(uint64_t state, uint32_t a, uint32_t b)
+{
+    return (state << 62) | ((uint64_t)b << 31) | (uint64_t)a;
+}
+
+__device__ __forceinline__ void publish_desc(uint64_t* d, uint64_t v)
+{
+    __hip_atomic_store(d, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Sum of (a, b) over tiles [first, me).  Called by all 64 lanes of one wave.
+__device__ __forceinline__ void lookback(uint64_t* desc, int first, int me, uint32_t* out_a, uint32_t* out_b,
+                                         int32_t* error_word)
+{
+    const int lane = threadIdx.x & 63;
+    uint32_t acc_a = 0, acc_b = 0;
+    int hi = me;
+    bool done = false;
+    while (hi > first && !done) {
+        const int idx = hi - 1 - lane;
+        const bool valid = idx >= first;
+        uint64_t d = make_desc(kDescPfx, 0, 0);
+        int spins = 0;
+        while (true) {
+            if (valid) d = __hip_atomic_load(desc + idx, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const bool ready = (d >> 62) != 0;
+            if (__ballot(ready) == ~0ull) break;
+            if (++spins > kSpinLimit) {
+                if (lane == 0) atomicOr(error_word, 2);
+                d = make_desc(kDescPfx, 0, 0);
+                break;
+            }
+            __builtin_amdgcn_s_sleep(2);
+        }
+        const uint64_t pfx_mask = __ballot((d >> 62) == kDescPfx);
+        int last = 64;                                   // lanes [0, last] contribute
+        if (pfx_mask) { last = __ffsll((unsigned long long)pfx_mask) - 1; done = true; }
+        if (lane <= last) {
+            acc_a += (uint32_t)(d & 0x7FFFFFFFull);
+            acc_b += (uint32_t)((d >> 31) & 0x7FFFFFFFull);
+        }
+        hi -= 64;
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        acc_a += __shfl_xor(acc_a, o, 64);
+        acc_b += __shfl_xor(acc_b, o, 64);
+    }
+    *out_a = acc_a;
+    *out_b = acc_b;
+}
+
+// Workgroups are handed to the 8 XCDs round-robin and each XCD has its own L2.
+// Giving XCD x the x-th contiguous eighth of the tiles keeps the irregular
+// accesses of neighbouring tiles (same table, same gradient columns) in one L2.
+// Only locality depends on this; any placement gives the same results.
+struct XcdTiles {
+    int tile, hi, step;
+    __device__ __forceinline__ XcdTiles(int n_tiles)
+    {
+        const int x = blockIdx.x & 7, i = blockIdx.x >> 3;
+        const int chunk = (n_tiles + 7) >> 3;
+        step = (gridDim.x + 7) >> 3;
+        tile = x * chunk + i;
+        hi = min((x + 1) * chunk, n_tiles);
+    }
+    __device__ __forceinline__ bool valid() const { return tile < hi; }
+    __device__ __forceinline__ void next() { tile += step; }
+};
