@@ -245,3 +245,10 @@ def test_split_batch_keeps_every_bag_and_gradient_row():
                     g, G = f * Bm + s, f * wl.batch + first + s
                     assert np.array_equal(p.ids[p.offsets[g]:p.offsets[g + 1]], b.ids[b.offsets[G]:b.offsets[G + 1]])
             first += Bm
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode != 0 and "ONE GPU" in r.stderr and r.stdout.strip() == ""
