@@ -33,7 +33,7 @@ int32_t pos_tile_for(int64_t nnz)
 {
     static const char* env = getenv("PK_TUNE_POS_TILE");      // tuning aid
     if (env && atoi(env) >= kPosTileMin && atoi(env) <= kPosTileMax) return atoi(env) / 64 * 64;
-    int64_t t = nnz < (2 << 20) ? 256 : 512;
+    int64_t t = nnz < (1 << 19) ? 128 : nnz < (2 << 20) ? 256 : 512;
     if (t < kPosTileMin) t = kPosTileMin;
     if (t > kPosTileMax) t = kPosTileMax;
     return (int32_t)t;
