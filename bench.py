@@ -264,7 +264,12 @@ def main():
         if k in alg:
             kern[k]["alg_bytes_per_step"] = alg[k] / prof_steps
             kern[k]["GBps"] = alg[k] / prof_steps / (kern[k]["ms_per_step"] * 1e-3) / 1e9
-    dom = max(kern, key=lambda k: kern[k]["ms_per_step"])
+    # the dominant kernel: the one that takes the most time; kernels within 5 % of it count as tied, and a tie
+    # goes to the one that moves the most bytes (two kernels of the default workload take the same time to
+    # within run-to-run noise, and the line should not flip between them)
+    t_max = max(v["ms_per_step"] for v in kern.values())
+    dom = max((k for k in kern if kern[k]["ms_per_step"] >= 0.95 * t_max),
+              key=lambda k: kern[k].get("alg_bytes_per_step", 0))
     dk = kern[dom]
     launches = max(1.0, dk["launches_per_step"])
     traffic = measured_traffic(dom, args.workload)
