@@ -49,3 +49,19 @@ def stack_tables(pl, Wt):
         assert all(pl.table_base[ts[i]] < pl.table_base[ts[i + 1]] for i in range(len(ts) - 1))
         out.append(np.ascontiguousarray(np.concatenate([Wt[t] for t in ts], axis=0)))
     return out
+
+
+def pooled_rel_band(tables, fields):
+    """Relative tolerance of every pooled output column: 2e-2 where the field's table is bf16
+    (fp32 accumulation), 1e-5 where it is fp32.  Fields are concatenated in field order."""
+    cols = []
+    for t, _ in fields:
+        cols.append(np.full(tables[t][1], 2e-2 if tables[t][2] == 1 else 1e-5))
+    return np.concatenate(cols)
+
+
+def pooled_close(got, ref, tables, fields):
+    """|got - ref| <= 1e-6 + rel * |ref| with rel chosen per column by the dtype of the field's table."""
+    tol = 1e-6 + pooled_rel_band(tables, fields)[None, :] * np.abs(ref)
+    bad = np.abs(got.astype(np.float64) - ref.astype(np.float64)) > tol
+    return not bad.any(), int(bad.sum())

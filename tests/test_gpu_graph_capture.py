@@ -7,7 +7,7 @@ import pytest
 import torch
 
 from oracle import pk_oracle as orc
-from helpers import small_problem, stack_tables
+from helpers import pooled_close, small_problem, stack_tables
 from test_gpu_parity import bits_of, close, f32_of, say
 
 pytestmark = pytest.mark.gpu
@@ -44,8 +44,7 @@ def test_a_step_replayed_from_a_graph_matches_the_oracle(tables, fields, groups)
         def check(tag):
             ref_out, ctx = orc.forward(pl, W, B, pr["ids"], pr["offsets"])
             orc.backward_update(pl, W, A, ctx, B, pr["grad"], lr, eps)
-            bf16 = any(t[2] == 1 for t in tables)
-            assert close(out.cpu().numpy(), ref_out, bf16=bf16)[0], tag
+            assert pooled_close(out.cpu().numpy(), ref_out, tables, fields)[0], tag
             for p in range(pl.n_packs):
                 dt = int(pl.pack_dtype[p])
                 assert close(f32_of(bits_of(layer.W[p]), dt), f32_of(W[p], dt), bf16=dt == 1)[0], tag

@@ -52,20 +52,22 @@ def test_hybrid_hash_follows_alg1_and_is_transparent(cold_on_host, dtype):
             ids = torch.from_numpy(pr["ids"]).cuda()
             offsets = torch.from_numpy(pr["offsets"]).cuda()
             grad = torch.from_numpy(pr["grad"]).cuda()
+            # bf16: the rows on the device may sit one bf16 step away from the oracle's after an update
+            # (both are inside the row band, checked below), and pooled sums of such rows can cancel.  The
+            # pooled output is therefore held, within the band for bf16 tables, against the oracle's
+            # forward pass over the rows the device holds at this moment.
+            W_now = W
+            if dtype == 1:
+                W_now = [(logical_rows(layer, p)[0].view(np.uint32) >> np.uint32(16)).astype(np.uint16)
+                         for p in range(pl.n_packs)]
             out = layer.forward(ids, offsets, pr["B"])
             layer.backward_update(grad, 0.05, 1e-8)
             queried, hits, flushed = layer.end_iteration()
             torch.cuda.synchronize()
             assert layer.error_word() == 0
             ref_out, ctx = orc.forward(pl, W, pr["B"], pr["ids"], pr["offsets"])
-            got_out = out.cpu().numpy()
-            if dtype == 0:
-                assert close(got_out, ref_out), f"iteration {itr}: pooled output"
-            else:
-                # bf16 rows agree within 2e-2 each (checked below), so a pooled sum agrees within 2e-2 of the
-                # sum of the magnitudes of its terms; over many steps terms cancel and |sum| alone is too tight
-                mag, _ = orc.forward(pl, [(w & np.uint16(0x7FFF)) for w in W], pr["B"], pr["ids"], pr["offsets"])
-                assert np.all(np.abs(got_out - ref_out) <= 1e-6 + 2e-2 * mag), f"iteration {itr}: pooled output"
+            ref_now = ref_out if dtype == 0 else orc.forward(pl, W_now, pr["B"], pr["ids"], pr["offsets"])[0]
+            assert close(out.cpu().numpy(), ref_now, bf16=dtype == 1), f"iteration {itr}: pooled output"
             orc.backward_update(pl, W, A, ctx, pr["B"], pr["grad"], 0.05, 1e-8)
             for p in range(pl.n_packs):
                 hit, fl = oracles[p].iteration(ctx[p].unique.astype(np.int64), itr)

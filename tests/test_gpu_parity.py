@@ -15,7 +15,7 @@ import torch
 import synth
 from oracle import pk_oracle as orc
 from oracle.sparse_tables import SparseOracle
-from helpers import small_problem, stack_tables
+from helpers import pooled_close, small_problem, stack_tables
 
 pytestmark = pytest.mark.gpu
 
@@ -70,7 +70,7 @@ def run_dense_case(name, tables, fields, steps, lr=0.05, eps=1e-8, out_pad=0, gr
             ref_out, ctx = orc.forward(pl, W, B, pr["ids"], pr["offsets"])
             orc.backward_update(pl, W, A, ctx, B, pr["grad"], lr, eps)
             got = out_buf.cpu().numpy()
-            ok, nbad = close(got[:, :layer.out_dim], ref_out, bf16=any(t[2] == 1 for t in tables))
+            ok, nbad = pooled_close(got[:, :layer.out_dim], ref_out, tables, fields)     # band by the field's table dtype
             assert ok, f"{name} step {s}: {nbad} pooled outputs out of tolerance"
             if out_pad:
                 assert (got[:, layer.out_dim:] == 7.0).all()
