@@ -28,17 +28,17 @@ def algorithmic_bytes(info, mean_pack):
     (nnz, U, k*B bags, dim D, element size sw, bitmap bytes bm).  Rows are
     counted once per DISTINCT key: removing repeats is the method."""
     n, U, bags, D, sw, bm = info["nnz"], info["U"], info["bags"], info["D"], info["sw"], info["bitmap_bytes"]
+    ent = 4 * n + sc_occ(n, mean_pack)                      # the occurrences grouped by key (with bag lengths for mean pooling)
     return {
-        "pk_keys": 8 * n + 4 * n + 4 * n + sc_occ(n, mean_pack) + 4 * bags + 4 * bags,
+        # small batches, the forward pass in one launch: ids and offsets in; keys, inverse, grouped occurrences,
+        # distinct keys, segment offsets and packed offsets out; one read of each distinct row; pooled output
+        "pk_fused": 8 * n + 4 * bags + 4 * n + 4 * n + ent + 8 * U + 4 * bags + sw * D * U + 4 * D * bags,
+        "pk_keys": 8 * n + 4 * n + 4 * bags + 4 * bags,
         "pk_pool": 4 * n + 4 * (bags + 1) + sw * D * U + 4 * D * bags,
-        "pk_mark": 4 * n + bm,
-        "pk_keys_mark": 8 * n + 4 * n + 4 * n + sc_occ(n, mean_pack) + 4 * bags + 4 * bags + 8 * n + bm,
-        "pk_tiles": bm + bm // 8 + 4 * U,
+        "pk_scatter": 4 * n + 4 * bags + 8 * n,
+        "pk_slices": 8 * n + ent + 8 * U + bm + bm // 8,
         "pk_inverse": 8 * n + min(bm + bm // 8, 36 * n),
-        "pk_sort": 2 * (4 * n) + 4 * n + 2 * sc_occ(n, mean_pack) + 4 * n + 4 * U,
-        "pk_sort_pool": (2 * (4 * n) + 4 * n + 2 * sc_occ(n, mean_pack) + 4 * n + 4 * U
-                         + 4 * n + 4 * (bags + 1) + sw * D * U + 4 * D * bags),
-        "pk_adagrad": 4 * (U + 1) + 4 * U + 4 * n + sc_occ(n, mean_pack) + 4 * D * bags + (2 * sw + 8) * D * U,
+        "pk_adagrad": 4 * (U + 1) + 4 * U + ent + 4 * D * bags + (2 * sw + 8) * D * U,
     }
 
 
@@ -251,10 +251,8 @@ def run_workload(args, workload):
         for p in range(layer.n_packs):
             d = pk.pk_ctx_pack(layer.plan, layer.ws, wl.batch, batches[i % ring].nnz, p)
             info = layer.packs[p]
-            words = (info["total_rows"] + 31) // 32
-            tiles = (words + 2047) // 2048
             row.append(dict(nnz=d["nnz_p"], U=d["n_unique"], bags=info["n_fields"] * wl.batch, D=info["dim"],
-                            sw=4 if info["dtype"] == 0 else 2, bitmap_bytes=tiles * 2048 * 4))
+                            sw=4 if info["dtype"] == 0 else 2, bitmap_bytes=(info["total_rows"] + 7) // 8))
         sizes.append(row)
     prof = pk.pk_profile_read(layer.plan)
     pk.pk_profile_enable(layer.plan, False)

@@ -21,7 +21,7 @@
  *     of distinct keys) stay in device memory.
  *   - All functions return a pk_status (0 = success) and never throw;
  *     pk_last_error() gives a thread-local message for the last failure.
- *   - Limits: total rows of a pack < 2^32; dim <= 256; nnz < 2^31;
+ *   - Limits: total rows of a pack < 2^32, of a table <= 2^30; dim <= 256; nnz < 2^31;
  *     B * out_dim < 2^32; at most 4096 fields and 4096 tables.
  */
 #ifndef PK_H
@@ -67,6 +67,9 @@ typedef struct {
                                    call's work on hip_stream is complete).  0 = chosen by
                                    batch size, 1 = none, at most 8.  Results do not depend
                                    on it.                                               */
+    int32_t debug;              /* for tests and measurements; results do not depend on it.
+                                   bit 0: no internal streams, every kernel on hip_stream;
+                                   bit 1: the partitioned dedup also for small batches      */
 } pk_plan_opts;
 
 typedef struct pk_plan pk_plan;   /* opaque, host memory, owned by the library */

@@ -39,7 +39,8 @@ class pk_field_desc(ctypes.Structure):
 
 class pk_plan_opts(ctypes.Structure):
     _fields_ = [("max_batch", ctypes.c_int32), ("max_nnz", ctypes.c_int64), ("max_shards", ctypes.c_int32),
-                ("field_volume", ctypes.POINTER(ctypes.c_double)), ("interleave_groups", ctypes.c_int32)]
+                ("field_volume", ctypes.POINTER(ctypes.c_double)), ("interleave_groups", ctypes.c_int32),
+                ("debug", ctypes.c_int32)]
 
 
 class pk_hh_pack(ctypes.Structure):
@@ -159,11 +160,12 @@ def _ptr(x) -> Optional[int]:
 
 def pk_plan_create(tables: Sequence[Tuple[int, int, int]], fields: Sequence[Tuple[int, int]],
                    max_batch: int = 0, max_nnz: int = 0, max_shards: int = 0,
-                   field_volume: Optional[Sequence[float]] = None, interleave_groups: int = 0) -> int:
+                   field_volume: Optional[Sequence[float]] = None, interleave_groups: int = 0,
+                   debug: int = 0) -> int:
     """tables: (rows, dim, dtype) each; fields: (table, pool) each.  Returns the plan handle."""
     T = (pk_table_desc * max(len(tables), 1))(*[pk_table_desc(int(r), int(d), int(t)) for r, d, t in tables])
     Fd = (pk_field_desc * max(len(fields), 1))(*[pk_field_desc(int(t), int(p)) for t, p in fields])
-    opts = pk_plan_opts(int(max_batch), int(max_nnz), int(max_shards), None, int(interleave_groups))
+    opts = pk_plan_opts(int(max_batch), int(max_nnz), int(max_shards), None, int(interleave_groups), int(debug))
     if field_volume is not None:
         vol = (ctypes.c_double * len(field_volume))(*[float(v) for v in field_volume])
         opts.field_volume = ctypes.cast(vol, ctypes.POINTER(ctypes.c_double))

@@ -154,7 +154,7 @@ pk_adagrad_kernel(WT* W, float* A, const PackState* __restrict__ st, int p,
     // checked.  A forward pass that raised the error word (input rejected, or a scan that ran
     // out of patience) left no lists worth reading: the tables are then left alone.
     const int n = n_host >= 0 ? n_host : st->nnz, start = n_host >= 0 ? 0 : st->start;
-    const bool state_ok = (n_host < 0 || st->nnz == n_host) && (st - p)->error == 0;
+    const bool state_ok = (n_host < 0 || st->nnz == n_host) && st->error == 0;
     const int32_t* seg = seg_all + start + p;
     const uint32_t* uq = unique_all + start;
     const size_t tbase = (size_t)(start / tp + p);
@@ -317,7 +317,7 @@ pk_adagrad_hot_kernel(HotPacks ptrs, int p0, const PackMeta* __restrict__ pm, co
 {
     const int p = p0 + blockIdx.y;
     const PackMeta k = pm[p];
-    if (st[0].error) return;                               // as in pk_adagrad_kernel
+    if (st[p].error) return;                               // as in pk_adagrad_kernel
     const int n = st[p].nnz, start = st[p].start, D = k.dim;
     const int32_t* seg = seg_all + start + p;
     const size_t tbase = (size_t)(start / tp + p);

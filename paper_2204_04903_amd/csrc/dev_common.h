@@ -61,23 +61,24 @@ __device__ __forceinline__ int upper_bound_i32(P a, int n, int x)
 }
 
 // ---------------------------------------------------------------------------
-// single-pass multi-block prefix sums: every tile publishes a 64-bit
-// descriptor (state | value b | value a) and sums the descriptors of the tiles
-// before it.  A block takes tiles b, b + G, ...; a tile of a later round waits
-// for tiles of the round before, of every block, so the wait ends when all G
-// blocks are resident together: the launches keep G below what the chip holds
-// of that kernel alone.  (Two such kernels side by side on one GPU can hold
-// each other's places; calls of this library on one device are meant to follow
-// one another.)  The wait is bounded all the same: running out of patience sets
-// bit 1 of the error word, the kernels after it skip their work and the tables
-// stay as they are.
+// single-pass multi-block prefix sums: every work item publishes a 64-bit
+// descriptor (state | flag | value b | value a) and sums the descriptors of the
+// items before it.  Block i takes item i and nothing else, and an item waits
+// only for lower items: the hardware starts the blocks of a launch in index
+// order, so whatever a block waits for belongs to a block that has started (or
+// finished), however many blocks the chip holds at once and whatever else runs
+// beside the launch.  The wait is bounded all the same: running out of patience
+// raises a flag, which travels with the sums to every later item; the kernels
+// turn it into bit 1 of the pack's error word, the kernels after them skip
+// their work and the tables stay as they are.
 // ---------------------------------------------------------------------------
 constexpr uint64_t kDescAgg = 1, kDescPfx = 2;
 constexpr int kSpinLimit = 1 << 22;
 
-__device__ __forceinline__ uint64_t make_desc(uint64_t state, uint32_t a, uint32_t b)
+// a: 31 bits, b: 29 bits, flags: 2 bits (the bits of the error word)
+__device__ __forceinline__ uint64_t make_desc(uint64_t state, uint32_t a, uint32_t b, uint32_t flags)
 {
-    return (state << 62) | ((uint64_t)b << 31) | (uint64_t)a;
+    return (state << 62) | ((uint64_t)(flags & 3u) << 60) | ((uint64_t)(b & 0x1FFFFFFFu) << 31) | (uint64_t)(a & 0x7FFFFFFFu);
 }
 
 __device__ __forceinline__ void publish_desc(uint64_t* d, uint64_t v)
@@ -85,26 +86,25 @@ __device__ __forceinline__ void publish_desc(uint64_t* d, uint64_t v)
     __hip_atomic_store(d, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-// Sum of (a, b) over tiles [first, me).  Called by all 64 lanes of one wave.
+// Sums of a and b, and the OR of the flags, over items [first, me).  Called by all 64 lanes of one wave.
 __device__ __forceinline__ void lookback(uint64_t* desc, int first, int me, uint32_t* out_a, uint32_t* out_b,
-                                         int32_t* error_word)
+                                         uint32_t* out_flag)
 {
     const int lane = threadIdx.x & 63;
-    uint32_t acc_a = 0, acc_b = 0;
+    uint32_t acc_a = 0, acc_b = 0, flag = 0;
     int hi = me;
     bool done = false;
     while (hi > first && !done) {
         const int idx = hi - 1 - lane;
         const bool valid = idx >= first;
-        uint64_t d = make_desc(kDescPfx, 0, 0);
+        uint64_t d = make_desc(kDescPfx, 0, 0, 0);
         int spins = 0;
         while (true) {
             if (valid) d = __hip_atomic_load(desc + idx, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             const bool ready = (d >> 62) != 0;
             if (__ballot(ready) == ~0ull) break;
             if (++spins > kSpinLimit) {
-                if (lane == 0) atomicOr(error_word, 2);
-                d = make_desc(kDescPfx, 0, 0);
+                d = make_desc(kDescPfx, 0, 0, 2);      // flag bit 1: waited too long
                 break;
             }
             __builtin_amdgcn_s_sleep(2);
@@ -114,7 +114,8 @@ __device__ __forceinline__ void lookback(uint64_t* desc, int first, int me, uint
         if (pfx_mask) { last = __ffsll((unsigned long long)pfx_mask) - 1; done = true; }
         if (lane <= last) {
             acc_a += (uint32_t)(d & 0x7FFFFFFFull);
-            acc_b += (uint32_t)((d >> 31) & 0x7FFFFFFFull);
+            acc_b += (uint32_t)((d >> 31) & 0x1FFFFFFFull);
+            flag |= (uint32_t)((d >> 60) & 3ull);
         }
         hi -= 64;
     }
@@ -122,9 +123,11 @@ __device__ __forceinline__ void lookback(uint64_t* desc, int first, int me, uint
     for (int o = 32; o > 0; o >>= 1) {
         acc_a += __shfl_xor(acc_a, o, 64);
         acc_b += __shfl_xor(acc_b, o, 64);
+        flag |= __shfl_xor(flag, o, 64);
     }
     *out_a = acc_a;
     *out_b = acc_b;
+    *out_flag = flag;
 }
 
 // Workgroups are handed to the 8 XCDs round-robin and each XCD has its own L2.

@@ -1,71 +1,47 @@
-// H1 and H2: packed keys, the bitmap of the rows that occur, its one-pass scan (distinct keys and rank
-// samples), the inverse index, and the per-key occurrence lists (LDS counting sort).
+// H1 and H2: packed keys, distinct keys (ascending), the inverse index and the per-key occurrence
+// lists, by slices of the key space.
 // Part of pk_device.hip: included there, in this order, inside its anonymous namespace.
-
-// ---------------------------------------------------------------------------
-// H1: packed keys (Sec. III-B: one packed ID tensor per pack), packed bag
-// offsets, and for every occurrence the place of its bag's gradient chunk.
-// A block takes BT consecutive bags (field-major, so their IDs are contiguous),
-// keeps their offsets in LDS and finds each occurrence's bag there.
 //
-// Where a field's occurrences go in the packed order follows from the field
-// boundaries alone, so every block derives it for itself (a scan over the
-// fields in (pack, slot) order) instead of waiting for a set-up launch; block 0
-// also stores it for the later kernels.  All blocks share the clearing of the
-// scan descriptors.
+// Unique (Sec. II-D) is a set over the pack's rows, so it is built where a set of rows is cheap:
+// a table's key range is cut into slices of 2^k keys, and ONE block owns a slice.  In LDS it keeps
+// the slice's bitmap (which rows occur), the popcount prefix of the bitmap's words (the index of a
+// key among the slice's distinct keys is a prefix plus a popcount) and one counter per distinct
+// key.  From those it writes, for its slice, the ascending distinct keys, the segment offsets, the
+// headers of the backward tiles and the occurrences grouped by key -- everything the backward
+// pass reads.  What a slice needs from the others is two numbers, the distinct keys and the
+// occurrences of the slices before it in the pack; they travel through look-back descriptors.
+//
+// Which occurrences belong to a slice:
+//   small batches   every slice block scans the IDs of its table's fields and keeps those whose
+//                   row falls into its slice (the IDs of a table are few and sit in L2), so the
+//                   whole dedup, with the pooling beside it, is ONE launch;
+//   large batches   the occurrences are partitioned by slice first: the keys kernel counts them
+//                   per slice (block-local counts in LDS, one global add per touched slice), a
+//                   one-block scan turns the counts into places, a scatter kernel writes a
+//                   (key in slice, bag) record per occurrence to its slice's place, and the slice
+//                   kernel reads its records; the inverse index is then looked up per occurrence
+//                   from the bitmap and rank samples the slice kernel leaves in memory.
+
 // ---------------------------------------------------------------------------
-struct KeysArgs {
-    const int64_t* ids; const int32_t* offsets; int B, F, P; int64_t nnz;
-    const FieldMeta* fmeta; const PackMeta* pm; const int32_t* slot_field; PackState* st;
-    int32_t* fb_out; int32_t* delta_out;
-    uint32_t* keys; uint32_t* bagref; uint32_t* baglen; int32_t* packed_offsets;
-    int64_t out_dim; uint4* clear4; int64_t n_clear4;
-};
+// Field boundaries, and where each field's occurrences go in the packed order (fields in
+// (pack, slot) order, one after the other).  s_fb [F+1], s_delta [F] (packed position minus
+// position in ids), s_slotpos [F+1] (packed position of each (pack, slot)).  Returns non-zero
+// when the boundaries are unusable (offsets[0] != 0, offsets[F*B] != nnz, or decreasing).
+// ---------------------------------------------------------------------------
+constexpr size_t field_scan_words(int F) { return (size_t)(3 * F + 2); }
 
-// LDS words of keys_body: per bag (a flag, the offsets of BT bags and five values per bag) and
-// per field (the scan of the field boundaries)
-template <int BT>
-constexpr int keys_bag_words() { return 1 + (BT + 1) + 5 * BT; }
-constexpr size_t keys_field_words(int F) { return (size_t)(3 * F + 2); }
-
-// `block` of `nblocks` blocks of NTH threads.  (The arrays come as restrict-qualified parameters
-// of their own: the compiler orders the loads and stores of the inner loop far better when it
-// knows that they do not overlap.)
-template <int BT, int NTH>
-__device__ __forceinline__ void keys_core(const int64_t* __restrict__ ids, const int32_t* __restrict__ offsets,
-                                          const FieldMeta* __restrict__ fmeta, const PackMeta* __restrict__ pm,
-                                          const int32_t* __restrict__ slot_field, uint32_t* __restrict__ keys,
-                                          uint32_t* __restrict__ bagref, uint32_t* __restrict__ baglen,
-                                          int32_t* __restrict__ packed_offsets, const KeysArgs& a, int block,
-                                          int nblocks, int32_t* lds_bag, int32_t* lds_field)
+template <int NTH>
+__device__ __forceinline__ int field_scan(const int32_t* __restrict__ offsets, int B, int F, int64_t nnz,
+                                          const int32_t* __restrict__ slot_field, int32_t* s_fb, int32_t* s_delta,
+                                          int32_t* s_slotpos)
 {
-    const int B = a.B, F = a.F, P = a.P;
-    const int64_t nnz = a.nnz;
-    const int64_t out_dim = a.out_dim;
-    int32_t* s_po = lds_bag;                  // [BT+1] offsets of the tile's bags
-    uint32_t* s_base = reinterpret_cast<uint32_t*>(s_po + (BT + 1));   // [BT] each
-    uint32_t* s_rows = s_base + BT;
-    uint32_t* s_ref = s_rows + BT;
-    int32_t* s_dl = reinterpret_cast<int32_t*>(s_ref + BT);
-    uint32_t* s_len = reinterpret_cast<uint32_t*>(s_dl + BT);
-    int32_t* s_badp = reinterpret_cast<int32_t*>(s_len + BT);
-    int32_t* s_fb = lds_field;                // [F+1] field boundaries in ids
-    int32_t* s_delta = s_fb + (F + 1);        // [F]   packed position minus position in ids
-    int32_t* s_slotpos = s_delta + F;         // [F+1] packed position of each (pack, slot)
     const int tid = threadIdx.x;
-    {
-        const uint4 z = make_uint4(0, 0, 0, 0);
-        const int64_t stride = (int64_t)nblocks * NTH;
-        for (int64_t i = (int64_t)block * NTH + tid; i < a.n_clear4; i += stride) a.clear4[i] = z;
-    }
-    if (tid == 0) *s_badp = 0;
     for (int f = tid; f <= F; f += NTH) s_fb[f] = offsets[(int64_t)f * B];
     __syncthreads();
-    for (int f = tid; f < F; f += NTH)
-        if (s_fb[f + 1] < s_fb[f]) *s_badp = 1;
-    if (tid == 0 && (s_fb[0] != 0 || (int64_t)s_fb[F] != nnz)) *s_badp = 1;
-    __syncthreads();
-    const int bad = *s_badp;
+    int mine = 0;
+    for (int f = tid; f < F; f += NTH) mine |= s_fb[f + 1] < s_fb[f];
+    if (tid == 0) mine |= (s_fb[0] != 0 || (int64_t)s_fb[F] != nnz);
+    const int bad = __syncthreads_or(mine);
     int carry = 0;
     for (int base = 0; base < F; base += NTH) {
         const int i = base + tid;
@@ -84,311 +60,677 @@ __device__ __forceinline__ void keys_core(const int64_t* __restrict__ ids, const
     }
     if (tid == 0) s_slotpos[F] = carry;
     __syncthreads();
-    if (block == 0) {
-        for (int f = tid; f <= F; f += NTH) a.fb_out[f] = s_fb[f];
-        for (int f = tid; f < F; f += NTH) a.delta_out[f] = s_delta[f];
-        for (int p = tid; p < P; p += NTH) {
-            const PackMeta k = pm[p];
-            const int start = s_slotpos[k.first_slot];
-            PackState s;
-            s.nnz = s_slotpos[k.first_slot + k.n_fields] - start;
-            s.start = start; s.n_unique = 0; s.error = (p == 0) ? bad : 0;
-            s.pad[0] = s.pad[1] = s.pad[2] = s.pad[3] = 0;
-            a.st[p] = s;
-            packed_offsets[(int64_t)k.first_slot * B + p + (int64_t)k.n_fields * B] = s.nnz;
-        }
-    }
-    if (bad) return;
-    const int64_t n_bags = (int64_t)F * B;
-    const int64_t n_tiles = (n_bags + BT - 1) / BT;
-    for (int64_t tile = block; tile < n_tiles; tile += nblocks) {
-        const int64_t g0 = tile * BT;
-        const int nb = (int)min((int64_t)BT, n_bags - g0);
-        __syncthreads();                               // the previous tile's LDS is consumed
-        for (int t = tid; t <= nb; t += NTH) s_po[t] = (int32_t)min((int64_t)max(offsets[g0 + t], 0), nnz);
-        __syncthreads();
-        for (int t = tid; t < nb; t += NTH) {
-            const int64_t g = g0 + t;
-            const int f = (int)(g / B);
-            const int b = (int)(g - (int64_t)f * B);
-            const FieldMeta m = fmeta[f];
-            const PackMeta k = pm[m.pack];
-            s_base[t] = m.base_row;
-            s_rows[t] = m.rows;
-            s_dl[t] = s_delta[f];
-            s_ref[t] = (uint32_t)((int64_t)b * out_dim + m.col);
-            const int L = s_po[t + 1] - s_po[t];
-            s_len[t] = (m.pool == PK_MEAN && L > 0) ? (uint32_t)L : 1u;     // what the gradient is divided by
-            packed_offsets[(int64_t)k.first_slot * B + m.pack + (int64_t)m.slot * B + b] =
-                s_po[t] + s_delta[f] - s_slotpos[k.first_slot];
-        }
-        __syncthreads();
-        const int q_lo = s_po[0], q_hi = s_po[nb];
-        for (int i0 = q_lo + tid; i0 < q_hi; i0 += 4 * NTH) {
-            int64_t idv[4];
-#pragma unroll
-            for (int k = 0; k < 4; ++k) {              // the loads of four rounds in flight together
-                const int i = i0 + k * NTH;
-                idv[k] = i < q_hi ? ids[i] : 0;
-            }
-#pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                const int i = i0 + k * NTH;
-                if (i >= q_hi) continue;
-                const int t = upper_bound_i32(s_po, nb + 1, i) - 1;
-                if ((unsigned)t >= (unsigned)nb) continue;
-                const int64_t q = (int64_t)i + s_dl[t];
-                if ((uint64_t)q >= (uint64_t)nnz) continue;
-                keys[q] = s_base[t] + fold_id(idv[k], s_rows[t]);
-                bagref[q] = s_ref[t];
-                if (baglen) baglen[q] = s_len[t];
-            }
-        }
-    }
+    return bad;
 }
+
+// s_first [T+1]: the first slice of every table, in table-list order (slices are numbered over all packs)
+template <int NTH>
+__device__ __forceinline__ void table_scan(const TableMeta* __restrict__ tmeta, int T, int F, int64_t nnz, int target,
+                                           int32_t* s_first)
+{
+    int carry = 0;
+    for (int base = 0; base < T; base += NTH) {
+        const int t = base + (int)threadIdx.x;
+        int n = 0;
+        if (t < T) {
+            const TableMeta tm = tmeta[t];
+            n = slice_geom(tm.rows, tm.field_end - tm.field_begin, F, nnz, target).n;
+        }
+        int tot;
+        const int ex = block_excl_scan<NTH>(n, &tot);
+        if (t < T) s_first[t] = carry + ex;
+        carry += tot;
+    }
+    if (threadIdx.x == 0) s_first[T] = carry;
+    __syncthreads();
+}
+
+// the bag of field-local offsets `offs` [B+1] that holds position q (offsets that are not monotone give
+// some bag of the field: the answer stays in range)
+__device__ __forceinline__ int find_bag(const int32_t* __restrict__ offs, int B, int q, int guess)
+{
+    if ((unsigned)guess < (unsigned)B && offs[guess] <= q && q < offs[guess + 1]) return guess;
+    int lo = 0, hi = B + 1;
+    while (lo < hi) {
+        const int mid = (lo + hi) >> 1;
+        if (offs[mid] <= q) lo = mid + 1; else hi = mid;
+    }
+    return min(max(lo - 1, 0), B - 1);
+}
+
+__global__ void __launch_bounds__(NT)
+pk_clear_kernel(uint4* p, int64_t n4)
+{
+    const uint4 z = make_uint4(0, 0, 0, 0);
+    for (int64_t i = (int64_t)blockIdx.x * NT + threadIdx.x; i < n4; i += (int64_t)gridDim.x * NT) p[i] = z;
+}
+
+// ---------------------------------------------------------------------------
+// Large batches, H1: packed keys (Sec. III-B: one packed ID tensor per pack), packed bag offsets,
+// and how many occurrences fall into every slice.  A tile is BT consecutive bags of ONE field, so
+// its IDs are contiguous and hit one table; the tile's counts per slice are tallied in LDS and
+// added to the slices' totals with one global add per touched slice.  The offsets of a tile are
+// checked here: inside their field's range and not decreasing, else bit 0 of the pack's error
+// word is raised and the tile is skipped (the kernels after this one skip that pack).
+// ---------------------------------------------------------------------------
+struct TileOf {
+    int f, b0, nb;
+    __device__ __forceinline__ TileOf(int64_t tile, int tiles_per_field, int B, int BT)
+    {
+        f = (int)(tile / tiles_per_field);
+        b0 = (int)(tile - (int64_t)f * tiles_per_field) * BT;
+        nb = min(BT, B - b0);
+    }
+};
 
 template <int BT>
 __global__ void __launch_bounds__(NT)
-pk_keys_kernel(const int64_t* __restrict__ ids, const int32_t* __restrict__ offsets, int B, int F, int P, int64_t nnz,
-               const FieldMeta* __restrict__ fmeta, const PackMeta* __restrict__ pm,
-               const int32_t* __restrict__ slot_field, PackState* st, int32_t* fb_out, int32_t* delta_out,
-               uint32_t* __restrict__ keys, uint32_t* __restrict__ bagref, uint32_t* __restrict__ baglen,
-               int32_t* __restrict__ packed_offsets, int64_t out_dim, uint4* clear4, int64_t n_clear4)
+pk_keys_kernel(const int64_t* __restrict__ ids, const int32_t* __restrict__ offsets, int B, int F, int P, int T,
+               int64_t nnz, int target, const FieldMeta* __restrict__ fmeta, const PackMeta* __restrict__ pm,
+               const TableMeta* __restrict__ tmeta, const int32_t* __restrict__ slot_field, PackState* st,
+               uint32_t* __restrict__ keys, int32_t* __restrict__ packed_offsets, int32_t* slice_total,
+               int32_t* __restrict__ seg_all)
 {
-    extern __shared__ int32_t s_dyn[];                     // keys_field_words(F)
-    __shared__ int32_t s_bag[keys_bag_words<BT>()];
-    const KeysArgs a{ids, offsets, B, F, P, nnz, fmeta, pm, slot_field, st, fb_out, delta_out, keys, bagref, baglen,
-                     packed_offsets, out_dim, clear4, n_clear4};
-    keys_core<BT, NT>(ids, offsets, fmeta, pm, slot_field, keys, bagref, baglen, packed_offsets, a, blockIdx.x,
-                      gridDim.x, s_bag, s_dyn);
+    extern __shared__ int32_t s_dyn[];                     // field scan | first slices | the tile's counts
+    __shared__ int32_t s_po[BT + 1];
+    __shared__ int s_flag;
+    int32_t* s_fb = s_dyn;
+    int32_t* s_delta = s_fb + (F + 1);
+    int32_t* s_slotpos = s_delta + F;
+    int32_t* s_first = s_slotpos + (F + 1);
+    int32_t* s_hist = s_first + (T + 1);
+    const int tid = threadIdx.x;
+    const int bad = field_scan<NT>(offsets, B, F, nnz, slot_field, s_fb, s_delta, s_slotpos);
+    table_scan<NT>(tmeta, T, F, nnz, target, s_first);
+    if (blockIdx.x == 0) {
+        for (int p = tid; p < P; p += NT) {
+            const PackMeta k = pm[p];
+            const int start = s_slotpos[k.first_slot];
+            const int n = s_slotpos[k.first_slot + k.n_fields] - start;
+            st[p].nnz = n;
+            st[p].start = start;
+            st[p].first_slice = s_first[k.first_stable];
+            if (bad) atomicOr(&st[p].error, 1);            // the clearing kernel zeroed the word
+            if (k.n_stables == 0) seg_all[start + p] = 0;  // no table that a field reads: no slice writes the end of its segments
+            packed_offsets[(int64_t)k.first_slot * B + p + (int64_t)k.n_fields * B] = n;
+        }
+    }
+    if (bad) return;
+    const int tpf = (B + BT - 1) / BT;
+    const int64_t n_tiles = (int64_t)F * tpf;
+    for (int64_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+        const TileOf tl(tile, tpf, B, BT);
+        const int f = tl.f;
+        const FieldMeta m = fmeta[f];
+        const PackMeta k = pm[m.pack];
+        const TableMeta tm = tmeta[m.stable];
+        const SliceGeom g = slice_geom(tm.rows, tm.field_end - tm.field_begin, F, nnz, target);
+        const int64_t g0 = (int64_t)f * B + tl.b0;
+        __syncthreads();                                   // the previous tile's LDS is consumed
+        for (int t = tid; t <= tl.nb; t += NT) s_po[t] = offsets[g0 + t];
+        for (int s = tid; s < g.n; s += NT) s_hist[s] = 0;
+        if (tid == 0) s_flag = 0;
+        __syncthreads();
+        for (int t = tid; t < tl.nb; t += NT)
+            if (s_po[t] > s_po[t + 1] || s_po[t] < s_fb[f] || s_po[t + 1] > s_fb[f + 1]) s_flag = 1;
+        __syncthreads();
+        if (s_flag) {
+            if (tid == 0) atomicOr(&st[m.pack].error, 1);
+            continue;
+        }
+        const int dl = s_delta[f];
+        const int pbase = s_slotpos[k.first_slot];
+        for (int t = tid; t < tl.nb; t += NT)
+            packed_offsets[(int64_t)k.first_slot * B + m.pack + (int64_t)m.slot * B + tl.b0 + t] = s_po[t] + dl - pbase;
+        const int q_lo = s_po[0], q_hi = s_po[tl.nb];
+        for (int i0 = q_lo + tid; i0 < q_hi; i0 += 4 * NT) {
+            int64_t idv[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {                  // the loads of four rounds in flight together
+                const int i = i0 + j * NT;
+                idv[j] = i < q_hi ? ids[i] : 0;
+            }
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int i = i0 + j * NT;
+                if (i >= q_hi) continue;
+                const uint32_t kk = fold_id(idv[j], m.rows);
+                keys[i + dl] = m.base_row + kk;
+                atomicAdd(&s_hist[kk >> g.log_keys], 1);
+            }
+        }
+        __syncthreads();
+        const int slice0 = s_first[m.stable];
+        for (int s = tid; s < g.n; s += NT) {
+            const int c = s_hist[s];
+            if (c) atomicAdd(&slice_total[slice0 + s], c);
+        }
+    }
+}
+
+// Large batches: the slices' totals become places (one block: there are a few thousand slices).
+// Every slice gets its table, its index in the table, the place of its first record and the number
+// of records; the cursors of the scatter kernel start at those places.
+constexpr int kScanThreads = 1024;
+__global__ void __launch_bounds__(kScanThreads)
+pk_slice_scan_kernel(const TableMeta* __restrict__ tmeta, int T, int F, int64_t nnz, int target,
+                     const int32_t* __restrict__ slice_total, int32_t* __restrict__ slice_cursor,
+                     SliceInfo* __restrict__ slice_info, int n_slices)
+{
+    extern __shared__ int32_t s_first[];                   // [T+1]
+    table_scan<kScanThreads>(tmeta, T, F, nnz, target, s_first);
+    int carry = 0;
+    for (int base = 0; base < n_slices; base += kScanThreads) {
+        const int s = base + (int)threadIdx.x;
+        const int c = s < n_slices ? slice_total[s] : 0;
+        int tot;
+        const int ex = block_excl_scan<kScanThreads>(c, &tot);
+        if (s < n_slices) {
+            const int t = upper_bound_i32(s_first, T + 1, s) - 1;
+            SliceInfo si;
+            si.table = t; si.idx = s - s_first[t]; si.start = carry + ex; si.count = c;
+            slice_info[s] = si;
+            slice_cursor[s] = carry + ex;
+        }
+        carry += tot;
+    }
+}
+
+// Large batches: one record per occurrence, (key inside its slice, bag inside its pack), written to
+// the slice's place.  A tile counts its occurrences per slice in LDS, reserves room in every
+// touched slice with one global add, and then places its records from block-local cursors.
+template <int BT>
+__global__ void __launch_bounds__(NT)
+pk_scatter_kernel(const int32_t* __restrict__ offsets, int B, int F, int T, int64_t nnz, int target,
+                  const FieldMeta* __restrict__ fmeta, const PackMeta* __restrict__ pm,
+                  const TableMeta* __restrict__ tmeta, const int32_t* __restrict__ slot_field,
+                  const PackState* __restrict__ st, const uint32_t* __restrict__ keys, int32_t* slice_cursor,
+                  uint2* __restrict__ rec, int hist_words)
+{
+    extern __shared__ int32_t s_dyn[];                     // field scan | first slices | counts | places
+    __shared__ int32_t s_po[BT + 1];
+    int32_t* s_fb = s_dyn;
+    int32_t* s_delta = s_fb + (F + 1);
+    int32_t* s_slotpos = s_delta + F;
+    int32_t* s_first = s_slotpos + (F + 1);
+    int32_t* s_hist = s_first + (T + 1);
+    int32_t* s_place = s_hist + hist_words;
+    const int tid = threadIdx.x;
+    const int bad = field_scan<NT>(offsets, B, F, nnz, slot_field, s_fb, s_delta, s_slotpos);
+    table_scan<NT>(tmeta, T, F, nnz, target, s_first);
+    if (bad) return;
+    const int tpf = (B + BT - 1) / BT;
+    const int64_t n_tiles = (int64_t)F * tpf;
+    for (int64_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+        const TileOf tl(tile, tpf, B, BT);
+        const int f = tl.f;
+        const FieldMeta m = fmeta[f];
+        if (st[m.pack].error) continue;                    // the keys kernel rejected offsets of this pack
+        const TableMeta tm = tmeta[m.stable];
+        const SliceGeom g = slice_geom(tm.rows, tm.field_end - tm.field_begin, F, nnz, target);
+        const int64_t g0 = (int64_t)f * B + tl.b0;
+        __syncthreads();
+        for (int t = tid; t <= tl.nb; t += NT) s_po[t] = offsets[g0 + t];
+        for (int s = tid; s < g.n; s += NT) s_hist[s] = 0;
+        __syncthreads();
+        const int dl = s_delta[f];
+        const int q_lo = s_po[0], q_hi = s_po[tl.nb];
+        for (int i = q_lo + tid; i < q_hi; i += NT) {
+            const uint32_t s = (keys[i + dl] - m.base_row) >> g.log_keys;
+            if (s < (uint32_t)g.n) atomicAdd(&s_hist[s], 1);
+        }
+        __syncthreads();
+        const int slice0 = s_first[m.stable];
+        for (int s = tid; s < g.n; s += NT) {
+            const int c = s_hist[s];
+            s_place[s] = c ? atomicAdd(&slice_cursor[slice0 + s], c) : 0;
+            s_hist[s] = 0;
+        }
+        __syncthreads();
+        const uint32_t bag0 = (uint32_t)m.slot * (uint32_t)B + (uint32_t)tl.b0;
+        for (int i = q_lo + tid; i < q_hi; i += NT) {
+            const uint32_t kk = keys[i + dl] - m.base_row;
+            const uint32_t s = kk >> g.log_keys;
+            if (s >= (uint32_t)g.n) continue;
+            const int t = upper_bound_i32(s_po, tl.nb + 1, i) - 1;
+            const int64_t at = (int64_t)s_place[s] + atomicAdd(&s_hist[s], 1);
+            if ((uint64_t)at < (uint64_t)nnz) rec[at] = make_uint2(kk - (s << g.log_keys), bag0 + (uint32_t)t);
+        }
+    }
 }
 
 // ---------------------------------------------------------------------------
-// H2, first half: which rows occur.  Global atomics run at a fixed, low rate on
-// this GPU whatever their address, so the bitmap is not built with them: a block
-// owns a slice of a pack's key space, keeps the slice's bits in LDS, scans the
-// keys of the fields whose tables overlap the slice (they are contiguous in the
-// packed order) and stores the finished words with plain coalesced writes.
-// Every bitmap word is written by exactly one block, so nothing needs clearing.
+// The slice kernel's body.
 // ---------------------------------------------------------------------------
-constexpr int kMarkThreads = 1024;
-constexpr int kMarkUnroll = 8;
+constexpr int kSliceThreads = 1024;
 
-struct MarkArgs {
-    const MarkItem* items; const int32_t* item_fields; const PackMeta* pm; const PackState* st;
-    const int32_t* fb; const int32_t* delta; const uint32_t* keys; uint32_t* bitmap; int64_t nnz;
+struct SliceArgs {
+    const TableMeta* tmeta; const int32_t* table_fields; int T;
+    const FieldMeta* fmeta; const PackMeta* pm; const int32_t* slot_field; PackState* st; int P;
+    int F, B; int64_t nnz; int target;
+    const int64_t* ids; const int32_t* offsets;                 // small batches: the block finds its occurrences itself
+    const SliceInfo* slice_info; const uint2* rec;              // large batches: the slice's records
+    int32_t* packed_offsets;
+    uint32_t* keys; int32_t* inverse;                           // written here for small batches only
+    uint32_t* bitmap; int32_t* rank;                            // written here for large batches only
+    uint32_t* unique; int32_t* seg_all; uint32_t* ent_all; int ent_mult;
+    int4* tile_hdr; int tp; double* ghot; int dmax;
+    uint64_t* desc; int32_t* done; int n_slices;                // small batches: descriptors the library owns, cleaned by the last block
+    int64_t out_dim;
 };
 
-// set bit k of the slice if it is inside (one LDS read where the bit is already there)
-__device__ __forceinline__ void mark_bit(uint32_t* s_bits, uint32_t k, uint32_t span)
-{
-    if (k < span) {
-        const uint32_t bit = 1u << (k & 31);
-        if (!(s_bits[k >> 5] & bit)) atomicOr(&s_bits[k >> 5], bit);
-    }
-}
+// LDS of a slice block: bitmap words | their popcount prefix | counters of a round of distinct keys.
+// The same words first hold the set-up scans (first slices of the tables, then the field scan).
+constexpr int kSliceLds = 2 * kSliceWordsMax + kSliceRanks;
+static_assert(kSliceLds >= 3 * 4096 + 2 && kSliceLds >= 4096 + 1, "set-up scans must fit the slice block's LDS");
 
-// One slice.  FROM_IDS: the keys are formed here from the IDs of the fields (the same hash
-// as in keys_body), so that this does not have to wait for the keys kernel and can share
-// its launch; `ka` is then that kernel's argument block.
+// one occurrence of a slice: its key inside the slice and where it comes from
+struct SliceRec {
+    uint32_t kl;       // key minus the slice's first key
+    int32_t x;         // small batches: the field's index in the table's field list; large: the bag inside the pack
+    int32_t q;         // small batches: position in ids
+};
+
 template <bool FROM_IDS>
-__device__ __forceinline__ void mark_body(const MarkArgs& ma, const KeysArgs& ka, int item, uint32_t* s_bits)
+__device__ __forceinline__ void slice_body(const SliceArgs& a, int slice, int32_t* s_main, int32_t* s_tf)
 {
-    int mine = 0;
-    if (FROM_IDS) {                                        // the checks of keys_body, which runs beside this
-        for (int f = threadIdx.x; f < ka.F; f += kMarkThreads)
-            mine |= ka.offsets[(int64_t)(f + 1) * ka.B] < ka.offsets[(int64_t)f * ka.B];
-        if (threadIdx.x == 0) mine |= ka.offsets[0] != 0 || (int64_t)ka.offsets[(int64_t)ka.F * ka.B] != ka.nnz;
-    }
-    const MarkItem it = ma.items[item];
-    for (int w = threadIdx.x; w < it.n_words; w += kMarkThreads) s_bits[w] = 0;
-    const uint32_t span = (uint32_t)it.n_words * 32u;
-    int bad;
+    const int tid = threadIdx.x;
+    uint32_t* s_bits = reinterpret_cast<uint32_t*>(s_main);
+    uint32_t* s_pre = s_bits + kSliceWordsMax;
+    int32_t* s_cnt = s_main + 2 * kSliceWordsMax;
+    __shared__ uint32_t s_bc[4];
+    const int F = a.F, B = a.B, T = a.T;
+    const int64_t out_dim = a.out_dim;
+
+    // ---- which slice, of which table; where the pack's arrays start ----
+    int t, idx, pack_first, is_last, pstart, nnz_p, rec_start = 0, rec_count = 0;
     if (FROM_IDS) {
-        bad = __syncthreads_or(mine);
-    } else {
+        table_scan<kSliceThreads>(a.tmeta, T, F, a.nnz, a.target, s_main);
+        t = upper_bound_i32(s_main, T + 1, slice) - 1;
+        idx = slice - s_main[t];
+        const PackMeta k0 = a.pm[a.tmeta[t].pack];
+        pack_first = s_main[k0.first_stable];
+        is_last = slice + 1 == s_main[k0.first_stable + k0.n_stables];
         __syncthreads();
-        bad = ma.st[0].error;
+    } else {
+        const SliceInfo si = a.slice_info[slice];
+        t = si.table; idx = si.idx; rec_start = si.start; rec_count = si.count;
+        pack_first = 0; is_last = 0;
     }
-    if (!bad) {
-        for (int fi = it.field_begin; fi < it.field_end; ++fi) {
-            const int f = ma.item_fields[fi];
+    const TableMeta tm = a.tmeta[t];
+    const int p = tm.pack;
+    const PackMeta k = a.pm[p];
+    const int nf = tm.field_end - tm.field_begin;
+    const SliceGeom geo = slice_geom(tm.rows, nf, F, a.nnz, a.target);
+    const int lg = geo.log_keys;
+    uint32_t own_flags = 0;
+    if (FROM_IDS) {
+        int32_t* s_fb = s_main;
+        int32_t* s_delta = s_fb + (F + 1);
+        int32_t* s_slotpos = s_delta + F;
+        const int bad = field_scan<kSliceThreads>(a.offsets, B, F, a.nnz, a.slot_field, s_fb, s_delta, s_slotpos);
+        pstart = s_slotpos[k.first_slot];
+        nnz_p = s_slotpos[k.first_slot + k.n_fields] - pstart;
+        for (int j = tid; j < nf; j += kSliceThreads) {
+            const int f = a.table_fields[tm.field_begin + j];
+            s_tf[3 * j] = s_fb[f];
+            s_tf[3 * j + 1] = s_fb[f + 1];
+            s_tf[3 * j + 2] = s_delta[f];
+        }
+        __syncthreads();
+        if (bad) {                                         // every block sees the same boundaries: nobody publishes, nobody waits
+            if (is_last && tid == 0) { a.st[p].n_unique = 0; a.st[p].error = 1; }
+            return;
+        }
+        // the offsets of this slice's share of the table's bags: inside the field and not decreasing
+        int viol = 0;
+        const int b_lo = (int)((int64_t)B * idx / geo.n), b_hi = (int)((int64_t)B * (idx + 1) / geo.n);
+        for (int j = 0; j < nf; ++j) {
+            const int f = a.table_fields[tm.field_begin + j];
+            const int32_t* offs = a.offsets + (int64_t)f * B;
+            for (int b = b_lo + tid; b < b_hi; b += kSliceThreads) {
+                const int o0 = offs[b], o1 = offs[b + 1];
+                viol |= o0 > o1 || o0 < s_tf[3 * j] || o1 > s_tf[3 * j + 1];
+            }
+        }
+        if (__syncthreads_or(viol)) own_flags |= 1u;
+    } else {
+        pstart = a.st[p].start;
+        nnz_p = a.st[p].nnz;
+        pack_first = a.st[p].first_slice;
+        is_last = t == k.first_stable + k.n_stables - 1 && idx + 1 == geo.n;   // last slice of the pack's last table
+        if (a.st[p].error) return;                         // offsets of this pack were rejected: no block of it publishes or waits
+    }
+
+    const uint32_t lo = (uint32_t)idx << lg;               // first key of the slice inside its table
+    const uint32_t nkeys = min((uint32_t)1 << lg, tm.rows - lo);
+    const int words = 1 << (lg - 5);
+    const int32_t* __restrict__ tf = a.table_fields + tm.field_begin;
+
+    // all occurrences of the slice, in any order: fn(SliceRec)
+    auto for_records = [&](auto&& fn) {
+        if (FROM_IDS) {
+            for (int j = 0; j < nf; ++j) {
+                const int q0 = s_tf[3 * j], q1 = s_tf[3 * j + 1];
+                for (int i0 = q0 + tid; i0 < q1; i0 += 4 * kSliceThreads) {
+                    int64_t idv[4];
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        const int i = i0 + u * kSliceThreads;
+                        idv[u] = i < q1 ? a.ids[i] : 0;
+                    }
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        const int i = i0 + u * kSliceThreads;
+                        if (i >= q1) continue;
+                        const uint32_t kk = fold_id(idv[u], tm.rows);
+                        if ((kk >> lg) == (uint32_t)idx) fn(SliceRec{kk - lo, j, i});
+                    }
+                }
+            }
+        } else {
+            const uint2* __restrict__ rec = a.rec + rec_start;
+            for (int i0 = tid; i0 < rec_count; i0 += 4 * kSliceThreads) {
+                uint2 r[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int i = i0 + u * kSliceThreads;
+                    r[u] = i < rec_count ? rec[i] : make_uint2(0, 0);
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int i = i0 + u * kSliceThreads;
+                    if (i < rec_count && r[u].x < nkeys) fn(SliceRec{r[u].x, (int32_t)r[u].y, 0});
+                }
+            }
+        }
+    };
+
+    // ---- which keys occur ----
+    for (int w = tid; w < words; w += kSliceThreads) s_bits[w] = 0;
+    __syncthreads();
+    int mine = 0;
+    for_records([&](const SliceRec& r) {
+        const uint32_t bit = 1u << (r.kl & 31);
+        if (!(s_bits[r.kl >> 5] & bit)) atomicOr(&s_bits[r.kl >> 5], bit);
+        ++mine;
+    });
+    int n_rec;
+    (void)block_excl_scan<kSliceThreads>(mine, &n_rec);    // its barriers also complete the bitmap
+    if (!FROM_IDS) n_rec = rec_count;
+    // popcount prefix of the words: thread i owns words [i * wpt, (i + 1) * wpt)
+    const int wpt = max(1, words / kSliceThreads);
+    int c = 0;
+    if (tid * wpt < words)
+        for (int j = 0; j < wpt; ++j) c += __popc(s_bits[tid * wpt + j]);
+    int n_u;
+    const int ex = block_excl_scan<kSliceThreads>(c, &n_u);
+    if (tid * wpt < words) {
+        int run = ex;
+        for (int j = 0; j < wpt; ++j) {
+            s_pre[tid * wpt + j] = (uint32_t)run;
+            run += __popc(s_bits[tid * wpt + j]);
+        }
+    }
+    // ---- distinct keys and occurrences of the pack's slices before this one ----
+    if (tid < 64) {
+        uint32_t pa = 0, pb = 0, pf = 0;
+        if (slice == pack_first) {
+            if (tid == 0) publish_desc(a.desc + slice, make_desc(kDescPfx, (uint32_t)n_u, (uint32_t)n_rec, own_flags));
+        } else {
+            if (tid == 0) publish_desc(a.desc + slice, make_desc(kDescAgg, (uint32_t)n_u, (uint32_t)n_rec, own_flags));
+            lookback(a.desc, pack_first, slice, &pa, &pb, &pf);
+            if (tid == 0)
+                publish_desc(a.desc + slice, make_desc(kDescPfx, pa + (uint32_t)n_u, pb + (uint32_t)n_rec, pf | own_flags));
+        }
+        if (tid == 0) {
+            s_bc[0] = pa; s_bc[1] = pb; s_bc[2] = pf | own_flags;
             if (FROM_IDS) {
-                const FieldMeta m = ka.fmeta[f];
-                const int64_t q0 = ka.offsets[(int64_t)f * ka.B], q1 = ka.offsets[(int64_t)(f + 1) * ka.B];
-                const uint32_t base = m.base_row - it.key_lo;      // modulo 2^32, like the subtraction below
-                int64_t q = q0 + threadIdx.x;
-                for (; q + (kMarkUnroll - 1) * kMarkThreads < q1; q += kMarkUnroll * kMarkThreads) {
-                    int64_t id[kMarkUnroll];
-#pragma unroll
-                    for (int j = 0; j < kMarkUnroll; ++j) id[j] = ka.ids[q + j * kMarkThreads];
-#pragma unroll
-                    for (int j = 0; j < kMarkUnroll; ++j) mark_bit(s_bits, base + fold_id(id[j], m.rows), span);
-                }
-                for (; q < q1; q += kMarkThreads) mark_bit(s_bits, base + fold_id(ka.ids[q], m.rows), span);
-            } else {
-                const int64_t q0 = (int64_t)ma.fb[f] + ma.delta[f], q1 = (int64_t)ma.fb[f + 1] + ma.delta[f];
-                if (q0 < 0 || q1 > ma.nnz) continue;
-                int64_t q = q0 + threadIdx.x;
-                for (; q + (kMarkUnroll - 1) * kMarkThreads < q1; q += kMarkUnroll * kMarkThreads) {
-                    uint32_t k[kMarkUnroll];
-#pragma unroll
-                    for (int j = 0; j < kMarkUnroll; ++j) k[j] = ma.keys[q + j * kMarkThreads] - it.key_lo;   // loads in flight together
-#pragma unroll
-                    for (int j = 0; j < kMarkUnroll; ++j) mark_bit(s_bits, k[j], span);
-                }
-                for (; q < q1; q += kMarkThreads) mark_bit(s_bits, ma.keys[q] - it.key_lo, span);
+                // The descriptors belong to the library and must be zero when the next call starts: the
+                // block that finishes its look-back last (every block has then published, and read what
+                // it needed) clears them.  Reading the own descriptor back first makes sure that the
+                // store has arrived before this block counts as finished (same address: same order).
+                const uint64_t back = __hip_atomic_load(a.desc + slice, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                s_bc[3] = ((back >> 62) == kDescPfx && atomicAdd(a.done, 1) == a.n_slices - 1) ? 1u : 0u;
             }
         }
     }
     __syncthreads();
-    uint4* dst = reinterpret_cast<uint4*>(ma.bitmap + (size_t)ma.pm[it.pack].first_tile * kTileWords + it.key_lo / 32);
-    const uint4* src = reinterpret_cast<const uint4*>(s_bits);
-    for (int w = threadIdx.x; w < it.n_words / 4; w += kMarkThreads) dst[w] = src[w];
-}
+    const int base_u = (int)s_bc[0];
+    const int rec_before = FROM_IDS ? (int)s_bc[1] : rec_start - pstart;
+    const uint32_t flags = s_bc[2];
+    if (FROM_IDS && s_bc[3]) {
+        for (int i = tid; i < a.n_slices; i += kSliceThreads) publish_desc(a.desc + i, 0);
+        if (tid == 0) *a.done = 0;
+    }
 
-__global__ void __launch_bounds__(kMarkThreads)
-pk_mark_kernel(MarkArgs ma)
-{
-    __shared__ uint32_t s_bits[kMarkWords];
-    mark_body<false>(ma, KeysArgs{}, blockIdx.x, s_bits);
-}
+    // whatever the descriptors held, no write below leaves the pack's arrays
+    if (base_u < 0 || rec_before < 0 || (int64_t)base_u + n_u > (int64_t)nnz_p || (int64_t)rec_before + n_rec > (int64_t)nnz_p) {
+        if (tid == 0) atomicOr(&a.st[p].error, 2);
+        return;
+    }
 
-// Small batches: the keys and the bitmap in one launch.  Blocks [0, mark_blocks) take the
-// slices and form the keys they need themselves; the others are the keys kernel.  (With few
-// occurrences every launch is mostly latency, and the second one would wait for the first.)
-constexpr int kFusedKeysBags = 1024;       // bags per block iteration of the keys part
-template <int BT>
-__global__ void __launch_bounds__(kMarkThreads)
-pk_keys_mark_kernel(const int64_t* __restrict__ ids, const int32_t* __restrict__ offsets, int B, int F, int P,
-                    int64_t nnz, const FieldMeta* __restrict__ fmeta, const PackMeta* __restrict__ pm,
-                    const int32_t* __restrict__ slot_field, PackState* st, int32_t* fb_out, int32_t* delta_out,
-                    uint32_t* __restrict__ keys, uint32_t* __restrict__ bagref, uint32_t* __restrict__ baglen,
-                    int32_t* __restrict__ packed_offsets, int64_t out_dim, uint4* clear4, int64_t n_clear4,
-                    MarkArgs ma, int mark_blocks)
-{
-    __shared__ uint32_t s_raw[kMarkWords];                 // either role's LDS
-    const KeysArgs ka{ids, offsets, B, F, P, nnz, fmeta, pm, slot_field, st, fb_out, delta_out, keys, bagref, baglen,
-                      packed_offsets, out_dim, clear4, n_clear4};
-    if ((int)blockIdx.x < mark_blocks)
-        mark_body<true>(ma, ka, blockIdx.x, s_raw);
-    else
-        keys_core<BT, kMarkThreads>(ids, offsets, fmeta, pm, slot_field, keys, bagref, baglen, packed_offsets, ka,
-                                    (int)blockIdx.x - mark_blocks, (int)gridDim.x - mark_blocks,
-                                    reinterpret_cast<int32_t*>(s_raw),
-                                    reinterpret_cast<int32_t*>(s_raw) + keys_bag_words<BT>());
-}
-
-// ---------------------------------------------------------------------------
-// H2 (Unique, Sec. II-D) via a bitmap over the pack's rows: the ascending
-// distinct keys are the set bits in order, and the index of a key among them is
-// the number of set bits before it.  One pass: popcount per 256-bit block,
-// prefix over all blocks of the pack, rank samples, distinct keys written out.
-// ---------------------------------------------------------------------------
-// A block iteration scans a run of K tiles of one pack (K * kTileWords bitmap words, every
-// thread K consecutive 256-bit blocks): with several thousand tiles, fewer and larger steps
-// keep the chain of prefixes short.
-template <int K>
-__global__ void __launch_bounds__(NT, 4)   // four blocks per CU must fit: 1024 blocks resident at once
-pk_tiles_kernel(const uint4* __restrict__ bitmap4, uint64_t* tile_desc, int n_runs_total,
-                const PackMeta* __restrict__ pm, PackState* st, int P,
-                int32_t* __restrict__ rank, uint32_t* __restrict__ unique)
-{
-    __shared__ uint32_t s_pre;
-    // Block b takes runs b, b+G, b+2G, ...: a run waits for the runs before it, those of
-    // other blocks' earlier rounds included; the launch keeps G small enough for all blocks
-    // to be resident, so the waits end.
-    int p = 0, first = 0;                                  // the pack of the run, the pack's first run
-    for (int run = blockIdx.x; run < n_runs_total; run += gridDim.x) {
-        while (p + 1 < P && run >= first + (pm[p].n_tiles + K - 1) / K) {
-            first += (pm[p].n_tiles + K - 1) / K;
-            ++p;
-        }
-        const int n_blocks = pm[p].n_tiles * NT;           // 256-bit blocks of the pack
-        const int b0 = ((run - first) * NT + (int)threadIdx.x) * K;   // this thread's first one
-        const size_t t0 = (size_t)pm[p].first_tile * NT + b0;
-        uint32_t w[K][8];
-        int c[K], mine = 0;
-#pragma unroll
-        for (int k = 0; k < K; ++k) {
-            uint4 a = make_uint4(0, 0, 0, 0), b = a;
-            if (b0 + k < n_blocks) { a = bitmap4[2 * (t0 + k)]; b = bitmap4[2 * (t0 + k) + 1]; }
-            w[k][0] = a.x; w[k][1] = a.y; w[k][2] = a.z; w[k][3] = a.w;
-            w[k][4] = b.x; w[k][5] = b.y; w[k][6] = b.z; w[k][7] = b.w;
-            c[k] = 0;
-#pragma unroll
-            for (int i = 0; i < 8; ++i) c[k] += __popc(w[k][i]);
-            mine += c[k];
-        }
-        int tot;
-        const int ex = block_excl_scan<NT>(mine, &tot);    // its barriers also fence s_pre between rounds
-        if (threadIdx.x < 64) {
-            if (run == first) {
-                if (threadIdx.x == 0) { publish_desc(tile_desc + run, make_desc(kDescPfx, (uint32_t)tot, 0)); s_pre = 0; }
-            } else {
-                if (threadIdx.x == 0) publish_desc(tile_desc + run, make_desc(kDescAgg, (uint32_t)tot, 0));
-                uint32_t pa, pb;
-                lookback(tile_desc, first, run, &pa, &pb, &st[0].error);
-                if (threadIdx.x == 0) {
-                    publish_desc(tile_desc + run, make_desc(kDescPfx, pa + (uint32_t)tot, 0));
-                    s_pre = pa;
-                }
-            }
-        }
-        __syncthreads();
-        int pre = (int)s_pre + ex;
-        if (run == first + (pm[p].n_tiles + K - 1) / K - 1 && threadIdx.x == 0) st[p].n_unique = (int)s_pre + tot;
-        uint32_t* uq = unique + st[p].start;
-#pragma unroll
-        for (int k = 0; k < K; ++k) {
-            if (b0 + k >= n_blocks) break;
-            rank[t0 + k] = pre;
-            if (c[k] != 0) {
-                const uint32_t key0 = (uint32_t)(b0 + k) * 256u;
-#pragma unroll
-                for (int i = 0; i < 8; ++i) {
-                    uint32_t x = w[k][i];
-                    while (x) {
-                        const int bit = __ffs(x) - 1;
-                        x &= x - 1;
-                        uq[pre] = key0 + i * 32 + bit;
-                        ++pre;
-                    }
-                }
+    // ---- the slice's distinct keys, ascending; bitmap and rank samples for the inverse kernel ----
+    uint32_t* __restrict__ uq = a.unique + pstart;
+    int32_t* __restrict__ seg = a.seg_all + pstart + p;
+    if (tid * wpt < words) {
+        for (int j = 0; j < wpt; ++j) {
+            const int w = tid * wpt + j;
+            uint32_t x = s_bits[w];
+            int at = base_u + (int)s_pre[w];
+            const uint32_t key0 = tm.key_lo + lo + (uint32_t)w * 32u;
+            while (x) {
+                const int bit = __ffs(x) - 1;
+                x &= x - 1;
+                uq[at++] = key0 + bit;
             }
         }
     }
+    if (!FROM_IDS) {
+        const size_t w0 = (size_t)tm.word_base + (size_t)idx * words;
+        for (int w = tid; w < words; w += kSliceThreads) {
+            a.bitmap[w0 + w] = s_bits[w];
+            if ((w & (kRankWords - 1)) == 0) a.rank[(w0 + w) / kRankWords] = base_u + (int)s_pre[w];
+        }
+    }
+    if (is_last && tid == 0) {
+        a.st[p].n_unique = base_u + n_u;
+        seg[base_u + n_u] = nnz_p;
+        if (FROM_IDS) a.st[p].error = (int32_t)flags;
+        else if (flags) atomicOr(&a.st[p].error, (int32_t)flags);
+    }
+
+    // ---- occurrences per distinct key, segment offsets, headers of the backward tiles, and every
+    //      occurrence's gradient place at its key's next free position; a round handles kSliceRanks keys ----
+    const int tp = a.tp, dim = k.dim;
+    const bool wide = k.has_mean != 0;                     // the pack's entries carry the bag length
+    uint32_t* __restrict__ ent = a.ent_all + (size_t)pstart * a.ent_mult;
+    const size_t tbase = (size_t)(pstart / tp + p);
+    int4* th = a.tile_hdr + tbase;
+    double* gh = a.ghot + tbase * a.dmax;
+    const int32_t* __restrict__ po = a.packed_offsets + (int64_t)k.first_slot * B + p;
+    auto rank_of = [&](uint32_t kl) {
+        return (int)(s_pre[kl >> 5] + __popc(s_bits[kl >> 5] & ((1u << (kl & 31)) - 1u)));
+    };
+    int placed = 0;                                        // occurrences of the keys of earlier rounds
+    for (int r0 = 0; r0 < n_u; r0 += kSliceRanks) {
+        const int width = min(kSliceRanks, n_u - r0);
+        __syncthreads();
+        for (int i = tid; i < width; i += kSliceThreads) s_cnt[i] = 0;
+        __syncthreads();
+        for_records([&](const SliceRec& r) {
+            const uint32_t rr = (uint32_t)(rank_of(r.kl) - r0);
+            if (rr < (uint32_t)width) atomicAdd(&s_cnt[rr], 1);
+        });
+        __syncthreads();
+        constexpr int per = kSliceRanks / kSliceThreads;   // consecutive counters per thread
+        int sum = 0;
+#pragma unroll
+        for (int j = 0; j < per; ++j) {
+            const int i = tid * per + j;
+            sum += i < width ? s_cnt[i] : 0;
+        }
+        int tot;
+        int s0 = rec_before + placed + block_excl_scan<kSliceThreads>(sum, &tot);
+#pragma unroll
+        for (int j = 0; j < per; ++j) {
+            const int i = tid * per + j;
+            if (i < width) {
+                const int len = s_cnt[i];
+                const int u = base_u + r0 + i;
+                seg[u] = s0;
+                s_cnt[i] = s0;                             // from here on: the segment's next free position
+                // headers of the backward tiles the segment overlaps: x = the key that holds the
+                // tile's first position, y = the key that holds its last one, z = where the
+                // tile's decoded window ends (its last key is decoded to its end unless it is long)
+                for (int tt = s0 / tp; (int64_t)tt * tp < (int64_t)s0 + len; ++tt) {
+                    const int t_first = tt * tp, t_end = min(t_first + tp, nnz_p);
+                    if (t_first >= s0) th[tt].x = u;
+                    if (t_end - 1 < s0 + len) {
+                        th[tt].y = u;
+                        th[tt].z = len <= kWarmMax ? s0 + len : t_end;
+                    }
+                }
+                if (len > kWarmMax && s0 / tp != (s0 + len - 1) / tp) {
+                    const int slot = s0 / tp;              // one such key at most starts in a tile
+                    for (int d = 0; d < dim; ++d) gh[(size_t)slot * dim + d] = 0.0;
+                }
+                s0 += len;
+            }
+        }
+        __syncthreads();
+        for_records([&](const SliceRec& r) {
+            const int rk = rank_of(r.kl);
+            const uint32_t rr = (uint32_t)(rk - r0);
+            if (rr >= (uint32_t)width) return;
+            const int pos = atomicAdd(&s_cnt[rr], 1);
+            uint32_t ref, len;
+            if (FROM_IDS) {
+                const int f = tf[r.x];
+                const FieldMeta m = a.fmeta[f];
+                const int32_t* offs = a.offsets + (int64_t)f * B;
+                const int b = find_bag(offs, B, r.q, r.q - s_tf[3 * r.x]);
+                const int L = offs[b + 1] - offs[b];
+                ref = (uint32_t)((int64_t)b * out_dim + m.col);
+                len = (m.pool == PK_MEAN && L > 0) ? (uint32_t)L : 1u;
+                const int qp = r.q + s_tf[3 * r.x + 2];
+                if ((unsigned)qp < (unsigned)a.nnz) {
+                    a.keys[qp] = tm.key_lo + lo + r.kl;
+                    a.inverse[qp] = base_u + rk;
+                }
+            } else {
+                const uint32_t g = (uint32_t)r.x;
+                const uint32_t slot = g / (uint32_t)B, b = g - slot * (uint32_t)B;
+                const int f = slot < (uint32_t)k.n_fields ? a.slot_field[k.first_slot + (int)slot] : a.slot_field[k.first_slot];
+                const FieldMeta m = a.fmeta[f];
+                ref = (uint32_t)((int64_t)b * out_dim + m.col);
+                len = 1u;
+                if (wide && m.pool == PK_MEAN && slot < (uint32_t)k.n_fields) {
+                    const int L = po[g + 1] - po[g];
+                    if (L > 0) len = (uint32_t)L;
+                }
+            }
+            if ((unsigned)pos < (unsigned)nnz_p) {
+                if (wide) reinterpret_cast<uint2*>(ent)[pos] = make_uint2(ref, len);
+                else ent[pos] = ref;
+            }
+        });
+        placed += tot;
+    }
 }
 
-// inverse[q] = number of distinct keys below key[q]: the rank sample of the key's
-// 256-bit block plus the set bits before it inside the block.
-template <int KT>
-__global__ void __launch_bounds__(NT)
-pk_inverse_kernel(const PackMeta* __restrict__ pm, const PackState* __restrict__ st,
-                  const uint32_t* __restrict__ keys, const uint4* __restrict__ bitmap4,
-                  const int32_t* __restrict__ rank, int32_t* __restrict__ inverse)
+// Large batches: one block per slice.  (Block i takes slice i; see the look-back's note on order.)
+__global__ void __launch_bounds__(kSliceThreads)
+pk_slices_kernel(SliceArgs a)
 {
-    const int p = blockIdx.y;
-    const int n = st[p].nnz, start = st[p].start;
-    const size_t rb = (size_t)pm[p].first_tile * NT;          // rank blocks before this pack
-    const uint4* bm = bitmap4 + 2 * rb;
-    const int32_t* rk = rank + rb;
-    const int n_tiles = (n + KT - 1) / KT;
-    for (XcdTiles it(n_tiles); it.valid(); it.next()) {
-        uint32_t key[KT / NT];
-#pragma unroll
-        for (int k = 0; k < KT / NT; ++k) {
-            const int q = it.tile * KT + k * NT + threadIdx.x;
-            key[k] = q < n ? keys[start + q] : 0;
+    __shared__ int32_t s_main[kSliceLds];
+    slice_body<false>(a, blockIdx.x, s_main, nullptr);
+}
+
+// Small batches: the blocks beside the slice blocks that write what is per bag and per pack:
+// packed bag offsets and the packs' sizes.  (The slice blocks check the offsets.)
+__device__ __forceinline__ void meta_body(const SliceArgs& a, int block, int nblocks, int32_t* s_main)
+{
+    const int F = a.F, B = a.B, P = a.P, tid = threadIdx.x;
+    int32_t* s_fb = s_main;
+    int32_t* s_delta = s_fb + (F + 1);
+    int32_t* s_slotpos = s_delta + F;
+    const int bad = field_scan<kSliceThreads>(a.offsets, B, F, a.nnz, a.slot_field, s_fb, s_delta, s_slotpos);
+    if (block == 0) {
+        for (int p = tid; p < P; p += kSliceThreads) {
+            const PackMeta k = a.pm[p];
+            const int start = s_slotpos[k.first_slot];
+            const int n = s_slotpos[k.first_slot + k.n_fields] - start;
+            a.st[p].nnz = n;
+            a.st[p].start = start;
+            a.st[p].first_slice = 0;
+            if (k.n_stables == 0) {                        // no slice block writes these
+                a.st[p].n_unique = 0;
+                a.st[p].error = bad ? 1 : 0;
+                a.seg_all[start + p] = 0;
+            }
+            a.packed_offsets[(int64_t)k.first_slot * B + p + (int64_t)k.n_fields * B] = n;
         }
+    }
+    if (bad) return;
+    int32_t* po = a.packed_offsets;
+    const int64_t n_bags = (int64_t)F * B;
+    for (int64_t g = (int64_t)block * kSliceThreads + tid; g < n_bags; g += (int64_t)nblocks * kSliceThreads) {
+        const int f = (int)(g / B);
+        const int b = (int)(g - (int64_t)f * B);
+        const FieldMeta m = a.fmeta[f];
+        const PackMeta k = a.pm[m.pack];
+        const int o = min(max(a.offsets[g], s_fb[f]), s_fb[f + 1]);
+        po[(int64_t)k.first_slot * B + m.pack + (int64_t)m.slot * B + b] = o + s_delta[f] - s_slotpos[k.first_slot];
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Large batches: inverse[q] = number of distinct keys of the pack below key[q]: the rank sample of
+// the key's 256-key block (written by the slice kernel) plus the set bits before the key inside
+// the block.  Tiles as in the keys kernel: bags of one field, hence one table.
+// ---------------------------------------------------------------------------
+template <int BT>
+__global__ void __launch_bounds__(NT)
+pk_inverse_kernel(const int32_t* __restrict__ offsets, int B, int F, int64_t nnz, const FieldMeta* __restrict__ fmeta,
+                  const TableMeta* __restrict__ tmeta, const int32_t* __restrict__ slot_field,
+                  const PackState* __restrict__ st, const uint32_t* __restrict__ keys,
+                  const uint4* __restrict__ bitmap4, const int32_t* __restrict__ rank, int32_t* __restrict__ inverse)
+{
+    extern __shared__ int32_t s_dyn[];
+    int32_t* s_fb = s_dyn;
+    int32_t* s_delta = s_fb + (F + 1);
+    int32_t* s_slotpos = s_delta + F;
+    const int tid = threadIdx.x;
+    if (field_scan<NT>(offsets, B, F, nnz, slot_field, s_fb, s_delta, s_slotpos)) return;
+    const int tpf = (B + BT - 1) / BT;
+    const int64_t n_tiles = (int64_t)F * tpf;
+    for (int64_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+        const TileOf tl(tile, tpf, B, BT);
+        const int f = tl.f;
+        const FieldMeta m = fmeta[f];
+        if (st[m.pack].error) continue;
+        const TableMeta tm = tmeta[m.stable];
+        const int64_t g0 = (int64_t)f * B + tl.b0;
+        const int q_lo = min(max(offsets[g0], s_fb[f]), s_fb[f + 1]) + s_delta[f];
+        const int q_hi = min(max(offsets[g0 + tl.nb], s_fb[f]), s_fb[f + 1]) + s_delta[f];
+        const uint4* bm = bitmap4 + (size_t)tm.word_base / 4;
+        const int32_t* rk = rank + (size_t)tm.word_base / kRankWords;
+        for (int q0 = q_lo + tid; q0 < q_hi; q0 += 4 * NT) {
+            uint32_t kk[4];
 #pragma unroll
-        for (int k = 0; k < KT / NT; ++k) {
-            const int q = it.tile * KT + k * NT + threadIdx.x;
-            if (q < n) {
-                const uint32_t blk = key[k] >> 8;
-                const int wi = (key[k] >> 5) & 7;
-                const uint4 a = bm[2 * (size_t)blk], b = bm[2 * (size_t)blk + 1];
-                const uint32_t w[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+            for (int j = 0; j < 4; ++j) {
+                const int q = q0 + j * NT;
+                kk[j] = q < q_hi ? keys[q] - tm.key_lo : 0;
+            }
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int q = q0 + j * NT;
+                if (q >= q_hi || kk[j] >= tm.rows) continue;
+                const uint32_t blk = kk[j] >> 8;
+                const int wi = (kk[j] >> 5) & 7;
+                const uint4 x = bm[2 * (size_t)blk], y = bm[2 * (size_t)blk + 1];
+                const uint32_t w[8] = {x.x, x.y, x.z, x.w, y.x, y.y, y.z, y.w};
                 int r = rk[blk];
                 uint32_t cur = 0;
 #pragma unroll
@@ -396,283 +738,9 @@ pk_inverse_kernel(const PackMeta* __restrict__ pm, const PackState* __restrict__
                     if (i < wi) r += __popc(w[i]);
                     if (i == wi) cur = w[i];
                 }
-                r += __popc(cur & ((1u << (key[k] & 31)) - 1u));
-                inverse[start + q] = r;
+                r += __popc(cur & ((1u << (kk[j] & 31)) - 1u));
+                inverse[q] = r;
             }
         }
     }
-}
-
-// number of distinct keys of the pack below `key` (key may be absent, or one past the last row)
-__device__ __forceinline__ int rank_of_key(const uint4* __restrict__ bm, const int32_t* __restrict__ rk,
-                                           uint64_t key64, uint64_t key_end, int n_unique)
-{
-    if (key64 >= key_end) return n_unique;
-    const uint32_t key = (uint32_t)key64;
-    const uint32_t blk = key >> 8;
-    const int wi = (key >> 5) & 7;
-    const uint4 a = bm[2 * (size_t)blk], b = bm[2 * (size_t)blk + 1];
-    const uint32_t w[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
-    int r = rk[blk];
-    uint32_t cur = 0;
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        if (i < wi) r += __popc(w[i]);
-        if (i == wi) cur = w[i];
-    }
-    return r + __popc(cur & ((1u << (key & 31)) - 1u));
-}
-
-// H2, last part: the occurrences grouped by distinct key (a counting sort by
-// rank), the segment offsets, and what the backward pass needs to cut its work
-// by occurrences -- in one kernel and without global atomics.
-//
-// A table's distinct keys are a contiguous range of ranks, and its occurrences
-// are the occurrences of the fields that read it (contiguous in the packed
-// order).  A work item is one table and up to kSortCap of its ranks; which items
-// exist depends on the batch, so every block derives the list for itself from
-// the rank samples.  An item
-//   1. counts the occurrences of each of its ranks in LDS,
-//   2. scans the counts, learns the number of occurrences before it from the
-//      items before it (descriptor look-back), and writes the segment offsets,
-//      for each backward tile the key that holds the tile's first position, and
-//      zeroed partial sums for keys that are long and cross a tile boundary,
-//   3. passes over the occurrences again and stores each one's gradient place
-//      (and mean-pooling scale) at its segment's next free position.
-// Block b takes items b, b+G, ...: an item only waits for lower items, which are
-// in earlier rounds or in lower blocks of this round; G is small enough for all
-// blocks to be resident, so the waits end.
-constexpr int kSortThreads = 1024;
-constexpr int kSortUnroll2 = 4;       // occurrences per thread in flight in the placing pass
-
-struct SortArgs {
-    const TableMeta* tmeta; const int32_t* table_fields; int T;
-    const PackMeta* pm; PackState* st; int P;
-    const int32_t* fb; const int32_t* delta;
-    const uint4* bitmap4; const int32_t* rank;
-    const int32_t* inverse; const uint32_t* bagref; const uint32_t* baglen;
-    int32_t* seg_all; uint32_t* ent_all; int ent_mult;
-    int4* tile_hdr; int tp; uint64_t* desc; double* ghot; int dmax;
-    int64_t nnz;
-};
-
-// What a work item (a table's ranks [c0, c0 + width), width counters in s_cnt) needs to know
-struct SortItem {
-    TableMeta tm;
-    int p;               // pack
-    int dim, wide;       // the pack's dimension; its entries carry the bag length (mean pooling)
-    int n, start;        // occurrences of the pack, position of its first one in the packed order
-    int c0;
-    uint32_t width;
-};
-
-// Step 1 of an item: occurrences per rank, counted in LDS.  Returns this thread's share of
-// the counters (`per` consecutive ones starting at tid * per), scanned over the block.
-__device__ __forceinline__ int sort_count(const SortArgs& sa, const SortItem& it, int32_t* s_cnt, int* per_out,
-                                          int* n_item)
-{
-    const int tid = threadIdx.x;
-    const int32_t* inverse = sa.inverse;
-    __syncthreads();                               // the previous use of s_cnt is over
-    for (int i = tid; i < (int)it.width; i += kSortThreads) s_cnt[i] = 0;
-    __syncthreads();
-    for (int fi = it.tm.field_begin; fi < it.tm.field_end; ++fi) {
-        const int f = sa.table_fields[fi];
-        const int64_t q0 = (int64_t)sa.fb[f] + sa.delta[f], q1 = (int64_t)sa.fb[f + 1] + sa.delta[f];
-        if (q0 < 0 || q1 > sa.nnz) continue;
-        int64_t q = q0 + tid;
-        for (; q + (kMarkUnroll - 1) * kSortThreads < q1; q += kMarkUnroll * kSortThreads) {
-            uint32_t r[kMarkUnroll];
-#pragma unroll
-            for (int j = 0; j < kMarkUnroll; ++j) r[j] = (uint32_t)(inverse[q + j * kSortThreads] - it.c0);
-#pragma unroll
-            for (int j = 0; j < kMarkUnroll; ++j)
-                if (r[j] < it.width) atomicAdd(&s_cnt[r[j]], 1);
-        }
-        for (; q < q1; q += kSortThreads) {
-            const uint32_t r0 = (uint32_t)(inverse[q] - it.c0);
-            if (r0 < it.width) atomicAdd(&s_cnt[r0], 1);
-        }
-    }
-    __syncthreads();
-    const int per = ((int)it.width + kSortThreads - 1) / kSortThreads;   // consecutive counters per thread
-    int mine = 0;
-    for (int j = 0; j < per; ++j) {
-        const int i = tid * per + j;
-        mine += i < (int)it.width ? s_cnt[i] : 0;
-    }
-    *per_out = per;
-    return block_excl_scan<kSortThreads>(mine, n_item);
-}
-
-// Steps 2 and 3 of an item, given the occurrences of the pack before it: segment offsets,
-// headers of the backward tiles, zeroed partial sums for long keys that cross tile
-// boundaries; then every occurrence's gradient place goes to its segment's cursor.
-__device__ __forceinline__ void sort_place(const SortArgs& sa, const SortItem& it, int32_t* s_cnt, int before,
-                                           int ex, int per)
-{
-    const int tid = threadIdx.x;
-    const int tp = sa.tp, n = it.n;
-    const int32_t* inverse = sa.inverse;
-    int32_t* seg = sa.seg_all + it.start + it.p;
-    uint32_t* ent = sa.ent_all + (size_t)it.start * sa.ent_mult;
-    const size_t tbase = (size_t)(it.start / tp + it.p);
-    int4* th = sa.tile_hdr + tbase;
-    double* gh = sa.ghot + tbase * sa.dmax;
-    const bool wide = it.wide != 0;
-    int s0 = before + ex;
-    for (int j = 0; j < per; ++j) {
-        const int i = tid * per + j;
-        if (i < (int)it.width) {
-            const int len = s_cnt[i];
-            seg[it.c0 + i] = s0;
-            s_cnt[i] = s0;                                 // from here on: the segment's next free position
-            // headers of the backward tiles the segment overlaps: x = the key that holds the
-            // tile's first position, y = the key that holds its last one, z = where the
-            // tile's decoded window ends (its last key is decoded to its end unless it is long)
-            for (int tt = s0 / tp; (int64_t)tt * tp < (int64_t)s0 + len; ++tt) {
-                const int t_first = tt * tp, t_end = min(t_first + tp, n);
-                if (t_first >= s0) th[tt].x = it.c0 + i;
-                if (t_end - 1 < s0 + len) {
-                    th[tt].y = it.c0 + i;
-                    th[tt].z = len <= kWarmMax ? s0 + len : t_end;
-                }
-            }
-            if (len > kWarmMax && s0 / tp != (s0 + len - 1) / tp) {
-                const int slot = s0 / tp;                  // one such key at most starts in a tile
-                for (int d = 0; d < it.dim; ++d) gh[(size_t)slot * it.dim + d] = 0.0;
-            }
-            s0 += len;
-        }
-    }
-    __syncthreads();
-    for (int fi = it.tm.field_begin; fi < it.tm.field_end; ++fi) {
-        const int f = sa.table_fields[fi];
-        const int64_t q0 = (int64_t)sa.fb[f] + sa.delta[f], q1 = (int64_t)sa.fb[f + 1] + sa.delta[f];
-        if (q0 < 0 || q1 > sa.nnz) continue;
-        int64_t q = q0 + tid;
-        for (; q + (kSortUnroll2 - 1) * kSortThreads < q1; q += kSortUnroll2 * kSortThreads) {
-            uint32_t r[kSortUnroll2], e[kSortUnroll2], c[kSortUnroll2];
-#pragma unroll
-            for (int j = 0; j < kSortUnroll2; ++j) {
-                r[j] = (uint32_t)(inverse[q + j * kSortThreads] - it.c0);
-                e[j] = sa.bagref[q + j * kSortThreads];
-                c[j] = wide ? sa.baglen[q + j * kSortThreads] : 1u;
-            }
-#pragma unroll
-            for (int j = 0; j < kSortUnroll2; ++j)
-                if (r[j] < it.width) {
-                    const int pos = atomicAdd(&s_cnt[r[j]], 1);
-                    if ((unsigned)pos < (unsigned)n) {
-                        if (wide) reinterpret_cast<uint2*>(ent)[pos] = make_uint2(e[j], c[j]);
-                        else ent[pos] = e[j];
-                    }
-                }
-        }
-        for (; q < q1; q += kSortThreads) {
-            const uint32_t r0 = (uint32_t)(inverse[q] - it.c0);
-            if (r0 < it.width) {
-                const int pos = atomicAdd(&s_cnt[r0], 1);
-                if ((unsigned)pos < (unsigned)n) {
-                    if (wide) reinterpret_cast<uint2*>(ent)[pos] = make_uint2(sa.bagref[q], sa.baglen[q]);
-                    else ent[pos] = sa.bagref[q];
-                }
-            }
-        }
-    }
-}
-
-// `block` of `nblocks` blocks of kSortThreads threads; s_dyn: (4 T + 1) ints of LDS
-__device__ __forceinline__ void sort_body(const SortArgs& sa, int block, int nblocks, int32_t* s_dyn)
-{
-    const TableMeta* __restrict__ tmeta = sa.tmeta;
-    const int T = sa.T, P = sa.P;
-    const PackMeta* __restrict__ pm = sa.pm;
-    PackState* st = sa.st;
-    const int32_t* __restrict__ fb = sa.fb;
-    const uint4* __restrict__ bitmap4 = sa.bitmap4;
-    const int32_t* __restrict__ rank = sa.rank;
-    int32_t* s_rlo = s_dyn;                  // [T]   first rank of each table inside its pack
-    int32_t* s_u = s_dyn + T;                // [T]   distinct keys of each table
-    int32_t* s_first = s_u + T;              // [T+1] first work item of each table
-    int32_t* s_occ = s_first + T + 1;        // [T]   occurrences in the tables before (all packs)
-    __shared__ int32_t s_cnt[kSortCap];
-    __shared__ uint32_t s_base;
-    const int tid = threadIdx.x;
-    if (st[0].error) return;
-    int carry = 0, carry_occ = 0;
-    for (int base = 0; base < T; base += kSortThreads) {
-        const int t = base + tid;
-        int chunks = 0, occ = 0;
-        if (t < T) {
-            const TableMeta tm = tmeta[t];
-            for (int fi = tm.field_begin; fi < tm.field_end; ++fi) {
-                const int f = sa.table_fields[fi];
-                occ += fb[f + 1] - fb[f];
-            }
-            const PackMeta k = pm[tm.pack];
-            const size_t rb = (size_t)k.first_tile * NT;
-            const uint64_t key_end = (uint64_t)k.n_tiles * (uint64_t)(kTileWords * 32);
-            const int nu = st[tm.pack].n_unique;
-            const int r_lo = rank_of_key(bitmap4 + 2 * rb, rank + rb, tm.key_lo, key_end, nu);
-            const int r_hi = rank_of_key(bitmap4 + 2 * rb, rank + rb, (uint64_t)tm.key_lo + tm.rows, key_end, nu);
-            s_rlo[t] = r_lo;
-            s_u[t] = r_hi - r_lo;
-            chunks = (r_hi - r_lo + kSortCap - 1) / kSortCap;
-        }
-        int tot, tot_occ;
-        const int ex = block_excl_scan<kSortThreads>(chunks, &tot);
-        const int ex_occ = block_excl_scan<kSortThreads>(occ, &tot_occ);
-        if (t < T) { s_first[t] = carry + ex; s_occ[t] = carry_occ + ex_occ; }
-        carry += tot;
-        carry_occ += tot_occ;
-    }
-    if (tid == 0) s_first[T] = carry;
-    for (int p = block; p < P; p += nblocks)     // the entry after the last segment of each pack
-        if (tid == 0) {
-            const PackState ps = st[p];
-            sa.seg_all[ps.start + p + ps.n_unique] = ps.nnz;
-        }
-    __syncthreads();
-    const int total = s_first[T];
-    for (int item = block; item < total; item += nblocks) {
-        const int t = upper_bound_i32(s_first, T + 1, item) - 1;
-        SortItem it;
-        it.tm = tmeta[t];
-        it.p = it.tm.pack;
-        const PackMeta k = pm[it.p];
-        it.dim = k.dim; it.wide = k.has_mean;
-        it.n = st[it.p].nnz; it.start = st[it.p].start;
-        const int chunk = item - s_first[t];
-        it.c0 = s_rlo[t] + chunk * kSortCap;
-        it.width = (uint32_t)min(kSortCap, s_rlo[t] + s_u[t] - it.c0);
-        const uint32_t occ_before = (uint32_t)(s_occ[t] - s_occ[k.first_stable]);   // in the pack's earlier tables
-        const int first_item = s_first[t];             // the table's first item: its start is known
-        int per, n_item;
-        const int ex = sort_count(sa, it, s_cnt, &per, &n_item);
-        // occurrences before the item: those of the pack's earlier tables (known from the field
-        // boundaries) plus those of the table's earlier items (descriptor look-back inside the table)
-        if (tid < 64) {
-            if (chunk == 0) {
-                if (tid == 0) { publish_desc(sa.desc + item, make_desc(kDescPfx, (uint32_t)n_item, 0)); s_base = occ_before; }
-            } else {
-                if (tid == 0) publish_desc(sa.desc + item, make_desc(kDescAgg, (uint32_t)n_item, 0));
-                uint32_t pa, pb;
-                lookback(sa.desc, first_item, item, &pa, &pb, &st[0].error);
-                if (tid == 0) {
-                    publish_desc(sa.desc + item, make_desc(kDescPfx, pa + (uint32_t)n_item, 0));
-                    s_base = occ_before + pa;
-                }
-            }
-        }
-        __syncthreads();
-        sort_place(sa, it, s_cnt, (int)s_base, ex, per);
-    }
-}
-
-__global__ void __launch_bounds__(kSortThreads, 8)
-pk_sort_kernel(SortArgs sa)
-{
-    extern __shared__ int32_t s_dyn[];
-    sort_body(sa, blockIdx.x, gridDim.x, s_dyn);
 }

@@ -8,26 +8,51 @@
 // coalesced access.  The concatenation of the fields of a sample is the write
 // address.
 // ---------------------------------------------------------------------------
+// What the pooling of a pack reads its rows' keys from: the packed keys and packed bag offsets the
+// dedup stage left in the workspace, or (small batches, where the pooling runs beside the dedup in
+// one launch) the caller's IDs and offsets, hashed here the same way.
+struct PoolSrc {
+    const uint32_t* keys_all; const int32_t* po; const PackState* st;      // from the workspace
+    const int64_t* ids; const int32_t* offsets; int64_t nnz; int bad;      // from the caller's inputs
+    uint32_t rows;                                                         // rows of the pack's table
+};
+
 // `block` of `nblocks` blocks of `nthreads` threads; HYB: rows may live in a Hot-storage;
-// DEEP: eight rows of a bag in flight instead of four (the kernel that shares the sort's
-// launch has no registers for that)
-template <typename WT, int VEC, int LPR, int NCH, bool HYB, bool DEEP>
-__device__ __forceinline__ void pool_body(const WT* __restrict__ W, const uint32_t* __restrict__ keys_all,
-                                          const int32_t* __restrict__ po, const PackState* __restrict__ st,
+// DEEP: eight rows of a bag in flight instead of four (the kernel that shares the dedup's
+// launch has no registers for that); IDS: keys are formed from the caller's IDs
+template <typename WT, int VEC, int LPR, int NCH, bool HYB, bool DEEP, bool IDS>
+__device__ __forceinline__ void pool_body(const WT* __restrict__ W, const PoolSrc& src,
                                           const FieldMeta* __restrict__ fmeta, const int32_t* __restrict__ slot_field,
                                           int B, int D, int64_t n_bags, float* __restrict__ out, int64_t out_stride,
                                           int block, int nblocks, int nthreads, const HotView hv)
 {
     const int GPB = nthreads / LPR;
     const int li = threadIdx.x % LPR, gi = threadIdx.x / LPR;
-    const int n = st->nnz;
-    const uint32_t* keys = keys_all + st->start;
+    const int n = IDS ? (int)src.nnz : src.st->nnz;
+    const uint32_t* __restrict__ keys = IDS ? nullptr : src.keys_all + src.st->start;
+    const int64_t* __restrict__ ids = src.ids;
+    const uint32_t last_row = src.rows - 1;
     for (int64_t bag = (int64_t)block * GPB + gi; bag < n_bags; bag += (int64_t)nblocks * GPB) {
         const int j = (int)(bag / B);
         const int b = (int)(bag - (int64_t)j * B);
-        const FieldMeta m = fmeta[slot_field[j]];
-        const int q0 = min(max(po[bag], 0), n);
-        const int q1 = min(max(po[bag + 1], q0), n);
+        const int f = slot_field[j];
+        const FieldMeta m = fmeta[f];
+        int q0, q1;
+        if (IDS) {
+            const int32_t* offs = src.offsets + (int64_t)f * B;
+            const int lo = min(max(offs[0], 0), n), hi = min(max(offs[B], lo), n);   // the field's range
+            q0 = src.bad ? 0 : min(max(offs[b], lo), hi);
+            q1 = src.bad ? 0 : min(max(offs[b + 1], q0), hi);
+        } else {
+            q0 = min(max(src.po[bag], 0), n);
+            q1 = min(max(src.po[bag + 1], q0), n);
+        }
+        // the key of position q; a key that is no row of the pack (only possible after rejected
+        // offsets, which raise the error word) is bent to the last row so that no read leaves the table
+        auto key_at = [&](int q) -> uint32_t {
+            if (IDS) return m.base_row + fold_id(ids[q], m.rows);
+            return min(keys[q], last_row);
+        };
         float acc[NCH][VEC];
 #pragma unroll
         for (int c = 0; c < NCH; ++c)
@@ -38,7 +63,7 @@ __device__ __forceinline__ void pool_body(const WT* __restrict__ W, const uint32
             for (; q + 8 <= q1; q += 8) {
                 const WT* r[8];
 #pragma unroll
-                for (int k = 0; k < 8; ++k) r[k] = row_of<const WT, HYB>(W, hv, keys[q + k], D);
+                for (int k = 0; k < 8; ++k) r[k] = row_of<const WT, HYB>(W, hv, key_at(q + k), D);
 #pragma unroll
                 for (int c = 0; c < NCH; ++c) {
                     const int d0 = (c * LPR + li) * VEC;
@@ -56,10 +81,10 @@ __device__ __forceinline__ void pool_body(const WT* __restrict__ W, const uint32
             }
         }
         for (; q + 4 <= q1; q += 4) {
-            const WT* r0 = row_of<const WT, HYB>(W, hv, keys[q], D);
-            const WT* r1 = row_of<const WT, HYB>(W, hv, keys[q + 1], D);
-            const WT* r2 = row_of<const WT, HYB>(W, hv, keys[q + 2], D);
-            const WT* r3 = row_of<const WT, HYB>(W, hv, keys[q + 3], D);
+            const WT* r0 = row_of<const WT, HYB>(W, hv, key_at(q), D);
+            const WT* r1 = row_of<const WT, HYB>(W, hv, key_at(q + 1), D);
+            const WT* r2 = row_of<const WT, HYB>(W, hv, key_at(q + 2), D);
+            const WT* r3 = row_of<const WT, HYB>(W, hv, key_at(q + 3), D);
 #pragma unroll
             for (int c = 0; c < NCH; ++c) {
                 const int d0 = (c * LPR + li) * VEC;
@@ -75,7 +100,7 @@ __device__ __forceinline__ void pool_body(const WT* __restrict__ W, const uint32
             }
         }
         for (; q < q1; ++q) {
-            const WT* r0 = row_of<const WT, HYB>(W, hv, keys[q], D);
+            const WT* r0 = row_of<const WT, HYB>(W, hv, key_at(q), D);
 #pragma unroll
             for (int c = 0; c < NCH; ++c) {
                 const int d0 = (c * LPR + li) * VEC;
@@ -104,61 +129,75 @@ __device__ __forceinline__ void pool_body(const WT* __restrict__ W, const uint32
 template <typename WT, int VEC, int LPR, int NCH, bool HYB>
 __global__ void __launch_bounds__(NT)
 pk_pool_kernel(const WT* __restrict__ W, const uint32_t* __restrict__ keys_all, const int32_t* __restrict__ po,
-               const PackState* __restrict__ st, const FieldMeta* __restrict__ fmeta,
+               const PackState* __restrict__ st, uint32_t rows, const FieldMeta* __restrict__ fmeta,
                const int32_t* __restrict__ slot_field, int B, int D, int64_t n_bags,
                float* __restrict__ out, int64_t out_stride, const HotView hv)
 {
-    pool_body<WT, VEC, LPR, NCH, HYB, true>(W, keys_all, po, st, fmeta, slot_field, B, D, n_bags, out, out_stride,
-                                      blockIdx.x, gridDim.x, NT, hv);
+    const PoolSrc src{keys_all, po, st, nullptr, nullptr, 0, 0, rows};
+    pool_body<WT, VEC, LPR, NCH, HYB, true, false>(W, src, fmeta, slot_field, B, D, n_bags, out, out_stride,
+                                                   blockIdx.x, gridDim.x, NT, hv);
 }
 
-// Small batches: the sort kernel has few work items (one per table) and leaves most of the
-// chip idle, and the pooling of all packs depends on the keys only, so both run in ONE
-// launch: the first `sort_blocks` blocks sort, the others pool.  (Side streams do the same
-// for large batches; for small ones a cross-stream dependency costs more than it hides.)
+// Small batches: the whole forward pass is ONE launch.  The first blocks are the slices of the
+// dedup (they find their occurrences in the caller's IDs), the next ones write what is per bag and
+// per pack, and the rest pool: the pooling needs the rows' keys only, which it forms from the IDs
+// itself, so it depends on nothing the other blocks write.  (With few occurrences a launch is
+// mostly latency, and a second launch would wait for the first.)
 constexpr int kFusedPacks = 16;
 struct PoolPack {
-    const void* W; const int32_t* po; const int32_t* slot_field;
-    int64_t n_bags; int32_t D; int32_t variant; int32_t block_begin; int32_t pad;   // pad: the pack's index
+    const void* W; const int32_t* slot_field;
+    int64_t n_bags; int32_t D; int32_t variant; int32_t block_begin; uint32_t rows;
 };
 struct PoolJob {
     PoolPack pack[kFusedPacks];
     int32_t n_packs; int32_t B; int32_t n_blocks; int32_t pad;
-    const uint32_t* keys; const PackState* st; const FieldMeta* fmeta; float* out; int64_t out_stride;
+    float* out; int64_t out_stride;
 };
 
 // variant = 12 * dtype + shape; the shapes in the order of the host's dispatch
 #define PK_POOL_SHAPES(WT, VECW, base)                                                          \
-    case base + 0:  pool_body<WT, VECW, 1, 1, false, false>(PK_POOL_ARGS); break;                       \
-    case base + 1:  pool_body<WT, VECW, 2, 1, false, false>(PK_POOL_ARGS); break;                       \
-    case base + 2:  pool_body<WT, VECW, 4, 1, false, false>(PK_POOL_ARGS); break;                       \
-    case base + 3:  pool_body<WT, VECW, 8, 1, false, false>(PK_POOL_ARGS); break;                       \
-    case base + 4:  pool_body<WT, VECW, 16, 1, false, false>(PK_POOL_ARGS); break;                      \
-    case base + 5:  pool_body<WT, VECW, 32, 1, false, false>(PK_POOL_ARGS); break;                      \
-    case base + 6:  pool_body<WT, VECW, 64, 1, false, false>(PK_POOL_ARGS); break;                      \
-    case base + 7:  pool_body<WT, 1, 4, 1, false, false>(PK_POOL_ARGS); break;                          \
-    case base + 8:  pool_body<WT, 1, 16, 1, false, false>(PK_POOL_ARGS); break;                         \
-    case base + 9:  pool_body<WT, 1, 64, 1, false, false>(PK_POOL_ARGS); break;                         \
-    case base + 10: pool_body<WT, 1, 64, 2, false, false>(PK_POOL_ARGS); break;                         \
-    case base + 11: pool_body<WT, 1, 64, 4, false, false>(PK_POOL_ARGS); break;
+    case base + 0:  pool_body<WT, VECW, 1, 1, false, false, true>(PK_POOL_ARGS); break;                 \
+    case base + 1:  pool_body<WT, VECW, 2, 1, false, false, true>(PK_POOL_ARGS); break;                 \
+    case base + 2:  pool_body<WT, VECW, 4, 1, false, false, true>(PK_POOL_ARGS); break;                 \
+    case base + 3:  pool_body<WT, VECW, 8, 1, false, false, true>(PK_POOL_ARGS); break;                 \
+    case base + 4:  pool_body<WT, VECW, 16, 1, false, false, true>(PK_POOL_ARGS); break;                \
+    case base + 5:  pool_body<WT, VECW, 32, 1, false, false, true>(PK_POOL_ARGS); break;                \
+    case base + 6:  pool_body<WT, VECW, 64, 1, false, false, true>(PK_POOL_ARGS); break;                \
+    case base + 7:  pool_body<WT, 1, 4, 1, false, false, true>(PK_POOL_ARGS); break;                    \
+    case base + 8:  pool_body<WT, 1, 16, 1, false, false, true>(PK_POOL_ARGS); break;                   \
+    case base + 9:  pool_body<WT, 1, 64, 1, false, false, true>(PK_POOL_ARGS); break;                   \
+    case base + 10: pool_body<WT, 1, 64, 2, false, false, true>(PK_POOL_ARGS); break;                   \
+    case base + 11: pool_body<WT, 1, 64, 4, false, false, true>(PK_POOL_ARGS); break;
 #define PK_POOL_ARGS                                                                            \
-    static_cast<const WT_*>(k.W), pj.keys, k.po, pj.st + k.pad, pj.fmeta, k.slot_field, pj.B, k.D, k.n_bags, pj.out,  \
-        pj.out_stride, local, n_local, kSortThreads, HotView{nullptr, nullptr, nullptr}
+    static_cast<const WT_*>(k.W), src, a.fmeta, k.slot_field, pj.B, k.D, k.n_bags, pj.out, pj.out_stride, local,  \
+        n_local, kSliceThreads, HotView{nullptr, nullptr, nullptr}
 
-__global__ void __launch_bounds__(kSortThreads, 8)
-pk_sort_pool_kernel(SortArgs sa, PoolJob pj, int sort_blocks)
+__global__ void __launch_bounds__(kSliceThreads, 8)
+pk_fused_kernel(SliceArgs a, PoolJob pj, int slice_blocks, int meta_blocks)
 {
-    extern __shared__ int32_t s_dyn[];
-    if ((int)blockIdx.x < sort_blocks) {
-        sort_body(sa, blockIdx.x, sort_blocks, s_dyn);
+    extern __shared__ int32_t s_dyn[];                     // three words per field of a table
+    __shared__ int32_t s_main[kSliceLds];
+    if ((int)blockIdx.x < slice_blocks) {
+        slice_body<true>(a, blockIdx.x, s_main, s_dyn);
         return;
     }
-    const int pb = (int)blockIdx.x - sort_blocks;
+    if ((int)blockIdx.x < slice_blocks + meta_blocks) {
+        meta_body(a, (int)blockIdx.x - slice_blocks, meta_blocks, s_main);
+        return;
+    }
+    // unusable field boundaries (the slice blocks raise the error word): every bag pools to zeros
+    int mine = 0;
+    for (int f = threadIdx.x; f < a.F; f += kSliceThreads)
+        mine |= a.offsets[(int64_t)(f + 1) * a.B] < a.offsets[(int64_t)f * a.B];
+    if (threadIdx.x == 0) mine |= a.offsets[0] != 0 || (int64_t)a.offsets[(int64_t)a.F * a.B] != a.nnz;
+    const int bad = __syncthreads_or(mine);
+    const int pb = (int)blockIdx.x - slice_blocks - meta_blocks;
     int p = 0;
     while (p + 1 < pj.n_packs && pb >= pj.pack[p + 1].block_begin) ++p;
     const PoolPack k = pj.pack[p];
     const int local = pb - k.block_begin;
     const int n_local = (p + 1 < pj.n_packs ? pj.pack[p + 1].block_begin : pj.n_blocks) - k.block_begin;
+    const PoolSrc src{nullptr, nullptr, nullptr, a.ids, a.offsets, a.nnz, bad, k.rows};
     switch (k.variant) {
         {
             using WT_ = float;

@@ -10,8 +10,8 @@ struct DeviceState {
     FieldMeta* fmeta = nullptr;
     PackMeta* pmeta = nullptr;
     int32_t* slot_field = nullptr;
-    MarkItem* mark_items = nullptr;
-    int32_t* mark_fields = nullptr;
+    uint64_t* small_desc = nullptr;       // look-back descriptors of the one-launch forward pass (zero between calls)
+    int32_t* small_done = nullptr;        // ... and its count of blocks that are through their look-back
     TableMeta* sort_tables = nullptr;
     int32_t* table_fields = nullptr;
     std::mutex mu;
@@ -23,7 +23,6 @@ struct DeviceState {
     hipEvent_t ev_fork = nullptr;
     hipEvent_t ev_join[kSide] = {};
     bool overlap = true;
-    bool fuse = true;
     std::vector<int64_t> hh_n_hot;        // HybridHash: rows in each pack's Hot-storage
     // profiling
     bool prof_on = false;
@@ -61,27 +60,32 @@ pk_status ensure_device_state(const pk_plan* cplan, DeviceState** out)
         fm[f].pack = plan->field_pack[f];
         fm[f].slot = plan->field_slot[f];
         fm[f].pool = plan->fields[f].pool;
+        fm[f].stable = -1;
+        fm[f].pad = 0;
     }
+    for (size_t i = 0; i < plan->sort_tables.size(); ++i)
+        for (int32_t j = plan->sort_tables[i].field_begin; j < plan->sort_tables[i].field_end; ++j)
+            fm[plan->table_fields[j]].stable = (int32_t)i;
     std::vector<PackMeta> pmv(P);
     for (size_t p = 0; p < P; ++p) {
         const Pack& k = plan->packs[p];
         pmv[p].dim = k.dim; pmv[p].dtype = k.dtype; pmv[p].n_fields = (int32_t)k.fields.size();
         pmv[p].first_slot = k.first_slot; pmv[p].has_mean = k.has_mean ? 1 : 0;
-        pmv[p].first_tile = k.first_tile; pmv[p].n_tiles = k.n_tiles; pmv[p].first_stable = k.first_stable;
+        pmv[p].first_stable = k.first_stable; pmv[p].n_stables = k.n_stables; pmv[p].pad = 0;
     }
     auto pad = [](size_t b) { return (b + 255) / 256 * 256; };
     const size_t b_f = pad(F * sizeof(FieldMeta)), b_p = pad(P * sizeof(PackMeta)), b_s = pad(F * 4);
-    const size_t b_i = pad(plan->mark_items.size() * sizeof(MarkItem)), b_m = pad(plan->mark_fields.size() * 4);
+    const size_t b_d = pad((size_t)kSmallSlicesMax * 8), b_c = 256;
     const size_t b_t = pad(plan->sort_tables.size() * sizeof(TableMeta)), b_tf = pad(plan->table_fields.size() * 4);
-    e = hipMalloc(&ds->blob, b_f + b_p + b_s + b_i + b_m + b_t + b_tf + 256);
+    e = hipMalloc(&ds->blob, b_f + b_p + b_s + b_d + b_c + b_t + b_tf + 256);
     if (e != hipSuccess) { delete ds; return fail(PK_EHIP, hip_msg("hipMalloc(plan metadata)", e)); }
     {
         char* at = static_cast<char*>(ds->blob);
         ds->fmeta = reinterpret_cast<FieldMeta*>(at); at += b_f;
         ds->pmeta = reinterpret_cast<PackMeta*>(at); at += b_p;
         ds->slot_field = reinterpret_cast<int32_t*>(at); at += b_s;
-        ds->mark_items = reinterpret_cast<MarkItem*>(at); at += b_i;
-        ds->mark_fields = reinterpret_cast<int32_t*>(at); at += b_m;
+        ds->small_desc = reinterpret_cast<uint64_t*>(at); at += b_d;
+        ds->small_done = reinterpret_cast<int32_t*>(at); at += b_c;
         ds->sort_tables = reinterpret_cast<TableMeta*>(at); at += b_t;
         ds->table_fields = reinterpret_cast<int32_t*>(at);
     }
@@ -91,8 +95,7 @@ pk_status ensure_device_state(const pk_plan* cplan, DeviceState** out)
     up(ds->fmeta, fm.data(), F * sizeof(FieldMeta));
     up(ds->pmeta, pmv.data(), P * sizeof(PackMeta));
     up(ds->slot_field, plan->slot_field.data(), F * 4);
-    up(ds->mark_items, plan->mark_items.data(), plan->mark_items.size() * sizeof(MarkItem));
-    up(ds->mark_fields, plan->mark_fields.data(), plan->mark_fields.size() * 4);
+    if (e == hipSuccess) e = hipMemset(ds->small_desc, 0, b_d + b_c);
     up(ds->sort_tables, plan->sort_tables.data(), plan->sort_tables.size() * sizeof(TableMeta));
     up(ds->table_fields, plan->table_fields.data(), plan->table_fields.size() * 4);
     if (e != hipSuccess) { (void)hipFree(ds->blob); delete ds; return fail(PK_EHIP, hip_msg("hipMemcpy(plan metadata)", e)); }
@@ -102,8 +105,7 @@ pk_status ensure_device_state(const pk_plan* cplan, DeviceState** out)
     }
     if (e == hipSuccess) e = hipEventCreateWithFlags(&ds->ev_fork, hipEventDisableTiming);
     if (e != hipSuccess) { (void)hipFree(ds->blob); delete ds; return fail(PK_EHIP, hip_msg("side stream setup", e)); }
-    if (getenv("PK_TUNE_NO_OVERLAP")) ds->overlap = false;       // tuning aids
-    if (getenv("PK_TUNE_NO_FUSE")) ds->fuse = false;
+    if (plan->opts.debug & 1) ds->overlap = false;
     plan->device_state = ds;
     *out = ds;
     return PK_OK;
@@ -206,7 +208,7 @@ bool cols_aligned(const pk_plan* plan, int p)
 }
 
 struct PoolArgs {
-    const void* W; const uint32_t* keys; const int32_t* po; const PackState* st; const FieldMeta* fmeta;
+    const void* W; const uint32_t* keys; const int32_t* po; const PackState* st; uint32_t rows; const FieldMeta* fmeta;
     const int32_t* slot_field; int B; int D; int64_t n_bags; float* out; int64_t out_stride; unsigned grid_cap;
     bool aligned; HotView hv;
 };
@@ -224,12 +226,12 @@ pk_status launch_pool(DeviceState* ds, hipStream_t stream, const PoolArgs& a)
     const unsigned grid = blocks_for(a.n_bags, GPB, a.grid_cap);
     if (a.hv.slot_of)
         PK_LAUNCH("pk_pool", (pk_pool_kernel<WT, VEC, LPR, NCH, true>), dim3(grid), dim3(NT), 0,
-                  static_cast<const WT*>(a.W), a.keys, a.po, a.st, a.fmeta, a.slot_field, a.B, a.D, a.n_bags, a.out,
-                  a.out_stride, a.hv);
+                  static_cast<const WT*>(a.W), a.keys, a.po, a.st, a.rows, a.fmeta, a.slot_field, a.B, a.D, a.n_bags,
+                  a.out, a.out_stride, a.hv);
     else
         PK_LAUNCH("pk_pool", (pk_pool_kernel<WT, VEC, LPR, NCH, false>), dim3(grid), dim3(NT), 0,
-                  static_cast<const WT*>(a.W), a.keys, a.po, a.st, a.fmeta, a.slot_field, a.B, a.D, a.n_bags, a.out,
-                  a.out_stride, a.hv);
+                  static_cast<const WT*>(a.W), a.keys, a.po, a.st, a.rows, a.fmeta, a.slot_field, a.B, a.D, a.n_bags,
+                  a.out, a.out_stride, a.hv);
     return PK_OK;
 }
 
@@ -274,7 +276,7 @@ pk_status dispatch_pool(DeviceState* ds, hipStream_t stream, int D, const PoolAr
 template <typename WT, int VECW>
 pk_status dispatch_adagrad(DeviceState* ds, hipStream_t stream, int D, const AdaArgs& a) { PK_DISPATCH_BODY(launch_adagrad) }
 
-// shape of the pooling code for a pack, as numbered in pk_sort_pool_kernel, and its lanes per row
+// shape of the pooling code for a pack, as numbered in pk_fused_kernel, and its lanes per row
 int pool_variant(int dtype, int D, bool aligned, int* lpr_out)
 {
     static const int lanes[12] = {1, 2, 4, 8, 16, 32, 64, 4, 16, 64, 64, 64};

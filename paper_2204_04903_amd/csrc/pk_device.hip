@@ -6,14 +6,19 @@
 // once per field (D-Packing, Sec. III-B).
 //
 // Stages of one step (all packs of the plan share the integer stages):
+//   small batches, forward pass in ONE launch (fused): slice blocks (H1 + H2: every block owns a
+//             slice of a table's key range and finds its occurrences in the IDs), blocks that write
+//             the packed bag offsets, and pooling blocks (H3-H5, keys formed from the IDs)
+//   large batches:
+//   clear     per-pack state, slice totals and look-back descriptors of this call
 //   keys      H1: key = base_row + (uint64)id mod rows in packed order, packed bag offsets,
-//             per occurrence the place of its bag's gradient chunk (and the bag length)
+//             occurrences per slice
 //   pool      H3-H5: per pack, gather rows by key, pool per bag, write concatenated
-//   mark      H2: which rows occur (bitmap slices built in LDS)
-//   tiles     H2: one-pass popcount scan of the bitmap -> rank samples, distinct keys (ascending)
-//   inverse   H2: inverse[q] = rank(key[q])
-//   sort      H2: occurrences grouped by distinct key (LDS counting sort), segment offsets,
-//             headers of the backward tiles; small batches: pooling shares this launch
+//   scan      H2: places of the slices' records
+//   scatter   H2: one (key in slice, bag) record per occurrence, grouped by slice
+//   slices    H2: per slice, in LDS: bitmap -> distinct keys (ascending), occurrences grouped by
+//             key, segment offsets, headers of the backward tiles
+//   inverse   H2: inverse[q] = rank(key[q]) from the bitmap and rank samples of the slices
 //   adagrad   H6+H7: per pack, per distinct key: reduce gradients, update row in place
 //   hot       H7: keys whose occurrences span several backward tiles, from their partial sums
 #include <hip/hip_runtime.h>
@@ -31,9 +36,9 @@ using namespace pk;
 
 // One translation unit; the kernels and their launch helpers are kept in section files:
 //   dev_common.h   block scans, folding hash, look-back prefix sums, tile order
-//   dev_dedup.h    keys, mark, tiles, inverse, sort (H1, H2)
+//   dev_dedup.h    keys, slice scan, scatter, slices, inverse (H1, H2)
 //   dev_rows.h     row access, plain or hybrid row addressing
-//   dev_pool.h     pooling (H3-H5) and the launch it shares with the sort for small batches
+//   dev_pool.h     pooling (H3-H5) and the one launch of the forward pass for small batches
 //   dev_adagrad.h  gradient reduction + Adagrad (H6, H7)
 //   dev_hybrid.h   HybridHash bookkeeping kernels
 //   host_launch.h  device state of a plan, profiling brackets, launchers, template dispatch
@@ -96,143 +101,135 @@ static pk_status forward_impl(const pk_plan* plan, int stages, const char* who, 
     const Layout& L = ws.L;
 
     PackState* st = ws.at<PackState>(L.state);
-    int32_t* fb = ws.at<int32_t>(L.fb);
-    int32_t* delta = ws.at<int32_t>(L.delta);
     int32_t* packed_offsets = ws.at<int32_t>(L.packed_offsets);
     uint32_t* keys = ws.at<uint32_t>(L.keys);
     int32_t* inverse = ws.at<int32_t>(L.inverse);
-    uint32_t* bagref = ws.at<uint32_t>(L.bagref);
-    uint32_t* baglen = plan->any_mean ? ws.at<uint32_t>(L.baglen) : nullptr;
     uint32_t* seg_ent = ws.at<uint32_t>(L.seg_ent);
     int4* tile_hdr = ws.at<int4>(L.tile_hdr);
     uint32_t* unique = ws.at<uint32_t>(L.unique);
     int32_t* seg = ws.at<int32_t>(L.seg);
     double* ghot = ws.at<double>(L.ghot);
-    uint32_t* bitmap = ws.at<uint32_t>(L.bitmap);
-    uint64_t* tile_desc = ws.at<uint64_t>(L.tile_desc);
-    uint64_t* sort_desc = ws.at<uint64_t>(L.sort_desc);
-    int32_t* rank = ws.at<int32_t>(L.rank);
-    const int64_t n_tiles = L.n_tiles_total;
-    const int64_t n_clear4 = (int64_t)(L.clear_bytes / 16);
     const int T = (int)plan->sort_tables.size();
-
-    // keys: BT bags per block iteration; fewer when bags are long, so that blocks stay comparable
     const int64_t n_bags = (int64_t)F * B;
-    const bool long_bags = nnz / n_bags >= 16;
-    const int bt = long_bags ? 32 : 256;
-    const dim3 key_grid(blocks_for(n_bags, bt, 256 * 8));
-    const MarkArgs ma{ds->mark_items, ds->mark_fields, ds->pmeta, st, fb, delta, keys, bitmap, nnz};
-    const int n_mark = (int)plan->mark_items.size();
-    // small batches: the keys and the bitmap in one launch (its LDS holds either role's arrays)
-    const bool fuse_keys_mark = do_dedup && ds->fuse && nnz < (1 << 20) &&
-                                keys_bag_words<kFusedKeysBags>() + keys_field_words(F) <= (size_t)kMarkWords;
-    if (!do_dedup) {
-    } else if (fuse_keys_mark) {
-        if (long_bags)
-            PK_LAUNCH("pk_keys_mark", pk_keys_mark_kernel<kFusedKeysBags / 8>,
-                      dim3((unsigned)n_mark + blocks_for(n_bags, kFusedKeysBags / 8, 512)), dim3(kMarkThreads), 0, ids,
-                      offsets, B, F, P, nnz, ds->fmeta, ds->pmeta, ds->slot_field, st, fb, delta, keys, bagref, baglen,
-                      packed_offsets, plan->out_dim, reinterpret_cast<uint4*>(tile_desc), n_clear4, ma, n_mark);
-        else
-            PK_LAUNCH("pk_keys_mark", pk_keys_mark_kernel<kFusedKeysBags>,
-                      dim3((unsigned)n_mark + blocks_for(n_bags, kFusedKeysBags, 512)), dim3(kMarkThreads), 0, ids,
-                      offsets, B, F, P, nnz, ds->fmeta, ds->pmeta, ds->slot_field, st, fb, delta, keys, bagref, baglen,
-                      packed_offsets, plan->out_dim, reinterpret_cast<uint4*>(tile_desc), n_clear4, ma, n_mark);
-    } else if (long_bags) {
-        PK_LAUNCH("pk_keys", pk_keys_kernel<32>, key_grid, dim3(NT), keys_field_words(F) * 4, ids, offsets, B, F, P, nnz,
-                  ds->fmeta, ds->pmeta, ds->slot_field, st, fb, delta, keys, bagref, baglen, packed_offsets,
-                  plan->out_dim, reinterpret_cast<uint4*>(tile_desc), n_clear4);
-    } else {
-        PK_LAUNCH("pk_keys", pk_keys_kernel<256>, key_grid, dim3(NT), keys_field_words(F) * 4, ids, offsets, B, F, P, nnz,
-                  ds->fmeta, ds->pmeta, ds->slot_field, st, fb, delta, keys, bagref, baglen, packed_offsets,
-                  plan->out_dim, reinterpret_cast<uint4*>(tile_desc), n_clear4);
-    }
 
-    // Pooling needs the keys only.  Large batches: it runs on side streams beside the rest of
-    // the dedup chain.  Small ones: it shares the launch of the sort kernel (a cross-stream
-    // dependency would cost more than a small pooling kernel takes).
-    // Interleaving groups (Sec. III-C, K-Interleaving): pack p belongs to group p mod G; a
-    // group's packed operations follow one another on the group's stream, the groups run side
-    // by side.  G = 0 lets the size decide (up to 4 groups for large batches, none for small).
-    const int G = plan->opts.interleave_groups;
-    const bool overlap = ds->overlap && !ds->prof_on &&
-                         (G >= 2 || (G == 0 && (P > 1 || nnz >= (1 << 20)) && nnz >= (1 << 18)));
-    const int n_side = overlap && do_pool ? std::min<int>(P, G >= 2 ? G : 4) : 0;
-    const bool fuse_pool = do_dedup && do_pool && !hot && !n_side && P <= kFusedPacks && T > 0 && nnz < (1 << 20) &&
-                           ds->fuse;
     auto pool_aligned = [&](int p) {
         return cols_aligned(plan, p) && aligned16(out) && out_row_stride % 4 == 0 && aligned16(W[p]);
     };
+    SliceArgs sa{};
+    sa.tmeta = ds->sort_tables; sa.table_fields = ds->table_fields; sa.T = T;
+    sa.fmeta = ds->fmeta; sa.pm = ds->pmeta; sa.slot_field = ds->slot_field; sa.st = st; sa.P = P;
+    sa.F = F; sa.B = B; sa.nnz = nnz;
+    sa.ids = ids; sa.offsets = offsets;
+    sa.packed_offsets = packed_offsets;
+    sa.keys = keys; sa.inverse = inverse;
+    sa.unique = unique; sa.seg_all = seg; sa.ent_all = seg_ent; sa.ent_mult = plan->any_mean ? 2 : 1;
+    sa.tile_hdr = tile_hdr; sa.tp = L.pos_tile; sa.ghot = ghot; sa.dmax = L.dmax;
+    sa.n_slices = L.n_slices;
+    sa.out_dim = plan->out_dim;
+
+    // ---- small batches: dedup (and pooling) in one launch ----
+    if (L.small && do_dedup) {
+        const bool fuse_pool = do_pool && !hot && P <= kFusedPacks;
+        sa.target = kSliceOccSmall;
+        sa.desc = ds->small_desc; sa.done = ds->small_done;
+        PoolJob pj{};
+        int nb = 0, np = 0;
+        for (int p = 0; p < P && fuse_pool; ++p) {
+            const Pack& k = plan->packs[p];
+            if (k.fields.empty()) continue;
+            int lpr = 1;
+            PoolPack& q = pj.pack[np++];
+            q.W = W[p]; q.slot_field = ds->slot_field + k.first_slot;
+            q.n_bags = (int64_t)k.fields.size() * B; q.D = k.dim; q.rows = (uint32_t)k.rows;
+            q.variant = pool_variant(k.dtype, k.dim, pool_aligned(p), &lpr);
+            q.block_begin = nb;
+            nb += (int)blocks_for(q.n_bags, kSliceThreads / lpr, 2048);
+        }
+        pj.n_packs = np; pj.B = B; pj.n_blocks = nb; pj.out = out; pj.out_stride = out_row_stride;
+        const int meta_blocks = (int)blocks_for(n_bags, kSliceThreads * 4, 64);
+        const size_t dyn = (size_t)std::max(1, plan->max_table_fields) * 3 * 4;
+        PK_LAUNCH("pk_fused", pk_fused_kernel, dim3((unsigned)(L.n_slices + meta_blocks + nb)), dim3(kSliceThreads), dyn,
+                  sa, pj, L.n_slices, meta_blocks);
+        if (!do_pool || fuse_pool) return PK_OK;
+    }
+
+    // ---- large batches: partition the occurrences by slice, then one block per slice ----
+    const bool long_bags = nnz / std::max<int64_t>(n_bags, 1) >= 16;
+    const int bt = long_bags ? 32 : 256;
+    const int64_t n_tiles = (int64_t)F * ((B + bt - 1) / bt);
+    const size_t scan_words = field_scan_words(F) + (size_t)T + 1;
+    if (do_dedup && !L.small && (scan_words + 2 * (size_t)L.max_table_slices) * 4 > 64 * 1024)
+        return fail(PK_EOVERFLOW, std::string(who) + ": fields, tables and slices per table together exceed what the "
+                                  "dedup kernels stage in LDS");
+    if (do_dedup && !L.small) {
+        sa.target = kSliceOccLarge;
+        sa.desc = ws.at<uint64_t>(L.slice_desc); sa.done = nullptr;
+        sa.slice_info = ws.at<SliceInfo>(L.slice_info); sa.rec = ws.at<uint2>(L.rec);
+        sa.bitmap = ws.at<uint32_t>(L.bitmap); sa.rank = ws.at<int32_t>(L.rank);
+        int32_t* slice_total = ws.at<int32_t>(L.slice_total);
+        int32_t* slice_cursor = ws.at<int32_t>(L.slice_cursor);
+        const int64_t n_clear4 = (int64_t)(L.clear_bytes / 16);
+        PK_LAUNCH("pk_clear", pk_clear_kernel, dim3(blocks_for(n_clear4, NT, 256)), dim3(NT), 0,
+                  ws.at<uint4>(L.clear_begin), n_clear4);
+        const dim3 key_grid(blocks_for(n_tiles, 1, 256 * 8));
+        const size_t keys_lds = (scan_words + (size_t)L.max_table_slices) * 4;
+        if (long_bags)
+            PK_LAUNCH("pk_keys", pk_keys_kernel<32>, key_grid, dim3(NT), keys_lds, ids, offsets, B, F, P, T, nnz,
+                      sa.target, ds->fmeta, ds->pmeta, ds->sort_tables, ds->slot_field, st, keys, packed_offsets,
+                      slice_total, seg);
+        else
+            PK_LAUNCH("pk_keys", pk_keys_kernel<256>, key_grid, dim3(NT), keys_lds, ids, offsets, B, F, P, T, nnz,
+                      sa.target, ds->fmeta, ds->pmeta, ds->sort_tables, ds->slot_field, st, keys, packed_offsets,
+                      slice_total, seg);
+    }
+
+    // Pooling needs the keys only.  Large batches: it runs on side streams beside the rest of
+    // the dedup chain.  Interleaving groups (Sec. III-C, K-Interleaving): pack p belongs to group
+    // p mod G; a group's packed operations follow one another on the group's stream, the groups
+    // run side by side.  G = 0 lets the size decide (up to 4 groups for large batches, none for small).
+    const int G = plan->opts.interleave_groups;
+    const bool overlap = ds->overlap && !ds->prof_on && !L.small &&
+                         (G >= 2 || (G == 0 && (P > 1 || nnz >= (1 << 20)) && nnz >= (1 << 18)));
+    const int n_side = overlap && do_pool ? std::min<int>(P, G >= 2 ? G : 4) : 0;
     if (n_side) { rc = fork_streams(ds, stream, n_side); if (rc != PK_OK) return rc; }
-    for (int p = 0; p < P && do_pool && !fuse_pool; ++p) {
+    for (int p = 0; p < P && do_pool; ++p) {
         const Pack& k = plan->packs[p];
         if (k.fields.empty()) continue;
-        PoolArgs a{W[p], keys, packed_offsets + po_off(plan, p, B), st + p, ds->fmeta, ds->slot_field + k.first_slot,
-                   B, k.dim, (int64_t)k.fields.size() * B, out, out_row_stride, 256 * 32, pool_aligned(p),
-                   hot ? hot[p] : HotView{nullptr, nullptr, nullptr}};
+        PoolArgs a{W[p], keys, packed_offsets + po_off(plan, p, B), st + p, (uint32_t)k.rows, ds->fmeta,
+                   ds->slot_field + k.first_slot, B, k.dim, (int64_t)k.fields.size() * B, out, out_row_stride, 256 * 32,
+                   pool_aligned(p), hot ? hot[p] : HotView{nullptr, nullptr, nullptr}};
         hipStream_t ps = n_side ? ds->side[p % n_side] : stream;
         rc = k.dtype == PK_F32 ? dispatch_pool<float, 4>(ds, ps, k.dim, a)
                                : dispatch_pool<uint16_t, 8>(ds, ps, k.dim, a);
         if (rc != PK_OK) return rc;
     }
-
-    if (!do_dedup) {
-        if (n_side) { rc = join_streams(ds, stream, n_side); if (rc != PK_OK) return rc; }
-        return PK_OK;
-    }
-    if (!fuse_keys_mark) PK_LAUNCH("pk_mark", pk_mark_kernel, dim3((unsigned)n_mark), dim3(kMarkThreads), 0, ma);
-    // a grid that the chip holds at once (the scan's waits need that); with more tiles than that,
-    // runs of four tiles per block iteration
-    constexpr int kTilesGrid = 1024, kTileRun = 4;
-    if (n_tiles <= kTilesGrid) {
-        PK_LAUNCH("pk_tiles", pk_tiles_kernel<1>, dim3(blocks_for(n_tiles, 1, kTilesGrid)), dim3(NT), 0,
-                  reinterpret_cast<const uint4*>(bitmap), tile_desc, (int)n_tiles, ds->pmeta, st, P, rank, unique);
-    } else {
-        int64_t n_runs = 0;
-        for (const Pack& k : plan->packs) n_runs += (k.n_tiles + kTileRun - 1) / kTileRun;
-        PK_LAUNCH("pk_tiles", pk_tiles_kernel<kTileRun>, dim3(blocks_for(n_runs, 1, kTilesGrid)), dim3(NT), 0,
-                  reinterpret_cast<const uint4*>(bitmap), tile_desc, (int)n_runs, ds->pmeta, st, P, rank, unique);
-    }
-    const int kt = nnz < (1 << 20) ? 256 : 1024;      // occurrences per tile of the inverse kernel
-    const unsigned xq = (blocks_for(nnz, kt, 256 * 16) + 7u) & ~7u;
-    if (kt == 256)
-        PK_LAUNCH("pk_inverse", pk_inverse_kernel<256>, dim3(xq, P), dim3(NT), 0, ds->pmeta, st, keys,
-                  reinterpret_cast<const uint4*>(bitmap), rank, inverse);
-    else
-        PK_LAUNCH("pk_inverse", pk_inverse_kernel<1024>, dim3(xq, P), dim3(NT), 0, ds->pmeta, st, keys,
-                  reinterpret_cast<const uint4*>(bitmap), rank, inverse);
-    if (T > 0) {
-        // at most nnz / kSortCap + T work items exist; the grid is kept small enough for every
-        // block to be resident (two per CU when their LDS fits)
-        const size_t sort_lds = (size_t)(4 * T + 1) * 4;
-        const int64_t resident = 2 * (kSortCap * 4 + 256 + sort_lds) <= 160 * 1024 ? 512 : 256;
-        const unsigned sgrid = (unsigned)std::max<int64_t>(1, std::min<int64_t>(nnz / kSortCap + T, resident));
-        const SortArgs sa{ds->sort_tables, ds->table_fields, T, ds->pmeta, st, P, fb, delta,
-                          reinterpret_cast<const uint4*>(bitmap), rank, inverse, bagref, baglen, seg, seg_ent,
-                          plan->any_mean ? 2 : 1, tile_hdr, L.pos_tile, sort_desc, ghot, L.dmax, nnz};
-        if (fuse_pool) {
-            PoolJob pj{};
-            int nb = 0, np = 0;
-            for (int p = 0; p < P; ++p) {
-                const Pack& k = plan->packs[p];
-                if (k.fields.empty()) continue;
-                int lpr = 1;
-                PoolPack& q = pj.pack[np++];
-                q.W = W[p]; q.po = packed_offsets + po_off(plan, p, B); q.slot_field = ds->slot_field + k.first_slot;
-                q.n_bags = (int64_t)k.fields.size() * B; q.D = k.dim;
-                q.variant = pool_variant(k.dtype, k.dim, pool_aligned(p), &lpr);
-                q.block_begin = nb;
-                // pj.st is indexed by pack: remember which pack this entry is
-                q.pad = p;
-                nb += (int)blocks_for(q.n_bags, kSortThreads / lpr, 2048);
-            }
-            pj.n_packs = np; pj.B = B; pj.n_blocks = nb; pj.keys = keys; pj.st = st; pj.fmeta = ds->fmeta;
-            pj.out = out; pj.out_stride = out_row_stride;
-            PK_LAUNCH("pk_sort_pool", pk_sort_pool_kernel, dim3(sgrid + (unsigned)nb), dim3(kSortThreads), sort_lds, sa,
-                      pj, (int)sgrid);
-        } else {
-            PK_LAUNCH("pk_sort", pk_sort_kernel, dim3(sgrid), dim3(kSortThreads), sort_lds, sa);
-        }
+    if (do_dedup && !L.small) {
+        int32_t* slice_total = ws.at<int32_t>(L.slice_total);
+        int32_t* slice_cursor = ws.at<int32_t>(L.slice_cursor);
+        PK_LAUNCH("pk_slice_scan", pk_slice_scan_kernel, dim3(1), dim3(kScanThreads), (size_t)(T + 1) * 4,
+                  ds->sort_tables, T, F, nnz, sa.target, slice_total, slice_cursor, ws.at<SliceInfo>(L.slice_info),
+                  L.n_slices);
+        const dim3 tile_grid(blocks_for(n_tiles, 1, 256 * 8));
+        const size_t sc_lds = (scan_words + 2 * (size_t)L.max_table_slices) * 4;
+        if (long_bags)
+            PK_LAUNCH("pk_scatter", pk_scatter_kernel<32>, tile_grid, dim3(NT), sc_lds, offsets, B, F, T, nnz,
+                      sa.target, ds->fmeta, ds->pmeta, ds->sort_tables, ds->slot_field, st, keys, slice_cursor,
+                      ws.at<uint2>(L.rec), L.max_table_slices);
+        else
+            PK_LAUNCH("pk_scatter", pk_scatter_kernel<256>, tile_grid, dim3(NT), sc_lds, offsets, B, F, T, nnz,
+                      sa.target, ds->fmeta, ds->pmeta, ds->sort_tables, ds->slot_field, st, keys, slice_cursor,
+                      ws.at<uint2>(L.rec), L.max_table_slices);
+        if (L.n_slices > 0)
+            PK_LAUNCH("pk_slices", pk_slices_kernel, dim3((unsigned)L.n_slices), dim3(kSliceThreads), 0, sa);
+        const size_t inv_lds = field_scan_words(F) * 4;
+        if (long_bags)
+            PK_LAUNCH("pk_inverse", pk_inverse_kernel<32>, tile_grid, dim3(NT), inv_lds, offsets, B, F, nnz, ds->fmeta,
+                      ds->sort_tables, ds->slot_field, st, keys, reinterpret_cast<const uint4*>(sa.bitmap), sa.rank,
+                      inverse);
+        else
+            PK_LAUNCH("pk_inverse", pk_inverse_kernel<256>, tile_grid, dim3(NT), inv_lds, offsets, B, F, nnz, ds->fmeta,
+                      ds->sort_tables, ds->slot_field, st, keys, reinterpret_cast<const uint4*>(sa.bitmap), sa.rank,
+                      inverse);
     }
     if (n_side) { rc = join_streams(ds, stream, n_side); if (rc != PK_OK) return rc; }
     return PK_OK;
@@ -553,11 +550,12 @@ pk_status pk_ctx_pack(const pk_plan* plan, const void* workspace, int32_t B, int
 pk_status pk_ctx_error(const pk_plan* plan, const void* workspace, int32_t* error_word)
 {
     if (!plan || !workspace || !error_word) return fail(PK_EINVAL, "pk_ctx_error: NULL argument");
-    PackState s;
+    std::vector<PackState> s(plan->packs.size());
     hipError_t e = hipDeviceSynchronize();
-    if (e == hipSuccess) e = hipMemcpy(&s, workspace, sizeof(PackState), hipMemcpyDeviceToHost);
+    if (e == hipSuccess) e = hipMemcpy(s.data(), workspace, s.size() * sizeof(PackState), hipMemcpyDeviceToHost);
     if (e != hipSuccess) return fail(PK_EHIP, hip_msg("pk_ctx_error", e));
-    *error_word = s.error;
+    *error_word = 0;
+    for (size_t p = 0; p < s.size(); ++p) *error_word |= s[p].error;      // every pack keeps a word of its own
     return PK_OK;
 }
 

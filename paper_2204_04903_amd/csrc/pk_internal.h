@@ -13,13 +13,46 @@ namespace pk {
 
 constexpr int kColdMax   = 8;      // keys with at most this many occurrences: one lane group per key
 constexpr int kWarmMax   = 256;    // up to this many: one wavefront per key; above: split, partial sums
-constexpr int kTileWords = 2048;   // bitmap words scanned by one block (256 threads x 8 words)
-constexpr int kRankWords = 8;      // one rank sample per 8 words (256 keys)
+constexpr int kRankWords = 8;      // one rank sample per 8 bitmap words (256 keys)
 constexpr int kPosTileMax = 512;   // occurrences handled per block iteration in the backward pass (upper end)
 constexpr int kPosTileMin = 64;
-constexpr int kMarkWords = 16384;  // bitmap words (512K keys, 64 KB of LDS) owned by one block of the mark kernel
-constexpr int kSortCap   = 16384;  // distinct keys whose occurrences one block of the sort kernel groups in LDS
 constexpr size_t kAlign = 256;
+
+// The dedup cuts every table's key range into slices of 2^k keys; one block owns a slice and keeps
+// the slice's bitmap, its popcount prefix and the occurrence counters of its distinct keys in LDS.
+constexpr int kSliceLogMin = 10;           // 1 K keys
+constexpr int kSliceLogMax = 17;           // 128 K keys: 4096 bitmap words
+constexpr int kSliceWordsMax = 1 << (kSliceLogMax - 5);
+constexpr int kSliceRanks = 8192;          // distinct keys whose occurrences are counted and placed per round
+constexpr int kSliceOccLarge = 8192;       // occurrences per slice aimed at when the occurrences are partitioned
+constexpr int kSliceOccSmall = 1024;       // ... and when every slice block scans its table's IDs itself
+constexpr int64_t kSmallNnz = 1 << 19;     // below this many occurrences the forward pass is one launch
+constexpr int kSmallSlicesMax = 4096;      // ... if it has no more slices than this (descriptors the library owns)
+constexpr int kTableSlicesMax = 8192;      // slices per table (their counters are staged in LDS): rows <= 2^30
+
+#if defined(__HIPCC__)
+#define PK_HD __host__ __device__
+#else
+#define PK_HD
+#endif
+
+// Slices of one table: 2^log_keys keys each, n of them.  The aim is `target` occurrences per slice
+// if every field of the layer had the same number of occurrences.  Depends on sizes only (no data),
+// so host and device derive the same cut.
+struct SliceGeom { int32_t log_keys; int32_t n; };
+PK_HD inline SliceGeom slice_geom(uint32_t rows, int32_t n_table_fields, int32_t F, int64_t nnz, int32_t target)
+{
+    const int64_t est = (nnz * n_table_fields + F - 1) / F;
+    int64_t want = (est + target - 1) / target;
+    if (want < 1) want = 1;
+    const int64_t per = ((int64_t)rows + want - 1) / want;
+    int lg = kSliceLogMin;
+    while (lg < kSliceLogMax && ((int64_t)1 << lg) < per) ++lg;
+    SliceGeom g;
+    g.log_keys = lg;
+    g.n = (int32_t)(((int64_t)rows + ((int64_t)1 << lg) - 1) >> lg);
+    return g;
+}
 
 // Per field, device side (indexed by field index).
 struct FieldMeta {
@@ -29,6 +62,8 @@ struct FieldMeta {
     int32_t  pack;
     int32_t  slot;       // rank of the field among its pack's fields
     int32_t  pool;       // PK_SUM / PK_MEAN
+    int32_t  stable;     // the field's table in the (pack, first key) ordered table list
+    int32_t  pad;
 };
 
 // Per pack, device side, static.
@@ -38,20 +73,9 @@ struct PackMeta {
     int32_t n_fields;
     int32_t first_slot;      // index of the pack's slot 0 in the slot-ordered arrays
     int32_t has_mean;
-    int32_t first_tile;      // first bitmap tile (of kTileWords words) of the pack
-    int32_t n_tiles;
     int32_t first_stable;    // index of the pack's first table in the (pack, key) ordered table list
-};
-
-// A slice of a pack's key space (kMarkWords bitmap words) and the fields whose
-// tables overlap it; static, device side.
-struct MarkItem {
-    int32_t pack;
-    uint32_t key_lo;         // first key of the slice (multiple of 32)
-    int32_t n_words;         // bitmap words of the slice
-    int32_t field_begin;     // range in the item field list
-    int32_t field_end;
-    int32_t pad[3];
+    int32_t n_stables;       // tables of the pack that some field reads
+    int32_t pad;
 };
 
 // A table that at least one field reads, and those fields; static, device side,
@@ -62,7 +86,16 @@ struct TableMeta {
     uint32_t rows;
     int32_t field_begin;     // range in the table field list
     int32_t field_end;
-    int32_t pad[3];
+    uint32_t word_base;      // first word of the table's bitmap (tables are padded to whole largest slices)
+    int32_t pad[2];
+};
+
+// One slice as the partitioned path hands it to the slice kernel (written by the scan kernel).
+struct SliceInfo {
+    int32_t table;           // index in the table list
+    int32_t idx;             // slice of the table
+    int32_t start;           // position of the slice's first record in the records (all packs)
+    int32_t count;           // records
 };
 
 // Per pack, device side, rewritten by every forward call.
@@ -70,8 +103,9 @@ struct PackState {
     int32_t nnz;        // occurrences in the pack
     int32_t start;      // position of the pack's first occurrence in the packed order
     int32_t n_unique;
-    int32_t error;      // only pack 0's word is used
-    int32_t pad[4];
+    int32_t error;      // bit 0: offsets rejected; bit 1: a scan waited too long
+    int32_t first_slice;    // partitioned path: the pack's first slice
+    int32_t pad[3];
 };
 
 struct Pack {
@@ -81,18 +115,20 @@ struct Pack {
     std::vector<int32_t> tables;
     std::vector<int32_t> fields;
     int32_t first_slot = 0;
-    int32_t first_tile = 0, n_tiles = 0;
-    int32_t first_stable = 0;
+    int32_t first_stable = 0, n_stables = 0;
 };
 
 // Byte offsets of the workspace's arrays for one (plan, B, nnz).
 struct Layout {
-    size_t state, fb, delta, packed_offsets, keys, inverse, bagref, baglen, seg_ent, tile_hdr,
-           unique, seg, ghot, bitmap, tile_desc, sort_desc, rank, total;
-    size_t clear_bytes;          // scan descriptors, contiguous from `tile_desc`
-    int64_t n_tiles_total;
+    size_t state, packed_offsets, keys, inverse, seg_ent, tile_hdr, unique, seg, ghot,
+           clear_begin, slice_total, slice_desc, slice_cursor, slice_info, rec, bitmap, rank, total;
+    size_t clear_bytes;          // what the partitioned path clears before its first kernel: per-pack state,
+                                 // slice totals and look-back descriptors, contiguous from `clear_begin`
+    int32_t n_slices;            // slices of all tables for this nnz
+    int32_t max_table_slices;    // most slices any table has
     int32_t dmax;
     int32_t pos_tile;            // occurrences per backward tile for this nnz
+    bool small;                  // the forward pass's dedup is one launch (every slice block scans its table's IDs)
 };
 
 }  // namespace pk
@@ -107,13 +143,12 @@ struct pk_plan {
     std::vector<int32_t> field_pack, field_slot;
     std::vector<int64_t> field_col;
     std::vector<int32_t> slot_field;      // fields in (pack, slot) order
-    std::vector<pk::MarkItem> mark_items;
-    std::vector<int32_t> mark_fields;     // per item: the fields whose table overlaps the slice
     std::vector<pk::TableMeta> sort_tables;   // tables with fields, in (pack, first key) order
     std::vector<int32_t> table_fields;        // per entry of sort_tables: the fields that read it
     int64_t out_dim = 0;
     bool any_mean = false;
-    int32_t n_tiles_total = 0;
+    int64_t bitmap_words = 0;             // all tables' bitmaps, each padded to whole largest slices
+    int32_t max_table_fields = 0;         // most fields reading one table
     int32_t dmax = 0;
     void* device_state = nullptr;         // owned by pk_device.hip (metadata upload, events)
 };

@@ -31,12 +31,23 @@ static size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 // tiles so that the launch still has thousands of blocks.
 int32_t pos_tile_for(int64_t nnz)
 {
-    static const char* env = getenv("PK_TUNE_POS_TILE");      // tuning aid
-    if (env && atoi(env) >= kPosTileMin && atoi(env) <= kPosTileMax) return atoi(env) / 64 * 64;
     int64_t t = nnz < (1 << 19) ? 128 : nnz < (2 << 20) ? 256 : 512;
     if (t < kPosTileMin) t = kPosTileMin;
     if (t > kPosTileMax) t = kPosTileMax;
     return (int32_t)t;
+}
+
+// slices of all tables (and the most any table has) when a slice aims at `target` occurrences
+static void count_slices(const pk_plan* plan, int64_t nnz, int32_t target, int64_t* total, int32_t* most)
+{
+    const int32_t F = (int32_t)plan->fields.size();
+    *total = 0;
+    *most = 0;
+    for (const TableMeta& tm : plan->sort_tables) {
+        const SliceGeom g = slice_geom(tm.rows, tm.field_end - tm.field_begin, F, nnz, target);
+        *total += g.n;
+        *most = std::max(*most, g.n);
+    }
 }
 
 Layout make_layout(const pk_plan* plan, int32_t B, int64_t nnz)
@@ -44,16 +55,25 @@ Layout make_layout(const pk_plan* plan, int32_t B, int64_t nnz)
     const size_t F = plan->fields.size(), P = plan->packs.size();
     const size_t n = (size_t)std::max<int64_t>(nnz, 1);
     Layout L{};
+    int64_t slices = 0;
+    int32_t most = 0;
+    count_slices(plan, nnz, kSliceOccSmall, &slices, &most);
+    L.small = nnz < kSmallNnz && slices <= kSmallSlicesMax && !(plan->opts.debug & 2);
+    if (!L.small) count_slices(plan, nnz, kSliceOccLarge, &slices, &most);
+    L.n_slices = (int32_t)slices;
+    L.max_table_slices = most;
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
+    L.clear_begin    = off;
     L.state          = take(P * sizeof(PackState));
-    L.fb             = take((F + 1) * 4);
-    L.delta          = take(F * 4);
+    L.slice_total    = take(L.small ? 0 : (size_t)slices * 4);
+    L.slice_desc     = take(L.small ? 0 : (size_t)slices * 8);
+    L.clear_bytes    = off - L.clear_begin;
+    L.slice_cursor   = take(L.small ? 0 : (size_t)slices * 4);
+    L.slice_info     = take(L.small ? 0 : (size_t)slices * sizeof(SliceInfo));
     L.packed_offsets = take((F * (size_t)B + P) * 4);
     L.keys           = take(n * 4);
     L.inverse        = take(n * 4);
-    L.bagref         = take(n * 4);
-    L.baglen         = take(plan->any_mean ? n * 4 : 0);
     L.seg_ent        = take(n * (plan->any_mean ? 8 : 4));
     L.pos_tile       = pos_tile_for(nnz);
     const size_t tile_cap = n / L.pos_tile + P + 2;      // backward tiles of all packs
@@ -62,12 +82,9 @@ Layout make_layout(const pk_plan* plan, int32_t B, int64_t nnz)
     L.seg            = take((n + P + 1) * 4);
     L.dmax           = plan->dmax;
     L.ghot           = take(tile_cap * (size_t)plan->dmax * 8);
-    L.n_tiles_total  = plan->n_tiles_total;
-    L.bitmap         = take((size_t)plan->n_tiles_total * kTileWords * 4);
-    L.tile_desc      = take((size_t)plan->n_tiles_total * 8);
-    L.sort_desc      = take((n / kSortCap + plan->sort_tables.size() + 2) * 8);
-    L.clear_bytes    = off - L.tile_desc;     // scan descriptors only: the bitmap is fully rewritten every call
-    L.rank           = take((size_t)plan->n_tiles_total * (kTileWords / kRankWords) * 4);
+    L.rec            = take(L.small ? 0 : n * 8);
+    L.bitmap         = take(L.small ? 0 : (size_t)plan->bitmap_words * 4);
+    L.rank           = take(L.small ? 0 : (size_t)plan->bitmap_words / kRankWords * 4);
     L.total = off;
     return L;
 }
@@ -103,10 +120,15 @@ pk_status pk_plan_create(const pk_table_desc* tables, int32_t n_tables, const pk
     }
     if (n_fields > 4096 || n_tables > 4096)
         return fail(PK_EOVERFLOW, "pk_plan_create: at most 4096 fields and 4096 tables (their metadata is staged in LDS)");
+    for (int32_t t = 0; t < n_tables; ++t)
+        if (tables[t].rows > ((int64_t)kTableSlicesMax << kSliceLogMax))
+            return fail(PK_EOVERFLOW, "pk_plan_create: table " + std::to_string(t) + " has more than 2^30 rows");
     if (opts && (opts->max_batch < 0 || opts->max_nnz < 0 || opts->max_shards < 0))
         return fail(PK_EINVAL, "pk_plan_create: negative option");
     if (opts && (opts->interleave_groups < 0 || opts->interleave_groups > 8))
         return fail(PK_EINVAL, "pk_plan_create: interleave_groups must be 0 (automatic) to 8");
+    if (opts && (opts->debug < 0 || opts->debug > 3))
+        return fail(PK_EINVAL, "pk_plan_create: unknown debug bits");
     if (opts && opts->field_volume)
         for (int32_t f = 0; f < n_fields; ++f)
             if (!(opts->field_volume[f] >= 0.0))
@@ -188,18 +210,14 @@ pk_status pk_plan_create(const pk_table_desc* tables, int32_t n_tables, const pk
         return fail(PK_EOVERFLOW, "pk_plan_create: out_dim does not fit 31 bits");
     }
     int32_t slot0 = 0;
-    int64_t tile0 = 0;
     for (auto& pk_ : pl->packs) {
         pk_.first_slot = slot0;
         slot0 += (int32_t)pk_.fields.size();
         for (int32_t f : pk_.fields) pl->slot_field.push_back(f);
-        int64_t words = (pk_.rows + 31) / 32;
-        pk_.n_tiles = (int32_t)((words + kTileWords - 1) / kTileWords);
-        pk_.first_tile = (int32_t)tile0;
-        tile0 += pk_.n_tiles;
     }
-    pl->n_tiles_total = (int32_t)tile0;
-    // tables that some field reads, in (pack, first key) order, with their fields
+    // tables that some field reads, in (pack, first key) order, with their fields; each gets a
+    // bitmap region of its own, padded to whole largest slices so that its place does not depend
+    // on how finely a call cuts the table
     for (size_t p = 0; p < pl->packs.size(); ++p) {
         pl->packs[p].first_stable = (int32_t)pl->sort_tables.size();
         for (int32_t t : pl->packs[p].tables) {                // ascending table index = ascending first key
@@ -211,40 +229,17 @@ pk_status pk_plan_create(const pk_table_desc* tables, int32_t n_tables, const pk
             for (int32_t f = 0; f < n_fields; ++f)
                 if (fields[f].table == t) pl->table_fields.push_back(f);
             tm.field_end = (int32_t)pl->table_fields.size();
-            if (tm.field_end > tm.field_begin) pl->sort_tables.push_back(tm);
+            if (tm.field_end == tm.field_begin) continue;
+            tm.word_base = (uint32_t)pl->bitmap_words;
+            pl->bitmap_words += ((tables[t].rows + ((int64_t)1 << kSliceLogMax) - 1) >> kSliceLogMax) * kSliceWordsMax;
+            pl->max_table_fields = std::max(pl->max_table_fields, tm.field_end - tm.field_begin);
+            pl->sort_tables.push_back(tm);
         }
+        pl->packs[p].n_stables = (int32_t)pl->sort_tables.size() - pl->packs[p].first_stable;
     }
-    // Slices of every pack's key space for the mark kernel.  A block scans all keys of the
-    // fields whose tables overlap its slice, so a slice ends where a table ends (at the
-    // 128-key boundary below it: slices are copied out in 16-byte pieces): a slice then overlaps
-    // one table and at most a sliver of the one before, and blocks have comparable work
-    // however small the tables are.  Large tables are cut every kMarkWords words.
-    for (size_t p = 0; p < pl->packs.size(); ++p) {
-        const Pack& k = pl->packs[p];
-        const int64_t words = (int64_t)k.n_tiles * kTileWords;
-        size_t next_table = 0;                                 // first table of the pack that ends above `lo`
-        for (int64_t w0 = 0; w0 < words;) {
-            const int64_t lo = w0 * 32;
-            int64_t hi = std::min<int64_t>(lo + (int64_t)kMarkWords * 32, words * 32);
-            for (; next_table < k.tables.size(); ++next_table) {
-                const int32_t t = k.tables[next_table];
-                const int64_t cut = (pl->table_base[t] + tables[t].rows) / 128 * 128;
-                if (cut > lo) { hi = std::min(hi, cut); break; }
-            }
-            MarkItem it{};
-            it.pack = (int32_t)p;
-            it.key_lo = (uint32_t)lo;
-            it.n_words = (int32_t)((hi - lo) / 32);
-            w0 += it.n_words;
-            it.field_begin = (int32_t)pl->mark_fields.size();
-            for (int32_t f : k.fields) {
-                const int32_t t = fields[f].table;
-                const int64_t t_lo = pl->table_base[t], t_hi = t_lo + tables[t].rows;
-                if (t_lo < hi && t_hi > lo) pl->mark_fields.push_back(f);
-            }
-            it.field_end = (int32_t)pl->mark_fields.size();
-            pl->mark_items.push_back(it);
-        }
+    if (pl->bitmap_words >= ((int64_t)1 << 32)) {
+        delete pl;
+        return fail(PK_EOVERFLOW, "pk_plan_create: the tables' bitmaps do not fit 2^32 words");
     }
     for (auto& pk_ : pl->packs) pl->dmax = std::max(pl->dmax, pk_.dim);
     *out = pl;

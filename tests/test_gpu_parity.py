@@ -46,7 +46,7 @@ def run_dense_case(name, tables, fields, steps, lr=0.05, eps=1e-8, out_pad=0, gr
     """steps: list of dicts from small_problem (ids, offsets, grad, B, Wt of the first one)."""
     from paper_2204_04903_amd.layer import PackedEmbedding
     say(f"[case] {name}: tables={len(tables)} fields={len(fields)} steps={len(steps)}")
-    pl = orc.plan(tables, fields, **{k: v for k, v in plan_opts.items() if k != "interleave_groups"})
+    pl = orc.plan(tables, fields, **{k: v for k, v in plan_opts.items() if k not in ("interleave_groups", "debug")})
     Wt0 = steps[0]["Wt"]
     W = stack_tables(pl, [w.copy() for w in Wt0])
     A = [np.zeros(w.shape, np.float32) for w in W]
@@ -161,6 +161,40 @@ def test_random_medium_layers_hot_keys_and_many_distinct_keys(seed, B):
     fields = [(0, 0), (1, 1), (2, 0), (3, 1), (4, 0), (5, 1), (2, 1), (4, 1), (0, 1)]
     steps = [small_problem(seed * 11 + s, B=B, tables=tables, fields=fields, max_len=12) for s in range(2)]
     run_dense_case(f"medium {seed}", tables, fields, steps, lr=0.01)
+
+
+@pytest.mark.parametrize("case", ["mixed", "medium", "bf16", "wild", "dims", "empty", "20 packs"])
+def test_partitioned_dedup_on_small_inputs(case):
+    # debug bit 1: the dedup of large batches (occurrences partitioned by slice, one block per slice, inverse
+    # looked up afterwards) on inputs that the one-launch forward pass would otherwise take
+    rng = np.random.default_rng(5)
+    if case == "mixed":
+        steps = [small_problem(610 + s, B=37, max_len=6) for s in range(2)]
+        tables, fields = steps[0]["tables"], steps[0]["fields"]
+    elif case == "medium":
+        tables = [(5, 8, 0), (300, 64, 0), (400000, 8, 0), (3, 64, 1), (50000, 32, 0), (40, 32, 0)]
+        fields = [(0, 0), (1, 1), (2, 0), (3, 1), (4, 0), (5, 1), (2, 1), (4, 1), (0, 1)]
+        steps = [small_problem(620 + s, B=4096, tables=tables, fields=fields, max_len=12) for s in range(2)]
+    elif case == "bf16":
+        tables = [(300, 64, 1), (200, 64, 1), (150, 8, 1)]
+        fields = [(0, 0), (1, 1), (0, 0), (2, 0)]
+        steps = [small_problem(630 + s, B=40, tables=tables, fields=fields, max_len=9) for s in range(2)]
+    elif case == "wild":
+        steps = [small_problem(640 + s, B=33, wild_ids=True) for s in range(2)]
+        tables, fields = steps[0]["tables"], steps[0]["fields"]
+    elif case == "dims":
+        tables = [(97, d, 0) for d in (3, 100, 200)] + [(50, 100, 1)]
+        fields = [(t, t % 2) for t in range(len(tables))] + [(0, 0)]
+        steps = [small_problem(650 + s, B=19, tables=tables, fields=fields, max_len=4) for s in range(2)]
+    elif case == "empty":
+        tables, fields = [(11, 8, 0), (13, 16, 0)], [(0, 0), (1, 1)]
+        steps = [small_problem(660, B=5, tables=tables, fields=fields, max_len=0)]
+    else:
+        dims = [1, 2, 3, 4, 5, 6, 7, 8, 12, 16, 20, 24, 32, 40, 48, 64, 96, 128, 200, 256]
+        tables = [(17 + 3 * i, d, 0) for i, d in enumerate(dims)]
+        fields = [(t, t % 2) for t in range(len(tables)) if t != 3] + [(0, 1), (19, 0)]
+        steps = [small_problem(670 + s, B=11, tables=tables, fields=fields, max_len=4) for s in range(2)]
+    run_dense_case(f"partitioned {case}", tables, fields, steps, lr=0.01, debug=2)
 
 
 def test_wild_64bit_ids_are_folded():
