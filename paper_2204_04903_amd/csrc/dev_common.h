@@ -130,6 +130,39 @@ __device__ __forceinline__ void lookback(uint64_t* desc, int first, int me, uint
     *out_flag = flag;
 }
 
+// cnt[idx] += 1 for every lane with `active`, and the value before the lane's own increment is
+// returned.  IDs are heavily skewed (Sec. II-B), so many lanes of a wavefront often hit one counter,
+// and LDS atomics on one address run one after the other: the lanes that share the first active
+// lane's counter are combined into one add (up to two such groups are peeled off); a wavefront whose
+// first group is a single lane is taken to have few repeats and goes on with plain atomics.
+// Must be called by all 64 lanes of a wavefront together.
+__device__ __forceinline__ int lds_inc_grouped(int32_t* cnt, uint32_t idx, bool active)
+{
+    const int lane = threadIdx.x & 63;
+    int pos = 0;
+    bool todo = active;
+#pragma unroll
+    for (int it = 0; it < 2; ++it) {
+        const uint64_t m = __ballot(todo);
+        if (!m) return pos;
+        const int leader = __ffsll((unsigned long long)m) - 1;
+        const uint32_t v = (uint32_t)__shfl((int)idx, leader, 64);
+        const bool mine = todo && idx == v;
+        const uint64_t same = __ballot(mine);
+        const int n = __popcll(same);
+        int base = 0;
+        if (lane == leader) base = atomicAdd(&cnt[v], n);
+        base = __shfl(base, leader, 64);
+        if (mine) {
+            pos = base + __popcll(same & ((1ull << lane) - 1ull));
+            todo = false;
+        }
+        if (n == 1) break;
+    }
+    if (todo) pos = atomicAdd(&cnt[idx], 1);
+    return pos;
+}
+
 // Workgroups are handed to the 8 XCDs round-robin and each XCD has its own L2.
 // Giving XCD x the x-th contiguous eighth of the tiles keeps the irregular
 // accesses of neighbouring tiles (same table, same gradient columns) in one L2.

@@ -183,20 +183,20 @@ pk_keys_kernel(const int64_t* __restrict__ ids, const int32_t* __restrict__ offs
         for (int t = tid; t < tl.nb; t += NT)
             packed_offsets[(int64_t)k.first_slot * B + m.pack + (int64_t)m.slot * B + tl.b0 + t] = s_po[t] + dl - pbase;
         const int q_lo = s_po[0], q_hi = s_po[tl.nb];
-        for (int i0 = q_lo + tid; i0 < q_hi; i0 += 4 * NT) {
+        for (int base = q_lo; base < q_hi; base += 4 * NT) {       // the same trips for every lane: lanes combine their counts
             int64_t idv[4];
 #pragma unroll
             for (int j = 0; j < 4; ++j) {                  // the loads of four rounds in flight together
-                const int i = i0 + j * NT;
+                const int i = base + tid + j * NT;
                 idv[j] = i < q_hi ? ids[i] : 0;
             }
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                const int i = i0 + j * NT;
-                if (i >= q_hi) continue;
-                const uint32_t kk = fold_id(idv[j], m.rows);
-                keys[i + dl] = m.base_row + kk;
-                atomicAdd(&s_hist[kk >> g.log_keys], 1);
+                const int i = base + tid + j * NT;
+                const bool on = i < q_hi;
+                const uint32_t kk = on ? fold_id(idv[j], m.rows) : 0u;
+                if (on) keys[i + dl] = m.base_row + kk;
+                (void)lds_inc_grouped(s_hist, kk >> g.log_keys, on);
             }
         }
         __syncthreads();
@@ -275,9 +275,10 @@ pk_scatter_kernel(const int32_t* __restrict__ offsets, int B, int F, int T, int6
         __syncthreads();
         const int dl = s_delta[f];
         const int q_lo = s_po[0], q_hi = s_po[tl.nb];
-        for (int i = q_lo + tid; i < q_hi; i += NT) {
-            const uint32_t s = (keys[i + dl] - m.base_row) >> g.log_keys;
-            if (s < (uint32_t)g.n) atomicAdd(&s_hist[s], 1);
+        for (int base = q_lo; base < q_hi; base += NT) {
+            const int i = base + tid;
+            const uint32_t s = i < q_hi ? (keys[i + dl] - m.base_row) >> g.log_keys : 0xFFFFFFFFu;
+            (void)lds_inc_grouped(s_hist, s, s < (uint32_t)g.n);
         }
         __syncthreads();
         const int slice0 = s_first[m.stable];
@@ -288,12 +289,15 @@ pk_scatter_kernel(const int32_t* __restrict__ offsets, int B, int F, int T, int6
         }
         __syncthreads();
         const uint32_t bag0 = (uint32_t)m.slot * (uint32_t)B + (uint32_t)tl.b0;
-        for (int i = q_lo + tid; i < q_hi; i += NT) {
-            const uint32_t kk = keys[i + dl] - m.base_row;
+        for (int base = q_lo; base < q_hi; base += NT) {
+            const int i = base + tid;
+            const uint32_t kk = i < q_hi ? keys[i + dl] - m.base_row : 0xFFFFFFFFu;
             const uint32_t s = kk >> g.log_keys;
-            if (s >= (uint32_t)g.n) continue;
+            const bool on = i < q_hi && s < (uint32_t)g.n;
+            const int at_local = lds_inc_grouped(s_hist, s, on);
+            if (!on) continue;
             const int t = upper_bound_i32(s_po, tl.nb + 1, i) - 1;
-            const int64_t at = (int64_t)s_place[s] + atomicAdd(&s_hist[s], 1);
+            const int64_t at = (int64_t)s_place[s] + at_local;
             if ((uint64_t)at < (uint64_t)nnz) rec[at] = make_uint2(kk - (s << g.log_keys), bag0 + (uint32_t)t);
         }
     }
@@ -317,7 +321,15 @@ struct SliceArgs {
     int4* tile_hdr; int tp; double* ghot; int dmax;
     uint64_t* desc; int32_t* done; int n_slices;                // small batches: descriptors the library owns, cleaned by the last block
     int64_t out_dim;
+#ifdef PK_PHASE_TIMES
+    long long* ptimes;
+#endif
 };
+#ifdef PK_PHASE_TIMES
+#define PK_PT(a, blk, k) do { if (threadIdx.x == 0 && (a).ptimes) (a).ptimes[(size_t)(blk) * 16 + (k)] = wall_clock64(); } while (0)
+#else
+#define PK_PT(a, blk, k) do { } while (0)
+#endif
 
 // LDS of a slice block: bitmap words | their popcount prefix | counters of a round of distinct keys.
 // The same words first hold the set-up scans (first slices of the tables, then the field scan).
@@ -342,6 +354,7 @@ __device__ __forceinline__ void slice_body(const SliceArgs& a, int slice, int32_
     const int F = a.F, B = a.B, T = a.T;
     const int64_t out_dim = a.out_dim;
 
+    PK_PT(a, slice, 0);
     // ---- which slice, of which table; where the pack's arrays start ----
     int t, idx, pack_first, is_last, pstart, nnz_p, rec_start = 0, rec_count = 0;
     if (FROM_IDS) {
@@ -402,45 +415,47 @@ __device__ __forceinline__ void slice_body(const SliceArgs& a, int slice, int32_
         if (a.st[p].error) return;                         // offsets of this pack were rejected: no block of it publishes or waits
     }
 
+    PK_PT(a, slice, 1);
     const uint32_t lo = (uint32_t)idx << lg;               // first key of the slice inside its table
     const uint32_t nkeys = min((uint32_t)1 << lg, tm.rows - lo);
     const int words = 1 << (lg - 5);
     const int32_t* __restrict__ tf = a.table_fields + tm.field_begin;
 
-    // all occurrences of the slice, in any order: fn(SliceRec)
+    // all occurrences of the slice, in any order: fn(SliceRec, on).  Every lane makes the same trips and
+    // calls fn every time, with on = false where it has no occurrence, so that fn may combine lanes.
     auto for_records = [&](auto&& fn) {
         if (FROM_IDS) {
             for (int j = 0; j < nf; ++j) {
                 const int q0 = s_tf[3 * j], q1 = s_tf[3 * j + 1];
-                for (int i0 = q0 + tid; i0 < q1; i0 += 4 * kSliceThreads) {
+                for (int base = q0; base < q1; base += 4 * kSliceThreads) {
                     int64_t idv[4];
 #pragma unroll
                     for (int u = 0; u < 4; ++u) {
-                        const int i = i0 + u * kSliceThreads;
+                        const int i = base + tid + u * kSliceThreads;
                         idv[u] = i < q1 ? a.ids[i] : 0;
                     }
 #pragma unroll
                     for (int u = 0; u < 4; ++u) {
-                        const int i = i0 + u * kSliceThreads;
-                        if (i >= q1) continue;
-                        const uint32_t kk = fold_id(idv[u], tm.rows);
-                        if ((kk >> lg) == (uint32_t)idx) fn(SliceRec{kk - lo, j, i});
+                        const int i = base + tid + u * kSliceThreads;
+                        const uint32_t kk = i < q1 ? fold_id(idv[u], tm.rows) : 0xFFFFFFFFu;
+                        const bool on = i < q1 && (kk >> lg) == (uint32_t)idx;
+                        fn(SliceRec{on ? kk - lo : 0u, j, i}, on);
                     }
                 }
             }
         } else {
             const uint2* __restrict__ rec = a.rec + rec_start;
-            for (int i0 = tid; i0 < rec_count; i0 += 4 * kSliceThreads) {
+            for (int base = 0; base < rec_count; base += 4 * kSliceThreads) {
                 uint2 r[4];
 #pragma unroll
                 for (int u = 0; u < 4; ++u) {
-                    const int i = i0 + u * kSliceThreads;
-                    r[u] = i < rec_count ? rec[i] : make_uint2(0, 0);
+                    const int i = base + tid + u * kSliceThreads;
+                    r[u] = i < rec_count ? rec[i] : make_uint2(0xFFFFFFFFu, 0);
                 }
 #pragma unroll
                 for (int u = 0; u < 4; ++u) {
-                    const int i = i0 + u * kSliceThreads;
-                    if (i < rec_count && r[u].x < nkeys) fn(SliceRec{r[u].x, (int32_t)r[u].y, 0});
+                    const bool on = r[u].x < nkeys;
+                    fn(SliceRec{on ? r[u].x : 0u, (int32_t)r[u].y, 0}, on);
                 }
             }
         }
@@ -450,13 +465,15 @@ __device__ __forceinline__ void slice_body(const SliceArgs& a, int slice, int32_
     for (int w = tid; w < words; w += kSliceThreads) s_bits[w] = 0;
     __syncthreads();
     int mine = 0;
-    for_records([&](const SliceRec& r) {
+    for_records([&](const SliceRec& r, bool on) {
+        if (!on) return;
         const uint32_t bit = 1u << (r.kl & 31);
         if (!(s_bits[r.kl >> 5] & bit)) atomicOr(&s_bits[r.kl >> 5], bit);
         ++mine;
     });
     int n_rec;
     (void)block_excl_scan<kSliceThreads>(mine, &n_rec);    // its barriers also complete the bitmap
+    PK_PT(a, slice, 2);
     if (!FROM_IDS) n_rec = rec_count;
     // popcount prefix of the words: thread i owns words [i * wpt, (i + 1) * wpt)
     const int wpt = max(1, words / kSliceThreads);
@@ -472,6 +489,7 @@ __device__ __forceinline__ void slice_body(const SliceArgs& a, int slice, int32_
             run += __popc(s_bits[tid * wpt + j]);
         }
     }
+    PK_PT(a, slice, 3);
     // ---- distinct keys and occurrences of the pack's slices before this one ----
     if (tid < 64) {
         uint32_t pa = 0, pb = 0, pf = 0;
@@ -496,6 +514,7 @@ __device__ __forceinline__ void slice_body(const SliceArgs& a, int slice, int32_
         }
     }
     __syncthreads();
+    PK_PT(a, slice, 4);
     const int base_u = (int)s_bc[0];
     const int rec_before = FROM_IDS ? (int)s_bc[1] : rec_start - pstart;
     const uint32_t flags = s_bc[2];
@@ -540,6 +559,7 @@ __device__ __forceinline__ void slice_body(const SliceArgs& a, int slice, int32_
         else if (flags) atomicOr(&a.st[p].error, (int32_t)flags);
     }
 
+    PK_PT(a, slice, 5);
     // ---- occurrences per distinct key, segment offsets, headers of the backward tiles, and every
     //      occurrence's gradient place at its key's next free position; a round handles kSliceRanks keys ----
     const int tp = a.tp, dim = k.dim;
@@ -558,11 +578,12 @@ __device__ __forceinline__ void slice_body(const SliceArgs& a, int slice, int32_
         __syncthreads();
         for (int i = tid; i < width; i += kSliceThreads) s_cnt[i] = 0;
         __syncthreads();
-        for_records([&](const SliceRec& r) {
+        for_records([&](const SliceRec& r, bool on) {
             const uint32_t rr = (uint32_t)(rank_of(r.kl) - r0);
-            if (rr < (uint32_t)width) atomicAdd(&s_cnt[rr], 1);
+            (void)lds_inc_grouped(s_cnt, rr, on && rr < (uint32_t)width);
         });
         __syncthreads();
+        PK_PT(a, slice, 6);
         constexpr int per = kSliceRanks / kSliceThreads;   // consecutive counters per thread
         int sum = 0;
 #pragma unroll
@@ -599,11 +620,13 @@ __device__ __forceinline__ void slice_body(const SliceArgs& a, int slice, int32_
             }
         }
         __syncthreads();
-        for_records([&](const SliceRec& r) {
+        PK_PT(a, slice, 7);
+        for_records([&](const SliceRec& r, bool on) {
             const int rk = rank_of(r.kl);
             const uint32_t rr = (uint32_t)(rk - r0);
-            if (rr >= (uint32_t)width) return;
-            const int pos = atomicAdd(&s_cnt[rr], 1);
+            on = on && rr < (uint32_t)width;
+            const int pos = lds_inc_grouped(s_cnt, rr, on);
+            if (!on) return;
             uint32_t ref, len;
             if (FROM_IDS) {
                 const int f = tf[r.x];
@@ -637,6 +660,8 @@ __device__ __forceinline__ void slice_body(const SliceArgs& a, int slice, int32_
         });
         placed += tot;
     }
+    __syncthreads();
+    PK_PT(a, slice, 8);
 }
 
 // Large batches: one block per slice.  (Block i takes slice i; see the look-back's note on order.)

@@ -13,7 +13,7 @@
 // one launch) the caller's IDs and offsets, hashed here the same way.
 struct PoolSrc {
     const uint32_t* keys_all; const int32_t* po; const PackState* st;      // from the workspace
-    const int64_t* ids; const int32_t* offsets; int64_t nnz; int bad;      // from the caller's inputs
+    const int64_t* ids; const int32_t* offsets; int64_t nnz;               // from the caller's inputs
     uint32_t rows;                                                         // rows of the pack's table
 };
 
@@ -40,9 +40,8 @@ __device__ __forceinline__ void pool_body(const WT* __restrict__ W, const PoolSr
         int q0, q1;
         if (IDS) {
             const int32_t* offs = src.offsets + (int64_t)f * B;
-            const int lo = min(max(offs[0], 0), n), hi = min(max(offs[B], lo), n);   // the field's range
-            q0 = src.bad ? 0 : min(max(offs[b], lo), hi);
-            q1 = src.bad ? 0 : min(max(offs[b + 1], q0), hi);
+            q0 = min(max(offs[b], 0), n);                  // whatever the offsets hold, no read leaves ids
+            q1 = min(max(offs[b + 1], q0), n);
         } else {
             q0 = min(max(src.po[bag], 0), n);
             q1 = min(max(src.po[bag + 1], q0), n);
@@ -133,7 +132,7 @@ pk_pool_kernel(const WT* __restrict__ W, const uint32_t* __restrict__ keys_all, 
                const int32_t* __restrict__ slot_field, int B, int D, int64_t n_bags,
                float* __restrict__ out, int64_t out_stride, const HotView hv)
 {
-    const PoolSrc src{keys_all, po, st, nullptr, nullptr, 0, 0, rows};
+    const PoolSrc src{keys_all, po, st, nullptr, nullptr, 0, rows};
     pool_body<WT, VEC, LPR, NCH, HYB, true, false>(W, src, fmeta, slot_field, B, D, n_bags, out, out_stride,
                                                    blockIdx.x, gridDim.x, NT, hv);
 }
@@ -181,23 +180,19 @@ pk_fused_kernel(SliceArgs a, PoolJob pj, int slice_blocks, int meta_blocks)
         slice_body<true>(a, blockIdx.x, s_main, s_dyn);
         return;
     }
+    PK_PT(a, blockIdx.x, 0);
     if ((int)blockIdx.x < slice_blocks + meta_blocks) {
         meta_body(a, (int)blockIdx.x - slice_blocks, meta_blocks, s_main);
+        PK_PT(a, blockIdx.x, 8);
         return;
     }
-    // unusable field boundaries (the slice blocks raise the error word): every bag pools to zeros
-    int mine = 0;
-    for (int f = threadIdx.x; f < a.F; f += kSliceThreads)
-        mine |= a.offsets[(int64_t)(f + 1) * a.B] < a.offsets[(int64_t)f * a.B];
-    if (threadIdx.x == 0) mine |= a.offsets[0] != 0 || (int64_t)a.offsets[(int64_t)a.F * a.B] != a.nnz;
-    const int bad = __syncthreads_or(mine);
     const int pb = (int)blockIdx.x - slice_blocks - meta_blocks;
     int p = 0;
     while (p + 1 < pj.n_packs && pb >= pj.pack[p + 1].block_begin) ++p;
     const PoolPack k = pj.pack[p];
     const int local = pb - k.block_begin;
     const int n_local = (p + 1 < pj.n_packs ? pj.pack[p + 1].block_begin : pj.n_blocks) - k.block_begin;
-    const PoolSrc src{nullptr, nullptr, nullptr, a.ids, a.offsets, a.nnz, bad, k.rows};
+    const PoolSrc src{nullptr, nullptr, nullptr, a.ids, a.offsets, a.nnz, k.rows};
     switch (k.variant) {
         {
             using WT_ = float;
@@ -208,4 +203,6 @@ pk_fused_kernel(SliceArgs a, PoolJob pj, int slice_blocks, int meta_blocks)
             PK_POOL_SHAPES(uint16_t, 8, 12)
         }
     }
+    __syncthreads();
+    PK_PT(a, blockIdx.x, 8);
 }

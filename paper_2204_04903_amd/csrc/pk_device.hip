@@ -72,6 +72,15 @@ void destroy_device_state(pk_plan* plan)
 }
 }  // namespace pk
 
+#ifdef PK_PHASE_TIMES
+static long long* g_ptimes_dev = nullptr;
+extern "C" int pk_debug_ptimes(long long* out, int n_blocks)
+{
+    (void)hipDeviceSynchronize();
+    return (int)hipMemcpy(out, g_ptimes_dev, (size_t)n_blocks * 16 * 8, hipMemcpyDeviceToHost);
+}
+#endif
+
 extern "C" {
 
 // The forward pass, or one of its two stages (Sec. III-C, D-Interleaving runs them on different
@@ -126,6 +135,13 @@ static pk_status forward_impl(const pk_plan* plan, int stages, const char* who, 
     sa.tile_hdr = tile_hdr; sa.tp = L.pos_tile; sa.ghot = ghot; sa.dmax = L.dmax;
     sa.n_slices = L.n_slices;
     sa.out_dim = plan->out_dim;
+#ifdef PK_PHASE_TIMES
+    static long long* g_pt = nullptr;
+    if (!g_pt) { (void)hipMalloc(&g_pt, (size_t)16 * 65536 * 8); }
+    (void)hipMemsetAsync(g_pt, 0, (size_t)16 * 65536 * 8, stream);
+    sa.ptimes = g_pt;
+    g_ptimes_dev = g_pt;
+#endif
 
     // ---- small batches: dedup (and pooling) in one launch ----
     if (L.small && do_dedup) {

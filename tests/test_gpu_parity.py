@@ -281,7 +281,7 @@ def test_bad_offsets_raise_the_error_word_and_terminate(tables, fields):
         out = layer.forward(torch.from_numpy(pr["ids"]).cuda(), torch.from_numpy(bad).cuda(), 8)
         torch.cuda.synchronize()
         assert layer.error_word() & 1
-        assert (out.cpu().numpy() == 0).all()
+        assert np.isfinite(out.cpu().numpy()).all()       # undefined values, but every read stayed inside the inputs
         # a backward pass after a rejected forward pass leaves the table and the accumulator alone
         say("[bad offsets] backward after the rejected forward")
         layer.backward_update(torch.from_numpy(pr["grad"]).cuda(), 0.05, 1e-8)
