@@ -36,7 +36,8 @@ def algorithmic_bytes(info, mean_pack):
         "pk_keys": 8 * n + 4 * n + 4 * bags + 4 * bags,
         "pk_pool": 4 * n + 4 * (bags + 1) + sw * D * U + 4 * D * bags,
         "pk_scatter": 4 * n + 4 * bags + 8 * n,
-        "pk_slices": 8 * n + ent + 8 * U + bm + bm // 8,
+        "pk_slices_mark": 8 * n + bm,        # (the listed slices' launches, pk_slices_*_big, share these bytes)
+        "pk_slices_place": 8 * n + bm + ent + 8 * U + bm // 8,
         "pk_inverse": 8 * n + min(bm + bm // 8, 36 * n),
         "pk_adagrad": 4 * (U + 1) + 4 * U + ent + 4 * D * bags + (2 * sw + 8) * D * U,
     }

@@ -86,48 +86,69 @@ __device__ __forceinline__ void publish_desc(uint64_t* d, uint64_t v)
     __hip_atomic_store(d, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-// Sums of a and b, and the OR of the flags, over items [first, me).  Called by all 64 lanes of one wave.
-__device__ __forceinline__ void lookback(uint64_t* desc, int first, int me, uint32_t* out_a, uint32_t* out_b,
-                                         uint32_t* out_flag)
+// One round of a look-back: lane i reads d[-i] if it is `valid`; the wave waits until every valid lane's
+// descriptor is there (bounded), then adds, into acc_*, the descriptors from lane 0 up to the nearest one
+// that carries a prefix.  Returns whether a prefix was met.
+__device__ __forceinline__ bool lookback_round(const uint64_t* d_lane0, bool valid, uint32_t* acc_a, uint32_t* acc_b,
+                                               uint32_t* acc_f)
 {
     const int lane = threadIdx.x & 63;
-    uint32_t acc_a = 0, acc_b = 0, flag = 0;
-    int hi = me;
-    bool done = false;
-    while (hi > first && !done) {
-        const int idx = hi - 1 - lane;
-        const bool valid = idx >= first;
-        uint64_t d = make_desc(kDescPfx, 0, 0, 0);
-        int spins = 0;
-        while (true) {
-            if (valid) d = __hip_atomic_load(desc + idx, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            const bool ready = (d >> 62) != 0;
-            if (__ballot(ready) == ~0ull) break;
-            if (++spins > kSpinLimit) {
-                d = make_desc(kDescPfx, 0, 0, 2);      // flag bit 1: waited too long
-                break;
-            }
-            __builtin_amdgcn_s_sleep(2);
+    uint64_t d = make_desc(kDescAgg, 0, 0, 0);
+    int spins = 0;
+    while (true) {
+        if (valid) d = __hip_atomic_load(d_lane0 - lane, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const bool ready = (d >> 62) != 0;
+        if (__ballot(ready) == ~0ull) break;
+        if (++spins > kSpinLimit) {
+            d = make_desc(kDescPfx, 0, 0, 2);          // flag bit 1: waited too long
+            break;
         }
-        const uint64_t pfx_mask = __ballot((d >> 62) == kDescPfx);
-        int last = 64;                                   // lanes [0, last] contribute
-        if (pfx_mask) { last = __ffsll((unsigned long long)pfx_mask) - 1; done = true; }
-        if (lane <= last) {
-            acc_a += (uint32_t)(d & 0x7FFFFFFFull);
-            acc_b += (uint32_t)((d >> 31) & 0x1FFFFFFFull);
-            flag |= (uint32_t)((d >> 60) & 3ull);
-        }
-        hi -= 64;
+        __builtin_amdgcn_s_sleep(2);
     }
+    const uint64_t pfx_mask = __ballot(valid && (d >> 62) == kDescPfx);
+    int last = 64;                                       // lanes [0, last] contribute
+    if (pfx_mask) last = __ffsll((unsigned long long)pfx_mask) - 1;
+    if (valid && lane <= last) {
+        *acc_a += (uint32_t)(d & 0x7FFFFFFFull);
+        *acc_b += (uint32_t)((d >> 31) & 0x1FFFFFFFull);
+        *acc_f |= (uint32_t)((d >> 60) & 3ull);
+    }
+    return pfx_mask != 0;
+}
+
+// Sums of a and b, and the OR of the flags, over the items [first, me) of one chain (the slices of a pack).
+// Two levels keep the walk short however many blocks run side by side: items are taken in groups of 64,
+// and the last item of a group also publishes the group's sum (and, once it knows it, the prefix up to
+// the group's end) in gdesc[g0 + group], so an item reads its own group's earlier items and then whole
+// groups.  own_*: what this item itself adds.  Called by all 64 lanes of one wave.
+__device__ __forceinline__ void lookback_grouped(uint64_t* desc, uint64_t* gdesc, int first, int g0, int me,
+                                                 uint32_t own_a, uint32_t own_b, uint32_t own_f,
+                                                 uint32_t* out_a, uint32_t* out_b, uint32_t* out_f)
+{
+    const int lane = threadIdx.x & 63;
+    const int l = me - first, g = l >> 6, r = l & 63;
+    uint32_t a = 0, b = 0, f = 0;
+    bool done = lookback_round(desc + me - 1, lane < r, &a, &b, &f);
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) {
-        acc_a += __shfl_xor(acc_a, o, 64);
-        acc_b += __shfl_xor(acc_b, o, 64);
-        flag |= __shfl_xor(flag, o, 64);
+        a += __shfl_xor(a, o, 64);
+        b += __shfl_xor(b, o, 64);
+        f |= __shfl_xor(f, o, 64);
     }
-    *out_a = acc_a;
-    *out_b = acc_b;
-    *out_flag = flag;
+    if (r == 63 && lane == 0)
+        publish_desc(gdesc + g0 + g, make_desc(done ? kDescPfx : kDescAgg, a + own_a, b + own_b, f | own_f));
+    uint32_t ga = 0, gb = 0, gf = 0;
+    for (int hi = g; hi > 0 && !done; hi -= 64)
+        done = lookback_round(gdesc + g0 + hi - 1, hi - 1 - lane >= 0, &ga, &gb, &gf);
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        ga += __shfl_xor(ga, o, 64);
+        gb += __shfl_xor(gb, o, 64);
+        gf |= __shfl_xor(gf, o, 64);
+    }
+    *out_a = a + ga;
+    *out_b = b + gb;
+    *out_f = f | gf;
 }
 
 // cnt[idx] += 1 for every lane with `active`, and the value before the lane's own increment is

@@ -66,7 +66,7 @@ __device__ __forceinline__ int field_scan(const int32_t* __restrict__ offsets, i
 // s_first [T+1]: the first slice of every table, in table-list order (slices are numbered over all packs)
 template <int NTH>
 __device__ __forceinline__ void table_scan(const TableMeta* __restrict__ tmeta, int T, int F, int64_t nnz, int target,
-                                           int32_t* s_first)
+                                           int log_max, int32_t* s_first)
 {
     int carry = 0;
     for (int base = 0; base < T; base += NTH) {
@@ -74,7 +74,7 @@ __device__ __forceinline__ void table_scan(const TableMeta* __restrict__ tmeta, 
         int n = 0;
         if (t < T) {
             const TableMeta tm = tmeta[t];
-            n = slice_geom(tm.rows, tm.field_end - tm.field_begin, F, nnz, target).n;
+            n = slice_geom(tm.rows, tm.field_end - tm.field_begin, F, nnz, target, log_max).n;
         }
         int tot;
         const int ex = block_excl_scan<NTH>(n, &tot);
@@ -126,8 +126,9 @@ struct TileOf {
 template <int BT>
 __global__ void __launch_bounds__(NT)
 pk_keys_kernel(const int64_t* __restrict__ ids, const int32_t* __restrict__ offsets, int B, int F, int P, int T,
-               int64_t nnz, int target, const FieldMeta* __restrict__ fmeta, const PackMeta* __restrict__ pm,
-               const TableMeta* __restrict__ tmeta, const int32_t* __restrict__ slot_field, PackState* st,
+               int64_t nnz, int target, int log_max, const FieldMeta* __restrict__ fmeta,
+               const PackMeta* __restrict__ pm, const TableMeta* __restrict__ tmeta,
+               const int32_t* __restrict__ slot_field, PackState* st,
                uint32_t* __restrict__ keys, int32_t* __restrict__ packed_offsets, int32_t* slice_total,
                int32_t* __restrict__ seg_all)
 {
@@ -141,7 +142,7 @@ pk_keys_kernel(const int64_t* __restrict__ ids, const int32_t* __restrict__ offs
     int32_t* s_hist = s_first + (T + 1);
     const int tid = threadIdx.x;
     const int bad = field_scan<NT>(offsets, B, F, nnz, slot_field, s_fb, s_delta, s_slotpos);
-    table_scan<NT>(tmeta, T, F, nnz, target, s_first);
+    table_scan<NT>(tmeta, T, F, nnz, target, log_max, s_first);
     if (blockIdx.x == 0) {
         for (int p = tid; p < P; p += NT) {
             const PackMeta k = pm[p];
@@ -164,7 +165,7 @@ pk_keys_kernel(const int64_t* __restrict__ ids, const int32_t* __restrict__ offs
         const FieldMeta m = fmeta[f];
         const PackMeta k = pm[m.pack];
         const TableMeta tm = tmeta[m.stable];
-        const SliceGeom g = slice_geom(tm.rows, tm.field_end - tm.field_begin, F, nnz, target);
+        const SliceGeom g = slice_geom(tm.rows, tm.field_end - tm.field_begin, F, nnz, target, log_max);
         const int64_t g0 = (int64_t)f * B + tl.b0;
         __syncthreads();                                   // the previous tile's LDS is consumed
         for (int t = tid; t <= tl.nb; t += NT) s_po[t] = offsets[g0 + t];
@@ -196,7 +197,7 @@ pk_keys_kernel(const int64_t* __restrict__ ids, const int32_t* __restrict__ offs
                 const bool on = i < q_hi;
                 const uint32_t kk = on ? fold_id(idv[j], m.rows) : 0u;
                 if (on) keys[i + dl] = m.base_row + kk;
-                (void)lds_inc_grouped(s_hist, kk >> g.log_keys, on);
+                if (on) atomicAdd(&s_hist[kk >> g.log_keys], 1);
             }
         }
         __syncthreads();
@@ -208,44 +209,60 @@ pk_keys_kernel(const int64_t* __restrict__ ids, const int32_t* __restrict__ offs
     }
 }
 
-// Large batches: the slices' totals become places (one block: there are a few thousand slices).
-// Every slice gets its table, its index in the table, the place of its first record and the number
-// of records; the cursors of the scatter kernel start at those places.
+constexpr int kBigSlicesMax = 256;         // listed slices with many records
+constexpr int kBigSliceFlag = 1 << 30;     // in SliceInfo::table: the slice is listed
+constexpr int kBigSliceCount = 6144;       // records from which a slice is listed
+
+// Large batches: the slices' totals become places.  A block takes 1024 slices; what lies before them
+// it adds up itself (there are some thousand slices: a block reads a few values per thread).  Every slice
+// gets its table, its index in the table, the place of its first record and the number of records; the
+// cursors of the scatter kernel start at those places.
 constexpr int kScanThreads = 1024;
 __global__ void __launch_bounds__(kScanThreads)
-pk_slice_scan_kernel(const TableMeta* __restrict__ tmeta, int T, int F, int64_t nnz, int target,
+pk_slice_scan_kernel(const TableMeta* __restrict__ tmeta, int T, int F, int64_t nnz, int target, int log_max,
                      const int32_t* __restrict__ slice_total, int32_t* __restrict__ slice_cursor,
-                     SliceInfo* __restrict__ slice_info, int n_slices)
+                     SliceInfo* __restrict__ slice_info, int n_slices, int big_count, int32_t* n_big,
+                     int32_t* __restrict__ big_list)
 {
     extern __shared__ int32_t s_first[];                   // [T+1]
-    table_scan<kScanThreads>(tmeta, T, F, nnz, target, s_first);
-    int carry = 0;
-    for (int base = 0; base < n_slices; base += kScanThreads) {
-        const int s = base + (int)threadIdx.x;
-        const int c = s < n_slices ? slice_total[s] : 0;
-        int tot;
-        const int ex = block_excl_scan<kScanThreads>(c, &tot);
-        if (s < n_slices) {
-            const int t = upper_bound_i32(s_first, T + 1, s) - 1;
-            SliceInfo si;
-            si.table = t; si.idx = s - s_first[t]; si.start = carry + ex; si.count = c;
-            slice_info[s] = si;
-            slice_cursor[s] = carry + ex;
+    table_scan<kScanThreads>(tmeta, T, F, nnz, target, log_max, s_first);
+    const int base = blockIdx.x * kScanThreads;
+    int before = 0;
+    for (int i = threadIdx.x; i < base; i += kScanThreads) before += slice_total[i];
+    int carry;
+    (void)block_excl_scan<kScanThreads>(before, &carry);
+    const int s = base + (int)threadIdx.x;
+    const int c = s < n_slices ? slice_total[s] : 0;
+    int tot;
+    const int ex = block_excl_scan<kScanThreads>(c, &tot);
+    if (s < n_slices) {
+        const int t = upper_bound_i32(s_first, T + 1, s) - 1;
+        SliceInfo si;
+        si.table = t; si.idx = s - s_first[t]; si.start = carry + ex; si.count = c;
+        // A slice that holds a hot key has many times the records of the others: such slices are listed,
+        // and blocks of four times the threads take them, in launches that run beside the others'.
+        if (c > big_count) {
+            const int at = atomicAdd(n_big, 1);
+            if (at < kBigSlicesMax) {
+                big_list[at] = s;
+                si.table |= kBigSliceFlag;
+            }
         }
-        carry += tot;
+        slice_info[s] = si;
+        slice_cursor[s] = carry + ex;
     }
 }
 
-// Large batches: one record per occurrence, (key inside its slice, bag inside its pack), written to
+// Large batches: one record per occurrence, (key inside its slice, place of its bag's gradient chunk), written to
 // the slice's place.  A tile counts its occurrences per slice in LDS, reserves room in every
 // touched slice with one global add, and then places its records from block-local cursors.
 template <int BT>
 __global__ void __launch_bounds__(NT)
-pk_scatter_kernel(const int32_t* __restrict__ offsets, int B, int F, int T, int64_t nnz, int target,
+pk_scatter_kernel(const int32_t* __restrict__ offsets, int B, int F, int T, int64_t nnz, int target, int log_max,
                   const FieldMeta* __restrict__ fmeta, const PackMeta* __restrict__ pm,
                   const TableMeta* __restrict__ tmeta, const int32_t* __restrict__ slot_field,
                   const PackState* __restrict__ st, const uint32_t* __restrict__ keys, int32_t* slice_cursor,
-                  uint2* __restrict__ rec, int hist_words)
+                  uint2* __restrict__ rec, int hist_words, int64_t out_dim)
 {
     extern __shared__ int32_t s_dyn[];                     // field scan | first slices | counts | places
     __shared__ int32_t s_po[BT + 1];
@@ -257,7 +274,7 @@ pk_scatter_kernel(const int32_t* __restrict__ offsets, int B, int F, int T, int6
     int32_t* s_place = s_hist + hist_words;
     const int tid = threadIdx.x;
     const int bad = field_scan<NT>(offsets, B, F, nnz, slot_field, s_fb, s_delta, s_slotpos);
-    table_scan<NT>(tmeta, T, F, nnz, target, s_first);
+    table_scan<NT>(tmeta, T, F, nnz, target, log_max, s_first);
     if (bad) return;
     const int tpf = (B + BT - 1) / BT;
     const int64_t n_tiles = (int64_t)F * tpf;
@@ -267,7 +284,7 @@ pk_scatter_kernel(const int32_t* __restrict__ offsets, int B, int F, int T, int6
         const FieldMeta m = fmeta[f];
         if (st[m.pack].error) continue;                    // the keys kernel rejected offsets of this pack
         const TableMeta tm = tmeta[m.stable];
-        const SliceGeom g = slice_geom(tm.rows, tm.field_end - tm.field_begin, F, nnz, target);
+        const SliceGeom g = slice_geom(tm.rows, tm.field_end - tm.field_begin, F, nnz, target, log_max);
         const int64_t g0 = (int64_t)f * B + tl.b0;
         __syncthreads();
         for (int t = tid; t <= tl.nb; t += NT) s_po[t] = offsets[g0 + t];
@@ -278,7 +295,7 @@ pk_scatter_kernel(const int32_t* __restrict__ offsets, int B, int F, int T, int6
         for (int base = q_lo; base < q_hi; base += NT) {
             const int i = base + tid;
             const uint32_t s = i < q_hi ? (keys[i + dl] - m.base_row) >> g.log_keys : 0xFFFFFFFFu;
-            (void)lds_inc_grouped(s_hist, s, s < (uint32_t)g.n);
+            if (s < (uint32_t)g.n) atomicAdd(&s_hist[s], 1);
         }
         __syncthreads();
         const int slice0 = s_first[m.stable];
@@ -288,17 +305,24 @@ pk_scatter_kernel(const int32_t* __restrict__ offsets, int B, int F, int T, int6
             s_hist[s] = 0;
         }
         __syncthreads();
-        const uint32_t bag0 = (uint32_t)m.slot * (uint32_t)B + (uint32_t)tl.b0;
         for (int base = q_lo; base < q_hi; base += NT) {
             const int i = base + tid;
             const uint32_t kk = i < q_hi ? keys[i + dl] - m.base_row : 0xFFFFFFFFu;
             const uint32_t s = kk >> g.log_keys;
-            const bool on = i < q_hi && s < (uint32_t)g.n;
-            const int at_local = lds_inc_grouped(s_hist, s, on);
-            if (!on) continue;
+            if (i >= q_hi || s >= (uint32_t)g.n) continue;
+            const int at_local = atomicAdd(&s_hist[s], 1);
             const int t = upper_bound_i32(s_po, tl.nb + 1, i) - 1;
             const int64_t at = (int64_t)s_place[s] + at_local;
-            if ((uint64_t)at < (uint64_t)nnz) rec[at] = make_uint2(kk - (s << g.log_keys), bag0 + (uint32_t)t);
+            // the record: key inside the slice, the gradient's scale (bag length for mean pooling, 1 for sum;
+            // 0 = too long for its bits, to be looked up) above it, and the place of the bag's gradient chunk
+            uint32_t len = 1u;
+            if (m.pool == PK_MEAN) {
+                const uint32_t L = (uint32_t)max(s_po[t + 1] - s_po[t], 1);
+                len = (L >> (32 - log_max)) ? 0u : L;
+            }
+            if ((uint64_t)at < (uint64_t)nnz)
+                rec[at] = make_uint2((kk - (s << g.log_keys)) | (len << log_max),
+                                     (uint32_t)((int64_t)(tl.b0 + t) * out_dim + m.col));
         }
     }
 }
@@ -306,20 +330,23 @@ pk_scatter_kernel(const int32_t* __restrict__ offsets, int B, int F, int T, int6
 // ---------------------------------------------------------------------------
 // The slice kernel's body.
 // ---------------------------------------------------------------------------
-constexpr int kSliceThreads = 1024;
+// a field of a table as the slice blocks need it; static, device side, indexed like the table field list
+struct TableField { int32_t field, slot, col, pool; };
 
 struct SliceArgs {
-    const TableMeta* tmeta; const int32_t* table_fields; int T;
-    const FieldMeta* fmeta; const PackMeta* pm; const int32_t* slot_field; PackState* st; int P;
-    int F, B; int64_t nnz; int target;
-    const int64_t* ids; const int32_t* offsets;                 // small batches: the block finds its occurrences itself
+    const TableMeta* tmeta; const TableField* tfields; int T;
+    const PackMeta* pm; const int32_t* slot_field; PackState* st; int P;
+    int F, B; int64_t nnz; int target, log_max;
+    const int64_t* ids; const int32_t* offsets; const SmallSlice* small_slices;   // small batches: the block finds its occurrences itself
     const SliceInfo* slice_info; const uint2* rec;              // large batches: the slice's records
+    const FieldMeta* fmeta;
     int32_t* packed_offsets;
     uint32_t* keys; int32_t* inverse;                           // written here for small batches only
-    uint32_t* bitmap; int32_t* rank;                            // written here for large batches only
+    uint32_t* bitmap; int32_t* rank; int32_t* slice_nu;         // large batches only: bitmap, rank samples, distinct keys per slice
+    const int32_t* big_list; const int32_t* n_big;              // ... and the listed slices with many records
     uint32_t* unique; int32_t* seg_all; uint32_t* ent_all; int ent_mult;
     int4* tile_hdr; int tp; double* ghot; int dmax;
-    uint64_t* desc; int32_t* done; int n_slices;                // small batches: descriptors the library owns, cleaned by the last block
+    uint64_t* desc; uint64_t* gdesc; int32_t* done; int n_slices;   // small batches: descriptors the library owns, cleaned by the last block
     int64_t out_dim;
 #ifdef PK_PHASE_TIMES
     long long* ptimes;
@@ -331,64 +358,82 @@ struct SliceArgs {
 #define PK_PT(a, blk, k) do { } while (0)
 #endif
 
-// LDS of a slice block: bitmap words | their popcount prefix | counters of a round of distinct keys.
-// The same words first hold the set-up scans (first slices of the tables, then the field scan).
-constexpr int kSliceLds = 2 * kSliceWordsMax + kSliceRanks;
-static_assert(kSliceLds >= 3 * 4096 + 2 && kSliceLds >= 4096 + 1, "set-up scans must fit the slice block's LDS");
+// LDS words of a slice block: bitmap words | their popcount prefix | counters of a round of distinct keys.
+// Small batches: the same words first hold the field scan, and the upper three quarters of the
+// counters hold the slice's occurrences when they are few (kept from the first pass over the IDs,
+// so that the IDs are read once).
+constexpr int slice_lds_words(int log_max, int ranks) { return 2 * (1 << (log_max - 5)) + ranks; }
+constexpr int kSliceTfWords = 5;           // dynamic LDS words per field of a table
 
-// one occurrence of a slice: its key inside the slice and where it comes from
+// one occurrence of a slice
 struct SliceRec {
     uint32_t kl;       // key minus the slice's first key
-    int32_t x;         // small batches: the field's index in the table's field list; large: the bag inside the pack
+    int32_t x;         // small batches: the field's index in the table's field list; large: the place of the gradient chunk
     int32_t q;         // small batches: position in ids
+    int32_t b, L;      // small batches: bag of the field and its length, if known (b >= 0); large: L = the record's scale
 };
 
-template <bool FROM_IDS>
+// MODE: what the block does with its slice
+//   kSliceFused  small batches: everything, occurrences found in the IDs, sums of the slices before it by look-back
+//   kSliceMark   large batches, first half: which keys occur -> the slice's bitmap and its number of distinct keys
+//   kSlicePlace  large batches, second half (after a scan of those numbers): everything else
+// (With thousands of slices in flight a look-back makes every block wait for the slowest slice before it;
+// two launches with a scan between them let every block run without waiting.)
+enum { kSliceFused = 0, kSliceMark = 1, kSlicePlace = 2 };
+
+template <int MODE, int NTH, int LOGMAX, int RANKS, bool BIG = false>
 __device__ __forceinline__ void slice_body(const SliceArgs& a, int slice, int32_t* s_main, int32_t* s_tf)
 {
+    constexpr bool FROM_IDS = MODE == kSliceFused;
+    constexpr bool GROUPED = FROM_IDS || BIG || NTH > 256;          // lanes that share a key combine their counter updates
+    constexpr int WMAX = 1 << (LOGMAX - 5);
+    constexpr int CACHE = FROM_IDS ? (RANKS * 3 / 4) / 4 : 0;      // occurrences kept in LDS (16 bytes each)
+    static_assert(!FROM_IDS || (RANKS - 4 * CACHE >= CACHE), "cached occurrences need as many counters");
+    static_assert(!FROM_IDS || slice_lds_words(LOGMAX, RANKS) >= 3 * 4096 + 2, "the field scan must fit the block's LDS");
     const int tid = threadIdx.x;
     uint32_t* s_bits = reinterpret_cast<uint32_t*>(s_main);
-    uint32_t* s_pre = s_bits + kSliceWordsMax;
-    int32_t* s_cnt = s_main + 2 * kSliceWordsMax;
+    uint32_t* s_pre = s_bits + WMAX;
+    int32_t* s_cnt = s_main + 2 * WMAX;
+    uint4* s_cache = reinterpret_cast<uint4*>(s_cnt + (RANKS - 4 * CACHE));
     __shared__ uint32_t s_bc[4];
-    const int F = a.F, B = a.B, T = a.T;
+    __shared__ int s_ncache;
+    const int F = a.F, B = a.B;
     const int64_t out_dim = a.out_dim;
 
     PK_PT(a, slice, 0);
     // ---- which slice, of which table; where the pack's arrays start ----
-    int t, idx, pack_first, is_last, pstart, nnz_p, rec_start = 0, rec_count = 0;
+    int t, idx, lg, n_tslices, pack_first, is_last, p, nf, field_begin, pstart, nnz_p, rec_start = 0, rec_count = 0;
+    uint32_t key_lo, rows, own_flags = 0;
     if (FROM_IDS) {
-        table_scan<kSliceThreads>(a.tmeta, T, F, a.nnz, a.target, s_main);
-        t = upper_bound_i32(s_main, T + 1, slice) - 1;
-        idx = slice - s_main[t];
-        const PackMeta k0 = a.pm[a.tmeta[t].pack];
-        pack_first = s_main[k0.first_stable];
-        is_last = slice + 1 == s_main[k0.first_stable + k0.n_stables];
-        __syncthreads();
+        const SmallSlice ss = a.small_slices[slice];
+        t = ss.table; idx = ss.idx; lg = ss.log_keys; n_tslices = ss.n_table_slices; pack_first = ss.pack_first;
+        is_last = ss.is_last; p = ss.pack; field_begin = ss.field_begin; nf = ss.field_end - ss.field_begin;
+        key_lo = ss.key_lo; rows = ss.rows;
     } else {
         const SliceInfo si = a.slice_info[slice];
-        t = si.table; idx = si.idx; rec_start = si.start; rec_count = si.count;
+        if (BIG != ((si.table & kBigSliceFlag) != 0)) return;          // listed slices belong to the launch that takes the list
+        t = si.table & ~kBigSliceFlag; idx = si.idx; rec_start = si.start; rec_count = si.count;
+        const TableMeta tm = a.tmeta[t];
+        p = tm.pack; field_begin = tm.field_begin; nf = tm.field_end - tm.field_begin; key_lo = tm.key_lo; rows = tm.rows;
+        const SliceGeom geo = slice_geom(rows, nf, F, a.nnz, a.target, a.log_max);
+        lg = geo.log_keys; n_tslices = geo.n;
         pack_first = 0; is_last = 0;
     }
-    const TableMeta tm = a.tmeta[t];
-    const int p = tm.pack;
     const PackMeta k = a.pm[p];
-    const int nf = tm.field_end - tm.field_begin;
-    const SliceGeom geo = slice_geom(tm.rows, nf, F, a.nnz, a.target);
-    const int lg = geo.log_keys;
-    uint32_t own_flags = 0;
     if (FROM_IDS) {
         int32_t* s_fb = s_main;
         int32_t* s_delta = s_fb + (F + 1);
         int32_t* s_slotpos = s_delta + F;
-        const int bad = field_scan<kSliceThreads>(a.offsets, B, F, a.nnz, a.slot_field, s_fb, s_delta, s_slotpos);
+        const int bad = field_scan<NTH>(a.offsets, B, F, a.nnz, a.slot_field, s_fb, s_delta, s_slotpos);
         pstart = s_slotpos[k.first_slot];
         nnz_p = s_slotpos[k.first_slot + k.n_fields] - pstart;
-        for (int j = tid; j < nf; j += kSliceThreads) {
-            const int f = a.table_fields[tm.field_begin + j];
-            s_tf[3 * j] = s_fb[f];
-            s_tf[3 * j + 1] = s_fb[f + 1];
-            s_tf[3 * j + 2] = s_delta[f];
+        for (int j = tid; j < nf; j += NTH) {
+            const TableField tf = a.tfields[field_begin + j];
+            s_tf[kSliceTfWords * j] = s_fb[tf.field];
+            s_tf[kSliceTfWords * j + 1] = s_fb[tf.field + 1];
+            s_tf[kSliceTfWords * j + 2] = s_delta[tf.field];
+            s_tf[kSliceTfWords * j + 3] = tf.col;
+            s_tf[kSliceTfWords * j + 4] = tf.pool | (tf.field << 1);
         }
         __syncthreads();
         if (bad) {                                         // every block sees the same boundaries: nobody publishes, nobody waits
@@ -397,13 +442,12 @@ __device__ __forceinline__ void slice_body(const SliceArgs& a, int slice, int32_
         }
         // the offsets of this slice's share of the table's bags: inside the field and not decreasing
         int viol = 0;
-        const int b_lo = (int)((int64_t)B * idx / geo.n), b_hi = (int)((int64_t)B * (idx + 1) / geo.n);
+        const int b_lo = (int)((int64_t)B * idx / n_tslices), b_hi = (int)((int64_t)B * (idx + 1) / n_tslices);
         for (int j = 0; j < nf; ++j) {
-            const int f = a.table_fields[tm.field_begin + j];
-            const int32_t* offs = a.offsets + (int64_t)f * B;
-            for (int b = b_lo + tid; b < b_hi; b += kSliceThreads) {
+            const int32_t* offs = a.offsets + (int64_t)(s_tf[kSliceTfWords * j + 4] >> 1) * B;
+            for (int b = b_lo + tid; b < b_hi; b += NTH) {
                 const int o0 = offs[b], o1 = offs[b + 1];
-                viol |= o0 > o1 || o0 < s_tf[3 * j] || o1 > s_tf[3 * j + 1];
+                viol |= o0 > o1 || o0 < s_tf[kSliceTfWords * j] || o1 > s_tf[kSliceTfWords * j + 1];
             }
         }
         if (__syncthreads_or(viol)) own_flags |= 1u;
@@ -411,77 +455,127 @@ __device__ __forceinline__ void slice_body(const SliceArgs& a, int slice, int32_
         pstart = a.st[p].start;
         nnz_p = a.st[p].nnz;
         pack_first = a.st[p].first_slice;
-        is_last = t == k.first_stable + k.n_stables - 1 && idx + 1 == geo.n;   // last slice of the pack's last table
+        is_last = t == k.first_stable + k.n_stables - 1 && idx + 1 == n_tslices;   // last slice of the pack's last table
         if (a.st[p].error) return;                         // offsets of this pack were rejected: no block of it publishes or waits
+        for (int j = tid; j < nf; j += NTH) {
+            const TableField tf = a.tfields[field_begin + j];
+            s_tf[kSliceTfWords * j] = tf.slot;
+            s_tf[kSliceTfWords * j + 3] = tf.col;
+            s_tf[kSliceTfWords * j + 4] = tf.pool;
+        }
     }
-
     PK_PT(a, slice, 1);
     const uint32_t lo = (uint32_t)idx << lg;               // first key of the slice inside its table
-    const uint32_t nkeys = min((uint32_t)1 << lg, tm.rows - lo);
+    const uint32_t nkeys = min((uint32_t)1 << lg, rows - lo);
     const int words = 1 << (lg - 5);
-    const int32_t* __restrict__ tf = a.table_fields + tm.field_begin;
+    bool cached = false;
+    int n_rec = 0;
 
     // all occurrences of the slice, in any order: fn(SliceRec, on).  Every lane makes the same trips and
     // calls fn every time, with on = false where it has no occurrence, so that fn may combine lanes.
     auto for_records = [&](auto&& fn) {
-        if (FROM_IDS) {
+        if (FROM_IDS && cached) {
+            for (int base = 0; base < n_rec; base += NTH) {
+                const int i = base + tid;
+                const bool on = i < n_rec;
+                const uint4 e = on ? s_cache[i] : make_uint4(0, 0, 0, 0);
+                fn(SliceRec{e.x & ((1u << LOGMAX) - 1u), (int32_t)(e.x >> LOGMAX), (int32_t)e.y, (int32_t)e.z, (int32_t)e.w}, on);
+            }
+        } else if (FROM_IDS) {
             for (int j = 0; j < nf; ++j) {
-                const int q0 = s_tf[3 * j], q1 = s_tf[3 * j + 1];
-                for (int base = q0; base < q1; base += 4 * kSliceThreads) {
+                const int q0 = s_tf[kSliceTfWords * j], q1 = s_tf[kSliceTfWords * j + 1];
+                for (int base = q0; base < q1; base += 4 * NTH) {
                     int64_t idv[4];
 #pragma unroll
                     for (int u = 0; u < 4; ++u) {
-                        const int i = base + tid + u * kSliceThreads;
+                        const int i = base + tid + u * NTH;
                         idv[u] = i < q1 ? a.ids[i] : 0;
                     }
 #pragma unroll
                     for (int u = 0; u < 4; ++u) {
-                        const int i = base + tid + u * kSliceThreads;
-                        const uint32_t kk = i < q1 ? fold_id(idv[u], tm.rows) : 0xFFFFFFFFu;
+                        const int i = base + tid + u * NTH;
+                        const uint32_t kk = i < q1 ? fold_id(idv[u], rows) : 0xFFFFFFFFu;
                         const bool on = i < q1 && (kk >> lg) == (uint32_t)idx;
-                        fn(SliceRec{on ? kk - lo : 0u, j, i}, on);
+                        fn(SliceRec{on ? kk - lo : 0u, j, i, -1, 0}, on);
                     }
                 }
             }
         } else {
             const uint2* __restrict__ rec = a.rec + rec_start;
-            for (int base = 0; base < rec_count; base += 4 * kSliceThreads) {
-                uint2 r[4];
+            constexpr int UN = BIG ? 8 : 4;                // records per thread in flight: a listed slice is long
+            for (int base = 0; base < rec_count; base += UN * NTH) {
+                uint2 r[UN];
 #pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    const int i = base + tid + u * kSliceThreads;
+                for (int u = 0; u < UN; ++u) {
+                    const int i = base + tid + u * NTH;
                     r[u] = i < rec_count ? rec[i] : make_uint2(0xFFFFFFFFu, 0);
                 }
 #pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    const bool on = r[u].x < nkeys;
-                    fn(SliceRec{on ? r[u].x : 0u, (int32_t)r[u].y, 0}, on);
+                for (int u = 0; u < UN; ++u) {
+                    const uint32_t kl = r[u].x & ((1u << LOGMAX) - 1u);
+                    const bool on = r[u].x != 0xFFFFFFFFu && kl < nkeys;
+                    fn(SliceRec{on ? kl : 0u, (int32_t)r[u].y, 0, -1, (int32_t)(r[u].x >> LOGMAX)}, on);
                 }
             }
         }
     };
+    // the bag of an occurrence found in the IDs, and its length
+    auto bag_of = [&](int j, int q, int* L) {
+        const int32_t* offs = a.offsets + (int64_t)(s_tf[kSliceTfWords * j + 4] >> 1) * B;
+        const int b = find_bag(offs, B, q, q - s_tf[kSliceTfWords * j]);
+        *L = offs[b + 1] - offs[b];
+        return b;
+    };
 
     // ---- which keys occur ----
-    for (int w = tid; w < words; w += kSliceThreads) s_bits[w] = 0;
+    const size_t gw0 = FROM_IDS ? 0 : (size_t)a.tmeta[t].word_base + (size_t)idx * words;   // the slice's bitmap in memory
+    if (MODE == kSlicePlace) {
+        for (int w = tid; w < words; w += NTH) s_bits[w] = a.bitmap[gw0 + w];
+    } else {
+        for (int w = tid; w < words; w += NTH) s_bits[w] = 0;
+    }
+    if (tid == 0) s_ncache = 0;
     __syncthreads();
     int mine = 0;
+    if (MODE != kSlicePlace)
     for_records([&](const SliceRec& r, bool on) {
-        if (!on) return;
-        const uint32_t bit = 1u << (r.kl & 31);
-        if (!(s_bits[r.kl >> 5] & bit)) atomicOr(&s_bits[r.kl >> 5], bit);
-        ++mine;
+        if (on) {
+            const uint32_t bit = 1u << (r.kl & 31);
+            if (!(s_bits[r.kl >> 5] & bit)) atomicOr(&s_bits[r.kl >> 5], bit);
+            ++mine;
+        }
+        if (FROM_IDS) {                                    // keep the occurrence while it is at hand
+            const uint64_t m = __ballot(on);
+            if (m) {
+                const int lane = tid & 63, leader = __ffsll((unsigned long long)m) - 1;
+                int base = 0;
+                if (lane == leader) base = atomicAdd(&s_ncache, __popcll(m));
+                base = __shfl(base, leader, 64);
+                const int at = base + __popcll(m & ((1ull << lane) - 1ull));
+                if (on && at < CACHE) s_cache[at] = make_uint4(r.kl | ((uint32_t)r.x << LOGMAX), (uint32_t)r.q, 0u, 0u);
+            }
+        }
     });
-    int n_rec;
-    (void)block_excl_scan<kSliceThreads>(mine, &n_rec);    // its barriers also complete the bitmap
-    PK_PT(a, slice, 2);
+    (void)block_excl_scan<NTH>(mine, &n_rec);              // its barriers also complete the bitmap
     if (!FROM_IDS) n_rec = rec_count;
+    cached = FROM_IDS && n_rec <= CACHE;
+    if (cached) {                                          // the bags of the kept occurrences, all lookups in flight together
+        for (int i = tid; i < n_rec; i += NTH) {
+            uint4 e = s_cache[i];
+            int L;
+            const int b = bag_of((int)(e.x >> LOGMAX), (int)e.y, &L);
+            e.z = (uint32_t)b; e.w = (uint32_t)L;
+            s_cache[i] = e;
+        }
+    }
+    PK_PT(a, slice, 2);
     // popcount prefix of the words: thread i owns words [i * wpt, (i + 1) * wpt)
-    const int wpt = max(1, words / kSliceThreads);
+    const int wpt = max(1, words / NTH);
     int c = 0;
     if (tid * wpt < words)
         for (int j = 0; j < wpt; ++j) c += __popc(s_bits[tid * wpt + j]);
     int n_u;
-    const int ex = block_excl_scan<kSliceThreads>(c, &n_u);
+    const int ex = block_excl_scan<NTH>(c, &n_u);
     if (tid * wpt < words) {
         int run = ex;
         for (int j = 0; j < wpt; ++j) {
@@ -489,79 +583,96 @@ __device__ __forceinline__ void slice_body(const SliceArgs& a, int slice, int32_
             run += __popc(s_bits[tid * wpt + j]);
         }
     }
+    if (MODE == kSliceMark) {                              // the bitmap and the count go to memory; the rest follows the scan
+        for (int w = tid; w < words; w += NTH) a.bitmap[gw0 + w] = s_bits[w];
+        if (tid == 0) a.slice_nu[slice] = n_u;
+        return;
+    }
+    // the counts of this slice are out early: the slices after it add them up while it goes on
+    if (FROM_IDS && tid == 0)
+        publish_desc(a.desc + slice, make_desc(slice == pack_first ? kDescPfx : kDescAgg, (uint32_t)n_u, (uint32_t)n_rec, own_flags));
     PK_PT(a, slice, 3);
-    // ---- distinct keys and occurrences of the pack's slices before this one ----
-    if (tid < 64) {
-        uint32_t pa = 0, pb = 0, pf = 0;
-        if (slice == pack_first) {
-            if (tid == 0) publish_desc(a.desc + slice, make_desc(kDescPfx, (uint32_t)n_u, (uint32_t)n_rec, own_flags));
-        } else {
-            if (tid == 0) publish_desc(a.desc + slice, make_desc(kDescAgg, (uint32_t)n_u, (uint32_t)n_rec, own_flags));
-            lookback(a.desc, pack_first, slice, &pa, &pb, &pf);
-            if (tid == 0)
-                publish_desc(a.desc + slice, make_desc(kDescPfx, pa + (uint32_t)n_u, pb + (uint32_t)n_rec, pf | own_flags));
-        }
-        if (tid == 0) {
-            s_bc[0] = pa; s_bc[1] = pb; s_bc[2] = pf | own_flags;
-            if (FROM_IDS) {
-                // The descriptors belong to the library and must be zero when the next call starts: the
-                // block that finishes its look-back last (every block has then published, and read what
-                // it needed) clears them.  Reading the own descriptor back first makes sure that the
-                // store has arrived before this block counts as finished (same address: same order).
-                const uint64_t back = __hip_atomic_load(a.desc + slice, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                s_bc[3] = ((back >> 62) == kDescPfx && atomicAdd(a.done, 1) == a.n_slices - 1) ? 1u : 0u;
+
+    int base_u = 0, rec_before = 0;
+    uint32_t* __restrict__ uq = a.unique + pstart;
+    int32_t* __restrict__ seg = a.seg_all + pstart + p;
+    // Distinct keys and occurrences of the pack's slices before this one; then what needs them: the slice's
+    // distinct keys (ascending) in their place, bitmap and rank samples for the inverse kernel, the pack's
+    // totals.  Returns false when the sums cannot be right (then nothing is written).
+    auto after_lookback = [&]() -> bool {
+        if (!FROM_IDS) {
+            if (tid == 0) { s_bc[0] = (uint32_t)(a.slice_nu[slice] - a.slice_nu[pack_first]); s_bc[2] = 0; }   // scanned: distinct keys before
+        } else if (tid < 64) {
+            uint32_t pa = 0, pb = 0, pf = 0;
+            if (slice != pack_first) {
+                const int g0 = (pack_first >> 6) + p;      // the pack's first group descriptor (packs never share one)
+                lookback_grouped(a.desc, a.gdesc, pack_first, g0, slice, (uint32_t)n_u, (uint32_t)n_rec, own_flags, &pa, &pb, &pf);
+                if (tid == 0) {
+                    const uint64_t incl = make_desc(kDescPfx, pa + (uint32_t)n_u, pb + (uint32_t)n_rec, pf | own_flags);
+                    publish_desc(a.desc + slice, incl);
+                    if (((slice - pack_first) & 63) == 63) publish_desc(a.gdesc + g0 + ((slice - pack_first) >> 6), incl);
+                }
+            }
+            if (tid == 0) {
+                s_bc[0] = pa; s_bc[1] = pb; s_bc[2] = pf | own_flags;
+                if (FROM_IDS) {
+                    // The descriptors belong to the library and must be zero when the next call starts: the
+                    // block that finishes its look-back last (every block has then published, and read what
+                    // it needed) clears them.  Reading the own descriptor back first makes sure that the
+                    // store has arrived before this block counts as finished (same address: same order).
+                    const uint64_t back = __hip_atomic_load(a.desc + slice, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    s_bc[3] = ((back >> 62) == kDescPfx && atomicAdd(a.done, 1) == a.n_slices - 1) ? 1u : 0u;
+                }
             }
         }
-    }
-    __syncthreads();
-    PK_PT(a, slice, 4);
-    const int base_u = (int)s_bc[0];
-    const int rec_before = FROM_IDS ? (int)s_bc[1] : rec_start - pstart;
-    const uint32_t flags = s_bc[2];
-    if (FROM_IDS && s_bc[3]) {
-        for (int i = tid; i < a.n_slices; i += kSliceThreads) publish_desc(a.desc + i, 0);
-        if (tid == 0) *a.done = 0;
-    }
-
-    // whatever the descriptors held, no write below leaves the pack's arrays
-    if (base_u < 0 || rec_before < 0 || (int64_t)base_u + n_u > (int64_t)nnz_p || (int64_t)rec_before + n_rec > (int64_t)nnz_p) {
-        if (tid == 0) atomicOr(&a.st[p].error, 2);
+        __syncthreads();
+        PK_PT(a, slice, 4);
+        base_u = (int)s_bc[0];
+        rec_before = FROM_IDS ? (int)s_bc[1] : rec_start - pstart;
+        const uint32_t flags = s_bc[2];
+        if (FROM_IDS && s_bc[3]) {
+            for (int i = tid; i < a.n_slices; i += NTH) publish_desc(a.desc + i, 0);
+            for (int i = tid; i < (a.n_slices >> 6) + a.P + 2; i += NTH) publish_desc(a.gdesc + i, 0);
+            if (tid == 0) *a.done = 0;
+        }
+        // whatever the descriptors held, no write below leaves the pack's arrays
+        if (base_u < 0 || rec_before < 0 || (int64_t)base_u + n_u > (int64_t)nnz_p ||
+            (int64_t)rec_before + n_rec > (int64_t)nnz_p) {
+            if (tid == 0) atomicOr(&a.st[p].error, 2);
+            return false;
+        }
+        if (tid * wpt < words) {
+            for (int j = 0; j < wpt; ++j) {
+                const int w = tid * wpt + j;
+                uint32_t x = s_bits[w];
+                int at = base_u + (int)s_pre[w];
+                const uint32_t key0 = key_lo + lo + (uint32_t)w * 32u;
+                while (x) {
+                    const int bit = __ffs(x) - 1;
+                    x &= x - 1;
+                    uq[at++] = key0 + bit;
+                }
+            }
+        }
+        if (!FROM_IDS) {                                   // rank samples beside the bitmap, for the inverse kernel
+            for (int w = tid * kRankWords; w < words; w += NTH * kRankWords) a.rank[(gw0 + w) / kRankWords] = base_u + (int)s_pre[w];
+        }
+        if (is_last && tid == 0) {
+            a.st[p].n_unique = base_u + n_u;
+            seg[base_u + n_u] = nnz_p;
+            if (FROM_IDS) a.st[p].error = (int32_t)flags;
+            else if (flags) atomicOr(&a.st[p].error, (int32_t)flags);
+        }
+        PK_PT(a, slice, 5);
+        return true;
+    };
+    if (n_u == 0) {
+        (void)after_lookback();
         return;
     }
 
-    // ---- the slice's distinct keys, ascending; bitmap and rank samples for the inverse kernel ----
-    uint32_t* __restrict__ uq = a.unique + pstart;
-    int32_t* __restrict__ seg = a.seg_all + pstart + p;
-    if (tid * wpt < words) {
-        for (int j = 0; j < wpt; ++j) {
-            const int w = tid * wpt + j;
-            uint32_t x = s_bits[w];
-            int at = base_u + (int)s_pre[w];
-            const uint32_t key0 = tm.key_lo + lo + (uint32_t)w * 32u;
-            while (x) {
-                const int bit = __ffs(x) - 1;
-                x &= x - 1;
-                uq[at++] = key0 + bit;
-            }
-        }
-    }
-    if (!FROM_IDS) {
-        const size_t w0 = (size_t)tm.word_base + (size_t)idx * words;
-        for (int w = tid; w < words; w += kSliceThreads) {
-            a.bitmap[w0 + w] = s_bits[w];
-            if ((w & (kRankWords - 1)) == 0) a.rank[(w0 + w) / kRankWords] = base_u + (int)s_pre[w];
-        }
-    }
-    if (is_last && tid == 0) {
-        a.st[p].n_unique = base_u + n_u;
-        seg[base_u + n_u] = nnz_p;
-        if (FROM_IDS) a.st[p].error = (int32_t)flags;
-        else if (flags) atomicOr(&a.st[p].error, (int32_t)flags);
-    }
-
-    PK_PT(a, slice, 5);
     // ---- occurrences per distinct key, segment offsets, headers of the backward tiles, and every
-    //      occurrence's gradient place at its key's next free position; a round handles kSliceRanks keys ----
+    //      occurrence's gradient place at its key's next free position; a round handles RANKS keys ----
     const int tp = a.tp, dim = k.dim;
     const bool wide = k.has_mean != 0;                     // the pack's entries carry the bag length
     uint32_t* __restrict__ ent = a.ent_all + (size_t)pstart * a.ent_mult;
@@ -572,28 +683,30 @@ __device__ __forceinline__ void slice_body(const SliceArgs& a, int slice, int32_
     auto rank_of = [&](uint32_t kl) {
         return (int)(s_pre[kl >> 5] + __popc(s_bits[kl >> 5] & ((1u << (kl & 31)) - 1u)));
     };
+    const int rounds_cap = cached ? RANKS - 4 * CACHE : RANKS;      // cached occurrences take the upper counters' room
     int placed = 0;                                        // occurrences of the keys of earlier rounds
-    for (int r0 = 0; r0 < n_u; r0 += kSliceRanks) {
-        const int width = min(kSliceRanks, n_u - r0);
+    for (int r0 = 0; r0 < n_u; r0 += rounds_cap) {
+        const int width = min(rounds_cap, n_u - r0);
         __syncthreads();
-        for (int i = tid; i < width; i += kSliceThreads) s_cnt[i] = 0;
+        for (int i = tid; i < width; i += NTH) s_cnt[i] = 0;
         __syncthreads();
         for_records([&](const SliceRec& r, bool on) {
             const uint32_t rr = (uint32_t)(rank_of(r.kl) - r0);
-            (void)lds_inc_grouped(s_cnt, rr, on && rr < (uint32_t)width);
+            if (GROUPED) (void)lds_inc_grouped(s_cnt, rr, on && rr < (uint32_t)width);
+            else if (on && rr < (uint32_t)width) atomicAdd(&s_cnt[rr], 1);
         });
         __syncthreads();
         PK_PT(a, slice, 6);
-        constexpr int per = kSliceRanks / kSliceThreads;   // consecutive counters per thread
+        const int per = (width + NTH - 1) / NTH;           // consecutive counters per thread
         int sum = 0;
-#pragma unroll
         for (int j = 0; j < per; ++j) {
             const int i = tid * per + j;
             sum += i < width ? s_cnt[i] : 0;
         }
         int tot;
-        int s0 = rec_before + placed + block_excl_scan<kSliceThreads>(sum, &tot);
-#pragma unroll
+        const int ex_occ = block_excl_scan<NTH>(sum, &tot);
+        if (r0 == 0 && !after_lookback()) return;          // the same for every thread
+        int s0 = rec_before + placed + ex_occ;
         for (int j = 0; j < per; ++j) {
             const int i = tid * per + j;
             if (i < width) {
@@ -625,32 +738,32 @@ __device__ __forceinline__ void slice_body(const SliceArgs& a, int slice, int32_
             const int rk = rank_of(r.kl);
             const uint32_t rr = (uint32_t)(rk - r0);
             on = on && rr < (uint32_t)width;
-            const int pos = lds_inc_grouped(s_cnt, rr, on);
+            int pos = 0;
+            if (GROUPED) pos = lds_inc_grouped(s_cnt, rr, on);
             if (!on) return;
-            uint32_t ref, len;
+            if (!GROUPED) pos = atomicAdd(&s_cnt[rr], 1);
+            uint32_t ref, len = 1u;
             if (FROM_IDS) {
-                const int f = tf[r.x];
-                const FieldMeta m = a.fmeta[f];
-                const int32_t* offs = a.offsets + (int64_t)f * B;
-                const int b = find_bag(offs, B, r.q, r.q - s_tf[3 * r.x]);
-                const int L = offs[b + 1] - offs[b];
-                ref = (uint32_t)((int64_t)b * out_dim + m.col);
-                len = (m.pool == PK_MEAN && L > 0) ? (uint32_t)L : 1u;
-                const int qp = r.q + s_tf[3 * r.x + 2];
+                int L = r.L, b = r.b;
+                if (b < 0) b = bag_of(r.x, r.q, &L);
+                ref = (uint32_t)((int64_t)b * out_dim + s_tf[kSliceTfWords * r.x + 3]);
+                if ((s_tf[kSliceTfWords * r.x + 4] & 1) == PK_MEAN && L > 0) len = (uint32_t)L;
+                const int qp = r.q + s_tf[kSliceTfWords * r.x + 2];
                 if ((unsigned)qp < (unsigned)a.nnz) {
-                    a.keys[qp] = tm.key_lo + lo + r.kl;
+                    a.keys[qp] = key_lo + lo + r.kl;
                     a.inverse[qp] = base_u + rk;
                 }
             } else {
-                const uint32_t g = (uint32_t)r.x;
-                const uint32_t slot = g / (uint32_t)B, b = g - slot * (uint32_t)B;
-                const int f = slot < (uint32_t)k.n_fields ? a.slot_field[k.first_slot + (int)slot] : a.slot_field[k.first_slot];
-                const FieldMeta m = a.fmeta[f];
-                ref = (uint32_t)((int64_t)b * out_dim + m.col);
-                len = 1u;
-                if (wide && m.pool == PK_MEAN && slot < (uint32_t)k.n_fields) {
-                    const int L = po[g + 1] - po[g];
-                    if (L > 0) len = (uint32_t)L;
+                ref = (uint32_t)r.x;                       // the record holds the place of the gradient chunk
+                if (wide) {
+                    len = (uint32_t)r.L;
+                    if (len == 0) {                        // a bag too long for the record's bits: its length from the bag
+                        const uint32_t b = ref / (uint32_t)out_dim, col = ref - b * (uint32_t)out_dim;
+                        int j = 0;
+                        while (j + 1 < nf && (uint32_t)s_tf[kSliceTfWords * j + 3] != col) ++j;
+                        const uint32_t g = (uint32_t)s_tf[kSliceTfWords * j] * (uint32_t)B + b;
+                        len = (uint32_t)max(po[g + 1] - po[g], 1);
+                    }
                 }
             }
             if ((unsigned)pos < (unsigned)nnz_p) {
@@ -660,16 +773,60 @@ __device__ __forceinline__ void slice_body(const SliceArgs& a, int slice, int32_
         });
         placed += tot;
     }
+
     __syncthreads();
     PK_PT(a, slice, 8);
 }
 
-// Large batches: one block per slice.  (Block i takes slice i; see the look-back's note on order.)
-__global__ void __launch_bounds__(kSliceThreads)
+// Large batches: one block per slice, in two launches with a scan between them.
+constexpr int kFineThreads = 256, kFineRanks = 2048;
+constexpr int kSliceThreads = 1024, kSliceRanks = 8192;
+
+template <int MODE>
+__global__ void __launch_bounds__(kFineThreads, 8)
 pk_slices_kernel(SliceArgs a)
 {
-    __shared__ int32_t s_main[kSliceLds];
-    slice_body<false>(a, blockIdx.x, s_main, nullptr);
+    extern __shared__ int32_t s_dyn[];
+    __shared__ int32_t s_main[slice_lds_words(kSliceLogFine, kFineRanks)];
+    slice_body<MODE, kFineThreads, kSliceLogFine, kFineRanks>(a, blockIdx.x, s_main, s_dyn);
+}
+
+// ... the listed slices with many records: four times the threads, same cut
+template <int MODE>
+__global__ void __launch_bounds__(kSliceThreads)
+pk_slices_big_kernel(SliceArgs a)
+{
+    extern __shared__ int32_t s_dyn[];
+    __shared__ int32_t s_main[slice_lds_words(kSliceLogFine, kSliceRanks)];
+    if ((int)blockIdx.x >= min(*a.n_big, kBigSlicesMax)) return;
+    slice_body<MODE, kSliceThreads, kSliceLogFine, kSliceRanks, true>(a, a.big_list[blockIdx.x], s_main, s_dyn);
+}
+
+// ... and the shape for calls with a table too long for slices of 32 K keys
+template <int MODE>
+__global__ void __launch_bounds__(kSliceThreads)
+pk_slices_wide_kernel(SliceArgs a)
+{
+    extern __shared__ int32_t s_dyn[];
+    __shared__ int32_t s_main[slice_lds_words(kSliceLogMax, kSliceRanks)];
+    slice_body<MODE, kSliceThreads, kSliceLogMax, kSliceRanks>(a, blockIdx.x, s_main, s_dyn);
+}
+
+// Large batches: the slices' numbers of distinct keys become running sums, in place (exclusive, over all
+// packs; a slice takes the difference to its pack's first slice).  Blocks as in the scan of the records.
+__global__ void __launch_bounds__(kScanThreads)
+pk_unique_scan_kernel(int32_t* __restrict__ slice_nu, int n_slices, int32_t* __restrict__ sums)
+{
+    const int base = blockIdx.x * kScanThreads;
+    int before = 0;
+    for (int i = threadIdx.x; i < base; i += kScanThreads) before += slice_nu[i];
+    int carry;
+    (void)block_excl_scan<kScanThreads>(before, &carry);
+    const int s = base + (int)threadIdx.x;
+    const int c = s < n_slices ? slice_nu[s] : 0;
+    int tot;
+    const int ex = block_excl_scan<kScanThreads>(c, &tot);
+    if (s < n_slices) sums[s] = carry + ex;
 }
 
 // Small batches: the blocks beside the slice blocks that write what is per bag and per pack:

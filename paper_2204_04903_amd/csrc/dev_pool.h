@@ -174,10 +174,10 @@ struct PoolJob {
 __global__ void __launch_bounds__(kSliceThreads, 8)
 pk_fused_kernel(SliceArgs a, PoolJob pj, int slice_blocks, int meta_blocks)
 {
-    extern __shared__ int32_t s_dyn[];                     // three words per field of a table
-    __shared__ int32_t s_main[kSliceLds];
+    extern __shared__ int32_t s_dyn[];                     // kSliceTfWords words per field of a table
+    __shared__ int32_t s_main[slice_lds_words(kSliceLogMax, kSliceRanks)];
     if ((int)blockIdx.x < slice_blocks) {
-        slice_body<true>(a, blockIdx.x, s_main, s_dyn);
+        slice_body<kSliceFused, kSliceThreads, kSliceLogMax, kSliceRanks>(a, blockIdx.x, s_main, s_dyn);
         return;
     }
     PK_PT(a, blockIdx.x, 0);

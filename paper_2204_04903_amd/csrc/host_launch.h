@@ -12,6 +12,8 @@ struct DeviceState {
     int32_t* slot_field = nullptr;
     uint64_t* small_desc = nullptr;       // look-back descriptors of the one-launch forward pass (zero between calls)
     int32_t* small_done = nullptr;        // ... and its count of blocks that are through their look-back
+    SmallSlice* small_slices = nullptr;   // the cut of the one-launch forward pass
+    TableField* tfields = nullptr;        // the table field list with what the slice blocks need of a field
     TableMeta* sort_tables = nullptr;
     int32_t* table_fields = nullptr;
     std::mutex mu;
@@ -75,9 +77,11 @@ pk_status ensure_device_state(const pk_plan* cplan, DeviceState** out)
     }
     auto pad = [](size_t b) { return (b + 255) / 256 * 256; };
     const size_t b_f = pad(F * sizeof(FieldMeta)), b_p = pad(P * sizeof(PackMeta)), b_s = pad(F * 4);
-    const size_t b_d = pad((size_t)kSmallSlicesMax * 8), b_c = 256;
+    const size_t b_d = pad(((size_t)kSmallSlicesMax + kSmallSlicesMax / 64 + 4096 + 2) * 8), b_c = 256;   // per slice, then per group of 64
+    const size_t b_ss = pad(plan->small_slices.size() * sizeof(SmallSlice));
+    const size_t b_tfi = pad(plan->table_fields.size() * sizeof(TableField));
     const size_t b_t = pad(plan->sort_tables.size() * sizeof(TableMeta)), b_tf = pad(plan->table_fields.size() * 4);
-    e = hipMalloc(&ds->blob, b_f + b_p + b_s + b_d + b_c + b_t + b_tf + 256);
+    e = hipMalloc(&ds->blob, b_f + b_p + b_s + b_d + b_c + b_ss + b_tfi + b_t + b_tf + 256);
     if (e != hipSuccess) { delete ds; return fail(PK_EHIP, hip_msg("hipMalloc(plan metadata)", e)); }
     {
         char* at = static_cast<char*>(ds->blob);
@@ -86,6 +90,8 @@ pk_status ensure_device_state(const pk_plan* cplan, DeviceState** out)
         ds->slot_field = reinterpret_cast<int32_t*>(at); at += b_s;
         ds->small_desc = reinterpret_cast<uint64_t*>(at); at += b_d;
         ds->small_done = reinterpret_cast<int32_t*>(at); at += b_c;
+        ds->small_slices = reinterpret_cast<SmallSlice*>(at); at += b_ss;
+        ds->tfields = reinterpret_cast<TableField*>(at); at += b_tfi;
         ds->sort_tables = reinterpret_cast<TableMeta*>(at); at += b_t;
         ds->table_fields = reinterpret_cast<int32_t*>(at);
     }
@@ -96,6 +102,13 @@ pk_status ensure_device_state(const pk_plan* cplan, DeviceState** out)
     up(ds->pmeta, pmv.data(), P * sizeof(PackMeta));
     up(ds->slot_field, plan->slot_field.data(), F * 4);
     if (e == hipSuccess) e = hipMemset(ds->small_desc, 0, b_d + b_c);
+    up(ds->small_slices, plan->small_slices.data(), plan->small_slices.size() * sizeof(SmallSlice));
+    std::vector<TableField> tfi(plan->table_fields.size());
+    for (size_t i = 0; i < tfi.size(); ++i) {
+        const int32_t f = plan->table_fields[i];
+        tfi[i] = TableField{f, plan->field_slot[f], (int32_t)plan->field_col[f], plan->fields[f].pool};
+    }
+    up(ds->tfields, tfi.data(), tfi.size() * sizeof(TableField));
     up(ds->sort_tables, plan->sort_tables.data(), plan->sort_tables.size() * sizeof(TableMeta));
     up(ds->table_fields, plan->table_fields.data(), plan->table_fields.size() * 4);
     if (e != hipSuccess) { (void)hipFree(ds->blob); delete ds; return fail(PK_EHIP, hip_msg("hipMemcpy(plan metadata)", e)); }
@@ -112,18 +125,18 @@ pk_status ensure_device_state(const pk_plan* cplan, DeviceState** out)
 }
 
 // fork: side streams wait for what the caller's stream has enqueued so far
-pk_status fork_streams(DeviceState* ds, hipStream_t main, int n)
+pk_status fork_streams(DeviceState* ds, hipStream_t main, int n, int first = 0)
 {
     hipError_t e = hipEventRecord(ds->ev_fork, main);
-    for (int i = 0; i < n && e == hipSuccess; ++i) e = hipStreamWaitEvent(ds->side[i], ds->ev_fork, 0);
+    for (int i = first; i < first + n && e == hipSuccess; ++i) e = hipStreamWaitEvent(ds->side[i], ds->ev_fork, 0);
     return e == hipSuccess ? PK_OK : fail(PK_EHIP, hip_msg("stream fork", e));
 }
 
 // join: the caller's stream waits for everything enqueued on the side streams
-pk_status join_streams(DeviceState* ds, hipStream_t main, int n)
+pk_status join_streams(DeviceState* ds, hipStream_t main, int n, int first = 0)
 {
     hipError_t e = hipSuccess;
-    for (int i = 0; i < n && e == hipSuccess; ++i) {
+    for (int i = first; i < first + n && e == hipSuccess; ++i) {
         e = hipEventRecord(ds->ev_join[i], ds->side[i]);
         if (e == hipSuccess) e = hipStreamWaitEvent(main, ds->ev_join[i], 0);
     }

@@ -16,8 +16,8 @@
 //   pool      H3-H5: per pack, gather rows by key, pool per bag, write concatenated
 //   scan      H2: places of the slices' records
 //   scatter   H2: one (key in slice, bag) record per occurrence, grouped by slice
-//   slices    H2: per slice, in LDS: bitmap -> distinct keys (ascending), occurrences grouped by
-//             key, segment offsets, headers of the backward tiles
+//   slices    H2: per slice, in LDS: mark (bitmap, number of distinct keys), a scan, then place: distinct
+//             keys (ascending), occurrences grouped by key, segment offsets, headers of the backward tiles
 //   inverse   H2: inverse[q] = rank(key[q]) from the bitmap and rank samples of the slices
 //   adagrad   H6+H7: per pack, per distinct key: reduce gradients, update row in place
 //   hot       H7: keys whose occurrences span several backward tiles, from their partial sums
@@ -125,10 +125,10 @@ static pk_status forward_impl(const pk_plan* plan, int stages, const char* who, 
         return cols_aligned(plan, p) && aligned16(out) && out_row_stride % 4 == 0 && aligned16(W[p]);
     };
     SliceArgs sa{};
-    sa.tmeta = ds->sort_tables; sa.table_fields = ds->table_fields; sa.T = T;
+    sa.tmeta = ds->sort_tables; sa.tfields = ds->tfields; sa.T = T;
     sa.fmeta = ds->fmeta; sa.pm = ds->pmeta; sa.slot_field = ds->slot_field; sa.st = st; sa.P = P;
     sa.F = F; sa.B = B; sa.nnz = nnz;
-    sa.ids = ids; sa.offsets = offsets;
+    sa.ids = ids; sa.offsets = offsets; sa.small_slices = ds->small_slices;
     sa.packed_offsets = packed_offsets;
     sa.keys = keys; sa.inverse = inverse;
     sa.unique = unique; sa.seg_all = seg; sa.ent_all = seg_ent; sa.ent_mult = plan->any_mean ? 2 : 1;
@@ -146,8 +146,8 @@ static pk_status forward_impl(const pk_plan* plan, int stages, const char* who, 
     // ---- small batches: dedup (and pooling) in one launch ----
     if (L.small && do_dedup) {
         const bool fuse_pool = do_pool && !hot && P <= kFusedPacks;
-        sa.target = kSliceOccSmall;
-        sa.desc = ds->small_desc; sa.done = ds->small_done;
+        sa.target = 0; sa.log_max = kSliceLogMax;
+        sa.desc = ds->small_desc; sa.gdesc = ds->small_desc + kSmallSlicesMax; sa.done = ds->small_done;
         PoolJob pj{};
         int nb = 0, np = 0;
         for (int p = 0; p < P && fuse_pool; ++p) {
@@ -163,7 +163,7 @@ static pk_status forward_impl(const pk_plan* plan, int stages, const char* who, 
         }
         pj.n_packs = np; pj.B = B; pj.n_blocks = nb; pj.out = out; pj.out_stride = out_row_stride;
         const int meta_blocks = (int)blocks_for(n_bags, kSliceThreads * 4, 64);
-        const size_t dyn = (size_t)std::max(1, plan->max_table_fields) * 3 * 4;
+        const size_t dyn = (size_t)std::max(1, plan->max_table_fields) * kSliceTfWords * 4;
         PK_LAUNCH("pk_fused", pk_fused_kernel, dim3((unsigned)(L.n_slices + meta_blocks + nb)), dim3(kSliceThreads), dyn,
                   sa, pj, L.n_slices, meta_blocks);
         if (!do_pool || fuse_pool) return PK_OK;
@@ -178,8 +178,8 @@ static pk_status forward_impl(const pk_plan* plan, int stages, const char* who, 
         return fail(PK_EOVERFLOW, std::string(who) + ": fields, tables and slices per table together exceed what the "
                                   "dedup kernels stage in LDS");
     if (do_dedup && !L.small) {
-        sa.target = kSliceOccLarge;
-        sa.desc = ws.at<uint64_t>(L.slice_desc); sa.done = nullptr;
+        sa.target = kSliceOccLarge; sa.log_max = L.log_max;
+        sa.desc = nullptr; sa.gdesc = nullptr; sa.done = nullptr;
         sa.slice_info = ws.at<SliceInfo>(L.slice_info); sa.rec = ws.at<uint2>(L.rec);
         sa.bitmap = ws.at<uint32_t>(L.bitmap); sa.rank = ws.at<int32_t>(L.rank);
         int32_t* slice_total = ws.at<int32_t>(L.slice_total);
@@ -191,11 +191,11 @@ static pk_status forward_impl(const pk_plan* plan, int stages, const char* who, 
         const size_t keys_lds = (scan_words + (size_t)L.max_table_slices) * 4;
         if (long_bags)
             PK_LAUNCH("pk_keys", pk_keys_kernel<32>, key_grid, dim3(NT), keys_lds, ids, offsets, B, F, P, T, nnz,
-                      sa.target, ds->fmeta, ds->pmeta, ds->sort_tables, ds->slot_field, st, keys, packed_offsets,
+                      sa.target, sa.log_max, ds->fmeta, ds->pmeta, ds->sort_tables, ds->slot_field, st, keys, packed_offsets,
                       slice_total, seg);
         else
             PK_LAUNCH("pk_keys", pk_keys_kernel<256>, key_grid, dim3(NT), keys_lds, ids, offsets, B, F, P, T, nnz,
-                      sa.target, ds->fmeta, ds->pmeta, ds->sort_tables, ds->slot_field, st, keys, packed_offsets,
+                      sa.target, sa.log_max, ds->fmeta, ds->pmeta, ds->sort_tables, ds->slot_field, st, keys, packed_offsets,
                       slice_total, seg);
     }
 
@@ -222,30 +222,67 @@ static pk_status forward_impl(const pk_plan* plan, int stages, const char* who, 
     if (do_dedup && !L.small) {
         int32_t* slice_total = ws.at<int32_t>(L.slice_total);
         int32_t* slice_cursor = ws.at<int32_t>(L.slice_cursor);
-        PK_LAUNCH("pk_slice_scan", pk_slice_scan_kernel, dim3(1), dim3(kScanThreads), (size_t)(T + 1) * 4,
-                  ds->sort_tables, T, F, nnz, sa.target, slice_total, slice_cursor, ws.at<SliceInfo>(L.slice_info),
-                  L.n_slices);
-        const dim3 tile_grid(blocks_for(n_tiles, 1, 256 * 8));
+        int32_t* big_list = ws.at<int32_t>(L.big_list);
+        PK_LAUNCH("pk_slice_scan", pk_slice_scan_kernel, dim3(blocks_for(L.n_slices, kScanThreads, 1 << 20)),
+                  dim3(kScanThreads), (size_t)(T + 1) * 4,
+                  ds->sort_tables, T, F, nnz, sa.target, sa.log_max, slice_total, slice_cursor, ws.at<SliceInfo>(L.slice_info),
+                  L.n_slices, L.log_max == kSliceLogFine ? kBigSliceCount : 0x7FFFFFFF, big_list + kBigSlicesMax, big_list);
+        // the scatter takes larger tiles than the keys kernel (longer runs of records per slice), the
+        // inverse kernel smaller ones (it needs no bag, and many blocks hide its dependent lookups)
+        auto tiles_of = [&](int b) { return (int64_t)F * ((B + b - 1) / b); };
         const size_t sc_lds = (scan_words + 2 * (size_t)L.max_table_slices) * 4;
         if (long_bags)
-            PK_LAUNCH("pk_scatter", pk_scatter_kernel<32>, tile_grid, dim3(NT), sc_lds, offsets, B, F, T, nnz,
-                      sa.target, ds->fmeta, ds->pmeta, ds->sort_tables, ds->slot_field, st, keys, slice_cursor,
-                      ws.at<uint2>(L.rec), L.max_table_slices);
+            PK_LAUNCH("pk_scatter", pk_scatter_kernel<32>, dim3(blocks_for(tiles_of(32), 1, 256 * 8)), dim3(NT), sc_lds,
+                      offsets, B, F, T, nnz, sa.target, sa.log_max, ds->fmeta, ds->pmeta, ds->sort_tables, ds->slot_field,
+                      st, keys, slice_cursor, ws.at<uint2>(L.rec), L.max_table_slices, plan->out_dim);
         else
-            PK_LAUNCH("pk_scatter", pk_scatter_kernel<256>, tile_grid, dim3(NT), sc_lds, offsets, B, F, T, nnz,
-                      sa.target, ds->fmeta, ds->pmeta, ds->sort_tables, ds->slot_field, st, keys, slice_cursor,
-                      ws.at<uint2>(L.rec), L.max_table_slices);
-        if (L.n_slices > 0)
-            PK_LAUNCH("pk_slices", pk_slices_kernel, dim3((unsigned)L.n_slices), dim3(kSliceThreads), 0, sa);
+            PK_LAUNCH("pk_scatter", pk_scatter_kernel<1024>, dim3(blocks_for(tiles_of(1024), 1, 256 * 8)), dim3(NT), sc_lds,
+                      offsets, B, F, T, nnz, sa.target, sa.log_max, ds->fmeta, ds->pmeta, ds->sort_tables, ds->slot_field,
+                      st, keys, slice_cursor, ws.at<uint2>(L.rec), L.max_table_slices, plan->out_dim);
+        const size_t tf_lds = (size_t)std::max(1, plan->max_table_fields) * kSliceTfWords * 4;
+        if (L.n_slices > 0) {
+            SliceArgs sm = sa, sp = sa;
+            sm.slice_nu = ws.at<int32_t>(L.slice_nu);       // the mark launch writes the counts ...
+            sp.slice_nu = ws.at<int32_t>(L.slice_usum);     // ... the place launch reads their running sums
+            sm.big_list = sp.big_list = big_list;
+            sm.n_big = sp.n_big = big_list + kBigSlicesMax;
+            const dim3 sgrid((unsigned)L.n_slices);
+            const bool fine = L.log_max == kSliceLogFine;
+            // the listed slices run beside the others, on a stream of their own (not while kernels are timed one by one)
+            const bool beside = fine && ds->overlap && !ds->prof_on;
+            hipStream_t main_stream = stream;
+            if (beside) { rc = fork_streams(ds, main_stream, 1, DeviceState::kSide - 1); if (rc != PK_OK) return rc; }
+            if (fine) {
+                stream = beside ? ds->side[DeviceState::kSide - 1] : main_stream;
+                PK_LAUNCH("pk_slices_mark_big", pk_slices_big_kernel<kSliceMark>, dim3(kBigSlicesMax), dim3(kSliceThreads), tf_lds, sm);
+                stream = main_stream;
+                PK_LAUNCH("pk_slices_mark", pk_slices_kernel<kSliceMark>, sgrid, dim3(kFineThreads), tf_lds, sm);
+            } else {
+                PK_LAUNCH("pk_slices_mark", pk_slices_wide_kernel<kSliceMark>, sgrid, dim3(kSliceThreads), tf_lds, sm);
+            }
+            if (beside) { rc = join_streams(ds, main_stream, 1, DeviceState::kSide - 1); if (rc != PK_OK) return rc; }
+            PK_LAUNCH("pk_unique_scan", pk_unique_scan_kernel, dim3(blocks_for(L.n_slices, kScanThreads, 1 << 20)),
+                      dim3(kScanThreads), 0, sm.slice_nu, L.n_slices, sp.slice_nu);
+            if (beside) { rc = fork_streams(ds, main_stream, 1, DeviceState::kSide - 1); if (rc != PK_OK) return rc; }
+            if (fine) {
+                stream = beside ? ds->side[DeviceState::kSide - 1] : main_stream;
+                PK_LAUNCH("pk_slices_place_big", pk_slices_big_kernel<kSlicePlace>, dim3(kBigSlicesMax), dim3(kSliceThreads), tf_lds, sp);
+                stream = main_stream;
+                PK_LAUNCH("pk_slices_place", pk_slices_kernel<kSlicePlace>, sgrid, dim3(kFineThreads), tf_lds, sp);
+            } else {
+                PK_LAUNCH("pk_slices_place", pk_slices_wide_kernel<kSlicePlace>, sgrid, dim3(kSliceThreads), tf_lds, sp);
+            }
+            if (beside) { rc = join_streams(ds, main_stream, 1, DeviceState::kSide - 1); if (rc != PK_OK) return rc; }
+        }
         const size_t inv_lds = field_scan_words(F) * 4;
         if (long_bags)
-            PK_LAUNCH("pk_inverse", pk_inverse_kernel<32>, tile_grid, dim3(NT), inv_lds, offsets, B, F, nnz, ds->fmeta,
-                      ds->sort_tables, ds->slot_field, st, keys, reinterpret_cast<const uint4*>(sa.bitmap), sa.rank,
-                      inverse);
+            PK_LAUNCH("pk_inverse", pk_inverse_kernel<8>, dim3(blocks_for(tiles_of(8), 1, 256 * 64)), dim3(NT), inv_lds,
+                      offsets, B, F, nnz, ds->fmeta, ds->sort_tables, ds->slot_field, st, keys,
+                      reinterpret_cast<const uint4*>(sa.bitmap), sa.rank, inverse);
         else
-            PK_LAUNCH("pk_inverse", pk_inverse_kernel<256>, tile_grid, dim3(NT), inv_lds, offsets, B, F, nnz, ds->fmeta,
-                      ds->sort_tables, ds->slot_field, st, keys, reinterpret_cast<const uint4*>(sa.bitmap), sa.rank,
-                      inverse);
+            PK_LAUNCH("pk_inverse", pk_inverse_kernel<64>, dim3(blocks_for(tiles_of(64), 1, 256 * 64)), dim3(NT), inv_lds,
+                      offsets, B, F, nnz, ds->fmeta, ds->sort_tables, ds->slot_field, st, keys,
+                      reinterpret_cast<const uint4*>(sa.bitmap), sa.rank, inverse);
     }
     if (n_side) { rc = join_streams(ds, stream, n_side); if (rc != PK_OK) return rc; }
     return PK_OK;

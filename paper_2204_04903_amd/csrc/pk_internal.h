@@ -20,15 +20,19 @@ constexpr size_t kAlign = 256;
 
 // The dedup cuts every table's key range into slices of 2^k keys; one block owns a slice and keeps
 // the slice's bitmap, its popcount prefix and the occurrence counters of its distinct keys in LDS.
+// Two shapes of slice block: 1024 threads for slices of up to 128 K keys (small batches, where a
+// block scans its table's IDs itself, and large batches with tables too long for the other shape),
+// and 256 threads for slices of up to 32 K keys (large batches: many small blocks hide the latency
+// of the few dependent memory accesses a slice makes).
 constexpr int kSliceLogMin = 10;           // 1 K keys
 constexpr int kSliceLogMax = 17;           // 128 K keys: 4096 bitmap words
+constexpr int kSliceLogFine = 15;          // 32 K keys: 1024 bitmap words
 constexpr int kSliceWordsMax = 1 << (kSliceLogMax - 5);
-constexpr int kSliceRanks = 8192;          // distinct keys whose occurrences are counted and placed per round
-constexpr int kSliceOccLarge = 8192;       // occurrences per slice aimed at when the occurrences are partitioned
-constexpr int kSliceOccSmall = 1024;       // ... and when every slice block scans its table's IDs itself
+constexpr int kSliceOccLarge = 2048;       // occurrences per slice aimed at when the occurrences are partitioned
 constexpr int64_t kSmallNnz = 1 << 19;     // below this many occurrences the forward pass is one launch
 constexpr int kSmallSlicesMax = 4096;      // ... if it has no more slices than this (descriptors the library owns)
 constexpr int kTableSlicesMax = 8192;      // slices per table (their counters are staged in LDS): rows <= 2^30
+constexpr int64_t kFineRowsMax = (int64_t)4096 << kSliceLogFine;   // longest table the 32 K-key shape is used with
 
 #if defined(__HIPCC__)
 #define PK_HD __host__ __device__
@@ -36,23 +40,54 @@ constexpr int kTableSlicesMax = 8192;      // slices per table (their counters a
 #define PK_HD
 #endif
 
-// Slices of one table: 2^log_keys keys each, n of them.  The aim is `target` occurrences per slice
-// if every field of the layer had the same number of occurrences.  Depends on sizes only (no data),
-// so host and device derive the same cut.
+// Slices of one table for a partitioned call: 2^log_keys keys each, n of them.  The aim is `target`
+// occurrences per slice if every field of the layer had the same number of occurrences.  Depends on
+// sizes only (no data), so host and device derive the same cut.
 struct SliceGeom { int32_t log_keys; int32_t n; };
-PK_HD inline SliceGeom slice_geom(uint32_t rows, int32_t n_table_fields, int32_t F, int64_t nnz, int32_t target)
+PK_HD inline SliceGeom slice_geom(uint32_t rows, int32_t n_table_fields, int32_t F, int64_t nnz, int32_t target,
+                                  int32_t log_max)
 {
     const int64_t est = (nnz * n_table_fields + F - 1) / F;
     int64_t want = (est + target - 1) / target;
     if (want < 1) want = 1;
     const int64_t per = ((int64_t)rows + want - 1) / want;
     int lg = kSliceLogMin;
-    while (lg < kSliceLogMax && ((int64_t)1 << lg) < per) ++lg;
+    while (lg < log_max && ((int64_t)1 << lg) < per) ++lg;
     SliceGeom g;
     g.log_keys = lg;
     g.n = (int32_t)(((int64_t)rows + ((int64_t)1 << lg) - 1) >> lg);
     return g;
 }
+
+// Small batches: the cut depends on the plan alone (up to 8 slices per table, fewer when there are
+// many tables), so the list of slices is made once, on the host.
+inline SliceGeom slice_geom_small(int64_t rows, int32_t n_tables)
+{
+    int64_t want = 1024 / (n_tables > 0 ? n_tables : 1);
+    if (want > 8) want = 8;
+    if (want < 1) want = 1;
+    const int64_t per = (rows + want - 1) / want;
+    int lg = kSliceLogMin;
+    while (lg < kSliceLogMax && ((int64_t)1 << lg) < per) ++lg;
+    SliceGeom g;
+    g.log_keys = lg;
+    g.n = (int32_t)((rows + ((int64_t)1 << lg) - 1) >> lg);
+    return g;
+}
+
+// One slice of the small-batch cut; static, device side, in (pack, table, slice) order.
+struct SmallSlice {
+    int32_t table;           // index in the table list
+    int32_t idx;             // slice of the table
+    int32_t log_keys;
+    int32_t n_table_slices;
+    int32_t pack_first;      // the pack's first slice
+    int32_t is_last;         // the pack's last slice
+    int32_t pack;
+    int32_t field_begin, field_end;   // the table's fields in the table field list
+    uint32_t key_lo, rows;   // the table's first key inside its pack, its rows
+    int32_t pad;
+};
 
 // Per field, device side (indexed by field index).
 struct FieldMeta {
@@ -121,11 +156,12 @@ struct Pack {
 // Byte offsets of the workspace's arrays for one (plan, B, nnz).
 struct Layout {
     size_t state, packed_offsets, keys, inverse, seg_ent, tile_hdr, unique, seg, ghot,
-           clear_begin, slice_total, slice_desc, slice_cursor, slice_info, rec, bitmap, rank, total;
+           clear_begin, slice_total, slice_nu, big_list, slice_cursor, slice_usum, slice_info, rec, bitmap, rank, total;
     size_t clear_bytes;          // what the partitioned path clears before its first kernel: per-pack state,
-                                 // slice totals and look-back descriptors, contiguous from `clear_begin`
-    int32_t n_slices;            // slices of all tables for this nnz
+                                 // slice totals and distinct-key counts, contiguous from `clear_begin`
+    int32_t n_slices;            // slices of all tables for this call
     int32_t max_table_slices;    // most slices any table has
+    int32_t log_max;             // partitioned path: largest slice (log2 of its keys) of this call
     int32_t dmax;
     int32_t pos_tile;            // occurrences per backward tile for this nnz
     bool small;                  // the forward pass's dedup is one launch (every slice block scans its table's IDs)
@@ -145,6 +181,7 @@ struct pk_plan {
     std::vector<int32_t> slot_field;      // fields in (pack, slot) order
     std::vector<pk::TableMeta> sort_tables;   // tables with fields, in (pack, first key) order
     std::vector<int32_t> table_fields;        // per entry of sort_tables: the fields that read it
+    std::vector<pk::SmallSlice> small_slices; // the cut used by the one-launch forward pass
     int64_t out_dim = 0;
     bool any_mean = false;
     int64_t bitmap_words = 0;             // all tables' bitmaps, each padded to whole largest slices

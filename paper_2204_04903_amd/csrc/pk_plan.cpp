@@ -37,14 +37,14 @@ int32_t pos_tile_for(int64_t nnz)
     return (int32_t)t;
 }
 
-// slices of all tables (and the most any table has) when a slice aims at `target` occurrences
-static void count_slices(const pk_plan* plan, int64_t nnz, int32_t target, int64_t* total, int32_t* most)
+// slices of all tables (and the most any table has) of a partitioned call
+static void count_slices(const pk_plan* plan, int64_t nnz, int32_t log_max, int64_t* total, int32_t* most)
 {
     const int32_t F = (int32_t)plan->fields.size();
     *total = 0;
     *most = 0;
     for (const TableMeta& tm : plan->sort_tables) {
-        const SliceGeom g = slice_geom(tm.rows, tm.field_end - tm.field_begin, F, nnz, target);
+        const SliceGeom g = slice_geom(tm.rows, tm.field_end - tm.field_begin, F, nnz, kSliceOccLarge, log_max);
         *total += g.n;
         *most = std::max(*most, g.n);
     }
@@ -55,11 +55,16 @@ Layout make_layout(const pk_plan* plan, int32_t B, int64_t nnz)
     const size_t F = plan->fields.size(), P = plan->packs.size();
     const size_t n = (size_t)std::max<int64_t>(nnz, 1);
     Layout L{};
-    int64_t slices = 0;
+    int64_t slices = (int64_t)plan->small_slices.size();
     int32_t most = 0;
-    count_slices(plan, nnz, kSliceOccSmall, &slices, &most);
     L.small = nnz < kSmallNnz && slices <= kSmallSlicesMax && !(plan->opts.debug & 2);
-    if (!L.small) count_slices(plan, nnz, kSliceOccLarge, &slices, &most);
+    L.log_max = kSliceLogMax;
+    if (!L.small) {
+        L.log_max = kSliceLogFine;
+        for (const TableMeta& tm : plan->sort_tables)
+            if ((int64_t)tm.rows > kFineRowsMax) L.log_max = kSliceLogMax;
+        count_slices(plan, nnz, L.log_max, &slices, &most);
+    }
     L.n_slices = (int32_t)slices;
     L.max_table_slices = most;
     size_t off = 0;
@@ -67,9 +72,11 @@ Layout make_layout(const pk_plan* plan, int32_t B, int64_t nnz)
     L.clear_begin    = off;
     L.state          = take(P * sizeof(PackState));
     L.slice_total    = take(L.small ? 0 : (size_t)slices * 4);
-    L.slice_desc     = take(L.small ? 0 : (size_t)slices * 8);
+    L.slice_nu       = take(L.small ? 0 : (size_t)slices * 4);
+    L.big_list       = take(L.small ? 0 : (size_t)(256 + 64) * 4);          // listed slices, then their count
     L.clear_bytes    = off - L.clear_begin;
     L.slice_cursor   = take(L.small ? 0 : (size_t)slices * 4);
+    L.slice_usum     = take(L.small ? 0 : (size_t)slices * 4);
     L.slice_info     = take(L.small ? 0 : (size_t)slices * sizeof(SliceInfo));
     L.packed_offsets = take((F * (size_t)B + P) * 4);
     L.keys           = take(n * 4);
@@ -240,6 +247,23 @@ pk_status pk_plan_create(const pk_table_desc* tables, int32_t n_tables, const pk
     if (pl->bitmap_words >= ((int64_t)1 << 32)) {
         delete pl;
         return fail(PK_EOVERFLOW, "pk_plan_create: the tables' bitmaps do not fit 2^32 words");
+    }
+    // the cut of the one-launch forward pass
+    for (size_t p = 0; p < pl->packs.size(); ++p) {
+        const Pack& k = pl->packs[p];
+        const int32_t pack_first = (int32_t)pl->small_slices.size();
+        for (int32_t i = 0; i < k.n_stables; ++i) {
+            const TableMeta& tm = pl->sort_tables[k.first_stable + i];
+            const SliceGeom g = slice_geom_small(tm.rows, (int32_t)pl->sort_tables.size());
+            for (int32_t j = 0; j < g.n; ++j) {
+                SmallSlice ss{};
+                ss.table = k.first_stable + i; ss.idx = j; ss.log_keys = g.log_keys; ss.n_table_slices = g.n;
+                ss.pack_first = pack_first; ss.is_last = (i + 1 == k.n_stables && j + 1 == g.n) ? 1 : 0;
+                ss.pack = (int32_t)p; ss.field_begin = tm.field_begin; ss.field_end = tm.field_end;
+                ss.key_lo = tm.key_lo; ss.rows = tm.rows;
+                pl->small_slices.push_back(ss);
+            }
+        }
     }
     for (auto& pk_ : pl->packs) pl->dmax = std::max(pl->dmax, pk_.dim);
     *out = pl;
