@@ -135,6 +135,22 @@ pk_status pk_forward(const pk_plan* plan, void* const* W,
                      float* out, int64_t out_row_stride,
                      void* workspace, size_t ws_bytes, void* hip_stream);
 
+/* ---- the forward pass for callers that cannot allocate -------------------------
+ * For callers that may not allocate device memory around the call: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  The same
+ * kernels as pk_forward, with the workspace, the plan's device metadata and the
+ * scan descriptors in a static device array of 32 MiB that the library holds on
+ * every GPU it runs on until the process ends; neither this call nor anything it
+ * runs calls hipMalloc, hipFree or another allocating routine (no internal streams
+ * or events either: every kernel runs on hip_stream).  Arguments as for pk_forward,
+ * without the workspace.  PK_EWORKSPACE when the plan's metadata plus
+ * pk_workspace_bytes(plan, B, nnz) exceed the 32 MiB.  All calls on one GPU share
+ * that array: calls that overlap on one GPU race, and the dedup context of a call
+ * (there is no pointer to hand to pk_backward_update) lasts until the next call. */
+pk_status pk_forward_static(const pk_plan* plan, void* const* W,
+                            const int64_t* ids, const int32_t* offsets, int32_t B, int64_t nnz,
+                            float* out, int64_t out_row_stride, void* hip_stream);
+
 /* ---- backward + update (Sec. II-D: mirror of the forward pass; Adagrad from
  * the workload configurations) -------------------------------------------------
  * For every distinct key u of the preceding pk_forward (same plan, B, nnz and

@@ -25,7 +25,7 @@ EXPORTS = [
     "pk_plan_table_slot", "pk_plan_field_col", "pk_plan_out_dim", "pk_workspace_bytes", "pk_forward",
     "pk_backward_update", "pk_ctx_pack", "pk_ctx_error", "pk_profile_enable", "pk_profile_read", "pk_last_error",
     "pk_hh_scratch_bytes", "pk_hh_init", "pk_hh_forward", "pk_hh_backward_update", "pk_hh_end_iteration",
-    "pk_hh_hot_count", "pk_forward_dedup", "pk_forward_pool", "pk_micro_batch_size",
+    "pk_hh_hot_count", "pk_forward_dedup", "pk_forward_pool", "pk_micro_batch_size", "pk_forward_static",
 ]
 
 
@@ -101,6 +101,8 @@ def lib():
         L.pk_workspace_bytes.argtypes = [vp, i32, i64]
         L.pk_forward.restype = ctypes.c_int
         L.pk_forward.argtypes = [vp, ctypes.POINTER(vp), vp, vp, i32, i64, vp, i64, vp, ctypes.c_size_t, vp]
+        L.pk_forward_static.restype = ctypes.c_int
+        L.pk_forward_static.argtypes = [vp, ctypes.POINTER(vp), vp, vp, i32, i64, vp, i64, vp]
         L.pk_forward_dedup.restype = ctypes.c_int
         L.pk_forward_dedup.argtypes = [vp, vp, vp, i32, i64, vp, ctypes.c_size_t, vp]
         L.pk_forward_pool.restype = ctypes.c_int
@@ -230,6 +232,12 @@ def pk_forward(plan: int, W: Sequence, ids, offsets, B: int, nnz: int, out, out_
                workspace, ws_bytes: int, stream: int = 0) -> None:
     _check(lib().pk_forward(plan, _ptr_array(W), _ptr(ids), _ptr(offsets), B, nnz, _ptr(out), out_row_stride,
                             _ptr(workspace), ws_bytes, stream))
+
+
+def pk_forward_static(plan: int, W: Sequence, ids, offsets, B: int, nnz: int, out, out_row_stride: int,
+                      stream: int = 0) -> None:
+    _check(lib().pk_forward_static(plan, _ptr_array(W), _ptr(ids), _ptr(offsets), B, nnz, _ptr(out), out_row_stride,
+                                   stream))
 
 
 def pk_forward_dedup(plan: int, ids, offsets, B: int, nnz: int, workspace, ws_bytes: int, stream: int = 0) -> None:

@@ -39,6 +39,86 @@ std::string hip_msg(const char* what, hipError_t e)
     return std::string(what) + ": " + hipGetErrorString(e);
 }
 
+// The plan's device-side metadata as host arrays, and where each array goes inside one block of
+// device memory (256-byte aligned pieces): look-back descriptors and their counter first.
+struct MetaImage {
+    std::vector<FieldMeta> fm;
+    std::vector<PackMeta> pmv;
+    std::vector<TableField> tfi;
+    size_t o_desc, o_done, o_fm, o_pm, o_slot, o_ss, o_tfi, o_tab, o_tf, total;
+};
+
+void build_meta_image(const pk_plan* plan, MetaImage* mi)
+{
+    const size_t F = plan->fields.size(), P = plan->packs.size();
+    mi->fm.resize(F);
+    for (size_t f = 0; f < F; ++f) {
+        const int32_t t = plan->fields[f].table;
+        mi->fm[f].base_row = (uint32_t)plan->table_base[t];
+        mi->fm[f].rows = (uint32_t)plan->tables[t].rows;
+        mi->fm[f].col = (int32_t)plan->field_col[f];
+        mi->fm[f].pack = plan->field_pack[f];
+        mi->fm[f].slot = plan->field_slot[f];
+        mi->fm[f].pool = plan->fields[f].pool;
+        mi->fm[f].stable = -1;
+        mi->fm[f].pad = 0;
+    }
+    for (size_t i = 0; i < plan->sort_tables.size(); ++i)
+        for (int32_t j = plan->sort_tables[i].field_begin; j < plan->sort_tables[i].field_end; ++j)
+            mi->fm[plan->table_fields[j]].stable = (int32_t)i;
+    mi->pmv.resize(P);
+    for (size_t p = 0; p < P; ++p) {
+        const Pack& k = plan->packs[p];
+        mi->pmv[p].dim = k.dim; mi->pmv[p].dtype = k.dtype; mi->pmv[p].n_fields = (int32_t)k.fields.size();
+        mi->pmv[p].first_slot = k.first_slot; mi->pmv[p].has_mean = k.has_mean ? 1 : 0;
+        mi->pmv[p].first_stable = k.first_stable; mi->pmv[p].n_stables = k.n_stables; mi->pmv[p].pad = 0;
+    }
+    mi->tfi.resize(plan->table_fields.size());
+    for (size_t i = 0; i < mi->tfi.size(); ++i) {
+        const int32_t f = plan->table_fields[i];
+        mi->tfi[i] = TableField{f, plan->field_slot[f], (int32_t)plan->field_col[f], plan->fields[f].pool};
+    }
+    auto pad = [](size_t b) { return (b + 255) / 256 * 256; };
+    size_t off = 0;
+    auto take = [&](size_t bytes) { const size_t o = off; off += pad(bytes); return o; };
+    mi->o_desc = take(((size_t)kSmallSlicesMax + kSmallSlicesMax / 64 + 4096 + 2) * 8);   // per slice, then per group of 64
+    mi->o_done = take(256);
+    mi->o_fm   = take(F * sizeof(FieldMeta));
+    mi->o_pm   = take(P * sizeof(PackMeta));
+    mi->o_slot = take(F * 4);
+    mi->o_ss   = take(plan->small_slices.size() * sizeof(SmallSlice));
+    mi->o_tfi  = take(mi->tfi.size() * sizeof(TableField));
+    mi->o_tab  = take(plan->sort_tables.size() * sizeof(TableMeta));
+    mi->o_tf   = take(plan->table_fields.size() * 4);
+    mi->total = off;
+}
+
+void point_into(DeviceState* ds, char* base, const MetaImage& mi)
+{
+    ds->small_desc = reinterpret_cast<uint64_t*>(base + mi.o_desc);
+    ds->small_done = reinterpret_cast<int32_t*>(base + mi.o_done);
+    ds->fmeta = reinterpret_cast<FieldMeta*>(base + mi.o_fm);
+    ds->pmeta = reinterpret_cast<PackMeta*>(base + mi.o_pm);
+    ds->slot_field = reinterpret_cast<int32_t*>(base + mi.o_slot);
+    ds->small_slices = reinterpret_cast<SmallSlice*>(base + mi.o_ss);
+    ds->tfields = reinterpret_cast<TableField*>(base + mi.o_tfi);
+    ds->sort_tables = reinterpret_cast<TableMeta*>(base + mi.o_tab);
+    ds->table_fields = reinterpret_cast<int32_t*>(base + mi.o_tf);
+}
+
+// the pieces of the image that hold data (the descriptors and their counter only have to be zero)
+template <typename Fn>
+void for_meta_pieces(const pk_plan* plan, const MetaImage& mi, Fn&& fn)
+{
+    fn(mi.o_fm, mi.fm.data(), mi.fm.size() * sizeof(FieldMeta));
+    fn(mi.o_pm, mi.pmv.data(), mi.pmv.size() * sizeof(PackMeta));
+    fn(mi.o_slot, plan->slot_field.data(), plan->slot_field.size() * 4);
+    fn(mi.o_ss, plan->small_slices.data(), plan->small_slices.size() * sizeof(SmallSlice));
+    fn(mi.o_tfi, mi.tfi.data(), mi.tfi.size() * sizeof(TableField));
+    fn(mi.o_tab, plan->sort_tables.data(), plan->sort_tables.size() * sizeof(TableMeta));
+    fn(mi.o_tf, plan->table_fields.data(), plan->table_fields.size() * 4);
+}
+
 pk_status ensure_device_state(const pk_plan* cplan, DeviceState** out)
 {
     pk_plan* plan = const_cast<pk_plan*>(cplan);
@@ -52,65 +132,16 @@ pk_status ensure_device_state(const pk_plan* cplan, DeviceState** out)
     if (ds) return fail(PK_EINVAL, "a plan can be used on one device only");
     ds = new DeviceState();
     ds->device = dev;
-    const size_t F = plan->fields.size(), P = plan->packs.size();
-    std::vector<FieldMeta> fm(F);
-    for (size_t f = 0; f < F; ++f) {
-        const int32_t t = plan->fields[f].table;
-        fm[f].base_row = (uint32_t)plan->table_base[t];
-        fm[f].rows = (uint32_t)plan->tables[t].rows;
-        fm[f].col = (int32_t)plan->field_col[f];
-        fm[f].pack = plan->field_pack[f];
-        fm[f].slot = plan->field_slot[f];
-        fm[f].pool = plan->fields[f].pool;
-        fm[f].stable = -1;
-        fm[f].pad = 0;
-    }
-    for (size_t i = 0; i < plan->sort_tables.size(); ++i)
-        for (int32_t j = plan->sort_tables[i].field_begin; j < plan->sort_tables[i].field_end; ++j)
-            fm[plan->table_fields[j]].stable = (int32_t)i;
-    std::vector<PackMeta> pmv(P);
-    for (size_t p = 0; p < P; ++p) {
-        const Pack& k = plan->packs[p];
-        pmv[p].dim = k.dim; pmv[p].dtype = k.dtype; pmv[p].n_fields = (int32_t)k.fields.size();
-        pmv[p].first_slot = k.first_slot; pmv[p].has_mean = k.has_mean ? 1 : 0;
-        pmv[p].first_stable = k.first_stable; pmv[p].n_stables = k.n_stables; pmv[p].pad = 0;
-    }
-    auto pad = [](size_t b) { return (b + 255) / 256 * 256; };
-    const size_t b_f = pad(F * sizeof(FieldMeta)), b_p = pad(P * sizeof(PackMeta)), b_s = pad(F * 4);
-    const size_t b_d = pad(((size_t)kSmallSlicesMax + kSmallSlicesMax / 64 + 4096 + 2) * 8), b_c = 256;   // per slice, then per group of 64
-    const size_t b_ss = pad(plan->small_slices.size() * sizeof(SmallSlice));
-    const size_t b_tfi = pad(plan->table_fields.size() * sizeof(TableField));
-    const size_t b_t = pad(plan->sort_tables.size() * sizeof(TableMeta)), b_tf = pad(plan->table_fields.size() * 4);
-    e = hipMalloc(&ds->blob, b_f + b_p + b_s + b_d + b_c + b_ss + b_tfi + b_t + b_tf + 256);
+    MetaImage mi;
+    build_meta_image(plan, &mi);
+    e = hipMalloc(&ds->blob, mi.total);
     if (e != hipSuccess) { delete ds; return fail(PK_EHIP, hip_msg("hipMalloc(plan metadata)", e)); }
-    {
-        char* at = static_cast<char*>(ds->blob);
-        ds->fmeta = reinterpret_cast<FieldMeta*>(at); at += b_f;
-        ds->pmeta = reinterpret_cast<PackMeta*>(at); at += b_p;
-        ds->slot_field = reinterpret_cast<int32_t*>(at); at += b_s;
-        ds->small_desc = reinterpret_cast<uint64_t*>(at); at += b_d;
-        ds->small_done = reinterpret_cast<int32_t*>(at); at += b_c;
-        ds->small_slices = reinterpret_cast<SmallSlice*>(at); at += b_ss;
-        ds->tfields = reinterpret_cast<TableField*>(at); at += b_tfi;
-        ds->sort_tables = reinterpret_cast<TableMeta*>(at); at += b_t;
-        ds->table_fields = reinterpret_cast<int32_t*>(at);
-    }
-    auto up = [&](void* dst, const void* src, size_t bytes) {
-        if (e == hipSuccess && bytes) e = hipMemcpy(dst, src, bytes, hipMemcpyHostToDevice);
-    };
-    up(ds->fmeta, fm.data(), F * sizeof(FieldMeta));
-    up(ds->pmeta, pmv.data(), P * sizeof(PackMeta));
-    up(ds->slot_field, plan->slot_field.data(), F * 4);
-    if (e == hipSuccess) e = hipMemset(ds->small_desc, 0, b_d + b_c);
-    up(ds->small_slices, plan->small_slices.data(), plan->small_slices.size() * sizeof(SmallSlice));
-    std::vector<TableField> tfi(plan->table_fields.size());
-    for (size_t i = 0; i < tfi.size(); ++i) {
-        const int32_t f = plan->table_fields[i];
-        tfi[i] = TableField{f, plan->field_slot[f], (int32_t)plan->field_col[f], plan->fields[f].pool};
-    }
-    up(ds->tfields, tfi.data(), tfi.size() * sizeof(TableField));
-    up(ds->sort_tables, plan->sort_tables.data(), plan->sort_tables.size() * sizeof(TableMeta));
-    up(ds->table_fields, plan->table_fields.data(), plan->table_fields.size() * 4);
+    char* base = static_cast<char*>(ds->blob);
+    point_into(ds, base, mi);
+    e = hipMemset(base, 0, mi.o_fm);                   // descriptors and their counter start at zero
+    for_meta_pieces(plan, mi, [&](size_t off, const void* src, size_t bytes) {
+        if (e == hipSuccess && bytes) e = hipMemcpy(base + off, src, bytes, hipMemcpyHostToDevice);
+    });
     if (e != hipSuccess) { (void)hipFree(ds->blob); delete ds; return fail(PK_EHIP, hip_msg("hipMemcpy(plan metadata)", e)); }
     for (int i = 0; i < DeviceState::kSide && e == hipSuccess; ++i) {
         e = hipStreamCreateWithFlags(&ds->side[i], hipStreamNonBlocking);     // default priority

@@ -34,6 +34,11 @@
 
 using namespace pk;
 
+// The scratch of pk_forward_static: workspace, plan metadata and look-back descriptors of callers that
+// cannot allocate.  Every GPU the library runs on holds its own copy until the process ends.
+constexpr size_t kStaticScratchBytes = (size_t)32 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
 // One translation unit; the kernels and their launch helpers are kept in section files:
 //   dev_common.h   block scans, folding hash, look-back prefix sums, tile order
 //   dev_dedup.h    keys, slice scan, scatter, slices, inverse (H1, H2)
@@ -88,7 +93,7 @@ extern "C" {
 // dedup stage filled.  hot: per pack, where the rows of a Hot-storage live (HybridHash), or NULL.
 enum { kDedup = 1, kPool = 2 };
 
-static pk_status forward_impl(const pk_plan* plan, int stages, const char* who, void* const* W, const HotView* hot,
+static pk_status forward_impl(const pk_plan* plan, DeviceState* ds_given, int stages, const char* who, void* const* W, const HotView* hot,
                               const int64_t* ids, const int32_t* offsets, int32_t B, int64_t nnz, float* out,
                               int64_t out_row_stride, void* workspace, size_t ws_bytes, void* hip_stream)
 {
@@ -102,9 +107,11 @@ static pk_status forward_impl(const pk_plan* plan, int stages, const char* who, 
         if (!W[p]) return fail(PK_EINVAL, std::string(who) + ": W[" + std::to_string(p) + "] is NULL");
     if (do_pool && out_row_stride < plan->out_dim)
         return fail(PK_ESHAPE, std::string(who) + ": out_row_stride is smaller than out_dim");
-    DeviceState* ds = nullptr;
-    rc = ensure_device_state(plan, &ds);
-    if (rc != PK_OK) return rc;
+    DeviceState* ds = ds_given;
+    if (!ds) {
+        rc = ensure_device_state(plan, &ds);
+        if (rc != PK_OK) return rc;
+    }
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     Ws ws{static_cast<char*>(workspace), make_layout(plan, B, nnz)};
     const Layout& L = ws.L;
@@ -292,22 +299,87 @@ pk_status pk_forward(const pk_plan* plan, void* const* W, const int64_t* ids, co
                      int64_t nnz, float* out, int64_t out_row_stride, void* workspace, size_t ws_bytes,
                      void* hip_stream)
 {
-    return forward_impl(plan, kDedup | kPool, "pk_forward", W, nullptr, ids, offsets, B, nnz, out, out_row_stride,
+    return forward_impl(plan, nullptr, kDedup | kPool, "pk_forward", W, nullptr, ids, offsets, B, nnz, out, out_row_stride,
                         workspace, ws_bytes, hip_stream);
 }
 
 pk_status pk_forward_dedup(const pk_plan* plan, const int64_t* ids, const int32_t* offsets, int32_t B, int64_t nnz,
                    void* workspace, size_t ws_bytes, void* hip_stream)
 {
-    return forward_impl(plan, kDedup, "pk_forward_dedup", nullptr, nullptr, ids, offsets, B, nnz, nullptr, 0, workspace,
+    return forward_impl(plan, nullptr, kDedup, "pk_forward_dedup", nullptr, nullptr, ids, offsets, B, nnz, nullptr, 0, workspace,
                         ws_bytes, hip_stream);
 }
 
 pk_status pk_forward_pool(const pk_plan* plan, void* const* W, int32_t B, int64_t nnz, float* out, int64_t out_row_stride,
                   void* workspace, size_t ws_bytes, void* hip_stream)
 {
-    return forward_impl(plan, kPool, "pk_forward_pool", W, nullptr, nullptr, nullptr, B, nnz, out, out_row_stride, workspace,
+    return forward_impl(plan, nullptr, kPool, "pk_forward_pool", W, nullptr, nullptr, nullptr, B, nnz, out, out_row_stride, workspace,
                         ws_bytes, hip_stream);
+}
+
+// ---- the forward pass for callers that cannot allocate --------------------------------------
+// Plan metadata reaches the scratch through kernel arguments (no copy engine, no staging buffer).
+struct PutChunk { unsigned char b[2048]; };
+__global__ void __launch_bounds__(256)
+pk_put_kernel(unsigned char* dst, PutChunk c, int n)
+{
+    for (int i = threadIdx.x; i < n; i += 256) dst[i] = c.b[i];
+}
+
+namespace {
+constexpr int kStaticDevices = 64;
+struct StaticDev {
+    unsigned char* ptr = nullptr;        // this device's copy of `scratch`
+    uint64_t plan_serial = 0;            // whose metadata the scratch holds
+    DeviceState ds;                      // pointers into the scratch; no streams, no events
+};
+StaticDev g_static[kStaticDevices];
+std::mutex g_static_mu;
+}  // namespace
+
+pk_status pk_forward_static(const pk_plan* plan, void* const* W, const int64_t* ids, const int32_t* offsets, int32_t B,
+                            int64_t nnz, float* out, int64_t out_row_stride, void* hip_stream)
+{
+    if (!plan) return fail(PK_EINVAL, "pk_forward_static: plan is NULL");
+    if (B <= 0 || nnz < 0 || nnz >= ((int64_t)1 << 31)) return fail(PK_ESHAPE, "pk_forward_static: bad B or nnz");
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail(PK_EHIP, hip_msg("hipGetDevice", e));
+    if (dev < 0 || dev >= kStaticDevices) return fail(PK_EINVAL, "pk_forward_static: device index out of range");
+    std::lock_guard<std::mutex> lock(g_static_mu);
+    StaticDev& sd = g_static[dev];
+    if (!sd.ptr) {                               // once per device, with that device current
+        unsigned char* ptr = nullptr;
+        e = hipGetSymbolAddress(reinterpret_cast<void**>(&ptr), HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !ptr) return fail(PK_EHIP, hip_msg("hipGetSymbolAddress(scratch)", e));
+        sd.ptr = ptr;
+        sd.ds.device = dev;
+        sd.ds.overlap = false;                   // no internal streams: every kernel on the caller's stream
+    }
+    MetaImage mi;
+    build_meta_image(plan, &mi);
+    const Layout L = make_layout(plan, B, nnz);
+    if (mi.total + L.total > kStaticScratchBytes)
+        return fail(PK_EWORKSPACE, "pk_forward_static: this plan, B and nnz need " + std::to_string(mi.total + L.total) +
+                                   " bytes of scratch; the static scratch holds " + std::to_string(kStaticScratchBytes));
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    if (sd.plan_serial != plan->serial) {        // another plan's metadata (or none) is there: put this plan's
+        pk_status rc = PK_OK;
+        for_meta_pieces(plan, mi, [&](size_t off, const void* src, size_t bytes) {
+            for (size_t done = 0; done < bytes && rc == PK_OK; done += sizeof(PutChunk)) {
+                PutChunk c;
+                const size_t n = std::min(sizeof(PutChunk), bytes - done);
+                std::copy(static_cast<const unsigned char*>(src) + done, static_cast<const unsigned char*>(src) + done + n, c.b);
+                pk_put_kernel<<<1, 256, 0, stream>>>(sd.ptr + off + done, c, (int)n);
+                if (hipGetLastError() != hipSuccess) rc = fail(PK_EHIP, "pk_forward_static: launch of pk_put failed");
+            }
+        });
+        if (rc != PK_OK) return rc;
+        sd.plan_serial = plan->serial;
+    }
+    point_into(&sd.ds, reinterpret_cast<char*>(sd.ptr), mi);
+    return forward_impl(plan, &sd.ds, kDedup | kPool, "pk_forward_static", W, nullptr, ids, offsets, B, nnz, out, out_row_stride,
+                        sd.ptr + mi.total, kStaticScratchBytes - mi.total, hip_stream);
 }
 
 static pk_status backward_impl(const pk_plan* plan, void* const* W, float* const* A, const HotView* hot,
@@ -459,7 +531,7 @@ pk_status pk_hh_forward(const pk_plan* plan, const pk_hh_pack* packs, const int6
     if (rc != PK_OK) return rc;
     std::vector<void*> W; std::vector<float*> A; std::vector<HotView> hv;
     hh_views(plan, packs, &W, &A, &hv);
-    return forward_impl(plan, kDedup | kPool, "pk_hh_forward", W.data(), hv.data(), ids, offsets, B, nnz, out,
+    return forward_impl(plan, nullptr, kDedup | kPool, "pk_hh_forward", W.data(), hv.data(), ids, offsets, B, nnz, out,
                         out_row_stride, workspace, ws_bytes,
                         hip_stream);
 }

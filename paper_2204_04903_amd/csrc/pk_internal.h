@@ -188,6 +188,7 @@ struct pk_plan {
     int32_t max_table_fields = 0;         // most fields reading one table
     int32_t dmax = 0;
     void* device_state = nullptr;         // owned by pk_device.hip (metadata upload, events)
+    uint64_t serial = 0;                  // distinguishes plans, also when one is created where another was freed
 };
 
 namespace pk {

@@ -11,6 +11,7 @@
 #include <algorithm>
 #include <cmath>
 #include <cstdlib>
+#include <atomic>
 #include <new>
 
 namespace pk {
@@ -143,6 +144,8 @@ pk_status pk_plan_create(const pk_table_desc* tables, int32_t n_tables, const pk
 
     pk_plan* pl = new (std::nothrow) pk_plan();
     if (!pl) return fail(PK_ENOMEM, "pk_plan_create: out of host memory");
+    static std::atomic<uint64_t> next_serial{1};
+    pl->serial = next_serial.fetch_add(1);
     pl->tables.assign(tables, tables + n_tables);
     pl->fields.assign(fields, fields + n_fields);
     if (opts) pl->opts = *opts;
