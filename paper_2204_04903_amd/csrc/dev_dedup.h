@@ -870,59 +870,66 @@ __device__ __forceinline__ void meta_body(const SliceArgs& a, int block, int nbl
 // ---------------------------------------------------------------------------
 // Large batches: inverse[q] = number of distinct keys of the pack below key[q]: the rank sample of
 // the key's 256-key block (written by the slice kernel) plus the set bits before the key inside
-// the block.  Tiles as in the keys kernel: bags of one field, hence one table.
+// the block.  Tiles of KT consecutive positions of the packed order (all packs in one launch); which
+// table a position belongs to follows from where its field's occurrences start, staged in LDS with
+// the table's first key and the place of its bitmap.
 // ---------------------------------------------------------------------------
-template <int BT>
+template <int KT>
 __global__ void __launch_bounds__(NT)
-pk_inverse_kernel(const int32_t* __restrict__ offsets, int B, int F, int64_t nnz, const FieldMeta* __restrict__ fmeta,
+pk_inverse_kernel(const int32_t* __restrict__ offsets, int B, int F, int P, int64_t nnz,
+                  const FieldMeta* __restrict__ fmeta, const PackMeta* __restrict__ pm,
                   const TableMeta* __restrict__ tmeta, const int32_t* __restrict__ slot_field,
                   const PackState* __restrict__ st, const uint32_t* __restrict__ keys,
                   const uint4* __restrict__ bitmap4, const int32_t* __restrict__ rank, int32_t* __restrict__ inverse)
 {
-    extern __shared__ int32_t s_dyn[];
+    extern __shared__ int32_t s_dyn[];                     // field scan | per slot: first key, bitmap place, rows, pack
     int32_t* s_fb = s_dyn;
     int32_t* s_delta = s_fb + (F + 1);
     int32_t* s_slotpos = s_delta + F;
-    const int tid = threadIdx.x;
+    uint32_t* s_klo = reinterpret_cast<uint32_t*>(s_slotpos + (F + 1));
+    uint32_t* s_wb = s_klo + F;
+    uint32_t* s_rows = s_wb + F;
+    int32_t* s_pack = reinterpret_cast<int32_t*>(s_rows + F);
     if (field_scan<NT>(offsets, B, F, nnz, slot_field, s_fb, s_delta, s_slotpos)) return;
-    const int tpf = (B + BT - 1) / BT;
-    const int64_t n_tiles = (int64_t)F * tpf;
-    for (int64_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
-        const TileOf tl(tile, tpf, B, BT);
-        const int f = tl.f;
-        const FieldMeta m = fmeta[f];
-        if (st[m.pack].error) continue;
+    for (int j = threadIdx.x; j < F; j += NT) {
+        const FieldMeta m = fmeta[slot_field[j]];
         const TableMeta tm = tmeta[m.stable];
-        const int64_t g0 = (int64_t)f * B + tl.b0;
-        const int q_lo = min(max(offsets[g0], s_fb[f]), s_fb[f + 1]) + s_delta[f];
-        const int q_hi = min(max(offsets[g0 + tl.nb], s_fb[f]), s_fb[f + 1]) + s_delta[f];
-        const uint4* bm = bitmap4 + (size_t)tm.word_base / 4;
-        const int32_t* rk = rank + (size_t)tm.word_base / kRankWords;
-        for (int q0 = q_lo + tid; q0 < q_hi; q0 += 4 * NT) {
-            uint32_t kk[4];
+        s_klo[j] = tm.key_lo; s_wb[j] = tm.word_base; s_rows[j] = tm.rows; s_pack[j] = m.pack;
+    }
+    __syncthreads();
+    const int n = s_slotpos[F];
+    const int n_tiles = (n + KT - 1) / KT;
+    for (XcdTiles it(n_tiles); it.valid(); it.next()) {
+        uint32_t key[KT / NT];
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const int q = q0 + j * NT;
-                kk[j] = q < q_hi ? keys[q] - tm.key_lo : 0;
+        for (int k = 0; k < KT / NT; ++k) {
+            const int q = it.tile * KT + k * NT + (int)threadIdx.x;
+            key[k] = q < n ? keys[q] : 0;
+        }
+        int j = -1;
+#pragma unroll
+        for (int k = 0; k < KT / NT; ++k) {
+            const int q = it.tile * KT + k * NT + (int)threadIdx.x;
+            if (q >= n) continue;
+            if (j < 0 || q >= s_slotpos[j + 1]) j = upper_bound_i32(s_slotpos, F + 1, q) - 1;   // the slot of this position
+            if (st[s_pack[j]].error) continue;
+            const uint32_t kk = key[k] - s_klo[j];
+            if (kk >= s_rows[j]) continue;                 // no key of this table (only after rejected offsets)
+            const uint4* bm = bitmap4 + (size_t)s_wb[j] / 4;
+            const int32_t* rk = rank + (size_t)s_wb[j] / kRankWords;
+            const uint32_t blk = kk >> 8;
+            const int wi = (kk >> 5) & 7;
+            const uint4 x = bm[2 * (size_t)blk], y = bm[2 * (size_t)blk + 1];
+            const uint32_t w[8] = {x.x, x.y, x.z, x.w, y.x, y.y, y.z, y.w};
+            int r = rk[blk];
+            uint32_t cur = 0;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                if (i < wi) r += __popc(w[i]);
+                if (i == wi) cur = w[i];
             }
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const int q = q0 + j * NT;
-                if (q >= q_hi || kk[j] >= tm.rows) continue;
-                const uint32_t blk = kk[j] >> 8;
-                const int wi = (kk[j] >> 5) & 7;
-                const uint4 x = bm[2 * (size_t)blk], y = bm[2 * (size_t)blk + 1];
-                const uint32_t w[8] = {x.x, x.y, x.z, x.w, y.x, y.y, y.z, y.w};
-                int r = rk[blk];
-                uint32_t cur = 0;
-#pragma unroll
-                for (int i = 0; i < 8; ++i) {
-                    if (i < wi) r += __popc(w[i]);
-                    if (i == wi) cur = w[i];
-                }
-                r += __popc(cur & ((1u << (kk[j] & 31)) - 1u));
-                inverse[q] = r;
-            }
+            r += __popc(cur & ((1u << (kk & 31)) - 1u));
+            inverse[q] = r;
         }
     }
 }

@@ -177,8 +177,9 @@ static pk_status forward_impl(const pk_plan* plan, DeviceState* ds_given, int st
     }
 
     // ---- large batches: partition the occurrences by slice, then one block per slice ----
-    const bool long_bags = nnz / std::max<int64_t>(n_bags, 1) >= 16;
-    const int bt = long_bags ? 32 : 256;
+    // bags per tile of the keys and scatter kernels: about 16 K occurrences, 32 to 1024 bags
+    const int64_t avg_len = std::max<int64_t>(nnz / std::max<int64_t>(n_bags, 1), 1);
+    const int bt = avg_len >= 48 ? 32 : avg_len >= 32 ? 128 : avg_len >= 12 ? 512 : 1024;     // (a mix of short and very long bags counts as long)
     const int64_t n_tiles = (int64_t)F * ((B + bt - 1) / bt);
     const size_t scan_words = field_scan_words(F) + (size_t)T + 1;
     if (do_dedup && !L.small && (scan_words + 2 * (size_t)L.max_table_slices) * 4 > 64 * 1024)
@@ -196,14 +197,16 @@ static pk_status forward_impl(const pk_plan* plan, DeviceState* ds_given, int st
                   ws.at<uint4>(L.clear_begin), n_clear4);
         const dim3 key_grid(blocks_for(n_tiles, 1, 256 * 8));
         const size_t keys_lds = (scan_words + (size_t)L.max_table_slices) * 4;
-        if (long_bags)
-            PK_LAUNCH("pk_keys", pk_keys_kernel<32>, key_grid, dim3(NT), keys_lds, ids, offsets, B, F, P, T, nnz,
-                      sa.target, sa.log_max, ds->fmeta, ds->pmeta, ds->sort_tables, ds->slot_field, st, keys, packed_offsets,
-                      slice_total, seg);
-        else
-            PK_LAUNCH("pk_keys", pk_keys_kernel<256>, key_grid, dim3(NT), keys_lds, ids, offsets, B, F, P, T, nnz,
-                      sa.target, sa.log_max, ds->fmeta, ds->pmeta, ds->sort_tables, ds->slot_field, st, keys, packed_offsets,
-                      slice_total, seg);
+#define PK_KEYS_LAUNCH(BT)                                                                                      \
+    PK_LAUNCH("pk_keys", pk_keys_kernel<BT>, key_grid, dim3(NT), keys_lds, ids, offsets, B, F, P, T, nnz, sa.target, \
+              sa.log_max, ds->fmeta, ds->pmeta, ds->sort_tables, ds->slot_field, st, keys, packed_offsets, slice_total, seg)
+        switch (bt) {
+            case 32: PK_KEYS_LAUNCH(32); break;
+            case 128: PK_KEYS_LAUNCH(128); break;
+            case 512: PK_KEYS_LAUNCH(512); break;
+            default: PK_KEYS_LAUNCH(1024); break;
+        }
+#undef PK_KEYS_LAUNCH
     }
 
     // Pooling needs the keys only.  Large batches: it runs on side streams beside the rest of
@@ -234,18 +237,19 @@ static pk_status forward_impl(const pk_plan* plan, DeviceState* ds_given, int st
                   dim3(kScanThreads), (size_t)(T + 1) * 4,
                   ds->sort_tables, T, F, nnz, sa.target, sa.log_max, slice_total, slice_cursor, ws.at<SliceInfo>(L.slice_info),
                   L.n_slices, L.log_max == kSliceLogFine ? kBigSliceCount : 0x7FFFFFFF, big_list + kBigSlicesMax, big_list);
-        // the scatter takes larger tiles than the keys kernel (longer runs of records per slice), the
-        // inverse kernel smaller ones (it needs no bag, and many blocks hide its dependent lookups)
-        auto tiles_of = [&](int b) { return (int64_t)F * ((B + b - 1) / b); };
         const size_t sc_lds = (scan_words + 2 * (size_t)L.max_table_slices) * 4;
-        if (long_bags)
-            PK_LAUNCH("pk_scatter", pk_scatter_kernel<32>, dim3(blocks_for(tiles_of(32), 1, 256 * 8)), dim3(NT), sc_lds,
-                      offsets, B, F, T, nnz, sa.target, sa.log_max, ds->fmeta, ds->pmeta, ds->sort_tables, ds->slot_field,
-                      st, keys, slice_cursor, ws.at<uint2>(L.rec), L.max_table_slices, plan->out_dim);
-        else
-            PK_LAUNCH("pk_scatter", pk_scatter_kernel<1024>, dim3(blocks_for(tiles_of(1024), 1, 256 * 8)), dim3(NT), sc_lds,
-                      offsets, B, F, T, nnz, sa.target, sa.log_max, ds->fmeta, ds->pmeta, ds->sort_tables, ds->slot_field,
-                      st, keys, slice_cursor, ws.at<uint2>(L.rec), L.max_table_slices, plan->out_dim);
+        const dim3 tile_grid(blocks_for(n_tiles, 1, 256 * 8));
+#define PK_SCATTER_LAUNCH(BT)                                                                                   \
+    PK_LAUNCH("pk_scatter", pk_scatter_kernel<BT>, tile_grid, dim3(NT), sc_lds, offsets, B, F, T, nnz, sa.target,   \
+              sa.log_max, ds->fmeta, ds->pmeta, ds->sort_tables, ds->slot_field, st, keys, slice_cursor,            \
+              ws.at<uint2>(L.rec), L.max_table_slices, plan->out_dim)
+        switch (bt) {
+            case 32: PK_SCATTER_LAUNCH(32); break;
+            case 128: PK_SCATTER_LAUNCH(128); break;
+            case 512: PK_SCATTER_LAUNCH(512); break;
+            default: PK_SCATTER_LAUNCH(1024); break;
+        }
+#undef PK_SCATTER_LAUNCH
         const size_t tf_lds = (size_t)std::max(1, plan->max_table_fields) * kSliceTfWords * 4;
         if (L.n_slices > 0) {
             SliceArgs sm = sa, sp = sa;
@@ -281,15 +285,11 @@ static pk_status forward_impl(const pk_plan* plan, DeviceState* ds_given, int st
             }
             if (beside) { rc = join_streams(ds, main_stream, 1, DeviceState::kSide - 1); if (rc != PK_OK) return rc; }
         }
-        const size_t inv_lds = field_scan_words(F) * 4;
-        if (long_bags)
-            PK_LAUNCH("pk_inverse", pk_inverse_kernel<8>, dim3(blocks_for(tiles_of(8), 1, 256 * 64)), dim3(NT), inv_lds,
-                      offsets, B, F, nnz, ds->fmeta, ds->sort_tables, ds->slot_field, st, keys,
-                      reinterpret_cast<const uint4*>(sa.bitmap), sa.rank, inverse);
-        else
-            PK_LAUNCH("pk_inverse", pk_inverse_kernel<64>, dim3(blocks_for(tiles_of(64), 1, 256 * 64)), dim3(NT), inv_lds,
-                      offsets, B, F, nnz, ds->fmeta, ds->sort_tables, ds->slot_field, st, keys,
-                      reinterpret_cast<const uint4*>(sa.bitmap), sa.rank, inverse);
+        const size_t inv_lds = (field_scan_words(F) + 4 * (size_t)F) * 4;
+        const unsigned xq = (blocks_for(nnz, 1024, 256 * 16) + 7u) & ~7u;
+        PK_LAUNCH("pk_inverse", pk_inverse_kernel<1024>, dim3(xq), dim3(NT), inv_lds, offsets, B, F, P, nnz, ds->fmeta,
+                  ds->pmeta, ds->sort_tables, ds->slot_field, st, keys, reinterpret_cast<const uint4*>(sa.bitmap), sa.rank,
+                  inverse);
     }
     if (n_side) { rc = join_streams(ds, stream, n_side); if (rc != PK_OK) return rc; }
     return PK_OK;
