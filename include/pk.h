@@ -80,9 +80,10 @@ typedef struct pk_plan pk_plan;   /* opaque, host memory, owned by the library *
  * volume of a pack is the number of floats it gathers, sum over its tables of
  * dim x occurrences (occurrences of a table = sum of field_volume over the
  * fields that read it; every field counts 1 when field_volume is NULL); a pack
- * gets round(volume / smallest non-zero volume) shards, at most max_shards and
- * at most one per table, and its tables are dealt to the shards in turn (the
- * paper's example: one operation for dim 8, four shards for dim 32).  Shards
+ * whose volume is above the average over the packs gets round(volume / smallest
+ * non-zero volume) shards, at most max_shards and at most one per table, and
+ * its tables are dealt to the shards in turn (the paper's example: one
+ * operation for dim 8, four shards for dim 32).  Shards
  * are packs of their own, ordered (dim, dtype, shard).
  * Inside a pack the tables are stacked in table-index order into ONE caller
  * buffer [total_rows, dim]; pk_plan_table_slot tells where each table starts.
@@ -215,8 +216,9 @@ int32_t pk_micro_batch_size(const pk_plan* plan, int32_t B, int64_t nnz,
  *   itr >= warmup_iters: a row found in the Hot-storage is read and updated there,
  *     the others in the Cold-storage; FCounter counts; when itr is a multiple of
  *     flush_iters the Hot-storage is refreshed to hold the top-k rows of
- *     FCounter (larger count first, equal counts by smaller row; rows never
- *     queried do not enter; k = hot_rows): rows that leave are written back to
+ *     FCounter (larger count first, equal counts by smaller row; counts are
+ *     compared up to 65535: rows queried in that many iterations or more are
+ *     equally hot; rows never queried do not enter; k = hot_rows): rows that leave are written back to
  *     the Cold-storage, rows that enter are loaded, rows that stay keep their slot.
  * The Hot-storage never changes a value the layer computes.  All buffers belong
  * to the caller; pk_hh_init must run once before the first iteration. */

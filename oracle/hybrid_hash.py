@@ -16,6 +16,9 @@ Readings where the paper is silent:
     batch, Sec. IV-C): FCounter counts iterations in which a row was queried.
   - top-k: by count, larger first; equal counts by row, smaller first; rows never
     queried do not enter, so fewer than k rows may be hot.
+  - the selection compares counts up to COUNT_CAP = 65535: rows queried in that many
+    iterations or more count as equally hot (and are told apart by row).  FCounter
+    itself keeps counting.
   - the Hot-storage is where a hot row is read AND updated, so before a reload the
     rows it holds are written back to the Cold-storage.
 The cache is transparent: it never changes a value the layer computes.
@@ -23,6 +26,9 @@ The cache is transparent: it never changes a value the layer computes.
 from __future__ import annotations
 
 import numpy as np
+
+
+COUNT_CAP = 65535
 
 
 class HybridHashOracle:
@@ -35,7 +41,7 @@ class HybridHashOracle:
     def top_k(self) -> np.ndarray:
         """Rows of the k largest positive counts; ties go to the smaller row.  Ascending rows."""
         rows = np.nonzero(self.fcounter)[0]
-        order = sorted(rows.tolist(), key=lambda r: (-int(self.fcounter[r]), r))
+        order = sorted(rows.tolist(), key=lambda r: (-min(int(self.fcounter[r]), COUNT_CAP), r))
         return np.array(sorted(order[:self.k]), np.int64)
 
     def iteration(self, ids, itr: int):

@@ -119,11 +119,13 @@ double orc_calc_vparam(int32_t n_tables, const int32_t *table_pack, const int32_
 
 /* ---- Eq. 1 shard split (Sec. III-B) ----------------------------------------
  * A packed operation whose volume is high is split evenly into shards.  The
- * paper's example fixes the rule used here: with one operation for the dim-8
- * tables and uniform data, the dim-32 tables get four shards, i.e. the number
- * of shards of a pack is its volume relative to the lightest pack's,
- *   shards(p) = round(V_p / min_q V_q), at least 1, at most max_shards and at
- *   most the pack's table count;
+ * paper's text and example fix the rule used here: a pack is split only when its
+ * volume is ABOVE THE AVERAGE over the packs (zero-volume packs aside), and
+ * with one operation for the dim-8 tables and uniform data the dim-32 tables
+ * get four shards, i.e. a pack that is split gets its volume relative to the
+ * lightest pack's,
+ *   shards(p) = round(V_p / min_q V_q) if V_p > mean_q V_q, else 1; at most
+ *   max_shards and at most the pack's table count;
  * the pack's tables (in table order) are dealt to its shards in turn, so each
  * shard holds an equal share of them.  Shards become packs of their own,
  * ordered by (dim, dtype, shard); tables are stacked per shard in table order.
@@ -137,18 +139,21 @@ int32_t orc_shard_split(int32_t n_tables, const int64_t *rows, const int32_t *di
                         int32_t *table_pack, int64_t *table_base,
                         int32_t *pack_dim, int32_t *pack_dtype, int64_t *pack_rows)
 {
-    double vmin = 0.0;
+    double vmin = 0.0, vsum = 0.0;
+    int32_t n_vol = 0;
     for (int32_t p = 0; p < n_base; ++p) {
         double v = orc_calc_vparam(n_tables, base_pack, dim, occurrences, p);
         if (v > 0.0 && (vmin == 0.0 || v < vmin)) vmin = v;
+        if (v > 0.0) { vsum += v; ++n_vol; }
     }
+    const double vmean = n_vol > 0 ? vsum / n_vol : 0.0;
     int32_t n_packs = 0;
     for (int32_t p = 0; p < n_base; ++p) {
         double v = orc_calc_vparam(n_tables, base_pack, dim, occurrences, p);
         int32_t n_tab = 0;
         for (int32_t t = 0; t < n_tables; ++t) if (base_pack[t] == p) ++n_tab;
         int32_t s = 1;
-        if (vmin > 0.0 && v > 0.0) s = (int32_t)floor(v / vmin + 0.5);
+        if (vmin > 0.0 && v > vmean) s = (int32_t)floor(v / vmin + 0.5);      /* only packs above the average are split */
         if (s > max_shards) s = max_shards;
         if (s > n_tab) s = n_tab;
         if (s < 1) s = 1;

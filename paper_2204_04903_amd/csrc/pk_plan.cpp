@@ -162,20 +162,24 @@ pk_status pk_plan_create(const pk_table_desc* tables, int32_t n_tables, const pk
         group[it - keys.begin()].push_back(t);
     }
     // Eq. 1 (Sec. III-B): volume of a packed operation = floats it gathers = sum over its
-    // tables of dim x occurrences.  A pack is split into round(volume / smallest volume)
-    // shards (the paper's example: dim 8 -> one operation, dim 32 -> four), at most
-    // max_shards and at most one per table; its tables are dealt to the shards in turn.
+    // tables of dim x occurrences.  A pack whose volume is above the average is split into
+    // round(volume / smallest volume) shards (the paper's example: dim 8 -> one operation,
+    // dim 32 -> four), at most max_shards and at most one per table; its tables are dealt to
+    // the shards in turn.
     std::vector<int32_t> n_shards(keys.size(), 1);
     if (opts && opts->max_shards > 1) {
         std::vector<double> occ(n_tables, 0.0), vol(keys.size(), 0.0);
         for (int32_t f = 0; f < n_fields; ++f) occ[fields[f].table] += opts->field_volume ? opts->field_volume[f] : 1.0;
-        double vmin = 0.0;
+        double vmin = 0.0, vsum = 0.0;
+        int n_vol = 0;
         for (size_t g = 0; g < keys.size(); ++g) {
             for (int32_t t : group[g]) vol[g] += (double)tables[t].dim * occ[t];
             if (vol[g] > 0.0 && (vmin == 0.0 || vol[g] < vmin)) vmin = vol[g];
+            if (vol[g] > 0.0) { vsum += vol[g]; ++n_vol; }
         }
+        const double vmean = n_vol > 0 ? vsum / n_vol : 0.0;
         for (size_t g = 0; g < keys.size(); ++g) {
-            int64_t s = (vmin > 0.0 && vol[g] > 0.0) ? (int64_t)std::floor(vol[g] / vmin + 0.5) : 1;
+            int64_t s = (vmin > 0.0 && vol[g] > vmean) ? (int64_t)std::floor(vol[g] / vmin + 0.5) : 1;
             s = std::min<int64_t>(s, opts->max_shards);
             s = std::min<int64_t>(s, (int64_t)group[g].size());
             n_shards[g] = (int32_t)std::max<int64_t>(s, 1);

@@ -84,3 +84,39 @@ def test_hybrid_hash_follows_alg1_and_is_transparent(cold_on_host, dtype):
         assert sum(o.fcounter.sum() for o in oracles) > 0 and any(len(o.hot) for o in oracles)
     finally:
         layer.close()
+
+
+def test_selection_at_the_count_cap_follows_the_oracle():
+    # rows queried in 65535 iterations or more are equally hot: FCounter is set by hand (nobody runs that many
+    # iterations in a test) and the reloads that follow must pick the rows the oracle picks
+    from paper_2204_04903_amd.layer import HybridEmbedding
+    tables, fields = [(64, 8, 0)], [(0, 0)]
+    steps = [small_problem(700 + s, B=6, tables=tables, fields=fields, max_len=2) for s in range(3)]
+    pl = orc.plan(tables, fields)
+    layer = HybridEmbedding(tables, fields, [5], 0, 1, cold_on_host=False)
+    try:
+        layer.load_table(0, steps[0]["Wt"][0])
+        oracle = HybridHashOracle(64, 5, 0, 1)
+        preset = {3: 70000, 10: 65535, 11: 65534, 20: 900000, 30: 65535, 40: 65533, 41: 65536, 50: 12}
+        fc = torch.zeros(64, dtype=torch.int32)
+        for r, v in preset.items():
+            fc[r] = v
+            oracle.fcounter[r] = v
+        torch.cuda.synchronize()
+        layer.hh[0]["fcounter"].copy_(fc.cuda())
+        W = stack_tables(pl, [steps[0]["Wt"][0].copy()])
+        for itr, pr in enumerate(steps):
+            out = layer.forward(torch.from_numpy(pr["ids"]).cuda(), torch.from_numpy(pr["offsets"]).cuda(), pr["B"])
+            layer.backward_update(torch.from_numpy(pr["grad"]).cuda(), 0.05, 1e-8)
+            queried, hits, flushed = layer.end_iteration()
+            torch.cuda.synchronize()
+            _, ctx = orc.forward(pl, W, pr["B"], pr["ids"], pr["offsets"])
+            hit, fl = oracle.iteration(ctx[0].unique.astype(np.int64), itr)
+            assert flushed == fl and hits[0] == int(hit.sum())
+            n_hot = layer.hot_count(0)
+            got_hot = layer.hh[0]["hot_row"].cpu().numpy()[:n_hot].astype(np.int64)
+            assert np.array_equal(np.sort(got_hot), oracle.hot), f"iteration {itr}: {np.sort(got_hot)} vs {oracle.hot}"
+            assert np.array_equal(layer.hh[0]["fcounter"].cpu().numpy().astype(np.int64), oracle.fcounter)
+        assert set(oracle.hot.tolist()) <= {3, 10, 20, 30, 41}          # the five rows at the cap
+    finally:
+        layer.close()

@@ -104,7 +104,7 @@ def test_small_mixed_packs_shared_tables_two_steps(seed):
 
 
 def test_eq1_shard_split_packs_two_steps():
-    # heavy packs split into shards (Sec. III-B, Eq. 1): 1 + 4 + 2 packs instead of 3
+    # the pack above the average volume split into shards (Sec. III-B, Eq. 1): 1 + 1 + 4 packs instead of 3
     rng = np.random.default_rng(77)
     dims = [8] * 4 + [32] * 8 + [16] * 4
     tables = [(int(rng.integers(20, 200)), d, 0) for d in dims]

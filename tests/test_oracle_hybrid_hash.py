@@ -58,3 +58,15 @@ def test_hit_ratio_grows_with_hot_storage_on_skewed_queries():
     assert ratios == sorted(ratios) and ratios[0] > 0.05 and ratios[-1] < 1.0
     gains = np.diff(ratios)
     assert gains[-1] < gains[0] * 4 and ratios[-1] - ratios[0] > 0.2
+
+
+def test_selection_compares_counts_up_to_the_cap():
+    # counts of 65535 and more are equally hot in the selection; the smaller row wins among them
+    o = HybridHashOracle(n_rows=10, k=3, warmup_iters=0, flush_iters=1)
+    o.fcounter[:] = [5, 70000, 65535, 65534, 0, 900000, 65535, 1, 2, 3]
+    assert list(o.top_k()) == [1, 2, 5]            # rows 1, 2, 5, 6 sit at the cap: rows 1, 2, 5 are the smallest
+    o.k = 5
+    assert list(o.top_k()) == [1, 2, 3, 5, 6]      # then the cap's last row, then 65534
+    o.fcounter[1] = 65534                          # below the cap the true count decides again
+    o.k = 3
+    assert list(o.top_k()) == [2, 5, 6]

@@ -88,6 +88,21 @@ def test_eq1_shard_split_reproduces_the_worked_example():
     assert list(pl.table_pack[:n]) == [0] * n
 
 
+def test_eq1_only_packs_above_the_average_are_split():
+    # Sec. III-B: a packed operation is split when its volume is above the average.  Three packs with
+    # volumes V, 1.6 V and 4 V (average 2.2 V): only the last one is split, into 4; a rule that split
+    # every pack by its ratio to the lightest would cut the middle one in two as well.
+    n = 8
+    tables = [(100, 10, 0)] * n + [(100, 16, 0)] * n + [(100, 40, 0)] * n
+    fields = [(t, 0) for t in range(3 * n)]
+    pl = orc.plan(tables, fields, max_shards=8)
+    occ = [1.0] * (3 * n)
+    v = [orc.calc_vparam(pl0 := orc.plan(tables, fields), occ, p) for p in range(3)]
+    assert v[1] / v[0] == 1.6 and v[2] / v[0] == 4.0
+    assert list(pl.shards) == [1, 1, 4]
+    assert pl.n_packs == 6
+
+
 def test_eq1_shard_split_rule_against_plain_python():
     # the same rule written out in Python on an irregular problem: volumes from per-field
     # statistics, rounding, both caps, tables dealt in turn, stacking per shard
@@ -104,11 +119,12 @@ def test_eq1_shard_split_rule_against_plain_python():
         base = sorted(set(dims))
         V = {d: sum(d * occ[t] for t in range(len(tables)) if dims[t] == d) for d in base}
         vmin = min(V.values())
+        vmean = sum(V.values()) / len(V)
         exp_pack, exp_base, exp_rows, q0 = {}, {}, [], 0
         exp_shards = []
         for d in base:
             ts = [t for t in range(len(tables)) if dims[t] == d]
-            s = max(1, min(int(np.floor(V[d] / vmin + 0.5)), max_shards, len(ts)))
+            s = max(1, min(int(np.floor(V[d] / vmin + 0.5)) if V[d] > vmean else 1, max_shards, len(ts)))
             exp_shards.append(s)
             rows_acc = [0] * s
             for i, t in enumerate(ts):
