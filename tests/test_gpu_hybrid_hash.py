@@ -117,6 +117,6 @@ def test_selection_at_the_count_cap_follows_the_oracle():
             got_hot = layer.hh[0]["hot_row"].cpu().numpy()[:n_hot].astype(np.int64)
             assert np.array_equal(np.sort(got_hot), oracle.hot), f"iteration {itr}: {np.sort(got_hot)} vs {oracle.hot}"
             assert np.array_equal(layer.hh[0]["fcounter"].cpu().numpy().astype(np.int64), oracle.fcounter)
-        assert set(oracle.hot.tolist()) <= {3, 10, 20, 30, 41}          # the five rows at the cap
+        assert len(oracle.hot) == 5 and all(oracle.fcounter[r] >= 65535 for r in oracle.hot)      # rows at the cap fill it
     finally:
         layer.close()
