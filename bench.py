@@ -101,6 +101,9 @@ def parse_args():
                          "pipelined the same way; 0 = off: one pk_forward and one pk_backward_update per batch)")
     ap.add_argument("--micro-serial", action="store_true",
                     help="with --micro-batches: no second stream, every micro-batch starts when the one before is done")
+    ap.add_argument("--partition", type=int, default=0,
+                    help="also time Partition (Sec. II-D) of every pack's distinct keys over this many owners, after "
+                         "the timed steps, and report the sizes of the owners' groups and what Shuffle would carry")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (a known size for scaling rocprofv3's byte counters)")
@@ -299,6 +302,45 @@ def run_workload(args, workload):
     if layer.error_word() != 0:
         raise RuntimeError(f"{workload}: the device error word is {layer.error_word()} after the timed steps")
 
+    # ---- Partition of the last step's distinct keys (outside the timed steps) ----------------------
+    partition_info = None
+    if args.partition > 0 and not hybrid:
+        n_own = args.partition
+        reps = 20
+        step(0)
+        for p in range(layer.n_packs):
+            layer.partition(p, n_own)                                   # warm-up
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        nnz0 = batches[0].nnz
+        need = pk.pk_partition_scratch_bytes(layer.plan, nnz0, n_own)
+        scratch = torch.empty(need, dtype=torch.uint8, device="cuda")
+        pkeys = torch.empty(nnz0, dtype=torch.int32, device="cuda")
+        pidx = torch.empty(nnz0, dtype=torch.int32, device="cuda")
+        poffs = [torch.empty(n_own + 1, dtype=torch.int32, device="cuda") for _ in range(layer.n_packs)]
+        e0.record()
+        for _ in range(reps):
+            for p in range(layer.n_packs):
+                pk.pk_partition_unique(layer.plan, layer.ws, layer.ws_bytes, wl.batch, nnz0, p, n_own, pkeys, pidx,
+                                       poffs[p], scratch, need, stream)
+        e1.record()
+        torch.cuda.synchronize()
+        packs = []
+        for p in range(layer.n_packs):
+            o = poffs[p].cpu().numpy().astype(np.int64)
+            cnt = np.diff(o)
+            info = layer.packs[p]
+            row_b = info["dim"] * (4 if info["dtype"] == 0 else 2)
+            away = int(cnt.sum() - cnt[0])                             # this worker is owner 0: the rest travels
+            packs.append({"distinct_keys": int(o[-1]), "per_owner": cnt.tolist(),
+                          "keys_sent_bytes": 4 * away, "rows_received_bytes": row_b * away,
+                          "gradient_rows_sent_bytes": 4 * info["dim"] * away})
+        tot = sum(q["keys_sent_bytes"] + q["rows_received_bytes"] + q["gradient_rows_sent_bytes"] for q in packs)
+        partition_info = {"owners": n_own, "rule": "row mod owners", "ms_per_step": e0.elapsed_time(e1) / reps,
+                          "alg_bytes_per_step": sum(12 * q["distinct_keys"] for q in packs),
+                          "packs": packs, "shuffle_bytes_per_step": tot,
+                          "shuffle_bytes_per_link": tot / max(1, n_own - 1)}
+
     # ---- the CPU oracle on the host cores, bounded samples --------------------------------------
     cpu = None
     if not args.no_cpu_baseline:
@@ -326,6 +368,7 @@ def run_workload(args, workload):
         "cpu_baseline": cpu,
         "hybrid_hash": hybrid_info,
         "d_interleaving": micro_info,
+        "partition": partition_info,
         "kernels": {k: {kk: round(vv, 6) for kk, vv in v.items()} for k, v in kern.items()},
         "input_generation_s": round(gen_s, 2),
     }

@@ -259,6 +259,24 @@ pk_status pk_hh_end_iteration(pk_plan* plan, const pk_hh_pack* packs, int64_t it
 /* Rows currently in pack p's Hot-storage (host-side count). */
 pk_status pk_hh_hot_count(const pk_plan* plan, int32_t p, int64_t* n_hot);
 
+/* ---- Partition (Sec. II-D operator list; Sec. III-B: fused with Unique), one GPU's share ---------
+ * On several workers the rows of a packed table are dealt to the workers, the distinct keys of a batch are
+ * split by the worker that holds their rows, and only the keys and rows of other workers travel (Shuffle).
+ * This call is the split as one GPU sees it, for pack p of the preceding pk_forward (same plan, B, nnz,
+ * workspace): row r belongs to worker r mod n_owners (the paper does not say how rows are dealt), and
+ *   part_keys    device, uint32 [>= distinct keys of the pack; nnz always does]: the pack's distinct keys
+ *                regrouped by owner, owner 0 first, ascending inside an owner
+ *   part_index   device, int32, same length: where each of them stands in the pack's `unique` list
+ *                (where Stitch puts the row that comes back for it)
+ *   part_offsets device, int32 [n_owners + 1]: start of every owner's group; the last entry is the number
+ *                of distinct keys
+ * scratch: device, >= pk_partition_scratch_bytes(plan, nnz, n_owners).  1 <= n_owners <= 64.
+ * Enqueues on hip_stream. */
+size_t    pk_partition_scratch_bytes(const pk_plan* plan, int64_t nnz, int32_t n_owners);
+pk_status pk_partition_unique(const pk_plan* plan, const void* workspace, size_t ws_bytes, int32_t B, int64_t nnz,
+                              int32_t p, int32_t n_owners, uint32_t* part_keys, int32_t* part_index,
+                              int32_t* part_offsets, void* scratch, size_t scratch_bytes, void* hip_stream);
+
 /* ---- parity access to the context saved in the workspace ---------------------
  * SYNCHRONISES the device (copies a few bytes of the header back).  Returns
  * device pointers into the workspace, valid until the next pk_forward:

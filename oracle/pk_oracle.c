@@ -419,3 +419,21 @@ void orc_direct_table_adagrad(void *Wt, float *At, int32_t dtype, int64_t rows, 
         }
     }
 }
+
+/* Sec. II-D (operator list) and Sec. III-B (the fused Unique&Partition kernel): Partition splits the
+ * distinct IDs by the worker that stores their rows.  Reading (the paper does not say how rows are dealt
+ * to workers): row r of a packed table lives on worker r mod n_owners.  The distinct keys of a pack
+ * (ascending) are regrouped by owner, owner 0 first, ascending inside an owner; offsets[o] = number of
+ * keys of the owners before o (n_owners + 1 entries), index[i] = where part_keys[i] stands in `unique`
+ * (what Stitch needs to put the rows that come back in their places). */
+void orc_partition(int32_t U, const uint64_t *unique, int32_t n_owners, uint64_t *part_keys, int32_t *index,
+                   int32_t *offsets)
+{
+    int32_t at = 0;
+    for (int32_t o = 0; o < n_owners; ++o) {
+        offsets[o] = at;
+        for (int32_t u = 0; u < U; ++u)
+            if ((int32_t)(unique[u] % (uint64_t)n_owners) == o) { part_keys[at] = unique[u]; index[at] = u; ++at; }
+    }
+    offsets[n_owners] = at;
+}

@@ -47,6 +47,7 @@ def lib():
         _lib.orc_bf16_round.argtypes = [ctypes.c_float]
         _lib.orc_bf16_widen.restype = ctypes.c_float
         _lib.orc_bf16_widen.argtypes = [ctypes.c_uint16]
+        _lib.orc_partition.restype = None
         for name in ("orc_segments", "orc_gather", "orc_pool", "orc_scatter_add", "orc_adagrad_rows",
                      "orc_direct_field_forward", "orc_direct_field_grad", "orc_direct_table_adagrad"):
             getattr(_lib, name).restype = None
@@ -165,6 +166,16 @@ def segments(inverse: np.ndarray, U: int):
     so = np.zeros(U + 1, np.int32); sp = np.zeros(inverse.shape[0], np.int32)
     lib().orc_segments(i64(inverse.shape[0]), _p(inverse), i32(U), _p(so), _p(sp))
     return so, sp
+
+
+def partition(uq: np.ndarray, n_owners: int):
+    """Sec. II-D Partition of the distinct keys of a pack: (keys grouped by owner, their indices in `uq`,
+    offsets of the owners' groups)."""
+    uq = _c(uq, np.uint64)
+    U = uq.shape[0]
+    keys = np.zeros(U, np.uint64); idx = np.zeros(U, np.int32); off = np.zeros(n_owners + 1, np.int32)
+    lib().orc_partition(i32(U), _p(uq), i32(n_owners), _p(keys), _p(idx), _p(off))
+    return keys, idx, off
 
 
 def gather(W: np.ndarray, dtype: int, uq: np.ndarray) -> np.ndarray:

@@ -26,6 +26,7 @@ EXPORTS = [
     "pk_backward_update", "pk_ctx_pack", "pk_ctx_error", "pk_profile_enable", "pk_profile_read", "pk_last_error",
     "pk_hh_scratch_bytes", "pk_hh_init", "pk_hh_forward", "pk_hh_backward_update", "pk_hh_end_iteration",
     "pk_hh_hot_count", "pk_forward_dedup", "pk_forward_pool", "pk_micro_batch_size", "pk_forward_static",
+    "pk_partition_scratch_bytes", "pk_partition_unique",
 ]
 
 
@@ -103,6 +104,10 @@ def lib():
         L.pk_forward.argtypes = [vp, ctypes.POINTER(vp), vp, vp, i32, i64, vp, i64, vp, ctypes.c_size_t, vp]
         L.pk_forward_static.restype = ctypes.c_int
         L.pk_forward_static.argtypes = [vp, ctypes.POINTER(vp), vp, vp, i32, i64, vp, i64, vp]
+        L.pk_partition_scratch_bytes.restype = ctypes.c_size_t
+        L.pk_partition_scratch_bytes.argtypes = [vp, i64, i32]
+        L.pk_partition_unique.restype = ctypes.c_int
+        L.pk_partition_unique.argtypes = [vp, vp, ctypes.c_size_t, i32, i64, i32, i32, vp, vp, vp, vp, ctypes.c_size_t, vp]
         L.pk_forward_dedup.restype = ctypes.c_int
         L.pk_forward_dedup.argtypes = [vp, vp, vp, i32, i64, vp, ctypes.c_size_t, vp]
         L.pk_forward_pool.restype = ctypes.c_int
@@ -238,6 +243,19 @@ def pk_forward_static(plan: int, W: Sequence, ids, offsets, B: int, nnz: int, ou
                       stream: int = 0) -> None:
     _check(lib().pk_forward_static(plan, _ptr_array(W), _ptr(ids), _ptr(offsets), B, nnz, _ptr(out), out_row_stride,
                                    stream))
+
+
+def pk_partition_scratch_bytes(plan: int, nnz: int, n_owners: int) -> int:
+    n = int(lib().pk_partition_scratch_bytes(plan, nnz, n_owners))
+    if n == 0:
+        raise PkError(PK_EINVAL, lib().pk_last_error().decode())
+    return n
+
+
+def pk_partition_unique(plan: int, workspace, ws_bytes: int, B: int, nnz: int, p: int, n_owners: int, part_keys,
+                        part_index, part_offsets, scratch, scratch_bytes: int, stream: int = 0) -> None:
+    _check(lib().pk_partition_unique(plan, _ptr(workspace), ws_bytes, B, nnz, p, n_owners, _ptr(part_keys),
+                                     _ptr(part_index), _ptr(part_offsets), _ptr(scratch), scratch_bytes, stream))
 
 
 def pk_forward_dedup(plan: int, ids, offsets, B: int, nnz: int, workspace, ws_bytes: int, stream: int = 0) -> None:

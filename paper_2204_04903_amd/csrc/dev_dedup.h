@@ -933,3 +933,91 @@ pk_inverse_kernel(const int32_t* __restrict__ offsets, int B, int F, int P, int6
         }
     }
 }
+
+// ---------------------------------------------------------------------------
+// Partition (Sec. II-D operator list; Sec. III-B fuses it with Unique): one GPU's share of it.  With the
+// rows of a packed table dealt to n workers by row mod n, the distinct keys of a pack are regrouped by
+// owner -- owner 0 first, ascending inside an owner -- with the place of every key in `unique` beside it
+// (what Stitch needs for the rows that come back) and the offsets of the owners' groups.  A counting
+// sort in three small launches: counts per chunk of 2048 keys and owner, a scan in owner-major order,
+// and the placing pass (a wavefront per chunk, so that the order inside an owner is the key order).
+// ---------------------------------------------------------------------------
+constexpr int kPartChunk = 2048;
+constexpr int kPartOwnersMax = 64;
+
+__global__ void __launch_bounds__(NT)
+pk_partition_count_kernel(const PackState* __restrict__ st, int p, const uint32_t* __restrict__ unique_all,
+                          int n_owners, int32_t* __restrict__ chunk_counts)
+{
+    __shared__ int s_cnt[kPartOwnersMax];
+    const int U = st[p].n_unique;
+    const uint32_t* uq = unique_all + st[p].start;
+    const int n_chunks = (U + kPartChunk - 1) / kPartChunk;
+    for (int ch = blockIdx.x; ch < n_chunks; ch += gridDim.x) {
+        __syncthreads();
+        if (threadIdx.x < kPartOwnersMax) s_cnt[threadIdx.x] = 0;
+        __syncthreads();
+        for (int i = ch * kPartChunk + threadIdx.x; i < min((ch + 1) * kPartChunk, U); i += NT)
+            atomicAdd(&s_cnt[uq[i] % (uint32_t)n_owners], 1);
+        __syncthreads();
+        if ((int)threadIdx.x < n_owners) chunk_counts[(size_t)threadIdx.x * n_chunks + ch] = s_cnt[threadIdx.x];   // owner-major
+    }
+}
+
+// exclusive scan of the owner-major counts, in place; the owners' offsets on the way (one block)
+__global__ void __launch_bounds__(kScanThreads)
+pk_partition_scan_kernel(const PackState* __restrict__ st, int p, int n_owners, int32_t* chunk_counts,
+                         int32_t* __restrict__ offsets)
+{
+    const int U = st[p].n_unique;
+    const int n_chunks = (U + kPartChunk - 1) / kPartChunk;
+    const int total = n_owners * n_chunks;
+    int carry = 0;
+    for (int base = 0; base < total; base += kScanThreads) {
+        const int i = base + (int)threadIdx.x;
+        const int c = i < total ? chunk_counts[i] : 0;
+        int tot;
+        const int ex = block_excl_scan<kScanThreads>(c, &tot);
+        if (i < total) {
+            chunk_counts[i] = carry + ex;
+            if (i % n_chunks == 0) offsets[i / n_chunks] = carry + ex;
+        }
+        carry += tot;
+    }
+    if (threadIdx.x == 0) {
+        offsets[n_owners] = U;
+        if (n_chunks == 0) for (int o = 0; o < n_owners; ++o) offsets[o] = 0;
+    }
+}
+
+__global__ void __launch_bounds__(64)
+pk_partition_place_kernel(const PackState* __restrict__ st, int p, const uint32_t* __restrict__ unique_all,
+                          int n_owners, const int32_t* __restrict__ chunk_offsets, uint32_t* __restrict__ part_keys,
+                          int32_t* __restrict__ part_index)
+{
+    const int U = st[p].n_unique, lane = threadIdx.x;
+    const uint32_t* uq = unique_all + st[p].start;
+    const int n_chunks = (U + kPartChunk - 1) / kPartChunk;
+    const uint64_t below = (1ull << lane) - 1ull;
+    for (int ch = blockIdx.x; ch < n_chunks; ch += gridDim.x) {
+        int cur = lane < n_owners ? chunk_offsets[(size_t)lane * n_chunks + ch] : 0;   // lane o: owner o's next place
+        for (int base = ch * kPartChunk; base < min((ch + 1) * kPartChunk, U); base += 64) {
+            const int i = base + lane;
+            const bool on = i < U;
+            const uint32_t key = on ? uq[i] : 0u;
+            const int o = on ? (int)(key % (uint32_t)n_owners) : -1;
+            int rank = 0, add = 0;
+            for (int ov = 0; ov < n_owners; ++ov) {        // lanes are in key order: rank among the owner's lanes
+                const uint64_t m = __ballot(o == ov);
+                if (o == ov) rank = __popcll(m & below);
+                if (lane == ov) add = __popcll(m);
+            }
+            const int at = __shfl(cur, on ? o : 0, 64) + rank;
+            if (on) {
+                part_keys[at] = key;
+                part_index[at] = i;
+            }
+            cur += add;
+        }
+    }
+}

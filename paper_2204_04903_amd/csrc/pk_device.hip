@@ -649,6 +649,45 @@ pk_status pk_hh_hot_count(const pk_plan* plan, int32_t p, int64_t* n_hot)
     return PK_OK;
 }
 
+// ---- Partition: one GPU's share ------------------------------------------------------------
+size_t pk_partition_scratch_bytes(const pk_plan* plan, int64_t nnz, int32_t n_owners)
+{
+    if (!plan || nnz < 0 || n_owners < 1 || n_owners > kPartOwnersMax) {
+        set_error("pk_partition_scratch_bytes: plan is NULL, nnz negative or n_owners outside 1..64");
+        return 0;
+    }
+    return (size_t)(nnz / kPartChunk + 2) * (size_t)n_owners * 4;
+}
+
+pk_status pk_partition_unique(const pk_plan* plan, const void* workspace, size_t ws_bytes, int32_t B, int64_t nnz,
+                              int32_t p, int32_t n_owners, uint32_t* part_keys, int32_t* part_index,
+                              int32_t* part_offsets, void* scratch, size_t scratch_bytes, void* hip_stream)
+{
+    pk_status rc = check_common(plan, B, nnz, workspace, ws_bytes, "pk_partition_unique");
+    if (rc != PK_OK) return rc;
+    if (p < 0 || p >= (int32_t)plan->packs.size()) return fail(PK_EINVAL, "pk_partition_unique: pack out of range");
+    if (n_owners < 1 || n_owners > kPartOwnersMax) return fail(PK_EINVAL, "pk_partition_unique: n_owners must be 1 to 64");
+    if (!part_keys || !part_index || !part_offsets) return fail(PK_EINVAL, "pk_partition_unique: NULL argument");
+    if (!scratch || scratch_bytes < pk_partition_scratch_bytes(plan, nnz, n_owners))
+        return fail(PK_EWORKSPACE, "pk_partition_unique: scratch is NULL or smaller than pk_partition_scratch_bytes");
+    DeviceState* ds = nullptr;
+    rc = ensure_device_state(plan, &ds);
+    if (rc != PK_OK) return rc;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    const Layout L = make_layout(plan, B, nnz);
+    const char* wsb = static_cast<const char*>(workspace);
+    const PackState* st = reinterpret_cast<const PackState*>(wsb + L.state);
+    const uint32_t* unique = reinterpret_cast<const uint32_t*>(wsb + L.unique);
+    int32_t* counts = static_cast<int32_t*>(scratch);
+    const unsigned grid = blocks_for(nnz / kPartChunk + 1, 1, 4096);
+    PK_LAUNCH("pk_partition_count", pk_partition_count_kernel, dim3(grid), dim3(NT), 0, st, p, unique, n_owners, counts);
+    PK_LAUNCH("pk_partition_scan", pk_partition_scan_kernel, dim3(1), dim3(kScanThreads), 0, st, p, n_owners, counts,
+              part_offsets);
+    PK_LAUNCH("pk_partition_place", pk_partition_place_kernel, dim3(grid), dim3(64), 0, st, p, unique, n_owners, counts,
+              part_keys, part_index);
+    return PK_OK;
+}
+
 pk_status pk_ctx_pack(const pk_plan* plan, const void* workspace, int32_t B, int64_t nnz, int32_t p,
                       const uint32_t** keys, const uint32_t** unique, const int32_t** inverse,
                       const int32_t** packed_offsets, const int32_t** seg_offsets, int64_t* nnz_p, int64_t* n_unique)

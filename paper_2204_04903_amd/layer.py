@@ -100,6 +100,21 @@ class PackedEmbedding:
     def error_word(self) -> int:
         return pk.pk_ctx_error(self.plan, self.ws)
 
+    def partition(self, p: int, n_owners: int):
+        """Sec. II-D Partition of pack p's distinct keys by owner (row mod n_owners), after a forward pass.
+        Returns device tensors (part_keys [nnz] int32 bits of uint32, part_index [nnz] int32, part_offsets
+        [n_owners + 1] int32); only the first part_offsets[-1] entries of the first two are meaningful."""
+        B, nnz = self._shape
+        need = pk.pk_partition_scratch_bytes(self.plan, nnz, n_owners)
+        scratch = torch.empty(need, dtype=torch.uint8, device=self.device)
+        keys = torch.empty(max(nnz, 1), dtype=torch.int32, device=self.device)
+        index = torch.empty(max(nnz, 1), dtype=torch.int32, device=self.device)
+        offsets = torch.empty(n_owners + 1, dtype=torch.int32, device=self.device)
+        stream = torch.cuda.current_stream(self.device).cuda_stream
+        pk.pk_partition_unique(self.plan, self.ws, self.ws_bytes, B, nnz, p, n_owners, keys, index, offsets, scratch,
+                               need, stream)
+        return keys, index, offsets
+
 
 class MicroBatchPipeline:
     """D-Interleaving of the layer (Sec. III-C): micro-batches pass through it one after the other, and the

@@ -435,3 +435,19 @@ def test_bf16_tables_forward_and_update_within_band():
     np.testing.assert_allclose(got, np.concatenate(Wref, axis=0), rtol=2.0 ** -8, atol=1e-30)
     touched = np.zeros(W0.shape[0], bool); touched[ctx[0].unique.astype(np.int64)] = True
     assert (W[0][~touched] == W0[~touched]).all() and (~touched).any()
+
+
+@pytest.mark.parametrize("n_owners", [1, 2, 3, 8])
+def test_partition_matches_a_stable_numpy_sort_by_owner(n_owners):
+    # Sec. II-D Partition: distinct keys regrouped by the worker that holds the row (row mod n), order kept
+    rng = np.random.default_rng(n_owners)
+    uq = np.unique(rng.integers(0, 5000, size=700)).astype(np.uint64)
+    keys, idx, off = orc.partition(uq, n_owners)
+    order = np.argsort((uq % np.uint64(n_owners)).astype(np.int64), kind="stable")
+    assert np.array_equal(keys, uq[order])
+    assert np.array_equal(idx, order.astype(np.int32))
+    counts = np.bincount((uq % np.uint64(n_owners)).astype(np.int64), minlength=n_owners)
+    assert np.array_equal(off, np.concatenate([[0], np.cumsum(counts)]).astype(np.int32))
+    assert np.array_equal(uq[idx], keys)                     # Stitch's view: the index leads back to the key
+    e_keys, e_idx, e_off = orc.partition(np.zeros(0, np.uint64), n_owners)
+    assert len(e_keys) == 0 and list(e_off) == [0] * (n_owners + 1)
