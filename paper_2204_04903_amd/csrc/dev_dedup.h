@@ -63,25 +63,51 @@ __device__ __forceinline__ int field_scan(const int32_t* __restrict__ offsets, i
     return bad;
 }
 
-// s_first [T+1]: the first slice of every table, in table-list order (slices are numbered over all packs)
+// The cut of every table for this batch, from the field sizes the offsets give (s_fb: where every
+// field's occurrences begin).  s_first [T+1]: the first slice of every table, in table-list order
+// (slices are numbered over all packs); s_lg [T]: log2 of the keys per slice.
 template <int NTH>
-__device__ __forceinline__ void table_scan(const TableMeta* __restrict__ tmeta, int T, int F, int64_t nnz, int target,
-                                           int log_max, int32_t* s_first)
+__device__ __forceinline__ void table_cut(const TableMeta* __restrict__ tmeta, const FieldMeta* __restrict__ fmeta,
+                                          int T, int F, const int32_t* s_fb, int target, int log_max,
+                                          int32_t* s_first, int32_t* s_lg, TableCut* out)
 {
+    for (int t = threadIdx.x; t < T; t += NTH) s_lg[t] = 0;       // first the tables' occurrences
+    __syncthreads();
+    for (int f = threadIdx.x; f < F; f += NTH) atomicAdd(&s_lg[fmeta[f].stable], max(s_fb[f + 1] - s_fb[f], 0));
+    __syncthreads();
     int carry = 0;
     for (int base = 0; base < T; base += NTH) {
         const int t = base + (int)threadIdx.x;
-        int n = 0;
+        SliceGeom g{0, 0};
+        int occ = 0;
         if (t < T) {
-            const TableMeta tm = tmeta[t];
-            n = slice_geom(tm.rows, tm.field_end - tm.field_begin, F, nnz, target, log_max).n;
+            occ = s_lg[t];
+            g = slice_geom(tmeta[t].rows, occ, target, log_max);
         }
         int tot;
-        const int ex = block_excl_scan<NTH>(n, &tot);
-        if (t < T) s_first[t] = carry + ex;
+        const int ex = block_excl_scan<NTH>(g.n, &tot);
+        if (t < T) {
+            s_first[t] = carry + ex;
+            s_lg[t] = g.log_keys;
+            if (out) out[t] = TableCut{g.log_keys, g.n, carry + ex, occ};
+        }
         carry += tot;
     }
     if (threadIdx.x == 0) s_first[T] = carry;
+    __syncthreads();
+}
+
+// the same from the array the keys kernel wrote
+template <int NTH>
+__device__ __forceinline__ void table_cut_load(const TableCut* __restrict__ cut, int T, int32_t* s_first, int32_t* s_lg)
+{
+    for (int t = threadIdx.x; t < T; t += NTH) {
+        const TableCut c = cut[t];
+        s_first[t] = c.first;
+        if (s_lg) s_lg[t] = c.log_keys;
+        if (t == T - 1) s_first[T] = c.first + c.n;
+    }
+    if (T == 0 && threadIdx.x == 0) s_first[0] = 0;
     __syncthreads();
 }
 
@@ -130,19 +156,21 @@ pk_keys_kernel(const int64_t* __restrict__ ids, const int32_t* __restrict__ offs
                const PackMeta* __restrict__ pm, const TableMeta* __restrict__ tmeta,
                const int32_t* __restrict__ slot_field, PackState* st,
                uint32_t* __restrict__ keys, int32_t* __restrict__ packed_offsets, int32_t* slice_total,
-               int32_t* __restrict__ seg_all)
+               int32_t* __restrict__ seg_all, TableCut* __restrict__ cut, int n_slices_max)
 {
-    extern __shared__ int32_t s_dyn[];                     // field scan | first slices | the tile's counts
+    extern __shared__ int32_t s_dyn[];                     // field scan | first slices, slice sizes | the tile's counts
     __shared__ int32_t s_po[BT + 1];
     __shared__ int s_flag;
     int32_t* s_fb = s_dyn;
     int32_t* s_delta = s_fb + (F + 1);
     int32_t* s_slotpos = s_delta + F;
     int32_t* s_first = s_slotpos + (F + 1);
-    int32_t* s_hist = s_first + (T + 1);
+    int32_t* s_lg = s_first + (T + 1);
+    int32_t* s_hist = s_lg + T;
     const int tid = threadIdx.x;
-    const int bad = field_scan<NT>(offsets, B, F, nnz, slot_field, s_fb, s_delta, s_slotpos);
-    table_scan<NT>(tmeta, T, F, nnz, target, log_max, s_first);
+    int bad = field_scan<NT>(offsets, B, F, nnz, slot_field, s_fb, s_delta, s_slotpos);
+    table_cut<NT>(tmeta, fmeta, T, F, s_fb, target, log_max, s_first, s_lg, blockIdx.x == 0 ? cut : nullptr);
+    bad |= s_first[T] > n_slices_max;                      // cannot be for offsets that pass the scan: the slices' arrays are that long
     if (blockIdx.x == 0) {
         for (int p = tid; p < P; p += NT) {
             const PackMeta k = pm[p];
@@ -164,8 +192,9 @@ pk_keys_kernel(const int64_t* __restrict__ ids, const int32_t* __restrict__ offs
         const int f = tl.f;
         const FieldMeta m = fmeta[f];
         const PackMeta k = pm[m.pack];
-        const TableMeta tm = tmeta[m.stable];
-        const SliceGeom g = slice_geom(tm.rows, tm.field_end - tm.field_begin, F, nnz, target, log_max);
+        SliceGeom g;
+        g.log_keys = s_lg[m.stable];
+        g.n = s_first[m.stable + 1] - s_first[m.stable];
         const int64_t g0 = (int64_t)f * B + tl.b0;
         __syncthreads();                                   // the previous tile's LDS is consumed
         for (int t = tid; t <= tl.nb; t += NT) s_po[t] = offsets[g0 + t];
@@ -219,13 +248,13 @@ constexpr int kBigSliceCount = 6144;       // records from which a slice is list
 // cursors of the scatter kernel start at those places.
 constexpr int kScanThreads = 1024;
 __global__ void __launch_bounds__(kScanThreads)
-pk_slice_scan_kernel(const TableMeta* __restrict__ tmeta, int T, int F, int64_t nnz, int target, int log_max,
+pk_slice_scan_kernel(const TableCut* __restrict__ cut, int T,
                      const int32_t* __restrict__ slice_total, int32_t* __restrict__ slice_cursor,
                      SliceInfo* __restrict__ slice_info, int n_slices, int big_count, int32_t* n_big,
                      int32_t* __restrict__ big_list)
 {
     extern __shared__ int32_t s_first[];                   // [T+1]
-    table_scan<kScanThreads>(tmeta, T, F, nnz, target, log_max, s_first);
+    table_cut_load<kScanThreads>(cut, T, s_first, nullptr);
     const int base = blockIdx.x * kScanThreads;
     int before = 0;
     for (int i = threadIdx.x; i < base; i += kScanThreads) before += slice_total[i];
@@ -239,9 +268,10 @@ pk_slice_scan_kernel(const TableMeta* __restrict__ tmeta, int T, int F, int64_t 
         const int t = upper_bound_i32(s_first, T + 1, s) - 1;
         SliceInfo si;
         si.table = t; si.idx = s - s_first[t]; si.start = carry + ex; si.count = c;
+        if (s >= s_first[T]) { si.table = -1; si.idx = 0; si.count = 0; }      // room for slices this batch does not have
         // A slice that holds a hot key has many times the records of the others: such slices are listed,
         // and blocks of four times the threads take them, in launches that run beside the others'.
-        if (c > big_count) {
+        if (c > big_count && si.table >= 0) {
             const int at = atomicAdd(n_big, 1);
             if (at < kBigSlicesMax) {
                 big_list[at] = s;
@@ -258,9 +288,9 @@ pk_slice_scan_kernel(const TableMeta* __restrict__ tmeta, int T, int F, int64_t 
 // touched slice with one global add, and then places its records from block-local cursors.
 template <int BT>
 __global__ void __launch_bounds__(NT)
-pk_scatter_kernel(const int32_t* __restrict__ offsets, int B, int F, int T, int64_t nnz, int target, int log_max,
+pk_scatter_kernel(const int32_t* __restrict__ offsets, int B, int F, int T, int64_t nnz, int log_max,
                   const FieldMeta* __restrict__ fmeta, const PackMeta* __restrict__ pm,
-                  const TableMeta* __restrict__ tmeta, const int32_t* __restrict__ slot_field,
+                  const TableCut* __restrict__ cut, const int32_t* __restrict__ slot_field,
                   const PackState* __restrict__ st, const uint32_t* __restrict__ keys, int32_t* slice_cursor,
                   uint2* __restrict__ rec, int hist_words, int64_t out_dim)
 {
@@ -270,11 +300,12 @@ pk_scatter_kernel(const int32_t* __restrict__ offsets, int B, int F, int T, int6
     int32_t* s_delta = s_fb + (F + 1);
     int32_t* s_slotpos = s_delta + F;
     int32_t* s_first = s_slotpos + (F + 1);
-    int32_t* s_hist = s_first + (T + 1);
+    int32_t* s_lg = s_first + (T + 1);
+    int32_t* s_hist = s_lg + T;
     int32_t* s_place = s_hist + hist_words;
     const int tid = threadIdx.x;
     const int bad = field_scan<NT>(offsets, B, F, nnz, slot_field, s_fb, s_delta, s_slotpos);
-    table_scan<NT>(tmeta, T, F, nnz, target, log_max, s_first);
+    table_cut_load<NT>(cut, T, s_first, s_lg);
     if (bad) return;
     const int tpf = (B + BT - 1) / BT;
     const int64_t n_tiles = (int64_t)F * tpf;
@@ -283,8 +314,9 @@ pk_scatter_kernel(const int32_t* __restrict__ offsets, int B, int F, int T, int6
         const int f = tl.f;
         const FieldMeta m = fmeta[f];
         if (st[m.pack].error) continue;                    // the keys kernel rejected offsets of this pack
-        const TableMeta tm = tmeta[m.stable];
-        const SliceGeom g = slice_geom(tm.rows, tm.field_end - tm.field_begin, F, nnz, target, log_max);
+        SliceGeom g;
+        g.log_keys = s_lg[m.stable];
+        g.n = s_first[m.stable + 1] - s_first[m.stable];
         const int64_t g0 = (int64_t)f * B + tl.b0;
         __syncthreads();
         for (int t = tid; t <= tl.nb; t += NT) s_po[t] = offsets[g0 + t];
@@ -339,6 +371,7 @@ struct SliceArgs {
     int F, B; int64_t nnz; int target, log_max;
     const int64_t* ids; const int32_t* offsets; const SmallSlice* small_slices;   // small batches: the block finds its occurrences itself
     const SliceInfo* slice_info; const uint2* rec;              // large batches: the slice's records
+    const TableCut* cut;                                        // ... and the tables' cuts for this batch
     const FieldMeta* fmeta;
     int32_t* packed_offsets;
     uint32_t* keys; int32_t* inverse;                           // written here for small batches only
@@ -411,12 +444,13 @@ __device__ __forceinline__ void slice_body(const SliceArgs& a, int slice, int32_
         key_lo = ss.key_lo; rows = ss.rows;
     } else {
         const SliceInfo si = a.slice_info[slice];
+        if (si.table < 0) return;                                      // room for a slice this batch does not have
         if (BIG != ((si.table & kBigSliceFlag) != 0)) return;          // listed slices belong to the launch that takes the list
         t = si.table & ~kBigSliceFlag; idx = si.idx; rec_start = si.start; rec_count = si.count;
         const TableMeta tm = a.tmeta[t];
         p = tm.pack; field_begin = tm.field_begin; nf = tm.field_end - tm.field_begin; key_lo = tm.key_lo; rows = tm.rows;
-        const SliceGeom geo = slice_geom(rows, nf, F, a.nnz, a.target, a.log_max);
-        lg = geo.log_keys; n_tslices = geo.n;
+        const TableCut tc = a.cut[t];
+        lg = tc.log_keys; n_tslices = tc.n;
         pack_first = 0; is_last = 0;
     }
     const PackMeta k = a.pm[p];

@@ -181,7 +181,7 @@ static pk_status forward_impl(const pk_plan* plan, DeviceState* ds_given, int st
     const int64_t avg_len = std::max<int64_t>(nnz / std::max<int64_t>(n_bags, 1), 1);
     const int bt = avg_len >= 48 ? 32 : avg_len >= 32 ? 128 : avg_len >= 12 ? 512 : 1024;     // (a mix of short and very long bags counts as long)
     const int64_t n_tiles = (int64_t)F * ((B + bt - 1) / bt);
-    const size_t scan_words = field_scan_words(F) + (size_t)T + 1;
+    const size_t scan_words = field_scan_words(F) + 2 * (size_t)T + 1;
     if (do_dedup && !L.small && (scan_words + 2 * (size_t)L.max_table_slices) * 4 > 64 * 1024)
         return fail(PK_EOVERFLOW, std::string(who) + ": fields, tables and slices per table together exceed what the "
                                   "dedup kernels stage in LDS");
@@ -189,6 +189,7 @@ static pk_status forward_impl(const pk_plan* plan, DeviceState* ds_given, int st
         sa.target = kSliceOccLarge; sa.log_max = L.log_max;
         sa.desc = nullptr; sa.gdesc = nullptr; sa.done = nullptr;
         sa.slice_info = ws.at<SliceInfo>(L.slice_info); sa.rec = ws.at<uint2>(L.rec);
+        sa.cut = ws.at<TableCut>(L.tgeom);
         sa.bitmap = ws.at<uint32_t>(L.bitmap); sa.rank = ws.at<int32_t>(L.rank);
         int32_t* slice_total = ws.at<int32_t>(L.slice_total);
         int32_t* slice_cursor = ws.at<int32_t>(L.slice_cursor);
@@ -199,7 +200,8 @@ static pk_status forward_impl(const pk_plan* plan, DeviceState* ds_given, int st
         const size_t keys_lds = (scan_words + (size_t)L.max_table_slices) * 4;
 #define PK_KEYS_LAUNCH(BT)                                                                                      \
     PK_LAUNCH("pk_keys", pk_keys_kernel<BT>, key_grid, dim3(NT), keys_lds, ids, offsets, B, F, P, T, nnz, sa.target, \
-              sa.log_max, ds->fmeta, ds->pmeta, ds->sort_tables, ds->slot_field, st, keys, packed_offsets, slice_total, seg)
+              sa.log_max, ds->fmeta, ds->pmeta, ds->sort_tables, ds->slot_field, st, keys, packed_offsets, slice_total, seg, \
+              ws.at<TableCut>(L.tgeom), L.n_slices)
         switch (bt) {
             case 32: PK_KEYS_LAUNCH(32); break;
             case 128: PK_KEYS_LAUNCH(128); break;
@@ -235,13 +237,13 @@ static pk_status forward_impl(const pk_plan* plan, DeviceState* ds_given, int st
         int32_t* big_list = ws.at<int32_t>(L.big_list);
         PK_LAUNCH("pk_slice_scan", pk_slice_scan_kernel, dim3(blocks_for(L.n_slices, kScanThreads, 1 << 20)),
                   dim3(kScanThreads), (size_t)(T + 1) * 4,
-                  ds->sort_tables, T, F, nnz, sa.target, sa.log_max, slice_total, slice_cursor, ws.at<SliceInfo>(L.slice_info),
+                  ws.at<TableCut>(L.tgeom), T, slice_total, slice_cursor, ws.at<SliceInfo>(L.slice_info),
                   L.n_slices, L.log_max == kSliceLogFine ? kBigSliceCount : 0x7FFFFFFF, big_list + kBigSlicesMax, big_list);
         const size_t sc_lds = (scan_words + 2 * (size_t)L.max_table_slices) * 4;
         const dim3 tile_grid(blocks_for(n_tiles, 1, 256 * 8));
 #define PK_SCATTER_LAUNCH(BT)                                                                                   \
-    PK_LAUNCH("pk_scatter", pk_scatter_kernel<BT>, tile_grid, dim3(NT), sc_lds, offsets, B, F, T, nnz, sa.target,   \
-              sa.log_max, ds->fmeta, ds->pmeta, ds->sort_tables, ds->slot_field, st, keys, slice_cursor,            \
+    PK_LAUNCH("pk_scatter", pk_scatter_kernel<BT>, tile_grid, dim3(NT), sc_lds, offsets, B, F, T, nnz,              \
+              sa.log_max, ds->fmeta, ds->pmeta, ws.at<TableCut>(L.tgeom), ds->slot_field, st, keys, slice_cursor,   \
               ws.at<uint2>(L.rec), L.max_table_slices, plan->out_dim)
         switch (bt) {
             case 32: PK_SCATTER_LAUNCH(32); break;

@@ -4,6 +4,7 @@
 
 #include <cstdint>
 #include <cstddef>
+#include <algorithm>
 #include <string>
 #include <vector>
 
@@ -41,15 +42,16 @@ constexpr int64_t kFineRowsMax = (int64_t)4096 << kSliceLogFine;   // longest ta
 #endif
 
 // Slices of one table for a partitioned call: 2^log_keys keys each, n of them.  The aim is `target`
-// occurrences per slice if every field of the layer had the same number of occurrences.  Depends on
-// sizes only (no data), so host and device derive the same cut.
+// occurrences per slice, given how many occurrences the table's fields have in THIS batch (the
+// offsets say so: a layer's fields differ widely in length, Sec. II-B).  The kernels derive the cut
+// from the offsets; the host only needs the most slices a batch can give (slice_count_max).
 struct SliceGeom { int32_t log_keys; int32_t n; };
-PK_HD inline SliceGeom slice_geom(uint32_t rows, int32_t n_table_fields, int32_t F, int64_t nnz, int32_t target,
-                                  int32_t log_max)
+constexpr int kSliceWantMax = 1024;        // slices asked for a table on account of its occurrences
+PK_HD inline SliceGeom slice_geom(uint32_t rows, int64_t occ, int32_t target, int32_t log_max)
 {
-    const int64_t est = (nnz * n_table_fields + F - 1) / F;
-    int64_t want = (est + target - 1) / target;
+    int64_t want = (occ + target - 1) / target;
     if (want < 1) want = 1;
+    if (want > kSliceWantMax) want = kSliceWantMax;
     const int64_t per = ((int64_t)rows + want - 1) / want;
     int lg = kSliceLogMin;
     while (lg < log_max && ((int64_t)1 << lg) < per) ++lg;
@@ -57,6 +59,15 @@ PK_HD inline SliceGeom slice_geom(uint32_t rows, int32_t n_table_fields, int32_t
     g.log_keys = lg;
     g.n = (int32_t)(((int64_t)rows + ((int64_t)1 << lg) - 1) >> lg);
     return g;
+}
+// The most slices slice_geom gives a table of a batch with nnz occurrences: either the slices are as
+// large as they may be (2^log_max keys), or there are at most as many as were asked for.
+inline int32_t slice_count_max(uint32_t rows, int64_t nnz, int32_t target, int32_t log_max)
+{
+    const int64_t coarse = ((int64_t)rows + ((int64_t)1 << log_max) - 1) >> log_max;
+    const int64_t fine = ((int64_t)rows + ((int64_t)1 << kSliceLogMin) - 1) >> kSliceLogMin;
+    const int64_t want = std::min<int64_t>(kSliceWantMax, nnz / target + 1);
+    return (int32_t)std::min(fine, std::max(coarse, want));
 }
 
 // Small batches: the cut depends on the plan alone (up to 8 slices per table, fewer when there are
@@ -125,6 +136,14 @@ struct TableMeta {
     int32_t pad[2];
 };
 
+// The cut of one table for the batch at hand (written by the keys kernel, read by the kernels after it).
+struct TableCut {
+    int32_t log_keys;        // 2^log_keys keys per slice
+    int32_t n;               // slices of the table
+    int32_t first;           // the table's first slice (slices are numbered over all packs)
+    int32_t occ;             // occurrences of the table's fields in this batch
+};
+
 // One slice as the partitioned path hands it to the slice kernel (written by the scan kernel).
 struct SliceInfo {
     int32_t table;           // index in the table list
@@ -156,7 +175,7 @@ struct Pack {
 // Byte offsets of the workspace's arrays for one (plan, B, nnz).
 struct Layout {
     size_t state, packed_offsets, keys, inverse, seg_ent, tile_hdr, unique, seg, ghot,
-           clear_begin, slice_total, slice_nu, big_list, slice_cursor, slice_usum, slice_info, rec, bitmap, rank, total;
+           clear_begin, slice_total, slice_nu, big_list, slice_cursor, slice_usum, slice_info, tgeom, rec, bitmap, rank, total;
     size_t clear_bytes;          // what the partitioned path clears before its first kernel: per-pack state,
                                  // slice totals and distinct-key counts, contiguous from `clear_begin`
     int32_t n_slices;            // slices of all tables for this call

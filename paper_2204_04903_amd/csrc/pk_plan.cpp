@@ -38,17 +38,20 @@ int32_t pos_tile_for(int64_t nnz)
     return (int32_t)t;
 }
 
-// slices of all tables (and the most any table has) of a partitioned call
+// the most slices all tables together (and any one table) can have in a partitioned call: the tables'
+// shares of the occurrences are not known before the batch is
 static void count_slices(const pk_plan* plan, int64_t nnz, int32_t log_max, int64_t* total, int32_t* most)
 {
-    const int32_t F = (int32_t)plan->fields.size();
-    *total = 0;
+    int64_t each = 0, coarse = 0;
     *most = 0;
     for (const TableMeta& tm : plan->sort_tables) {
-        const SliceGeom g = slice_geom(tm.rows, tm.field_end - tm.field_begin, F, nnz, kSliceOccLarge, log_max);
-        *total += g.n;
-        *most = std::max(*most, g.n);
+        const int32_t n = slice_count_max(tm.rows, nnz, kSliceOccLarge, log_max);
+        each += n;
+        coarse += ((int64_t)tm.rows + ((int64_t)1 << log_max) - 1) >> log_max;
+        *most = std::max(*most, n);
     }
+    // the slices asked for on account of occurrences number at most nnz / target + one per table
+    *total = std::min<int64_t>(each, coarse + nnz / kSliceOccLarge + (int64_t)plan->sort_tables.size());
 }
 
 Layout make_layout(const pk_plan* plan, int32_t B, int64_t nnz)
@@ -79,6 +82,7 @@ Layout make_layout(const pk_plan* plan, int32_t B, int64_t nnz)
     L.slice_cursor   = take(L.small ? 0 : (size_t)slices * 4);
     L.slice_usum     = take(L.small ? 0 : (size_t)slices * 4);
     L.slice_info     = take(L.small ? 0 : (size_t)slices * sizeof(SliceInfo));
+    L.tgeom          = take(L.small ? 0 : plan->sort_tables.size() * sizeof(TableCut));
     L.packed_offsets = take((F * (size_t)B + P) * 4);
     L.keys           = take(n * 4);
     L.inverse        = take(n * 4);
