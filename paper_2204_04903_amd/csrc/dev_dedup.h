@@ -375,7 +375,7 @@ struct SliceArgs {
     const FieldMeta* fmeta;
     int32_t* packed_offsets;
     uint32_t* keys; int32_t* inverse;                           // written here for small batches only
-    uint32_t* bitmap; int32_t* rank; int32_t* slice_nu;         // large batches only: bitmap, rank samples, distinct keys per slice
+    uint32_t* bitmap; int32_t* slice_nu;                        // large batches only: bitmaps with rank samples, distinct keys per slice
     const int32_t* big_list; const int32_t* n_big;              // ... and the listed slices with many records
     uint32_t* unique; int32_t* seg_all; uint32_t* ent_all; int ent_mult;
     int4* tile_hdr; int tp; double* ghot; int dmax;
@@ -562,9 +562,12 @@ __device__ __forceinline__ void slice_body(const SliceArgs& a, int slice, int32_
     };
 
     // ---- which keys occur ----
-    const size_t gw0 = FROM_IDS ? 0 : (size_t)a.tmeta[t].word_base + (size_t)idx * words;   // the slice's bitmap in memory
+    // The slice's bitmap in memory: word w of the table's bitmap stands at w + w / 3 of the table's
+    // region, so that every 16 bytes hold three words and, in the fourth, the rank of their first key.
+    uint32_t* bmw = FROM_IDS ? nullptr : a.bitmap + a.tmeta[t].word_base;
+    const uint32_t tw0 = (uint32_t)idx * (uint32_t)words;
     if (MODE == kSlicePlace) {
-        for (int w = tid; w < words; w += NTH) s_bits[w] = a.bitmap[gw0 + w];
+        for (int w = tid; w < words; w += NTH) s_bits[w] = bmw[tw0 + w + (tw0 + w) / 3u];
     } else {
         for (int w = tid; w < words; w += NTH) s_bits[w] = 0;
     }
@@ -618,7 +621,7 @@ __device__ __forceinline__ void slice_body(const SliceArgs& a, int slice, int32_
         }
     }
     if (MODE == kSliceMark) {                              // the bitmap and the count go to memory; the rest follows the scan
-        for (int w = tid; w < words; w += NTH) a.bitmap[gw0 + w] = s_bits[w];
+        for (int w = tid; w < words; w += NTH) bmw[tw0 + w + (tw0 + w) / 3u] = s_bits[w];
         if (tid == 0) a.slice_nu[slice] = n_u;
         return;
     }
@@ -689,7 +692,8 @@ __device__ __forceinline__ void slice_body(const SliceArgs& a, int slice, int32_
             }
         }
         if (!FROM_IDS) {                                   // rank samples beside the bitmap, for the inverse kernel
-            for (int w = tid * kRankWords; w < words; w += NTH * kRankWords) a.rank[(gw0 + w) / kRankWords] = base_u + (int)s_pre[w];
+            for (uint32_t u = (tw0 + 2u) / 3u + tid; 3u * u < tw0 + (uint32_t)words; u += NTH)
+                bmw[4u * u + 3u] = (uint32_t)(base_u + (int)s_pre[3u * u - tw0]);
         }
         if (is_last && tid == 0) {
             a.st[p].n_unique = base_u + n_u;
@@ -902,9 +906,9 @@ __device__ __forceinline__ void meta_body(const SliceArgs& a, int block, int nbl
 }
 
 // ---------------------------------------------------------------------------
-// Large batches: inverse[q] = number of distinct keys of the pack below key[q]: the rank sample of
-// the key's 256-key block (written by the slice kernel) plus the set bits before the key inside
-// the block.  Tiles of KT consecutive positions of the packed order (all packs in one launch); which
+// Large batches: inverse[q] = number of distinct keys of the pack below key[q]: the rank sample that
+// stands beside the key's three bitmap words (written by the slice kernel) plus the set bits before
+// the key among them: one 16-byte read per position.  Tiles of KT consecutive positions of the packed order (all packs in one launch); which
 // table a position belongs to follows from where its field's occurrences start, staged in LDS with
 // the table's first key and the place of its bitmap.
 // ---------------------------------------------------------------------------
@@ -914,9 +918,9 @@ pk_inverse_kernel(const int32_t* __restrict__ offsets, int B, int F, int P, int6
                   const FieldMeta* __restrict__ fmeta, const PackMeta* __restrict__ pm,
                   const TableMeta* __restrict__ tmeta, const int32_t* __restrict__ slot_field,
                   const PackState* __restrict__ st, const uint32_t* __restrict__ keys,
-                  const uint4* __restrict__ bitmap4, const int32_t* __restrict__ rank, int32_t* __restrict__ inverse)
+                  const uint4* __restrict__ bitmap4, int32_t* __restrict__ inverse)
 {
-    extern __shared__ int32_t s_dyn[];                     // field scan | per slot: first key, bitmap place, rows, pack
+    extern __shared__ int32_t s_dyn[];                     // field scan | per slot: first key, bitmap place, rows, the pack's error word
     int32_t* s_fb = s_dyn;
     int32_t* s_delta = s_fb + (F + 1);
     int32_t* s_slotpos = s_delta + F;
@@ -928,7 +932,7 @@ pk_inverse_kernel(const int32_t* __restrict__ offsets, int B, int F, int P, int6
     for (int j = threadIdx.x; j < F; j += NT) {
         const FieldMeta m = fmeta[slot_field[j]];
         const TableMeta tm = tmeta[m.stable];
-        s_klo[j] = tm.key_lo; s_wb[j] = tm.word_base; s_rows[j] = tm.rows; s_pack[j] = m.pack;
+        s_klo[j] = tm.key_lo; s_wb[j] = tm.word_base; s_rows[j] = tm.rows; s_pack[j] = st[m.pack].error;   // (the error word, final by now)
     }
     __syncthreads();
     const int n = s_slotpos[F];
@@ -940,30 +944,40 @@ pk_inverse_kernel(const int32_t* __restrict__ offsets, int B, int F, int P, int6
             const int q = it.tile * KT + k * NT + (int)threadIdx.x;
             key[k] = q < n ? keys[q] : 0;
         }
+        // the lookups of the tile's positions are all asked for before any is used
         int j = -1;
+        uint32_t kk[KT / NT];
+        uint4 x[KT / NT];
+        bool ok[KT / NT];
 #pragma unroll
         for (int k = 0; k < KT / NT; ++k) {
             const int q = it.tile * KT + k * NT + (int)threadIdx.x;
-            if (q >= n) continue;
-            if (j < 0 || q >= s_slotpos[j + 1]) j = upper_bound_i32(s_slotpos, F + 1, q) - 1;   // the slot of this position
-            if (st[s_pack[j]].error) continue;
-            const uint32_t kk = key[k] - s_klo[j];
-            if (kk >= s_rows[j]) continue;                 // no key of this table (only after rejected offsets)
-            const uint4* bm = bitmap4 + (size_t)s_wb[j] / 4;
-            const int32_t* rk = rank + (size_t)s_wb[j] / kRankWords;
-            const uint32_t blk = kk >> 8;
-            const int wi = (kk >> 5) & 7;
-            const uint4 x = bm[2 * (size_t)blk], y = bm[2 * (size_t)blk + 1];
-            const uint32_t w[8] = {x.x, x.y, x.z, x.w, y.x, y.y, y.z, y.w};
-            int r = rk[blk];
+            ok[k] = q < n;
+            kk[k] = 0;
+            x[k] = make_uint4(0, 0, 0, 0);
+            if (ok[k]) {
+                if (j < 0 || q >= s_slotpos[j + 1]) j = upper_bound_i32(s_slotpos, F + 1, q) - 1;   // the slot of this position
+                kk[k] = key[k] - s_klo[j];
+                // no lookup for a pack with rejected offsets, nor for a key that is none of its table (only possible then)
+                ok[k] = s_pack[j] == 0 && kk[k] < s_rows[j];
+                if (ok[k]) x[k] = bitmap4[(size_t)s_wb[j] / 4 + (kk[k] >> 5) / 3u];
+            }
+        }
+#pragma unroll
+        for (int k = 0; k < KT / NT; ++k) {
+            const int q = it.tile * KT + k * NT + (int)threadIdx.x;
+            const uint32_t tw = kk[k] >> 5;
+            const int wi = (int)(tw - tw / 3u * 3u);
+            const uint32_t w[3] = {x[k].x, x[k].y, x[k].z};
+            int r = (int)x[k].w;                           // the rank of the 16 bytes' first key
             uint32_t cur = 0;
 #pragma unroll
-            for (int i = 0; i < 8; ++i) {
+            for (int i = 0; i < 3; ++i) {
                 if (i < wi) r += __popc(w[i]);
                 if (i == wi) cur = w[i];
             }
-            r += __popc(cur & ((1u << (kk & 31)) - 1u));
-            inverse[q] = r;
+            r += __popc(cur & ((1u << (kk[k] & 31)) - 1u));
+            if (ok[k]) inverse[q] = r;
         }
     }
 }

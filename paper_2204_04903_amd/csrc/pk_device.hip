@@ -190,7 +190,7 @@ static pk_status forward_impl(const pk_plan* plan, DeviceState* ds_given, int st
         sa.desc = nullptr; sa.gdesc = nullptr; sa.done = nullptr;
         sa.slice_info = ws.at<SliceInfo>(L.slice_info); sa.rec = ws.at<uint2>(L.rec);
         sa.cut = ws.at<TableCut>(L.tgeom);
-        sa.bitmap = ws.at<uint32_t>(L.bitmap); sa.rank = ws.at<int32_t>(L.rank);
+        sa.bitmap = ws.at<uint32_t>(L.bitmap);
         int32_t* slice_total = ws.at<int32_t>(L.slice_total);
         int32_t* slice_cursor = ws.at<int32_t>(L.slice_cursor);
         const int64_t n_clear4 = (int64_t)(L.clear_bytes / 16);
@@ -290,7 +290,7 @@ static pk_status forward_impl(const pk_plan* plan, DeviceState* ds_given, int st
         const size_t inv_lds = (field_scan_words(F) + 4 * (size_t)F) * 4;
         const unsigned xq = (blocks_for(nnz, 1024, 256 * 16) + 7u) & ~7u;
         PK_LAUNCH("pk_inverse", pk_inverse_kernel<1024>, dim3(xq), dim3(NT), inv_lds, offsets, B, F, P, nnz, ds->fmeta,
-                  ds->pmeta, ds->sort_tables, ds->slot_field, st, keys, reinterpret_cast<const uint4*>(sa.bitmap), sa.rank,
+                  ds->pmeta, ds->sort_tables, ds->slot_field, st, keys, reinterpret_cast<const uint4*>(sa.bitmap),
                   inverse);
     }
     if (n_side) { rc = join_streams(ds, stream, n_side); if (rc != PK_OK) return rc; }

@@ -14,7 +14,7 @@ namespace pk {
 
 constexpr int kColdMax   = 8;      // keys with at most this many occurrences: one lane group per key
 constexpr int kWarmMax   = 256;    // up to this many: one wavefront per key; above: split, partial sums
-constexpr int kRankWords = 8;      // one rank sample per 8 bitmap words (256 keys)
+constexpr int kRankWords = 3;      // in memory a rank sample follows every 3 bitmap words (96 keys): a lookup is one 16-byte read
 constexpr int kPosTileMax = 512;   // occurrences handled per block iteration in the backward pass (upper end)
 constexpr int kPosTileMin = 64;
 constexpr size_t kAlign = 256;
@@ -132,7 +132,7 @@ struct TableMeta {
     uint32_t rows;
     int32_t field_begin;     // range in the table field list
     int32_t field_end;
-    uint32_t word_base;      // first word of the table's bitmap (tables are padded to whole largest slices)
+    uint32_t word_base;      // first word of the table's bitmap and rank samples (a multiple of 4)
     int32_t pad[2];
 };
 
@@ -175,7 +175,7 @@ struct Pack {
 // Byte offsets of the workspace's arrays for one (plan, B, nnz).
 struct Layout {
     size_t state, packed_offsets, keys, inverse, seg_ent, tile_hdr, unique, seg, ghot,
-           clear_begin, slice_total, slice_nu, big_list, slice_cursor, slice_usum, slice_info, tgeom, rec, bitmap, rank, total;
+           clear_begin, slice_total, slice_nu, big_list, slice_cursor, slice_usum, slice_info, tgeom, rec, bitmap, total;
     size_t clear_bytes;          // what the partitioned path clears before its first kernel: per-pack state,
                                  // slice totals and distinct-key counts, contiguous from `clear_begin`
     int32_t n_slices;            // slices of all tables for this call
@@ -203,7 +203,7 @@ struct pk_plan {
     std::vector<pk::SmallSlice> small_slices; // the cut used by the one-launch forward pass
     int64_t out_dim = 0;
     bool any_mean = false;
-    int64_t bitmap_words = 0;             // all tables' bitmaps, each padded to whole largest slices
+    int64_t bitmap_words = 0;             // all tables' bitmaps with their rank samples
     int32_t max_table_fields = 0;         // most fields reading one table
     int32_t dmax = 0;
     void* device_state = nullptr;         // owned by pk_device.hip (metadata upload, events)

@@ -96,7 +96,6 @@ Layout make_layout(const pk_plan* plan, int32_t B, int64_t nnz)
     L.ghot           = take(tile_cap * (size_t)plan->dmax * 8);
     L.rec            = take(L.small ? 0 : n * 8);
     L.bitmap         = take(L.small ? 0 : (size_t)plan->bitmap_words * 4);
-    L.rank           = take(L.small ? 0 : (size_t)plan->bitmap_words / kRankWords * 4);
     L.total = off;
     return L;
 }
@@ -249,7 +248,9 @@ pk_status pk_plan_create(const pk_table_desc* tables, int32_t n_tables, const pk
             tm.field_end = (int32_t)pl->table_fields.size();
             if (tm.field_end == tm.field_begin) continue;
             tm.word_base = (uint32_t)pl->bitmap_words;
-            pl->bitmap_words += ((tables[t].rows + ((int64_t)1 << kSliceLogMax) - 1) >> kSliceLogMax) * kSliceWordsMax;
+            // three bitmap words and a rank sample to every 16 bytes; the table's words padded to whole largest slices
+            const int64_t table_words = ((tables[t].rows + ((int64_t)1 << kSliceLogMax) - 1) >> kSliceLogMax) * kSliceWordsMax;
+            pl->bitmap_words += ((table_words + 2) / 3 + 1) * 4;
             pl->max_table_fields = std::max(pl->max_table_fields, tm.field_end - tm.field_begin);
             pl->sort_tables.push_back(tm);
         }
