@@ -171,7 +171,11 @@ struct PoolJob {
     static_cast<const WT_*>(k.W), src, a.fmeta, k.slot_field, pj.B, k.D, k.n_bags, pj.out, pj.out_stride, local,  \
         n_local, kSliceThreads, HotView{nullptr, nullptr, nullptr}
 
-__global__ void __launch_bounds__(kSliceThreads, 8)
+// WAVES: wavefronts per SIMD the kernel is compiled for.  8 lets two blocks share a compute unit, which a
+// launch with more blocks than compute units needs; 4 gives a block twice the registers (nothing is then
+// kept in scratch memory), which is faster when every block has a compute unit to itself.
+template <int WAVES>
+__global__ void __launch_bounds__(kSliceThreads, WAVES)
 pk_fused_kernel(SliceArgs a, PoolJob pj, int slice_blocks, int meta_blocks)
 {
     extern __shared__ int32_t s_dyn[];                     // kSliceTfWords words per field of a table

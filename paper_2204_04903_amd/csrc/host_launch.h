@@ -6,6 +6,7 @@
 // ---------------------------------------------------------------------------
 struct DeviceState {
     int device = -1;
+    int n_cus = 256;                      // compute units of the device
     void* blob = nullptr;
     FieldMeta* fmeta = nullptr;
     PackMeta* pmeta = nullptr;
@@ -132,6 +133,7 @@ pk_status ensure_device_state(const pk_plan* cplan, DeviceState** out)
     if (ds) return fail(PK_EINVAL, "a plan can be used on one device only");
     ds = new DeviceState();
     ds->device = dev;
+    if (hipDeviceGetAttribute(&ds->n_cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || ds->n_cus <= 0) ds->n_cus = 256;
     MetaImage mi;
     build_meta_image(plan, &mi);
     e = hipMalloc(&ds->blob, mi.total);

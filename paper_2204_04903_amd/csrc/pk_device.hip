@@ -171,8 +171,11 @@ static pk_status forward_impl(const pk_plan* plan, DeviceState* ds_given, int st
         pj.n_packs = np; pj.B = B; pj.n_blocks = nb; pj.out = out; pj.out_stride = out_row_stride;
         const int meta_blocks = (int)blocks_for(n_bags, kSliceThreads * 4, 64);
         const size_t dyn = (size_t)std::max(1, plan->max_table_fields) * kSliceTfWords * 4;
-        PK_LAUNCH("pk_fused", pk_fused_kernel, dim3((unsigned)(L.n_slices + meta_blocks + nb)), dim3(kSliceThreads), dyn,
-                  sa, pj, L.n_slices, meta_blocks);
+        const unsigned fused_blocks = (unsigned)(L.n_slices + meta_blocks + nb);
+        if ((int)fused_blocks <= ds->n_cus)
+            PK_LAUNCH("pk_fused", pk_fused_kernel<4>, dim3(fused_blocks), dim3(kSliceThreads), dyn, sa, pj, L.n_slices, meta_blocks);
+        else
+            PK_LAUNCH("pk_fused", pk_fused_kernel<8>, dim3(fused_blocks), dim3(kSliceThreads), dyn, sa, pj, L.n_slices, meta_blocks);
         if (!do_pool || fuse_pool) return PK_OK;
     }
 
@@ -356,6 +359,7 @@ pk_status pk_forward_static(const pk_plan* plan, void* const* W, const int64_t* 
         if (e != hipSuccess || !ptr) return fail(PK_EHIP, hip_msg("hipGetSymbolAddress(scratch)", e));
         sd.ptr = ptr;
         sd.ds.device = dev;
+        if (hipDeviceGetAttribute(&sd.ds.n_cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || sd.ds.n_cus <= 0) sd.ds.n_cus = 256;
         sd.ds.overlap = false;                   // no internal streams: every kernel on the caller's stream
     }
     MetaImage mi;
