@@ -393,7 +393,7 @@ struct SliceArgs {
 
 // LDS words of a slice block: bitmap words | their popcount prefix | counters of a round of distinct keys.
 // Small batches: the same words first hold the field scan, and the upper three quarters of the
-// counters hold the slice's occurrences when they are few (kept from the first pass over the IDs,
+// counters hold the slice's occurrences when they are few (12 bytes each, kept from the first pass over the IDs,
 // so that the IDs are read once).
 constexpr int slice_lds_words(int log_max, int ranks) { return 2 * (1 << (log_max - 5)) + ranks; }
 constexpr int kSliceTfWords = 5;           // dynamic LDS words per field of a table
@@ -420,14 +420,18 @@ __device__ __forceinline__ void slice_body(const SliceArgs& a, int slice, int32_
     constexpr bool FROM_IDS = MODE == kSliceFused;
     constexpr bool GROUPED = FROM_IDS || BIG || NTH > 256;          // lanes that share a key combine their counter updates
     constexpr int WMAX = 1 << (LOGMAX - 5);
-    constexpr int CACHE = FROM_IDS ? (RANKS * 3 / 4) / 4 : 0;      // occurrences kept in LDS (16 bytes each)
-    static_assert(!FROM_IDS || (RANKS - 4 * CACHE >= CACHE), "cached occurrences need as many counters");
+    constexpr int CACHE = FROM_IDS ? (RANKS * 3 / 4) / 3 : 0;      // occurrences kept in LDS (12 bytes each)
+    static_assert(!FROM_IDS || (RANKS - 3 * CACHE >= CACHE), "cached occurrences need as many counters");
+    constexpr int kBagBits = 20;                                   // of a cached occurrence's third word: its bag; above them its length
+    constexpr uint32_t kLenMany = (1u << (32 - kBagBits)) - 1u;    // ... a length of this or more is looked up again
     static_assert(!FROM_IDS || slice_lds_words(LOGMAX, RANKS) >= 3 * 4096 + 2, "the field scan must fit the block's LDS");
     const int tid = threadIdx.x;
     uint32_t* s_bits = reinterpret_cast<uint32_t*>(s_main);
     uint32_t* s_pre = s_bits + WMAX;
     int32_t* s_cnt = s_main + 2 * WMAX;
-    uint4* s_cache = reinterpret_cast<uint4*>(s_cnt + (RANKS - 4 * CACHE));
+    uint32_t* s_ckey = reinterpret_cast<uint32_t*>(s_cnt + (RANKS - 3 * CACHE));   // key inside the slice | field of the table
+    uint32_t* s_cpos = s_ckey + CACHE;                                             // position in ids
+    uint32_t* s_cbag = s_cpos + CACHE;                                             // bag | its length
     __shared__ uint32_t s_bc[4];
     __shared__ int s_ncache;
     const int F = a.F, B = a.B;
@@ -512,8 +516,10 @@ __device__ __forceinline__ void slice_body(const SliceArgs& a, int slice, int32_
             for (int base = 0; base < n_rec; base += NTH) {
                 const int i = base + tid;
                 const bool on = i < n_rec;
-                const uint4 e = on ? s_cache[i] : make_uint4(0, 0, 0, 0);
-                fn(SliceRec{e.x & ((1u << LOGMAX) - 1u), (int32_t)(e.x >> LOGMAX), (int32_t)e.y, (int32_t)e.z, (int32_t)e.w}, on);
+                const uint32_t ek = on ? s_ckey[i] : 0u, eq = on ? s_cpos[i] : 0u, eb = on ? s_cbag[i] : 0u;
+                const uint32_t L = eb >> kBagBits;
+                fn(SliceRec{ek & ((1u << LOGMAX) - 1u), (int32_t)(ek >> LOGMAX), (int32_t)eq,
+                            L == kLenMany ? -1 : (int32_t)(eb & ((1u << kBagBits) - 1u)), (int32_t)L}, on);
             }
         } else if (FROM_IDS) {
             for (int j = 0; j < nf; ++j) {
@@ -589,20 +595,18 @@ __device__ __forceinline__ void slice_body(const SliceArgs& a, int slice, int32_
                 if (lane == leader) base = atomicAdd(&s_ncache, __popcll(m));
                 base = __shfl(base, leader, 64);
                 const int at = base + __popcll(m & ((1ull << lane) - 1ull));
-                if (on && at < CACHE) s_cache[at] = make_uint4(r.kl | ((uint32_t)r.x << LOGMAX), (uint32_t)r.q, 0u, 0u);
+                if (on && at < CACHE) { s_ckey[at] = r.kl | ((uint32_t)r.x << LOGMAX); s_cpos[at] = (uint32_t)r.q; }
             }
         }
     });
     (void)block_excl_scan<NTH>(mine, &n_rec);              // its barriers also complete the bitmap
     if (!FROM_IDS) n_rec = rec_count;
-    cached = FROM_IDS && n_rec <= CACHE;
+    cached = FROM_IDS && n_rec <= CACHE && B <= (1 << kBagBits);
     if (cached) {                                          // the bags of the kept occurrences, all lookups in flight together
         for (int i = tid; i < n_rec; i += NTH) {
-            uint4 e = s_cache[i];
             int L;
-            const int b = bag_of((int)(e.x >> LOGMAX), (int)e.y, &L);
-            e.z = (uint32_t)b; e.w = (uint32_t)L;
-            s_cache[i] = e;
+            const int b = bag_of((int)(s_ckey[i] >> LOGMAX), (int)s_cpos[i], &L);
+            s_cbag[i] = (uint32_t)b | (min((uint32_t)max(L, 0), kLenMany) << kBagBits);
         }
     }
     PK_PT(a, slice, 2);
@@ -721,7 +725,7 @@ __device__ __forceinline__ void slice_body(const SliceArgs& a, int slice, int32_
     auto rank_of = [&](uint32_t kl) {
         return (int)(s_pre[kl >> 5] + __popc(s_bits[kl >> 5] & ((1u << (kl & 31)) - 1u)));
     };
-    const int rounds_cap = cached ? RANKS - 4 * CACHE : RANKS;      // cached occurrences take the upper counters' room
+    const int rounds_cap = cached ? RANKS - 3 * CACHE : RANKS;      // cached occurrences take the upper counters' room
     int placed = 0;                                        // occurrences of the keys of earlier rounds
     for (int r0 = 0; r0 < n_u; r0 += rounds_cap) {
         const int width = min(rounds_cap, n_u - r0);
