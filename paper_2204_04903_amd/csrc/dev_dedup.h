@@ -63,6 +63,16 @@ __device__ __forceinline__ int field_scan(const int32_t* __restrict__ offsets, i
     return bad;
 }
 
+// the same from the copy the keys kernel left in memory: fscan = s_fb | s_delta | s_slotpos | verdict
+template <int NTH>
+__device__ __forceinline__ int field_scan_load(const int32_t* __restrict__ fscan, int F, int32_t* s_fb)
+{
+    for (int i = threadIdx.x; i < 3 * F + 2; i += NTH) s_fb[i] = fscan[i];
+    const int bad = fscan[3 * F + 2];
+    __syncthreads();
+    return bad;
+}
+
 // The cut of every table for this batch, from the field sizes the offsets give (s_fb: where every
 // field's occurrences begin).  s_first [T+1]: the first slice of every table, in table-list order
 // (slices are numbered over all packs); s_lg [T]: log2 of the keys per slice.
@@ -156,7 +166,7 @@ pk_keys_kernel(const int64_t* __restrict__ ids, const int32_t* __restrict__ offs
                const PackMeta* __restrict__ pm, const TableMeta* __restrict__ tmeta,
                const int32_t* __restrict__ slot_field, PackState* st,
                uint32_t* __restrict__ keys, int32_t* __restrict__ packed_offsets, int32_t* slice_total,
-               int32_t* __restrict__ seg_all, TableCut* __restrict__ cut, int n_slices_max)
+               int32_t* __restrict__ seg_all, TableCut* __restrict__ cut, int n_slices_max, int32_t* __restrict__ fscan)
 {
     extern __shared__ int32_t s_dyn[];                     // field scan | first slices, slice sizes | the tile's counts
     __shared__ int32_t s_po[BT + 1];
@@ -172,6 +182,8 @@ pk_keys_kernel(const int64_t* __restrict__ ids, const int32_t* __restrict__ offs
     table_cut<NT>(tmeta, fmeta, T, F, s_fb, target, log_max, s_first, s_lg, blockIdx.x == 0 ? cut : nullptr);
     bad |= s_first[T] > n_slices_max;                      // cannot be for offsets that pass the scan: the slices' arrays are that long
     if (blockIdx.x == 0) {
+        for (int i = tid; i < 3 * F + 2; i += NT) fscan[i] = s_fb[i];     // the kernels after this one read it from here
+        if (tid == 0) fscan[3 * F + 2] = bad;
         for (int p = tid; p < P; p += NT) {
             const PackMeta k = pm[p];
             const int start = s_slotpos[k.first_slot];
@@ -292,7 +304,7 @@ pk_scatter_kernel(const int32_t* __restrict__ offsets, int B, int F, int T, int6
                   const FieldMeta* __restrict__ fmeta, const PackMeta* __restrict__ pm,
                   const TableCut* __restrict__ cut, const int32_t* __restrict__ slot_field,
                   const PackState* __restrict__ st, const uint32_t* __restrict__ keys, int32_t* slice_cursor,
-                  uint2* __restrict__ rec, int hist_words, int64_t out_dim)
+                  uint2* __restrict__ rec, int hist_words, int64_t out_dim, const int32_t* __restrict__ fscan)
 {
     extern __shared__ int32_t s_dyn[];                     // field scan | first slices | counts | places
     __shared__ int32_t s_po[BT + 1];
@@ -304,7 +316,7 @@ pk_scatter_kernel(const int32_t* __restrict__ offsets, int B, int F, int T, int6
     int32_t* s_hist = s_lg + T;
     int32_t* s_place = s_hist + hist_words;
     const int tid = threadIdx.x;
-    const int bad = field_scan<NT>(offsets, B, F, nnz, slot_field, s_fb, s_delta, s_slotpos);
+    const int bad = field_scan_load<NT>(fscan, F, s_fb);
     table_cut_load<NT>(cut, T, s_first, s_lg);
     if (bad) return;
     const int tpf = (B + BT - 1) / BT;
@@ -918,27 +930,22 @@ __device__ __forceinline__ void meta_body(const SliceArgs& a, int block, int nbl
 // ---------------------------------------------------------------------------
 template <int KT>
 __global__ void __launch_bounds__(NT)
-pk_inverse_kernel(const int32_t* __restrict__ offsets, int B, int F, int P, int64_t nnz,
-                  const FieldMeta* __restrict__ fmeta, const PackMeta* __restrict__ pm,
-                  const TableMeta* __restrict__ tmeta, const int32_t* __restrict__ slot_field,
+pk_inverse_kernel(int F, const int32_t* __restrict__ fscan, const SlotMeta* __restrict__ slot_meta,
                   const PackState* __restrict__ st, const uint32_t* __restrict__ keys,
                   const uint4* __restrict__ bitmap4, int32_t* __restrict__ inverse)
 {
     extern __shared__ int32_t s_dyn[];                     // field scan | per slot: first key, bitmap place, rows, the pack's error word
     int32_t* s_fb = s_dyn;
-    int32_t* s_delta = s_fb + (F + 1);
-    int32_t* s_slotpos = s_delta + F;
+    int32_t* s_slotpos = s_fb + (F + 1) + F;
     uint32_t* s_klo = reinterpret_cast<uint32_t*>(s_slotpos + (F + 1));
     uint32_t* s_wb = s_klo + F;
     uint32_t* s_rows = s_wb + F;
     int32_t* s_pack = reinterpret_cast<int32_t*>(s_rows + F);
-    if (field_scan<NT>(offsets, B, F, nnz, slot_field, s_fb, s_delta, s_slotpos)) return;
     for (int j = threadIdx.x; j < F; j += NT) {
-        const FieldMeta m = fmeta[slot_field[j]];
-        const TableMeta tm = tmeta[m.stable];
-        s_klo[j] = tm.key_lo; s_wb[j] = tm.word_base; s_rows[j] = tm.rows; s_pack[j] = st[m.pack].error;   // (the error word, final by now)
+        const SlotMeta m = slot_meta[j];
+        s_klo[j] = m.key_lo; s_wb[j] = m.word_base; s_rows[j] = m.rows; s_pack[j] = st[m.pack].error;   // (the error word, final by now)
     }
-    __syncthreads();
+    if (field_scan_load<NT>(fscan, F, s_fb)) return;
     const int n = s_slotpos[F];
     const int n_tiles = (n + KT - 1) / KT;
     for (XcdTiles it(n_tiles); it.valid(); it.next()) {

@@ -17,6 +17,7 @@ struct DeviceState {
     TableField* tfields = nullptr;        // the table field list with what the slice blocks need of a field
     TableMeta* sort_tables = nullptr;
     int32_t* table_fields = nullptr;
+    SlotMeta* slot_meta = nullptr;        // per (pack, slot): what the inverse kernel needs of the slot's table
     std::mutex mu;
     // Side streams: packs (and the pooling of a pack vs the dedup chain) are independent
     // pieces of memory-bound work; running them side by side hides launch gaps and
@@ -46,7 +47,8 @@ struct MetaImage {
     std::vector<FieldMeta> fm;
     std::vector<PackMeta> pmv;
     std::vector<TableField> tfi;
-    size_t o_desc, o_done, o_fm, o_pm, o_slot, o_ss, o_tfi, o_tab, o_tf, total;
+    std::vector<SlotMeta> slm;
+    size_t o_desc, o_done, o_fm, o_pm, o_slot, o_ss, o_tfi, o_tab, o_tf, o_slm, total;
 };
 
 void build_meta_image(const pk_plan* plan, MetaImage* mi)
@@ -79,6 +81,12 @@ void build_meta_image(const pk_plan* plan, MetaImage* mi)
         const int32_t f = plan->table_fields[i];
         mi->tfi[i] = TableField{f, plan->field_slot[f], (int32_t)plan->field_col[f], plan->fields[f].pool};
     }
+    mi->slm.resize(F);
+    for (size_t j = 0; j < F; ++j) {
+        const FieldMeta& m = mi->fm[plan->slot_field[j]];
+        const TableMeta& tm = plan->sort_tables[m.stable];
+        mi->slm[j] = SlotMeta{tm.key_lo, tm.word_base, tm.rows, m.pack};
+    }
     auto pad = [](size_t b) { return (b + 255) / 256 * 256; };
     size_t off = 0;
     auto take = [&](size_t bytes) { const size_t o = off; off += pad(bytes); return o; };
@@ -91,6 +99,7 @@ void build_meta_image(const pk_plan* plan, MetaImage* mi)
     mi->o_tfi  = take(mi->tfi.size() * sizeof(TableField));
     mi->o_tab  = take(plan->sort_tables.size() * sizeof(TableMeta));
     mi->o_tf   = take(plan->table_fields.size() * 4);
+    mi->o_slm  = take(F * sizeof(SlotMeta));
     mi->total = off;
 }
 
@@ -105,6 +114,7 @@ void point_into(DeviceState* ds, char* base, const MetaImage& mi)
     ds->tfields = reinterpret_cast<TableField*>(base + mi.o_tfi);
     ds->sort_tables = reinterpret_cast<TableMeta*>(base + mi.o_tab);
     ds->table_fields = reinterpret_cast<int32_t*>(base + mi.o_tf);
+    ds->slot_meta = reinterpret_cast<SlotMeta*>(base + mi.o_slm);
 }
 
 // the pieces of the image that hold data (the descriptors and their counter only have to be zero)
@@ -118,6 +128,7 @@ void for_meta_pieces(const pk_plan* plan, const MetaImage& mi, Fn&& fn)
     fn(mi.o_tfi, mi.tfi.data(), mi.tfi.size() * sizeof(TableField));
     fn(mi.o_tab, plan->sort_tables.data(), plan->sort_tables.size() * sizeof(TableMeta));
     fn(mi.o_tf, plan->table_fields.data(), plan->table_fields.size() * 4);
+    fn(mi.o_slm, mi.slm.data(), mi.slm.size() * sizeof(SlotMeta));
 }
 
 pk_status ensure_device_state(const pk_plan* cplan, DeviceState** out)

@@ -204,7 +204,7 @@ static pk_status forward_impl(const pk_plan* plan, DeviceState* ds_given, int st
 #define PK_KEYS_LAUNCH(BT)                                                                                      \
     PK_LAUNCH("pk_keys", pk_keys_kernel<BT>, key_grid, dim3(NT), keys_lds, ids, offsets, B, F, P, T, nnz, sa.target, \
               sa.log_max, ds->fmeta, ds->pmeta, ds->sort_tables, ds->slot_field, st, keys, packed_offsets, slice_total, seg, \
-              ws.at<TableCut>(L.tgeom), L.n_slices)
+              ws.at<TableCut>(L.tgeom), L.n_slices, ws.at<int32_t>(L.fscan))
         switch (bt) {
             case 32: PK_KEYS_LAUNCH(32); break;
             case 128: PK_KEYS_LAUNCH(128); break;
@@ -247,7 +247,7 @@ static pk_status forward_impl(const pk_plan* plan, DeviceState* ds_given, int st
 #define PK_SCATTER_LAUNCH(BT)                                                                                   \
     PK_LAUNCH("pk_scatter", pk_scatter_kernel<BT>, tile_grid, dim3(NT), sc_lds, offsets, B, F, T, nnz,              \
               sa.log_max, ds->fmeta, ds->pmeta, ws.at<TableCut>(L.tgeom), ds->slot_field, st, keys, slice_cursor,   \
-              ws.at<uint2>(L.rec), L.max_table_slices, plan->out_dim)
+              ws.at<uint2>(L.rec), L.max_table_slices, plan->out_dim, ws.at<int32_t>(L.fscan))
         switch (bt) {
             case 32: PK_SCATTER_LAUNCH(32); break;
             case 128: PK_SCATTER_LAUNCH(128); break;
@@ -292,9 +292,8 @@ static pk_status forward_impl(const pk_plan* plan, DeviceState* ds_given, int st
         }
         const size_t inv_lds = (field_scan_words(F) + 4 * (size_t)F) * 4;
         const unsigned xq = (blocks_for(nnz, 1024, 256 * 16) + 7u) & ~7u;
-        PK_LAUNCH("pk_inverse", pk_inverse_kernel<1024>, dim3(xq), dim3(NT), inv_lds, offsets, B, F, P, nnz, ds->fmeta,
-                  ds->pmeta, ds->sort_tables, ds->slot_field, st, keys, reinterpret_cast<const uint4*>(sa.bitmap),
-                  inverse);
+        PK_LAUNCH("pk_inverse", pk_inverse_kernel<1024>, dim3(xq), dim3(NT), inv_lds, F, ws.at<int32_t>(L.fscan), ds->slot_meta, st,
+                  keys, reinterpret_cast<const uint4*>(sa.bitmap), inverse);
     }
     if (n_side) { rc = join_streams(ds, stream, n_side); if (rc != PK_OK) return rc; }
     return PK_OK;

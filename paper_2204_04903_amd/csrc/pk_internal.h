@@ -136,6 +136,14 @@ struct TableMeta {
     int32_t pad[2];
 };
 
+// What the inverse kernel needs of a (pack, slot): static, device side, in slot order.
+struct SlotMeta {
+    uint32_t key_lo;         // first key of the slot's table inside its pack
+    uint32_t word_base;      // where the table's bitmap starts
+    uint32_t rows;           // rows of the table
+    int32_t  pack;
+};
+
 // The cut of one table for the batch at hand (written by the keys kernel, read by the kernels after it).
 struct TableCut {
     int32_t log_keys;        // 2^log_keys keys per slice
@@ -175,7 +183,7 @@ struct Pack {
 // Byte offsets of the workspace's arrays for one (plan, B, nnz).
 struct Layout {
     size_t state, packed_offsets, keys, inverse, seg_ent, tile_hdr, unique, seg, ghot,
-           clear_begin, slice_total, slice_nu, big_list, slice_cursor, slice_usum, slice_info, tgeom, rec, bitmap, total;
+           clear_begin, slice_total, slice_nu, big_list, slice_cursor, slice_usum, slice_info, tgeom, fscan, rec, bitmap, total;
     size_t clear_bytes;          // what the partitioned path clears before its first kernel: per-pack state,
                                  // slice totals and distinct-key counts, contiguous from `clear_begin`
     int32_t n_slices;            // slices of all tables for this call

@@ -83,6 +83,7 @@ Layout make_layout(const pk_plan* plan, int32_t B, int64_t nnz)
     L.slice_usum     = take(L.small ? 0 : (size_t)slices * 4);
     L.slice_info     = take(L.small ? 0 : (size_t)slices * sizeof(SliceInfo));
     L.tgeom          = take(L.small ? 0 : plan->sort_tables.size() * sizeof(TableCut));
+    L.fscan          = take(L.small ? 0 : (3 * F + 3) * 4);          // the field scan of the batch, with its verdict
     L.packed_offsets = take((F * (size_t)B + P) * 4);
     L.keys           = take(n * 4);
     L.inverse        = take(n * 4);
