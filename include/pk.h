@@ -125,12 +125,18 @@ size_t    pk_workspace_bytes(const pk_plan* plan, int32_t B, int64_t nnz);
  *           It carries the dedup context (keys, unique, inverse, segment lists)
  *           from pk_forward to the pk_backward_update that follows.
  * hip_stream: hipStream_t (NULL = default stream).
- * Offsets that violate the contract set a device error word (pk_ctx_error);
- * results are then undefined but all kernels still terminate.
- * Calls on one device are meant to follow one another (one stream, or streams
- * ordered by events as for the two stages below): the dedup kernels of two
- * calls running side by side can wait for each other's places on the chip
- * until their bounded waits give up, which raises the error word. */
+ * Offsets that violate the contract (offsets[0] != 0, offsets[n_fields*B] != nnz,
+ * a bag that ends before it begins or reaches outside its field's range) raise
+ * bit 0 of the error word of the packs they touch (of every pack, when it is the
+ * first or last offset of a field that is wrong); see pk_ctx_error.  Such a pack's
+ * results are undefined, but no read or write leaves the caller's buffers and
+ * all kernels still terminate.
+ * Small batches (nnz < 2^19) run as ONE launch whose blocks sum each other's
+ * counts through descriptors in device memory that the library owns and that
+ * are shared by all calls on a plan: such calls on one plan must follow one
+ * another (one stream, or streams ordered by events as for the two stages
+ * below).  A block's wait for another block is bounded; giving up raises bit 1
+ * of the error word. */
 pk_status pk_forward(const pk_plan* plan, void* const* W,
                      const int64_t* ids, const int32_t* offsets, int32_t B, int64_t nnz,
                      float* out, int64_t out_row_stride,
@@ -158,9 +164,9 @@ pk_status pk_forward_static(const pk_plan* plan, void* const* W,
  * workspace):
  *   g = sum over its occurrences of grad_out[b, col(f) .. col(f)+dim) * (1/L for mean)
  *   A[row] += g*g ;  W[row] -= lr * g / (sqrt(A[row]) + eps)
- * Rows of keys that do not occur are neither read nor written.  If that
- * pk_forward raised the device error word (pk_ctx_error), nothing is read or
- * written: W and A stay as they are.
+ * Rows of keys that do not occur are neither read nor written.  For a pack whose
+ * error word that pk_forward raised (pk_ctx_error), nothing is read or written:
+ * its W and A stay as they are.
  * A:        host array of n_packs DEVICE pointers, fp32 [total_rows, dim].
  * grad_out: device, fp32 [B, grad_row_stride]. */
 pk_status pk_backward_update(const pk_plan* plan, void* const* W, float* const* A,
@@ -290,9 +296,11 @@ pk_status pk_ctx_pack(const pk_plan* plan, const void* workspace, int32_t B, int
                       const uint32_t** keys, const uint32_t** unique, const int32_t** inverse,
                       const int32_t** packed_offsets, const int32_t** seg_offsets,
                       int64_t* nnz_p, int64_t* n_unique);
-/* Device error word of the last pk_forward on this workspace (0 = inputs
- * passed the checks).  SYNCHRONISES. bit 0: offsets[0] != 0 or
- * offsets[n_fields*B] != nnz; bit 1: a scan waited too long. */
+/* Device error word of the last pk_forward on this workspace: the OR over the
+ * packs' words (0 = inputs passed the checks).  SYNCHRONISES.  bit 0: offsets
+ * rejected (see pk_forward); bit 1: a block waited too long for another block's
+ * counts.  A pack whose word is set is skipped by pk_backward_update: its
+ * tables and accumulators stay as they are. */
 pk_status pk_ctx_error(const pk_plan* plan, const void* workspace, int32_t* error_word);
 
 /* ---- per-kernel timing (for the benchmark's roofline figures) -----------------
