@@ -336,10 +336,18 @@ pk_scatter_kernel(const int32_t* __restrict__ offsets, int B, int F, int T, int6
         __syncthreads();
         const int dl = s_delta[f];
         const int q_lo = s_po[0], q_hi = s_po[tl.nb];
-        for (int base = q_lo; base < q_hi; base += NT) {
-            const int i = base + tid;
-            const uint32_t s = i < q_hi ? (keys[i + dl] - m.base_row) >> g.log_keys : 0xFFFFFFFFu;
-            if (s < (uint32_t)g.n) atomicAdd(&s_hist[s], 1);
+        for (int base = q_lo; base < q_hi; base += 4 * NT) {      // four loads in flight
+            uint32_t kv[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int i = base + tid + u * NT;
+                kv[u] = i < q_hi ? keys[i + dl] - m.base_row : 0xFFFFFFFFu;
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const uint32_t s = kv[u] >> g.log_keys;
+                if (s < (uint32_t)g.n) atomicAdd(&s_hist[s], 1);
+            }
         }
         __syncthreads();
         const int slice0 = s_first[m.stable];
@@ -349,24 +357,44 @@ pk_scatter_kernel(const int32_t* __restrict__ offsets, int B, int F, int T, int6
             s_hist[s] = 0;
         }
         __syncthreads();
-        for (int base = q_lo; base < q_hi; base += NT) {
-            const int i = base + tid;
-            const uint32_t kk = i < q_hi ? keys[i + dl] - m.base_row : 0xFFFFFFFFu;
-            const uint32_t s = kk >> g.log_keys;
-            if (i >= q_hi || s >= (uint32_t)g.n) continue;
-            const int at_local = atomicAdd(&s_hist[s], 1);
-            const int t = upper_bound_i32(s_po, tl.nb + 1, i) - 1;
-            const int64_t at = (int64_t)s_place[s] + at_local;
-            // the record: key inside the slice, the gradient's scale (bag length for mean pooling, 1 for sum;
-            // 0 = too long for its bits, to be looked up) above it, and the place of the bag's gradient chunk
-            uint32_t len = 1u;
-            if (m.pool == PK_MEAN) {
-                const uint32_t L = (uint32_t)max(s_po[t + 1] - s_po[t], 1);
-                len = (L >> (32 - log_max)) ? 0u : L;
+        // Every wavefront takes a contiguous quarter of the tile's positions, 64 at a time, so that a lane's
+        // positions rise by 64 from one to the next: where bags are not short, the bag of a position is found
+        // by stepping on from the bag of the lane's previous one (one search at the start).
+        const int lane = tid & 63;
+        const int per_wave = ((q_hi - q_lo + NT - 1) / NT) * 64;
+        const int w_lo = q_lo + (tid >> 6) * per_wave, w_hi = min(w_lo + per_wave, q_hi);
+        const bool stepped = (int64_t)tl.nb * 64 <= (int64_t)6 * (q_hi - q_lo);     // (short bags: a search per position is shorter)
+        int t = stepped && w_lo + lane < w_hi ? upper_bound_i32(s_po, tl.nb + 1, w_lo + lane) - 1 : 0;
+        for (int base = w_lo; base < w_hi; base += 4 * 64) {
+            uint32_t kv[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int i = base + u * 64 + lane;
+                kv[u] = i < w_hi ? keys[i + dl] - m.base_row : 0xFFFFFFFFu;
             }
-            if ((uint64_t)at < (uint64_t)nnz)
-                rec[at] = make_uint2((kk - (s << g.log_keys)) | (len << log_max),
-                                     (uint32_t)((int64_t)(tl.b0 + t) * out_dim + m.col));
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int i = base + u * 64 + lane;
+                const uint32_t kk = kv[u];
+                const uint32_t s = kk >> g.log_keys;
+                if (i >= w_hi) continue;
+                if (s >= (uint32_t)g.n && !stepped) continue;
+                if (stepped) { while (t + 1 < tl.nb && s_po[t + 1] <= i) ++t; }
+                else t = upper_bound_i32(s_po, tl.nb + 1, i) - 1;
+                if (s >= (uint32_t)g.n) continue;
+                const int at_local = atomicAdd(&s_hist[s], 1);
+                const int64_t at = (int64_t)s_place[s] + at_local;
+                // the record: key inside the slice, the gradient's scale (bag length for mean pooling, 1 for sum;
+                // 0 = too long for its bits, to be looked up) above it, and the place of the bag's gradient chunk
+                uint32_t len = 1u;
+                if (m.pool == PK_MEAN) {
+                    const uint32_t L = (uint32_t)max(s_po[t + 1] - s_po[t], 1);
+                    len = (L >> (32 - log_max)) ? 0u : L;
+                }
+                if ((uint64_t)at < (uint64_t)nnz)
+                    rec[at] = make_uint2((kk - (s << g.log_keys)) | (len << log_max),
+                                         (uint32_t)((int64_t)(tl.b0 + t) * out_dim + m.col));
+            }
         }
     }
 }

@@ -217,11 +217,11 @@ static pk_status forward_impl(const pk_plan* plan, DeviceState* ds_given, int st
     // Pooling needs the keys only.  Large batches: it runs on side streams beside the rest of
     // the dedup chain.  Interleaving groups (Sec. III-C, K-Interleaving): pack p belongs to group
     // p mod G; a group's packed operations follow one another on the group's stream, the groups
-    // run side by side.  G = 0 lets the size decide (up to 4 groups for large batches, none for small).
+    // run side by side.  G = 0 lets the size decide (2 groups for large batches: a process has 4 hardware queues and the dedup chain uses two; none for small).
     const int G = plan->opts.interleave_groups;
     const bool overlap = ds->overlap && !ds->prof_on && !L.small &&
                          (G >= 2 || (G == 0 && (P > 1 || nnz >= (1 << 20)) && nnz >= (1 << 18)));
-    const int n_side = overlap && do_pool ? std::min<int>(P, G >= 2 ? G : 4) : 0;
+    const int n_side = overlap && do_pool ? std::min<int>(P, G >= 2 ? G : 2) : 0;
     if (n_side) { rc = fork_streams(ds, stream, n_side); if (rc != PK_OK) return rc; }
     for (int p = 0; p < P && do_pool; ++p) {
         const Pack& k = plan->packs[p];
@@ -409,7 +409,7 @@ static pk_status backward_impl(const pk_plan* plan, void* const* W, float* const
     // packs touch disjoint tables: one side stream each
     const int G = plan->opts.interleave_groups;
     const bool overlap = ds->overlap && !ds->prof_on && P > 1 && G != 1;
-    const int n_side = overlap ? std::min<int>(P, G >= 2 ? G : 4) : 0;
+    const int n_side = overlap ? std::min<int>(P, G >= 2 ? G : 2) : 0;
     if (n_side) { rc = fork_streams(ds, stream, n_side); if (rc != PK_OK) return rc; }
     for (int p = 0; p < P; ++p) {
         const Pack& k = plan->packs[p];
