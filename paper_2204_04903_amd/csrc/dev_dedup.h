@@ -134,11 +134,41 @@ __device__ __forceinline__ int find_bag(const int32_t* __restrict__ offs, int B,
     return min(max(lo - 1, 0), B - 1);
 }
 
+// Large batches, first launch: the per-slice counters are zeroed by all blocks; block 0 clears the
+// pack states and makes what every later kernel reads instead of deriving it again: the field scan
+// (with its verdict), the cut of every table for this batch, and the packs' sizes.
 __global__ void __launch_bounds__(NT)
-pk_clear_kernel(uint4* p, int64_t n4)
+pk_setup_kernel(uint4* zero, int64_t n4, const int32_t* __restrict__ offsets, int B, int F, int P, int T, int64_t nnz,
+                int target, int log_max, const FieldMeta* __restrict__ fmeta, const PackMeta* __restrict__ pm,
+                const TableMeta* __restrict__ tmeta, const int32_t* __restrict__ slot_field, PackState* st,
+                int32_t* __restrict__ packed_offsets, int32_t* __restrict__ seg_all, TableCut* __restrict__ cut,
+                int n_slices_max, int32_t* __restrict__ fscan)
 {
+    extern __shared__ int32_t s_dyn[];                     // block 0: field scan | first slices, slice sizes
     const uint4 z = make_uint4(0, 0, 0, 0);
-    for (int64_t i = (int64_t)blockIdx.x * NT + threadIdx.x; i < n4; i += (int64_t)gridDim.x * NT) p[i] = z;
+    for (int64_t i = (int64_t)blockIdx.x * NT + threadIdx.x; i < n4; i += (int64_t)gridDim.x * NT) zero[i] = z;
+    if (blockIdx.x != 0) return;
+    int32_t* s_fb = s_dyn;
+    int32_t* s_delta = s_fb + (F + 1);
+    int32_t* s_slotpos = s_delta + F;
+    int32_t* s_first = s_slotpos + (F + 1);
+    int32_t* s_lg = s_first + (T + 1);
+    const int tid = threadIdx.x;
+    int bad = field_scan<NT>(offsets, B, F, nnz, slot_field, s_fb, s_delta, s_slotpos);
+    table_cut<NT>(tmeta, fmeta, T, F, s_fb, target, log_max, s_first, s_lg, cut);
+    bad |= s_first[T] > n_slices_max;                      // cannot be for offsets that pass the scan: the slices' arrays are that long
+    for (int i = tid; i < 3 * F + 2; i += NT) fscan[i] = s_fb[i];
+    if (tid == 0) fscan[3 * F + 2] = bad;
+    for (int p = tid; p < P; p += NT) {
+        const PackMeta k = pm[p];
+        const int start = s_slotpos[k.first_slot];
+        const int n = s_slotpos[k.first_slot + k.n_fields] - start;
+        PackState ps{};
+        ps.nnz = n; ps.start = start; ps.first_slice = s_first[k.first_stable]; ps.error = bad ? 1 : 0;
+        st[p] = ps;
+        if (k.n_stables == 0) seg_all[start + p] = 0;      // no table that a field reads: no slice writes the end of its segments
+        packed_offsets[(int64_t)k.first_slot * B + p + (int64_t)k.n_fields * B] = n;
+    }
 }
 
 // ---------------------------------------------------------------------------
@@ -161,42 +191,19 @@ struct TileOf {
 
 template <int BT>
 __global__ void __launch_bounds__(NT)
-pk_keys_kernel(const int64_t* __restrict__ ids, const int32_t* __restrict__ offsets, int B, int F, int P, int T,
-               int64_t nnz, int target, int log_max, const FieldMeta* __restrict__ fmeta,
-               const PackMeta* __restrict__ pm, const TableMeta* __restrict__ tmeta,
-               const int32_t* __restrict__ slot_field, PackState* st,
+pk_keys_kernel(const int64_t* __restrict__ ids, const int32_t* __restrict__ offsets, int B, int F,
+               const FieldMeta* __restrict__ fmeta, const PackMeta* __restrict__ pm, PackState* st,
                uint32_t* __restrict__ keys, int32_t* __restrict__ packed_offsets, int32_t* slice_total,
-               int32_t* __restrict__ seg_all, TableCut* __restrict__ cut, int n_slices_max, int32_t* __restrict__ fscan)
+               const TableCut* __restrict__ cut, const int32_t* __restrict__ fscan)
 {
-    extern __shared__ int32_t s_dyn[];                     // field scan | first slices, slice sizes | the tile's counts
+    extern __shared__ int32_t s_hist[];                    // the tile's counts per slice of its table
     __shared__ int32_t s_po[BT + 1];
     __shared__ int s_flag;
-    int32_t* s_fb = s_dyn;
-    int32_t* s_delta = s_fb + (F + 1);
-    int32_t* s_slotpos = s_delta + F;
-    int32_t* s_first = s_slotpos + (F + 1);
-    int32_t* s_lg = s_first + (T + 1);
-    int32_t* s_hist = s_lg + T;
     const int tid = threadIdx.x;
-    int bad = field_scan<NT>(offsets, B, F, nnz, slot_field, s_fb, s_delta, s_slotpos);
-    table_cut<NT>(tmeta, fmeta, T, F, s_fb, target, log_max, s_first, s_lg, blockIdx.x == 0 ? cut : nullptr);
-    bad |= s_first[T] > n_slices_max;                      // cannot be for offsets that pass the scan: the slices' arrays are that long
-    if (blockIdx.x == 0) {
-        for (int i = tid; i < 3 * F + 2; i += NT) fscan[i] = s_fb[i];     // the kernels after this one read it from here
-        if (tid == 0) fscan[3 * F + 2] = bad;
-        for (int p = tid; p < P; p += NT) {
-            const PackMeta k = pm[p];
-            const int start = s_slotpos[k.first_slot];
-            const int n = s_slotpos[k.first_slot + k.n_fields] - start;
-            st[p].nnz = n;
-            st[p].start = start;
-            st[p].first_slice = s_first[k.first_stable];
-            if (bad) atomicOr(&st[p].error, 1);            // the clearing kernel zeroed the word
-            if (k.n_stables == 0) seg_all[start + p] = 0;  // no table that a field reads: no slice writes the end of its segments
-            packed_offsets[(int64_t)k.first_slot * B + p + (int64_t)k.n_fields * B] = n;
-        }
-    }
-    if (bad) return;
+    if (fscan[3 * F + 2]) return;                          // the field boundaries are unusable: the packs' error words say so
+    const int32_t* fb = fscan;                             // where every field's occurrences begin
+    const int32_t* delta = fscan + (F + 1);                // packed position minus position in ids, per field
+    const int32_t* slotpos = delta + F;                    // packed position of each (pack, slot)
     const int tpf = (B + BT - 1) / BT;
     const int64_t n_tiles = (int64_t)F * tpf;
     for (int64_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
@@ -204,9 +211,13 @@ pk_keys_kernel(const int64_t* __restrict__ ids, const int32_t* __restrict__ offs
         const int f = tl.f;
         const FieldMeta m = fmeta[f];
         const PackMeta k = pm[m.pack];
+        const TableCut tc = cut[m.stable];
+        const int f_lo = fb[f], f_hi = fb[f + 1];
+        const int dl = delta[f];
+        const int pbase = slotpos[k.first_slot];
         SliceGeom g;
-        g.log_keys = s_lg[m.stable];
-        g.n = s_first[m.stable + 1] - s_first[m.stable];
+        g.log_keys = tc.log_keys;
+        g.n = tc.n;
         const int64_t g0 = (int64_t)f * B + tl.b0;
         __syncthreads();                                   // the previous tile's LDS is consumed
         for (int t = tid; t <= tl.nb; t += NT) s_po[t] = offsets[g0 + t];
@@ -214,14 +225,12 @@ pk_keys_kernel(const int64_t* __restrict__ ids, const int32_t* __restrict__ offs
         if (tid == 0) s_flag = 0;
         __syncthreads();
         for (int t = tid; t < tl.nb; t += NT)
-            if (s_po[t] > s_po[t + 1] || s_po[t] < s_fb[f] || s_po[t + 1] > s_fb[f + 1]) s_flag = 1;
+            if (s_po[t] > s_po[t + 1] || s_po[t] < f_lo || s_po[t + 1] > f_hi) s_flag = 1;
         __syncthreads();
         if (s_flag) {
             if (tid == 0) atomicOr(&st[m.pack].error, 1);
             continue;
         }
-        const int dl = s_delta[f];
-        const int pbase = s_slotpos[k.first_slot];
         for (int t = tid; t < tl.nb; t += NT)
             packed_offsets[(int64_t)k.first_slot * B + m.pack + (int64_t)m.slot * B + tl.b0 + t] = s_po[t] + dl - pbase;
         const int q_lo = s_po[0], q_hi = s_po[tl.nb];
@@ -242,7 +251,7 @@ pk_keys_kernel(const int64_t* __restrict__ ids, const int32_t* __restrict__ offs
             }
         }
         __syncthreads();
-        const int slice0 = s_first[m.stable];
+        const int slice0 = tc.first;
         for (int s = tid; s < g.n; s += NT) {
             const int c = s_hist[s];
             if (c) atomicAdd(&slice_total[slice0 + s], c);
@@ -300,25 +309,18 @@ pk_slice_scan_kernel(const TableCut* __restrict__ cut, int T,
 // touched slice with one global add, and then places its records from block-local cursors.
 template <int BT>
 __global__ void __launch_bounds__(NT)
-pk_scatter_kernel(const int32_t* __restrict__ offsets, int B, int F, int T, int64_t nnz, int log_max,
-                  const FieldMeta* __restrict__ fmeta, const PackMeta* __restrict__ pm,
-                  const TableCut* __restrict__ cut, const int32_t* __restrict__ slot_field,
+pk_scatter_kernel(const int32_t* __restrict__ offsets, int B, int F, int64_t nnz, int log_max,
+                  const FieldMeta* __restrict__ fmeta, const TableCut* __restrict__ cut,
                   const PackState* __restrict__ st, const uint32_t* __restrict__ keys, int32_t* slice_cursor,
                   uint2* __restrict__ rec, int hist_words, int64_t out_dim, const int32_t* __restrict__ fscan)
 {
-    extern __shared__ int32_t s_dyn[];                     // field scan | first slices | counts | places
+    extern __shared__ int32_t s_dyn[];                     // counts | places, per slice of the tile's table
     __shared__ int32_t s_po[BT + 1];
-    int32_t* s_fb = s_dyn;
-    int32_t* s_delta = s_fb + (F + 1);
-    int32_t* s_slotpos = s_delta + F;
-    int32_t* s_first = s_slotpos + (F + 1);
-    int32_t* s_lg = s_first + (T + 1);
-    int32_t* s_hist = s_lg + T;
+    int32_t* s_hist = s_dyn;
     int32_t* s_place = s_hist + hist_words;
     const int tid = threadIdx.x;
-    const int bad = field_scan_load<NT>(fscan, F, s_fb);
-    table_cut_load<NT>(cut, T, s_first, s_lg);
-    if (bad) return;
+    if (fscan[3 * F + 2]) return;
+    const int32_t* delta = fscan + (F + 1);
     const int tpf = (B + BT - 1) / BT;
     const int64_t n_tiles = (int64_t)F * tpf;
     for (int64_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
@@ -326,15 +328,16 @@ pk_scatter_kernel(const int32_t* __restrict__ offsets, int B, int F, int T, int6
         const int f = tl.f;
         const FieldMeta m = fmeta[f];
         if (st[m.pack].error) continue;                    // the keys kernel rejected offsets of this pack
+        const TableCut tc = cut[m.stable];
+        const int dl = delta[f];
         SliceGeom g;
-        g.log_keys = s_lg[m.stable];
-        g.n = s_first[m.stable + 1] - s_first[m.stable];
+        g.log_keys = tc.log_keys;
+        g.n = tc.n;
         const int64_t g0 = (int64_t)f * B + tl.b0;
         __syncthreads();
         for (int t = tid; t <= tl.nb; t += NT) s_po[t] = offsets[g0 + t];
         for (int s = tid; s < g.n; s += NT) s_hist[s] = 0;
         __syncthreads();
-        const int dl = s_delta[f];
         const int q_lo = s_po[0], q_hi = s_po[tl.nb];
         for (int base = q_lo; base < q_hi; base += 4 * NT) {      // four loads in flight
             uint32_t kv[4];
@@ -350,7 +353,7 @@ pk_scatter_kernel(const int32_t* __restrict__ offsets, int B, int F, int T, int6
             }
         }
         __syncthreads();
-        const int slice0 = s_first[m.stable];
+        const int slice0 = tc.first;
         for (int s = tid; s < g.n; s += NT) {
             const int c = s_hist[s];
             s_place[s] = c ? atomicAdd(&slice_cursor[slice0 + s], c) : 0;

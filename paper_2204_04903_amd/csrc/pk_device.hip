@@ -185,7 +185,8 @@ static pk_status forward_impl(const pk_plan* plan, DeviceState* ds_given, int st
     const int bt = avg_len >= 48 ? 32 : avg_len >= 32 ? 128 : avg_len >= 12 ? 512 : 1024;     // (a mix of short and very long bags counts as long)
     const int64_t n_tiles = (int64_t)F * ((B + bt - 1) / bt);
     const size_t scan_words = field_scan_words(F) + 2 * (size_t)T + 1;
-    if (do_dedup && !L.small && (scan_words + 2 * (size_t)L.max_table_slices) * 4 > 64 * 1024)
+    if (do_dedup && !L.small &&
+        std::max({scan_words, 2 * (size_t)L.max_table_slices, field_scan_words(F) + 4 * (size_t)F}) * 4 > 64 * 1024)
         return fail(PK_EOVERFLOW, std::string(who) + ": fields, tables and slices per table together exceed what the "
                                   "dedup kernels stage in LDS");
     if (do_dedup && !L.small) {
@@ -196,15 +197,19 @@ static pk_status forward_impl(const pk_plan* plan, DeviceState* ds_given, int st
         sa.bitmap = ws.at<uint32_t>(L.bitmap);
         int32_t* slice_total = ws.at<int32_t>(L.slice_total);
         int32_t* slice_cursor = ws.at<int32_t>(L.slice_cursor);
-        const int64_t n_clear4 = (int64_t)(L.clear_bytes / 16);
-        PK_LAUNCH("pk_clear", pk_clear_kernel, dim3(blocks_for(n_clear4, NT, 256)), dim3(NT), 0,
-                  ws.at<uint4>(L.clear_begin), n_clear4);
+        // block 0 of the first launch clears the pack states itself (it then fills them); the others zero the rest
+        const size_t state_bytes = L.slice_total - L.clear_begin;
+        const int64_t n_clear4 = (int64_t)((L.clear_bytes - state_bytes) / 16);
+        const size_t setup_lds = scan_words * 4;
+        PK_LAUNCH("pk_setup", pk_setup_kernel, dim3(blocks_for(n_clear4, NT, 256)), dim3(NT), setup_lds,
+                  ws.at<uint4>(L.slice_total), n_clear4, offsets, B, F, P, T, nnz, sa.target, sa.log_max, ds->fmeta, ds->pmeta,
+                  ds->sort_tables, ds->slot_field, st, packed_offsets, seg, ws.at<TableCut>(L.tgeom), L.n_slices,
+                  ws.at<int32_t>(L.fscan));
         const dim3 key_grid(blocks_for(n_tiles, 1, 256 * 8));
-        const size_t keys_lds = (scan_words + (size_t)L.max_table_slices) * 4;
+        const size_t keys_lds = (size_t)L.max_table_slices * 4;
 #define PK_KEYS_LAUNCH(BT)                                                                                      \
-    PK_LAUNCH("pk_keys", pk_keys_kernel<BT>, key_grid, dim3(NT), keys_lds, ids, offsets, B, F, P, T, nnz, sa.target, \
-              sa.log_max, ds->fmeta, ds->pmeta, ds->sort_tables, ds->slot_field, st, keys, packed_offsets, slice_total, seg, \
-              ws.at<TableCut>(L.tgeom), L.n_slices, ws.at<int32_t>(L.fscan))
+    PK_LAUNCH("pk_keys", pk_keys_kernel<BT>, key_grid, dim3(NT), keys_lds, ids, offsets, B, F, ds->fmeta, ds->pmeta, st,  \
+              keys, packed_offsets, slice_total, ws.at<TableCut>(L.tgeom), ws.at<int32_t>(L.fscan))
         switch (bt) {
             case 32: PK_KEYS_LAUNCH(32); break;
             case 128: PK_KEYS_LAUNCH(128); break;
@@ -242,12 +247,12 @@ static pk_status forward_impl(const pk_plan* plan, DeviceState* ds_given, int st
                   dim3(kScanThreads), (size_t)(T + 1) * 4,
                   ws.at<TableCut>(L.tgeom), T, slice_total, slice_cursor, ws.at<SliceInfo>(L.slice_info),
                   L.n_slices, L.log_max == kSliceLogFine ? kBigSliceCount : 0x7FFFFFFF, big_list + kBigSlicesMax, big_list);
-        const size_t sc_lds = (scan_words + 2 * (size_t)L.max_table_slices) * 4;
+        const size_t sc_lds = 2 * (size_t)L.max_table_slices * 4;
         const dim3 tile_grid(blocks_for(n_tiles, 1, 256 * 8));
 #define PK_SCATTER_LAUNCH(BT)                                                                                   \
-    PK_LAUNCH("pk_scatter", pk_scatter_kernel<BT>, tile_grid, dim3(NT), sc_lds, offsets, B, F, T, nnz,              \
-              sa.log_max, ds->fmeta, ds->pmeta, ws.at<TableCut>(L.tgeom), ds->slot_field, st, keys, slice_cursor,   \
-              ws.at<uint2>(L.rec), L.max_table_slices, plan->out_dim, ws.at<int32_t>(L.fscan))
+    PK_LAUNCH("pk_scatter", pk_scatter_kernel<BT>, tile_grid, dim3(NT), sc_lds, offsets, B, F, nnz, sa.log_max, ds->fmeta,  \
+              ws.at<TableCut>(L.tgeom), st, keys, slice_cursor, ws.at<uint2>(L.rec), L.max_table_slices, plan->out_dim,     \
+              ws.at<int32_t>(L.fscan))
         switch (bt) {
             case 32: PK_SCATTER_LAUNCH(32); break;
             case 128: PK_SCATTER_LAUNCH(128); break;
