@@ -302,7 +302,7 @@ def test_bad_offsets_raise_the_error_word_and_terminate(tables, fields):
 
 
 # --------------------------------------------------------------------------- the five configurations
-def run_config(idx, steps=2, **shrink):
+def run_config(idx, steps=2, plan_opts=None, **shrink):
     """Lazily materialised tables: device fill by the generator's kernel, the
     oracle on the generator's host values for the distinct rows only."""
     from paper_2204_04903_amd.layer import PackedEmbedding
@@ -310,7 +310,7 @@ def run_config(idx, steps=2, **shrink):
     say(f"[config {idx}] {wl.description}; B={wl.batch} fields={wl.n_fields} shrink={shrink}")
     so = SparseOracle(orc, synth, wl)
     pl = so.pl
-    layer = PackedEmbedding(so.tables, so.fields)
+    layer = PackedEmbedding(so.tables, so.fields, **(plan_opts or {}))
     try:
         stream = torch.cuda.current_stream().cuda_stream
         for t, ts in enumerate(wl.tables):
@@ -378,6 +378,14 @@ def test_config5_shrunk_long_sequences_bf16():
 
 
 @pytest.mark.timeout(600)
+def test_tables_above_the_fine_slice_limit():
+    """Two tables of 140 M rows: the large-batch dedup then cuts slices of 2^17 keys (the wide slice kernels)."""
+    free, _ = torch.cuda.mem_get_info()
+    if free < 90 * 2**30:
+        pytest.skip("needs 90 GiB of free device memory")
+    run_config(2, n_fields=2, row_scale=140.0, plan_opts=dict(debug=2))
+
+
 def test_config2_full_size():
     run_config(2)
 
