@@ -270,7 +270,7 @@ static pk_status forward_impl(const pk_plan* plan, DeviceState* ds_given, int st
             const dim3 sgrid((unsigned)L.n_slices);
             const bool fine = L.log_max == kSliceLogFine;
             // the listed slices run beside the others, on a stream of their own (not while kernels are timed one by one)
-            const bool beside = fine && ds->overlap && !ds->prof_on;
+            const bool beside = fine && ds->overlap && !ds->prof_on && do_pool;   // (a dedup on its own is itself running beside other work: a process has four hardware queues)
             hipStream_t main_stream = stream;
             if (beside) { rc = fork_streams(ds, main_stream, 1, DeviceState::kSide - 1); if (rc != PK_OK) return rc; }
             if (fine) {
