@@ -265,31 +265,47 @@ def test_hot_key_with_integer_gradients_is_exact():
         layer.close()
 
 
+@pytest.mark.parametrize("debug", [0, 2])                   # the one-launch forward pass, and the large-batch kernels
+@pytest.mark.parametrize("kind", ["field boundary", "decreasing inside a field", "past the field's end"])
 @pytest.mark.parametrize("tables,fields", [
     ([(11, 8, 0)], [(0, 0), (0, 0)]),                      # one pack
-    ([(11, 8, 0), (7, 16, 0)], [(0, 0), (1, 1)]),          # two packs: the error word lives in the first one's state
+    ([(11, 8, 0), (7, 16, 0)], [(0, 0), (1, 1)]),          # two packs
 ])
-def test_bad_offsets_raise_the_error_word_and_terminate(tables, fields):
+def test_bad_offsets_raise_the_error_word_and_terminate(tables, fields, kind, debug):
     from paper_2204_04903_amd.layer import PackedEmbedding
     pr = small_problem(95, B=8, tables=tables, fields=fields, max_len=3, allow_empty=False)
-    layer = PackedEmbedding(tables, fields)
+    layer = PackedEmbedding(tables, fields, debug=debug)
     try:
         for t in range(len(tables)):
             layer.load_table(t, pr["Wt"][t])
         bad = pr["offsets"].copy()
-        bad[8] = bad[16] + 3          # the boundary between the two fields runs past the end
+        if kind == "field boundary":
+            bad[8] = bad[16] + 3      # the boundary between the two fields runs past the end
+        elif kind == "decreasing inside a field":
+            bad[3] = bad[5] + 1       # bag 3 of field 0 would begin after bag 4 does
+        else:
+            bad[5] = bad[8] + 2       # bag 5 of field 0 would begin among the second field's IDs
         out = layer.forward(torch.from_numpy(pr["ids"]).cuda(), torch.from_numpy(bad).cuda(), 8)
         torch.cuda.synchronize()
         assert layer.error_word() & 1
         assert np.isfinite(out.cpu().numpy()).all()       # undefined values, but every read stayed inside the inputs
-        # a backward pass after a rejected forward pass leaves the table and the accumulator alone
+        # A backward pass after a rejected forward pass leaves the tables and accumulators of the packs whose
+        # offsets were rejected alone: every pack for a wrong field boundary, the pack of field 0 for a
+        # wrong offset inside that field (the other pack's offsets passed: it is updated).
         say("[bad offsets] backward after the rejected forward")
         layer.backward_update(torch.from_numpy(pr["grad"]).cuda(), 0.05, 1e-8)
         torch.cuda.synchronize()
         W0 = stack_tables(orc.plan(tables, fields), [w.copy() for w in pr["Wt"]])
-        for p in range(layer.n_packs):
+        rejected = range(layer.n_packs) if kind == "field boundary" else [layer.table_slot[fields[0][0]][0]]
+        for p in rejected:
             assert np.array_equal(bits_of(layer.W[p]), W0[p])
             assert (layer.A[p] == 0).all()
+        for p in range(layer.n_packs):
+            assert torch.isfinite(layer.A[p]).all()
+        for t in range(len(tables)):                       # start the check below from the same tables again
+            layer.load_table(t, pr["Wt"][t])
+        for p in range(layer.n_packs):
+            layer.A[p].zero_()
         # and the same workspace works again afterwards
         out = layer.forward(torch.from_numpy(pr["ids"]).cuda(), torch.from_numpy(pr["offsets"]).cuda(), 8)
         torch.cuda.synchronize()
