@@ -108,7 +108,9 @@ __device__ __forceinline__ void row_step(WT* wrow, float* arow, int D, int li,
             for (int v = 0; v < VEC; ++v) {
                 const float g = (float)acc[c][v];
                 a[c][v] = a[c][v] + g * g;
-                w[c][v] = w[c][v] - lr * g / (sqrtf(a[c][v]) + eps);
+                // square root and reciprocal as the hardware gives them (1 ulp each): the step is within
+                // 3 ulp of lr*g/(sqrt(a)+eps), and it is at most lr in size
+                w[c][v] = w[c][v] - lr * g * __builtin_amdgcn_rcpf(__builtin_amdgcn_sqrtf(a[c][v]) + eps);
             }
             store_f32<VEC>(arow + d0, a[c]);
             Row<WT, VEC>::store(wrow + d0, w[c]);
@@ -338,7 +340,7 @@ pk_adagrad_hot_kernel(HotPacks ptrs, int p0, const PackMeta* __restrict__ pm, co
                 const float g = (float)gh[(size_t)t * D + d];
                 const float a = arow[d] + g * g;
                 arow[d] = a;
-                wrow[d] = wrow[d] - lr * g / (sqrtf(a) + eps);
+                wrow[d] = wrow[d] - lr * g * __builtin_amdgcn_rcpf(__builtin_amdgcn_sqrtf(a) + eps);
             }
         } else {
             uint16_t* wrow;
@@ -348,7 +350,7 @@ pk_adagrad_hot_kernel(HotPacks ptrs, int p0, const PackMeta* __restrict__ pm, co
                 const float g = (float)gh[(size_t)t * D + d];
                 const float a = arow[d] + g * g;
                 arow[d] = a;
-                wrow[d] = (uint16_t)f32_to_bf16(bf16_to_f32(wrow[d]) - lr * g / (sqrtf(a) + eps));
+                wrow[d] = (uint16_t)f32_to_bf16(bf16_to_f32(wrow[d]) - lr * g * __builtin_amdgcn_rcpf(__builtin_amdgcn_sqrtf(a) + eps));
             }
         }
     }

@@ -196,7 +196,6 @@ static pk_status forward_impl(const pk_plan* plan, DeviceState* ds_given, int st
         sa.cut = ws.at<TableCut>(L.tgeom);
         sa.bitmap = ws.at<uint32_t>(L.bitmap);
         int32_t* slice_total = ws.at<int32_t>(L.slice_total);
-        int32_t* slice_cursor = ws.at<int32_t>(L.slice_cursor);
         // block 0 of the first launch clears the pack states itself (it then fills them); the others zero the rest
         const size_t state_bytes = L.slice_total - L.clear_begin;
         const int64_t n_clear4 = (int64_t)((L.clear_bytes - state_bytes) / 16);
