@@ -92,14 +92,15 @@ struct HotView {
     float* A_hot;
 };
 
+// (rows and dimensions are unsigned 32-bit numbers: the products below are one 32 x 32 -> 64 bit multiply each)
 template <typename WT, bool HYB>
 __device__ __forceinline__ WT* row_of(WT* cold, const HotView& hv, uint32_t row, int D)
 {
     if constexpr (HYB) {
         const int s = hv.slot_of[row];
-        if (s >= 0) return static_cast<WT*>(hv.W_hot) + (size_t)s * D;
+        if (s >= 0) return static_cast<WT*>(hv.W_hot) + (size_t)((uint64_t)(uint32_t)s * (uint32_t)D);
     }
-    return cold + (size_t)row * D;
+    return cold + (size_t)((uint64_t)row * (uint32_t)D);
 }
 
 // the row's weights and its accumulator
@@ -109,11 +110,11 @@ __device__ __forceinline__ void rows_of(WT* W, float* A, const HotView& hv, uint
     if (hv.slot_of) {
         const int s = hv.slot_of[row];
         if (s >= 0) {
-            *wrow = static_cast<WT*>(hv.W_hot) + (size_t)s * D;
-            *arow = hv.A_hot + (size_t)s * D;
+            *wrow = static_cast<WT*>(hv.W_hot) + (size_t)((uint64_t)(uint32_t)s * (uint32_t)D);
+            *arow = hv.A_hot + (size_t)((uint64_t)(uint32_t)s * (uint32_t)D);
             return;
         }
     }
-    *wrow = W + (size_t)row * D;
-    *arow = A + (size_t)row * D;
+    *wrow = W + (size_t)((uint64_t)row * (uint32_t)D);
+    *arow = A + (size_t)((uint64_t)row * (uint32_t)D);
 }
