@@ -98,16 +98,26 @@ __device__ __forceinline__ void pool_body(const WT* __restrict__ W, const PoolSr
                 }
             }
         }
-        for (; q < q1; ++q) {
-            const WT* r0 = row_of<const WT, HYB>(W, hv, key_at(q), D);
+        // What is left of the bag (up to three rows) in one round: the rows that are there are asked for
+        // together, the others count as zeros.  (One row after the other is a wait per row.)
+        if (q < q1) {
+            const int rem = q1 - q;
+            const WT* r[3];
+#pragma unroll
+            for (int k = 0; k < 3; ++k) r[k] = row_of<const WT, HYB>(W, hv, k < rem ? key_at(q + k) : key_at(q), D);
 #pragma unroll
             for (int c = 0; c < NCH; ++c) {
                 const int d0 = (c * LPR + li) * VEC;
                 if (d0 < D) {
-                    float x0[VEC];
-                    Row<WT, VEC>::load(r0 + d0, x0);
+                    float x[3][VEC];
 #pragma unroll
-                    for (int v = 0; v < VEC; ++v) acc[c][v] += x0[v];
+                    for (int k = 0; k < 3; ++k) {
+#pragma unroll
+                        for (int v = 0; v < VEC; ++v) x[k][v] = 0.f;
+                        if (k < rem) Row<WT, VEC>::load(r[k] + d0, x[k]);
+                    }
+#pragma unroll
+                    for (int v = 0; v < VEC; ++v) acc[c][v] += (x[0][v] + x[1][v]) + x[2][v];
                 }
             }
         }
