@@ -1029,10 +1029,10 @@ pk_inverse_kernel(int F, const int32_t* __restrict__ fscan, const SlotMeta* __re
 // rows of a packed table dealt to n workers by row mod n, the distinct keys of a pack are regrouped by
 // owner -- owner 0 first, ascending inside an owner -- with the place of every key in `unique` beside it
 // (what Stitch needs for the rows that come back) and the offsets of the owners' groups.  A counting
-// sort in three small launches: counts per chunk of 2048 keys and owner, a scan in owner-major order,
+// sort in three small launches: counts per chunk of 512 keys and owner, a scan in owner-major order,
 // and the placing pass (a wavefront per chunk, so that the order inside an owner is the key order).
 // ---------------------------------------------------------------------------
-constexpr int kPartChunk = 2048;
+constexpr int kPartChunk = 512;
 constexpr int kPartOwnersMax = 64;
 
 __global__ void __launch_bounds__(NT)
