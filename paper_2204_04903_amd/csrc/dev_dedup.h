@@ -194,7 +194,8 @@ __global__ void __launch_bounds__(NT)
 pk_keys_kernel(const int64_t* __restrict__ ids, const int32_t* __restrict__ offsets, int B, int F,
                const FieldMeta* __restrict__ fmeta, const PackMeta* __restrict__ pm, PackState* st,
                uint32_t* __restrict__ keys, int32_t* __restrict__ packed_offsets, int32_t* slice_total,
-               const TableCut* __restrict__ cut, const int32_t* __restrict__ fscan)
+               const TableCut* __restrict__ cut, const int32_t* __restrict__ fscan, int32_t* __restrict__ tile_hist,
+               int tile_hist_stride)
 {
     extern __shared__ int32_t s_hist[];                    // the tile's counts per slice of its table
     __shared__ int32_t s_po[BT + 1];
@@ -255,6 +256,7 @@ pk_keys_kernel(const int64_t* __restrict__ ids, const int32_t* __restrict__ offs
         for (int s = tid; s < g.n; s += NT) {
             const int c = s_hist[s];
             if (c) atomicAdd(&slice_total[slice0 + s], c);
+            if (tile_hist) tile_hist[tile * tile_hist_stride + s] = c;     // the scatter kernel takes its counts from here
         }
     }
 }
@@ -312,7 +314,8 @@ __global__ void __launch_bounds__(NT)
 pk_scatter_kernel(const int32_t* __restrict__ offsets, int B, int F, int64_t nnz, int log_max,
                   const FieldMeta* __restrict__ fmeta, const TableCut* __restrict__ cut,
                   const PackState* __restrict__ st, const uint32_t* __restrict__ keys, int32_t* slice_cursor,
-                  uint2* __restrict__ rec, int hist_words, int64_t out_dim, const int32_t* __restrict__ fscan)
+                  uint2* __restrict__ rec, int hist_words, int64_t out_dim, const int32_t* __restrict__ fscan,
+                  const int32_t* __restrict__ tile_hist, int tile_hist_stride)
 {
     extern __shared__ int32_t s_dyn[];                     // counts | places, per slice of the tile's table
     __shared__ int32_t s_po[BT + 1];
@@ -336,9 +339,16 @@ pk_scatter_kernel(const int32_t* __restrict__ offsets, int B, int F, int64_t nnz
         const int64_t g0 = (int64_t)f * B + tl.b0;
         __syncthreads();
         for (int t = tid; t <= tl.nb; t += NT) s_po[t] = offsets[g0 + t];
-        for (int s = tid; s < g.n; s += NT) s_hist[s] = 0;
+        for (int s = tid; s < g.n; s += NT) s_hist[s] = tile_hist ? tile_hist[tile * tile_hist_stride + s] : 0;
         __syncthreads();
         const int q_lo = s_po[0], q_hi = s_po[tl.nb];
+        if (tile_hist) {
+            // one word of every 128 bytes of the tile's keys, so that the placing pass finds them in the cache
+            uint32_t pf = 0;
+            for (int i = q_lo + tid * 32; i < q_hi; i += NT * 32) pf ^= keys[i + dl];
+            asm volatile("" ::"v"(pf));
+        }
+        if (!tile_hist)                                    // (the keys kernel's counts of this tile were not kept)
         for (int base = q_lo; base < q_hi; base += 4 * NT) {      // four loads in flight
             uint32_t kv[4];
 #pragma unroll
@@ -368,15 +378,16 @@ pk_scatter_kernel(const int32_t* __restrict__ offsets, int B, int F, int64_t nnz
         const int w_lo = q_lo + (tid >> 6) * per_wave, w_hi = min(w_lo + per_wave, q_hi);
         const bool stepped = (int64_t)tl.nb * 64 <= (int64_t)6 * (q_hi - q_lo);     // (short bags: a search per position is shorter)
         int t = stepped && w_lo + lane < w_hi ? upper_bound_i32(s_po, tl.nb + 1, w_lo + lane) - 1 : 0;
-        for (int base = w_lo; base < w_hi; base += 4 * 64) {
-            uint32_t kv[4];
+        constexpr int UP = 8;                              // key loads in flight (they come from memory: nothing has read them since they were written)
+        for (int base = w_lo; base < w_hi; base += UP * 64) {
+            uint32_t kv[UP];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
+            for (int u = 0; u < UP; ++u) {
                 const int i = base + u * 64 + lane;
                 kv[u] = i < w_hi ? keys[i + dl] - m.base_row : 0xFFFFFFFFu;
             }
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
+            for (int u = 0; u < UP; ++u) {
                 const int i = base + u * 64 + lane;
                 const uint32_t kk = kv[u];
                 const uint32_t s = kk >> g.log_keys;

@@ -181,8 +181,7 @@ static pk_status forward_impl(const pk_plan* plan, DeviceState* ds_given, int st
 
     // ---- large batches: partition the occurrences by slice, then one block per slice ----
     // bags per tile of the keys and scatter kernels: about 16 K occurrences, 32 to 1024 bags
-    const int64_t avg_len = std::max<int64_t>(nnz / std::max<int64_t>(n_bags, 1), 1);
-    const int bt = avg_len >= 48 ? 32 : avg_len >= 32 ? 128 : avg_len >= 12 ? 512 : 1024;     // (a mix of short and very long bags counts as long)
+    const int bt = L.bags_per_tile;
     const int64_t n_tiles = (int64_t)F * ((B + bt - 1) / bt);
     const size_t scan_words = field_scan_words(F) + 2 * (size_t)T + 1;
     if (do_dedup && !L.small &&
@@ -208,7 +207,8 @@ static pk_status forward_impl(const pk_plan* plan, DeviceState* ds_given, int st
         const size_t keys_lds = (size_t)L.max_table_slices * 4;
 #define PK_KEYS_LAUNCH(BT)                                                                                      \
     PK_LAUNCH("pk_keys", pk_keys_kernel<BT>, key_grid, dim3(NT), keys_lds, ids, offsets, B, F, ds->fmeta, ds->pmeta, st,  \
-              keys, packed_offsets, slice_total, ws.at<TableCut>(L.tgeom), ws.at<int32_t>(L.fscan))
+              keys, packed_offsets, slice_total, ws.at<TableCut>(L.tgeom), ws.at<int32_t>(L.fscan),                    \
+              L.tile_hist_stride ? ws.at<int32_t>(L.tile_hist) : nullptr, L.tile_hist_stride)
         switch (bt) {
             case 32: PK_KEYS_LAUNCH(32); break;
             case 128: PK_KEYS_LAUNCH(128); break;
@@ -251,7 +251,7 @@ static pk_status forward_impl(const pk_plan* plan, DeviceState* ds_given, int st
 #define PK_SCATTER_LAUNCH(BT)                                                                                   \
     PK_LAUNCH("pk_scatter", pk_scatter_kernel<BT>, tile_grid, dim3(NT), sc_lds, offsets, B, F, nnz, sa.log_max, ds->fmeta,  \
               ws.at<TableCut>(L.tgeom), st, keys, slice_cursor, ws.at<uint2>(L.rec), L.max_table_slices, plan->out_dim,     \
-              ws.at<int32_t>(L.fscan))
+              ws.at<int32_t>(L.fscan), L.tile_hist_stride ? ws.at<int32_t>(L.tile_hist) : nullptr, L.tile_hist_stride)
         switch (bt) {
             case 32: PK_SCATTER_LAUNCH(32); break;
             case 128: PK_SCATTER_LAUNCH(128); break;

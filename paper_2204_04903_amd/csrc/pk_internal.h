@@ -183,7 +183,7 @@ struct Pack {
 // Byte offsets of the workspace's arrays for one (plan, B, nnz).
 struct Layout {
     size_t state, packed_offsets, keys, inverse, seg_ent, tile_hdr, unique, seg, ghot,
-           clear_begin, slice_total, slice_nu, big_list, slice_cursor, slice_usum, slice_info, tgeom, fscan, rec, bitmap, total;
+           clear_begin, slice_total, slice_nu, big_list, slice_cursor, slice_usum, slice_info, tgeom, fscan, tile_hist, rec, bitmap, total;
     size_t clear_bytes;          // what the partitioned path clears before its first kernel: per-pack state,
                                  // slice totals and distinct-key counts, contiguous from `clear_begin`
     int32_t n_slices;            // slices of all tables for this call
@@ -191,6 +191,8 @@ struct Layout {
     int32_t log_max;             // partitioned path: largest slice (log2 of its keys) of this call
     int32_t dmax;
     int32_t pos_tile;            // occurrences per backward tile for this nnz
+    int32_t bags_per_tile;       // bags per tile of the keys and scatter kernels
+    int32_t tile_hist_stride;    // entries per tile of the stored per-slice counts (0: not stored, the scatter kernel counts again)
     bool small;                  // the forward pass's dedup is one launch (every slice block scans its table's IDs)
 };
 

@@ -84,6 +84,16 @@ Layout make_layout(const pk_plan* plan, int32_t B, int64_t nnz)
     L.slice_info     = take(L.small ? 0 : (size_t)slices * sizeof(SliceInfo));
     L.tgeom          = take(L.small ? 0 : plan->sort_tables.size() * sizeof(TableCut));
     L.fscan          = take(L.small ? 0 : (3 * F + 3) * 4);          // the field scan of the batch, with its verdict
+    // bags per tile of the keys and scatter kernels: about 16 K occurrences, 32 to 1024 bags (a mix of short
+    // and very long bags counts as long)
+    const int64_t n_bags = (int64_t)F * B;
+    const int64_t avg_len = std::max<int64_t>(nnz / std::max<int64_t>(n_bags, 1), 1);
+    L.bags_per_tile  = avg_len >= 48 ? 32 : avg_len >= 32 ? 128 : avg_len >= 12 ? 512 : 1024;
+    // the keys kernel's counts per (tile, slice of the tile's table), so that the scatter kernel need not count
+    // again; only while that table stays small
+    const int64_t n_tiles = (int64_t)F * ((B + L.bags_per_tile - 1) / L.bags_per_tile);
+    L.tile_hist_stride = (!L.small && n_tiles * (int64_t)most <= ((int64_t)8 << 20)) ? most : 0;
+    L.tile_hist      = take((size_t)n_tiles * (size_t)L.tile_hist_stride * 4);
     L.packed_offsets = take((F * (size_t)B + P) * 4);
     L.keys           = take(n * 4);
     L.inverse        = take(n * 4);
