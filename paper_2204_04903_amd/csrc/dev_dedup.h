@@ -137,7 +137,8 @@ __device__ __forceinline__ int find_bag(const int32_t* __restrict__ offs, int B,
 // Large batches, first launch: the per-slice counters are zeroed by all blocks; block 0 clears the
 // pack states and makes what every later kernel reads instead of deriving it again: the field scan
 // (with its verdict), the cut of every table for this batch, and the packs' sizes.
-__global__ void __launch_bounds__(NT)
+constexpr int kSetupThreads = 1024;         // block 0's scans run over up to 4096 fields and tables
+__global__ void __launch_bounds__(kSetupThreads)
 pk_setup_kernel(uint4* zero, int64_t n4, const int32_t* __restrict__ offsets, int B, int F, int P, int T, int64_t nnz,
                 int target, int log_max, const FieldMeta* __restrict__ fmeta, const PackMeta* __restrict__ pm,
                 const TableMeta* __restrict__ tmeta, const int32_t* __restrict__ slot_field, PackState* st,
@@ -146,7 +147,7 @@ pk_setup_kernel(uint4* zero, int64_t n4, const int32_t* __restrict__ offsets, in
 {
     extern __shared__ int32_t s_dyn[];                     // block 0: field scan | first slices, slice sizes
     const uint4 z = make_uint4(0, 0, 0, 0);
-    for (int64_t i = (int64_t)blockIdx.x * NT + threadIdx.x; i < n4; i += (int64_t)gridDim.x * NT) zero[i] = z;
+    for (int64_t i = (int64_t)blockIdx.x * kSetupThreads + threadIdx.x; i < n4; i += (int64_t)gridDim.x * kSetupThreads) zero[i] = z;
     if (blockIdx.x != 0) return;
     int32_t* s_fb = s_dyn;
     int32_t* s_delta = s_fb + (F + 1);
@@ -154,12 +155,12 @@ pk_setup_kernel(uint4* zero, int64_t n4, const int32_t* __restrict__ offsets, in
     int32_t* s_first = s_slotpos + (F + 1);
     int32_t* s_lg = s_first + (T + 1);
     const int tid = threadIdx.x;
-    int bad = field_scan<NT>(offsets, B, F, nnz, slot_field, s_fb, s_delta, s_slotpos);
-    table_cut<NT>(tmeta, fmeta, T, F, s_fb, target, log_max, s_first, s_lg, cut);
+    int bad = field_scan<kSetupThreads>(offsets, B, F, nnz, slot_field, s_fb, s_delta, s_slotpos);
+    table_cut<kSetupThreads>(tmeta, fmeta, T, F, s_fb, target, log_max, s_first, s_lg, cut);
     bad |= s_first[T] > n_slices_max;                      // cannot be for offsets that pass the scan: the slices' arrays are that long
-    for (int i = tid; i < 3 * F + 2; i += NT) fscan[i] = s_fb[i];
+    for (int i = tid; i < 3 * F + 2; i += kSetupThreads) fscan[i] = s_fb[i];
     if (tid == 0) fscan[3 * F + 2] = bad;
-    for (int p = tid; p < P; p += NT) {
+    for (int p = tid; p < P; p += kSetupThreads) {
         const PackMeta k = pm[p];
         const int start = s_slotpos[k.first_slot];
         const int n = s_slotpos[k.first_slot + k.n_fields] - start;

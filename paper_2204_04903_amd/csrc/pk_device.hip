@@ -199,7 +199,7 @@ static pk_status forward_impl(const pk_plan* plan, DeviceState* ds_given, int st
         const size_t state_bytes = L.slice_total - L.clear_begin;
         const int64_t n_clear4 = (int64_t)((L.clear_bytes - state_bytes) / 16);
         const size_t setup_lds = scan_words * 4;
-        PK_LAUNCH("pk_setup", pk_setup_kernel, dim3(blocks_for(n_clear4, NT, 256)), dim3(NT), setup_lds,
+        PK_LAUNCH("pk_setup", pk_setup_kernel, dim3(blocks_for(n_clear4, kSetupThreads, 256)), dim3(kSetupThreads), setup_lds,
                   ws.at<uint4>(L.slice_total), n_clear4, offsets, B, F, P, T, nnz, sa.target, sa.log_max, ds->fmeta, ds->pmeta,
                   ds->sort_tables, ds->slot_field, st, packed_offsets, seg, ws.at<TableCut>(L.tgeom), L.n_slices,
                   ws.at<int32_t>(L.fscan));
@@ -295,7 +295,8 @@ static pk_status forward_impl(const pk_plan* plan, DeviceState* ds_given, int st
             if (beside) { rc = join_streams(ds, main_stream, 1, DeviceState::kSide - 1); if (rc != PK_OK) return rc; }
         }
         const size_t inv_lds = (field_scan_words(F) + 4 * (size_t)F) * 4;
-        const unsigned xq = (blocks_for(nnz, 1024, 256 * 16) + 7u) & ~7u;
+        // (every block stages the field scan and the slots' metadata: with many fields fewer blocks take more tiles each)
+        const unsigned xq = (blocks_for(nnz, 1024, F > 256 ? 256 * 4 : 256 * 16) + 7u) & ~7u;
         PK_LAUNCH("pk_inverse", pk_inverse_kernel<1024>, dim3(xq), dim3(NT), inv_lds, F, ws.at<int32_t>(L.fscan), ds->slot_meta, st,
                   keys, reinterpret_cast<const uint4*>(sa.bitmap), inverse);
     }
