@@ -42,26 +42,21 @@ __device__ __forceinline__ int block_excl_scan(int v, int* total)
     return base + inc - v;
 }
 
-// x mod rows for x < rows * 2^32.  The quotient is estimated in double (x / rows < 2^32, so the
-// estimate is within 2^-19 of the true ratio: after truncation it is off by one at most) and the
-// remainder, formed exactly in integers, is put right.  Many times shorter than a 64-bit division.
-__device__ __forceinline__ uint32_t mod_step(uint64_t x, uint32_t rows, double inv)
-{
-    const uint64_t q = (uint64_t)((double)x * inv);
-    int64_t r = (int64_t)(x - q * (uint64_t)rows);
-    if (r < 0) r += rows;
-    else if (r >= (int64_t)rows) r -= rows;
-    return (uint32_t)r;
-}
+// The row of an ID: the ID, taken as an unsigned 64-bit number, modulo the table's rows (exact).
+// magic = floor((2^64 - 1) / rows): the upper half of ID * magic is the quotient or up to two below
+// it, so the remainder formed from it is put right by two conditional subtractions (rows <= 2^30:
+// nothing overflows).  A dozen integer operations instead of a 64-bit division.
+__device__ __forceinline__ uint64_t fold_magic(uint32_t rows) { return ~(uint64_t)0 / (uint64_t)rows; }
 
-// the row of an ID: the ID, taken as an unsigned 64-bit number, modulo the table's rows (exact)
-__device__ __forceinline__ uint32_t fold_id(int64_t id, uint32_t rows)
+__device__ __forceinline__ uint32_t fold_id(int64_t id, uint32_t rows, uint64_t magic)
 {
     const uint64_t u = (uint64_t)id;
     if (u < rows) return (uint32_t)u;
-    const double inv = 1.0 / (double)rows;
-    const uint32_t h = mod_step(u >> 32, rows, inv);                   // the upper half first
-    return mod_step(((uint64_t)h << 32) | (uint32_t)u, rows, inv);
+    const uint64_t q = __umul64hi(u, magic);
+    uint64_t r = u - q * (uint64_t)rows;
+    if (r >= rows) r -= rows;
+    if (r >= rows) r -= rows;
+    return (uint32_t)r;
 }
 
 // first index in [0, n) whose value exceeds x, for a non-decreasing array

@@ -247,7 +247,7 @@ pk_keys_kernel(const int64_t* __restrict__ ids, const int32_t* __restrict__ offs
             for (int j = 0; j < 4; ++j) {
                 const int i = base + tid + j * NT;
                 const bool on = i < q_hi;
-                const uint32_t kk = on ? fold_id(idv[j], m.rows) : 0u;
+                const uint32_t kk = on ? fold_id(idv[j], m.rows, m.magic) : 0u;
                 if (on) keys[i + dl] = m.base_row + kk;
                 if (on) atomicAdd(&s_hist[kk >> g.log_keys], 1);
             }
@@ -558,6 +558,7 @@ __device__ __forceinline__ void slice_body(const SliceArgs& a, int slice, int32_
         }
     }
     PK_PT(a, slice, 1);
+    const uint64_t magic = FROM_IDS ? fold_magic(rows) : 0;  // (one division per block; the IDs are folded without)
     const uint32_t lo = (uint32_t)idx << lg;               // first key of the slice inside its table
     const uint32_t nkeys = min((uint32_t)1 << lg, rows - lo);
     const int words = 1 << (lg - 5);
@@ -589,7 +590,7 @@ __device__ __forceinline__ void slice_body(const SliceArgs& a, int slice, int32_
 #pragma unroll
                     for (int u = 0; u < 4; ++u) {
                         const int i = base + tid + u * NTH;
-                        const uint32_t kk = i < q1 ? fold_id(idv[u], rows) : 0xFFFFFFFFu;
+                        const uint32_t kk = i < q1 ? fold_id(idv[u], rows, magic) : 0xFFFFFFFFu;
                         const bool on = i < q1 && (kk >> lg) == (uint32_t)idx;
                         fn(SliceRec{on ? kk - lo : 0u, j, i, -1, 0}, on);
                     }

@@ -49,7 +49,7 @@ __device__ __forceinline__ void pool_body(const WT* __restrict__ W, const PoolSr
         // the key of position q; a key that is no row of the pack (only possible after rejected
         // offsets, which raise the error word) is bent to the last row so that no read leaves the table
         auto key_at = [&](int q) -> uint32_t {
-            if (IDS) return m.base_row + fold_id(ids[q], m.rows);
+            if (IDS) return m.base_row + fold_id(ids[q], m.rows, m.magic);
             return min(keys[q], last_row);
         };
         float acc[NCH][VEC];

@@ -65,6 +65,7 @@ void build_meta_image(const pk_plan* plan, MetaImage* mi)
         mi->fm[f].pool = plan->fields[f].pool;
         mi->fm[f].stable = -1;
         mi->fm[f].pad = 0;
+        mi->fm[f].magic = ~(uint64_t)0 / (uint64_t)plan->tables[t].rows;
     }
     for (size_t i = 0; i < plan->sort_tables.size(); ++i)
         for (int32_t j = plan->sort_tables[i].field_begin; j < plan->sort_tables[i].field_end; ++j)

@@ -110,6 +110,7 @@ struct FieldMeta {
     int32_t  pool;       // PK_SUM / PK_MEAN
     int32_t  stable;     // the field's table in the (pack, first key) ordered table list
     int32_t  pad;
+    uint64_t magic;      // floor((2^64 - 1) / rows): folds an ID without a division
 };
 
 // Per pack, device side, static.
