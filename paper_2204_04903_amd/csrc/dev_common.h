@@ -195,6 +195,31 @@ __device__ __forceinline__ int lds_inc_grouped(int32_t* cnt, uint32_t idx, bool 
     return pos;
 }
 
+// The same for counters that are few (idx < n, n small and the same for the whole wavefront): with a
+// handful of counters nearly every lane shares its counter with others, and LDS atomics on one address
+// run one after the other, so the wavefront goes through the counters and makes one add for each that
+// some lane wants.  POS: the value before the lane's own increment is returned.
+constexpr int kFewCounters = 2;
+template <bool POS>
+__device__ __forceinline__ int lds_inc_few(int32_t* cnt, uint32_t idx, bool active, int n)
+{
+    const int lane = threadIdx.x & 63;
+    int pos = 0;
+    for (int s = 0; s < n; ++s) {
+        const bool mine = active && idx == (uint32_t)s;
+        const uint64_t m = __ballot(mine);
+        if (!m) continue;
+        const int leader = __ffsll((unsigned long long)m) - 1;
+        int base = 0;
+        if (lane == leader) base = atomicAdd(&cnt[s], __popcll(m));
+        if (POS) {
+            base = __shfl(base, leader, 64);
+            if (mine) pos = base + __popcll(m & ((1ull << lane) - 1ull));
+        }
+    }
+    return pos;
+}
+
 // Workgroups are handed to the 8 XCDs round-robin and each XCD has its own L2.
 // Giving XCD x the x-th contiguous eighth of the tiles keeps the irregular
 // accesses of neighbouring tiles (same table, same gradient columns) in one L2.

@@ -249,7 +249,8 @@ pk_keys_kernel(const int64_t* __restrict__ ids, const int32_t* __restrict__ offs
                 const bool on = i < q_hi;
                 const uint32_t kk = on ? fold_id(idv[j], m.rows, m.magic) : 0u;
                 if (on) keys[i + dl] = m.base_row + kk;
-                if (on) atomicAdd(&s_hist[kk >> g.log_keys], 1);
+                if (g.n <= kFewCounters) (void)lds_inc_few<false>(s_hist, kk >> g.log_keys, on, g.n);
+                else if (on) atomicAdd(&s_hist[kk >> g.log_keys], 1);
             }
         }
         __syncthreads();
@@ -360,7 +361,8 @@ pk_scatter_kernel(const int32_t* __restrict__ offsets, int B, int F, int64_t nnz
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
                 const uint32_t s = kv[u] >> g.log_keys;
-                if (s < (uint32_t)g.n) atomicAdd(&s_hist[s], 1);
+                if (g.n <= kFewCounters) (void)lds_inc_few<false>(s_hist, s, s < (uint32_t)g.n, g.n);
+                else if (s < (uint32_t)g.n) atomicAdd(&s_hist[s], 1);
             }
         }
         __syncthreads();
@@ -392,12 +394,15 @@ pk_scatter_kernel(const int32_t* __restrict__ offsets, int B, int F, int64_t nnz
                 const int i = base + u * 64 + lane;
                 const uint32_t kk = kv[u];
                 const uint32_t s = kk >> g.log_keys;
-                if (i >= w_hi) continue;
-                if (s >= (uint32_t)g.n && !stepped) continue;
-                if (stepped) { while (t + 1 < tl.nb && s_po[t + 1] <= i) ++t; }
-                else t = upper_bound_i32(s_po, tl.nb + 1, i) - 1;
-                if (s >= (uint32_t)g.n) continue;
-                const int at_local = atomicAdd(&s_hist[s], 1);
+                const bool valid = i < w_hi && s < (uint32_t)g.n;
+                if (i < w_hi) {
+                    if (stepped) { while (t + 1 < tl.nb && s_po[t + 1] <= i) ++t; }
+                    else if (valid) t = upper_bound_i32(s_po, tl.nb + 1, i) - 1;
+                }
+                int at_local = 0;
+                if (g.n <= kFewCounters) at_local = lds_inc_few<true>(s_hist, s, valid, g.n);   // (all lanes of the wavefront are here)
+                else if (valid) at_local = atomicAdd(&s_hist[s], 1);
+                if (!valid) continue;
                 const int64_t at = (int64_t)s_place[s] + at_local;
                 // the record: key inside the slice, the gradient's scale (bag length for mean pooling, 1 for sum;
                 // 0 = too long for its bits, to be looked up) above it, and the place of the bag's gradient chunk
